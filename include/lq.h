@@ -1,0 +1,182 @@
+/*
+ * lq.h  --  C ABI of the MI355X (gfx950) LQ decomposition library.
+ *
+ * The library computes the low-rank plus quantized decomposition  W ~= Q + L1 L2  of LQ-LoRA
+ * (arxiv 2311.12023, Section 3) and the per-matrix error table that feeds the paper's integer
+ * linear program (Algorithm 3), with every step running in hand-written HIP kernels.
+ *
+ * Conventions for every entry point
+ *  - Matrix and vector arguments are DEVICE pointers unless the comment says "host".  Matrices are
+ *    row-major, contiguous, fp32.  `stream` is a hipStream_t passed as void* (NULL = default stream).
+ *  - The caller owns every buffer.  The library allocates no device memory: scratch space comes in
+ *    through `workspace` (device, 256-byte aligned), sized by the matching *_workspace_bytes call.
+ *    The library keeps no state except immutable code-book tables built on first use per device.
+ *  - Return value: LQ_OK (0) or a negative lq_status.  Arguments are validated on the host before
+ *    anything is launched, so a call that fails validation has no effect on any buffer.
+ *    Device data is not inspected: non-finite weights, or non-positive Fisher weights, give
+ *    unspecified numbers (never an out-of-bounds access).
+ *  - lq_nf_quantize / lq_nf_dequantize only enqueue work on `stream`.  lq_factorize, lq_decompose
+ *    and lq_error_table write host outputs and therefore synchronize `stream` before returning.
+ *  - Calls that share a workspace, or that overlap on outputs, must not run concurrently.
+ */
+#ifndef LQ_H_
+#define LQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LQ_OK = 0,
+  LQ_ERR_NULL = -1,       /* a required pointer is NULL                                              */
+  LQ_ERR_SHAPE = -2,      /* d, k, n <= 0; n not a multiple of the block size; sizes beyond int32 rows */
+  LQ_ERR_CONFIG = -3,     /* bits / block sizes / scale bits / v dtype outside the supported set      */
+  LQ_ERR_RANK = -4,       /* rank < 1, rank >= min(d,k) (Section 2.1 requires r < min(d,k)), rank > 128 */
+  LQ_ERR_WEIGHT = -5,     /* exactly one of row_w / col_w is NULL                                     */
+  LQ_ERR_WORKSPACE = -6,  /* workspace NULL, misaligned or smaller than *_workspace_bytes             */
+  LQ_ERR_HIP = -7,        /* a HIP runtime call failed; lq_last_hip_error() gives its code            */
+  LQ_ERR_ARG = -8         /* iters < 1, n_cfgs < 1, bad parameter block                               */
+} lq_status;
+
+/* v dtype codes (b2 of the configuration tuple). */
+enum { LQ_V_FP32 = 0, LQ_V_BF16 = 1, LQ_V_FP16 = 2 };
+
+/*
+ * Quantization configuration c = (b0, b1, b2, B0, B1) of Section 3.2 (Table 1 lists the paper's
+ * search grid; b0 = 8 is the "NF-8" variant of Section 4.2).
+ *   bits        b0  NF code bits, one of 2, 3, 4, 8
+ *   block       B0  weights per absmax block: a power of two in [16, 1024]
+ *   scale_block B1  absmax values per second-level group: a power of two in [16, 256]
+ *   scale_bits  b1  bits of the integer-quantized absmax values, 2..8; 0 selects 8
+ *   v_dtype     b2  LQ_V_FP32 / LQ_V_BF16 / LQ_V_FP16 storage of the group scales v
+ */
+typedef struct {
+  int32_t bits;
+  int32_t block;
+  int32_t scale_block;
+  int32_t scale_bits;
+  int32_t v_dtype;
+} lq_config;
+
+/*
+ * Parameters of the randomized SVD that stands in for "SVD(A, r)" in Algorithm 4 (the paper uses a
+ * randomized SVD, Section 3.1 footnote 1, and gives no parameters).  Pass NULL for the defaults.
+ * A zero field selects its default.
+ *   first_width   sketch width l1 of the cold start (first LQ iteration, Q = 0); multiple of 32,
+ *                 rank < l1 <= 256.  Default: round_up32(max(2*rank, rank + 56)).
+ *   first_tol     the cold start runs subspace iterations until the top-`rank` Ritz values change
+ *                 by less than this relative amount between two checks.  Default 1e-6.
+ *   first_check   subspace iterations between two checks.  Default 8.
+ *   first_max     cap on cold-start subspace iterations.  Default 600.
+ *   warm_width    subspace width l of later LQ iterations, warm-started from the previous one;
+ *                 multiple of 32, rank < l <= first_width.  Default round_up32(rank + max(rank/2, 24)).
+ *   warm_power    subspace iterations per later LQ iteration.  Default 2.
+ *   warm_power_2  subspace iterations of the second LQ iteration (the one whose input differs most
+ *                 from its warm start).  Default 3.
+ *   max_batch     lq_error_table advances up to this many configurations in lock step (more
+ *                 workspace, better GPU occupancy).  Default 36.
+ */
+typedef struct {
+  int32_t first_width;
+  float   first_tol;
+  int32_t first_check;
+  int32_t first_max;
+  int32_t warm_width;
+  int32_t warm_power;
+  int32_t warm_power_2;
+  int32_t max_batch;
+} lq_svd_params;
+
+const char* lq_status_string(int status);
+/* hipError_t of the most recent failing HIP call on this thread (0 if none). */
+int lq_last_hip_error(void);
+
+/* NF-`bits` code book (Section 2.2): host_out[i] = value of code i, 2^bits ascending fp32 values
+ * in [-1, 1] with host_out[2^(bits-1) - 1] == 0.  host pointer.  LQ_ERR_CONFIG for bits not in 2..8. */
+int lq_nf_codebook(int bits, float* host_out);
+
+/* Bytes of the packed code array for n weights: ceil(n * bits / 8).  Codes are packed as a
+ * little-endian bit stream: code j occupies bits [j*bits, (j+1)*bits) (Appendix A: sub-8-bit codes
+ * are packed into int8 containers). */
+size_t lq_codes_bytes(int64_t n, int bits);
+/* storage(A, c) of Eq. 3 in bits: n * (b0 + b1/B0 + bits(b2)/(B0*B1)).  Negative on a bad config. */
+double lq_storage_bits(int64_t n, lq_config c);
+
+/*
+ * Quantize(x, c) of Section 3.2: Quantize-NF(x, b0, B0) -> codes and absmax s per block of B0
+ * consecutive weights; Quantize-INT(s, b1, B1) -> integer scale indices and one scale v per group
+ * of B1 consecutive blocks; cast(v, b2).
+ *   x            n fp32 weights (row-major flattening of the matrix); n % B0 == 0, n > 0
+ *   codes_packed lq_codes_bytes(n, b0) bytes
+ *   scale_idx    n / B0 bytes, one index in [0, 2^(b1-1) - 1] per block
+ *   v            ceil(n / (B0*B1)) fp32 values (already rounded to b2); the last group may be short
+ * Arithmetic (fixed, so that results are reproducible bit for bit): the normalised weight is
+ * fl32(u * fl32(1/s)); the code is the nearest code-book value, ties to the lower code; a block
+ * with s == 0 gets the code of value 0; sigma = fl32(v/(2^(b1-1)-1)),
+ * index = clamp(round_half_even(fl32(s/sigma)), 0, 2^(b1-1)-1).
+ */
+int lq_nf_quantize(const float* x, int64_t n, lq_config c, uint8_t* codes_packed, uint8_t* scale_idx,
+                   float* v, void* stream);
+
+/* Dequantize (Section 3.2, the reverse of the above): out[j] = fl32(codebook[code_j] *
+ * fl32(scale_idx[block] * fl32(v[group] / (2^(b1-1)-1)))).  out: n fp32 values. */
+int lq_nf_dequantize(const uint8_t* codes_packed, const uint8_t* scale_idx, const float* v, int64_t n,
+                     lq_config c, float* out, void* stream);
+
+/*
+ * Factorize(A, F, r) of Algorithm 4 / Eq. 5 by randomized subspace iteration from a cold start.
+ *   A      d x k
+ *   row_w, col_w  Fisher-scale positive weights (d and k values) or both NULL.  The SVD is taken of
+ *          diag(sqrt(row_w)) A diag(sqrt(col_w)) and the factors are un-scaled (Eq. 5).
+ *   seed   seeds the Gaussian sketch; equal seeds give bit-identical results
+ *   L1     d x rank  = D_row^-1 U sqrt(Sigma)        L2  rank x k = sqrt(Sigma) V^T D_col^-1
+ *   sigma  host, rank doubles: the singular values found (descending); may be NULL
+ */
+size_t lq_factorize_workspace_bytes(int64_t d, int64_t k, int rank, const lq_svd_params* p);
+int lq_factorize(const float* A, int64_t d, int64_t k, int rank, const float* row_w, const float* col_w,
+                 uint64_t seed, const lq_svd_params* p, float* L1, float* L2, double* sigma,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * LQ(W, F, c, r) of Algorithm 2 (Eq. 2): Q <- 0; repeat `iters` times
+ *   L1, L2 <- Factorize(W - Q, F, r);  Q <- Quantize(W - L1 L2, c);
+ *   eps_t = || sqrt(F) .* (W - Q - L1 L2) ||_F  with F_ij = row_w[i]*col_w[j] (Eq. 4), or F = 1.
+ * With early_stop != 0 the loop ends after the first iteration whose eps exceeds the previous one and
+ * returns that iterate, as Algorithm 2 prints it (this mode synchronizes once per iteration).
+ *   W            d x k
+ *   L1, L2       d x rank, rank x k (balanced factors of the last Factorize)
+ *   q_codes, q_scale_idx, q_v   the quantized component, laid out as for lq_nf_quantize (n = d*k)
+ *   Q_dense      d x k dequantized Q, or NULL
+ *   err          host, 1 double: eps of the last iteration run        (may be NULL)
+ *   err_trace    host, iters doubles: eps_1..; entries past iters_done are NaN   (may be NULL)
+ *   iters_done   host, 1 int32                                         (may be NULL)
+ *   sigma        host, rank doubles: singular values of the last Factorize (may be NULL)
+ */
+size_t lq_decompose_workspace_bytes(int64_t d, int64_t k, int rank, const lq_svd_params* p);
+int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config c, int iters, int early_stop,
+                 const float* row_w, const float* col_w, uint64_t seed, const lq_svd_params* p,
+                 float* L1, float* L2, uint8_t* q_codes, uint8_t* q_scale_idx, float* q_v, float* Q_dense,
+                 double* err, double* err_trace, int32_t* iters_done, double* sigma,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Inner loops of GetConfig (Algorithm 3) for one matrix: for every configuration c of `cfgs`,
+ * err_sq[c] = eps^2 of LQ(W, F, c, rank) and storage_bits[c] = storage(W, c) (Eq. 3).
+ * The first Factorize (Q = 0) does not depend on c and is computed once; the configurations then
+ * advance in lock step, `max_batch` at a time.
+ *   cfgs          host, n_cfgs entries           err_sq, storage_bits   host, n_cfgs doubles each
+ *   err_trace     host, n_cfgs * iters doubles (row per configuration), or NULL
+ */
+size_t lq_error_table_workspace_bytes(int64_t d, int64_t k, int rank, int n_cfgs, const lq_svd_params* p);
+int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_config* cfgs, int n_cfgs,
+                   int iters, int early_stop, const float* row_w, const float* col_w, uint64_t seed,
+                   const lq_svd_params* p, double* err_sq, double* storage_bits, double* err_trace,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LQ_H_ */

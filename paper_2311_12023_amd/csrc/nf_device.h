@@ -1,0 +1,182 @@
+// Device-side building blocks of the NF quantizer (Sections 2.2 and 3.2), shared by the stand-alone
+// quantize / dequantize kernels and by the fused kernels of the decomposition loop.
+//
+// All arithmetic that decides a code or a scale index is written as single correctly rounded fp32
+// operations (the library is compiled with -ffp-contract=off), so results are reproducible bit for bit:
+//   normalised weight  fl32(u * fl32(1/s))           code = #{i : x >= thr[i]}
+//   sigma = fl32(v / levels)   index = clamp(rne(fl32(s / sigma)), 0, levels)   s^ = fl32(index * sigma)
+#pragma once
+
+#include <hip/hip_fp16.h>
+
+#include "lq_internal.h"
+
+namespace lq {
+
+struct DevTables {
+  float code[4][256];
+  float thr[4][256];
+};
+// Device address of the tables on the current device (uploads them on first use).
+int device_tables(const DevTables** out);
+
+template <int BITS>
+struct Slot;
+template <> struct Slot<2> { static constexpr int value = 0; };
+template <> struct Slot<3> { static constexpr int value = 1; };
+template <> struct Slot<4> { static constexpr int value = 2; };
+template <> struct Slot<8> { static constexpr int value = 3; };
+
+// Copies the code-book and thresholds of one bit width into LDS (ends with a barrier).
+template <int BITS>
+__device__ inline void load_tables(const DevTables* __restrict__ tab, float* s_code, float* s_thr) {
+  constexpr int NC = 1 << BITS;
+  for (int i = threadIdx.x; i < NC; i += blockDim.x) {
+    s_code[i] = tab->code[Slot<BITS>::value][i];
+    s_thr[i] = tab->thr[Slot<BITS>::value][i];
+  }
+  __syncthreads();
+}
+
+// Nearest code with ties to the lower index = number of thresholds <= x.
+// 2..4 bits: thresholds live in registers and are counted; 8 bits: binary search in LDS
+// (entry 255 of the table is +inf).
+template <int BITS>
+struct Thresholds {
+  float r[(1 << BITS) - 1];
+  __device__ explicit Thresholds(const float* s_thr) {
+#pragma unroll
+    for (int i = 0; i < (1 << BITS) - 1; ++i) r[i] = s_thr[i];
+  }
+  __device__ inline uint32_t nearest(float x) const {
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < (1 << BITS) - 1; ++i) c += (x >= r[i]) ? 1u : 0u;
+    return c;
+  }
+};
+template <>
+struct Thresholds<8> {
+  const float* t;
+  __device__ explicit Thresholds(const float* s_thr) : t(s_thr) {}
+  __device__ inline uint32_t nearest(float x) const {
+    uint32_t c = 0;
+#pragma unroll
+    for (int step = 128; step >= 1; step >>= 1) c += (x >= t[c + step - 1]) ? (uint32_t)step : 0u;
+    return c;
+  }
+};
+
+__device__ inline float run_absmax(const float (&t)[16]) {
+  float m = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) m = fmaxf(m, fabsf(t[j]));
+  return m;
+}
+
+// fl32(1/s); 0 for an all-zero block or when the reciprocal overflows.
+__device__ inline float safe_reciprocal(float s) {
+  float r = 0.0f;
+  if (s > 0.0f) {
+    r = 1.0f / s;
+    if (isinf(r)) r = 0.0f;
+  }
+  return r;
+}
+
+// ---- packed code stream: code j of run `run` occupies bits [(16*run + j)*BITS, +BITS) ------------
+template <int BITS>
+__device__ inline void store_codes(uint8_t* __restrict__ codes, int64_t run, const uint32_t (&c)[16]) {
+  if constexpr (BITS == 8) {
+    uint4 w;
+    w.x = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
+    w.y = c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24);
+    w.z = c[8] | (c[9] << 8) | (c[10] << 16) | (c[11] << 24);
+    w.w = c[12] | (c[13] << 8) | (c[14] << 16) | (c[15] << 24);
+    *reinterpret_cast<uint4*>(codes + run * 16) = w;
+  } else {
+    uint64_t w = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w |= (uint64_t)c[j] << (j * BITS);
+    if constexpr (BITS == 4) {
+      *reinterpret_cast<uint2*>(codes + run * 8) = make_uint2((uint32_t)w, (uint32_t)(w >> 32));
+    } else if constexpr (BITS == 2) {
+      *reinterpret_cast<uint32_t*>(codes + run * 4) = (uint32_t)w;
+    } else {   // 3 bits: 48 bits, 2-byte aligned
+      uint16_t* p = reinterpret_cast<uint16_t*>(codes + run * 6);
+      p[0] = (uint16_t)w; p[1] = (uint16_t)(w >> 16); p[2] = (uint16_t)(w >> 32);
+    }
+  }
+}
+
+template <int BITS>
+__device__ inline void load_codes(const uint8_t* __restrict__ codes, int64_t run, uint32_t (&c)[16]) {
+  if constexpr (BITS == 8) {
+    const uint4 w = *reinterpret_cast<const uint4*>(codes + run * 16);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int j = 0; j < 16; ++j) c[j] = (ww[j >> 2] >> ((j & 3) * 8)) & 0xffu;
+  } else {
+    uint64_t w;
+    if constexpr (BITS == 4) {
+      const uint2 u = *reinterpret_cast<const uint2*>(codes + run * 8);
+      w = (uint64_t)u.x | ((uint64_t)u.y << 32);
+    } else if constexpr (BITS == 2) {
+      w = *reinterpret_cast<const uint32_t*>(codes + run * 4);
+    } else {
+      const uint16_t* p = reinterpret_cast<const uint16_t*>(codes + run * 6);
+      w = (uint64_t)p[0] | ((uint64_t)p[1] << 16) | ((uint64_t)p[2] << 32);
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) c[j] = (uint32_t)(w >> (j * BITS)) & ((1u << BITS) - 1u);
+  }
+}
+
+// ---- second-level (integer) scale quantization -------------------------------------------------
+// Maximum over the `width` consecutive lanes (power of two, 16..256, aligned) that hold one scale
+// group; the workgroup has 256 threads.  s_wave: 4 floats of LDS.  Contains barriers when
+// width > 64, so every thread of the workgroup must call it.
+__device__ inline float group_max(float x, int width, float* s_wave) {
+  const int w = width < 64 ? width : 64;
+  for (int off = 1; off < w; off <<= 1) x = fmaxf(x, __shfl_xor(x, off));
+  if (width > 64) {
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) s_wave[wave] = x;
+    __syncthreads();
+    const int per = width >> 6;             // waves per group: 2 or 4
+    const int base = wave & ~(per - 1);
+    float m = s_wave[base];
+    for (int i = 1; i < per; ++i) m = fmaxf(m, s_wave[base + i]);
+    x = m;
+    __syncthreads();
+  }
+  return x;
+}
+
+__device__ inline uint32_t scale_index(float s, float sigma, int levels) {
+  if (!(sigma > 0.0f)) return 0u;
+  float r = rintf(s / sigma);
+  r = fminf(fmaxf(r, 0.0f), (float)levels);
+  return (uint32_t)r;
+}
+
+__device__ inline float block_scale(uint32_t idx, float v_stored, int levels) {
+  const float sigma = v_stored / (float)levels;
+  return (float)idx * sigma;
+}
+
+// cast(v, b2): round to nearest even into the storage type, returned as fp32.
+__device__ inline float cast_group_scale(float v, int v_dtype) {
+  if (v_dtype == LQ_V_BF16) {
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7f800000u) != 0x7f800000u) {
+      u += 0x7fffu + ((u >> 16) & 1u);
+      u &= 0xffff0000u;
+    }
+    return __uint_as_float(u);
+  }
+  if (v_dtype == LQ_V_FP16) return __half2float(__float2half_rn(v));
+  return v;
+}
+
+}  // namespace lq

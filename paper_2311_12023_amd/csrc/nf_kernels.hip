@@ -1,0 +1,201 @@
+// NormalFloat block quantization kernels for gfx950 (Sections 2.2 and 3.2).
+//
+// Work unit: a "run" of 16 consecutive weights held by one lane (64 B of fp32 in, 2*bits bytes of
+// packed codes out).  A block of B0 weights is B0/16 consecutive runs, i.e. consecutive lanes of one
+// wavefront, so the block absmax is a few cross-lane maxima and never touches LDS.  Code-book and
+// thresholds sit in LDS (8-bit) or registers (2..4-bit).
+#include <hip/hip_fp16.h>
+
+#include <mutex>
+
+#include "nf_device.h"
+
+namespace lq {
+
+__device__ DevTables g_nf_tables;
+
+static std::mutex g_tables_mutex;
+static const DevTables* g_tables_ptr[64] = {nullptr};
+
+int device_tables(const DevTables** out) {
+  int dev = 0;
+  LQ_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return LQ_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_tables_mutex);
+  if (!g_tables_ptr[dev]) {
+    static_assert(sizeof(DevTables) == sizeof(HostTables), "table layouts differ");
+    void* p = nullptr;
+    LQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_nf_tables)));
+    LQ_HIP_TRY(hipMemcpy(p, &host_tables(), sizeof(HostTables), hipMemcpyHostToDevice));
+    g_tables_ptr[dev] = (const DevTables*)p;
+  }
+  *out = g_tables_ptr[dev];
+  return LQ_OK;
+}
+
+int ensure_device_tables() {
+  const DevTables* t;
+  return device_tables(&t);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Quantize(x, c) in one pass.  A workgroup of 256 lanes walks chunks of 4096*U weights that hold whole
+// scale groups (B0*B1 <= 4096*U); lane t owns runs t, t+256, ... of the chunk, so every load
+// instruction of a wavefront covers one contiguous 4 KB stretch.  Block absmax: cross-lane maxima over
+// B0/16 lanes.  Group absmax: cross-lane / LDS maxima over B0*B1/16 runs.  Nothing but the inputs and
+// outputs touches memory.
+template <int BITS, int U>
+__global__ __launch_bounds__(256) void quantize_fused_kernel(const float* __restrict__ x, int64_t nruns,
+                                                             int runs_per_block, int scale_block, int levels,
+                                                             int v_dtype, const DevTables* __restrict__ tab,
+                                                             uint8_t* __restrict__ codes, uint8_t* __restrict__ sidx,
+                                                             float* __restrict__ v) {
+  __shared__ float s_code[1 << BITS];
+  __shared__ float s_thr[1 << BITS];
+  __shared__ float s_wave[4];
+  load_tables<BITS>(tab, s_code, s_thr);
+  Thresholds<BITS> thr(s_thr);
+
+  const int runs_per_group = runs_per_block * scale_block;          // 16 .. 256*U
+  const int slabs_per_group = runs_per_group > 256 ? runs_per_group / 256 : 1;
+  const int lane_width = runs_per_group > 256 ? 256 : runs_per_group;
+  const int64_t chunk_runs = 256 * U;
+  const int64_t nchunks = (nruns + chunk_runs - 1) / chunk_runs;
+  for (int64_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+    float t[U][16];
+    float amax[U];
+    int64_t run[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      run[u] = chunk * chunk_runs + u * 256 + threadIdx.x;
+      if (run[u] < nruns) {
+        const float4* p = reinterpret_cast<const float4*>(x + run[u] * 16);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 f = p[q];
+          t[u][4 * q] = f.x; t[u][4 * q + 1] = f.y; t[u][4 * q + 2] = f.z; t[u][4 * q + 3] = f.w;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) t[u][j] = 0.0f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float m = run_absmax(t[u]);
+      for (int off = 1; off < runs_per_block; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
+      amax[u] = m;
+    }
+    // group maxima: first across the slabs that belong to one group, then across lanes
+    float gmax[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float m = amax[u];
+      const int g0 = u - (u % slabs_per_group);
+#pragma unroll
+      for (int w = 0; w < U; ++w)
+        if (w >= g0 && w < g0 + slabs_per_group) m = fmaxf(m, amax[w]);
+      gmax[u] = m;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) gmax[u] = group_max(gmax[u], lane_width, s_wave);
+
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float rcp = safe_reciprocal(amax[u]);
+      uint32_t c[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) c[j] = thr.nearest(t[u][j] * rcp);
+      if (run[u] < nruns) {
+        store_codes<BITS>(codes, run[u], c);
+        if ((run[u] & (runs_per_block - 1)) == 0) {
+          const float sigma = gmax[u] / (float)levels;
+          sidx[run[u] / runs_per_block] = (uint8_t)scale_index(amax[u], sigma, levels);
+        }
+        if (run[u] % runs_per_group == 0) v[run[u] / runs_per_group] = cast_group_scale(gmax[u], v_dtype);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dequantize: one run per lane.
+template <int BITS>
+__global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ codes,
+                                                      const uint8_t* __restrict__ sidx, const float* __restrict__ v,
+                                                      int64_t nruns, int runs_per_block, int scale_block, int levels,
+                                                      const DevTables* __restrict__ tab, float* __restrict__ out) {
+  __shared__ float s_code[1 << BITS];
+  __shared__ float s_thr[1 << BITS];
+  load_tables<BITS>(tab, s_code, s_thr);
+  const int64_t run = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (run >= nruns) return;
+  const int64_t blk = run / runs_per_block;
+  const float sh = block_scale(sidx[blk], v[blk / scale_block], levels);
+  uint32_t c[16];
+  load_codes<BITS>(codes, run, c);
+  float4* o = reinterpret_cast<float4*>(out + run * 16);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float4 f;
+    f.x = s_code[c[4 * q]] * sh; f.y = s_code[c[4 * q + 1]] * sh;
+    f.z = s_code[c[4 * q + 2]] * sh; f.w = s_code[c[4 * q + 3]] * sh;
+    o[q] = f;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int BITS>
+static void launch_quantize_bits(const float* x, int64_t nruns, const lq_config& c, const DevTables* tab,
+                                 uint8_t* codes, uint8_t* sidx, float* v, hipStream_t st) {
+  const int rpb = c.block / 16;
+  const int lv = scale_levels(c);
+  const bool big = (int64_t)c.block * c.scale_block > 8192;
+  const int64_t chunk_runs = big ? 1024 : 512;
+  const int64_t nchunks = (nruns + chunk_runs - 1) / chunk_runs;
+  const int64_t cap = 256 * 8;
+  const dim3 grid((unsigned)(nchunks < cap ? nchunks : cap)), block(256);
+  if (big)
+    hipLaunchKernelGGL((quantize_fused_kernel<BITS, 4>), grid, block, 0, st, x, nruns, rpb, c.scale_block, lv,
+                       c.v_dtype, tab, codes, sidx, v);
+  else
+    hipLaunchKernelGGL((quantize_fused_kernel<BITS, 2>), grid, block, 0, st, x, nruns, rpb, c.scale_block, lv,
+                       c.v_dtype, tab, codes, sidx, v);
+}
+
+int launch_quantize(const float* x, int64_t n, const lq_config& c, uint8_t* codes, uint8_t* sidx, float* v,
+                    hipStream_t st) {
+  const DevTables* tab;
+  LQ_TRY(device_tables(&tab));
+  const int64_t nruns = n / 16;
+  switch (c.bits) {
+    case 2: launch_quantize_bits<2>(x, nruns, c, tab, codes, sidx, v, st); break;
+    case 3: launch_quantize_bits<3>(x, nruns, c, tab, codes, sidx, v, st); break;
+    case 4: launch_quantize_bits<4>(x, nruns, c, tab, codes, sidx, v, st); break;
+    case 8: launch_quantize_bits<8>(x, nruns, c, tab, codes, sidx, v, st); break;
+    default: return LQ_ERR_CONFIG;
+  }
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
+int launch_dequant(const uint8_t* codes, const uint8_t* sidx, const float* v, int64_t n, const lq_config& c,
+                   float* out, hipStream_t st) {
+  const DevTables* tab;
+  LQ_TRY(device_tables(&tab));
+  const int64_t nruns = n / 16;
+  const int rpb = c.block / 16;
+  const dim3 grid((unsigned)((nruns + 255) / 256)), block(256);
+  const int lv = scale_levels(c);
+  switch (c.bits) {
+    case 2: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
+    case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
+    case 4: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
+    case 8: hipLaunchKernelGGL(dequant_kernel<8>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
+    default: return LQ_ERR_CONFIG;
+  }
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
+}  // namespace lq

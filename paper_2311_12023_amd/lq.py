@@ -1,0 +1,223 @@
+"""Python binding of the LQ C ABI (include/lq.h): argument marshalling only.
+
+torch supplies device memory and the current stream; every step of the path runs in the HIP
+library.  There is no fallback: if the library is missing, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblq_hip.so")
+
+V_DTYPES = {"fp32": 0, "bf16": 1, "fp16": 2}
+
+
+class LqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = _lib.lq_status_string(status).decode()
+        if status == -7:
+            msg += f" (hipError {_lib.lq_last_hip_error()})"
+        super().__init__(f"{where}: {msg}")
+
+
+class Config(C.Structure):
+    """lq_config: (bits b0, block B0, scale_block B1, scale_bits b1, v_dtype b2)."""
+    _fields_ = [("bits", C.c_int32), ("block", C.c_int32), ("scale_block", C.c_int32),
+                ("scale_bits", C.c_int32), ("v_dtype", C.c_int32)]
+
+    def __repr__(self):
+        return f"Config({self.bits},{self.block},{self.scale_block},{self.scale_bits},{self.v_dtype})"
+
+
+def config(bits, block, scale_block, scale_bits=8, v_dtype="fp32") -> Config:
+    return Config(bits, block, scale_block, scale_bits, V_DTYPES[v_dtype] if isinstance(v_dtype, str) else v_dtype)
+
+
+class SvdParams(C.Structure):
+    """lq_svd_params; zero fields select the library defaults."""
+    _fields_ = [("first_width", C.c_int32), ("first_tol", C.c_float), ("first_check", C.c_int32),
+                ("first_max", C.c_int32), ("warm_width", C.c_int32), ("warm_power", C.c_int32),
+                ("warm_power_2", C.c_int32), ("max_batch", C.c_int32)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2311_12023_amd.build`")
+_lib = C.CDLL(LIB_PATH)
+
+_vp, _i64, _int, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+_lib.lq_status_string.restype = C.c_char_p
+_lib.lq_status_string.argtypes = [_int]
+_lib.lq_last_hip_error.restype = _int
+_lib.lq_nf_codebook.argtypes = [_int, _vp]
+_lib.lq_codes_bytes.restype = _sz
+_lib.lq_codes_bytes.argtypes = [_i64, _int]
+_lib.lq_storage_bits.restype = C.c_double
+_lib.lq_storage_bits.argtypes = [_i64, Config]
+_lib.lq_nf_quantize.argtypes = [_vp, _i64, Config, _vp, _vp, _vp, _vp]
+_lib.lq_nf_dequantize.argtypes = [_vp, _vp, _vp, _i64, Config, _vp, _vp]
+_PP = C.POINTER(SvdParams)
+_lib.lq_factorize_workspace_bytes.restype = _sz
+_lib.lq_factorize_workspace_bytes.argtypes = [_i64, _i64, _int, _PP]
+_lib.lq_factorize.argtypes = [_vp, _i64, _i64, _int, _vp, _vp, C.c_uint64, _PP, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.lq_decompose_workspace_bytes.restype = _sz
+_lib.lq_decompose_workspace_bytes.argtypes = [_i64, _i64, _int, _PP]
+_lib.lq_decompose.argtypes = [_vp, _i64, _i64, _int, Config, _int, _int, _vp, _vp, C.c_uint64, _PP,
+                              _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.lq_error_table_workspace_bytes.restype = _sz
+_lib.lq_error_table_workspace_bytes.argtypes = [_i64, _i64, _int, _int, _PP]
+_lib.lq_error_table.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _int, _int, _vp, _vp, C.c_uint64, _PP,
+                                _vp, _vp, _vp, _vp, _sz, _vp]
+
+
+def _check(status, where):
+    if status != 0:
+        raise LqError(status, where)
+
+
+def _dev(t, dtype, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _pp(p):
+    return None if p is None else C.byref(p)
+
+
+def nf_codebook(bits: int) -> np.ndarray:
+    out = np.zeros(1 << max(bits, 0) if 0 < bits <= 8 else 1, np.float32)
+    _check(_lib.lq_nf_codebook(bits, out.ctypes.data), "lq_nf_codebook")
+    return out
+
+
+def codes_bytes(n: int, bits: int) -> int:
+    return _lib.lq_codes_bytes(n, bits)
+
+
+def storage_bits(n: int, cfg: Config) -> float:
+    return _lib.lq_storage_bits(n, cfg)
+
+
+def nf_quantize(x: torch.Tensor, cfg: Config):
+    """Quantize(x, c): -> (codes_packed uint8, scale_idx uint8, v fp32), all on x's device."""
+    n = x.numel()
+    sb = cfg.scale_bits or 8
+    nb = n // max(cfg.block, 1)
+    ng = (nb + max(cfg.scale_block, 1) - 1) // max(cfg.scale_block, 1)
+    codes = torch.empty(max(codes_bytes(n, cfg.bits), 1), dtype=torch.uint8, device=x.device)
+    sidx = torch.empty(max(nb, 1), dtype=torch.uint8, device=x.device)
+    v = torch.empty(max(ng, 1), dtype=torch.float32, device=x.device)
+    _check(_lib.lq_nf_quantize(_dev(x, torch.float32, "x"), n, cfg, codes.data_ptr(), sidx.data_ptr(), v.data_ptr(),
+                               _stream()), "lq_nf_quantize")
+    return codes, sidx, v
+
+
+def nf_dequantize(codes: torch.Tensor, scale_idx: torch.Tensor, v: torch.Tensor, n: int, cfg: Config,
+                  out: torch.Tensor | None = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    _check(_lib.lq_nf_dequantize(_dev(codes, torch.uint8, "codes"), _dev(scale_idx, torch.uint8, "scale_idx"),
+                                 _dev(v, torch.float32, "v"), n, cfg, _dev(out, torch.float32, "out"), _stream()),
+           "lq_nf_dequantize")
+    return out
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+
+
+def _aligned_ptr(ws: torch.Tensor) -> int:
+    p = ws.data_ptr()
+    return (p + 255) & ~255
+
+
+def factorize(a: torch.Tensor, rank: int, row_w=None, col_w=None, seed: int = 0, params: SvdParams | None = None,
+              workspace: torch.Tensor | None = None):
+    """Factorize(A, F, r): -> (L1 d x r, L2 r x k, sigma numpy float64[r])."""
+    d, k = a.shape
+    need = _lib.lq_factorize_workspace_bytes(d, k, rank, _pp(params))
+    ws = workspace if workspace is not None else _workspace(need, a.device)
+    l1 = torch.empty((d, rank), dtype=torch.float32, device=a.device)
+    l2 = torch.empty((rank, k), dtype=torch.float32, device=a.device)
+    sigma = np.zeros(max(rank, 1))
+    _check(_lib.lq_factorize(_dev(a, torch.float32, "a"), d, k, rank, _dev(row_w, torch.float32, "row_w"),
+                             _dev(col_w, torch.float32, "col_w"), seed, _pp(params), l1.data_ptr(), l2.data_ptr(),
+                             sigma.ctypes.data, _aligned_ptr(ws), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()),
+                             _stream()), "lq_factorize")
+    return l1, l2, sigma
+
+
+def decompose(w: torch.Tensor, rank: int, cfg: Config, iters: int, early_stop: bool = False, row_w=None, col_w=None,
+              seed: int = 0, params: SvdParams | None = None, want_dense: bool = False,
+              workspace: torch.Tensor | None = None):
+    """LQ(W, F, c, r): -> dict(L1, L2, codes, scale_idx, v, Q, err, trace, iters_done, sigma)."""
+    d, k = w.shape
+    n = d * k
+    nb = n // max(cfg.block, 1)
+    ng = (nb + max(cfg.scale_block, 1) - 1) // max(cfg.scale_block, 1)
+    need = _lib.lq_decompose_workspace_bytes(d, k, rank, _pp(params))
+    ws = workspace if workspace is not None else _workspace(need, w.device)
+    dev = w.device
+    out = dict(L1=torch.empty((d, max(rank, 1)), dtype=torch.float32, device=dev),
+               L2=torch.empty((max(rank, 1), k), dtype=torch.float32, device=dev),
+               codes=torch.empty(max(codes_bytes(n, cfg.bits), 1), dtype=torch.uint8, device=dev),
+               scale_idx=torch.empty(max(nb, 1), dtype=torch.uint8, device=dev),
+               v=torch.empty(max(ng, 1), dtype=torch.float32, device=dev),
+               Q=torch.empty((d, k), dtype=torch.float32, device=dev) if want_dense else None)
+    err = C.c_double(float("nan"))
+    done = C.c_int32(0)
+    trace = np.full(max(iters, 1), np.nan)
+    sigma = np.zeros(max(rank, 1))
+    _check(_lib.lq_decompose(_dev(w, torch.float32, "w"), d, k, rank, cfg, iters, 1 if early_stop else 0,
+                             _dev(row_w, torch.float32, "row_w"), _dev(col_w, torch.float32, "col_w"), seed,
+                             _pp(params), out["L1"].data_ptr(), out["L2"].data_ptr(), out["codes"].data_ptr(),
+                             out["scale_idx"].data_ptr(), out["v"].data_ptr(),
+                             None if out["Q"] is None else out["Q"].data_ptr(), C.addressof(err), trace.ctypes.data,
+                             C.addressof(done), sigma.ctypes.data, _aligned_ptr(ws),
+                             ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()), "lq_decompose")
+    out.update(err=err.value, trace=trace, iters_done=done.value, sigma=sigma)
+    return out
+
+
+def error_table_workspace(d: int, k: int, rank: int, n_cfgs: int, params: SvdParams | None = None, device="cuda"):
+    return _workspace(_lib.lq_error_table_workspace_bytes(d, k, rank, n_cfgs, _pp(params)), device)
+
+
+def error_table(w: torch.Tensor, rank: int, cfgs, iters: int, early_stop: bool = False, row_w=None, col_w=None,
+                seed: int = 0, params: SvdParams | None = None, workspace: torch.Tensor | None = None,
+                want_trace: bool = False):
+    """Algorithm 3 inner loops for one matrix: -> (err_sq, storage_bits[, trace]) numpy float64."""
+    d, k = w.shape
+    arr = (Config * max(len(cfgs), 1))(*cfgs)
+    ws = workspace if workspace is not None else error_table_workspace(d, k, rank, len(cfgs), params, w.device)
+    e = np.zeros(max(len(cfgs), 1))
+    s = np.zeros(max(len(cfgs), 1))
+    tr = np.full((max(len(cfgs), 1), max(iters, 1)), np.nan) if want_trace else None
+    _check(_lib.lq_error_table(_dev(w, torch.float32, "w"), d, k, rank, C.addressof(arr), len(cfgs), iters,
+                               1 if early_stop else 0, _dev(row_w, torch.float32, "row_w"),
+                               _dev(col_w, torch.float32, "col_w"), seed, _pp(params), e.ctypes.data, s.ctypes.data,
+                               None if tr is None else tr.ctypes.data, _aligned_ptr(ws),
+                               ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()), "lq_error_table")
+    return (e, s, tr) if want_trace else (e, s)
+
+
+def fisher_row_col(f: torch.Tensor):
+    """RowAverage / ColAverage of sqrt(F) (Algorithm 4) as Fisher-scale vectors for row_w / col_w:
+    row_w = a^2, col_w = (b / mean(sqrt F))^2 with a, b the row / column means of sqrt(F).
+    Set-up step, run once per matrix with plain tensor ops on the device holding F."""
+    sf = f.to(torch.float64).sqrt()
+    a = sf.mean(dim=1)
+    b = sf.mean(dim=0) / sf.mean()
+    return (a * a).to(torch.float32).contiguous(), (b * b).to(torch.float32).contiguous()
