@@ -1,0 +1,34 @@
+/*
+ * lq_testing.h  --  entry points that expose single kernels of the randomized SVD to the test-suite.
+ * They are part of the shared library so that each building block can be checked against a plain
+ * reference on the GPU machine; applications use lq.h only.  All pointers are device pointers, matrices
+ * row-major.  "Wide" matrices have l rows (multiple of 32, at most 256) and a leading dimension that
+ * is a multiple of 32 with zero padding.  Each call enqueues on `stream` and returns an lq_status.
+ */
+#ifndef LQ_TESTING_H_
+#define LQ_TESTING_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* mode 0: C[l x big] = X[l x K] * A[big x K]^T;  mode 1: C[l x big] = X[l x K] * A[K x big].
+ * part: scratch of splits * l * ldc floats (used when splits > 1). */
+int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
+                      int64_t lda, float* C, int64_t ldc, int splits, float* part, void* stream);
+/* Rows of X (l x m) are orthonormalised in place by Cholesky-QR (Gram in fp64).
+ * scratch: at least 17 * l * l doubles. */
+int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, void* stream);
+/* Eigen-decomposition of the symmetric l x l fp64 matrix G (destroyed): eigenvalues descending in
+ * lambda (l doubles), eigenvectors as rows of Ut (l x l fp32).  scratch: l * l doubles. */
+int lq_test_sym_eig(double* G, int l, float* Ut, double* lambda, double* scratch, void* stream);
+/* Largest LDS allocation per workgroup the device reports, in bytes. */
+size_t lq_test_lds_limit(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LQ_TESTING_H_ */

@@ -1,0 +1,263 @@
+// fp32 MFMA GEMMs of the randomized SVD (the sketch, power-iteration and projection products of
+// Algorithm 4's "SVD(A, r)"), written for gfx950's v_mfma_f32_32x32x2_f32.
+//
+// Every product has one skinny operand X (l x K, l = 32*LT <= 256 rows, row-major, K contiguous) and
+// one large operand A that is streamed from HBM exactly once:
+//   MODE_NT:  C[l x M] = X[l x K] * A[M x K]^T      (A row-major, reduction along A's rows)
+//   MODE_NN:  C[l x N] = X[l x K] * A[K x N]        (A row-major, reduction down A's columns)
+// The result is "wide" again (l rows), so the output of one product is the X of the next.
+//
+// Mapping: a workgroup has 4 wavefronts.  X's K-chunk (l x 32) is staged in LDS and shared; each
+// wavefront fetches its own slice of A straight from global memory in MFMA operand layout (every
+// element of A is needed by one wavefront only, so LDS staging would buy nothing) and owns
+// LT x NT accumulator tiles of 32x32.  The reduction index inside a 32-chunk is permuted
+// (lane half h, register e, sub-chunk c  <->  k = 8c + 4h + e) so that both operands are fetched with
+// 128-bit loads; any permutation is valid as long as A and X agree on it.
+// gridDim = (tiles along the large dimension, K splits, batch).  With K splits > 1 each split writes
+// its own partial result and splitk_reduce_kernel adds them in a fixed order (deterministic).
+#include "kernels.h"
+
+namespace lq {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 32;           // K chunk staged per step
+constexpr int XPITCH = BK + 4;   // LDS row pitch in floats: 16-byte aligned rows, conflict-free b128 reads
+
+template <int LT, int MODE, int NT>
+__global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
+  extern __shared__ float xs[];   // [32*LT][XPITCH]
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int ln = lane & 31, lh = lane >> 5;
+  const int split = blockIdx.y, z = blockIdx.z;
+  constexpr int L = 32 * LT;
+
+  const float* __restrict__ X = g.X + (size_t)z * g.strideX;
+  const float* __restrict__ A = g.A + (size_t)z * g.strideA;
+  float* __restrict__ C = g.C + ((size_t)z * g.splits + split) * g.strideC;
+
+  const int64_t kbeg = (int64_t)split * g.kchunk;
+  const int64_t kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
+  const int nsteps = (int)((kend - kbeg + BK - 1) / BK);
+
+  // this wavefront's slice of the large dimension
+  int64_t big0;   // first row (NT mode) or column (NN mode) of the slice
+  if constexpr (MODE == MODE_NT) big0 = (int64_t)blockIdx.x * 128 + wave * 32;
+  else big0 = (int64_t)blockIdx.x * (128 * NT) + wave * (32 * NT);
+
+  floatx16 acc[LT][NT];
+#pragma unroll
+  for (int i = 0; i < LT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  // ---- operand fetch helpers -----------------------------------------------------------------
+  // X tile: L x 32 floats = L*8 float4, LT per thread.  X has a padded, zero-filled leading dimension
+  // that is a multiple of 32, so no K guard is needed on it.
+  float4 xreg[LT];
+  auto fetch_x = [&](int64_t k0) {
+#pragma unroll
+    for (int i = 0; i < LT; ++i) {
+      const int idx = tid + i * 256;            // float4 index in the tile
+      const int row = idx >> 3, c4 = idx & 7;
+      xreg[i] = *reinterpret_cast<const float4*>(X + (size_t)row * g.ldx + k0 + c4 * 4);
+    }
+  };
+  auto stash_x = [&]() {
+#pragma unroll
+    for (int i = 0; i < LT; ++i) {
+      const int idx = tid + i * 256;
+      const int row = idx >> 3, c4 = idx & 7;
+      *reinterpret_cast<float4*>(xs + row * XPITCH + c4 * 4) = xreg[i];
+    }
+  };
+  // A operand of one 32-chunk: breg[c][e][j], k = k0 + 8c + 4h + e.
+  float breg[4][4][NT];
+  auto fetch_a = [&](int64_t k0) {
+    if constexpr (MODE == MODE_NT) {
+      int64_t row = big0 + ln;
+      if (row >= g.big) row = g.big - 1;        // clamped rows are computed and never stored
+      const float* p = A + (size_t)row * g.lda;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int64_t kk = k0 + 8 * c + 4 * lh;
+        float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (kk < kend) f = *reinterpret_cast<const float4*>(p + kk);   // K and kend are multiples of 4
+        breg[c][0][0] = f.x; breg[c][1][0] = f.y; breg[c][2][0] = f.z; breg[c][3][0] = f.w;
+      }
+    } else {
+      int64_t col = big0 + (int64_t)ln * NT;
+      if (col + NT > g.big) col = g.big - NT;   // big is a multiple of NT; clamped columns never stored
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int64_t kk = k0 + 8 * c + 4 * lh + e;
+          if constexpr (NT == 2) {
+            float2 f = make_float2(0.f, 0.f);
+            if (kk < kend) f = *reinterpret_cast<const float2*>(A + (size_t)kk * g.lda + col);
+            breg[c][e][0] = f.x; breg[c][e][1] = f.y;
+          } else {
+            float f = 0.f;
+            if (kk < kend) f = A[(size_t)kk * g.lda + col];
+            breg[c][e][0] = f;
+          }
+        }
+    }
+  };
+
+  if (nsteps > 0) {
+    fetch_x(kbeg);
+    fetch_a(kbeg);
+  }
+  for (int step = 0; step < nsteps; ++step) {
+    __syncthreads();          // everyone is done reading the previous X tile
+    stash_x();
+    float bcur[4][4][NT];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) bcur[c][e][j] = breg[c][e][j];
+    __syncthreads();
+    if (step + 1 < nsteps) {   // next chunk's loads fly while this chunk multiplies
+      const int64_t k1 = kbeg + (int64_t)(step + 1) * BK;
+      fetch_x(k1);
+      fetch_a(k1);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+#pragma unroll
+      for (int i = 0; i < LT; ++i) {
+        const float4 a4 = *reinterpret_cast<const float4*>(xs + (32 * i + ln) * XPITCH + 8 * c + 4 * lh);
+        const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bcur[c][e][j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- store: accumulator element e of a lane is row 8*(e/4) + 4*h + e%4, column n of its tile ----
+  if constexpr (MODE == MODE_NT) {
+    const int64_t col = big0 + ln;
+    if (col < g.big) {
+#pragma unroll
+      for (int i = 0; i < LT; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
+          C[(size_t)row * g.ldc + col] = acc[i][0][e];
+        }
+    }
+  } else {
+    const int64_t col = big0 + (int64_t)ln * NT;
+    if (col + NT <= g.big) {
+#pragma unroll
+      for (int i = 0; i < LT; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
+          if constexpr (NT == 2)
+            *reinterpret_cast<float2*>(C + (size_t)row * g.ldc + col) = make_float2(acc[i][0][e], acc[i][1][e]);
+          else
+            C[(size_t)row * g.ldc + col] = acc[i][0][e];
+        }
+    }
+  }
+  (void)L;
+}
+
+// out[z][i] = sum_s part[z][s][i], i < count (count = rows * ldc), fixed summation order.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                            int splits, int64_t count4, size_t part_stride,
+                                                            size_t out_stride) {
+  const int z = blockIdx.y;
+  const float4* p = reinterpret_cast<const float4*>(part + (size_t)z * splits * part_stride);
+  float4* o = reinterpret_cast<float4*>(out + (size_t)z * out_stride);
+  const size_t ps4 = part_stride / 4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += (int64_t)gridDim.x * 256) {
+    float4 s = p[i];
+    for (int q = 1; q < splits; ++q) {
+      const float4 t = p[(size_t)q * ps4 + i];
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    o[i] = s;
+  }
+}
+
+template <int LT, int MODE, int NT>
+static void launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
+  const size_t lds = (size_t)32 * LT * XPITCH * sizeof(float);
+  hipLaunchKernelGGL((wide_gemm_kernel<LT, MODE, NT>), grid, dim3(256), lds, st, g);
+}
+
+template <int MODE>
+static int launch_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
+  switch (lt) {
+    case 1: launch_one<1, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
+    case 2: launch_one<2, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
+    case 3: launch_one<3, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
+    case 4: launch_one<4, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
+    case 5: launch_one<5, MODE, 1>(g, grid, st); break;
+    case 6: launch_one<6, MODE, 1>(g, grid, st); break;
+    case 7: launch_one<7, MODE, 1>(g, grid, st); break;
+    case 8: launch_one<8, MODE, 1>(g, grid, st); break;
+    default: return LQ_ERR_ARG;
+  }
+  return LQ_OK;
+}
+
+int gemm_tile_span(int mode, int lt) { return mode == MODE_NT ? 128 : (lt <= 4 ? 256 : 128); }
+
+// Number of K splits for a product: enough workgroups to fill 256 CUs a few times over, chunks that are
+// multiples of 32 and at least 256 long.
+int gemm_choose_splits(int mode, int lt, int64_t big, int64_t K, int batch) {
+  const int64_t tiles = (big + gemm_tile_span(mode, lt) - 1) / gemm_tile_span(mode, lt);
+  const int64_t have = tiles * batch;
+  int64_t s = (1024 + have - 1) / have;
+  const int64_t smax = (K + 255) / 256;
+  if (s > smax) s = smax;
+  if (s > 32) s = 32;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+// C = X * op(A) for `batch` problems.  `part` is scratch for splits > 1 (batch * splits * l * ldc floats).
+int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
+                     const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
+                     int splits, float* part, hipStream_t st) {
+  if (l % 32 != 0 || l < 32 || l > 256 || big < 1 || K < 1 || batch < 1) return LQ_ERR_ARG;
+  if (mode == MODE_NN && (big % 2) != 0) return LQ_ERR_ARG;
+  const int lt = l / 32;
+  GemmArgs g;
+  g.X = X; g.A = A; g.ldx = ldx; g.lda = lda; g.ldc = ldc; g.strideX = strideX; g.strideA = strideA;
+  g.big = big; g.K = K; g.splits = splits;
+  int64_t kchunk = (K + splits - 1) / splits;
+  kchunk = (kchunk + BK - 1) / BK * BK;
+  g.kchunk = kchunk;
+  const size_t out_elems = (size_t)l * ldc;
+  if (splits > 1) { g.C = part; g.strideC = out_elems; }
+  else { g.C = C; g.strideC = strideC; }
+  const int span = gemm_tile_span(mode, lt);
+  const dim3 grid((unsigned)((big + span - 1) / span), (unsigned)splits, (unsigned)batch);
+  int rc = (mode == MODE_NT) ? launch_mode<MODE_NT>(g, lt, grid, st) : launch_mode<MODE_NN>(g, lt, grid, st);
+  if (rc != LQ_OK) return rc;
+  LQ_HIP_TRY(hipGetLastError());
+  if (splits > 1) {
+    const int64_t count4 = (int64_t)(out_elems / 4);
+    const dim3 rgrid((unsigned)((count4 + 255) / 256 < 2048 ? (count4 + 255) / 256 : 2048), (unsigned)batch);
+    hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, dim3(256), 0, st, (const float*)part, C, splits, count4,
+                       out_elems, strideC);
+    LQ_HIP_TRY(hipGetLastError());
+  }
+  return LQ_OK;
+}
+
+}  // namespace lq

@@ -1,0 +1,106 @@
+// Launchers of the randomized-SVD and fused decomposition kernels (host-callable, all asynchronous on
+// the given stream).  "Wide" matrices are l x m row-major with l = 32..256 rows (a multiple of 32) and
+// a zero-padded leading dimension that is a multiple of 32.
+#pragma once
+
+#include "lq_internal.h"
+
+namespace lq {
+
+struct DevTables;
+
+constexpr int MODE_NT = 0;   // C[l x M] = X[l x K] * A[M x K]^T
+constexpr int MODE_NN = 1;   // C[l x N] = X[l x K] * A[K x N]
+
+struct GemmArgs {
+  const float* X;
+  const float* A;
+  float* C;
+  int64_t ldx, lda, ldc;
+  size_t strideX, strideA, strideC;   // per-problem strides in floats (0 = shared operand)
+  int64_t big;                        // extent of the large output dimension (M or N)
+  int64_t K, kchunk;                  // reduction length and length per split
+  int splits;
+};
+
+int gemm_tile_span(int mode, int lt);
+int gemm_choose_splits(int mode, int lt, int64_t big, int64_t K, int batch);
+int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
+                     const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
+                     int splits, float* part, hipStream_t st);
+
+// ---- small dense kernels (small_kernels.hip) --------------------------------------------------
+constexpr int GRAM_CHUNKS = 16;
+// G[z] (l x l, fp64, row-major) = X[z] X[z]^T for wide X (l x m, fp32).  `part` holds
+// batch * GRAM_CHUNKS * l * l doubles of scratch.
+int launch_gram(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, double* part, double* G, int batch,
+                hipStream_t st);
+// In-place Cholesky G = C C^T (lower C, fp64; the strict upper triangle is left untouched).  A pivot that
+// is not positive relative to the largest diagonal entry marks a dependent direction: its diagonal entry
+// is stored as 0 and the triangular solve zeroes that row.
+int launch_cholesky(double* G, int l, int batch, hipStream_t st);
+// X[z] <- C[z]^-1 X[z] by forward substitution (C lower triangular, fp64, from launch_cholesky).
+int launch_trsm(const double* Cfac, int l, float* X, int64_t m, int64_t ldx, size_t strideX, int batch,
+                hipStream_t st);
+// Symmetric eigen-decomposition by parallel two-sided Jacobi, fp64.  G (l x l) is destroyed.  Outputs,
+// sorted by descending eigenvalue: lambda[z][l] and Ut[z] (l x l fp32, row j = j-th eigenvector).
+// `vt` holds batch * l * l doubles of scratch.
+int launch_jacobi_eig(double* G, int l, double* vt, float* Ut, double* lambda, int batch, hipStream_t st);
+// Fills a wide matrix (l x m, padded ld) with N(0,1) draws from a counter-based generator; pads are zeroed.
+int launch_gaussian_fill(float* X, int l, int64_t m, int64_t ldx, uint64_t seed, hipStream_t st);
+// out[i][j] = sr[i] * A[i][j] * sc[j]  (sr = sqrt(row_w), sc = sqrt(col_w): D_row A D_col of Eq. 5).
+int launch_scale_matrix(const float* A, int64_t d, int64_t k, const float* sr, const float* sc, float* out,
+                        hipStream_t st);
+// s[i] = sqrt(w[i]), rs[i] = 1/sqrt(w[i]).
+int launch_sqrt_vecs(const float* w, int64_t n, float* s, float* rs, hipStream_t st);
+// Balanced factors from Ritz-ordered wide bases (Algorithm 4): L1[i][p] = Y[p][i] sqrt(sigma_p) rsr[i],
+// L2[p][j] = B[p][j] / sqrt(sigma_p) * rsc[j], sigma_p = sqrt(lambda_p).  rsr / rsc may be NULL (= 1).
+int launch_assemble_factors(const float* Y, int64_t ldy, const float* B, int64_t ldb, const double* lambda, int rank,
+                            int64_t d, int64_t k, const float* rsr, const float* rsc, float* L1, float* L2,
+                            hipStream_t st);
+
+// ---- fused kernels of the LQ loop (fused_kernels.hip) -------------------------------------------
+struct LoopProblem {       // one (matrix, configuration) cell of a lock-step batch; lives in device memory
+  lq_config cfg;
+  int32_t levels;          // 2^(b1-1) - 1
+  int32_t pad[2];
+};
+
+struct PhaseArgs {
+  const float* W;          // d x k, shared by the batch
+  int64_t d, k;
+  int rank;
+  const float* Y;          // wide Ritz basis (>= rank rows used), ld = ldy, per-problem stride strideY
+  const float* B;          // wide projected matrix, ld = ldb, stride strideB
+  int64_t ldy, ldb;
+  size_t strideY, strideB;
+  const float* rsr;        // 1/sqrt(row_w) (d) or NULL
+  const float* rsc;        // 1/sqrt(col_w) (k) or NULL
+  const float* sr;         // sqrt(row_w) or NULL
+  const float* sc;         // sqrt(col_w) or NULL
+  const float* row_w;      // Fisher-scale weights or NULL
+  const float* col_w;
+  const LoopProblem* prob; // batch entries
+  const DevTables* tables; // code-books and thresholds on this device
+  uint8_t* codes;   size_t strideCodes;     // bytes
+  BlockRec* blk;    size_t strideBlk;       // records
+  uint8_t* sidx;    size_t strideSidx;
+  float* v;         size_t strideV;
+  float* R;         size_t strideR;         // scaled residual sqrt(rw_i) (W - Q) sqrt(cw_j), or NULL
+  float* Qd;        size_t strideQd;        // dense Q or NULL
+  double* err_part; size_t strideErrPart;   // per-workgroup partial sums of the squared error
+  double* err_out;  size_t strideErrOut;    // eps (norm) of this iteration, one double per problem
+  int batch;
+};
+
+// Phase 1: T = W - L1 L2 tile by tile (MFMA), block absmax, codes, per-block error sums.
+int launch_lowrank_blockquant(const PhaseArgs& a, hipStream_t st);
+// Phase 2: Quantize-INT of the block absmax values, cast of v, and eps of the iteration (err_out).
+// min_block: smallest B0 in the batch (sizes the grid).
+int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st);
+// Phase 3: R = sqrt(rw_i) (W - Q) sqrt(cw_j) and / or dense Q.
+int launch_residual(const PhaseArgs& a, hipStream_t st);
+// Number of error partials phase 2 writes per problem for block size B0.
+int64_t err_partials_per_problem(int64_t n, int block);
+
+}  // namespace lq

@@ -1,14 +1,505 @@
-// C ABI, part 2 (placeholder while the decomposition kernels are being brought up).
-#include "lq_internal.h"
-extern "C" {
-size_t lq_factorize_workspace_bytes(int64_t, int64_t, int, const lq_svd_params*) { return 0; }
-int lq_factorize(const float*, int64_t, int64_t, int, const float*, const float*, uint64_t, const lq_svd_params*,
-                 float*, float*, double*, void*, size_t, void*) { return LQ_ERR_ARG; }
-size_t lq_decompose_workspace_bytes(int64_t, int64_t, int, const lq_svd_params*) { return 0; }
-int lq_decompose(const float*, int64_t, int64_t, int, lq_config, int, int, const float*, const float*, uint64_t,
-                 const lq_svd_params*, float*, float*, uint8_t*, uint8_t*, float*, float*, double*, double*, int32_t*,
-                 double*, void*, size_t, void*) { return LQ_ERR_ARG; }
-size_t lq_error_table_workspace_bytes(int64_t, int64_t, int, int, const lq_svd_params*) { return 0; }
-int lq_error_table(const float*, int64_t, int64_t, int, const lq_config*, int, int, int, const float*, const float*,
-                   uint64_t, const lq_svd_params*, double*, double*, double*, void*, size_t, void*) { return LQ_ERR_ARG; }
+// C ABI, part 2: Factorize (Algorithm 4), the LQ loop (Algorithm 2) and the error-table sweep
+// (Algorithm 3).  Host orchestration only: validation, workspace carving, kernel sequencing.
+//
+// Data layout.  Every skinny matrix of the randomized SVD is kept "wide": l rows (the subspace
+// dimension) by d or k columns, row-major, leading dimension padded to a multiple of 32 with zeros.
+//   Y (l x d): orthonormal rows spanning the left subspace;   B = Y A (l x k): projected matrix.
+// After the Rayleigh-Ritz rotation the rows are ordered by descending singular value, so the first
+// `rank` rows give L1 L2 = Y_r^T B_r, and the first `warm_width` rows seed the next iteration.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "../../include/lq_testing.h"
+#include "kernels.h"
+#include "nf_device.h"
+
+namespace lq {
+
+int check_quant_args(int64_t n, lq_config& c);
+size_t lds_limit_for_tests();
+
+constexpr int MAX_ITERS = 1024;
+constexpr int MAX_RANK = 128;
+
+static int64_t up32(int64_t x) { return (x + 31) / 32 * 32; }
+static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct Params {
+  int l1, check, maxit, lw, qw, qw2, max_batch;
+  double tol;
+};
+
+static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
+  lq_svd_params z;
+  std::memset(&z, 0, sizeof(z));
+  if (p) z = *p;
+  out.l1 = z.first_width ? z.first_width : (int)std::min<int64_t>(256, up32(std::max(2 * rank, rank + 56)));
+  out.tol = z.first_tol > 0 ? z.first_tol : 1e-6;
+  out.check = z.first_check ? z.first_check : 8;
+  out.maxit = z.first_max ? z.first_max : 600;
+  out.lw = z.warm_width ? z.warm_width : (int)std::min<int64_t>(out.l1, up32(rank + std::max(rank / 2, 24)));
+  out.qw = z.warm_power ? z.warm_power : 2;
+  out.qw2 = z.warm_power_2 ? z.warm_power_2 : 3;
+  out.max_batch = z.max_batch ? z.max_batch : 36;
+  if (out.l1 % 32 || out.l1 <= rank || out.l1 > 256) return LQ_ERR_ARG;
+  if (out.lw % 32 || out.lw <= rank || out.lw > out.l1) return LQ_ERR_ARG;
+  if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.max_batch < 1) return LQ_ERR_ARG;
+  return LQ_OK;
 }
+
+static int check_matrix_args(int64_t d, int64_t k, int rank) {
+  if (d <= 0 || k <= 0 || d > (1 << 30) || k > (1 << 30)) return LQ_ERR_SHAPE;
+  if (k % 16 != 0) return LQ_ERR_SHAPE;       // rows are whole 16-weight runs (every block size divides k)
+  if (rank < 1 || rank > MAX_RANK || rank >= std::min(d, k)) return LQ_ERR_RANK;
+  return LQ_OK;
+}
+
+// ---- workspace plan ---------------------------------------------------------------------------------
+struct Plan {
+  int64_t d, k, ldd, ldk, n;
+  int rank, batch, lmax;
+  Params prm;
+  // shared
+  size_t sr, sc, rsr, rsc;              // floats: d, k, d, k
+  size_t Ya, Yb, Ba, Bb;                // cold-start wide bases (l1 rows)
+  size_t gpart, gram_part, G, Vt, Ut, lam, lam_cold, prob, errs;
+  // per problem (offset of problem 0, stride)
+  size_t R, strideR;
+  size_t Yw, Yw2, strideYw;             // floats
+  size_t Bw, Bw2, strideBw;
+  size_t codes, strideCodes, blk, strideBlk, sidx, strideSidx, v, strideV, epart, strideEpart;
+  size_t gpart_floats;
+  size_t total;
+};
+
+static size_t gemm_part_floats(int l, int64_t ldd, int64_t ldk, int64_t d, int64_t k, int batch) {
+  const int lt = l / 32;
+  const int s_nt = gemm_choose_splits(MODE_NT, lt, d, k, batch);     // output l x d, reduce over k
+  const int s_nn = gemm_choose_splits(MODE_NN, lt, k, d, batch);     // output l x k, reduce over d
+  size_t a = s_nt > 1 ? (size_t)batch * s_nt * l * ldd : 0;
+  size_t b = s_nn > 1 ? (size_t)batch * s_nn * l * ldk : 0;
+  return std::max(a, b);
+}
+
+static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int batch, Plan& pl) {
+  pl.d = d; pl.k = k; pl.ldd = up32(d); pl.ldk = up32(k); pl.n = d * k;
+  pl.rank = rank; pl.batch = batch; pl.prm = prm; pl.lmax = prm.l1;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+  const int l1 = prm.l1, lw = prm.lw;
+  pl.sr = take(d * 4); pl.sc = take(k * 4); pl.rsr = take(d * 4); pl.rsc = take(k * 4);
+  pl.Ya = take((size_t)l1 * pl.ldd * 4); pl.Yb = take((size_t)l1 * pl.ldd * 4);
+  pl.Ba = take((size_t)l1 * pl.ldk * 4); pl.Bb = take((size_t)l1 * pl.ldk * 4);
+  pl.gpart_floats = std::max(gemm_part_floats(l1, pl.ldd, pl.ldk, d, k, 1),
+                             gemm_part_floats(lw, pl.ldd, pl.ldk, d, k, batch));
+  pl.gpart = take(pl.gpart_floats * 4);
+  const size_t ll = (size_t)l1 * l1;
+  pl.gram_part = take((size_t)batch * GRAM_CHUNKS * ll * 8);
+  pl.G = take((size_t)batch * ll * 8);
+  pl.Vt = take((size_t)batch * ll * 8);
+  pl.Ut = take((size_t)batch * ll * 4);
+  pl.lam = take((size_t)batch * l1 * 8);
+  pl.lam_cold = take((size_t)l1 * 8);
+  pl.prob = take((size_t)batch * sizeof(LoopProblem));
+  pl.errs = take((size_t)batch * MAX_ITERS * 8);
+  const size_t n = (size_t)pl.n;
+  pl.strideR = up256(n * 4) / 4;            pl.R = take(pl.strideR * 4 * batch);
+  pl.strideYw = (size_t)lw * pl.ldd;        pl.Yw = take(pl.strideYw * 4 * batch); pl.Yw2 = take(pl.strideYw * 4 * batch);
+  pl.strideBw = (size_t)lw * pl.ldk;        pl.Bw = take(pl.strideBw * 4 * batch); pl.Bw2 = take(pl.strideBw * 4 * batch);
+  pl.strideCodes = up256(n);                pl.codes = take(pl.strideCodes * batch);
+  pl.strideBlk = up256(n / 16 * sizeof(BlockRec)) / sizeof(BlockRec); pl.blk = take(pl.strideBlk * sizeof(BlockRec) * batch);
+  pl.strideSidx = up256(n / 16);            pl.sidx = take(pl.strideSidx * batch);
+  pl.strideV = up256(n / 256 * 4 + 4) / 4;  pl.v = take(pl.strideV * 4 * batch);
+  pl.strideEpart = up256((size_t)err_partials_per_problem(pl.n, 16) * 8) / 8; pl.epart = take(pl.strideEpart * 8 * batch);
+  pl.total = off;
+}
+
+// ---- execution context --------------------------------------------------------------------------------
+struct Ctx {
+  Plan pl;
+  char* ws;
+  hipStream_t st;
+  const float* W;
+  const float* row_w;
+  const float* col_w;
+  bool weighted;
+  const DevTables* tables;
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+static int orthonormalize(const Ctx& c, float* X, int l, int64_t m, int64_t ldx, size_t strideX, int batch) {
+  double* G = c.at<double>(c.pl.G);
+  LQ_TRY(launch_gram(X, l, m, ldx, strideX, c.at<double>(c.pl.gram_part), G, batch, c.st));
+  LQ_TRY(launch_cholesky(G, l, batch, c.st));
+  return launch_trsm(G, l, X, m, ldx, strideX, batch, c.st);
+}
+
+static int gemm(const Ctx& c, int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t sX,
+                const float* A, int64_t lda, size_t sA, float* C, int64_t ldc, size_t sC, int batch) {
+  int splits = gemm_choose_splits(mode, l / 32, big, K, batch);
+  if (splits > 1 && (size_t)batch * splits * l * ldc > c.pl.gpart_floats) splits = 1;
+  return launch_wide_gemm(mode, l, big, K, X, ldx, sX, A, lda, sA, C, ldc, sC, batch, splits,
+                          c.at<float>(c.pl.gpart), c.st);
+}
+
+// Rayleigh-Ritz on the subspace spanned by the rows of Y (orthonormal) with B = Y A:
+// eigen-decomposition of B B^T, then both bases are rotated into Ritz order.  Y2 / B2 receive the result.
+static int ritz_rotate(const Ctx& c, int l, const float* Y, float* Y2, size_t sY, const float* B, float* B2, size_t sB,
+                       double* lambda, int batch) {
+  const Plan& pl = c.pl;
+  double* G = c.at<double>(pl.G);
+  float* Ut = c.at<float>(pl.Ut);
+  LQ_TRY(launch_gram(B, l, pl.k, pl.ldk, sB, c.at<double>(pl.gram_part), G, batch, c.st));
+  LQ_TRY(launch_jacobi_eig(G, l, c.at<double>(pl.Vt), Ut, lambda, batch, c.st));
+  LQ_TRY(launch_wide_gemm(MODE_NN, l, pl.ldd, l, Ut, l, (size_t)l * l, Y, pl.ldd, sY, Y2, pl.ldd, sY, batch, 1,
+                          nullptr, c.st));
+  return launch_wide_gemm(MODE_NN, l, pl.ldk, l, Ut, l, (size_t)l * l, B, pl.ldk, sB, B2, pl.ldk, sB, batch, 1,
+                          nullptr, c.st);
+}
+
+// Cold-start randomized SVD of A (d x k): on return *Yout / *Bout (l1 rows, Ritz order) and lam_cold.
+static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const float** Yout, const float** Bout) {
+  const Plan& pl = c.pl;
+  const int l = pl.prm.l1, r = pl.rank;
+  float* Ya = c.at<float>(pl.Ya); float* Yb = c.at<float>(pl.Yb);
+  float* Ba = c.at<float>(pl.Ba); float* Bb = c.at<float>(pl.Bb);
+  double* lam = c.at<double>(pl.lam_cold);
+  LQ_HIP_TRY(hipMemsetAsync(Ya, 0, (size_t)l * pl.ldd * 4, c.st));
+  LQ_HIP_TRY(hipMemsetAsync(Yb, 0, (size_t)l * pl.ldd * 4, c.st));
+  LQ_HIP_TRY(hipMemsetAsync(Bb, 0, (size_t)l * pl.ldk * 4, c.st));
+  LQ_TRY(launch_gaussian_fill(Ba, l, pl.k, pl.ldk, seed, c.st));
+  LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Ya, pl.ldd, 0, 1));
+  LQ_TRY(orthonormalize(c, Ya, l, pl.d, pl.ldd, 0, 1));
+  std::vector<double> prev(r, 0.0), cur(r, 0.0);
+  bool have_prev = false;
+  for (int it = 1; it <= pl.prm.maxit; ++it) {
+    LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, Ya, pl.ldd, 0, A, pl.k, 0, Ba, pl.ldk, 0, 1));
+    if (it % pl.prm.check == 0 || it == pl.prm.maxit) {
+      LQ_TRY(ritz_rotate(c, l, Ya, Yb, 0, Ba, Bb, 0, lam, 1));
+      std::swap(Ya, Yb); std::swap(Ba, Bb);
+      LQ_HIP_TRY(hipMemcpyAsync(cur.data(), lam, sizeof(double) * r, hipMemcpyDeviceToHost, c.st));
+      LQ_HIP_TRY(hipStreamSynchronize(c.st));
+      bool done = have_prev;
+      for (int j = 0; j < r && done; ++j) {
+        const double a = std::sqrt(cur[j]), b = std::sqrt(prev[j]);
+        if (!(std::fabs(a - b) <= pl.prm.tol * a)) done = false;
+      }
+      prev = cur; have_prev = true;
+      if (done || it == pl.prm.maxit) break;
+    }
+    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Ya, pl.ldd, 0, 1));
+    LQ_TRY(orthonormalize(c, Ya, l, pl.d, pl.ldd, 0, 1));
+  }
+  *Yout = Ya; *Bout = Ba;
+  return LQ_OK;
+}
+
+// One warm-started Factorize for every problem of the batch: `power` subspace iterations on R_b
+// starting from the rows of Bsrc, then Rayleigh-Ritz.  Results land in Yw / Bw (swapped with Yw2 / Bw2).
+struct WideSet { float* Yw; float* Yw2; float* Bw; float* Bw2; };
+
+static int warm_factorize(const Ctx& c, WideSet& w, const float* Bsrc, size_t sBsrc, int power, int batch) {
+  const Plan& pl = c.pl;
+  const int l = pl.prm.lw;
+  const float* R = c.at<float>(pl.R);
+  const float* X = Bsrc; size_t sX = sBsrc;
+  for (int it = 0; it < power; ++it) {
+    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, X, pl.ldk, sX, R, pl.k, pl.strideR, w.Yw, pl.ldd, pl.strideYw, batch));
+    LQ_TRY(orthonormalize(c, w.Yw, l, pl.d, pl.ldd, pl.strideYw, batch));
+    LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R, pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw,
+                batch));
+    X = w.Bw; sX = pl.strideBw;
+  }
+  LQ_TRY(ritz_rotate(c, l, w.Yw, w.Yw2, pl.strideYw, w.Bw, w.Bw2, pl.strideBw, c.at<double>(pl.lam), batch));
+  std::swap(w.Yw, w.Yw2); std::swap(w.Bw, w.Bw2);
+  return LQ_OK;
+}
+
+static int setup_common(Ctx& c, const float* W, const float* row_w, const float* col_w, void* workspace,
+                        hipStream_t st) {
+  c.ws = (char*)workspace; c.st = st; c.W = W; c.row_w = row_w; c.col_w = col_w; c.weighted = row_w != nullptr;
+  LQ_TRY(device_tables(&c.tables));
+  const Plan& pl = c.pl;
+  if (c.weighted) {
+    LQ_TRY(launch_sqrt_vecs(row_w, pl.d, c.at<float>(pl.sr), c.at<float>(pl.rsr), st));
+    LQ_TRY(launch_sqrt_vecs(col_w, pl.k, c.at<float>(pl.sc), c.at<float>(pl.rsc), st));
+  }
+  return LQ_OK;
+}
+
+// Input of the first Factorize: W itself, or D_row W D_col staged in problem 0's residual buffer.
+static int first_input(const Ctx& c, const float** A) {
+  const Plan& pl = c.pl;
+  if (!c.weighted) { *A = c.W; return LQ_OK; }
+  float* As = c.at<float>(pl.R);
+  LQ_TRY(launch_scale_matrix(c.W, pl.d, pl.k, c.at<float>(pl.sr), c.at<float>(pl.sc), As, c.st));
+  *A = As;
+  return LQ_OK;
+}
+
+struct LoopOut {          // batch == 1 only: user buffers that receive the quantized component directly
+  uint8_t* codes; uint8_t* sidx; float* v; float* Qd;
+};
+
+// Runs Algorithm 2 for `batch` configurations in lock step from the shared first factorization
+// (Y1, B1, lam_cold).  Host outputs: trace[b * iters + t], iters_done[b].  On return *Yfin / *Bfin /
+// *lamfin describe the last Factorize of problem 0 (wide, Ritz order).
+static int run_loop(Ctx& c, const lq_config* cfgs, int batch, int iters, int early_stop, const float* Y1,
+                    const float* B1, const LoopOut* direct, double* trace, int32_t* iters_done, const float** Yfin,
+                    const float** Bfin, const double** lamfin) {
+  const Plan& pl = c.pl;
+  std::vector<LoopProblem> probs(batch);
+  int min_block = 1 << 30;
+  for (int b = 0; b < batch; ++b) {
+    std::memset(&probs[b], 0, sizeof(LoopProblem));
+    probs[b].cfg = cfgs[b];
+    probs[b].levels = scale_levels(cfgs[b]);
+    min_block = std::min(min_block, (int)cfgs[b].block);
+  }
+  LoopProblem* dprob = c.at<LoopProblem>(pl.prob);
+  LQ_HIP_TRY(hipMemcpyAsync(dprob, probs.data(), sizeof(LoopProblem) * batch, hipMemcpyHostToDevice, c.st));
+  WideSet w{c.at<float>(pl.Yw), c.at<float>(pl.Yw2), c.at<float>(pl.Bw), c.at<float>(pl.Bw2)};
+  LQ_HIP_TRY(hipMemsetAsync(w.Yw, 0, pl.strideYw * 4 * batch, c.st));
+  LQ_HIP_TRY(hipMemsetAsync(w.Yw2, 0, pl.strideYw * 4 * batch, c.st));
+  LQ_HIP_TRY(hipMemsetAsync(w.Bw, 0, pl.strideBw * 4 * batch, c.st));
+  LQ_HIP_TRY(hipMemsetAsync(w.Bw2, 0, pl.strideBw * 4 * batch, c.st));
+
+  PhaseArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.W = c.W; a.d = pl.d; a.k = pl.k; a.rank = pl.rank; a.ldy = pl.ldd; a.ldb = pl.ldk;
+  if (c.weighted) {
+    a.rsr = c.at<float>(pl.rsr); a.rsc = c.at<float>(pl.rsc); a.sr = c.at<float>(pl.sr); a.sc = c.at<float>(pl.sc);
+    a.row_w = c.row_w; a.col_w = c.col_w;
+  }
+  a.prob = dprob; a.tables = c.tables; a.batch = batch;
+  if (direct) {
+    a.codes = direct->codes; a.sidx = direct->sidx; a.v = direct->v;
+  } else {
+    a.codes = c.at<uint8_t>(pl.codes); a.strideCodes = pl.strideCodes;
+    a.sidx = c.at<uint8_t>(pl.sidx); a.strideSidx = pl.strideSidx;
+    a.v = c.at<float>(pl.v); a.strideV = pl.strideV;
+  }
+  a.blk = c.at<BlockRec>(pl.blk); a.strideBlk = pl.strideBlk;
+  a.err_part = c.at<double>(pl.epart); a.strideErrPart = pl.strideEpart;
+  double* errs = c.at<double>(pl.errs);
+  a.strideErrOut = MAX_ITERS;
+
+  const float* Ycur = Y1; const float* Bcur = B1; size_t sY = 0, sB = 0;
+  const double* lamcur = c.at<double>(pl.lam_cold);
+  double prev_eps = INFINITY;
+  int done = 0;
+  for (int t = 1; t <= iters; ++t) {
+    a.Y = Ycur; a.B = Bcur; a.strideY = sY; a.strideB = sB;
+    a.R = nullptr; a.Qd = nullptr; a.err_out = errs + (t - 1);
+    LQ_TRY(launch_lowrank_blockquant(a, c.st));
+    LQ_TRY(launch_scalequant_error(a, min_block, c.st));
+    done = t;
+    bool last = t == iters;
+    if (early_stop && batch == 1) {        // Algorithm 2's stopping rule needs eps_t on the host
+      double eps = 0.0;
+      LQ_HIP_TRY(hipMemcpyAsync(&eps, errs + (t - 1), sizeof(double), hipMemcpyDeviceToHost, c.st));
+      LQ_HIP_TRY(hipStreamSynchronize(c.st));
+      if (eps > prev_eps) last = true;
+      prev_eps = eps;
+    }
+    if (last) break;
+    a.R = c.at<float>(pl.R); a.strideR = pl.strideR;
+    LQ_TRY(launch_residual(a, c.st));
+    LQ_TRY(warm_factorize(c, w, Bcur, sB, t == 1 ? pl.prm.qw2 : pl.prm.qw, batch));
+    Ycur = w.Yw; Bcur = w.Bw; sY = pl.strideYw; sB = pl.strideBw;
+    lamcur = c.at<double>(pl.lam);
+  }
+  if (direct && direct->Qd) {
+    a.R = nullptr; a.Qd = direct->Qd; a.strideQd = 0;
+    LQ_TRY(launch_residual(a, c.st));
+  }
+  std::vector<double> host_err((size_t)batch * MAX_ITERS);
+  // copy only the used prefix of every row
+  for (int b = 0; b < batch; ++b)
+    LQ_HIP_TRY(hipMemcpyAsync(host_err.data() + (size_t)b * MAX_ITERS, errs + (size_t)b * MAX_ITERS,
+                              sizeof(double) * done, hipMemcpyDeviceToHost, c.st));
+  LQ_HIP_TRY(hipStreamSynchronize(c.st));
+  for (int b = 0; b < batch; ++b) {
+    int nd = done;
+    if (early_stop && batch > 1) {         // lock-step batches apply the rule after the fact
+      for (int t = 1; t < done; ++t)
+        if (host_err[(size_t)b * MAX_ITERS + t] > host_err[(size_t)b * MAX_ITERS + t - 1]) { nd = t + 1; break; }
+    }
+    if (iters_done) iters_done[b] = nd;
+    if (trace)
+      for (int t = 0; t < iters; ++t) trace[(size_t)b * iters + t] = t < nd ? host_err[(size_t)b * MAX_ITERS + t] : NAN;
+  }
+  if (Yfin) *Yfin = Ycur;
+  if (Bfin) *Bfin = Bcur;
+  if (lamfin) *lamfin = lamcur;
+  return LQ_OK;
+}
+
+static int emit_factors(const Ctx& c, const float* Y, const float* B, const double* lam, float* L1, float* L2,
+                        double* sigma_host) {
+  const Plan& pl = c.pl;
+  LQ_TRY(launch_assemble_factors(Y, pl.ldd, B, pl.ldk, lam, pl.rank, pl.d, pl.k,
+                                 c.weighted ? c.at<float>(pl.rsr) : nullptr, c.weighted ? c.at<float>(pl.rsc) : nullptr,
+                                 L1, L2, c.st));
+  std::vector<double> lamh(pl.rank);
+  LQ_HIP_TRY(hipMemcpyAsync(lamh.data(), lam, sizeof(double) * pl.rank, hipMemcpyDeviceToHost, c.st));
+  LQ_HIP_TRY(hipStreamSynchronize(c.st));
+  if (sigma_host)
+    for (int j = 0; j < pl.rank; ++j) sigma_host[j] = std::sqrt(lamh[j]);
+  return LQ_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+static int check_workspace(const void* ws, size_t have, size_t need) {
+  if (!ws || ((uintptr_t)ws & 255) != 0 || have < need) return LQ_ERR_WORKSPACE;
+  return LQ_OK;
+}
+
+}  // namespace lq
+
+using namespace lq;
+
+extern "C" {
+
+size_t lq_factorize_workspace_bytes(int64_t d, int64_t k, int rank, const lq_svd_params* p) {
+  return lq_decompose_workspace_bytes(d, k, rank, p);
+}
+
+size_t lq_decompose_workspace_bytes(int64_t d, int64_t k, int rank, const lq_svd_params* p) {
+  Params prm;
+  if (check_matrix_args(d, k, rank) != LQ_OK || resolve_params(rank, p, prm) != LQ_OK) return 0;
+  Plan pl;
+  make_plan(d, k, rank, prm, 1, pl);
+  return pl.total;
+}
+
+size_t lq_error_table_workspace_bytes(int64_t d, int64_t k, int rank, int n_cfgs, const lq_svd_params* p) {
+  Params prm;
+  if (n_cfgs < 1 || check_matrix_args(d, k, rank) != LQ_OK || resolve_params(rank, p, prm) != LQ_OK) return 0;
+  Plan pl;
+  make_plan(d, k, rank, prm, std::min(n_cfgs, prm.max_batch), pl);
+  return pl.total;
+}
+
+int lq_factorize(const float* A, int64_t d, int64_t k, int rank, const float* row_w, const float* col_w,
+                 uint64_t seed, const lq_svd_params* p, float* L1, float* L2, double* sigma, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+  if (!A || !L1 || !L2) return LQ_ERR_NULL;
+  LQ_TRY(check_matrix_args(d, k, rank));
+  if ((row_w == nullptr) != (col_w == nullptr)) return LQ_ERR_WEIGHT;
+  if (!aligned16(A) || !aligned16(L1) || !aligned16(L2)) return LQ_ERR_ARG;
+  Params prm;
+  LQ_TRY(resolve_params(rank, p, prm));
+  Ctx c;
+  make_plan(d, k, rank, prm, 1, c.pl);
+  LQ_TRY(check_workspace(workspace, workspace_bytes, c.pl.total));
+  LQ_TRY(setup_common(c, A, row_w, col_w, workspace, (hipStream_t)stream));
+  const float* A0; const float* Y; const float* B;
+  LQ_TRY(first_input(c, &A0));
+  LQ_TRY(cold_factorize(c, A0, seed, &Y, &B));
+  return emit_factors(c, Y, B, c.at<double>(c.pl.lam_cold), L1, L2, sigma);
+}
+
+int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, int iters, int early_stop,
+                 const float* row_w, const float* col_w, uint64_t seed, const lq_svd_params* p, float* L1, float* L2,
+                 uint8_t* q_codes, uint8_t* q_scale_idx, float* q_v, float* Q_dense, double* err, double* err_trace,
+                 int32_t* iters_done, double* sigma, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!W || !L1 || !L2 || !q_codes || !q_scale_idx || !q_v) return LQ_ERR_NULL;
+  LQ_TRY(check_matrix_args(d, k, rank));
+  LQ_TRY(check_quant_args(d * k, cfg));
+  if (cfg.block > 128 || k % cfg.block != 0) return cfg.block > 128 ? LQ_ERR_CONFIG : LQ_ERR_SHAPE;
+  if ((row_w == nullptr) != (col_w == nullptr)) return LQ_ERR_WEIGHT;
+  if (iters < 1 || iters > MAX_ITERS) return LQ_ERR_ARG;
+  if (!aligned16(W) || !aligned16(L1) || !aligned16(L2) || !aligned16(q_codes) || (Q_dense && !aligned16(Q_dense)))
+    return LQ_ERR_ARG;
+  Params prm;
+  LQ_TRY(resolve_params(rank, p, prm));
+  Ctx c;
+  make_plan(d, k, rank, prm, 1, c.pl);
+  LQ_TRY(check_workspace(workspace, workspace_bytes, c.pl.total));
+  LQ_TRY(setup_common(c, W, row_w, col_w, workspace, (hipStream_t)stream));
+  const float* A0; const float* Y1; const float* B1;
+  LQ_TRY(first_input(c, &A0));
+  LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));
+  LoopOut direct{q_codes, q_scale_idx, q_v, Q_dense};
+  std::vector<double> trace(iters, NAN);
+  int32_t done = 0;
+  const float* Yf; const float* Bf; const double* lamf;
+  LQ_TRY(run_loop(c, &cfg, 1, iters, early_stop, Y1, B1, &direct, trace.data(), &done, &Yf, &Bf, &lamf));
+  LQ_TRY(emit_factors(c, Yf, Bf, lamf, L1, L2, sigma));
+  if (err) *err = trace[done - 1];
+  if (err_trace) std::memcpy(err_trace, trace.data(), sizeof(double) * iters);
+  if (iters_done) *iters_done = done;
+  return LQ_OK;
+}
+
+int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_config* cfgs, int n_cfgs, int iters,
+                   int early_stop, const float* row_w, const float* col_w, uint64_t seed, const lq_svd_params* p,
+                   double* err_sq, double* storage_bits, double* err_trace, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+  if (!W || !cfgs || !err_sq || !storage_bits) return LQ_ERR_NULL;
+  if (n_cfgs < 1 || iters < 1 || iters > MAX_ITERS) return LQ_ERR_ARG;
+  LQ_TRY(check_matrix_args(d, k, rank));
+  std::vector<lq_config> cf(cfgs, cfgs + n_cfgs);
+  for (auto& cc : cf) {
+    LQ_TRY(check_quant_args(d * k, cc));
+    if (cc.block > 128) return LQ_ERR_CONFIG;
+    if (k % cc.block != 0) return LQ_ERR_SHAPE;
+  }
+  if ((row_w == nullptr) != (col_w == nullptr)) return LQ_ERR_WEIGHT;
+  if (!aligned16(W)) return LQ_ERR_ARG;
+  Params prm;
+  LQ_TRY(resolve_params(rank, p, prm));
+  Ctx c;
+  const int batch_max = std::min(n_cfgs, prm.max_batch);
+  make_plan(d, k, rank, prm, batch_max, c.pl);
+  LQ_TRY(check_workspace(workspace, workspace_bytes, c.pl.total));
+  LQ_TRY(setup_common(c, W, row_w, col_w, workspace, (hipStream_t)stream));
+  const float* A0; const float* Y1; const float* B1;
+  LQ_TRY(first_input(c, &A0));
+  LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));
+  std::vector<double> trace((size_t)batch_max * iters);
+  std::vector<int32_t> done(batch_max);
+  for (int c0 = 0; c0 < n_cfgs; c0 += batch_max) {
+    const int nb = std::min(batch_max, n_cfgs - c0);
+    LQ_TRY(run_loop(c, cf.data() + c0, nb, iters, early_stop, Y1, B1, nullptr, trace.data(), done.data(), nullptr,
+                    nullptr, nullptr));
+    for (int b = 0; b < nb; ++b) {
+      const double eps = trace[(size_t)b * iters + done[b] - 1];
+      err_sq[c0 + b] = eps * eps;
+      storage_bits[c0 + b] = lq_storage_bits(d * k, cf[c0 + b]);
+      if (err_trace) std::memcpy(err_trace + (size_t)(c0 + b) * iters, trace.data() + (size_t)b * iters, sizeof(double) * iters);
+    }
+  }
+  return LQ_OK;
+}
+
+// ---- test hooks (include/lq_testing.h) ----------------------------------------------------------------
+int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
+                      int64_t lda, float* C, int64_t ldc, int splits, float* part, void* stream) {
+  if (!X || !A || !C || (splits > 1 && !part) || splits < 1) return LQ_ERR_NULL;
+  return launch_wide_gemm(mode, l, big, K, X, ldx, 0, A, lda, 0, C, ldc, 0, 1, splits, part, (hipStream_t)stream);
+}
+
+int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, void* stream) {
+  if (!X || !scratch) return LQ_ERR_NULL;
+  if (l % 32 || l < 32 || l > 256) return LQ_ERR_ARG;
+  double* G = scratch;
+  double* part = scratch + (size_t)l * l;
+  LQ_TRY(launch_gram(X, l, m, ldx, 0, part, G, 1, (hipStream_t)stream));
+  LQ_TRY(launch_cholesky(G, l, 1, (hipStream_t)stream));
+  return launch_trsm(G, l, X, m, ldx, 0, 1, (hipStream_t)stream);
+}
+
+int lq_test_sym_eig(double* G, int l, float* Ut, double* lambda, double* scratch, void* stream) {
+  if (!G || !Ut || !lambda || !scratch) return LQ_ERR_NULL;
+  if (l % 2 || l < 2 || l > 256) return LQ_ERR_ARG;
+  return launch_jacobi_eig(G, l, scratch, Ut, lambda, 1, (hipStream_t)stream);
+}
+
+size_t lq_test_lds_limit(void) { return lds_limit_for_tests(); }
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+"""GPU checks of the randomized SVD's building blocks against plain numpy (fp64) references."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2311_12023_amd import lq
+    L = lq._lib
+    vp, i64, it = C.c_void_p, C.c_int64, C.c_int
+    L.lq_test_wide_gemm.argtypes = [it, it, i64, i64, vp, i64, vp, i64, vp, i64, it, vp, vp]
+    L.lq_test_orthonormalize.argtypes = [vp, it, i64, i64, vp, vp]
+    L.lq_test_sym_eig.argtypes = [vp, it, vp, vp, vp, vp]
+    L.lq_test_lds_limit.restype = C.c_size_t
+    return torch, lq, L
+
+
+def up32(x):
+    return (x + 31) // 32 * 32
+
+
+@pytest.mark.parametrize("mode,l,big,K,splits", [
+    (0, 32, 200, 160, 1), (0, 64, 768, 768, 3), (0, 96, 130, 1040, 2), (0, 128, 1000, 4096, 8), (0, 256, 300, 512, 1),
+    (1, 32, 208, 150, 1), (1, 64, 768, 768, 3), (1, 96, 1040, 131, 2), (1, 128, 4096, 1000, 8), (1, 256, 512, 300, 1),
+    (1, 160, 96, 32, 1)])
+def test_wide_gemm(env, mode, l, big, K, splits):
+    torch, lq, L = env
+    rng = np.random.default_rng(l * 7 + big + mode)
+    ldx = up32(K)
+    x = np.zeros((l, ldx), np.float32)
+    x[:, :K] = rng.standard_normal((l, K))
+    a = rng.standard_normal((big, K) if mode == 0 else (K, big)).astype(np.float32)
+    ldc = up32(big)
+    xt, at = torch.from_numpy(x).cuda(), torch.from_numpy(a).cuda()
+    ct = torch.full((l, ldc), 7.0, dtype=torch.float32, device="cuda")
+    part = torch.empty(max(splits, 1) * l * ldc, dtype=torch.float32, device="cuda")
+    rc = L.lq_test_wide_gemm(mode, l, big, K, xt.data_ptr(), ldx, at.data_ptr(), a.shape[1], ct.data_ptr(), ldc, splits,
+                             part.data_ptr(), None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    got = ct.cpu().numpy()
+    ref = x[:, :K].astype(np.float64) @ (a.T if mode == 0 else a).astype(np.float64)
+    scale = np.sqrt(K)
+    assert np.max(np.abs(got[:, :big] - ref)) < 2e-5 * scale
+    if splits == 1:
+        assert np.all(got[:, big:] == 7.0)          # columns past the matrix are never written
+
+
+@pytest.mark.parametrize("l,m", [(32, 100), (64, 768), (96, 4096), (128, 1000), (256, 2048)])
+def test_orthonormalize(env, l, m):
+    torch, lq, L = env
+    rng = np.random.default_rng(l + m)
+    ld = up32(m)
+    x = np.zeros((l, ld), np.float32)
+    # rows with a two-decade spread of singular values
+    base = rng.standard_normal((l, m))
+    u, _, vt = np.linalg.svd(base, full_matrices=False)
+    x[:, :m] = (u * np.logspace(0, -2, min(l, m))) @ vt
+    xt = torch.from_numpy(x).cuda()
+    scratch = torch.empty(17 * l * l, dtype=torch.float64, device="cuda")
+    assert L.lq_test_orthonormalize(xt.data_ptr(), l, m, ld, scratch.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    q = xt.cpu().numpy().astype(np.float64)
+    if l <= m:
+        assert np.max(np.abs(q @ q.T - np.eye(l))) < 5e-5
+        # same row space, nested: row i of q lies in the span of the first i+1 rows of x
+        coef = q[:, :m] @ np.linalg.pinv(x[:, :m].astype(np.float64))
+        assert np.max(np.abs(np.triu(coef, 1))) < 1e-2 * np.max(np.abs(coef))
+    assert np.all(q[:, m:] == 0)
+
+
+@pytest.mark.parametrize("l", [32, 64, 96, 128, 256])
+def test_sym_eig(env, l):
+    torch, lq, L = env
+    rng = np.random.default_rng(l)
+    b = rng.standard_normal((l, 3 * l)) * np.logspace(1, 0, l)[:, None]
+    g = b @ b.T
+    gt = torch.from_numpy(g.copy()).cuda()
+    ut = torch.empty((l, l), dtype=torch.float32, device="cuda")
+    lam = torch.empty(l, dtype=torch.float64, device="cuda")
+    scratch = torch.empty(l * l, dtype=torch.float64, device="cuda")
+    assert L.lq_test_sym_eig(gt.data_ptr(), l, ut.data_ptr(), lam.data_ptr(), scratch.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    lam_h, u = lam.cpu().numpy(), ut.cpu().numpy().astype(np.float64)
+    ref = np.sort(np.linalg.eigvalsh(g))[::-1]
+    assert np.all(np.diff(lam_h) <= 0)
+    assert np.max(np.abs(lam_h - ref) / ref) < 1e-9
+    assert np.max(np.abs(u @ u.T - np.eye(l))) < 1e-5
+    assert np.max(np.abs(u @ g @ u.T - np.diag(lam_h))) < 1e-4 * lam_h[0]
+
+
+def test_report_lds_limit(env):
+    torch, lq, L = env
+    lim = L.lq_test_lds_limit()
+    print("LDS bytes per workgroup reported by the device:", lim)
+    assert lim >= 65536
