@@ -1,0 +1,126 @@
+#!/usr/bin/env python3
+"""Benchmark: LQ error-table sweep of one LLaMA-2-7B-shaped layer on one MI355X.
+
+One step = the whole hot path over the workload: for each of the 7 weight matrices of the layer
+(4x 4096x4096, 2x 4096x11008, 1x 11008x4096; synthetic, see paper_2311_12023_amd/gen.py) one
+lq_error_table call over the 36 configurations bits {2,3,4,8} x B0 {16,32,64} x B1 {16,64,256}, rank 64,
+10 LQ iterations each.  Inputs are resident in HBM before the timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+RANK = 64
+ITERS = 10
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(first_matrix: np.ndarray) -> dict:
+    """The oracle, as it stands, timed on a bounded sample of the workload on the host cores."""
+    from oracle import lq_oracle as O
+    O.build()
+    sample = np.ascontiguousarray(first_matrix[:384, :384])
+    cfg = O.config(3, 64, 256)
+    t0 = time.perf_counter()
+    O.lq(sample, RANK, cfg, ITERS)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    return {"value": 1.0 / dt, "unit": "matrix-configs/s on the sample", "cores": cores, "kind": "oracle",
+            "sample": "one 384x384 corner of matrix 0, rank 64, NF3 B0=64 B1=256, 10 iterations "
+                      f"(exact Jacobi SVD each iteration); {dt:.1f} s. A full 4096x4096 cell costs about "
+                      "(4096/384)^3 times as much."}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--matrices", type=int, default=7, help="use only the first N matrices of the layer (debugging)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sweep shards over GPUs by "
+              "matrix without any collective, see DESIGN.md).", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2311_12023_amd import gen, lq
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = torch.device("cuda:0")
+    cfgs = [lq.config(*g) for g in gen.config_grid()]
+    host = [gen.workload_matrix(3, i) for i in range(min(args.matrices, len(gen.LLAMA2_7B_LAYER)))]
+    mats = [torch.from_numpy(w).to(dev) for w in host]
+    ws = lq.error_table_workspace(4096, 11008, RANK, len(cfgs), device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        out = []
+        for w in mats:
+            out.append(lq.error_table(w, RANK, cfgs, ITERS, seed=1, workspace=ws))
+        return out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lq.profile_enable(True)
+    lq.profile_reset()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = lq.profile_read()
+    lq.profile_enable(False)
+
+    cells = len(mats) * len(cfgs)
+    value = cells * args.steps / dt
+    # dominant kernel = largest summed event time
+    kernels = {}
+    for name, (ms, n, work) in prof.items():
+        kernels[name] = {"ms_total": round(ms, 3), "launches": n, "avg_us": round(1e3 * ms / n, 2),
+                         "work_per_s": work / (ms * 1e-3) if ms > 0 else 0.0}
+    dom = max(prof.items(), key=lambda kv: kv[1][0])
+    dname, (dms, dn, dwork) = dom
+    if dname.startswith("wide_gemm"):
+        ach = dwork / (dms * 1e-3) / 1e12
+        roof = {"kernel": dname, "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None, "launches": dn, "avg_us": 1e3 * dms / dn}
+    else:
+        ach = dwork / (dms * 1e-3) / 1e9
+        roof = {"kernel": dname, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None, "launches": dn, "avg_us": 1e3 * dms / dn}
+    line = {
+        "metric": "matrix-configs decomposed/sec (LLaMA-2-7B layer sweep)", "value": value, "unit": "matrix-configs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "LLaMA-2-7B-shaped layer (4x4096x4096, 2x4096x11008, 1x11008x4096), rank 64, "
+                               "36 configs (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256), 10 LQ iterations",
+                   "matrices": len(mats), "configs": len(cfgs), "iters": ITERS, "rank": RANK},
+        "roofline": roof,
+        "kernels": kernels,
+        "error_table_checksum": float(sum(np.sqrt(e).sum() for e, _ in res)),
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(host[0])
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -176,6 +176,19 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
                    const lq_svd_params* p, double* err_sq, double* storage_bits, double* err_trace,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the library
+ * is bracketed by two HIP events on the launch stream; lq_profile_read synchronizes the device and returns,
+ * for one kernel class, the summed event time, the number of launches and the summed algorithmic work
+ * (flops for the GEMM classes, bytes otherwise) since the last lq_profile_reset.  Class names are the
+ * kernels' names.  Not thread-safe against concurrent library calls.
+ */
+int lq_profile_enable(int on);
+int lq_profile_reset(void);
+int lq_profile_num_classes(void);
+const char* lq_profile_class_name(int cls);
+int lq_profile_read(int cls, double* total_ms, int64_t* launches, double* work);
+
 #ifdef __cplusplus
 }
 #endif

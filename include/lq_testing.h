@@ -20,11 +20,16 @@ extern "C" {
 int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
                       int64_t lda, float* C, int64_t ldc, int splits, float* part, void* stream);
 /* Rows of X (l x m) are orthonormalised in place by Cholesky-QR (Gram in fp64).
- * scratch: at least 17 * l * l doubles. */
-int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, void* stream);
+ * scratch: at least 17 * l * l doubles.  alt: l * ldx floats of scratch, or NULL to force the
+ * in-place triangular solve. */
+int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, float* alt, void* stream);
 /* Eigen-decomposition of the symmetric l x l fp64 matrix G (destroyed): eigenvalues descending in
  * lambda (l doubles), eigenvectors as rows of Ut (l x l fp32).  scratch: l * l doubles. */
 int lq_test_sym_eig(double* G, int l, float* Ut, double* lambda, double* scratch, void* stream);
+/* fp32 one-sided Jacobi variant used inside the decomposition for l <= 128 (multiple of 32): rows of Ut are
+ * approximate eigenvectors of the symmetric fp64 G (left untouched), ordered by descending eigenvalue
+ * estimate lambda (fp32 accuracy). */
+int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void* stream);
 /* Largest LDS allocation per workgroup the device reports, in bytes. */
 size_t lq_test_lds_limit(void);
 

@@ -11,6 +11,7 @@
 //   3  per weight: R = D_row (W - Q) D_col, the input of the next Factorize (and / or dense Q).
 #include "kernels.h"
 #include "nf_device.h"
+#include "profiler.h"
 
 namespace lq {
 
@@ -23,7 +24,8 @@ constexpr int KC = 32;     // rank chunk staged in LDS
 
 template <int BITS>
 __device__ inline void phase1_epilogue(const PhaseArgs& a, const LoopProblem& pr, int z, const float* pt,
-                                       const float* s_code, const float* s_thr, int64_t r0, int64_t c0) {
+                                       const float* s_code, const float* s_thr, int64_t r0, int64_t c0,
+                                       const float4 (&wreg)[2][4]) {
   Thresholds<BITS> thr(s_thr);
   const int tid = threadIdx.x;
   const int rpb = pr.cfg.block / 16;
@@ -37,11 +39,10 @@ __device__ inline void phase1_epilogue(const PhaseArgs& a, const LoopProblem& pr
     const bool live = row < a.d && col < a.k;
     float t[16], w[16];
     if (live) {
-      const float4* wp = reinterpret_cast<const float4*>(a.W + (size_t)row * a.k + col);
       const float rs = a.rsr ? a.rsr[row] : 1.0f;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const float4 f = wp[q];
+        const float4 f = wreg[u][q];
         const float4 p = *reinterpret_cast<const float4*>(pt + lr * PP + 16 * rc + 4 * q);
         float pv[4] = {p.x, p.y, p.z, p.w};
         const float fv[4] = {f.x, f.y, f.z, f.w};
@@ -89,14 +90,34 @@ __device__ inline void phase1_epilogue(const PhaseArgs& a, const LoopProblem& pr
 }
 
 __global__ __launch_bounds__(256) void lowrank_blockquant_kernel(PhaseArgs a) {
-  __shared__ float ys[KC][TM];       // Y chunk: [rank index][tile row]
-  __shared__ float bs[KC][TN];       // B chunk: [rank index][tile column]
-  __shared__ float pt[TM * PP];      // product tile
+  // The operand chunks (Y: KC x TM, B: KC x TN) and the product tile share one LDS buffer: the product is
+  // written after the last MFMA has read its operands.
+  __shared__ __attribute__((aligned(16))) float smem[TM * PP];
   __shared__ float s_code[256];
   __shared__ float s_thr[256];
-  const int z = blockIdx.z, tid = threadIdx.x;
+  float (*ys)[TM] = reinterpret_cast<float (*)[TM]>(smem);
+  float (*bs)[TN] = reinterpret_cast<float (*)[TN]>(smem + KC * TM);
+  float* pt = smem;
+  static_assert(KC * TM + KC * TN <= TM * PP, "operand chunks must fit in the product tile");
+  // problem index fastest: the workgroups that share a tile of W run together and hit it in L2
+  const int z = blockIdx.x, tid = threadIdx.x;
   const LoopProblem pr = a.prob[z];
-  const int64_t r0 = (int64_t)blockIdx.y * TM, c0 = (int64_t)blockIdx.x * TN;
+  const int64_t r0 = (int64_t)blockIdx.z * TM, c0 = (int64_t)blockIdx.y * TN;
+  // this lane's two runs of W, fetched now so that the loads overlap the MFMA stage
+  float4 wreg[2][4];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int rid = tid + 256 * u;
+    const int64_t row = r0 + (rid >> 3), col = c0 + 16 * (rid & 7);
+    if (row < a.d && col < a.k) {
+      const float4* wp = reinterpret_cast<const float4*>(a.W + (size_t)row * a.k + col);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) wreg[u][q] = wp[q];
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) wreg[u][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
   const float* __restrict__ Y = a.Y + (size_t)z * a.strideY;
   const float* __restrict__ B = a.B + (size_t)z * a.strideB;
   const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
@@ -135,6 +156,7 @@ __global__ __launch_bounds__(256) void lowrank_blockquant_kernel(PhaseArgs a) {
       }
     }
   }
+  __syncthreads();          // all operand reads done before the product overwrites the buffer
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -148,15 +170,16 @@ __global__ __launch_bounds__(256) void lowrank_blockquant_kernel(PhaseArgs a) {
   s_thr[tid] = a.tables->thr[slot][tid];
   __syncthreads();
   switch (pr.cfg.bits) {
-    case 2: phase1_epilogue<2>(a, pr, z, pt, s_code, s_thr, r0, c0); break;
-    case 3: phase1_epilogue<3>(a, pr, z, pt, s_code, s_thr, r0, c0); break;
-    case 4: phase1_epilogue<4>(a, pr, z, pt, s_code, s_thr, r0, c0); break;
-    default: phase1_epilogue<8>(a, pr, z, pt, s_code, s_thr, r0, c0); break;
+    case 2: phase1_epilogue<2>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
+    case 3: phase1_epilogue<3>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
+    case 4: phase1_epilogue<4>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
+    default: phase1_epilogue<8>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
   }
 }
 
 int launch_lowrank_blockquant(const PhaseArgs& a, hipStream_t st) {
-  const dim3 grid((unsigned)((a.k + TN - 1) / TN), (unsigned)((a.d + TM - 1) / TM), (unsigned)a.batch);
+  const dim3 grid((unsigned)a.batch, (unsigned)((a.k + TN - 1) / TN), (unsigned)((a.d + TM - 1) / TM));
+  prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st, (double)a.d * a.k * 4.0 * a.batch);
   hipLaunchKernelGGL(lowrank_blockquant_kernel, grid, dim3(256), 0, st, a);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
@@ -219,6 +242,7 @@ int64_t err_partials_per_problem(int64_t n, int block) { return (n / block + 255
 
 int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st) {
   const int64_t nwg = err_partials_per_problem(a.d * a.k, min_block);
+  prof::Scope ps(prof::SCALEQUANT_ERROR, st, (double)(a.d * a.k / min_block) * 17.0 * a.batch);
   hipLaunchKernelGGL(scalequant_error_kernel, dim3((unsigned)nwg, (unsigned)a.batch), dim3(256), 0, st, a);
   LQ_HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(error_finalize_kernel, dim3((unsigned)a.batch), dim3(256), 0, st, (const double*)a.err_part,
@@ -228,43 +252,41 @@ int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Phase 3: one run of 16 weights per lane.
+// Phase 3: one quad (4 consecutive weights) per lane and step, so each wavefront instruction reads / writes
+// 1 KB of contiguous fp32.
 template <int BITS>
 __device__ inline void phase3_body(const PhaseArgs& a, const LoopProblem& pr, int z, const float* s_code) {
-  const int64_t nruns = (a.d * a.k) >> 4;
-  const int rpb = pr.cfg.block / 16;
+  const int64_t nquads = (a.d * a.k) >> 2;
+  const int qpb_shift = __builtin_ctz(pr.cfg.block / 4), sb_shift = __builtin_ctz(pr.cfg.scale_block);
   const uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
   const uint8_t* sidx = a.sidx + (size_t)z * a.strideSidx;
   const float* v = a.v + (size_t)z * a.strideV;
-  for (int64_t run = (int64_t)blockIdx.x * 256 + threadIdx.x; run < nruns; run += (int64_t)gridDim.x * 256) {
-    const int64_t blk = run / rpb;
-    const float sh = block_scale(sidx[blk], v[blk / pr.cfg.scale_block], pr.levels);
-    uint32_t c[16];
-    load_codes<BITS>(codes, run, c);
-    const int64_t e0 = run << 4;
-    const int64_t row = e0 / a.k, col = e0 % a.k;
-    const float4* wp = reinterpret_cast<const float4*>(a.W + e0);
-    const float srow = a.sr ? a.sr[row] : 1.0f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 f = wp[q];
-      float4 qv, rv;
-      qv.x = s_code[c[4 * q]] * sh; qv.y = s_code[c[4 * q + 1]] * sh;
-      qv.z = s_code[c[4 * q + 2]] * sh; qv.w = s_code[c[4 * q + 3]] * sh;
-      rv.x = f.x - qv.x; rv.y = f.y - qv.y; rv.z = f.z - qv.z; rv.w = f.w - qv.w;
-      if (a.sr) {
-        const float4 cs = *reinterpret_cast<const float4*>(a.sc + col + 4 * q);
-        rv.x = srow * rv.x * cs.x; rv.y = srow * rv.y * cs.y; rv.z = srow * rv.z * cs.z; rv.w = srow * rv.w * cs.w;
-      }
-      if (a.R) reinterpret_cast<float4*>(a.R + (size_t)z * a.strideR + e0)[q] = rv;
-      if (a.Qd) reinterpret_cast<float4*>(a.Qd + (size_t)z * a.strideQd + e0)[q] = qv;
+  float* R = a.R ? a.R + (size_t)z * a.strideR : nullptr;
+  float* Qd = a.Qd ? a.Qd + (size_t)z * a.strideQd : nullptr;
+  for (int64_t quad = (int64_t)blockIdx.y * 256 + threadIdx.x; quad < nquads; quad += (int64_t)gridDim.y * 256) {
+    const int64_t blk = quad >> qpb_shift;
+    const float sh = block_scale(sidx[blk], v[blk >> sb_shift], pr.levels);
+    uint32_t c[4];
+    load_quad_codes<BITS>(codes, quad, c);
+    const int64_t e0 = quad << 2;
+    const float4 f = *reinterpret_cast<const float4*>(a.W + e0);
+    float4 qv, rv;
+    qv.x = s_code[c[0]] * sh; qv.y = s_code[c[1]] * sh; qv.z = s_code[c[2]] * sh; qv.w = s_code[c[3]] * sh;
+    rv.x = f.x - qv.x; rv.y = f.y - qv.y; rv.z = f.z - qv.z; rv.w = f.w - qv.w;
+    if (a.sr) {
+      const int64_t row = e0 / a.k, col = e0 % a.k;
+      const float srow = a.sr[row];
+      const float4 cs = *reinterpret_cast<const float4*>(a.sc + col);
+      rv.x = srow * rv.x * cs.x; rv.y = srow * rv.y * cs.y; rv.z = srow * rv.z * cs.z; rv.w = srow * rv.w * cs.w;
     }
+    if (R) *reinterpret_cast<float4*>(R + e0) = rv;
+    if (Qd) *reinterpret_cast<float4*>(Qd + e0) = qv;
   }
 }
 
 __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a) {
   __shared__ float s_code[256];
-  const int z = blockIdx.y;
+  const int z = blockIdx.x;          // problem index fastest: W is fetched from HBM once per batch
   const LoopProblem pr = a.prob[z];
   const int slot = pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3;
   s_code[threadIdx.x] = a.tables->code[slot][threadIdx.x];
@@ -278,10 +300,11 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a) {
 }
 
 int launch_residual(const PhaseArgs& a, hipStream_t st) {
-  const int64_t nruns = (a.d * a.k) >> 4;
-  const int64_t want = (nruns + 255) / 256;
-  const int64_t cap = 4096;
-  hipLaunchKernelGGL(residual_kernel, dim3((unsigned)(want < cap ? want : cap), (unsigned)a.batch), dim3(256), 0, st,
+  const int64_t nquads = (a.d * a.k) >> 2;
+  const int64_t want = (nquads + 255) / 256;
+  const int64_t cap = 8192;
+  prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * 8.0 * a.batch);
+  hipLaunchKernelGGL(residual_kernel, dim3((unsigned)a.batch, (unsigned)(want < cap ? want : cap)), dim3(256), 0, st,
                      a);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;

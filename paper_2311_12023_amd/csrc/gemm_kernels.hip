@@ -16,22 +16,82 @@
 // gridDim = (tiles along the large dimension, K splits, batch).  With K splits > 1 each split writes
 // its own partial result and splitk_reduce_kernel adds them in a fixed order (deterministic).
 #include "kernels.h"
+#include "profiler.h"
 
 namespace lq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
 
 constexpr int BK = 32;           // K chunk staged per step
 constexpr int XPITCH = BK + 4;   // LDS row pitch in floats: 16-byte aligned rows, conflict-free b128 reads
 
+// X tile fetch: L x 32 floats = L*8 float4, LT per thread.  X has a padded, zero-filled leading dimension that
+// is a multiple of 32, so no K guard is needed on it.
+template <int LT>
+__device__ __forceinline__ void fetch_x(const float* __restrict__ X, int64_t ldx, int64_t k0, int tid,
+                                        floatx4 (&xreg)[LT]) {
+#pragma unroll
+  for (int i = 0; i < LT; ++i) {
+    const int idx = tid + i * 256;            // float4 index in the tile
+    const int row = idx >> 3, c4 = idx & 7;
+    xreg[i] = *reinterpret_cast<const floatx4*>(X + (size_t)row * ldx + k0 + c4 * 4);
+  }
+}
+
+template <int LT>
+__device__ __forceinline__ void stash_x(float* xs, int tid, const floatx4 (&xreg)[LT]) {
+#pragma unroll
+  for (int i = 0; i < LT; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx >> 3, c4 = idx & 7;
+    *reinterpret_cast<floatx4*>(xs + row * XPITCH + c4 * 4) = xreg[i];
+  }
+}
+
+// A operand of one 32-chunk in MFMA layout: breg[c][e][j], k = k0 + 8c + 4h + e.
+template <int MODE, int NT>
+__device__ __forceinline__ void fetch_a(const float* __restrict__ A, int64_t lda, int64_t big, int64_t big0, int ln,
+                                        int lh, int64_t k0, int64_t kend, float (&breg)[4][4][NT]) {
+  if constexpr (MODE == MODE_NT) {
+    int64_t row = big0 + ln;
+    if (row >= big) row = big - 1;            // clamped rows are computed and never stored
+    const float* p = A + (size_t)row * lda;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int64_t kk = k0 + 8 * c + 4 * lh;
+      floatx4 f = {0.f, 0.f, 0.f, 0.f};
+      if (kk < kend) f = *reinterpret_cast<const floatx4*>(p + kk);   // K and kend are multiples of 4
+      breg[c][0][0] = f.x; breg[c][1][0] = f.y; breg[c][2][0] = f.z; breg[c][3][0] = f.w;
+    }
+  } else {
+    int64_t col = big0 + (int64_t)ln * NT;
+    if (col + NT > big) col = big - NT;       // big is a multiple of NT; clamped columns never stored
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int64_t kk = k0 + 8 * c + 4 * lh + e;
+        if constexpr (NT == 2) {
+          float2 f = make_float2(0.f, 0.f);
+          if (kk < kend) f = *reinterpret_cast<const float2*>(A + (size_t)kk * lda + col);
+          breg[c][e][0] = f.x; breg[c][e][1] = f.y;
+        } else {
+          float f = 0.f;
+          if (kk < kend) f = A[(size_t)kk * lda + col];
+          breg[c][e][0] = f;
+        }
+      }
+  }
+}
+
 template <int LT, int MODE, int NT>
 __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
-  extern __shared__ float xs[];   // [32*LT][XPITCH]
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // [32*LT][XPITCH]
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int ln = lane & 31, lh = lane >> 5;
   const int split = blockIdx.y, z = blockIdx.z;
-  constexpr int L = 32 * LT;
 
   const float* __restrict__ X = g.X + (size_t)z * g.strideX;
   const float* __restrict__ A = g.A + (size_t)z * g.strideA;
@@ -54,68 +114,15 @@ __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  // ---- operand fetch helpers -----------------------------------------------------------------
-  // X tile: L x 32 floats = L*8 float4, LT per thread.  X has a padded, zero-filled leading dimension
-  // that is a multiple of 32, so no K guard is needed on it.
-  float4 xreg[LT];
-  auto fetch_x = [&](int64_t k0) {
-#pragma unroll
-    for (int i = 0; i < LT; ++i) {
-      const int idx = tid + i * 256;            // float4 index in the tile
-      const int row = idx >> 3, c4 = idx & 7;
-      xreg[i] = *reinterpret_cast<const float4*>(X + (size_t)row * g.ldx + k0 + c4 * 4);
-    }
-  };
-  auto stash_x = [&]() {
-#pragma unroll
-    for (int i = 0; i < LT; ++i) {
-      const int idx = tid + i * 256;
-      const int row = idx >> 3, c4 = idx & 7;
-      *reinterpret_cast<float4*>(xs + row * XPITCH + c4 * 4) = xreg[i];
-    }
-  };
-  // A operand of one 32-chunk: breg[c][e][j], k = k0 + 8c + 4h + e.
+  floatx4 xreg[LT];
   float breg[4][4][NT];
-  auto fetch_a = [&](int64_t k0) {
-    if constexpr (MODE == MODE_NT) {
-      int64_t row = big0 + ln;
-      if (row >= g.big) row = g.big - 1;        // clamped rows are computed and never stored
-      const float* p = A + (size_t)row * g.lda;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int64_t kk = k0 + 8 * c + 4 * lh;
-        float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (kk < kend) f = *reinterpret_cast<const float4*>(p + kk);   // K and kend are multiples of 4
-        breg[c][0][0] = f.x; breg[c][1][0] = f.y; breg[c][2][0] = f.z; breg[c][3][0] = f.w;
-      }
-    } else {
-      int64_t col = big0 + (int64_t)ln * NT;
-      if (col + NT > g.big) col = g.big - NT;   // big is a multiple of NT; clamped columns never stored
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int64_t kk = k0 + 8 * c + 4 * lh + e;
-          if constexpr (NT == 2) {
-            float2 f = make_float2(0.f, 0.f);
-            if (kk < kend) f = *reinterpret_cast<const float2*>(A + (size_t)kk * g.lda + col);
-            breg[c][e][0] = f.x; breg[c][e][1] = f.y;
-          } else {
-            float f = 0.f;
-            if (kk < kend) f = A[(size_t)kk * g.lda + col];
-            breg[c][e][0] = f;
-          }
-        }
-    }
-  };
-
   if (nsteps > 0) {
-    fetch_x(kbeg);
-    fetch_a(kbeg);
+    fetch_x<LT>(X, g.ldx, kbeg, tid, xreg);
+    fetch_a<MODE, NT>(A, g.lda, g.big, big0, ln, lh, kbeg, kend, breg);
   }
   for (int step = 0; step < nsteps; ++step) {
     __syncthreads();          // everyone is done reading the previous X tile
-    stash_x();
+    stash_x<LT>(xs, tid, xreg);
     float bcur[4][4][NT];
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -126,21 +133,25 @@ __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
     __syncthreads();
     if (step + 1 < nsteps) {   // next chunk's loads fly while this chunk multiplies
       const int64_t k1 = kbeg + (int64_t)(step + 1) * BK;
-      fetch_x(k1);
-      fetch_a(k1);
+      fetch_x<LT>(X, g.ldx, k1, tid, xreg);
+      fetch_a<MODE, NT>(A, g.lda, g.big, big0, ln, lh, k1, kend, breg);
     }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
+      float av[LT][4];
 #pragma unroll
       for (int i = 0; i < LT; ++i) {
-        const float4 a4 = *reinterpret_cast<const float4*>(xs + (32 * i + ln) * XPITCH + 8 * c + 4 * lh);
-        const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+        const floatx4 a4 = *reinterpret_cast<const floatx4*>(xs + (32 * i + ln) * XPITCH + 8 * c + 4 * lh);
+        av[i][0] = a4.x; av[i][1] = a4.y; av[i][2] = a4.z; av[i][3] = a4.w;
+      }
+      // consecutive MFMAs go to different accumulators
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < LT; ++i)
 #pragma unroll
           for (int j = 0; j < NT; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bcur[c][e][j], acc[i][j], 0, 0, 0);
-      }
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][e], bcur[c][e][j], acc[i][j], 0, 0, 0);
     }
   }
 
@@ -171,7 +182,6 @@ __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
         }
     }
   }
-  (void)L;
 }
 
 // out[z][i] = sum_s part[z][s][i], i < count (count = rows * ldc), fixed summation order.
@@ -247,10 +257,14 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
   else { g.C = C; g.strideC = strideC; }
   const int span = gemm_tile_span(mode, lt);
   const dim3 grid((unsigned)((big + span - 1) / span), (unsigned)splits, (unsigned)batch);
-  int rc = (mode == MODE_NT) ? launch_mode<MODE_NT>(g, lt, grid, st) : launch_mode<MODE_NN>(g, lt, grid, st);
-  if (rc != LQ_OK) return rc;
+  {
+    prof::Scope ps(prof::GEMM_BASE + mode * 8 + (lt - 1), st, 2.0 * l * (double)big * (double)K * batch);
+    int rc = (mode == MODE_NT) ? launch_mode<MODE_NT>(g, lt, grid, st) : launch_mode<MODE_NN>(g, lt, grid, st);
+    if (rc != LQ_OK) return rc;
+  }
   LQ_HIP_TRY(hipGetLastError());
   if (splits > 1) {
+    prof::Scope ps(prof::SPLITK_REDUCE, st, (double)(splits + 1) * out_elems * 4.0 * batch);
     const int64_t count4 = (int64_t)(out_elems / 4);
     const dim3 rgrid((unsigned)((count4 + 255) / 256 < 2048 ? (count4 + 255) / 256 : 2048), (unsigned)batch);
     hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, dim3(256), 0, st, (const float*)part, C, splits, count4,

@@ -39,6 +39,11 @@ int launch_gram(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, d
 // is not positive relative to the largest diagonal entry marks a dependent direction: its diagonal entry
 // is stored as 0 and the triangular solve zeroes that row.
 int launch_cholesky(double* G, int l, int batch, hipStream_t st);
+// Cholesky factor of G[z] (l x l fp64, l <= 128) and its inverse in one kernel: Cinv[z] = C^-1 as dense fp32
+// l x l (zeros above the diagonal; a dependent direction gives a zero row).  cholinv_supported tells whether
+// the factor fits in LDS on this device.
+bool cholinv_supported(int l);
+int launch_cholinv(const double* G, int l, float* Cinv, int batch, hipStream_t st);
 // X[z] <- C[z]^-1 X[z] by forward substitution (C lower triangular, fp64, from launch_cholesky).
 int launch_trsm(const double* Cfac, int l, float* X, int64_t m, int64_t ldx, size_t strideX, int batch,
                 hipStream_t st);
@@ -46,6 +51,13 @@ int launch_trsm(const double* Cfac, int l, float* X, int64_t m, int64_t ldx, siz
 // sorted by descending eigenvalue: lambda[z][l] and Ut[z] (l x l fp32, row j = j-th eigenvector).
 // `vt` holds batch * l * l doubles of scratch.
 int launch_jacobi_eig(double* G, int l, double* vt, float* Ut, double* lambda, int batch, hipStream_t st);
+// Approximate eigenvectors (fp32 one-sided Jacobi in LDS, l <= 128) of the symmetric G[z]: rows of Ut[z] ordered by
+// descending eigenvalue estimate (lambda[z], accurate to fp32 only).  G is not modified.
+bool jacobi_fast_supported(int l);
+int launch_jacobi_fast(const double* G, int l, float* Ut, double* lambda, int batch, hipStream_t st);
+// lam[z][i] = squared norm of row i of the wide matrix X[z] (l x m), fp64.
+int launch_row_sumsq(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, double* lam, int batch,
+                     hipStream_t st);
 // Fills a wide matrix (l x m, padded ld) with N(0,1) draws from a counter-based generator; pads are zeroed.
 int launch_gaussian_fill(float* X, int l, int64_t m, int64_t ldx, uint64_t seed, hipStream_t st);
 // out[i][j] = sr[i] * A[i][j] * sc[j]  (sr = sqrt(row_w), sc = sqrt(col_w): D_row A D_col of Eq. 5).

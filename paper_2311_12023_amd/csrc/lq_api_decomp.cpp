@@ -129,9 +129,21 @@ struct Ctx {
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
 
-static int orthonormalize(const Ctx& c, float* X, int l, int64_t m, int64_t ldx, size_t strideX, int batch) {
+// Cholesky-QR: the rows of X (l x m) are replaced by an orthonormal basis of their span.  With the factor in
+// LDS the result is written to Xalt by the MFMA GEMM (C^-1 X) and the two pointers are exchanged; otherwise
+// X is solved in place.
+static int orthonormalize(const Ctx& c, float*& X, float*& Xalt, int l, int64_t m, int64_t ldx, size_t strideX,
+                          int batch) {
   double* G = c.at<double>(c.pl.G);
   LQ_TRY(launch_gram(X, l, m, ldx, strideX, c.at<double>(c.pl.gram_part), G, batch, c.st));
+  if (cholinv_supported(l)) {
+    float* Cinv = c.at<float>(c.pl.Ut);
+    LQ_TRY(launch_cholinv(G, l, Cinv, batch, c.st));
+    LQ_TRY(launch_wide_gemm(MODE_NN, l, ldx, l, Cinv, l, (size_t)l * l, X, ldx, strideX, Xalt, ldx, strideX, batch, 1,
+                            nullptr, c.st));
+    std::swap(X, Xalt);
+    return LQ_OK;
+  }
   LQ_TRY(launch_cholesky(G, l, batch, c.st));
   return launch_trsm(G, l, X, m, ldx, strideX, batch, c.st);
 }
@@ -152,11 +164,16 @@ static int ritz_rotate(const Ctx& c, int l, const float* Y, float* Y2, size_t sY
   double* G = c.at<double>(pl.G);
   float* Ut = c.at<float>(pl.Ut);
   LQ_TRY(launch_gram(B, l, pl.k, pl.ldk, sB, c.at<double>(pl.gram_part), G, batch, c.st));
-  LQ_TRY(launch_jacobi_eig(G, l, c.at<double>(pl.Vt), Ut, lambda, batch, c.st));
+  const bool fast = jacobi_fast_supported(l);
+  if (fast) LQ_TRY(launch_jacobi_fast(G, l, Ut, lambda, batch, c.st));
+  else LQ_TRY(launch_jacobi_eig(G, l, c.at<double>(pl.Vt), Ut, lambda, batch, c.st));
   LQ_TRY(launch_wide_gemm(MODE_NN, l, pl.ldd, l, Ut, l, (size_t)l * l, Y, pl.ldd, sY, Y2, pl.ldd, sY, batch, 1,
                           nullptr, c.st));
-  return launch_wide_gemm(MODE_NN, l, pl.ldk, l, Ut, l, (size_t)l * l, B, pl.ldk, sB, B2, pl.ldk, sB, batch, 1,
-                          nullptr, c.st);
+  LQ_TRY(launch_wide_gemm(MODE_NN, l, pl.ldk, l, Ut, l, (size_t)l * l, B, pl.ldk, sB, B2, pl.ldk, sB, batch, 1,
+                          nullptr, c.st));
+  // Ritz values from the rotated projection itself: sigma_i^2 = |row i of B2|^2
+  if (fast) LQ_TRY(launch_row_sumsq(B2, l, pl.k, pl.ldk, sB, lambda, batch, c.st));
+  return LQ_OK;
 }
 
 // Cold-start randomized SVD of A (d x k): on return *Yout / *Bout (l1 rows, Ritz order) and lam_cold.
@@ -171,7 +188,7 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
   LQ_HIP_TRY(hipMemsetAsync(Bb, 0, (size_t)l * pl.ldk * 4, c.st));
   LQ_TRY(launch_gaussian_fill(Ba, l, pl.k, pl.ldk, seed, c.st));
   LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Ya, pl.ldd, 0, 1));
-  LQ_TRY(orthonormalize(c, Ya, l, pl.d, pl.ldd, 0, 1));
+  LQ_TRY(orthonormalize(c, Ya, Yb, l, pl.d, pl.ldd, 0, 1));
   std::vector<double> prev(r, 0.0), cur(r, 0.0);
   bool have_prev = false;
   for (int it = 1; it <= pl.prm.maxit; ++it) {
@@ -190,7 +207,7 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
       if (done || it == pl.prm.maxit) break;
     }
     LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Ya, pl.ldd, 0, 1));
-    LQ_TRY(orthonormalize(c, Ya, l, pl.d, pl.ldd, 0, 1));
+    LQ_TRY(orthonormalize(c, Ya, Yb, l, pl.d, pl.ldd, 0, 1));
   }
   *Yout = Ya; *Bout = Ba;
   return LQ_OK;
@@ -207,7 +224,7 @@ static int warm_factorize(const Ctx& c, WideSet& w, const float* Bsrc, size_t sB
   const float* X = Bsrc; size_t sX = sBsrc;
   for (int it = 0; it < power; ++it) {
     LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, X, pl.ldk, sX, R, pl.k, pl.strideR, w.Yw, pl.ldd, pl.strideYw, batch));
-    LQ_TRY(orthonormalize(c, w.Yw, l, pl.d, pl.ldd, pl.strideYw, batch));
+    LQ_TRY(orthonormalize(c, w.Yw, w.Yw2, l, pl.d, pl.ldd, pl.strideYw, batch));
     LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R, pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw,
                 batch));
     X = w.Bw; sX = pl.strideBw;
@@ -484,12 +501,19 @@ int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, i
   return launch_wide_gemm(mode, l, big, K, X, ldx, 0, A, lda, 0, C, ldc, 0, 1, splits, part, (hipStream_t)stream);
 }
 
-int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, void* stream) {
+int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, float* alt, void* stream) {
   if (!X || !scratch) return LQ_ERR_NULL;
   if (l % 32 || l < 32 || l > 256) return LQ_ERR_ARG;
   double* G = scratch;
   double* part = scratch + (size_t)l * l;
   LQ_TRY(launch_gram(X, l, m, ldx, 0, part, G, 1, (hipStream_t)stream));
+  if (cholinv_supported(l) && alt) {
+    float* Cinv = reinterpret_cast<float*>(part);       // the Gram partials are dead by now
+    LQ_TRY(launch_cholinv(G, l, Cinv, 1, (hipStream_t)stream));
+    LQ_TRY(launch_wide_gemm(MODE_NN, l, ldx, l, Cinv, l, 0, X, ldx, 0, alt, ldx, 0, 1, 1, nullptr, (hipStream_t)stream));
+    LQ_HIP_TRY(hipMemcpyAsync(X, alt, (size_t)l * ldx * sizeof(float), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return LQ_OK;
+  }
   LQ_TRY(launch_cholesky(G, l, 1, (hipStream_t)stream));
   return launch_trsm(G, l, X, m, ldx, 0, 1, (hipStream_t)stream);
 }
@@ -498,6 +522,12 @@ int lq_test_sym_eig(double* G, int l, float* Ut, double* lambda, double* scratch
   if (!G || !Ut || !lambda || !scratch) return LQ_ERR_NULL;
   if (l % 2 || l < 2 || l > 256) return LQ_ERR_ARG;
   return launch_jacobi_eig(G, l, scratch, Ut, lambda, 1, (hipStream_t)stream);
+}
+
+int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void* stream) {
+  if (!G || !Ut || !lambda) return LQ_ERR_NULL;
+  if (!jacobi_fast_supported(l)) return LQ_ERR_ARG;
+  return launch_jacobi_fast(G, l, Ut, lambda, 1, (hipStream_t)stream);
 }
 
 size_t lq_test_lds_limit(void) { return lds_limit_for_tests(); }

@@ -132,6 +132,22 @@ __device__ inline void load_codes(const uint8_t* __restrict__ codes, int64_t run
   }
 }
 
+// ---- quad layout: one lane holds 4 consecutive weights, 4 lanes a 16-weight run, so that every wavefront
+// load / store covers one contiguous stretch.  Codes of quad `quad` occupy bits [quad*4*BITS, +4*BITS).
+template <int BITS>
+__device__ inline void load_quad_codes(const uint8_t* __restrict__ codes, int64_t quad, uint32_t (&c)[4]) {
+  uint32_t w;
+  if constexpr (BITS == 8) w = *reinterpret_cast<const uint32_t*>(codes + quad * 4);
+  else if constexpr (BITS == 4) w = *reinterpret_cast<const uint16_t*>(codes + quad * 2);
+  else if constexpr (BITS == 2) w = codes[quad];
+  else {   // 3 bits: 12 bits starting at bit 12*quad = byte floor(1.5*quad), nibble-aligned
+    const int64_t byte = (quad * 3) >> 1;
+    w = ((uint32_t)codes[byte] | ((uint32_t)codes[byte + 1] << 8)) >> ((quad & 1) * 4);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) c[j] = (w >> (j * BITS)) & ((1u << BITS) - 1u);
+}
+
 // ---- second-level (integer) scale quantization -------------------------------------------------
 // Maximum over the `width` consecutive lanes (power of two, 16..256, aligned) that hold one scale
 // group; the workgroup has 256 threads.  s_wave: 4 floats of LDS.  Contains barriers when

@@ -9,6 +9,7 @@
 #include <mutex>
 
 #include "nf_device.h"
+#include "profiler.h"
 
 namespace lq {
 
@@ -119,28 +120,23 @@ __global__ __launch_bounds__(256) void quantize_fused_kernel(const float* __rest
 }
 
 // ---------------------------------------------------------------------------------------------
-// Dequantize: one run per lane.
+// Dequantize: one quad (4 consecutive weights) per lane and step; every wavefront store is 1 KB contiguous.
 template <int BITS>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ codes,
                                                       const uint8_t* __restrict__ sidx, const float* __restrict__ v,
-                                                      int64_t nruns, int runs_per_block, int scale_block, int levels,
+                                                      int64_t nquads, int qpb_shift, int sb_shift, int levels,
                                                       const DevTables* __restrict__ tab, float* __restrict__ out) {
   __shared__ float s_code[1 << BITS];
   __shared__ float s_thr[1 << BITS];
   load_tables<BITS>(tab, s_code, s_thr);
-  const int64_t run = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (run >= nruns) return;
-  const int64_t blk = run / runs_per_block;
-  const float sh = block_scale(sidx[blk], v[blk / scale_block], levels);
-  uint32_t c[16];
-  load_codes<BITS>(codes, run, c);
-  float4* o = reinterpret_cast<float4*>(out + run * 16);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int64_t quad = (int64_t)blockIdx.x * 256 + threadIdx.x; quad < nquads; quad += (int64_t)gridDim.x * 256) {
+    const int64_t blk = quad >> qpb_shift;
+    const float sh = block_scale(sidx[blk], v[blk >> sb_shift], levels);
+    uint32_t c[4];
+    load_quad_codes<BITS>(codes, quad, c);
     float4 f;
-    f.x = s_code[c[4 * q]] * sh; f.y = s_code[c[4 * q + 1]] * sh;
-    f.z = s_code[c[4 * q + 2]] * sh; f.w = s_code[c[4 * q + 3]] * sh;
-    o[q] = f;
+    f.x = s_code[c[0]] * sh; f.y = s_code[c[1]] * sh; f.z = s_code[c[2]] * sh; f.w = s_code[c[3]] * sh;
+    *reinterpret_cast<float4*>(out + (quad << 2)) = f;
   }
 }
 
@@ -168,6 +164,8 @@ int launch_quantize(const float* x, int64_t n, const lq_config& c, uint8_t* code
   const DevTables* tab;
   LQ_TRY(device_tables(&tab));
   const int64_t nruns = n / 16;
+  prof::Scope ps(prof::QUANTIZE, st,
+                 (double)n * (4.0 + c.bits / 8.0 + 1.0 / c.block + 4.0 / ((double)c.block * c.scale_block)));
   switch (c.bits) {
     case 2: launch_quantize_bits<2>(x, nruns, c, tab, codes, sidx, v, st); break;
     case 3: launch_quantize_bits<3>(x, nruns, c, tab, codes, sidx, v, st); break;
@@ -183,15 +181,18 @@ int launch_dequant(const uint8_t* codes, const uint8_t* sidx, const float* v, in
                    float* out, hipStream_t st) {
   const DevTables* tab;
   LQ_TRY(device_tables(&tab));
-  const int64_t nruns = n / 16;
-  const int rpb = c.block / 16;
-  const dim3 grid((unsigned)((nruns + 255) / 256)), block(256);
+  const int64_t nruns = n / 4;            // quads
+  const int rpb = __builtin_ctz(c.block / 4);            // log2(quads per block)
+  const int64_t want = (nruns + 255) / 256;
+  const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
   const int lv = scale_levels(c);
+  prof::Scope ps(prof::DEQUANTIZE, st,
+                 (double)n * (4.0 + c.bits / 8.0 + 1.0 / c.block + 4.0 / ((double)c.block * c.scale_block)));
   switch (c.bits) {
-    case 2: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
-    case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
-    case 4: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
-    case 8: hipLaunchKernelGGL(dequant_kernel<8>, grid, block, 0, st, codes, sidx, v, nruns, rpb, c.scale_block, lv, tab, out); break;
+    case 2: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, st, codes, sidx, v, nruns, rpb, __builtin_ctz(c.scale_block), lv, tab, out); break;
+    case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, st, codes, sidx, v, nruns, rpb, __builtin_ctz(c.scale_block), lv, tab, out); break;
+    case 4: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, st, codes, sidx, v, nruns, rpb, __builtin_ctz(c.scale_block), lv, tab, out); break;
+    case 8: hipLaunchKernelGGL(dequant_kernel<8>, grid, block, 0, st, codes, sidx, v, nruns, rpb, __builtin_ctz(c.scale_block), lv, tab, out); break;
     default: return LQ_ERR_CONFIG;
   }
   LQ_HIP_TRY(hipGetLastError());

@@ -75,6 +75,12 @@ _lib.lq_error_table.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _int, _int, _v
                                 _vp, _vp, _vp, _vp, _sz, _vp]
 
 
+_lib.lq_profile_enable.argtypes = [_int]
+_lib.lq_profile_class_name.restype = C.c_char_p
+_lib.lq_profile_class_name.argtypes = [_int]
+_lib.lq_profile_read.argtypes = [_int, _vp, _vp, _vp]
+
+
 def _check(status, where):
     if status != 0:
         raise LqError(status, where)
@@ -221,3 +227,22 @@ def fisher_row_col(f: torch.Tensor):
     a = sf.mean(dim=1)
     b = sf.mean(dim=0) / sf.mean()
     return (a * a).to(torch.float32).contiguous(), (b * b).to(torch.float32).contiguous()
+
+
+def profile_enable(on: bool) -> None:
+    _check(_lib.lq_profile_enable(1 if on else 0), "lq_profile_enable")
+
+
+def profile_reset() -> None:
+    _check(_lib.lq_profile_reset(), "lq_profile_reset")
+
+
+def profile_read() -> dict:
+    """-> {kernel class name: (total_ms, launches, algorithmic work)} for classes that were launched."""
+    out = {}
+    for cls in range(_lib.lq_profile_num_classes()):
+        ms, n, wk = C.c_double(0), C.c_int64(0), C.c_double(0)
+        _check(_lib.lq_profile_read(cls, C.addressof(ms), C.addressof(n), C.addressof(wk)), "lq_profile_read")
+        if n.value:
+            out[_lib.lq_profile_class_name(cls).decode()] = (ms.value, n.value, wk.value)
+    return out

@@ -15,8 +15,9 @@ def env():
     L = lq._lib
     vp, i64, it = C.c_void_p, C.c_int64, C.c_int
     L.lq_test_wide_gemm.argtypes = [it, it, i64, i64, vp, i64, vp, i64, vp, i64, it, vp, vp]
-    L.lq_test_orthonormalize.argtypes = [vp, it, i64, i64, vp, vp]
+    L.lq_test_orthonormalize.argtypes = [vp, it, i64, i64, vp, vp, vp]
     L.lq_test_sym_eig.argtypes = [vp, it, vp, vp, vp, vp]
+    L.lq_test_sym_eig_fast.argtypes = [vp, it, vp, vp, vp]
     L.lq_test_lds_limit.restype = C.c_size_t
     return torch, lq, L
 
@@ -52,8 +53,9 @@ def test_wide_gemm(env, mode, l, big, K, splits):
         assert np.all(got[:, big:] == 7.0)          # columns past the matrix are never written
 
 
+@pytest.mark.parametrize("use_alt", [True, False])
 @pytest.mark.parametrize("l,m", [(32, 100), (64, 768), (96, 4096), (128, 1000), (256, 2048)])
-def test_orthonormalize(env, l, m):
+def test_orthonormalize(env, l, m, use_alt):
     torch, lq, L = env
     rng = np.random.default_rng(l + m)
     ld = up32(m)
@@ -64,7 +66,9 @@ def test_orthonormalize(env, l, m):
     x[:, :m] = (u * np.logspace(0, -2, min(l, m))) @ vt
     xt = torch.from_numpy(x).cuda()
     scratch = torch.empty(17 * l * l, dtype=torch.float64, device="cuda")
-    assert L.lq_test_orthonormalize(xt.data_ptr(), l, m, ld, scratch.data_ptr(), None) == 0
+    alt = torch.zeros((l, ld), dtype=torch.float32, device="cuda")
+    assert L.lq_test_orthonormalize(xt.data_ptr(), l, m, ld, scratch.data_ptr(), alt.data_ptr() if use_alt else None,
+                                    None) == 0
     torch.cuda.synchronize()
     q = xt.cpu().numpy().astype(np.float64)
     if l <= m:
@@ -93,6 +97,36 @@ def test_sym_eig(env, l):
     assert np.max(np.abs(lam_h - ref) / ref) < 1e-9
     assert np.max(np.abs(u @ u.T - np.eye(l))) < 1e-5
     assert np.max(np.abs(u @ g @ u.T - np.diag(lam_h))) < 1e-4 * lam_h[0]
+
+
+@pytest.mark.parametrize("l", [32, 64, 96, 128])
+@pytest.mark.parametrize("near_diagonal", [False, True])
+def test_sym_eig_fast(env, l, near_diagonal):
+    torch, lq, L = env
+    rng = np.random.default_rng(l + 1000)
+    if near_diagonal:      # the warm-started case: nearly orthogonal rows with a cluster of close values
+        lam = np.concatenate([[900.0, 400.0], np.linspace(10.0, 9.0, l - 2)])
+        pert = 1e-2 * rng.standard_normal((l, l))
+        q, _ = np.linalg.qr(np.eye(l) + pert)
+        g = (q * lam) @ q.T
+    else:
+        b = rng.standard_normal((l, 3 * l)) * np.logspace(1, 0, l)[:, None]
+        g = b @ b.T
+    g = (g + g.T) / 2
+    gt = torch.from_numpy(g.copy()).cuda()
+    ut = torch.empty((l, l), dtype=torch.float32, device="cuda")
+    lam_d = torch.empty(l, dtype=torch.float64, device="cuda")
+    assert L.lq_test_sym_eig_fast(gt.data_ptr(), l, ut.data_ptr(), lam_d.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(gt.cpu().numpy(), g)
+    u = ut.cpu().numpy().astype(np.float64)
+    ref = np.sort(np.linalg.eigvalsh(g))[::-1]
+    assert np.max(np.abs(u @ u.T - np.eye(l))) < 2e-5
+    rq = np.einsum("ij,jk,ik->i", u, g, u)                      # Rayleigh quotients of the returned rows
+    assert np.max(np.abs(rq - ref) / ref) < 5e-7                # second-order accurate eigenvalues
+    off = u @ g @ u.T - np.diag(rq)
+    assert np.max(np.abs(off)) < 2e-5 * ref[0]
+    assert np.max(np.abs(lam_d.cpu().numpy() - ref) / ref) < 1e-4
 
 
 def test_report_lds_limit(env):
