@@ -29,7 +29,7 @@ def cpu_baseline(first_matrix: np.ndarray) -> dict:
     """The oracle, as it stands, timed on a bounded sample of the workload on the host cores."""
     from oracle import lq_oracle as O
     O.build()
-    sample = np.ascontiguousarray(first_matrix[:384, :384])
+    sample = np.ascontiguousarray(first_matrix[:1024, :1024])
     cfg = O.config(3, 64, 256)
     t0 = time.perf_counter()
     O.lq(sample, RANK, cfg, ITERS)
@@ -40,9 +40,9 @@ def cpu_baseline(first_matrix: np.ndarray) -> dict:
         cores = os.cpu_count() or 1
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
     return {"value": 1.0 / dt, "unit": "matrix-configs/s on the sample", "cores": cores, "kind": "oracle",
-            "sample": "one 384x384 corner of matrix 0, rank 64, NF3 B0=64 B1=256, 10 iterations "
+            "sample": "one 1024x1024 corner of matrix 0, rank 64, NF3 B0=64 B1=256, 10 iterations "
                       f"(exact Jacobi SVD each iteration); {dt:.1f} s. A full 4096x4096 cell costs about "
-                      "(4096/384)^3 times as much."}
+                      "4^3 = 64 times as much."}
 
 
 def main() -> int:
@@ -66,7 +66,9 @@ def main() -> int:
     cfgs = [lq.config(*g) for g in gen.config_grid()]
     host = [gen.workload_matrix(3, i) for i in range(min(args.matrices, len(gen.LLAMA2_7B_LAYER)))]
     mats = [torch.from_numpy(w).to(dev) for w in host]
-    ws = lq.error_table_workspace(4096, 11008, RANK, len(cfgs), device=dev)
+    # one workspace, large enough for every shape of the layer
+    ws = max((lq.error_table_workspace(d, k, RANK, len(cfgs), device=dev) for d, k in {tuple(m.shape) for m in mats}),
+             key=lambda t: t.numel())
     torch.cuda.synchronize()
 
     def step():
