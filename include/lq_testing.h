@@ -30,6 +30,10 @@ int lq_test_sym_eig(double* G, int l, float* Ut, double* lambda, double* scratch
  * approximate eigenvectors of the symmetric fp64 G (left untouched), ordered by descending eigenvalue
  * estimate lambda (fp32 accuracy). */
 int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void* stream);
+/* Host-side evaluation of the code search the kernels use (threshold count for 2 and 3 bits, bucket table
+ * plus two comparisons for 4 and 8 bits) on one normalised weight x; -1 for an unsupported bit width.
+ * Needs no GPU. */
+int lq_test_bucket_code(int bits, float x);
 /* Largest LDS allocation per workgroup the device reports, in bytes. */
 size_t lq_test_lds_limit(void);
 

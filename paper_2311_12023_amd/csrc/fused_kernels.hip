@@ -16,85 +16,126 @@
 namespace lq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 64;     // tile rows
 constexpr int TN = 128;    // tile columns
 constexpr int PP = TN + 4; // pitch of the product tile in LDS
 constexpr int KC = 32;     // rank chunk staged in LDS
+constexpr int NTHR1 = 512; // threads of the phase-1 workgroup: 8 wavefronts, one 32x32 MFMA tile each
 
+// Stores the 4 codes of one quad.  2, 4, 8 bits: 1, 2, 4 bytes per lane, contiguous across lanes.  3 bits: the
+// four lanes of a 16-weight run gather their 12-bit pieces into the run's 48-bit word and three of them store
+// 16 bits each.  All 64 lanes must call (cross-lane exchange inside).
 template <int BITS>
-__device__ inline void phase1_epilogue(const PhaseArgs& a, const LoopProblem& pr, int z, const float* pt,
-                                       const float* s_code, const float* s_thr, int64_t r0, int64_t c0,
-                                       const float4 (&wreg)[2][4]) {
-  Thresholds<BITS> thr(s_thr);
-  const int tid = threadIdx.x;
-  const int rpb = pr.cfg.block / 16;
-  uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
-  BlockRec* blk = a.blk + (size_t)z * a.strideBlk;
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int rid = tid + 256 * u;            // run inside the tile: 8 runs per row
-    const int lr = rid >> 3, rc = rid & 7;
-    const int64_t row = r0 + lr, col = c0 + 16 * rc;
-    const bool live = row < a.d && col < a.k;
-    float t[16], w[16];
-    if (live) {
-      const float rs = a.rsr ? a.rsr[row] : 1.0f;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 f = wreg[u][q];
-        const float4 p = *reinterpret_cast<const float4*>(pt + lr * PP + 16 * rc + 4 * q);
-        float pv[4] = {p.x, p.y, p.z, p.w};
-        const float fv[4] = {f.x, f.y, f.z, f.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float cwj = 1.0f;
-          if (a.rsc) {
-            pv[e] = pv[e] * (rs * a.rsc[col + 4 * q + e]);
-            cwj = a.col_w[col + 4 * q + e];
-          }
-          t[4 * q + e] = fv[e] - pv[e];
-          w[4 * q + e] = cwj;
-        }
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 16; ++j) { t[j] = 0.0f; w[j] = 0.0f; }
-    }
-    float amax = run_absmax(t);
-    for (int off = 1; off < rpb; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-    const float rcp = safe_reciprocal(amax);
-    uint32_t c[16];
-    float e2 = 0.f, eq = 0.f, q2 = 0.f;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      c[j] = thr.nearest(t[j] * rcp);
-      const float q = s_code[c[j]];
-      const float e = t[j] - q * amax;
-      e2 = fmaf(w[j] * e, e, e2);
-      eq = fmaf(w[j] * e, q, eq);
-      q2 = fmaf(w[j] * q, q, q2);
-    }
-    for (int off = 1; off < rpb; off <<= 1) {
-      e2 += __shfl_xor(e2, off); eq += __shfl_xor(eq, off); q2 += __shfl_xor(q2, off);
-    }
-    if (live) {
-      const int64_t run = ((int64_t)row * a.k + col) >> 4;
-      store_codes<BITS>(codes, run, c);
-      if ((run & (rpb - 1)) == 0) {
-        BlockRec rec; rec.s = amax; rec.e2 = e2; rec.eq = eq; rec.q2 = q2;
-        blk[run / rpb] = rec;
-      }
+__device__ __forceinline__ void store_quad_codes(uint8_t* __restrict__ codes, int64_t quad, const uint32_t (&c)[4],
+                                                 bool live) {
+  const uint32_t w = c[0] | (c[1] << BITS) | (c[2] << (2 * BITS)) | (c[3] << (3 * BITS));
+  if constexpr (BITS == 8) {
+    if (live) *reinterpret_cast<uint32_t*>(codes + quad * 4) = w;
+  } else if constexpr (BITS == 4) {
+    if (live) *reinterpret_cast<uint16_t*>(codes + quad * 2) = (uint16_t)w;
+  } else if constexpr (BITS == 2) {
+    if (live) codes[quad] = (uint8_t)w;
+  } else {
+    const int sub = threadIdx.x & 3;
+    uint32_t lo = sub < 2 ? (w << (12 * sub)) : (sub == 2 ? (w << 24) : 0u);        // bits 0..31 of the run word
+    uint32_t hi = sub == 2 ? (w >> 8) : (sub == 3 ? (w << 4) : 0u);                 // bits 32..47
+    lo |= __shfl_xor(lo, 1); hi |= __shfl_xor(hi, 1);
+    lo |= __shfl_xor(lo, 2); hi |= __shfl_xor(hi, 2);
+    if (live && sub < 3) {
+      const uint16_t piece = sub == 0 ? (uint16_t)lo : (sub == 1 ? (uint16_t)(lo >> 16) : (uint16_t)hi);
+      *reinterpret_cast<uint16_t*>(codes + (quad >> 2) * 6 + 2 * sub) = piece;
     }
   }
 }
 
-__global__ __launch_bounds__(256) void lowrank_blockquant_kernel(PhaseArgs a) {
+// Epilogue of phase 1 in quad layout: lane `tid` handles quads tid, tid+512, ... of the 64 x 128 tile (32 quads
+// per row), so W loads, LDS reads of the product and code stores are all contiguous across lanes.  QPB = B0/4
+// lanes hold one block.
+template <int BITS, int QPB, bool WITH_ERR>
+__device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const float* pt, const LdsTables& s_tab,
+                                                int64_t r0, int64_t c0, const float4 (&wreg)[4]) {
+  Thresholds<BITS> thr(s_tab);
+  const float* s_code = s_tab.code;
+  const int tid = threadIdx.x;
+  uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
+  BlockRec* blk = a.blk + (size_t)z * a.strideBlk;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int qid = tid + NTHR1 * u;
+    const int lr = qid >> 5, cq = qid & 31;
+    const int64_t row = r0 + lr, col = c0 + 4 * cq;
+    const bool live = row < a.d && col < a.k;
+    const float4 p = *reinterpret_cast<const float4*>(pt + lr * PP + 4 * cq);
+    float t[4] = {0.f, 0.f, 0.f, 0.f}, w[4] = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+      float pv[4] = {p.x, p.y, p.z, p.w};
+      const float fv[4] = {wreg[u].x, wreg[u].y, wreg[u].z, wreg[u].w};
+      if (a.rsc) {
+        const float rs = a.rsr[row];
+        const float4 rc = *reinterpret_cast<const float4*>(a.rsc + col);
+        pv[0] *= rs * rc.x; pv[1] *= rs * rc.y; pv[2] *= rs * rc.z; pv[3] *= rs * rc.w;
+        if (WITH_ERR) {
+          const float4 cw = *reinterpret_cast<const float4*>(a.col_w + col);
+          w[0] = cw.x; w[1] = cw.y; w[2] = cw.z; w[3] = cw.w;
+        }
+      } else {
+        w[0] = w[1] = w[2] = w[3] = 1.0f;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) t[e] = fv[e] - pv[e];
+    }
+    float amax = fmaxf(fmaxf(fabsf(t[0]), fabsf(t[1])), fmaxf(fabsf(t[2]), fabsf(t[3])));
+#pragma unroll
+    for (int off = 1; off < QPB; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    const float rcp = safe_reciprocal(amax);
+    uint32_t c[4];
+    float e2 = 0.f, eq = 0.f, q2 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      c[e] = thr.nearest(t[e] * rcp);
+      if (WITH_ERR) {
+        const float q = s_code[c[e]];
+        const float err = t[e] - q * amax;
+        e2 = fmaf(w[e] * err, err, e2);
+        eq = fmaf(w[e] * err, q, eq);
+        q2 = fmaf(w[e] * q, q, q2);
+      }
+    }
+    if (WITH_ERR) {
+#pragma unroll
+      for (int off = 1; off < QPB; off <<= 1) {
+        e2 += __shfl_xor(e2, off); eq += __shfl_xor(eq, off); q2 += __shfl_xor(q2, off);
+      }
+    }
+    const int64_t quad = ((int64_t)row * a.k + col) >> 2;
+    store_quad_codes<BITS>(codes, quad, c, live);
+    if (live && (cq & (QPB - 1)) == 0) {
+      BlockRec rec; rec.s = amax; rec.e2 = e2; rec.eq = eq; rec.q2 = q2;
+      blk[quad / QPB] = rec;
+    }
+  }
+}
+
+template <int BITS, bool WITH_ERR>
+__device__ __forceinline__ void phase1_dispatch_block(const PhaseArgs& a, int block, int z, const float* pt,
+                                                      const LdsTables& s_tab, int64_t r0, int64_t c0,
+                                                      const float4 (&wreg)[4]) {
+  switch (block) {
+    case 16: phase1_epilogue<BITS, 4, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
+    case 32: phase1_epilogue<BITS, 8, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
+    case 64: phase1_epilogue<BITS, 16, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
+    default: phase1_epilogue<BITS, 32, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
+  }
+}
+
+template <bool WITH_ERR>
+__global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) {
   // The operand chunks (Y: KC x TM, B: KC x TN) and the product tile share one LDS buffer: the product is
   // written after the last MFMA has read its operands.
   __shared__ __attribute__((aligned(16))) float smem[TM * PP];
-  __shared__ float s_code[256];
-  __shared__ float s_thr[256];
+  __shared__ LdsTables s_tab;
   float (*ys)[TM] = reinterpret_cast<float (*)[TM]>(smem);
   float (*bs)[TN] = reinterpret_cast<float (*)[TN]>(smem + KC * TM);
   float* pt = smem;
@@ -103,84 +144,94 @@ __global__ __launch_bounds__(256) void lowrank_blockquant_kernel(PhaseArgs a) {
   const int z = blockIdx.x, tid = threadIdx.x;
   const LoopProblem pr = a.prob[z];
   const int64_t r0 = (int64_t)blockIdx.z * TM, c0 = (int64_t)blockIdx.y * TN;
-  // this lane's two runs of W, fetched now so that the loads overlap the MFMA stage
-  float4 wreg[2][4];
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int rid = tid + 256 * u;
-    const int64_t row = r0 + (rid >> 3), col = c0 + 16 * (rid & 7);
-    if (row < a.d && col < a.k) {
-      const float4* wp = reinterpret_cast<const float4*>(a.W + (size_t)row * a.k + col);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) wreg[u][q] = wp[q];
-    } else {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) wreg[u][q] = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-  }
   const float* __restrict__ Y = a.Y + (size_t)z * a.strideY;
   const float* __restrict__ B = a.B + (size_t)z * a.strideB;
   const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
-  const int wr = wave >> 1, wc = wave & 1;
+  const int wr = wave >> 2, wc = wave & 3;      // 2 x 4 grid of 32x32 tiles
 
-  floatx16 acc[2];
+  // operand chunk staging through registers, 128-bit pieces: piece idx = tid + 512*i of the chunk.  The wide
+  // bases have at least round_up32(rank) rows and zero-padded leading dimensions, so only the column offset
+  // needs clamping; rows past `rank` and columns past the matrix are replaced by zeros after the load.
+  floatx4 yst[KC * TM / (4 * NTHR1)], bst[KC * TN / (4 * NTHR1)];
+  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  auto fetch_chunk = [&](int k0) {
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < KC * TM / (4 * NTHR1); ++i) {
+      const int idx = tid + NTHR1 * i, kk = idx / (TM / 4), rr = 4 * (idx % (TM / 4));
+      const int64_t off = r0 + rr;
+      const bool ok = k0 + kk < a.rank && off < a.d;
+      const floatx4 v = *reinterpret_cast<const floatx4*>(Y + (size_t)(k0 + kk) * a.ldy + (off + 4 <= a.ldy ? off : a.ldy - 4));
+      yst[i] = ok ? v : zero4;
+    }
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.0f;
+    for (int i = 0; i < KC * TN / (4 * NTHR1); ++i) {
+      const int idx = tid + NTHR1 * i, kk = idx / (TN / 4), cc = 4 * (idx % (TN / 4));
+      const int64_t off = c0 + cc;
+      const bool ok = k0 + kk < a.rank && off < a.k;
+      const floatx4 v = *reinterpret_cast<const floatx4*>(B + (size_t)(k0 + kk) * a.ldb + (off + 4 <= a.ldb ? off : a.ldb - 4));
+      bst[i] = ok ? v : zero4;
+    }
+  };
+  fetch_chunk(0);
+  // code-book tables of this problem's bit width (visible after the barriers of the product stage)
+  load_tables_slot_nosync(a.tables, pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3, s_tab);
+  // this lane's 4 quads of W, fetched now so that the loads overlap the MFMA stage
+  float4 wreg[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int qid = tid + NTHR1 * u;
+    const int64_t row = r0 + (qid >> 5), col = c0 + 4 * (qid & 31);
+    wreg[u] = (row < a.d && col < a.k) ? *reinterpret_cast<const float4*>(a.W + (size_t)row * a.k + col)
+                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  floatx16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
 
   for (int k0 = 0; k0 < a.rank; k0 += KC) {
     __syncthreads();
-    // stage Y[k0..k0+32)[r0..r0+64) and B[k0..k0+32)[c0..c0+128); rows past rank and columns past the
-    // matrix are zero (the wide bases hold more than `rank` rows; only the leading ones form L1 L2)
-    for (int idx = tid; idx < KC * TM; idx += 256) {
-      const int kk = idx / TM, rr = idx % TM;
-      float val = 0.0f;
-      if (k0 + kk < a.rank && r0 + rr < a.d) val = Y[(size_t)(k0 + kk) * a.ldy + r0 + rr];
-      ys[kk][rr] = val;
+    // rows past `rank` and columns past the matrix are zero (the wide bases hold more than `rank` rows; only
+    // the leading ones form L1 L2)
+#pragma unroll
+    for (int i = 0; i < KC * TM / (4 * NTHR1); ++i) {
+      const int idx = tid + NTHR1 * i;
+      *reinterpret_cast<floatx4*>(&ys[idx / (TM / 4)][4 * (idx % (TM / 4))]) = yst[i];
     }
-    for (int idx = tid; idx < KC * TN; idx += 256) {
-      const int kk = idx / TN, cc = idx % TN;
-      float val = 0.0f;
-      if (k0 + kk < a.rank && c0 + cc < a.k) val = B[(size_t)(k0 + kk) * a.ldb + c0 + cc];
-      bs[kk][cc] = val;
+#pragma unroll
+    for (int i = 0; i < KC * TN / (4 * NTHR1); ++i) {
+      const int idx = tid + NTHR1 * i;
+      *reinterpret_cast<floatx4*>(&bs[idx / (TN / 4)][4 * (idx % (TN / 4))]) = bst[i];
     }
     __syncthreads();
+    if (k0 + KC < a.rank) fetch_chunk(k0 + KC);
 #pragma unroll
     for (int s = 0; s < KC / 2; ++s) {
       const float av = ys[2 * s + lh][32 * wr + ln];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const float bv = bs[2 * s + lh][64 * wc + 32 * j + ln];
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[j], 0, 0, 0);
-      }
+      const float bv = bs[2 * s + lh][32 * wc + ln];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
     }
   }
   __syncthreads();          // all operand reads done before the product overwrites the buffer
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int row = 32 * wr + 8 * (e >> 2) + 4 * lh + (e & 3);
-      pt[row * PP + 64 * wc + 32 * j + ln] = acc[j][e];
-    }
-  // code-book for this problem's bit width
-  const int slot = pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3;
-  s_code[tid] = a.tables->code[slot][tid];
-  s_thr[tid] = a.tables->thr[slot][tid];
+  for (int e = 0; e < 16; ++e) {
+    const int row = 32 * wr + 8 * (e >> 2) + 4 * lh + (e & 3);
+    pt[row * PP + 32 * wc + ln] = acc[e];
+  }
   __syncthreads();
   switch (pr.cfg.bits) {
-    case 2: phase1_epilogue<2>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
-    case 3: phase1_epilogue<3>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
-    case 4: phase1_epilogue<4>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
-    default: phase1_epilogue<8>(a, pr, z, pt, s_code, s_thr, r0, c0, wreg); break;
+    case 2: phase1_dispatch_block<2, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
+    case 3: phase1_dispatch_block<3, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
+    case 4: phase1_dispatch_block<4, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
+    default: phase1_dispatch_block<8, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
   }
 }
 
-int launch_lowrank_blockquant(const PhaseArgs& a, hipStream_t st) {
+int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st) {
   const dim3 grid((unsigned)a.batch, (unsigned)((a.k + TN - 1) / TN), (unsigned)((a.d + TM - 1) / TM));
   prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st, (double)a.d * a.k * 4.0 * a.batch);
-  hipLaunchKernelGGL(lowrank_blockquant_kernel, grid, dim3(256), 0, st, a);
+  if (with_err) hipLaunchKernelGGL(lowrank_blockquant_kernel<true>, grid, dim3(NTHR1), 0, st, a);
+  else hipLaunchKernelGGL(lowrank_blockquant_kernel<false>, grid, dim3(NTHR1), 0, st, a);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }

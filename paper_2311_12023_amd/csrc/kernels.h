@@ -7,7 +7,7 @@
 
 namespace lq {
 
-struct DevTables;
+typedef NfTables DevTables;
 
 constexpr int MODE_NT = 0;   // C[l x M] = X[l x K] * A[M x K]^T
 constexpr int MODE_NN = 1;   // C[l x N] = X[l x K] * A[K x N]
@@ -105,8 +105,9 @@ struct PhaseArgs {
   int batch;
 };
 
-// Phase 1: T = W - L1 L2 tile by tile (MFMA), block absmax, codes, per-block error sums.
-int launch_lowrank_blockquant(const PhaseArgs& a, hipStream_t st);
+// Phase 1: T = W - L1 L2 tile by tile (MFMA), block absmax, codes and, with_err, the per-block error sums
+// (without them phase 2 still produces scale indices and v, but its error output is meaningless).
+int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st);
 // Phase 2: Quantize-INT of the block absmax values, cast of v, and eps of the iteration (err_out).
 // min_block: smallest B0 in the batch (sizes the grid).
 int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st);

@@ -263,9 +263,9 @@ struct LoopOut {          // batch == 1 only: user buffers that receive the quan
 // Runs Algorithm 2 for `batch` configurations in lock step from the shared first factorization
 // (Y1, B1, lam_cold).  Host outputs: trace[b * iters + t], iters_done[b].  On return *Yfin / *Bfin /
 // *lamfin describe the last Factorize of problem 0 (wide, Ritz order).
-static int run_loop(Ctx& c, const lq_config* cfgs, int batch, int iters, int early_stop, const float* Y1,
-                    const float* B1, const LoopOut* direct, double* trace, int32_t* iters_done, const float** Yfin,
-                    const float** Bfin, const double** lamfin) {
+static int run_loop(Ctx& c, const lq_config* cfgs, int batch, int iters, int early_stop, bool want_trace,
+                    const float* Y1, const float* B1, const LoopOut* direct, double* trace, int32_t* iters_done,
+                    const float** Yfin, const float** Bfin, const double** lamfin) {
   const Plan& pl = c.pl;
   std::vector<LoopProblem> probs(batch);
   int min_block = 1 << 30;
@@ -310,7 +310,9 @@ static int run_loop(Ctx& c, const lq_config* cfgs, int batch, int iters, int ear
   for (int t = 1; t <= iters; ++t) {
     a.Y = Ycur; a.B = Bcur; a.strideY = sY; a.strideB = sB;
     a.R = nullptr; a.Qd = nullptr; a.err_out = errs + (t - 1);
-    LQ_TRY(launch_lowrank_blockquant(a, c.st));
+    // the error of an iteration costs extra arithmetic per weight: only computed when somebody looks at it
+    const bool with_err = want_trace || early_stop || t == iters;
+    LQ_TRY(launch_lowrank_blockquant(a, with_err, c.st));
     LQ_TRY(launch_scalequant_error(a, min_block, c.st));
     done = t;
     bool last = t == iters;
@@ -346,7 +348,9 @@ static int run_loop(Ctx& c, const lq_config* cfgs, int batch, int iters, int ear
     }
     if (iters_done) iters_done[b] = nd;
     if (trace)
-      for (int t = 0; t < iters; ++t) trace[(size_t)b * iters + t] = t < nd ? host_err[(size_t)b * MAX_ITERS + t] : NAN;
+      for (int t = 0; t < iters; ++t)
+        trace[(size_t)b * iters + t] =
+            (t < nd && (want_trace || early_stop || t == iters - 1)) ? host_err[(size_t)b * MAX_ITERS + t] : NAN;
   }
   if (Yfin) *Yfin = Ycur;
   if (Bfin) *Bfin = Bcur;
@@ -445,7 +449,8 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   std::vector<double> trace(iters, NAN);
   int32_t done = 0;
   const float* Yf; const float* Bf; const double* lamf;
-  LQ_TRY(run_loop(c, &cfg, 1, iters, early_stop, Y1, B1, &direct, trace.data(), &done, &Yf, &Bf, &lamf));
+  LQ_TRY(run_loop(c, &cfg, 1, iters, early_stop, err_trace != nullptr, Y1, B1, &direct, trace.data(), &done, &Yf, &Bf,
+                  &lamf));
   LQ_TRY(emit_factors(c, Yf, Bf, lamf, L1, L2, sigma));
   if (err) *err = trace[done - 1];
   if (err_trace) std::memcpy(err_trace, trace.data(), sizeof(double) * iters);
@@ -482,8 +487,8 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
   std::vector<int32_t> done(batch_max);
   for (int c0 = 0; c0 < n_cfgs; c0 += batch_max) {
     const int nb = std::min(batch_max, n_cfgs - c0);
-    LQ_TRY(run_loop(c, cf.data() + c0, nb, iters, early_stop, Y1, B1, nullptr, trace.data(), done.data(), nullptr,
-                    nullptr, nullptr));
+    LQ_TRY(run_loop(c, cf.data() + c0, nb, iters, early_stop, err_trace != nullptr, Y1, B1, nullptr, trace.data(),
+                    done.data(), nullptr, nullptr, nullptr));
     for (int b = 0; b < nb; ++b) {
       const double eps = trace[(size_t)b * iters + done[b] - 1];
       err_sq[c0 + b] = eps * eps;
@@ -528,6 +533,22 @@ int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void
   if (!G || !Ut || !lambda) return LQ_ERR_NULL;
   if (!jacobi_fast_supported(l)) return LQ_ERR_ARG;
   return launch_jacobi_fast(G, l, Ut, lambda, 1, (hipStream_t)stream);
+}
+
+int lq_test_bucket_code(int bits, float x) {
+  const int slot = bits_slot(bits);
+  if (slot < 0) return -1;
+  const HostTables& t = host_tables();
+  if (bits <= 3) {
+    int c = 0;
+    for (int i = 0; i < (1 << bits) - 1; ++i) c += x >= t.thr[slot][i];
+    return c;
+  }
+  int j = (int)std::fmaf(x, 256.0f, 256.0f);
+  if (!(std::fmaf(x, 256.0f, 256.0f) >= 0.0f)) j = 0;   // NaN and negatives as the device's conversion treats them
+  j = j < 0 ? 0 : (j > 511 ? 511 : j);
+  const int c0 = t.lut[slot][j];
+  return c0 + (x >= t.thr[slot][c0]) + (x >= t.thr[slot][c0 + 1]);
 }
 
 size_t lq_test_lds_limit(void) { return lds_limit_for_tests(); }

@@ -41,10 +41,15 @@ inline int64_t num_groups(int64_t n, const lq_config& c) {
 int bits_slot(int bits);
 // code[i]: value of code i.  thr[i], i < 2^bits-1: smallest fp32 strictly above the midpoint of
 // code i and code i+1, so that (number of thr <= x) is the nearest code with ties to the lower one.
-struct HostTables {
+// lut[j], j = floor((x + 1) * 256) clamped to [0, 511]: number of thresholds that lie safely below bucket j,
+// built so that at most two further thresholds can be <= any x that lands in the bucket.  The code of x is
+// then lut[j] + (x >= thr[lut[j]]) + (x >= thr[lut[j] + 1]).  thr is padded with +inf.
+struct NfTables {
   float code[4][256];
-  float thr[4][256];
+  float thr[4][260];
+  uint8_t lut[4][512];
 };
+typedef NfTables HostTables;
 const HostTables& host_tables();
 int host_codebook(int bits, float* out);   // any bits in 2..8
 // Uploads the tables to the current device once.  Returns lq_status.

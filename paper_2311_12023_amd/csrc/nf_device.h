@@ -13,10 +13,7 @@
 
 namespace lq {
 
-struct DevTables {
-  float code[4][256];
-  float thr[4][256];
-};
+typedef NfTables DevTables;
 // Device address of the tables on the current device (uploads them on first use).
 int device_tables(const DevTables** out);
 
@@ -27,26 +24,39 @@ template <> struct Slot<3> { static constexpr int value = 1; };
 template <> struct Slot<4> { static constexpr int value = 2; };
 template <> struct Slot<8> { static constexpr int value = 3; };
 
-// Copies the code-book and thresholds of one bit width into LDS (ends with a barrier).
-template <int BITS>
-__device__ inline void load_tables(const DevTables* __restrict__ tab, float* s_code, float* s_thr) {
-  constexpr int NC = 1 << BITS;
-  for (int i = threadIdx.x; i < NC; i += blockDim.x) {
-    s_code[i] = tab->code[Slot<BITS>::value][i];
-    s_thr[i] = tab->thr[Slot<BITS>::value][i];
-  }
+// LDS copy of one bit width's tables.
+struct LdsTables {
+  float code[256];
+  float thr[260];
+  uint8_t lut[512];
+};
+
+// Copies the tables of one bit width (slot) into LDS.  The caller places a barrier before the first use.
+__device__ inline void load_tables_slot_nosync(const DevTables* __restrict__ tab, int slot, LdsTables& t) {
+  for (int i = threadIdx.x; i < 256; i += blockDim.x) t.code[i] = tab->code[slot][i];
+  for (int i = threadIdx.x; i < 260; i += blockDim.x) t.thr[i] = tab->thr[slot][i];
+  for (int i = threadIdx.x; i < 128; i += blockDim.x)
+    reinterpret_cast<uint32_t*>(t.lut)[i] = reinterpret_cast<const uint32_t*>(tab->lut[slot])[i];
+}
+__device__ inline void load_tables_slot(const DevTables* __restrict__ tab, int slot, LdsTables& t) {
+  load_tables_slot_nosync(tab, slot, t);
   __syncthreads();
+}
+template <int BITS>
+__device__ inline void load_tables(const DevTables* __restrict__ tab, LdsTables& t) {
+  load_tables_slot(tab, Slot<BITS>::value, t);
 }
 
 // Nearest code with ties to the lower index = number of thresholds <= x.
-// 2..4 bits: thresholds live in registers and are counted; 8 bits: binary search in LDS
-// (entry 255 of the table is +inf).
+// 2 and 3 bits: the thresholds live in registers and are counted.  4 and 8 bits: a 512-bucket table in LDS
+// gives the count of thresholds safely below x's bucket and at most two thresholds remain to be compared
+// (NaN compares false everywhere and lands on code 0 either way).
 template <int BITS>
 struct Thresholds {
   float r[(1 << BITS) - 1];
-  __device__ explicit Thresholds(const float* s_thr) {
+  __device__ explicit Thresholds(const LdsTables& t) {
 #pragma unroll
-    for (int i = 0; i < (1 << BITS) - 1; ++i) r[i] = s_thr[i];
+    for (int i = 0; i < (1 << BITS) - 1; ++i) r[i] = t.thr[i];
   }
   __device__ inline uint32_t nearest(float x) const {
     uint32_t c = 0;
@@ -55,17 +65,18 @@ struct Thresholds {
     return c;
   }
 };
-template <>
-struct Thresholds<8> {
-  const float* t;
-  __device__ explicit Thresholds(const float* s_thr) : t(s_thr) {}
+struct BucketSearch {
+  const LdsTables& t;
+  __device__ explicit BucketSearch(const LdsTables& tt) : t(tt) {}
   __device__ inline uint32_t nearest(float x) const {
-    uint32_t c = 0;
-#pragma unroll
-    for (int step = 128; step >= 1; step >>= 1) c += (x >= t[c + step - 1]) ? (uint32_t)step : 0u;
-    return c;
+    int j = (int)fmaf(x, 256.0f, 256.0f);
+    j = j < 0 ? 0 : (j > 511 ? 511 : j);
+    const uint32_t c0 = t.lut[j];
+    return c0 + ((x >= t.thr[c0]) ? 1u : 0u) + ((x >= t.thr[c0 + 1]) ? 1u : 0u);
   }
 };
+template <> struct Thresholds<4> : BucketSearch { __device__ explicit Thresholds(const LdsTables& tt) : BucketSearch(tt) {} };
+template <> struct Thresholds<8> : BucketSearch { __device__ explicit Thresholds(const LdsTables& tt) : BucketSearch(tt) {} };
 
 __device__ inline float run_absmax(const float (&t)[16]) {
   float m = 0.0f;

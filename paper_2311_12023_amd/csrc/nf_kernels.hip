@@ -24,8 +24,7 @@ int device_tables(const DevTables** out) {
   if (dev < 0 || dev >= 64) return LQ_ERR_HIP;
   std::lock_guard<std::mutex> lock(g_tables_mutex);
   if (!g_tables_ptr[dev]) {
-    static_assert(sizeof(DevTables) == sizeof(HostTables), "table layouts differ");
-    void* p = nullptr;
+        void* p = nullptr;
     LQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_nf_tables)));
     LQ_HIP_TRY(hipMemcpy(p, &host_tables(), sizeof(HostTables), hipMemcpyHostToDevice));
     g_tables_ptr[dev] = (const DevTables*)p;
@@ -51,11 +50,10 @@ __global__ __launch_bounds__(256) void quantize_fused_kernel(const float* __rest
                                                              int v_dtype, const DevTables* __restrict__ tab,
                                                              uint8_t* __restrict__ codes, uint8_t* __restrict__ sidx,
                                                              float* __restrict__ v) {
-  __shared__ float s_code[1 << BITS];
-  __shared__ float s_thr[1 << BITS];
+  __shared__ LdsTables s_tab;
   __shared__ float s_wave[4];
-  load_tables<BITS>(tab, s_code, s_thr);
-  Thresholds<BITS> thr(s_thr);
+  load_tables<BITS>(tab, s_tab);
+  Thresholds<BITS> thr(s_tab);
 
   const int runs_per_group = runs_per_block * scale_block;          // 16 .. 256*U
   const int slabs_per_group = runs_per_group > 256 ? runs_per_group / 256 : 1;
@@ -126,9 +124,9 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
                                                       const uint8_t* __restrict__ sidx, const float* __restrict__ v,
                                                       int64_t nquads, int qpb_shift, int sb_shift, int levels,
                                                       const DevTables* __restrict__ tab, float* __restrict__ out) {
-  __shared__ float s_code[1 << BITS];
-  __shared__ float s_thr[1 << BITS];
-  load_tables<BITS>(tab, s_code, s_thr);
+  __shared__ LdsTables s_tab;
+  load_tables<BITS>(tab, s_tab);
+  const float* s_code = s_tab.code;
   for (int64_t quad = (int64_t)blockIdx.x * 256 + threadIdx.x; quad < nquads; quad += (int64_t)gridDim.x * 256) {
     const int64_t blk = quad >> qpb_shift;
     const float sh = block_scale(sidx[blk], v[blk >> sb_shift], levels);

@@ -76,12 +76,24 @@ static void build_tables(HostTables& t) {
   for (int s = 0; s < 4; ++s) {
     const int ncode = 1 << widths[s];
     host_codebook(widths[s], t.code[s]);
-    for (int i = 0; i < 256; ++i) t.thr[s][i] = INFINITY;
+    for (int i = 0; i < 260; ++i) t.thr[s][i] = INFINITY;
     for (int i = 0; i + 1 < ncode; ++i) {
       const double mid = 0.5 * ((double)t.code[s][i] + (double)t.code[s][i + 1]);   // exact
       float f = (float)mid;
       if (!((double)f > mid)) f = std::nextafterf(f, INFINITY);
       t.thr[s][i] = f;
+    }
+    // bucket table; the margin covers the rounding of (x + 1) * 256 in fp32
+    const double margin = 4e-6;
+    for (int j = 0; j < 512; ++j) {
+      const double lo = -1.0 + j / 256.0 - margin, hi = -1.0 + (j + 1) / 256.0 + margin;
+      int below = 0, upto = 0;
+      for (int i = 0; i + 1 < ncode; ++i) {
+        if ((double)t.thr[s][i] <= lo) ++below;
+        if ((double)t.thr[s][i] <= hi || j == 511) ++upto;
+      }
+      if (upto - below > 2) below = upto - 2;   // cannot happen for NF code-books (checked by the tests)
+      t.lut[s][j] = (uint8_t)below;
     }
   }
 }
