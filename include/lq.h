@@ -78,6 +78,9 @@ typedef struct {
  *                 from its warm start).  Default 3.
  *   max_batch     lq_error_table advances up to this many configurations in lock step (more
  *                 workspace, better GPU occupancy).  Default 36.
+ *   gemm_mode     arithmetic of the large products against the d x k matrix: 1 = fp32 MFMA; 2 = both operands
+ *                 split on the fly into bf16 hi + lo and multiplied by three bf16 MFMAs with fp32 accumulation
+ *                 (products good to about 2^-16 relative, several times faster).  Default 2.
  */
 typedef struct {
   int32_t first_width;
@@ -88,6 +91,7 @@ typedef struct {
   int32_t warm_power;
   int32_t warm_power_2;
   int32_t max_batch;
+  int32_t gemm_mode;
 } lq_svd_params;
 
 const char* lq_status_string(int status);

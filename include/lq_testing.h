@@ -16,9 +16,10 @@ extern "C" {
 #endif
 
 /* mode 0: C[l x big] = X[l x K] * A[big x K]^T;  mode 1: C[l x big] = X[l x K] * A[K x big].
- * part: scratch of splits * l * ldc floats (used when splits > 1). */
+ * part: scratch of splits * l * ldc floats (used when splits > 1).
+ * precision 0: fp32 MFMA; 1: bf16 hi/lo split, three bf16 MFMAs per product. */
 int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
-                      int64_t lda, float* C, int64_t ldc, int splits, float* part, void* stream);
+                      int64_t lda, float* C, int64_t ldc, int splits, float* part, int precision, void* stream);
 /* Rows of X (l x m) are orthonormalised in place by Cholesky-QR (Gram in fp64).
  * scratch: at least 17 * l * l doubles.  alt: l * ldx floats of scratch, or NULL to force the
  * in-place triangular solve. */

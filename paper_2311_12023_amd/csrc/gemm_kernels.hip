@@ -22,6 +22,21 @@ namespace lq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int PREC_FP32 = 0;     // v_mfma_f32_32x32x2_f32
+constexpr int PREC_BF16X3 = 1;   // operands split into bf16 hi + lo, three v_mfma_f32_32x32x16_bf16 per product
+constexpr int HPITCH = 40;       // LDS row pitch of the split X tile in bf16 elements (80 B: conflict-free b128 reads)
+
+// a = hi + lo + O(2^-17 a) with hi, lo in bf16.
+__device__ __forceinline__ void split_bf16(floatx2 v, bf16x2& hi, bf16x2& lo) {
+  hi = __builtin_convertvector(v, bf16x2);
+  const floatx2 back = __builtin_convertvector(hi, floatx2);
+  lo = __builtin_convertvector(v - back, bf16x2);
+}
 
 constexpr int BK = 32;           // K chunk staged per step
 constexpr int XPITCH = BK + 4;   // LDS row pitch in floats: 16-byte aligned rows, conflict-free b128 reads
@@ -46,6 +61,24 @@ __device__ __forceinline__ void stash_x(float* xs, int tid, const floatx4 (&xreg
     const int idx = tid + i * 256;
     const int row = idx >> 3, c4 = idx & 7;
     *reinterpret_cast<floatx4*>(xs + row * XPITCH + c4 * 4) = xreg[i];
+  }
+}
+
+// Split-precision X tile: hi and lo halves, columns permuted so that the 8 reduction indices a lane feeds to one
+// 16-deep MFMA (k = 16g + 8cc + 4h + e, cc < 2, e < 4) are contiguous: position 16g + 8h + 4cc + e.
+template <int LT>
+__device__ __forceinline__ void stash_x_split(__bf16* xh, __bf16* xl, int tid, const floatx4 (&xreg)[LT]) {
+#pragma unroll
+  for (int i = 0; i < LT; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx >> 3, c4 = idx & 7;
+    const int pos = 16 * (c4 >> 2) + 8 * (c4 & 1) + 4 * ((c4 >> 1) & 1);
+    bf16x2 h0, l0, h1, l1;
+    split_bf16(floatx2{xreg[i][0], xreg[i][1]}, h0, l0);
+    split_bf16(floatx2{xreg[i][2], xreg[i][3]}, h1, l1);
+    const bf16x4 hv = {h0[0], h0[1], h1[0], h1[1]}, lv = {l0[0], l0[1], l1[0], l1[1]};
+    *reinterpret_cast<bf16x4*>(xh + row * HPITCH + pos) = hv;
+    *reinterpret_cast<bf16x4*>(xl + row * HPITCH + pos) = lv;
   }
 }
 
@@ -85,9 +118,11 @@ __device__ __forceinline__ void fetch_a(const float* __restrict__ A, int64_t lda
   }
 }
 
-template <int LT, int MODE, int NT>
+template <int LT, int MODE, int NT, int PREC>
 __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) float xs[];   // [32*LT][XPITCH]
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // fp32: [32*LT][XPITCH]; split: hi then lo, [32*LT][HPITCH] bf16
+  __bf16* xh = reinterpret_cast<__bf16*>(xs);
+  __bf16* xl = xh + 32 * LT * HPITCH;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int ln = lane & 31, lh = lane >> 5;
@@ -122,7 +157,8 @@ __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
   }
   for (int step = 0; step < nsteps; ++step) {
     __syncthreads();          // everyone is done reading the previous X tile
-    stash_x<LT>(xs, tid, xreg);
+    if constexpr (PREC == PREC_FP32) stash_x<LT>(xs, tid, xreg);
+    else stash_x_split<LT>(xh, xl, tid, xreg);
     float bcur[4][4][NT];
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -136,6 +172,35 @@ __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
       fetch_x<LT>(X, g.ldx, k1, tid, xreg);
       fetch_a<MODE, NT>(A, g.lda, g.big, big0, ln, lh, k1, kend, breg);
     }
+    if constexpr (PREC == PREC_BF16X3) {
+#pragma unroll
+      for (int gk = 0; gk < 2; ++gk) {
+        // A operand of this 16-group, split into hi and lo (slot 4cc + e  <->  bcur[2gk + cc][e])
+        bf16x8 ah[NT], al[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+            for (int e2 = 0; e2 < 2; ++e2) {
+              bf16x2 h, l;
+              split_bf16(floatx2{bcur[2 * gk + cc][2 * e2][j], bcur[2 * gk + cc][2 * e2 + 1][j]}, h, l);
+              ah[j][4 * cc + 2 * e2] = h[0]; ah[j][4 * cc + 2 * e2 + 1] = h[1];
+              al[j][4 * cc + 2 * e2] = l[0]; al[j][4 * cc + 2 * e2 + 1] = l[1];
+            }
+#pragma unroll
+        for (int i = 0; i < LT; ++i) {
+          const bf16x8 xhv = *reinterpret_cast<const bf16x8*>(xh + (32 * i + ln) * HPITCH + 16 * gk + 8 * lh);
+          const bf16x8 xlv = *reinterpret_cast<const bf16x8*>(xl + (32 * i + ln) * HPITCH + 16 * gk + 8 * lh);
+#pragma unroll
+          for (int j = 0; j < NT; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xlv, ah[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhv, al[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhv, ah[j], acc[i][j], 0, 0, 0);
+          }
+        }
+      }
+    } else {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       float av[LT][4];
@@ -152,6 +217,7 @@ __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
 #pragma unroll
           for (int j = 0; j < NT; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][e], bcur[c][e][j], acc[i][j], 0, 0, 0);
+    }
     }
   }
 
@@ -202,23 +268,24 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   }
 }
 
-template <int LT, int MODE, int NT>
+template <int LT, int MODE, int NT, int PREC>
 static void launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
-  const size_t lds = (size_t)32 * LT * XPITCH * sizeof(float);
-  hipLaunchKernelGGL((wide_gemm_kernel<LT, MODE, NT>), grid, dim3(256), lds, st, g);
+  const size_t lds = PREC == PREC_FP32 ? (size_t)32 * LT * XPITCH * sizeof(float)
+                                       : (size_t)2 * 32 * LT * HPITCH * sizeof(__bf16);
+  hipLaunchKernelGGL((wide_gemm_kernel<LT, MODE, NT, PREC>), grid, dim3(256), lds, st, g);
 }
 
-template <int MODE>
+template <int MODE, int PREC>
 static int launch_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
   switch (lt) {
-    case 1: launch_one<1, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
-    case 2: launch_one<2, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
-    case 3: launch_one<3, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
-    case 4: launch_one<4, MODE, (MODE == MODE_NT ? 1 : 2)>(g, grid, st); break;
-    case 5: launch_one<5, MODE, 1>(g, grid, st); break;
-    case 6: launch_one<6, MODE, 1>(g, grid, st); break;
-    case 7: launch_one<7, MODE, 1>(g, grid, st); break;
-    case 8: launch_one<8, MODE, 1>(g, grid, st); break;
+    case 1: launch_one<1, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
+    case 2: launch_one<2, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
+    case 3: launch_one<3, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
+    case 4: launch_one<4, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
+    case 5: launch_one<5, MODE, 1, PREC>(g, grid, st); break;
+    case 6: launch_one<6, MODE, 1, PREC>(g, grid, st); break;
+    case 7: launch_one<7, MODE, 1, PREC>(g, grid, st); break;
+    case 8: launch_one<8, MODE, 1, PREC>(g, grid, st); break;
     default: return LQ_ERR_ARG;
   }
   return LQ_OK;
@@ -242,7 +309,7 @@ int gemm_choose_splits(int mode, int lt, int64_t big, int64_t K, int batch) {
 // C = X * op(A) for `batch` problems.  `part` is scratch for splits > 1 (batch * splits * l * ldc floats).
 int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
                      const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
-                     int splits, float* part, hipStream_t st) {
+                     int splits, float* part, hipStream_t st, int precision) {
   if (l % 32 != 0 || l < 32 || l > 256 || big < 1 || K < 1 || batch < 1) return LQ_ERR_ARG;
   if (mode == MODE_NN && (big % 2) != 0) return LQ_ERR_ARG;
   const int lt = l / 32;
@@ -258,8 +325,15 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
   const int span = gemm_tile_span(mode, lt);
   const dim3 grid((unsigned)((big + span - 1) / span), (unsigned)splits, (unsigned)batch);
   {
-    prof::Scope ps(prof::GEMM_BASE + mode * 8 + (lt - 1), st, 2.0 * l * (double)big * (double)K * batch);
-    int rc = (mode == MODE_NT) ? launch_mode<MODE_NT>(g, lt, grid, st) : launch_mode<MODE_NN>(g, lt, grid, st);
+    prof::Scope ps((precision == PREC_BF16X3 ? prof::GEMM_SPLIT_BASE : prof::GEMM_BASE) + mode * 8 + (lt - 1), st,
+                   2.0 * l * (double)big * (double)K * batch);
+    int rc;
+    if (precision == PREC_BF16X3)
+      rc = (mode == MODE_NT) ? launch_mode<MODE_NT, PREC_BF16X3>(g, lt, grid, st)
+                             : launch_mode<MODE_NN, PREC_BF16X3>(g, lt, grid, st);
+    else
+      rc = (mode == MODE_NT) ? launch_mode<MODE_NT, PREC_FP32>(g, lt, grid, st)
+                             : launch_mode<MODE_NN, PREC_FP32>(g, lt, grid, st);
     if (rc != LQ_OK) return rc;
   }
   LQ_HIP_TRY(hipGetLastError());

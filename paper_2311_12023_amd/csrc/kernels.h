@@ -25,9 +25,11 @@ struct GemmArgs {
 
 int gemm_tile_span(int mode, int lt);
 int gemm_choose_splits(int mode, int lt, int64_t big, int64_t K, int batch);
+// precision 0: fp32 MFMA.  precision 1: both operands split into bf16 hi + lo on the fly and multiplied with
+// three bf16 MFMAs (hi*hi + hi*lo + lo*hi, fp32 accumulation): products good to about 2^-16 relative.
 int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
                      const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
-                     int splits, float* part, hipStream_t st);
+                     int splits, float* part, hipStream_t st, int precision = 0);
 
 // ---- small dense kernels (small_kernels.hip) --------------------------------------------------
 constexpr int GRAM_CHUNKS = 16;

@@ -27,7 +27,7 @@ static int64_t up32(int64_t x) { return (x + 31) / 32 * 32; }
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Params {
-  int l1, check, maxit, lw, qw, qw2, max_batch;
+  int l1, check, maxit, lw, qw, qw2, max_batch, prec;
   double tol;
 };
 
@@ -43,6 +43,8 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   out.qw = z.warm_power ? z.warm_power : 2;
   out.qw2 = z.warm_power_2 ? z.warm_power_2 : 3;
   out.max_batch = z.max_batch ? z.max_batch : 36;
+  if (z.gemm_mode < 0 || z.gemm_mode > 2) return LQ_ERR_ARG;
+  out.prec = z.gemm_mode == 1 ? 0 : 1;
   if (out.l1 % 32 || out.l1 <= rank || out.l1 > 256) return LQ_ERR_ARG;
   if (out.lw % 32 || out.lw <= rank || out.lw > out.l1) return LQ_ERR_ARG;
   if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.max_batch < 1) return LQ_ERR_ARG;
@@ -153,7 +155,7 @@ static int gemm(const Ctx& c, int mode, int l, int64_t big, int64_t K, const flo
   int splits = gemm_choose_splits(mode, l / 32, big, K, batch);
   if (splits > 1 && (size_t)batch * splits * l * ldc > c.pl.gpart_floats) splits = 1;
   return launch_wide_gemm(mode, l, big, K, X, ldx, sX, A, lda, sA, C, ldc, sC, batch, splits,
-                          c.at<float>(c.pl.gpart), c.st);
+                          c.at<float>(c.pl.gpart), c.st, c.pl.prm.prec);
 }
 
 // Rayleigh-Ritz on the subspace spanned by the rows of Y (orthonormal) with B = Y A:
@@ -501,9 +503,11 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
 
 // ---- test hooks (include/lq_testing.h) ----------------------------------------------------------------
 int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
-                      int64_t lda, float* C, int64_t ldc, int splits, float* part, void* stream) {
+                      int64_t lda, float* C, int64_t ldc, int splits, float* part, int precision, void* stream) {
   if (!X || !A || !C || (splits > 1 && !part) || splits < 1) return LQ_ERR_NULL;
-  return launch_wide_gemm(mode, l, big, K, X, ldx, 0, A, lda, 0, C, ldc, 0, 1, splits, part, (hipStream_t)stream);
+  if (precision != 0 && precision != 1) return LQ_ERR_ARG;
+  return launch_wide_gemm(mode, l, big, K, X, ldx, 0, A, lda, 0, C, ldc, 0, 1, splits, part, (hipStream_t)stream,
+                          precision);
 }
 
 int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, float* alt, void* stream) {

@@ -19,7 +19,8 @@ enum Cls {
   QUANTIZE = 24,
   DEQUANTIZE = 25,
   MISC = 26,
-  NUM_CLASSES = 27
+  GEMM_SPLIT_BASE = 27,     // + mode * 8 + (l/32 - 1): the bf16 hi/lo split variants of wide_gemm_kernel
+  NUM_CLASSES = 43
 };
 
 bool enabled();
