@@ -68,8 +68,8 @@ typedef struct {
  *   first_width   sketch width l1 of the cold start (first LQ iteration, Q = 0); multiple of 32,
  *                 rank < l1 <= 256.  Default: round_up32(max(2*rank, rank + 56)).
  *   first_tol     the cold start runs subspace iterations until the top-`rank` Ritz values change
- *                 by less than this relative amount between two checks.  Default 1e-6.
- *   first_check   subspace iterations between two checks.  Default 8.
+ *                 by less than this relative amount (estimated from the observed geometric decay).  Default 2e-6.
+ *   first_check   smallest number of subspace iterations between two Rayleigh-Ritz checks.  Default 8.
  *   first_max     cap on cold-start subspace iterations.  Default 600.
  *   warm_width    subspace width l of later LQ iterations, warm-started from the previous one;
  *                 multiple of 32, rank < l <= first_width.  Default round_up32(rank + max(rank/2, 24)).

@@ -60,6 +60,8 @@ int launch_jacobi_fast(const double* G, int l, float* Ut, double* lambda, int ba
 // lam[z][i] = squared norm of row i of the wide matrix X[z] (l x m), fp64.
 int launch_row_sumsq(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, double* lam, int batch,
                      hipStream_t st);
+// X <- X - alpha * Y, both `count` floats (multiple of 4).
+int launch_axpy_sub(float* X, const float* Y, float alpha, int64_t count, hipStream_t st);
 // Fills a wide matrix (l x m, padded ld) with N(0,1) draws from a counter-based generator; pads are zeroed.
 int launch_gaussian_fill(float* X, int l, int64_t m, int64_t ldx, uint64_t seed, hipStream_t st);
 // out[i][j] = sr[i] * A[i][j] * sc[j]  (sr = sqrt(row_w), sc = sqrt(col_w): D_row A D_col of Eq. 5).

@@ -8,6 +8,8 @@
 // `rank` rows give L1 L2 = Y_r^T B_r, and the first `warm_width` rows seed the next iteration.
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -36,7 +38,7 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   std::memset(&z, 0, sizeof(z));
   if (p) z = *p;
   out.l1 = z.first_width ? z.first_width : (int)std::min<int64_t>(256, up32(std::max(2 * rank, rank + 56)));
-  out.tol = z.first_tol > 0 ? z.first_tol : 1e-6;
+  out.tol = z.first_tol > 0 ? z.first_tol : 2e-6;
   out.check = z.first_check ? z.first_check : 8;
   out.maxit = z.first_max ? z.first_max : 600;
   out.lw = z.warm_width ? z.warm_width : (int)std::min<int64_t>(out.l1, up32(rank + std::max(rank / 2, 24)));
@@ -179,6 +181,12 @@ static int ritz_rotate(const Ctx& c, int l, const float* Y, float* Y2, size_t sY
 }
 
 // Cold-start randomized SVD of A (d x k): on return *Yout / *Bout (l1 rows, Ritz order) and lam_cold.
+//
+// Subspace iteration on the shifted operator A A^T - alpha I, alpha = half the smallest Ritz value of the block:
+// same invariant subspaces, but the contraction factor per iteration improves from (s_{l+1}/s_r)^2 to
+// (s_{l+1}^2 - alpha)/(s_r^2 - alpha), about twice as fast on the flat spectra of weight matrices.  Convergence is
+// judged on the top-`rank` Ritz values; the Rayleigh-Ritz steps are scheduled from the observed rate instead
+// of at a fixed period, since each one costs an l x l eigen-solve.
 static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const float** Yout, const float** Bout) {
   const Plan& pl = c.pl;
   const int l = pl.prm.l1, r = pl.rank;
@@ -191,25 +199,54 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
   LQ_TRY(launch_gaussian_fill(Ba, l, pl.k, pl.ldk, seed, c.st));
   LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Ya, pl.ldd, 0, 1));
   LQ_TRY(orthonormalize(c, Ya, Yb, l, pl.d, pl.ldd, 0, 1));
-  std::vector<double> prev(r, 0.0), cur(r, 0.0);
+  std::vector<double> prev(r, 0.0), cur(l, 0.0);
   bool have_prev = false;
+  double alpha = 0.0;
+  double last_delta = -1.0;   // change of the Ritz values over the previous gap (valid when rate_ok)
+  double kappa = 0.0;         // observed decay rate of the error per iteration (natural log), 0 = unknown
+  int next_check = pl.prm.check, last_check = 0, last_gap = 0;
+  bool rate_ok = false;       // last_delta was measured with the current shift
   for (int it = 1; it <= pl.prm.maxit; ++it) {
     LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, Ya, pl.ldd, 0, A, pl.k, 0, Ba, pl.ldk, 0, 1));
-    if (it % pl.prm.check == 0 || it == pl.prm.maxit) {
+    if (it >= next_check || it == pl.prm.maxit) {
       LQ_TRY(ritz_rotate(c, l, Ya, Yb, 0, Ba, Bb, 0, lam, 1));
       std::swap(Ya, Yb); std::swap(Ba, Bb);
-      LQ_HIP_TRY(hipMemcpyAsync(cur.data(), lam, sizeof(double) * r, hipMemcpyDeviceToHost, c.st));
+      LQ_HIP_TRY(hipMemcpyAsync(cur.data(), lam, sizeof(double) * l, hipMemcpyDeviceToHost, c.st));
       LQ_HIP_TRY(hipStreamSynchronize(c.st));
-      bool done = have_prev;
-      for (int j = 0; j < r && done; ++j) {
+      double delta = 0.0;
+      for (int j = 0; j < r; ++j) {
         const double a = std::sqrt(cur[j]), b = std::sqrt(prev[j]);
-        if (!(std::fabs(a - b) <= pl.prm.tol * a)) done = false;
+        const double rel = a > 0 ? std::fabs(a - b) / a : 0.0;
+        if (!(rel <= delta)) delta = rel;      // NaN-safe maximum
       }
-      prev = cur; have_prev = true;
+      const int gap = it - last_check;
+      // The error decays geometrically, err(it) ~ exp(-kappa it), so the change over a gap is
+      // err(it) (exp(kappa gap) - 1).  kappa comes from two successive equal-shift gaps, derated by 0.7.
+      if (have_prev && rate_ok && last_delta > 0 && delta > 0 && delta < last_delta && gap == last_gap)
+        kappa = 0.7 * std::log(last_delta / delta) / gap;
+      double err_est = delta;
+      if (kappa > 0) err_est = std::min(delta, delta / std::expm1(kappa * gap));
+      if (getenv("LQ_TRACE")) fprintf(stderr, "[cold] it=%d delta=%.3e err_est=%.3e kappa=%.3f alpha=%.4g lamr=%.8g laml=%.6g\n", it, delta, err_est, kappa, alpha, cur[r - 1], cur[l - 1]);
+      const bool done = have_prev && err_est <= pl.prm.tol;
       if (done || it == pl.prm.maxit) break;
+      // next Rayleigh-Ritz where the error is predicted to reach the tolerance
+      int next_gap = pl.prm.check;
+      if (kappa > 0 && have_prev) {
+        const double need = std::log(err_est / pl.prm.tol) / kappa;
+        next_gap = (int)std::min<double>(std::max<double>(std::ceil(need), pl.prm.check), 8.0 * pl.prm.check);
+      }
+      rate_ok = have_prev;
+      last_delta = delta; last_gap = gap; last_check = it; next_check = it + next_gap;
+      for (int j = 0; j < r; ++j) prev[j] = cur[j];
+      have_prev = true;
+      const double new_alpha = 0.5 * cur[l - 1];
+      if (new_alpha > 1.25 * alpha && !getenv("LQ_NOSHIFT")) { alpha = new_alpha; rate_ok = false; kappa = 0.0; next_check = it + pl.prm.check; }
     }
-    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Ya, pl.ldd, 0, 1));
-    LQ_TRY(orthonormalize(c, Ya, Yb, l, pl.d, pl.ldd, 0, 1));
+    // Y <- orth((A A^T - alpha I) Y)
+    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Yb, pl.ldd, 0, 1));
+    if (alpha > 0.0) LQ_TRY(launch_axpy_sub(Yb, Ya, (float)alpha, (int64_t)l * pl.ldd, c.st));
+    LQ_TRY(orthonormalize(c, Yb, Ya, l, pl.d, pl.ldd, 0, 1));
+    std::swap(Ya, Yb);
   }
   *Yout = Ya; *Bout = Ba;
   return LQ_OK;

@@ -220,13 +220,17 @@ __global__ __launch_bounds__(1024) void cholinv_kernel(const double* __restrict_
         ck[e] = k > j ? colbuf[buf][k] * inv : 0.0;      // c_kj for this thread's columns
         tr[e] = k <= j ? rowbuf[buf][k] * inv : 0.0;     // scaled row j of the inverse
       }
+      // only row blocks that reach below row j change; the matrix part needs columns > j, the inverse part
+      // columns <= j (uniform conditions: whole 32-wide blocks are skipped)
 #pragma unroll
-      for (int ei = 0; ei < NB; ++ei)
+      for (int ei = 0; ei < NB; ++ei) {
+        if (32 * ei + 31 <= j) continue;
 #pragma unroll
         for (int ek = 0; ek < NB; ++ek) {
-          a[ei][ek] = fma(-ci[ei], ck[ek], a[ei][ek]);
-          t[ei][ek] = fma(-ci[ei], tr[ek], t[ei][ek]);
+          if (32 * ek + 31 > j) a[ei][ek] = fma(-ci[ei], ck[ek], a[ei][ek]);
+          if (32 * ek <= j) t[ei][ek] = fma(-ci[ei], tr[ek], t[ei][ek]);
         }
+      }
       if (ty == jt) {
 #pragma unroll
         for (int ek = 0; ek < NB; ++ek) t[jb][ek] = tr[ek];
@@ -294,8 +298,13 @@ int launch_trsm(const double* Cfac, int l, float* X, int64_t m, int64_t ldx, siz
 constexpr int JT = 512;
 
 __device__ inline void rr_pair(int a, int round, int n, int& p, int& q) {
+  // circle method: round < n-1, a < n/2, so both sums stay below 2(n-1) and one conditional subtraction
+  // replaces the modulo
   if (a == 0) { p = n - 1; q = round; }
-  else { p = (round + a) % (n - 1); q = (round - a + (n - 1)) % (n - 1); }
+  else {
+    p = round + a; if (p >= n - 1) p -= n - 1;
+    q = round - a + (n - 1); if (q >= n - 1) q -= n - 1;
+  }
   if (p > q) { const int t = p; p = q; q = t; }
 }
 
@@ -436,13 +445,16 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
       for (int off = 1; off < 16; off <<= 1) {
         al += __shfl_xor(al, off); be += __shfl_xor(be, off); ga += __shfl_xor(ga, off);
       }
-      const float lim = sqrtf(al * be);
-      if (ga != 0.0f && fabsf(ga) > 2e-6f * lim) {
+      // hardware reciprocal / square-root approximations (1 ulp) are enough here: a rotation that is orthogonal
+      // to 1e-7 and an angle that misses the exact one by 1e-7 change nothing in the convergence, and the
+      // eigenvector rows are renormalised at the end
+      const float ab = al * be;
+      if (ga != 0.0f && ga * ga > 4e-12f * ab) {
         rotated = true;
-        worst = fmaxf(worst, fabsf(ga) / lim);
-        const float zeta = (be - al) / (2.0f * ga);
-        const float tt = (zeta >= 0.f ? 1.0f : -1.0f) / (fabsf(zeta) + sqrtf(1.0f + zeta * zeta));
-        const float cs = 1.0f / sqrtf(1.0f + tt * tt), sn = cs * tt;
+        worst = fmaxf(worst, fabsf(ga) * __builtin_amdgcn_rsqf(ab));
+        const float zeta = (be - al) * 0.5f * __builtin_amdgcn_rcpf(ga);
+        const float tt = copysignf(__builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.0f + zeta * zeta)), zeta);
+        const float cs = __builtin_amdgcn_rsqf(1.0f + tt * tt), sn = cs * tt;
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
           X[p * P + sub + 16 * e] = cs * xp[e] - sn * xq[e];
@@ -455,10 +467,10 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
       __syncthreads();
     }
     if (rotated) { s_rot = 1; }
-    if (worst > 1e-3f) s_big = 1.0f;           // benign race: every writer stores the same value
+    if (worst > 1e-4f) s_big = 1.0f;           // benign race: every writer stores the same value
     __syncthreads();
     const bool more = s_rot != 0 && s_big != 0.0f;   // quadratic convergence: a sweep whose worst pair was
-    __syncthreads();                                 // below 1e-3 leaves nothing above ~1e-6 behind
+    __syncthreads();                                 // below 1e-4 leaves nothing above ~1e-7 behind
     if (!more) break;
   }
   // eigenvalue estimates = column norms; rank them (descending) and emit eigenvectors as rows
@@ -586,6 +598,26 @@ __global__ __launch_bounds__(256) void gaussian_fill_kernel(float* __restrict__ 
     }
     X[idx] = val;
   }
+}
+
+// X <- X - alpha * Y over `count` floats (count a multiple of 4).
+__global__ __launch_bounds__(256) void axpy_sub_kernel(float* __restrict__ X, const float* __restrict__ Y, float alpha,
+                                                       int64_t count4) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += (int64_t)gridDim.x * 256) {
+    float4 x = reinterpret_cast<float4*>(X)[i];
+    const float4 y = reinterpret_cast<const float4*>(Y)[i];
+    x.x = fmaf(-alpha, y.x, x.x); x.y = fmaf(-alpha, y.y, x.y); x.z = fmaf(-alpha, y.z, x.z); x.w = fmaf(-alpha, y.w, x.w);
+    reinterpret_cast<float4*>(X)[i] = x;
+  }
+}
+
+int launch_axpy_sub(float* X, const float* Y, float alpha, int64_t count, hipStream_t st) {
+  const int64_t count4 = count / 4;
+  const int64_t want = (count4 + 255) / 256;
+  prof::Scope ps(prof::MISC, st, (double)count * 12.0);
+  hipLaunchKernelGGL(axpy_sub_kernel, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, st, X, Y, alpha, count4);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
 }
 
 int launch_gaussian_fill(float* X, int l, int64_t m, int64_t ldx, uint64_t seed, hipStream_t st) {
