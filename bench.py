@@ -45,6 +45,29 @@ def cpu_baseline(first_matrix: np.ndarray) -> dict:
                       "4^3 = 64 times as much."}
 
 
+def roofline_of(name: str, ms: float, launches: int, work: float) -> dict:
+    """Roofline entry for one kernel class from its summed HIP-event time and algorithmic work."""
+    sec = ms * 1e-3
+    common = {"kernel": name, "traffic": None, "launches": launches, "avg_us": 1e3 * ms / launches}
+    if name.startswith("wide_gemm_kernel"):
+        lt, _, _, prec = (int(t) for t in name[name.index("<") + 1:name.index(">")].split(","))
+        if prec == 0:      # fp32 MFMA: work is flops
+            ach = work / sec / 1e12
+            return {**common, "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_FP32_MFMA_TFLOPS}
+        # split-bf16 mode: three bf16 MFMAs per product leave the kernel bound by streaming A (4 B per element,
+        # 2*l flop per element)
+        ach = work / (2.0 * 32 * lt) * 4.0 / sec / 1e9
+        return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                "algorithmic_tflops": work / sec / 1e12}
+    if name.startswith("lowrank_blockquant"):   # (2r + 10) flop per weight, ALU + MFMA; W is read from HBM once per batch
+        ach = work / sec / 1e12
+        return {**common, "bound": "alu", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_FP32_MFMA_TFLOPS}
+    ach = work / sec / 1e9
+    return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +75,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--matrices", type=int, default=7, help="use only the first N matrices of the layer (debugging)")
+    ap.add_argument("--streams", type=int, default=0, help="lq_svd_params.streams (0 = library default)")
+    ap.add_argument("--gemm-mode", type=int, default=0, help="lq_svd_params.gemm_mode (0 = library default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sweep shards over GPUs by "
@@ -64,17 +89,18 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
     cfgs = [lq.config(*g) for g in gen.config_grid()]
+    params = lq.SvdParams(streams=args.streams, gemm_mode=args.gemm_mode)
     host = [gen.workload_matrix(3, i) for i in range(min(args.matrices, len(gen.LLAMA2_7B_LAYER)))]
     mats = [torch.from_numpy(w).to(dev) for w in host]
     # one workspace, large enough for every shape of the layer
-    ws = max((lq.error_table_workspace(d, k, RANK, len(cfgs), device=dev) for d, k in {tuple(m.shape) for m in mats}),
+    ws = max((lq.error_table_workspace(d, k, RANK, len(cfgs), params, device=dev) for d, k in {tuple(m.shape) for m in mats}),
              key=lambda t: t.numel())
     torch.cuda.synchronize()
 
     def step():
         out = []
         for w in mats:
-            out.append(lq.error_table(w, RANK, cfgs, ITERS, seed=1, workspace=ws))
+            out.append(lq.error_table(w, RANK, cfgs, ITERS, seed=1, params=params, workspace=ws))
         return out
 
     for _ in range(args.warmup):
@@ -99,14 +125,7 @@ def main() -> int:
                          "work_per_s": work / (ms * 1e-3) if ms > 0 else 0.0}
     dom = max(prof.items(), key=lambda kv: kv[1][0])
     dname, (dms, dn, dwork) = dom
-    if dname.startswith("wide_gemm"):
-        ach = dwork / (dms * 1e-3) / 1e12
-        roof = {"kernel": dname, "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None, "launches": dn, "avg_us": 1e3 * dms / dn}
-    else:
-        ach = dwork / (dms * 1e-3) / 1e9
-        roof = {"kernel": dname, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None, "launches": dn, "avg_us": 1e3 * dms / dn}
+    roof = roofline_of(dname, dms, dn, dwork)
     line = {
         "metric": "matrix-configs decomposed/sec (LLaMA-2-7B layer sweep)", "value": value, "unit": "matrix-configs/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
@@ -115,6 +134,8 @@ def main() -> int:
                                "36 configs (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256), 10 LQ iterations",
                    "matrices": len(mats), "configs": len(cfgs), "iters": ITERS, "rank": RANK},
         "roofline": roof,
+        "rooflines": {n: roofline_of(n, ms, cnt, wk) for n, (ms, cnt, wk) in prof.items()
+                      if n.startswith(("wide_gemm", "lowrank", "residual", "quantize", "dequant"))},
         "kernels": kernels,
         "error_table_checksum": float(sum(np.sqrt(e).sum() for e, _ in res)),
     }

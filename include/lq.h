@@ -78,6 +78,9 @@ typedef struct {
  *                 from its warm start).  Default 3.
  *   max_batch     lq_error_table advances up to this many configurations in lock step (more
  *                 workspace, better GPU occupancy).  Default 36.
+ *   streams       lq_error_table splits a batch over this many HIP streams (1..4, all default priority, the
+ *                 first is the caller's) and interleaves them so that latency-bound steps of one part overlap
+ *                 throughput-bound kernels of another.  Default 3.
  *   gemm_mode     arithmetic of the large products against the d x k matrix: 1 = fp32 MFMA; 2 = both operands
  *                 split on the fly into bf16 hi + lo and multiplied by three bf16 MFMAs with fp32 accumulation
  *                 (products good to about 2^-16 relative, several times faster).  Default 2.
@@ -92,6 +95,7 @@ typedef struct {
   int32_t warm_power_2;
   int32_t max_batch;
   int32_t gemm_mode;
+  int32_t streams;
 } lq_svd_params;
 
 const char* lq_status_string(int status);
@@ -184,7 +188,7 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
  * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the library
  * is bracketed by two HIP events on the launch stream; lq_profile_read synchronizes the device and returns,
  * for one kernel class, the summed event time, the number of launches and the summed algorithmic work
- * (flops for the GEMM classes, bytes otherwise) since the last lq_profile_reset.  Class names are the
+ * (flops for the GEMM classes and for lowrank_blockquant_kernel, bytes otherwise) since the last lq_profile_reset.  Class names are the
  * kernels' names.  Not thread-safe against concurrent library calls.
  */
 int lq_profile_enable(int on);

@@ -229,7 +229,7 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) 
 
 int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st) {
   const dim3 grid((unsigned)a.batch, (unsigned)((a.k + TN - 1) / TN), (unsigned)((a.d + TM - 1) / TM));
-  prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st, (double)a.d * a.k * 4.0 * a.batch);
+  prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st, (double)a.d * a.k * (2.0 * a.rank + 10.0) * a.batch);   // flops
   if (with_err) hipLaunchKernelGGL(lowrank_blockquant_kernel<true>, grid, dim3(NTHR1), 0, st, a);
   else hipLaunchKernelGGL(lowrank_blockquant_kernel<false>, grid, dim3(NTHR1), 0, st, a);
   LQ_HIP_TRY(hipGetLastError());

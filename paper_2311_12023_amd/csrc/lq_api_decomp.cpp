@@ -29,7 +29,7 @@ static int64_t up32(int64_t x) { return (x + 31) / 32 * 32; }
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Params {
-  int l1, check, maxit, lw, qw, qw2, max_batch, prec;
+  int l1, check, maxit, lw, qw, qw2, max_batch, prec, streams;
   double tol;
 };
 
@@ -47,6 +47,8 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   out.max_batch = z.max_batch ? z.max_batch : 36;
   if (z.gemm_mode < 0 || z.gemm_mode > 2) return LQ_ERR_ARG;
   out.prec = z.gemm_mode == 1 ? 0 : 1;
+  out.streams = z.streams ? z.streams : 3;
+  if (out.streams < 1 || out.streams > 4) return LQ_ERR_ARG;
   if (out.l1 % 32 || out.l1 <= rank || out.l1 > 256) return LQ_ERR_ARG;
   if (out.lw % 32 || out.lw <= rank || out.lw > out.l1) return LQ_ERR_ARG;
   if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.max_batch < 1) return LQ_ERR_ARG;
@@ -130,6 +132,9 @@ struct Ctx {
   const float* col_w;
   bool weighted;
   const DevTables* tables;
+  // set once per call and shared by the per-stream contexts of a sweep
+  const float* sr; const float* sc; const float* rsr; const float* rsc;   // sqrt / 1/sqrt of the Fisher weights
+  const double* lam_cold;                                                   // Ritz values of the cold start
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
 
@@ -278,7 +283,10 @@ static int setup_common(Ctx& c, const float* W, const float* row_w, const float*
   c.ws = (char*)workspace; c.st = st; c.W = W; c.row_w = row_w; c.col_w = col_w; c.weighted = row_w != nullptr;
   LQ_TRY(device_tables(&c.tables));
   const Plan& pl = c.pl;
+  c.sr = c.sc = c.rsr = c.rsc = nullptr;
+  c.lam_cold = c.at<double>(pl.lam_cold);
   if (c.weighted) {
+    c.sr = c.at<float>(pl.sr); c.sc = c.at<float>(pl.sc); c.rsr = c.at<float>(pl.rsr); c.rsc = c.at<float>(pl.rsc);
     LQ_TRY(launch_sqrt_vecs(row_w, pl.d, c.at<float>(pl.sr), c.at<float>(pl.rsr), st));
     LQ_TRY(launch_sqrt_vecs(col_w, pl.k, c.at<float>(pl.sc), c.at<float>(pl.rsc), st));
   }
@@ -290,7 +298,7 @@ static int first_input(const Ctx& c, const float** A) {
   const Plan& pl = c.pl;
   if (!c.weighted) { *A = c.W; return LQ_OK; }
   float* As = c.at<float>(pl.R);
-  LQ_TRY(launch_scale_matrix(c.W, pl.d, pl.k, c.at<float>(pl.sr), c.at<float>(pl.sc), As, c.st));
+  LQ_TRY(launch_scale_matrix(c.W, pl.d, pl.k, c.sr, c.sc, As, c.st));
   *A = As;
   return LQ_OK;
 }
@@ -299,101 +307,130 @@ struct LoopOut {          // batch == 1 only: user buffers that receive the quan
   uint8_t* codes; uint8_t* sidx; float* v; float* Qd;
 };
 
-// Runs Algorithm 2 for `batch` configurations in lock step from the shared first factorization
-// (Y1, B1, lam_cold).  Host outputs: trace[b * iters + t], iters_done[b].  On return *Yfin / *Bfin /
-// *lamfin describe the last Factorize of problem 0 (wide, Ritz order).
-static int run_loop(Ctx& c, const lq_config* cfgs, int batch, int iters, int early_stop, bool want_trace,
-                    const float* Y1, const float* B1, const LoopOut* direct, double* trace, int32_t* iters_done,
-                    const float** Yfin, const float** Bfin, const double** lamfin) {
-  const Plan& pl = c.pl;
-  std::vector<LoopProblem> probs(batch);
-  int min_block = 1 << 30;
-  for (int b = 0; b < batch; ++b) {
-    std::memset(&probs[b], 0, sizeof(LoopProblem));
-    probs[b].cfg = cfgs[b];
-    probs[b].levels = scale_levels(cfgs[b]);
-    min_block = std::min(min_block, (int)cfgs[b].block);
-  }
-  LoopProblem* dprob = c.at<LoopProblem>(pl.prob);
-  LQ_HIP_TRY(hipMemcpyAsync(dprob, probs.data(), sizeof(LoopProblem) * batch, hipMemcpyHostToDevice, c.st));
-  WideSet w{c.at<float>(pl.Yw), c.at<float>(pl.Yw2), c.at<float>(pl.Bw), c.at<float>(pl.Bw2)};
-  LQ_HIP_TRY(hipMemsetAsync(w.Yw, 0, pl.strideYw * 4 * batch, c.st));
-  LQ_HIP_TRY(hipMemsetAsync(w.Yw2, 0, pl.strideYw * 4 * batch, c.st));
-  LQ_HIP_TRY(hipMemsetAsync(w.Bw, 0, pl.strideBw * 4 * batch, c.st));
-  LQ_HIP_TRY(hipMemsetAsync(w.Bw2, 0, pl.strideBw * 4 * batch, c.st));
-
+// Algorithm 2 for `batch` configurations in lock step from the shared first factorization (Y1, B1, lam_cold),
+// as a sequence of asynchronous steps on the context's stream so that several such loops (one per stream) can
+// be interleaved by the host: begin(), step(t) for t = 1.., finish().
+struct Loop {
+  Ctx* c = nullptr;
+  const lq_config* cfgs = nullptr;
+  int batch = 0, iters = 0, early_stop = 0;
+  bool want_trace = false;
+  const float* Y1 = nullptr; const float* B1 = nullptr;
+  const LoopOut* direct = nullptr;
+  // state
+  std::vector<LoopProblem> probs;
+  std::vector<double> host_err;
+  int min_block = 1 << 30, done = 0;
   PhaseArgs a;
-  std::memset(&a, 0, sizeof(a));
-  a.W = c.W; a.d = pl.d; a.k = pl.k; a.rank = pl.rank; a.ldy = pl.ldd; a.ldb = pl.ldk;
-  if (c.weighted) {
-    a.rsr = c.at<float>(pl.rsr); a.rsc = c.at<float>(pl.rsc); a.sr = c.at<float>(pl.sr); a.sc = c.at<float>(pl.sc);
-    a.row_w = c.row_w; a.col_w = c.col_w;
-  }
-  a.prob = dprob; a.tables = c.tables; a.batch = batch;
-  if (direct) {
-    a.codes = direct->codes; a.sidx = direct->sidx; a.v = direct->v;
-  } else {
-    a.codes = c.at<uint8_t>(pl.codes); a.strideCodes = pl.strideCodes;
-    a.sidx = c.at<uint8_t>(pl.sidx); a.strideSidx = pl.strideSidx;
-    a.v = c.at<float>(pl.v); a.strideV = pl.strideV;
-  }
-  a.blk = c.at<BlockRec>(pl.blk); a.strideBlk = pl.strideBlk;
-  a.err_part = c.at<double>(pl.epart); a.strideErrPart = pl.strideEpart;
-  double* errs = c.at<double>(pl.errs);
-  a.strideErrOut = MAX_ITERS;
-
-  const float* Ycur = Y1; const float* Bcur = B1; size_t sY = 0, sB = 0;
-  const double* lamcur = c.at<double>(pl.lam_cold);
+  WideSet w;
+  const float* Ycur = nullptr; const float* Bcur = nullptr;
+  size_t sY = 0, sB = 0;
+  const double* lamcur = nullptr;
+  double* errs = nullptr;
   double prev_eps = INFINITY;
-  int done = 0;
-  for (int t = 1; t <= iters; ++t) {
+  bool stopped = false;
+
+  int begin() {
+    const Plan& pl = c->pl;
+    probs.assign(batch, LoopProblem());
+    for (int b = 0; b < batch; ++b) {
+      std::memset(&probs[b], 0, sizeof(LoopProblem));
+      probs[b].cfg = cfgs[b];
+      probs[b].levels = scale_levels(cfgs[b]);
+      min_block = std::min(min_block, (int)cfgs[b].block);
+    }
+    LoopProblem* dprob = c->at<LoopProblem>(pl.prob);
+    LQ_HIP_TRY(hipMemcpyAsync(dprob, probs.data(), sizeof(LoopProblem) * batch, hipMemcpyHostToDevice, c->st));
+    w = WideSet{c->at<float>(pl.Yw), c->at<float>(pl.Yw2), c->at<float>(pl.Bw), c->at<float>(pl.Bw2)};
+    LQ_HIP_TRY(hipMemsetAsync(w.Yw, 0, pl.strideYw * 4 * batch, c->st));
+    LQ_HIP_TRY(hipMemsetAsync(w.Yw2, 0, pl.strideYw * 4 * batch, c->st));
+    LQ_HIP_TRY(hipMemsetAsync(w.Bw, 0, pl.strideBw * 4 * batch, c->st));
+    LQ_HIP_TRY(hipMemsetAsync(w.Bw2, 0, pl.strideBw * 4 * batch, c->st));
+    std::memset(&a, 0, sizeof(a));
+    a.W = c->W; a.d = pl.d; a.k = pl.k; a.rank = pl.rank; a.ldy = pl.ldd; a.ldb = pl.ldk;
+    if (c->weighted) {
+      a.rsr = c->rsr; a.rsc = c->rsc; a.sr = c->sr; a.sc = c->sc;
+      a.row_w = c->row_w; a.col_w = c->col_w;
+    }
+    a.prob = dprob; a.tables = c->tables; a.batch = batch;
+    if (direct) {
+      a.codes = direct->codes; a.sidx = direct->sidx; a.v = direct->v;
+    } else {
+      a.codes = c->at<uint8_t>(pl.codes); a.strideCodes = pl.strideCodes;
+      a.sidx = c->at<uint8_t>(pl.sidx); a.strideSidx = pl.strideSidx;
+      a.v = c->at<float>(pl.v); a.strideV = pl.strideV;
+    }
+    a.blk = c->at<BlockRec>(pl.blk); a.strideBlk = pl.strideBlk;
+    a.err_part = c->at<double>(pl.epart); a.strideErrPart = pl.strideEpart;
+    errs = c->at<double>(pl.errs);
+    a.strideErrOut = MAX_ITERS;
+    Ycur = Y1; Bcur = B1; sY = 0; sB = 0;
+    lamcur = c->lam_cold;
+    return LQ_OK;
+  }
+
+  // Iteration t: Quantize(W - L1 L2) and its error, then (unless it is the last) the next Factorize.
+  int step(int t) {
+    if (stopped || t > iters) return LQ_OK;
+    const Plan& pl = c->pl;
     a.Y = Ycur; a.B = Bcur; a.strideY = sY; a.strideB = sB;
     a.R = nullptr; a.Qd = nullptr; a.err_out = errs + (t - 1);
     // the error of an iteration costs extra arithmetic per weight: only computed when somebody looks at it
     const bool with_err = want_trace || early_stop || t == iters;
-    LQ_TRY(launch_lowrank_blockquant(a, with_err, c.st));
-    LQ_TRY(launch_scalequant_error(a, min_block, c.st));
+    LQ_TRY(launch_lowrank_blockquant(a, with_err, c->st));
+    LQ_TRY(launch_scalequant_error(a, min_block, c->st));
     done = t;
     bool last = t == iters;
     if (early_stop && batch == 1) {        // Algorithm 2's stopping rule needs eps_t on the host
       double eps = 0.0;
-      LQ_HIP_TRY(hipMemcpyAsync(&eps, errs + (t - 1), sizeof(double), hipMemcpyDeviceToHost, c.st));
-      LQ_HIP_TRY(hipStreamSynchronize(c.st));
+      LQ_HIP_TRY(hipMemcpyAsync(&eps, errs + (t - 1), sizeof(double), hipMemcpyDeviceToHost, c->st));
+      LQ_HIP_TRY(hipStreamSynchronize(c->st));
       if (eps > prev_eps) last = true;
       prev_eps = eps;
     }
-    if (last) break;
-    a.R = c.at<float>(pl.R); a.strideR = pl.strideR;
-    LQ_TRY(launch_residual(a, c.st));
-    LQ_TRY(warm_factorize(c, w, Bcur, sB, t == 1 ? pl.prm.qw2 : pl.prm.qw, batch));
+    if (last) { stopped = true; return LQ_OK; }
+    a.R = c->at<float>(pl.R); a.strideR = pl.strideR;
+    LQ_TRY(launch_residual(a, c->st));
+    LQ_TRY(warm_factorize(*c, w, Bcur, sB, t == 1 ? pl.prm.qw2 : pl.prm.qw, batch));
     Ycur = w.Yw; Bcur = w.Bw; sY = pl.strideYw; sB = pl.strideBw;
-    lamcur = c.at<double>(pl.lam);
+    lamcur = c->at<double>(pl.lam);
+    return LQ_OK;
   }
-  if (direct && direct->Qd) {
-    a.R = nullptr; a.Qd = direct->Qd; a.strideQd = 0;
-    LQ_TRY(launch_residual(a, c.st));
-  }
-  std::vector<double> host_err((size_t)batch * MAX_ITERS);
-  // copy only the used prefix of every row
-  for (int b = 0; b < batch; ++b)
-    LQ_HIP_TRY(hipMemcpyAsync(host_err.data() + (size_t)b * MAX_ITERS, errs + (size_t)b * MAX_ITERS,
-                              sizeof(double) * done, hipMemcpyDeviceToHost, c.st));
-  LQ_HIP_TRY(hipStreamSynchronize(c.st));
-  for (int b = 0; b < batch; ++b) {
-    int nd = done;
-    if (early_stop && batch > 1) {         // lock-step batches apply the rule after the fact
-      for (int t = 1; t < done; ++t)
-        if (host_err[(size_t)b * MAX_ITERS + t] > host_err[(size_t)b * MAX_ITERS + t - 1]) { nd = t + 1; break; }
+
+  // Dense Q if asked for, then the error trace comes to the host (synchronizes the stream).
+  // Host outputs: trace[b * iters + t] (NaN where not computed), iters_done[b].
+  int finish(double* trace, int32_t* iters_done) {
+    if (direct && direct->Qd) {
+      a.R = nullptr; a.Qd = direct->Qd; a.strideQd = 0;
+      LQ_TRY(launch_residual(a, c->st));
     }
-    if (iters_done) iters_done[b] = nd;
-    if (trace)
-      for (int t = 0; t < iters; ++t)
-        trace[(size_t)b * iters + t] =
-            (t < nd && (want_trace || early_stop || t == iters - 1)) ? host_err[(size_t)b * MAX_ITERS + t] : NAN;
+    host_err.assign((size_t)batch * MAX_ITERS, 0.0);
+    for (int b = 0; b < batch; ++b)   // only the used prefix of every row
+      LQ_HIP_TRY(hipMemcpyAsync(host_err.data() + (size_t)b * MAX_ITERS, errs + (size_t)b * MAX_ITERS,
+                                sizeof(double) * done, hipMemcpyDeviceToHost, c->st));
+    LQ_HIP_TRY(hipStreamSynchronize(c->st));
+    for (int b = 0; b < batch; ++b) {
+      int nd = done;
+      if (early_stop && batch > 1) {         // lock-step batches apply the rule after the fact
+        for (int t = 1; t < done; ++t)
+          if (host_err[(size_t)b * MAX_ITERS + t] > host_err[(size_t)b * MAX_ITERS + t - 1]) { nd = t + 1; break; }
+      }
+      if (iters_done) iters_done[b] = nd;
+      if (trace)
+        for (int t = 0; t < iters; ++t)
+          trace[(size_t)b * iters + t] =
+              (t < nd && (want_trace || early_stop || t == iters - 1)) ? host_err[(size_t)b * MAX_ITERS + t] : NAN;
+    }
+    return LQ_OK;
   }
-  if (Yfin) *Yfin = Ycur;
-  if (Bfin) *Bfin = Bcur;
-  if (lamfin) *lamfin = lamcur;
+};
+
+// Extra streams for lq_error_table's interleaved sub-batches: created once per host thread, default priority.
+static int extra_stream(int i, hipStream_t* out) {
+  static thread_local hipStream_t pool[4] = {nullptr, nullptr, nullptr, nullptr};   // per host thread: concurrent calls do not share them
+  if (i < 0 || i >= 4) return LQ_ERR_ARG;
+  if (!pool[i]) LQ_HIP_TRY(hipStreamCreateWithFlags(&pool[i], hipStreamNonBlocking));
+  *out = pool[i];
   return LQ_OK;
 }
 
@@ -401,8 +438,7 @@ static int emit_factors(const Ctx& c, const float* Y, const float* B, const doub
                         double* sigma_host) {
   const Plan& pl = c.pl;
   LQ_TRY(launch_assemble_factors(Y, pl.ldd, B, pl.ldk, lam, pl.rank, pl.d, pl.k,
-                                 c.weighted ? c.at<float>(pl.rsr) : nullptr, c.weighted ? c.at<float>(pl.rsc) : nullptr,
-                                 L1, L2, c.st));
+                                 c.rsr, c.rsc, L1, L2, c.st));
   std::vector<double> lamh(pl.rank);
   LQ_HIP_TRY(hipMemcpyAsync(lamh.data(), lam, sizeof(double) * pl.rank, hipMemcpyDeviceToHost, c.st));
   LQ_HIP_TRY(hipStreamSynchronize(c.st));
@@ -439,9 +475,11 @@ size_t lq_decompose_workspace_bytes(int64_t d, int64_t k, int rank, const lq_svd
 size_t lq_error_table_workspace_bytes(int64_t d, int64_t k, int rank, int n_cfgs, const lq_svd_params* p) {
   Params prm;
   if (n_cfgs < 1 || check_matrix_args(d, k, rank) != LQ_OK || resolve_params(rank, p, prm) != LQ_OK) return 0;
+  const int batch_max = std::min(n_cfgs, prm.max_batch);
+  const int nsub = std::max(1, std::min(prm.streams, batch_max / 4));
   Plan pl;
-  make_plan(d, k, rank, prm, std::min(n_cfgs, prm.max_batch), pl);
-  return pl.total;
+  make_plan(d, k, rank, prm, (batch_max + nsub - 1) / nsub, pl);
+  return up256(pl.total) * nsub;
 }
 
 int lq_factorize(const float* A, int64_t d, int64_t k, int rank, const float* row_w, const float* col_w,
@@ -487,10 +525,13 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   LoopOut direct{q_codes, q_scale_idx, q_v, Q_dense};
   std::vector<double> trace(iters, NAN);
   int32_t done = 0;
-  const float* Yf; const float* Bf; const double* lamf;
-  LQ_TRY(run_loop(c, &cfg, 1, iters, early_stop, err_trace != nullptr, Y1, B1, &direct, trace.data(), &done, &Yf, &Bf,
-                  &lamf));
-  LQ_TRY(emit_factors(c, Yf, Bf, lamf, L1, L2, sigma));
+  Loop lp;
+  lp.c = &c; lp.cfgs = &cfg; lp.batch = 1; lp.iters = iters; lp.early_stop = early_stop;
+  lp.want_trace = err_trace != nullptr; lp.Y1 = Y1; lp.B1 = B1; lp.direct = &direct;
+  LQ_TRY(lp.begin());
+  for (int t = 1; t <= iters; ++t) LQ_TRY(lp.step(t));
+  LQ_TRY(lp.finish(trace.data(), &done));
+  LQ_TRY(emit_factors(c, lp.Ycur, lp.Bcur, lp.lamcur, L1, L2, sigma));
   if (err) *err = trace[done - 1];
   if (err_trace) std::memcpy(err_trace, trace.data(), sizeof(double) * iters);
   if (iters_done) *iters_done = done;
@@ -514,28 +555,66 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
   if (!aligned16(W)) return LQ_ERR_ARG;
   Params prm;
   LQ_TRY(resolve_params(rank, p, prm));
-  Ctx c;
+  // The configurations of a batch are split over `streams` sub-batches, each with its own stream and workspace
+  // slice; the host enqueues their iterations alternately, so the latency-bound single-workgroup steps of one
+  // sub-batch (Cholesky, Jacobi) overlap the bandwidth- and MFMA-bound kernels of the other.
   const int batch_max = std::min(n_cfgs, prm.max_batch);
-  make_plan(d, k, rank, prm, batch_max, c.pl);
-  LQ_TRY(check_workspace(workspace, workspace_bytes, c.pl.total));
+  const int nsub = std::max(1, std::min(prm.streams, batch_max / 4));
+  const int per_sub = (batch_max + nsub - 1) / nsub;
+  std::vector<Ctx> cs(nsub);
+  make_plan(d, k, rank, prm, per_sub, cs[0].pl);
+  const size_t slice = up256(cs[0].pl.total);
+  LQ_TRY(check_workspace(workspace, workspace_bytes, slice * nsub));
+  Ctx& c = cs[0];
   LQ_TRY(setup_common(c, W, row_w, col_w, workspace, (hipStream_t)stream));
   const float* A0; const float* Y1; const float* B1;
   LQ_TRY(first_input(c, &A0));
   LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));
-  std::vector<double> trace((size_t)batch_max * iters);
-  std::vector<int32_t> done(batch_max);
-  for (int c0 = 0; c0 < n_cfgs; c0 += batch_max) {
+  hipEvent_t ready = nullptr;
+  if (nsub > 1) {
+    LQ_HIP_TRY(hipEventCreateWithFlags(&ready, hipEventDisableTiming));
+    LQ_HIP_TRY(hipEventRecord(ready, c.st));
+  }
+  for (int s1 = 1; s1 < nsub; ++s1) {
+    cs[s1] = c;
+    cs[s1].ws = (char*)workspace + slice * s1;
+    LQ_TRY(extra_stream(s1 - 1, &cs[s1].st));
+    LQ_HIP_TRY(hipStreamWaitEvent(cs[s1].st, ready, 0));
+  }
+  int rc = LQ_OK;
+  std::vector<double> trace((size_t)per_sub * iters);
+  std::vector<int32_t> done(per_sub);
+  for (int c0 = 0; c0 < n_cfgs && rc == LQ_OK; c0 += batch_max) {
     const int nb = std::min(batch_max, n_cfgs - c0);
-    LQ_TRY(run_loop(c, cf.data() + c0, nb, iters, early_stop, err_trace != nullptr, Y1, B1, nullptr, trace.data(),
-                    done.data(), nullptr, nullptr, nullptr));
-    for (int b = 0; b < nb; ++b) {
-      const double eps = trace[(size_t)b * iters + done[b] - 1];
-      err_sq[c0 + b] = eps * eps;
-      storage_bits[c0 + b] = lq_storage_bits(d * k, cf[c0 + b]);
-      if (err_trace) std::memcpy(err_trace + (size_t)(c0 + b) * iters, trace.data() + (size_t)b * iters, sizeof(double) * iters);
+    std::vector<Loop> loops(nsub);
+    int used = 0;
+    for (int s1 = 0; s1 < nsub; ++s1) {
+      const int b0 = s1 * per_sub, b1 = std::min(nb, b0 + per_sub);
+      if (b0 >= b1) break;
+      Loop& lp = loops[s1];
+      lp.c = &cs[s1]; lp.cfgs = cf.data() + c0 + b0; lp.batch = b1 - b0; lp.iters = iters; lp.early_stop = early_stop;
+      lp.want_trace = err_trace != nullptr; lp.Y1 = Y1; lp.B1 = B1; lp.direct = nullptr;
+      if ((rc = lp.begin()) != LQ_OK) break;
+      ++used;
+    }
+    for (int t = 1; t <= iters && rc == LQ_OK; ++t)
+      for (int s1 = 0; s1 < used && rc == LQ_OK; ++s1) rc = loops[s1].step(t);
+    for (int s1 = 0; s1 < used; ++s1) {           // always drain every stream, even after an error
+      const int frc = loops[s1].finish(trace.data(), done.data());
+      if (rc == LQ_OK) rc = frc;
+      if (frc != LQ_OK) continue;
+      const int b0 = s1 * per_sub;
+      for (int b = 0; b < loops[s1].batch; ++b) {
+        const int ci = c0 + b0 + b;
+        const double eps = trace[(size_t)b * iters + done[b] - 1];
+        err_sq[ci] = eps * eps;
+        storage_bits[ci] = lq_storage_bits(d * k, cf[ci]);
+        if (err_trace) std::memcpy(err_trace + (size_t)ci * iters, trace.data() + (size_t)b * iters, sizeof(double) * iters);
+      }
     }
   }
-  return LQ_OK;
+  if (ready) (void)hipEventDestroy(ready);
+  return rc;
 }
 
 // ---- test hooks (include/lq_testing.h) ----------------------------------------------------------------
