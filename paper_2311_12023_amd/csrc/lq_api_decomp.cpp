@@ -8,8 +8,6 @@
 // `rank` rows give L1 L2 = Y_r^T B_r, and the first `warm_width` rows seed the next iteration.
 #include <algorithm>
 #include <cmath>
-#include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -231,7 +229,6 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
         kappa = 0.7 * std::log(last_delta / delta) / gap;
       double err_est = delta;
       if (kappa > 0) err_est = std::min(delta, delta / std::expm1(kappa * gap));
-      if (getenv("LQ_TRACE")) fprintf(stderr, "[cold] it=%d delta=%.3e err_est=%.3e kappa=%.3f alpha=%.4g lamr=%.8g laml=%.6g\n", it, delta, err_est, kappa, alpha, cur[r - 1], cur[l - 1]);
       const bool done = have_prev && err_est <= pl.prm.tol;
       if (done || it == pl.prm.maxit) break;
       // next Rayleigh-Ritz where the error is predicted to reach the tolerance
@@ -245,7 +242,7 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
       for (int j = 0; j < r; ++j) prev[j] = cur[j];
       have_prev = true;
       const double new_alpha = 0.5 * cur[l - 1];
-      if (new_alpha > 1.25 * alpha && !getenv("LQ_NOSHIFT")) { alpha = new_alpha; rate_ok = false; kappa = 0.0; next_check = it + pl.prm.check; }
+      if (new_alpha > 1.25 * alpha) { alpha = new_alpha; rate_ok = false; kappa = 0.0; next_check = it + pl.prm.check; }
     }
     // Y <- orth((A A^T - alpha I) Y)
     LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Yb, pl.ldd, 0, 1));
