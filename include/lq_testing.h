@@ -15,11 +15,17 @@
 extern "C" {
 #endif
 
-/* mode 0: C[l x big] = X[l x K] * A[big x K]^T;  mode 1: C[l x big] = X[l x K] * A[K x big].
- * part: scratch of splits * l * ldc floats (used when splits > 1).
+/* mode 0: C[l x big] = X[l x K] * A[big x K]^T;  mode 1: C[l x big] = X[l x K] * A[K x big], for `batch` problems
+ * stored back to back (X: l x ldx each, A: its rows x lda, C: l x ldc).
+ * The reduction steps of the batch are dealt out in equal shares to about `workgroups` workgroups (0 = as many
+ * as the device holds at once); part: device scratch of part_floats floats for the tiles whose reduction ends up
+ * cut between workgroups, at least lq_test_wide_gemm_part_floats(l, workgroups); with less (or NULL) none is cut.
+ * Columns big .. ldc-1 of C are never written.
  * precision 0: fp32 MFMA; 1: bf16 hi/lo split, three bf16 MFMAs per product. */
 int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
-                      int64_t lda, float* C, int64_t ldc, int splits, float* part, int precision, void* stream);
+                      int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
+                      int precision, void* stream);
+size_t lq_test_wide_gemm_part_floats(int l, int workgroups);
 /* Rows of X (l x m) are orthonormalised in place by Cholesky-QR (Gram in fp64).
  * scratch: at least 17 * l * l doubles.  alt: l * ldx floats of scratch, or NULL to force the
  * in-place triangular solve. */

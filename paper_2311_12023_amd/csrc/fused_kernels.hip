@@ -305,8 +305,11 @@ int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st) {
 // ------------------------------------------------------------------------------------------------
 // Phase 3: one quad (4 consecutive weights) per lane and step, so each wavefront instruction reads / writes
 // 1 KB of contiguous fp32.
+// U quads per lane and step, all loads issued before the first use: the kernel is bound by the bytes each CU keeps
+// in flight.
 template <int BITS>
 __device__ inline void phase3_body(const PhaseArgs& a, const LoopProblem& pr, int z, const float* s_code) {
+  constexpr int U = 4;
   const int64_t nquads = (a.d * a.k) >> 2;
   const int qpb_shift = __builtin_ctz(pr.cfg.block / 4), sb_shift = __builtin_ctz(pr.cfg.scale_block);
   const uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
@@ -314,24 +317,40 @@ __device__ inline void phase3_body(const PhaseArgs& a, const LoopProblem& pr, in
   const float* v = a.v + (size_t)z * a.strideV;
   float* R = a.R ? a.R + (size_t)z * a.strideR : nullptr;
   float* Qd = a.Qd ? a.Qd + (size_t)z * a.strideQd : nullptr;
-  for (int64_t quad = (int64_t)blockIdx.y * 256 + threadIdx.x; quad < nquads; quad += (int64_t)gridDim.y * 256) {
-    const int64_t blk = quad >> qpb_shift;
-    const float sh = block_scale(sidx[blk], v[blk >> sb_shift], pr.levels);
-    uint32_t c[4];
-    load_quad_codes<BITS>(codes, quad, c);
-    const int64_t e0 = quad << 2;
-    const float4 f = *reinterpret_cast<const float4*>(a.W + e0);
-    float4 qv, rv;
-    qv.x = s_code[c[0]] * sh; qv.y = s_code[c[1]] * sh; qv.z = s_code[c[2]] * sh; qv.w = s_code[c[3]] * sh;
-    rv.x = f.x - qv.x; rv.y = f.y - qv.y; rv.z = f.z - qv.z; rv.w = f.w - qv.w;
-    if (a.sr) {
-      const int64_t row = e0 / a.k, col = e0 % a.k;
-      const float srow = a.sr[row];
-      const float4 cs = *reinterpret_cast<const float4*>(a.sc + col);
-      rv.x = srow * rv.x * cs.x; rv.y = srow * rv.y * cs.y; rv.z = srow * rv.z * cs.z; rv.w = srow * rv.w * cs.w;
+  for (int64_t q0 = (int64_t)blockIdx.y * (256 * U) + threadIdx.x; q0 < nquads; q0 += (int64_t)gridDim.y * (256 * U)) {
+    float4 f[U];
+    uint32_t c[U][4];
+    uint32_t si[U];
+    float vv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t quad = q0 + 256 * u;
+      const bool live = quad < nquads;
+      const int64_t qq = live ? quad : nquads - 1;
+      const int64_t blk = qq >> qpb_shift;
+      f[u] = *reinterpret_cast<const float4*>(a.W + (qq << 2));
+      load_quad_codes<BITS>(codes, qq, c[u]);
+      si[u] = sidx[blk];
+      vv[u] = v[blk >> sb_shift];
     }
-    if (R) *reinterpret_cast<float4*>(R + e0) = rv;
-    if (Qd) *reinterpret_cast<float4*>(Qd + e0) = qv;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t quad = q0 + 256 * u;
+      if (quad >= nquads) break;
+      const float sh = block_scale(si[u], vv[u], pr.levels);
+      const int64_t e0 = quad << 2;
+      float4 qv, rv;
+      qv.x = s_code[c[u][0]] * sh; qv.y = s_code[c[u][1]] * sh; qv.z = s_code[c[u][2]] * sh; qv.w = s_code[c[u][3]] * sh;
+      rv.x = f[u].x - qv.x; rv.y = f[u].y - qv.y; rv.z = f[u].z - qv.z; rv.w = f[u].w - qv.w;
+      if (a.sr) {
+        const int64_t row = e0 / a.k, col = e0 % a.k;
+        const float srow = a.sr[row];
+        const float4 cs = *reinterpret_cast<const float4*>(a.sc + col);
+        rv.x = srow * rv.x * cs.x; rv.y = srow * rv.y * cs.y; rv.z = srow * rv.z * cs.z; rv.w = srow * rv.w * cs.w;
+      }
+      if (R) *reinterpret_cast<float4*>(R + e0) = rv;
+      if (Qd) *reinterpret_cast<float4*>(Qd + e0) = qv;
+    }
   }
 }
 
@@ -352,7 +371,7 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a) {
 
 int launch_residual(const PhaseArgs& a, hipStream_t st) {
   const int64_t nquads = (a.d * a.k) >> 2;
-  const int64_t want = (nquads + 255) / 256;
+  const int64_t want = (nquads + 1023) / 1024;      // 4 quads per lane and step
   const int64_t cap = 8192;
   prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * 8.0 * a.batch);
   hipLaunchKernelGGL(residual_kernel, dim3((unsigned)a.batch, (unsigned)(want < cap ? want : cap)), dim3(256), 0, st,

@@ -8,13 +8,14 @@
 // The result is "wide" again (l rows), so the output of one product is the X of the next.
 //
 // Mapping: a workgroup has 4 wavefronts.  X's K-chunk (l x 32) is staged in LDS and shared; each
-// wavefront fetches its own slice of A straight from global memory in MFMA operand layout (every
-// element of A is needed by one wavefront only, so LDS staging would buy nothing) and owns
+// wavefront fetches its own slice of A (32*NT rows or columns) straight from global memory in MFMA operand
+// layout (every element of A is needed by one wavefront only, so LDS staging would buy nothing) and owns
 // LT x NT accumulator tiles of 32x32.  The reduction index inside a 32-chunk is permuted
 // (lane half h, register e, sub-chunk c  <->  k = 8c + 4h + e) so that both operands are fetched with
 // 128-bit loads; any permutation is valid as long as A and X agree on it.
-// gridDim = (tiles along the large dimension, K splits, batch).  With K splits > 1 each split writes
-// its own partial result and splitk_reduce_kernel adds them in a fixed order (deterministic).
+// The launch is one-dimensional: see the work decomposition at wide_gemm_kernel.
+#include <algorithm>
+
 #include "kernels.h"
 #include "profiler.h"
 
@@ -82,125 +83,94 @@ __device__ __forceinline__ void stash_x_split(__bf16* xh, __bf16* xl, int tid, c
   }
 }
 
-// A operand of one 32-chunk in MFMA layout: breg[c][e][j], k = k0 + 8c + 4h + e.
+// Lane-dependent part of the A addresses in bytes.  It does not change along the reduction, so every load is
+// "uniform base + 32-bit lane offset" and needs no per-load address registers.
 template <int MODE, int NT>
-__device__ __forceinline__ void fetch_a(const float* __restrict__ A, int64_t lda, int64_t big, int64_t big0, int ln,
-                                        int lh, int64_t k0, int64_t kend, float (&breg)[4][4][NT]) {
+__device__ __forceinline__ void lane_offsets(int64_t lda, int64_t big, int64_t big0, int ln, int lh,
+                                             uint32_t (&off)[NT]) {
   if constexpr (MODE == MODE_NT) {
-    int64_t row = big0 + ln;
-    if (row >= big) row = big - 1;            // clamped rows are computed and never stored
-    const float* p = A + (size_t)row * lda;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int64_t kk = k0 + 8 * c + 4 * lh;
-      floatx4 f = {0.f, 0.f, 0.f, 0.f};
-      if (kk < kend) f = *reinterpret_cast<const floatx4*>(p + kk);   // K and kend are multiples of 4
-      breg[c][0][0] = f.x; breg[c][1][0] = f.y; breg[c][2][0] = f.z; breg[c][3][0] = f.w;
+    for (int j = 0; j < NT; ++j) {
+      int64_t row = big0 + 32 * j + ln;
+      if (row >= big) row = big - 1;            // clamped rows are computed and never stored
+      off[j] = (uint32_t)((row * lda + 4 * lh) * 4);
     }
   } else {
     int64_t col = big0 + (int64_t)ln * NT;
-    if (col + NT > big) col = big - NT;       // big is a multiple of NT; clamped columns never stored
+    if (col + NT > big) col = big - NT;         // big is a multiple of NT; clamped columns never stored
+    off[0] = (uint32_t)((4 * lh * lda + col) * 4);
+  }
+}
+
+// A operand of one 32-chunk in MFMA layout: breg[c][j][e], k = k0 + 8c + 4h + e.  GUARD: the chunk may reach
+// past kend (only the last chunk of a split can).
+template <int MODE, int NT, bool GUARD>
+__device__ __forceinline__ void fetch_a(const float* __restrict__ A, int64_t lda, const uint32_t (&off)[NT], int lh,
+                                        int64_t k0, int64_t kend, floatx4 (&breg)[4][NT]) {
+  if constexpr (MODE == MODE_NT) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const char* base = reinterpret_cast<const char*>(A + k0 + 8 * c);
+        floatx4 f = {0.f, 0.f, 0.f, 0.f};
+        if (!GUARD || k0 + 8 * c + 4 * lh < kend)                       // K and kend are multiples of 4
+          f = *reinterpret_cast<const floatx4*>(base + off[j]);
+        breg[c][j] = f;
+      }
+  } else {
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int64_t kk = k0 + 8 * c + 4 * lh + e;
+        const char* base = reinterpret_cast<const char*>(A + (size_t)(k0 + 8 * c + e) * lda);
+        const bool ok = !GUARD || k0 + 8 * c + 4 * lh + e < kend;
         if constexpr (NT == 2) {
-          float2 f = make_float2(0.f, 0.f);
-          if (kk < kend) f = *reinterpret_cast<const float2*>(A + (size_t)kk * lda + col);
-          breg[c][e][0] = f.x; breg[c][e][1] = f.y;
+          floatx2 f = {0.f, 0.f};
+          if (ok) f = *reinterpret_cast<const floatx2*>(base + off[0]);
+          breg[c][0][e] = f.x; breg[c][1][e] = f.y;
         } else {
           float f = 0.f;
-          if (kk < kend) f = A[(size_t)kk * lda + col];
-          breg[c][e][0] = f;
+          if (ok) f = *reinterpret_cast<const float*>(base + off[0]);
+          breg[c][0][e] = f;
         }
       }
   }
 }
 
-template <int LT, int MODE, int NT, int PREC>
-__global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) float xs[];   // fp32: [32*LT][XPITCH]; split: hi then lo, [32*LT][HPITCH] bf16
-  __bf16* xh = reinterpret_cast<__bf16*>(xs);
-  __bf16* xl = xh + 32 * LT * HPITCH;
-  const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int ln = lane & 31, lh = lane >> 5;
-  const int split = blockIdx.y, z = blockIdx.z;
-
-  const float* __restrict__ X = g.X + (size_t)z * g.strideX;
-  const float* __restrict__ A = g.A + (size_t)z * g.strideA;
-  float* __restrict__ C = g.C + ((size_t)z * g.splits + split) * g.strideC;
-
-  const int64_t kbeg = (int64_t)split * g.kchunk;
-  const int64_t kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
-  const int nsteps = (int)((kend - kbeg + BK - 1) / BK);
-
-  // this wavefront's slice of the large dimension
-  int64_t big0;   // first row (NT mode) or column (NN mode) of the slice
-  if constexpr (MODE == MODE_NT) big0 = (int64_t)blockIdx.x * 128 + wave * 32;
-  else big0 = (int64_t)blockIdx.x * (128 * NT) + wave * (32 * NT);
-
-  floatx16 acc[LT][NT];
+// One 32-chunk of the reduction: acc += X-chunk (in LDS) * A-chunk (in registers).
+template <int LT, int NT, int PREC>
+__device__ __forceinline__ void multiply_chunk(const float* xs, const __bf16* xh, const __bf16* xl, int ln, int lh,
+                                               const floatx4 (&bcur)[4][NT], floatx16 (&acc)[LT][NT]) {
+  if constexpr (PREC == PREC_BF16X3) {
 #pragma unroll
-  for (int i = 0; i < LT; ++i)
+    for (int gk = 0; gk < 2; ++gk) {
+      // A operand of this 16-group, split into hi and lo (slot 4cc + e  <->  bcur[2gk + cc][e])
+      bf16x8 ah[NT], al[NT];
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
+      for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-  floatx4 xreg[LT];
-  float breg[4][4][NT];
-  if (nsteps > 0) {
-    fetch_x<LT>(X, g.ldx, kbeg, tid, xreg);
-    fetch_a<MODE, NT>(A, g.lda, g.big, big0, ln, lh, kbeg, kend, breg);
-  }
-  for (int step = 0; step < nsteps; ++step) {
-    __syncthreads();          // everyone is done reading the previous X tile
-    if constexpr (PREC == PREC_FP32) stash_x<LT>(xs, tid, xreg);
-    else stash_x_split<LT>(xh, xl, tid, xreg);
-    float bcur[4][4][NT];
+        for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) bcur[c][e][j] = breg[c][e][j];
-    __syncthreads();
-    if (step + 1 < nsteps) {   // next chunk's loads fly while this chunk multiplies
-      const int64_t k1 = kbeg + (int64_t)(step + 1) * BK;
-      fetch_x<LT>(X, g.ldx, k1, tid, xreg);
-      fetch_a<MODE, NT>(A, g.lda, g.big, big0, ln, lh, k1, kend, breg);
-    }
-    if constexpr (PREC == PREC_BF16X3) {
-#pragma unroll
-      for (int gk = 0; gk < 2; ++gk) {
-        // A operand of this 16-group, split into hi and lo (slot 4cc + e  <->  bcur[2gk + cc][e])
-        bf16x8 ah[NT], al[NT];
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-          for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-            for (int e2 = 0; e2 < 2; ++e2) {
-              bf16x2 h, l;
-              split_bf16(floatx2{bcur[2 * gk + cc][2 * e2][j], bcur[2 * gk + cc][2 * e2 + 1][j]}, h, l);
-              ah[j][4 * cc + 2 * e2] = h[0]; ah[j][4 * cc + 2 * e2 + 1] = h[1];
-              al[j][4 * cc + 2 * e2] = l[0]; al[j][4 * cc + 2 * e2 + 1] = l[1];
-            }
-#pragma unroll
-        for (int i = 0; i < LT; ++i) {
-          const bf16x8 xhv = *reinterpret_cast<const bf16x8*>(xh + (32 * i + ln) * HPITCH + 16 * gk + 8 * lh);
-          const bf16x8 xlv = *reinterpret_cast<const bf16x8*>(xl + (32 * i + ln) * HPITCH + 16 * gk + 8 * lh);
-#pragma unroll
-          for (int j = 0; j < NT; ++j) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xlv, ah[j], acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhv, al[j], acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhv, ah[j], acc[i][j], 0, 0, 0);
+          for (int e2 = 0; e2 < 2; ++e2) {
+            bf16x2 h, l;
+            split_bf16(floatx2{bcur[2 * gk + cc][j][2 * e2], bcur[2 * gk + cc][j][2 * e2 + 1]}, h, l);
+            ah[j][4 * cc + 2 * e2] = h[0]; ah[j][4 * cc + 2 * e2 + 1] = h[1];
+            al[j][4 * cc + 2 * e2] = l[0]; al[j][4 * cc + 2 * e2 + 1] = l[1];
           }
+#pragma unroll
+      for (int i = 0; i < LT; ++i) {
+        const bf16x8 xhv = *reinterpret_cast<const bf16x8*>(xh + (32 * i + ln) * HPITCH + 16 * gk + 8 * lh);
+        const bf16x8 xlv = *reinterpret_cast<const bf16x8*>(xl + (32 * i + ln) * HPITCH + 16 * gk + 8 * lh);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xlv, ah[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhv, al[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhv, ah[j], acc[i][j], 0, 0, 0);
         }
       }
-    } else {
+    }
+  } else {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       float av[LT][4];
@@ -216,55 +186,192 @@ __global__ __launch_bounds__(256) void wide_gemm_kernel(GemmArgs g) {
         for (int i = 0; i < LT; ++i)
 #pragma unroll
           for (int j = 0; j < NT; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][e], bcur[c][e][j], acc[i][j], 0, 0, 0);
-    }
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][e], bcur[c][j][e], acc[i][j], 0, 0, 0);
     }
   }
+}
 
-  // ---- store: accumulator element e of a lane is row 8*(e/4) + 4*h + e%4, column n of its tile ----
+// Stores the accumulators of one wavefront.  `col0`: column of the destination that this wavefront's slice starts
+// at; columns >= `limit` are not written.
+template <int LT, int MODE, int NT>
+__device__ __forceinline__ void store_acc(float* __restrict__ dst, int64_t ld, int64_t col0, int64_t limit, int ln,
+                                          int lh, const floatx16 (&acc)[LT][NT]) {
+  // accumulator element e of a lane is row 8*(e/4) + 4*h + e%4, column n of its tile
   if constexpr (MODE == MODE_NT) {
-    const int64_t col = big0 + ln;
-    if (col < g.big) {
 #pragma unroll
-      for (int i = 0; i < LT; ++i)
+    for (int j = 0; j < NT; ++j) {
+      const int64_t col = col0 + 32 * j + ln;
+      if (col < limit) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
-          C[(size_t)row * g.ldc + col] = acc[i][0][e];
-        }
+        for (int i = 0; i < LT; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int row = 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
+            dst[(size_t)row * ld + col] = acc[i][j][e];
+          }
+      }
     }
   } else {
-    const int64_t col = big0 + (int64_t)ln * NT;
-    if (col + NT <= g.big) {
+    const int64_t col = col0 + (int64_t)ln * NT;
+    if (col + NT <= limit) {
 #pragma unroll
       for (int i = 0; i < LT; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int row = 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
           if constexpr (NT == 2)
-            *reinterpret_cast<float2*>(C + (size_t)row * g.ldc + col) = make_float2(acc[i][0][e], acc[i][1][e]);
+            *reinterpret_cast<float2*>(dst + (size_t)row * ld + col) = make_float2(acc[i][0][e], acc[i][1][e]);
           else
-            C[(size_t)row * g.ldc + col] = acc[i][0][e];
+            dst[(size_t)row * ld + col] = acc[i][0][e];
         }
     }
   }
 }
 
-// out[z][i] = sum_s part[z][s][i], i < count (count = rows * ldc), fixed summation order.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
-                                                            int splits, int64_t count4, size_t part_stride,
-                                                            size_t out_stride) {
-  const int z = blockIdx.y;
-  const float4* p = reinterpret_cast<const float4*>(part + (size_t)z * splits * part_stride);
-  float4* o = reinterpret_cast<float4*>(out + (size_t)z * out_stride);
-  const size_t ps4 = part_stride / 4;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += (int64_t)gridDim.x * 256) {
-    float4 s = p[i];
-    for (int q = 1; q < splits; ++q) {
-      const float4 t = p[(size_t)q * ps4 + i];
-      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+// Work decomposition.  Output tiles are l rows x SPAN columns; the reduction of a tile is cut into 32-deep steps.
+// The sequence of all steps of all problems, in order (problem, step), is dealt out in equal contiguous shares
+// ("stream-K"), so every workgroup streams the same number of bytes whatever the batch size; the workgroups of one
+// share, one per tile position along the large dimension, walk through A side by side (in NN mode they read whole
+// rows of A between them) and all fetch the same chunks of X.  Workgroups are dispatched to the 8 XCDs round-robin by
+// linear index, so the index is decoded as (share mod 8, tile, share div 8): the workgroups of a share land on one XCD
+// and the X chunks they have in common are fetched into that XCD's L2 once.  A share that covers a tile's whole reduction stores the tile
+// directly; a share that ends or starts inside one stores a partial tile (at most two per workgroup: slot 0 for the
+// problem its first step falls in, slot 1 for the problem of its last step) and gemm_fixup_kernel adds the partial
+// tiles of each cut tile in step order, which makes the result independent of timing.
+//
+// STAGES: depth of the register ring that holds A chunks.  While chunk s multiplies, chunks s+1 .. s+STAGES-1 are
+// in flight: the kernel streams A once from HBM and what bounds it is the number of bytes each CU keeps in flight.
+template <int LT, int MODE, int NT, int PREC, int STAGES>
+__global__ __launch_bounds__(256, 2) void wide_gemm_kernel(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // fp32: [32*LT][XPITCH]; split: hi then lo, [32*LT][HPITCH] bf16
+  __bf16* xh = reinterpret_cast<__bf16*>(xs);
+  __bf16* xl = xh + 32 * LT * HPITCH;
+  constexpr int SPAN = 128 * NT;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int ln = lane & 31, lh = lane >> 5;
+
+  const int tile = (blockIdx.x >> 3) % g.tiles;
+  const int share = (int)(blockIdx.x & 7) + 8 * (int)((blockIdx.x >> 3) / g.tiles);
+  const int share0 = share * g.per_wg;
+  if (share0 >= g.total) return;                 // padding of the share count to a multiple of 8
+  const int share1 = share0 + g.per_wg < g.total ? share0 + g.per_wg : g.total;
+
+  // this wavefront's slice of the large dimension: first row (NT mode) or column (NN mode)
+  const int64_t big0 = (int64_t)tile * SPAN + wave * (32 * NT);
+  uint32_t off[NT];
+  lane_offsets<MODE, NT>(g.lda, g.big, big0, ln, lh, off);
+
+  for (int gs = share0; gs < share1;) {
+    const int z = gs / g.ns;
+    const int s0 = gs - z * g.ns;
+    const int s1 = g.ns - s0 < share1 - gs ? g.ns : s0 + (share1 - gs);
+    const float* __restrict__ X = g.X + (size_t)z * g.strideX;
+    const float* __restrict__ A = g.A + (size_t)z * g.strideA;
+    const int64_t kbeg = (int64_t)s0 * BK;
+    const int64_t kend = (int64_t)s1 * BK < g.K ? (int64_t)s1 * BK : g.K;
+    const int nsteps = s1 - s0;
+
+    floatx16 acc[LT][NT];
+#pragma unroll
+    for (int i = 0; i < LT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // The last chunk of a reduction whose length is not a multiple of 32 is handled after the pipelined loop, so that
+    // the loop itself has no guarded loads and no conditional prefetch: every load in it is issued STAGES-1 steps
+    // before its first use and nothing forces an early wait.  Prefetches past the end re-read the last full chunk.
+    const bool tail = s1 == g.ns && (g.K & (BK - 1)) != 0;
+    const int nfull = tail ? nsteps - 1 : nsteps;
+    const int64_t klast = kbeg + (int64_t)(nfull > 0 ? nfull - 1 : 0) * BK;      // last full chunk of this share
+    const int64_t kxlast = kbeg + (int64_t)(nsteps - 1) * BK;
+
+    floatx4 xreg[LT];
+    floatx4 ring[STAGES][4][NT];
+    fetch_x<LT>(X, g.ldx, kbeg, tid, xreg);
+    if (nfull > 0) {
+#pragma unroll
+      for (int u = 0; u < STAGES - 1; ++u) {
+        const int64_t k1 = kbeg + (int64_t)u * BK;
+        fetch_a<MODE, NT, false>(A, g.lda, off, lh, k1 < klast ? k1 : klast, kend, ring[u]);
+      }
     }
-    o[i] = s;
+
+    // one step of the ring, U = position of the consumed chunk (compile-time so that the ring stays in registers)
+#define LQ_GEMM_RING_STEP(U, STEP, PREFETCH)                                                                      \
+  {                                                                                                               \
+    __syncthreads(); /* everyone is done reading the previous X tile */                                           \
+    if constexpr (PREC == PREC_FP32) stash_x<LT>(xs, tid, xreg);                                                  \
+    else stash_x_split<LT>(xh, xl, tid, xreg);                                                                    \
+    __syncthreads();                                                                                              \
+    {                                                                                                             \
+      const int64_t kx = kbeg + (int64_t)((STEP) + 1) * BK;                                                       \
+      fetch_x<LT>(X, g.ldx, kx < kxlast ? kx : kxlast, tid, xreg);                                                \
+    }                                                                                                             \
+    if constexpr (PREFETCH) {                                                                                     \
+      const int64_t k1 = kbeg + (int64_t)((STEP) + STAGES - 1) * BK;                                              \
+      fetch_a<MODE, NT, false>(A, g.lda, off, lh, k1 < klast ? k1 : klast, kend,                                  \
+                               ring[((U) + STAGES - 1) % STAGES]);                                                \
+    }                                                                                                             \
+    multiply_chunk<LT, NT, PREC>(xs, xh, xl, ln, lh, ring[(U)], acc);                                             \
+  }
+    int step0 = 0;
+    for (; step0 + STAGES <= nfull; step0 += STAGES) {
+      LQ_GEMM_RING_STEP(0, step0, true)
+      if constexpr (STAGES > 1) LQ_GEMM_RING_STEP(1, step0 + 1, true)
+      if constexpr (STAGES > 2) LQ_GEMM_RING_STEP(2, step0 + 2, true)
+    }
+    // the remaining full chunks are already in the ring
+    if (step0 < nfull) LQ_GEMM_RING_STEP(0, step0, false)
+    if constexpr (STAGES > 2) {
+      if (step0 + 1 < nfull) LQ_GEMM_RING_STEP(1, step0 + 1, false)
+    }
+    if (tail) {
+      fetch_a<MODE, NT, true>(A, g.lda, off, lh, kbeg + (int64_t)nfull * BK, kend, ring[0]);
+      LQ_GEMM_RING_STEP(0, nfull, false)
+    }
+#undef LQ_GEMM_RING_STEP
+
+    // whole reduction: straight into C; otherwise into this workgroup's partial tile (all SPAN columns)
+    const bool whole = s0 == 0 && s1 == g.ns;
+    const size_t slot = ((size_t)share * g.tiles + tile) * 2 + (gs == share0 ? 0 : 1);
+    float* dst = whole ? g.C + (size_t)z * g.strideC : g.part + slot * (size_t)(32 * LT * SPAN);
+    store_acc<LT, MODE, NT>(dst, whole ? g.ldc : SPAN, whole ? big0 : wave * (32 * NT), whole ? g.big : SPAN, ln, lh,
+                            acc);
+    gs += nsteps;
+  }
+}
+
+// C tile = sum of its partial tiles in step order, for every tile whose reduction was cut between workgroups.
+// gridDim = (tiles, problems, l / 8): one workgroup per 8 rows of a tile, at most two float4 per thread.
+__global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g, int l, int span) {
+  const int t = blockIdx.x, z = blockIdx.y;
+  const int start = z * g.ns, end = start + g.ns;
+  const int w0 = start / g.per_wg, w1 = (end - 1) / g.per_wg;
+  if (w0 == w1) return;                          // stored directly by its only workgroup
+  float* __restrict__ C = g.C + (size_t)z * g.strideC;
+  const int64_t col0 = (int64_t)t * span;
+  const size_t tile_floats = (size_t)l * span;
+  const int quads = span / 4;
+  for (int idx = threadIdx.x; idx < 8 * quads; idx += 256) {
+    const int row = 8 * blockIdx.z + idx / quads, c4 = (idx % quads) * 4;
+    if (col0 + c4 >= g.big) continue;
+    const float* p0 = g.part + (size_t)row * span + c4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int w = w0; w <= w1; ++w) {
+      const size_t slot = ((size_t)w * g.tiles + t) * 2 + (start <= w * g.per_wg ? 0 : 1);
+      const float4 p = *reinterpret_cast<const float4*>(p0 + slot * tile_floats);
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    float* o = C + (size_t)row * g.ldc + col0 + c4;
+    if (col0 + c4 + 4 <= g.big) *reinterpret_cast<float4*>(o) = s;
+    else {
+      const float v[4] = {s.x, s.y, s.z, s.w};
+      for (int e = 0; e < 4 && col0 + c4 + e < g.big; ++e) o[e] = v[e];
+    }
   }
 }
 
@@ -272,16 +379,17 @@ template <int LT, int MODE, int NT, int PREC>
 static void launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
   const size_t lds = PREC == PREC_FP32 ? (size_t)32 * LT * XPITCH * sizeof(float)
                                        : (size_t)2 * 32 * LT * HPITCH * sizeof(__bf16);
-  hipLaunchKernelGGL((wide_gemm_kernel<LT, MODE, NT, PREC>), grid, dim3(256), lds, st, g);
+  constexpr int STAGES = (LT * NT <= 6) ? 3 : 2;    // accumulators + ring must leave two wavefronts per SIMD
+  hipLaunchKernelGGL((wide_gemm_kernel<LT, MODE, NT, PREC, STAGES>), grid, dim3(256), lds, st, g);
 }
 
 template <int MODE, int PREC>
 static int launch_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
   switch (lt) {
-    case 1: launch_one<1, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
-    case 2: launch_one<2, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
-    case 3: launch_one<3, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
-    case 4: launch_one<4, MODE, (MODE == MODE_NT ? 1 : 2), PREC>(g, grid, st); break;
+    case 1: launch_one<1, MODE, 2, PREC>(g, grid, st); break;
+    case 2: launch_one<2, MODE, 2, PREC>(g, grid, st); break;
+    case 3: launch_one<3, MODE, 2, PREC>(g, grid, st); break;
+    case 4: launch_one<4, MODE, 2, PREC>(g, grid, st); break;
     case 5: launch_one<5, MODE, 1, PREC>(g, grid, st); break;
     case 6: launch_one<6, MODE, 1, PREC>(g, grid, st); break;
     case 7: launch_one<7, MODE, 1, PREC>(g, grid, st); break;
@@ -291,39 +399,76 @@ static int launch_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
   return LQ_OK;
 }
 
-int gemm_tile_span(int mode, int lt) { return mode == MODE_NT ? 128 : (lt <= 4 ? 256 : 128); }
+int gemm_tile_span(int lt) { return lt <= 4 ? 256 : 128; }
 
-// Number of K splits for a product: enough workgroups to fill 256 CUs a few times over, chunks that are
-// multiples of 32 and at least 256 long.
-int gemm_choose_splits(int mode, int lt, int64_t big, int64_t K, int batch) {
-  const int64_t tiles = (big + gemm_tile_span(mode, lt) - 1) / gemm_tile_span(mode, lt);
-  const int64_t have = tiles * batch;
-  int64_t s = (1024 + have - 1) / have;
-  const int64_t smax = (K + 255) / 256;
-  if (s > smax) s = smax;
-  if (s > 32) s = 32;
-  if (s < 1) s = 1;
-  return (int)s;
+// Workgroups that are resident at once: two per CU (the kernel is compiled for two wavefronts per SIMD).
+static int resident_workgroups() {
+  static thread_local int cached[16] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 512;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    cached[dev] = 2 * cus;
+  }
+  return cached[dev];
 }
 
-// C = X * op(A) for `batch` problems.  `part` is scratch for splits > 1 (batch * splits * l * ldc floats).
+// Upper bound of the partial-tile scratch: two tiles per workgroup, at most twice the requested workgroups (plus the
+// rounding of the share count to a multiple of 8) run.
+size_t gemm_part_floats(int l, int workgroups) {
+  if (workgroups <= 0) workgroups = resident_workgroups();
+  return (size_t)4 * workgroups * l * gemm_tile_span(l / 32);
+}
+
+// Number of shares along the (problem, step) sequence for `tiles` tile columns.  Shares are dealt to the 8 XCDs in
+// turn, so their number is a multiple of 8; the smallest such number that fills every resident workgroup slot at
+// least once is taken (more shares only add partial tiles), shares of at least 8 steps.  With at least three
+// rounds of whole problems nothing is cut: the tail of the last round is short then and there are no partial tiles.
+static int choose_groups(int64_t tiles, int total, int batch, int workgroups) {
+  if (tiles * batch >= 3 * (int64_t)workgroups) return batch;
+  int64_t g = (workgroups + tiles - 1) / tiles;
+  g = (g + 7) / 8 * 8;
+  while (g > 8 && (total + g - 1) / g < 8) g -= 8;
+  if (g > total) g = total;
+  return (int)std::max<int64_t>(g, 1);
+}
+
+// C = X * op(A) for `batch` problems.  `part` (part_floats floats) is scratch for the partial tiles;
+// gemm_part_floats(l, workgroups) is enough for every shape with at most workgroups / 4 tile columns, and when
+// it is too small for the chosen shares no reduction is cut (every workgroup gets whole tiles).  workgroups = 0: as
+// many as are resident at once; negative: exactly -workgroups shares (for tests).
 int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
                      const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
-                     int splits, float* part, hipStream_t st, int precision) {
+                     float* part, size_t part_floats, hipStream_t st, int precision, int workgroups) {
   if (l % 32 != 0 || l < 32 || l > 256 || big < 1 || K < 1 || batch < 1) return LQ_ERR_ARG;
   if (mode == MODE_NN && (big % 2) != 0) return LQ_ERR_ARG;
+  // lane offsets into A are 32-bit byte offsets
+  if ((mode == MODE_NT ? (uint64_t)big * (uint64_t)lda : (uint64_t)8 * lda + (uint64_t)big) * 4 >= (1ull << 32))
+    return LQ_ERR_SHAPE;
   const int lt = l / 32;
+  const int span = gemm_tile_span(lt);
   GemmArgs g;
-  g.X = X; g.A = A; g.ldx = ldx; g.lda = lda; g.ldc = ldc; g.strideX = strideX; g.strideA = strideA;
-  g.big = big; g.K = K; g.splits = splits;
-  int64_t kchunk = (K + splits - 1) / splits;
-  kchunk = (kchunk + BK - 1) / BK * BK;
-  g.kchunk = kchunk;
-  const size_t out_elems = (size_t)l * ldc;
-  if (splits > 1) { g.C = part; g.strideC = out_elems; }
-  else { g.C = C; g.strideC = strideC; }
-  const int span = gemm_tile_span(mode, lt);
-  const dim3 grid((unsigned)((big + span - 1) / span), (unsigned)splits, (unsigned)batch);
+  g.X = X; g.A = A; g.C = C; g.part = part; g.ldx = ldx; g.lda = lda; g.ldc = ldc;
+  g.strideX = strideX; g.strideA = strideA; g.strideC = strideC;
+  g.big = big; g.K = K;
+  const int64_t tiles = (big + span - 1) / span;
+  const int64_t ns = (K + BK - 1) / BK;
+  if (tiles > (1 << 20) || ns * batch >= (1ll << 31)) return LQ_ERR_SHAPE;
+  g.ns = (int)ns;
+  g.tiles = (int)tiles;
+  g.total = (int)(ns * batch);
+  const int64_t forced = workgroups < 0 ? -(int64_t)workgroups : 0;     // negative: that many shares exactly
+  if (workgroups <= 0) workgroups = resident_workgroups();
+  int64_t groups = forced ? std::min<int64_t>(forced, g.total) : choose_groups(tiles, g.total, batch, workgroups);
+  int64_t per = (g.total + groups - 1) / groups;
+  if (per < 8 && !forced) per = std::min<int64_t>(8, g.total);
+  // every workgroup may leave two partial tiles; without room for them only whole reductions are dealt out
+  const size_t need = (size_t)2 * tiles * ((g.total + per - 1) / per) * l * span;
+  const bool cut = part != nullptr && part_floats >= need && groups > 1 && batch < (1 << 16);
+  g.per_wg = cut ? (int)per : (int)ns;
+  const int64_t ngroups = (g.total + g.per_wg - 1) / g.per_wg;
+  const dim3 grid((unsigned)(tiles * ((ngroups + 7) / 8 * 8)));
   {
     prof::Scope ps((precision == PREC_BF16X3 ? prof::GEMM_SPLIT_BASE : prof::GEMM_BASE) + mode * 8 + (lt - 1), st,
                    2.0 * l * (double)big * (double)K * batch);
@@ -337,12 +482,10 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
     if (rc != LQ_OK) return rc;
   }
   LQ_HIP_TRY(hipGetLastError());
-  if (splits > 1) {
-    prof::Scope ps(prof::SPLITK_REDUCE, st, (double)(splits + 1) * out_elems * 4.0 * batch);
-    const int64_t count4 = (int64_t)(out_elems / 4);
-    const dim3 rgrid((unsigned)((count4 + 255) / 256 < 2048 ? (count4 + 255) / 256 : 2048), (unsigned)batch);
-    hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, dim3(256), 0, st, (const float*)part, C, splits, count4,
-                       out_elems, strideC);
+  if (cut && g.per_wg % g.ns != 0) {
+    prof::Scope ps(prof::SPLITK_REDUCE, st, (double)tiles * batch * l * span * 4.0);
+    hipLaunchKernelGGL(gemm_fixup_kernel, dim3((unsigned)tiles, (unsigned)batch, (unsigned)(l / 8)), dim3(256), 0, st, g,
+                       l, span);
     LQ_HIP_TRY(hipGetLastError());
   }
   return LQ_OK;

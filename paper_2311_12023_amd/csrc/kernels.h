@@ -16,20 +16,23 @@ struct GemmArgs {
   const float* X;
   const float* A;
   float* C;
+  float* part;                        // partial tiles: 2 per workgroup, l x span floats each
   int64_t ldx, lda, ldc;
   size_t strideX, strideA, strideC;   // per-problem strides in floats (0 = shared operand)
   int64_t big;                        // extent of the large output dimension (M or N)
-  int64_t K, kchunk;                  // reduction length and length per split
-  int splits;
+  int64_t K;                          // reduction length
+  int tiles, ns;                      // tile positions along the large dimension, 32-deep reduction steps per problem
+  int total, per_wg;                  // steps of the whole batch, steps per workgroup (share)
 };
 
-int gemm_tile_span(int mode, int lt);
-int gemm_choose_splits(int mode, int lt, int64_t big, int64_t K, int batch);
+int gemm_tile_span(int lt);
+// Scratch (floats) that lets launch_wide_gemm cut tiles between `workgroups` workgroups (<= 0: the default count).
+size_t gemm_part_floats(int l, int workgroups);
 // precision 0: fp32 MFMA.  precision 1: both operands split into bf16 hi + lo on the fly and multiplied with
 // three bf16 MFMAs (hi*hi + hi*lo + lo*hi, fp32 accumulation): products good to about 2^-16 relative.
 int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
                      const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
-                     int splits, float* part, hipStream_t st, int precision = 0);
+                     float* part, size_t part_floats, hipStream_t st, int precision = 0, int workgroups = 0);
 
 // ---- small dense kernels (small_kernels.hip) --------------------------------------------------
 constexpr int GRAM_CHUNKS = 16;

@@ -78,15 +78,6 @@ struct Plan {
   size_t total;
 };
 
-static size_t gemm_part_floats(int l, int64_t ldd, int64_t ldk, int64_t d, int64_t k, int batch) {
-  const int lt = l / 32;
-  const int s_nt = gemm_choose_splits(MODE_NT, lt, d, k, batch);     // output l x d, reduce over k
-  const int s_nn = gemm_choose_splits(MODE_NN, lt, k, d, batch);     // output l x k, reduce over d
-  size_t a = s_nt > 1 ? (size_t)batch * s_nt * l * ldd : 0;
-  size_t b = s_nn > 1 ? (size_t)batch * s_nn * l * ldk : 0;
-  return std::max(a, b);
-}
-
 static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int batch, Plan& pl) {
   pl.d = d; pl.k = k; pl.ldd = up32(d); pl.ldk = up32(k); pl.n = d * k;
   pl.rank = rank; pl.batch = batch; pl.prm = prm; pl.lmax = prm.l1;
@@ -96,8 +87,7 @@ static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int bat
   pl.sr = take(d * 4); pl.sc = take(k * 4); pl.rsr = take(d * 4); pl.rsc = take(k * 4);
   pl.Ya = take((size_t)l1 * pl.ldd * 4); pl.Yb = take((size_t)l1 * pl.ldd * 4);
   pl.Ba = take((size_t)l1 * pl.ldk * 4); pl.Bb = take((size_t)l1 * pl.ldk * 4);
-  pl.gpart_floats = std::max(gemm_part_floats(l1, pl.ldd, pl.ldk, d, k, 1),
-                             gemm_part_floats(lw, pl.ldd, pl.ldk, d, k, batch));
+  pl.gpart_floats = std::max(gemm_part_floats(l1, 0), gemm_part_floats(lw, 0));
   pl.gpart = take(pl.gpart_floats * 4);
   const size_t ll = (size_t)l1 * l1;
   pl.gram_part = take((size_t)batch * GRAM_CHUNKS * ll * 8);
@@ -146,8 +136,8 @@ static int orthonormalize(const Ctx& c, float*& X, float*& Xalt, int l, int64_t 
   if (cholinv_supported(l)) {
     float* Cinv = c.at<float>(c.pl.Ut);
     LQ_TRY(launch_cholinv(G, l, Cinv, batch, c.st));
-    LQ_TRY(launch_wide_gemm(MODE_NN, l, ldx, l, Cinv, l, (size_t)l * l, X, ldx, strideX, Xalt, ldx, strideX, batch, 1,
-                            nullptr, c.st));
+    LQ_TRY(launch_wide_gemm(MODE_NN, l, ldx, l, Cinv, l, (size_t)l * l, X, ldx, strideX, Xalt, ldx, strideX, batch,
+                            nullptr, 0, c.st));
     std::swap(X, Xalt);
     return LQ_OK;
   }
@@ -157,10 +147,8 @@ static int orthonormalize(const Ctx& c, float*& X, float*& Xalt, int l, int64_t 
 
 static int gemm(const Ctx& c, int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t sX,
                 const float* A, int64_t lda, size_t sA, float* C, int64_t ldc, size_t sC, int batch) {
-  int splits = gemm_choose_splits(mode, l / 32, big, K, batch);
-  if (splits > 1 && (size_t)batch * splits * l * ldc > c.pl.gpart_floats) splits = 1;
-  return launch_wide_gemm(mode, l, big, K, X, ldx, sX, A, lda, sA, C, ldc, sC, batch, splits,
-                          c.at<float>(c.pl.gpart), c.st, c.pl.prm.prec);
+  return launch_wide_gemm(mode, l, big, K, X, ldx, sX, A, lda, sA, C, ldc, sC, batch, c.at<float>(c.pl.gpart),
+                          c.pl.gpart_floats, c.st, c.pl.prm.prec);
 }
 
 // Rayleigh-Ritz on the subspace spanned by the rows of Y (orthonormal) with B = Y A:
@@ -174,10 +162,10 @@ static int ritz_rotate(const Ctx& c, int l, const float* Y, float* Y2, size_t sY
   const bool fast = jacobi_fast_supported(l);
   if (fast) LQ_TRY(launch_jacobi_fast(G, l, Ut, lambda, batch, c.st));
   else LQ_TRY(launch_jacobi_eig(G, l, c.at<double>(pl.Vt), Ut, lambda, batch, c.st));
-  LQ_TRY(launch_wide_gemm(MODE_NN, l, pl.ldd, l, Ut, l, (size_t)l * l, Y, pl.ldd, sY, Y2, pl.ldd, sY, batch, 1,
-                          nullptr, c.st));
-  LQ_TRY(launch_wide_gemm(MODE_NN, l, pl.ldk, l, Ut, l, (size_t)l * l, B, pl.ldk, sB, B2, pl.ldk, sB, batch, 1,
-                          nullptr, c.st));
+  LQ_TRY(launch_wide_gemm(MODE_NN, l, pl.ldd, l, Ut, l, (size_t)l * l, Y, pl.ldd, sY, Y2, pl.ldd, sY, batch, nullptr, 0,
+                          c.st));
+  LQ_TRY(launch_wide_gemm(MODE_NN, l, pl.ldk, l, Ut, l, (size_t)l * l, B, pl.ldk, sB, B2, pl.ldk, sB, batch, nullptr, 0,
+                          c.st));
   // Ritz values from the rotated projection itself: sigma_i^2 = |row i of B2|^2
   if (fast) LQ_TRY(launch_row_sumsq(B2, l, pl.k, pl.ldk, sB, lambda, batch, c.st));
   return LQ_OK;
@@ -616,11 +604,18 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
 
 // ---- test hooks (include/lq_testing.h) ----------------------------------------------------------------
 int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
-                      int64_t lda, float* C, int64_t ldc, int splits, float* part, int precision, void* stream) {
-  if (!X || !A || !C || (splits > 1 && !part) || splits < 1) return LQ_ERR_NULL;
-  if (precision != 0 && precision != 1) return LQ_ERR_ARG;
-  return launch_wide_gemm(mode, l, big, K, X, ldx, 0, A, lda, 0, C, ldc, 0, 1, splits, part, (hipStream_t)stream,
-                          precision);
+                      int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
+                      int precision, void* stream) {
+  if (!X || !A || !C) return LQ_ERR_NULL;
+  if ((precision != 0 && precision != 1) || workgroups < -32768 || workgroups > 32768 || batch < 1) return LQ_ERR_ARG;
+  const size_t sA = (size_t)(mode == MODE_NT ? big : K) * lda;
+  return launch_wide_gemm(mode, l, big, K, X, ldx, (size_t)l * ldx, A, lda, sA, C, ldc, (size_t)l * ldc, batch, part,
+                          part_floats, (hipStream_t)stream, precision, workgroups);
+}
+
+size_t lq_test_wide_gemm_part_floats(int l, int workgroups) {
+  if (l % 32 != 0 || l < 32 || l > 256) return 0;
+  return gemm_part_floats(l, workgroups);
 }
 
 int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, float* alt, void* stream) {
@@ -632,7 +627,7 @@ int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scra
   if (cholinv_supported(l) && alt) {
     float* Cinv = reinterpret_cast<float*>(part);       // the Gram partials are dead by now
     LQ_TRY(launch_cholinv(G, l, Cinv, 1, (hipStream_t)stream));
-    LQ_TRY(launch_wide_gemm(MODE_NN, l, ldx, l, Cinv, l, 0, X, ldx, 0, alt, ldx, 0, 1, 1, nullptr, (hipStream_t)stream));
+    LQ_TRY(launch_wide_gemm(MODE_NN, l, ldx, l, Cinv, l, 0, X, ldx, 0, alt, ldx, 0, 1, nullptr, 0, (hipStream_t)stream));
     LQ_HIP_TRY(hipMemcpyAsync(X, alt, (size_t)l * ldx * sizeof(float), hipMemcpyDeviceToDevice, (hipStream_t)stream));
     return LQ_OK;
   }

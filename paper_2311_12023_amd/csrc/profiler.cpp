@@ -40,14 +40,14 @@ Scope::~Scope() {
 }
 
 static const char* const kNames[NUM_CLASSES] = {
-    "wide_gemm_kernel<1,0,1,0>", "wide_gemm_kernel<2,0,1,0>", "wide_gemm_kernel<3,0,1,0>", "wide_gemm_kernel<4,0,1,0>",
+    "wide_gemm_kernel<1,0,2,0>", "wide_gemm_kernel<2,0,2,0>", "wide_gemm_kernel<3,0,2,0>", "wide_gemm_kernel<4,0,2,0>",
     "wide_gemm_kernel<5,0,1,0>", "wide_gemm_kernel<6,0,1,0>", "wide_gemm_kernel<7,0,1,0>", "wide_gemm_kernel<8,0,1,0>",
     "wide_gemm_kernel<1,1,2,0>", "wide_gemm_kernel<2,1,2,0>", "wide_gemm_kernel<3,1,2,0>", "wide_gemm_kernel<4,1,2,0>",
     "wide_gemm_kernel<5,1,1,0>", "wide_gemm_kernel<6,1,1,0>", "wide_gemm_kernel<7,1,1,0>", "wide_gemm_kernel<8,1,1,0>",
-    "splitk_reduce_kernel", "gram_partial_kernel+gram_reduce_kernel", "cholesky_kernel", "trsm_kernel",
+    "gemm_fixup_kernel", "gram_partial_kernel+gram_reduce_kernel", "cholesky_kernel", "trsm_kernel",
     "jacobi_eig_kernel", "lowrank_blockquant_kernel", "scalequant_error_kernel+error_finalize_kernel",
     "residual_kernel", "quantize_fused_kernel", "dequant_kernel", "misc",
-    "wide_gemm_kernel<1,0,1,1>", "wide_gemm_kernel<2,0,1,1>", "wide_gemm_kernel<3,0,1,1>", "wide_gemm_kernel<4,0,1,1>",
+    "wide_gemm_kernel<1,0,2,1>", "wide_gemm_kernel<2,0,2,1>", "wide_gemm_kernel<3,0,2,1>", "wide_gemm_kernel<4,0,2,1>",
     "wide_gemm_kernel<5,0,1,1>", "wide_gemm_kernel<6,0,1,1>", "wide_gemm_kernel<7,0,1,1>", "wide_gemm_kernel<8,0,1,1>",
     "wide_gemm_kernel<1,1,2,1>", "wide_gemm_kernel<2,1,2,1>", "wide_gemm_kernel<3,1,2,1>", "wide_gemm_kernel<4,1,2,1>",
     "wide_gemm_kernel<5,1,1,1>", "wide_gemm_kernel<6,1,1,1>", "wide_gemm_kernel<7,1,1,1>", "wide_gemm_kernel<8,1,1,1>"};

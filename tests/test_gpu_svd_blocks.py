@@ -14,7 +14,9 @@ def env():
     from paper_2311_12023_amd import lq
     L = lq._lib
     vp, i64, it = C.c_void_p, C.c_int64, C.c_int
-    L.lq_test_wide_gemm.argtypes = [it, it, i64, i64, vp, i64, vp, i64, vp, i64, it, vp, it, vp]
+    L.lq_test_wide_gemm.argtypes = [it, it, i64, i64, vp, i64, vp, i64, vp, i64, it, it, vp, C.c_size_t, it, vp]
+    L.lq_test_wide_gemm_part_floats.restype = C.c_size_t
+    L.lq_test_wide_gemm_part_floats.argtypes = [it, it]
     L.lq_test_orthonormalize.argtypes = [vp, it, i64, i64, vp, vp, vp]
     L.lq_test_sym_eig.argtypes = [vp, it, vp, vp, vp, vp]
     L.lq_test_sym_eig_fast.argtypes = [vp, it, vp, vp, vp]
@@ -26,35 +28,47 @@ def up32(x):
     return (x + 31) // 32 * 32
 
 
-@pytest.mark.parametrize("mode,l,big,K,splits", [
-    (0, 32, 200, 160, 1), (0, 64, 768, 768, 3), (0, 96, 130, 1040, 2), (0, 128, 1000, 4096, 8), (0, 256, 300, 512, 1),
-    (1, 32, 208, 150, 1), (1, 64, 768, 768, 3), (1, 96, 1040, 131, 2), (1, 128, 4096, 1000, 8), (1, 256, 512, 300, 1),
-    (1, 160, 96, 32, 1)])
+# wgs: workgroups the reduction steps are dealt out to (None: no scratch, reductions are never cut; 0: device default).
+# The cases cover shares much shorter than one reduction, shares that run over several problems of a batch with cut
+# ends, a single workgroup, and shapes that are ragged against the 256 / 128-column tiles and the 32-deep steps.
+@pytest.mark.parametrize("mode,l,big,K,batch,wgs", [
+    (0, 32, 200, 160, 1, None), (0, 64, 768, 768, 1, 5), (0, 96, 130, 1040, 3, 7), (0, 128, 1000, 4096, 1, 0),
+    (0, 256, 300, 512, 2, None), (0, 96, 1500, 700, 5, 20), (0, 96, 1500, 700, 1, 1), (0, 96, 520, 4096, 1, 64),
+    (0, 96, 300, 1000, 7, 6),
+    (1, 32, 208, 150, 1, None), (1, 64, 768, 768, 1, 5), (1, 96, 1040, 131, 3, 7), (1, 128, 4096, 1000, 1, 0),
+    (1, 256, 512, 300, 2, None), (1, 160, 96, 32, 1, None), (1, 96, 1500, 700, 5, 20), (1, 96, 520, 4096, 1, 64),
+    (1, 96, 300, 1000, 7, 6)])
 @pytest.mark.parametrize("precision", [0, 1])
-def test_wide_gemm(env, mode, l, big, K, splits, precision):
+def test_wide_gemm(env, mode, l, big, K, batch, wgs, precision):
     torch, lq, L = env
     rng = np.random.default_rng(l * 7 + big + mode)
     ldx = up32(K)
-    x = np.zeros((l, ldx), np.float32)
-    x[:, :K] = rng.standard_normal((l, K))
-    a = rng.standard_normal((big, K) if mode == 0 else (K, big)).astype(np.float32)
+    x = np.zeros((batch, l, ldx), np.float32)
+    x[:, :, :K] = rng.standard_normal((batch, l, K))
+    a = rng.standard_normal((batch, big, K) if mode == 0 else (batch, K, big)).astype(np.float32)
     ldc = up32(big)
     xt, at = torch.from_numpy(x).cuda(), torch.from_numpy(a).cuda()
-    ct = torch.full((l, ldc), 7.0, dtype=torch.float32, device="cuda")
-    part = torch.empty(max(splits, 1) * l * ldc, dtype=torch.float32, device="cuda")
-    rc = L.lq_test_wide_gemm(mode, l, big, K, xt.data_ptr(), ldx, at.data_ptr(), a.shape[1], ct.data_ptr(), ldc, splits,
-                             part.data_ptr(), precision, None)
+    ct = torch.full((batch, l, ldc), 7.0, dtype=torch.float32, device="cuda")
+    nfl = 0 if wgs is None else L.lq_test_wide_gemm_part_floats(l, wgs)
+    part = torch.full((max(nfl, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    rc = L.lq_test_wide_gemm(mode, l, big, K, xt.data_ptr(), ldx, at.data_ptr(), a.shape[2], ct.data_ptr(), ldc, batch,
+                             wgs or 0, part.data_ptr() if nfl else None, nfl, precision, None)
     assert rc == 0
     torch.cuda.synchronize()
     got = ct.cpu().numpy()
-    ref = x[:, :K].astype(np.float64) @ (a.T if mode == 0 else a).astype(np.float64)
+    a64 = a.astype(np.float64)
+    ref = np.matmul(x[:, :, :K].astype(np.float64), a64.transpose(0, 2, 1) if mode == 0 else a64)
     scale = np.sqrt(K)
     # fp32 MFMA: rounding of the accumulation only.  Split bf16: each product carries about 2^-16 relative error
-    assert np.max(np.abs(got[:, :big] - ref)) < (2e-5 if precision == 0 else 1.5e-4) * scale
+    assert np.max(np.abs(got[:, :, :big] - ref)) < (2e-5 if precision == 0 else 1.5e-4) * scale
     if precision == 1:
-        assert np.sqrt(np.mean((got[:, :big] - ref) ** 2)) < 2e-5 * scale
-    if splits == 1:
-        assert np.all(got[:, big:] == 7.0)          # columns past the matrix are never written
+        assert np.sqrt(np.mean((got[:, :, :big] - ref) ** 2)) < 2e-5 * scale
+    assert np.all(got[:, :, big:] == 7.0)           # columns past the matrix are never written
+    # same call again: the summation order is fixed, so the result is too
+    ct2 = torch.full((batch, l, ldc), 7.0, dtype=torch.float32, device="cuda")
+    rc = L.lq_test_wide_gemm(mode, l, big, K, xt.data_ptr(), ldx, at.data_ptr(), a.shape[2], ct2.data_ptr(), ldc, batch,
+                             wgs or 0, part.data_ptr() if nfl else None, nfl, precision, None)
+    assert rc == 0 and torch.equal(ct, ct2)
 
 
 @pytest.mark.parametrize("use_alt", [True, False])
