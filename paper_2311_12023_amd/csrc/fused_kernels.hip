@@ -23,6 +23,57 @@ constexpr int TN = 128;    // tile columns
 constexpr int PP = TN + 4; // pitch of the product tile in LDS
 constexpr int KC = 32;     // rank chunk staged in LDS
 constexpr int NTHR1 = 512; // threads of the phase-1 workgroup: 8 wavefronts, one 32x32 MFMA tile each
+constexpr int KC2 = 64;    // rank chunk of the split-precision product
+constexpr int KP = KC2 + 8;// LDS row pitch of its operand planes in bf16 elements (144 B: conflict-free b128 reads)
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// ------------------------------------------------------------------------------------------------
+// Split-precision operands of L1 L2 = Y_r^T B_r: every factor entry x is stored as bf16 hi + bf16 lo
+// (x = hi + lo + O(2^-17 x)), transposed so that the reduction index is contiguous:
+//   plane[i][p], i < rows_pad (zero rows past the matrix), p < RK = round_up16(rank) (zeros past the rank);
+// per problem: Y hi, Y lo (dpad x RK each), then B hi, B lo (kpad x RK each).
+int64_t packed_rows_y(int64_t d) { return (d + TM - 1) / TM * TM; }
+int64_t packed_rows_b(int64_t k) { return (k + TN - 1) / TN * TN; }
+int packed_rank(int rank) { return (rank + 15) / 16 * 16; }
+size_t packed_factor_elems(int64_t d, int64_t k, int rank) {
+  return (size_t)2 * (packed_rows_y(d) + packed_rows_b(k)) * packed_rank(rank);
+}
+
+__global__ __launch_bounds__(256) void pack_factors_kernel(PhaseArgs a, int64_t dpad, int64_t kpad, int rk) {
+  const int z = blockIdx.y;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;          // row of the packed planes, Y rows first
+  if (i >= dpad + kpad) return;
+  const bool isy = i < dpad;
+  const int64_t r = isy ? i : i - dpad, lim = isy ? a.d : a.k, ld = isy ? a.ldy : a.ldb;
+  const float* src = isy ? a.Y + (size_t)z * a.strideY : a.B + (size_t)z * a.strideB;
+  __bf16* base = reinterpret_cast<__bf16*>(a.packed) + (size_t)z * a.stridePacked + (isy ? 0 : (size_t)2 * dpad * rk);
+  __bf16* hi = base + (size_t)r * rk;
+  __bf16* lo = hi + (size_t)(isy ? dpad : kpad) * rk;
+  for (int p0 = 0; p0 < rk; p0 += 8) {
+    bf16x8 h, l;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float x = (r < lim && p0 + e < a.rank) ? src[(size_t)(p0 + e) * ld + r] : 0.0f;
+      const __bf16 xh = (__bf16)x;
+      h[e] = xh;
+      l[e] = (__bf16)(x - (float)xh);
+    }
+    *reinterpret_cast<bf16x8*>(hi + p0) = h;
+    *reinterpret_cast<bf16x8*>(lo + p0) = l;
+  }
+}
+
+int launch_pack_factors(const PhaseArgs& a, hipStream_t st) {
+  const int64_t dpad = packed_rows_y(a.d), kpad = packed_rows_b(a.k);
+  prof::Scope ps(prof::MISC, st, (double)(a.d + a.k) * a.rank * 8.0 * a.batch);
+  hipLaunchKernelGGL(pack_factors_kernel, dim3((unsigned)((dpad + kpad + 255) / 256), (unsigned)a.batch), dim3(256), 0,
+                     st, a, dpad, kpad, packed_rank(a.rank));
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
 
 // Stores the 4 codes of one quad.  2, 4, 8 bits: 1, 2, 4 bytes per lane, contiguous across lanes.  3 bits: the
 // four lanes of a 16-weight run gather their 12-bit pieces into the run's 48-bit word and three of them store
@@ -130,49 +181,26 @@ __device__ __forceinline__ void phase1_dispatch_block(const PhaseArgs& a, int bl
   }
 }
 
-template <bool WITH_ERR>
+// SPLIT: L1 L2 from the packed bf16 hi/lo planes with three v_mfma_f32_32x32x16_bf16 per 16-deep group
+// (hi*hi + hi*lo + lo*hi, fp32 accumulation; products good to about 2^-16 relative) instead of fp32 MFMAs.
+template <bool WITH_ERR, bool SPLIT>
 __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) {
-  // The operand chunks (Y: KC x TM, B: KC x TN) and the product tile share one LDS buffer: the product is
-  // written after the last MFMA has read its operands.
-  __shared__ __attribute__((aligned(16))) float smem[TM * PP];
+  // The operand chunks and the product tile share one LDS buffer: the product is written after the last MFMA has
+  // read its operands.  fp32: Y chunk KC x TM, B chunk KC x TN.  Split: four planes (Y hi, Y lo: TM rows; B hi, B lo:
+  // TN rows) of KC2 reduction indices, pitch KP.
+  constexpr int SMEM_FLOATS = SPLIT ? ((2 * (TM + TN) * KP * 2 + 3) / 4 > TM * PP ? (2 * (TM + TN) * KP * 2 + 3) / 4 : TM * PP)
+                                    : TM * PP;
+  __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
   __shared__ LdsTables s_tab;
-  float (*ys)[TM] = reinterpret_cast<float (*)[TM]>(smem);
-  float (*bs)[TN] = reinterpret_cast<float (*)[TN]>(smem + KC * TM);
   float* pt = smem;
   static_assert(KC * TM + KC * TN <= TM * PP, "operand chunks must fit in the product tile");
   // problem index fastest: the workgroups that share a tile of W run together and hit it in L2
   const int z = blockIdx.x, tid = threadIdx.x;
   const LoopProblem pr = a.prob[z];
   const int64_t r0 = (int64_t)blockIdx.z * TM, c0 = (int64_t)blockIdx.y * TN;
-  const float* __restrict__ Y = a.Y + (size_t)z * a.strideY;
-  const float* __restrict__ B = a.B + (size_t)z * a.strideB;
   const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
   const int wr = wave >> 2, wc = wave & 3;      // 2 x 4 grid of 32x32 tiles
 
-  // operand chunk staging through registers, 128-bit pieces: piece idx = tid + 512*i of the chunk.  The wide
-  // bases have at least round_up32(rank) rows and zero-padded leading dimensions, so only the column offset
-  // needs clamping; rows past `rank` and columns past the matrix are replaced by zeros after the load.
-  floatx4 yst[KC * TM / (4 * NTHR1)], bst[KC * TN / (4 * NTHR1)];
-  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
-  auto fetch_chunk = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < KC * TM / (4 * NTHR1); ++i) {
-      const int idx = tid + NTHR1 * i, kk = idx / (TM / 4), rr = 4 * (idx % (TM / 4));
-      const int64_t off = r0 + rr;
-      const bool ok = k0 + kk < a.rank && off < a.d;
-      const floatx4 v = *reinterpret_cast<const floatx4*>(Y + (size_t)(k0 + kk) * a.ldy + (off + 4 <= a.ldy ? off : a.ldy - 4));
-      yst[i] = ok ? v : zero4;
-    }
-#pragma unroll
-    for (int i = 0; i < KC * TN / (4 * NTHR1); ++i) {
-      const int idx = tid + NTHR1 * i, kk = idx / (TN / 4), cc = 4 * (idx % (TN / 4));
-      const int64_t off = c0 + cc;
-      const bool ok = k0 + kk < a.rank && off < a.k;
-      const floatx4 v = *reinterpret_cast<const floatx4*>(B + (size_t)(k0 + kk) * a.ldb + (off + 4 <= a.ldb ? off : a.ldb - 4));
-      bst[i] = ok ? v : zero4;
-    }
-  };
-  fetch_chunk(0);
   // code-book tables of this problem's bit width (visible after the barriers of the product stage)
   load_tables_slot_nosync(a.tables, pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3, s_tab);
   // this lane's 4 quads of W, fetched now so that the loads overlap the MFMA stage
@@ -189,27 +217,103 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) 
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
 
-  for (int k0 = 0; k0 < a.rank; k0 += KC) {
-    __syncthreads();
-    // rows past `rank` and columns past the matrix are zero (the wide bases hold more than `rank` rows; only
-    // the leading ones form L1 L2)
+  if constexpr (SPLIT) {
+    __bf16* planes = reinterpret_cast<__bf16*>(smem);          // [Yh | Yl | Bh | Bl], rows x KP
+    const int rk = (a.rank + 15) / 16 * 16;
+    const int64_t dpad = (a.d + TM - 1) / TM * TM, kpad = (a.k + TN - 1) / TN * TN;
+    const __bf16* gy = reinterpret_cast<const __bf16*>(a.packed) + (size_t)z * a.stridePacked;
+    const __bf16* gb = gy + (size_t)2 * dpad * rk;
+    // piece idx = tid + 512 i, i < 6: 16 bytes (8 reduction indices) of one row of one plane
+    constexpr int PIECES = 2 * (TM + TN) * (KC2 / 8) / NTHR1;
+    floatx4 st[PIECES];
+    const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    auto fetch_planes = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < KC * TM / (4 * NTHR1); ++i) {
-      const int idx = tid + NTHR1 * i;
-      *reinterpret_cast<floatx4*>(&ys[idx / (TM / 4)][4 * (idx % (TM / 4))]) = yst[i];
+      for (int i = 0; i < PIECES; ++i) {
+        const int idx = tid + NTHR1 * i;
+        const int q = idx & 7, rowall = idx >> 3;            // rowall: 0..TM-1 Yh, TM..2TM-1 Yl, then TN Bh, TN Bl
+        const bool isy = rowall < 2 * TM;
+        const int rr = isy ? rowall : rowall - 2 * TM;
+        const int rows = isy ? TM : TN;
+        const int plane = rr >= rows ? 1 : 0, row = rr - plane * rows;
+        const __bf16* g = isy ? gy + ((size_t)plane * dpad + r0 + row) * rk : gb + ((size_t)plane * kpad + c0 + row) * rk;
+        st[i] = (k0 + 8 * q < rk) ? *reinterpret_cast<const floatx4*>(g + k0 + 8 * q) : zero4;
+      }
+    };
+    fetch_planes(0);
+    for (int k0 = 0; k0 < rk; k0 += KC2) {
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) {
+        const int idx = tid + NTHR1 * i;
+        *reinterpret_cast<floatx4*>(planes + (size_t)(idx >> 3) * KP + 8 * (idx & 7)) = st[i];
+      }
+      __syncthreads();
+      if (k0 + KC2 < rk) fetch_planes(k0 + KC2);
+      const __bf16* yh = planes + (size_t)(32 * wr + ln) * KP + 8 * lh;
+      const __bf16* yl = yh + (size_t)TM * KP;
+      const __bf16* bh = planes + (size_t)(2 * TM + 32 * wc + ln) * KP + 8 * lh;
+      const __bf16* bl = bh + (size_t)TN * KP;
+#pragma unroll
+      for (int kg = 0; kg < KC2 / 16; ++kg) {
+        if (k0 + 16 * kg < rk) {
+          const bf16x8 ah = *reinterpret_cast<const bf16x8*>(yh + 16 * kg), al = *reinterpret_cast<const bf16x8*>(yl + 16 * kg);
+          const bf16x8 vh = *reinterpret_cast<const bf16x8*>(bh + 16 * kg), vl = *reinterpret_cast<const bf16x8*>(bl + 16 * kg);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh, acc, 0, 0, 0);
+        }
+      }
     }
+  } else {
+    float (*ys)[TM] = reinterpret_cast<float (*)[TM]>(smem);
+    float (*bs)[TN] = reinterpret_cast<float (*)[TN]>(smem + KC * TM);
+    const float* __restrict__ Y = a.Y + (size_t)z * a.strideY;
+    const float* __restrict__ B = a.B + (size_t)z * a.strideB;
+    // operand chunk staging through registers, 128-bit pieces: piece idx = tid + 512*i of the chunk.  The wide
+    // bases have at least round_up32(rank) rows and zero-padded leading dimensions, so only the column offset
+    // needs clamping; rows past `rank` and columns past the matrix are replaced by zeros after the load.
+    floatx4 yst[KC * TM / (4 * NTHR1)], bst[KC * TN / (4 * NTHR1)];
+    const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    auto fetch_chunk = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < KC * TN / (4 * NTHR1); ++i) {
-      const int idx = tid + NTHR1 * i;
-      *reinterpret_cast<floatx4*>(&bs[idx / (TN / 4)][4 * (idx % (TN / 4))]) = bst[i];
-    }
-    __syncthreads();
-    if (k0 + KC < a.rank) fetch_chunk(k0 + KC);
+      for (int i = 0; i < KC * TM / (4 * NTHR1); ++i) {
+        const int idx = tid + NTHR1 * i, kk = idx / (TM / 4), rr = 4 * (idx % (TM / 4));
+        const int64_t off = r0 + rr;
+        const bool ok = k0 + kk < a.rank && off < a.d;
+        const floatx4 v = *reinterpret_cast<const floatx4*>(Y + (size_t)(k0 + kk) * a.ldy + (off + 4 <= a.ldy ? off : a.ldy - 4));
+        yst[i] = ok ? v : zero4;
+      }
 #pragma unroll
-    for (int s = 0; s < KC / 2; ++s) {
-      const float av = ys[2 * s + lh][32 * wr + ln];
-      const float bv = bs[2 * s + lh][32 * wc + ln];
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+      for (int i = 0; i < KC * TN / (4 * NTHR1); ++i) {
+        const int idx = tid + NTHR1 * i, kk = idx / (TN / 4), cc = 4 * (idx % (TN / 4));
+        const int64_t off = c0 + cc;
+        const bool ok = k0 + kk < a.rank && off < a.k;
+        const floatx4 v = *reinterpret_cast<const floatx4*>(B + (size_t)(k0 + kk) * a.ldb + (off + 4 <= a.ldb ? off : a.ldb - 4));
+        bst[i] = ok ? v : zero4;
+      }
+    };
+    fetch_chunk(0);
+    for (int k0 = 0; k0 < a.rank; k0 += KC) {
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < KC * TM / (4 * NTHR1); ++i) {
+        const int idx = tid + NTHR1 * i;
+        *reinterpret_cast<floatx4*>(&ys[idx / (TM / 4)][4 * (idx % (TM / 4))]) = yst[i];
+      }
+#pragma unroll
+      for (int i = 0; i < KC * TN / (4 * NTHR1); ++i) {
+        const int idx = tid + NTHR1 * i;
+        *reinterpret_cast<floatx4*>(&bs[idx / (TN / 4)][4 * (idx % (TN / 4))]) = bst[i];
+      }
+      __syncthreads();
+      if (k0 + KC < a.rank) fetch_chunk(k0 + KC);
+#pragma unroll
+      for (int s = 0; s < KC / 2; ++s) {
+        const float av = ys[2 * s + lh][32 * wr + ln];
+        const float bv = bs[2 * s + lh][32 * wc + ln];
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+      }
     }
   }
   __syncthreads();          // all operand reads done before the product overwrites the buffer
@@ -230,8 +334,14 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) 
 int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st) {
   const dim3 grid((unsigned)a.batch, (unsigned)((a.k + TN - 1) / TN), (unsigned)((a.d + TM - 1) / TM));
   prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st, (double)a.d * a.k * (2.0 * a.rank + 10.0) * a.batch);   // flops
-  if (with_err) hipLaunchKernelGGL(lowrank_blockquant_kernel<true>, grid, dim3(NTHR1), 0, st, a);
-  else hipLaunchKernelGGL(lowrank_blockquant_kernel<false>, grid, dim3(NTHR1), 0, st, a);
+  const bool split = a.packed != nullptr;
+  if (split) {
+    if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, true>), grid, dim3(NTHR1), 0, st, a);
+    else hipLaunchKernelGGL((lowrank_blockquant_kernel<false, true>), grid, dim3(NTHR1), 0, st, a);
+  } else {
+    if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, false>), grid, dim3(NTHR1), 0, st, a);
+    else hipLaunchKernelGGL((lowrank_blockquant_kernel<false, false>), grid, dim3(NTHR1), 0, st, a);
+  }
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }

@@ -93,6 +93,8 @@ struct PhaseArgs {
   const float* B;          // wide projected matrix, ld = ldb, stride strideB
   int64_t ldy, ldb;
   size_t strideY, strideB;
+  uint16_t* packed;        // bf16 hi/lo planes of the factors (launch_pack_factors) or NULL: fp32 product
+  size_t stridePacked;     // elements
   const float* rsr;        // 1/sqrt(row_w) (d) or NULL
   const float* rsc;        // 1/sqrt(col_w) (k) or NULL
   const float* sr;         // sqrt(row_w) or NULL
@@ -112,6 +114,10 @@ struct PhaseArgs {
   int batch;
 };
 
+// Splits the first `rank` rows of Y and B into the bf16 hi/lo planes that phase 1 multiplies when a.packed is set
+// (a.packed must hold packed_factor_elems(d, k, rank) elements per problem).
+size_t packed_factor_elems(int64_t d, int64_t k, int rank);
+int launch_pack_factors(const PhaseArgs& a, hipStream_t st);
 // Phase 1: T = W - L1 L2 tile by tile (MFMA), block absmax, codes and, with_err, the per-block error sums
 // (without them phase 2 still produces scale indices and v, but its error output is meaningless).
 int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st);

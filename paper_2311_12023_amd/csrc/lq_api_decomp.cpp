@@ -74,6 +74,7 @@ struct Plan {
   size_t Yw, Yw2, strideYw;             // floats
   size_t Bw, Bw2, strideBw;
   size_t codes, strideCodes, blk, strideBlk, sidx, strideSidx, v, strideV, epart, strideEpart;
+  size_t packed, stridePacked;          // bf16 elements per problem (0: fp32 phase 1)
   size_t gpart_floats;
   size_t total;
 };
@@ -107,6 +108,8 @@ static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int bat
   pl.strideSidx = up256(n / 16);            pl.sidx = take(pl.strideSidx * batch);
   pl.strideV = up256(n / 256 * 4 + 4) / 4;  pl.v = take(pl.strideV * 4 * batch);
   pl.strideEpart = up256((size_t)err_partials_per_problem(pl.n, 16) * 8) / 8; pl.epart = take(pl.strideEpart * 8 * batch);
+  pl.stridePacked = prm.prec ? up256(packed_factor_elems(d, k, rank) * 2) / 2 : 0;
+  pl.packed = take(pl.stridePacked * 2 * batch);
   pl.total = off;
 }
 
@@ -362,6 +365,12 @@ struct Loop {
     a.R = nullptr; a.Qd = nullptr; a.err_out = errs + (t - 1);
     // the error of an iteration costs extra arithmetic per weight: only computed when somebody looks at it
     const bool with_err = want_trace || early_stop || t == iters;
+    if (pl.stridePacked) {
+      a.packed = c->at<uint16_t>(pl.packed); a.stridePacked = pl.stridePacked;
+      LQ_TRY(launch_pack_factors(a, c->st));
+    } else {
+      a.packed = nullptr; a.stridePacked = 0;
+    }
     LQ_TRY(launch_lowrank_blockquant(a, with_err, c->st));
     LQ_TRY(launch_scalequant_error(a, min_block, c->st));
     done = t;
