@@ -92,8 +92,8 @@ __device__ __forceinline__ void store_quad_codes(uint8_t* __restrict__ codes, in
     const int sub = threadIdx.x & 3;
     uint32_t lo = sub < 2 ? (w << (12 * sub)) : (sub == 2 ? (w << 24) : 0u);        // bits 0..31 of the run word
     uint32_t hi = sub == 2 ? (w >> 8) : (sub == 3 ? (w << 4) : 0u);                 // bits 32..47
-    lo |= __shfl_xor(lo, 1); hi |= __shfl_xor(hi, 1);
-    lo |= __shfl_xor(lo, 2); hi |= __shfl_xor(hi, 2);
+    lo |= dpp_move_u32<DPP_QUAD_XOR1>(lo); hi |= dpp_move_u32<DPP_QUAD_XOR1>(hi);
+    lo |= dpp_move_u32<DPP_QUAD_XOR2>(lo); hi |= dpp_move_u32<DPP_QUAD_XOR2>(hi);
     if (live && sub < 3) {
       const uint16_t piece = sub == 0 ? (uint16_t)lo : (sub == 1 ? (uint16_t)(lo >> 16) : (uint16_t)hi);
       *reinterpret_cast<uint16_t*>(codes + (quad >> 2) * 6 + 2 * sub) = piece;
@@ -112,6 +112,8 @@ __device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const
   const int tid = threadIdx.x;
   uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
   BlockRec* blk = a.blk + (size_t)z * a.strideBlk;
+  // quad index of this lane's first quad; the next ones are NTHR1 / 32 rows further down
+  const int64_t quad0 = ((r0 + (tid >> 5)) * a.k + c0 + 4 * (tid & 31)) >> 2, quad_step = (NTHR1 / 32) * (a.k >> 2);
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const int qid = tid + NTHR1 * u;
@@ -137,9 +139,7 @@ __device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const
 #pragma unroll
       for (int e = 0; e < 4; ++e) t[e] = fv[e] - pv[e];
     }
-    float amax = fmaxf(fmaxf(fabsf(t[0]), fabsf(t[1])), fmaxf(fabsf(t[2]), fabsf(t[3])));
-#pragma unroll
-    for (int off = 1; off < QPB; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    const float amax = group_max_lanes<QPB>(fmaxf(fmaxf(fabsf(t[0]), fabsf(t[1])), fmaxf(fabsf(t[2]), fabsf(t[3]))));
     const float rcp = safe_reciprocal(amax);
     uint32_t c[4];
     float e2 = 0.f, eq = 0.f, q2 = 0.f;
@@ -154,13 +154,8 @@ __device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const
         q2 = fmaf(w[e] * q, q, q2);
       }
     }
-    if (WITH_ERR) {
-#pragma unroll
-      for (int off = 1; off < QPB; off <<= 1) {
-        e2 += __shfl_xor(e2, off); eq += __shfl_xor(eq, off); q2 += __shfl_xor(q2, off);
-      }
-    }
-    const int64_t quad = ((int64_t)row * a.k + col) >> 2;
+    if (WITH_ERR) { e2 = group_sum_lanes<QPB>(e2); eq = group_sum_lanes<QPB>(eq); q2 = group_sum_lanes<QPB>(q2); }
+    const int64_t quad = quad0 + (int64_t)u * quad_step;
     store_quad_codes<BITS>(codes, quad, c, live);
     if (live && (cq & (QPB - 1)) == 0) {
       BlockRec rec; rec.s = amax; rec.e2 = e2; rec.eq = eq; rec.q2 = q2;

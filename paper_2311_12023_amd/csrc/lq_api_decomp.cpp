@@ -669,6 +669,7 @@ int lq_test_bucket_code(int bits, float x) {
   if (!(std::fmaf(x, 256.0f, 256.0f) >= 0.0f)) j = 0;   // NaN and negatives as the device's conversion treats them
   j = j < 0 ? 0 : (j > 511 ? 511 : j);
   const int c0 = t.lut[slot][j];
+  if (bits == 4) return c0 + (x >= t.thr[slot][c0]);          // one threshold per bucket at most
   return c0 + (x >= t.thr[slot][c0]) + (x >= t.thr[slot][c0 + 1]);
 }
 

@@ -49,8 +49,9 @@ __device__ inline void load_tables(const DevTables* __restrict__ tab, LdsTables&
 
 // Nearest code with ties to the lower index = number of thresholds <= x.
 // 2 and 3 bits: the thresholds live in registers and are counted.  4 and 8 bits: a 512-bucket table in LDS
-// gives the count of thresholds safely below x's bucket and at most two thresholds remain to be compared
-// (NaN compares false everywhere and lands on code 0 either way).
+// gives the count of thresholds safely below x's bucket; at most two thresholds (8 bits) or one (4 bits, whose
+// thresholds are more than twenty buckets apart) remain to be compared.  NaN compares false everywhere and lands
+// on code 0 either way.
 template <int BITS>
 struct Thresholds {
   float r[(1 << BITS) - 1];
@@ -65,6 +66,7 @@ struct Thresholds {
     return c;
   }
 };
+template <int COMPARES>
 struct BucketSearch {
   const LdsTables& t;
   __device__ explicit BucketSearch(const LdsTables& tt) : t(tt) {}
@@ -72,11 +74,46 @@ struct BucketSearch {
     int j = (int)fmaf(x, 256.0f, 256.0f);
     j = j < 0 ? 0 : (j > 511 ? 511 : j);
     const uint32_t c0 = t.lut[j];
-    return c0 + ((x >= t.thr[c0]) ? 1u : 0u) + ((x >= t.thr[c0 + 1]) ? 1u : 0u);
+    uint32_t c = c0 + ((x >= t.thr[c0]) ? 1u : 0u);
+    if constexpr (COMPARES == 2) c += (x >= t.thr[c0 + 1]) ? 1u : 0u;
+    return c;
   }
 };
-template <> struct Thresholds<4> : BucketSearch { __device__ explicit Thresholds(const LdsTables& tt) : BucketSearch(tt) {} };
-template <> struct Thresholds<8> : BucketSearch { __device__ explicit Thresholds(const LdsTables& tt) : BucketSearch(tt) {} };
+template <> struct Thresholds<4> : BucketSearch<1> { __device__ explicit Thresholds(const LdsTables& tt) : BucketSearch<1>(tt) {} };
+template <> struct Thresholds<8> : BucketSearch<2> { __device__ explicit Thresholds(const LdsTables& tt) : BucketSearch<2>(tt) {} };
+
+// ---- reductions over the QPB = 4, 8, 16 or 32 consecutive lanes that hold one block (aligned groups) ----
+// Cross-lane moves by DPP: quad_perm for the two steps inside a quad; after those every quad is uniform, so the
+// mirror of a half row swaps the two quads of an 8-lane group and the mirror of a row the two halves of a 16-lane
+// group.  Only the last step of a 32-lane group goes through the LDS crossbar.
+constexpr int DPP_QUAD_XOR1 = 0xB1, DPP_QUAD_XOR2 = 0x4E, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_MIRROR = 0x140;
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, CTRL, 0xf, 0xf, true);
+}
+
+template <int QPB>
+__device__ __forceinline__ float group_max_lanes(float x) {
+  x = fmaxf(x, dpp_move<DPP_QUAD_XOR1>(x));
+  x = fmaxf(x, dpp_move<DPP_QUAD_XOR2>(x));
+  if constexpr (QPB >= 8) x = fmaxf(x, dpp_move<DPP_ROW_HALF_MIRROR>(x));
+  if constexpr (QPB >= 16) x = fmaxf(x, dpp_move<DPP_ROW_MIRROR>(x));
+  if constexpr (QPB >= 32) x = fmaxf(x, __shfl_xor(x, 16));
+  return x;
+}
+template <int QPB>
+__device__ __forceinline__ float group_sum_lanes(float x) {
+  x += dpp_move<DPP_QUAD_XOR1>(x);
+  x += dpp_move<DPP_QUAD_XOR2>(x);
+  if constexpr (QPB >= 8) x += dpp_move<DPP_ROW_HALF_MIRROR>(x);
+  if constexpr (QPB >= 16) x += dpp_move<DPP_ROW_MIRROR>(x);
+  if constexpr (QPB >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
 
 __device__ inline float run_absmax(const float (&t)[16]) {
   float m = 0.0f;

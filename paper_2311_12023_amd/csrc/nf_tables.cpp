@@ -92,7 +92,10 @@ static void build_tables(HostTables& t) {
         if ((double)t.thr[s][i] <= lo) ++below;
         if ((double)t.thr[s][i] <= hi || j == 511) ++upto;
       }
-      if (upto - below > 2) below = upto - 2;   // cannot happen for NF code-books (checked by the tests)
+      // the search compares one threshold (4 bits) or two (8 bits) after the table; more candidates per bucket
+      // cannot happen for NF code-books (checked by the tests)
+      const int compares = widths[s] == 4 ? 1 : 2;
+      if (upto - below > compares) below = upto - compares;
       t.lut[s][j] = (uint8_t)below;
     }
   }
