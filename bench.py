@@ -80,6 +80,10 @@ def main() -> int:
     ap.add_argument("--overlap", type=int, default=3,
                     help="matrices decomposed concurrently (host threads, each with its own stream and workspace)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event timing")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one plain elementwise kernel that reads and writes exactly 1 GiB each, so that a "
+                         "counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) of this command holds a dispatch of "
+                         "known HBM traffic to scale the counters by")
     ap.add_argument("--streams", type=int, default=0, help="lq_svd_params.streams (0 = library default)")
     ap.add_argument("--gemm-mode", type=int, default=0, help="lq_svd_params.gemm_mode (0 = library default)")
     args = ap.parse_args()
@@ -105,6 +109,12 @@ def main() -> int:
     streams = [torch.cuda.Stream(device=dev) for _ in range(nthreads)]
     order = sorted(range(len(mats)), key=lambda i: -mats[i].numel())      # largest first
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 2.0, out=dst)          # one elementwise kernel: 1 GiB in, 1 GiB out
+        torch.cuda.synchronize()
+        del src, dst
 
     import queue
     import threading

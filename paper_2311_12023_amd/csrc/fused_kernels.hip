@@ -410,77 +410,110 @@ int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st) {
 // ------------------------------------------------------------------------------------------------
 // Phase 3: one quad (4 consecutive weights) per lane and step, so each wavefront instruction reads / writes
 // 1 KB of contiguous fp32.
-// U quads per lane and step, all loads issued before the first use: the kernel is bound by the bytes each CU keeps
-// in flight.
-template <int BITS>
-__device__ inline void phase3_body(const PhaseArgs& a, const LoopProblem& pr, int z, const float* s_code) {
-  constexpr int U = 4;
-  const int64_t nquads = (a.d * a.k) >> 2;
+// A workgroup takes a stretch of 1024 quads (U = 4 per lane) of W, keeps it in registers and walks through all the
+// problems of the batch: W crosses the L2 / L1 fabric once per batch instead of once per problem, which is what
+// bounds the kernel (R is 4 B per weight out, W would be 4 B per weight in).  The codes, scale indices and group
+// scales of problem z+1 are fetched while problem z is computed.
+constexpr int RES_U = 4;
+
+struct ResidualFetch {                 // what one lane needs of one problem besides W
+  uint32_t cw[RES_U];                  // packed codes of the quad (4 * bits bits)
+  uint32_t si[RES_U];
+  float vv[RES_U];
+};
+
+__device__ __forceinline__ uint32_t load_quad_word(const uint8_t* __restrict__ codes, int64_t quad, int bits) {
+  if (bits == 8) return *reinterpret_cast<const uint32_t*>(codes + quad * 4);
+  if (bits == 4) return *reinterpret_cast<const uint16_t*>(codes + quad * 2);
+  if (bits == 2) return codes[quad];
+  const int64_t byte = (quad * 3) >> 1;     // 3 bits: 12 bits starting at bit 12*quad, nibble-aligned
+  return (((uint32_t)codes[byte] | ((uint32_t)codes[byte + 1] << 8)) >> ((quad & 1) * 4)) & 0xfffu;
+}
+
+__device__ __forceinline__ void residual_fetch(const PhaseArgs& a, const LoopProblem& pr, int z, const int64_t (&qq)[RES_U],
+                                               ResidualFetch& f) {
   const int qpb_shift = __builtin_ctz(pr.cfg.block / 4), sb_shift = __builtin_ctz(pr.cfg.scale_block);
   const uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
   const uint8_t* sidx = a.sidx + (size_t)z * a.strideSidx;
   const float* v = a.v + (size_t)z * a.strideV;
-  float* R = a.R ? a.R + (size_t)z * a.strideR : nullptr;
-  float* Qd = a.Qd ? a.Qd + (size_t)z * a.strideQd : nullptr;
-  for (int64_t q0 = (int64_t)blockIdx.y * (256 * U) + threadIdx.x; q0 < nquads; q0 += (int64_t)gridDim.y * (256 * U)) {
-    float4 f[U];
-    uint32_t c[U][4];
-    uint32_t si[U];
-    float vv[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t quad = q0 + 256 * u;
-      const bool live = quad < nquads;
-      const int64_t qq = live ? quad : nquads - 1;
-      const int64_t blk = qq >> qpb_shift;
-      f[u] = *reinterpret_cast<const float4*>(a.W + (qq << 2));
-      load_quad_codes<BITS>(codes, qq, c[u]);
-      si[u] = sidx[blk];
-      vv[u] = v[blk >> sb_shift];
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t quad = q0 + 256 * u;
-      if (quad >= nquads) break;
-      const float sh = block_scale(si[u], vv[u], pr.levels);
-      const int64_t e0 = quad << 2;
-      float4 qv, rv;
-      qv.x = s_code[c[u][0]] * sh; qv.y = s_code[c[u][1]] * sh; qv.z = s_code[c[u][2]] * sh; qv.w = s_code[c[u][3]] * sh;
-      rv.x = f[u].x - qv.x; rv.y = f[u].y - qv.y; rv.z = f[u].z - qv.z; rv.w = f[u].w - qv.w;
-      if (a.sr) {
-        const int64_t row = e0 / a.k, col = e0 % a.k;
-        const float srow = a.sr[row];
-        const float4 cs = *reinterpret_cast<const float4*>(a.sc + col);
-        rv.x = srow * rv.x * cs.x; rv.y = srow * rv.y * cs.y; rv.z = srow * rv.z * cs.z; rv.w = srow * rv.w * cs.w;
-      }
-      if (R) *reinterpret_cast<float4*>(R + e0) = rv;
-      if (Qd) *reinterpret_cast<float4*>(Qd + e0) = qv;
-    }
+  for (int u = 0; u < RES_U; ++u) {
+    const int64_t blk = qq[u] >> qpb_shift;
+    f.cw[u] = load_quad_word(codes, qq[u], pr.cfg.bits);
+    f.si[u] = sidx[blk];
+    f.vv[u] = v[blk >> sb_shift];
   }
 }
 
 __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a) {
-  __shared__ float s_code[256];
-  const int z = blockIdx.x;          // problem index fastest: W is fetched from HBM once per batch
-  const LoopProblem pr = a.prob[z];
-  const int slot = pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3;
-  s_code[threadIdx.x] = a.tables->code[slot][threadIdx.x];
-  __syncthreads();
-  switch (pr.cfg.bits) {
-    case 2: phase3_body<2>(a, pr, z, s_code); break;
-    case 3: phase3_body<3>(a, pr, z, s_code); break;
-    case 4: phase3_body<4>(a, pr, z, s_code); break;
-    default: phase3_body<8>(a, pr, z, s_code); break;
+  __shared__ float s_code[4][256];
+  __shared__ LoopProblem s_prob[64];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 1024; i += 256) s_code[i >> 8][i & 255] = a.tables->code[i >> 8][i & 255];
+  const int64_t nquads = (a.d * a.k) >> 2;
+  const int64_t q0 = (int64_t)blockIdx.x * (256 * RES_U) + tid;
+  int64_t qq[RES_U];                   // clamped quad indices (loads stay in bounds; stores are guarded)
+  float4 w[RES_U];
+#pragma unroll
+  for (int u = 0; u < RES_U; ++u) {
+    const int64_t quad = q0 + 256 * u;
+    qq[u] = quad < nquads ? quad : nquads - 1;
+    w[u] = *reinterpret_cast<const float4*>(a.W + (qq[u] << 2));
+  }
+  float srow[RES_U];
+  float4 cs[RES_U];
+  if (a.sr) {
+#pragma unroll
+    for (int u = 0; u < RES_U; ++u) {
+      const int64_t e0 = qq[u] << 2;
+      srow[u] = a.sr[e0 / a.k];
+      cs[u] = *reinterpret_cast<const float4*>(a.sc + e0 % a.k);
+    }
+  }
+  for (int z0 = 0; z0 < a.batch; z0 += 64) {         // problem records in LDS, 64 at a time
+    const int nz = a.batch - z0 < 64 ? a.batch - z0 : 64;
+    __syncthreads();
+    if (tid < nz) s_prob[tid] = a.prob[z0 + tid];
+    __syncthreads();
+    ResidualFetch cur, nxt;
+    residual_fetch(a, s_prob[0], z0, qq, cur);
+    for (int zi = 0; zi < nz; ++zi) {
+      const int z = z0 + zi;
+      const LoopProblem pr = s_prob[zi];
+      if (zi + 1 < nz) residual_fetch(a, s_prob[zi + 1], z + 1, qq, nxt);
+      const int bits = pr.cfg.bits;
+      const float* code = s_code[bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3];
+      const uint32_t mask = (1u << bits) - 1u;
+      float* R = a.R ? a.R + (size_t)z * a.strideR : nullptr;
+      float* Qd = a.Qd ? a.Qd + (size_t)z * a.strideQd : nullptr;
+#pragma unroll
+      for (int u = 0; u < RES_U; ++u) {
+        const int64_t quad = q0 + 256 * u;
+        if (quad >= nquads) break;
+        const float sh = block_scale(cur.si[u], cur.vv[u], pr.levels);
+        const uint32_t cw = cur.cw[u];
+        float4 qv, rv;
+        qv.x = code[cw & mask] * sh; qv.y = code[(cw >> bits) & mask] * sh;
+        qv.z = code[(cw >> (2 * bits)) & mask] * sh; qv.w = code[(cw >> (3 * bits)) & mask] * sh;
+        rv.x = w[u].x - qv.x; rv.y = w[u].y - qv.y; rv.z = w[u].z - qv.z; rv.w = w[u].w - qv.w;
+        if (a.sr) {
+          rv.x = srow[u] * rv.x * cs[u].x; rv.y = srow[u] * rv.y * cs[u].y;
+          rv.z = srow[u] * rv.z * cs[u].z; rv.w = srow[u] * rv.w * cs[u].w;
+        }
+        // R is written once and read back only after the whole batch has gone by: streaming stores
+        if (R) __builtin_nontemporal_store(floatx4{rv.x, rv.y, rv.z, rv.w}, reinterpret_cast<floatx4*>(R + (quad << 2)));
+        if (Qd) *reinterpret_cast<float4*>(Qd + (quad << 2)) = qv;
+      }
+      cur = nxt;
+    }
   }
 }
 
 int launch_residual(const PhaseArgs& a, hipStream_t st) {
   const int64_t nquads = (a.d * a.k) >> 2;
-  const int64_t want = (nquads + 1023) / 1024;      // 4 quads per lane and step
-  const int64_t cap = 8192;
-  prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * 8.0 * a.batch);
-  hipLaunchKernelGGL(residual_kernel, dim3((unsigned)a.batch, (unsigned)(want < cap ? want : cap)), dim3(256), 0, st,
-                     a);
+  const int64_t nwg = (nquads + 256 * RES_U - 1) / (256 * RES_U);
+  prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * 4.0 * (a.batch + 1));   // R out per problem, W in once
+  hipLaunchKernelGGL(residual_kernel, dim3((unsigned)nwg), dim3(256), 0, st, a);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }

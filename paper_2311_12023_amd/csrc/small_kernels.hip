@@ -10,16 +10,18 @@
 namespace lq {
 
 // ------------------------------------------------------------------------------------------------
-// Gram matrix: one workgroup per (column chunk, 32x32 output block, problem).  Inputs are fp32, products
-// and sums fp64 (the Gram matrix of a basis whose singular values span two decades loses what the SVD
-// tolerance needs if it is accumulated in fp32).
+// Gram matrix: one workgroup per (column chunk, 32x32 output block of the lower triangle, problem).  Inputs are
+// fp32, products and sums fp64 (the Gram matrix of a basis whose singular values span two decades loses what the
+// SVD tolerance needs if it is accumulated in fp32), which makes the kernel fp64-FMA bound: only the blocks on and
+// below the diagonal are computed and gram_reduce_kernel mirrors them.
 __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restrict__ X, int l, int64_t m, int64_t ldx,
                                                            size_t strideX, int64_t cols_per_chunk,
                                                            double* __restrict__ part) {
   __shared__ float xa[32][33];
   __shared__ float xb[32][33];
-  const int chunk = blockIdx.x, nblk = l / 32;
-  const int bi = blockIdx.y / nblk, bj = blockIdx.y % nblk;
+  const int chunk = blockIdx.x;
+  int bi = 0, bj = blockIdx.y;                    // blockIdx.y enumerates the pairs bj <= bi row by row
+  while (bj > bi) { bj -= bi + 1; ++bi; }
   const int z = blockIdx.z;
   const float* Xz = X + (size_t)z * strideX;
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
@@ -52,13 +54,15 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restri
 }
 
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ part, double* __restrict__ G,
-                                                          int ll) {
-  const int z = blockIdx.y;
+                                                          int l) {
+  const int z = blockIdx.y, ll = l * l;
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= ll) return;
+  const int r = i / l, q = i - r * l;
+  const int src = (r >> 5) >= (q >> 5) ? i : q * l + r;       // blocks above the diagonal: the transposed entry
   const double* P = part + (size_t)z * GRAM_CHUNKS * ll;
   double s = 0;
-  for (int c = 0; c < GRAM_CHUNKS; ++c) s += P[(size_t)c * ll + i];
+  for (int c = 0; c < GRAM_CHUNKS; ++c) s += P[(size_t)c * ll + src];
   G[(size_t)z * ll + i] = s;
 }
 
@@ -68,11 +72,11 @@ int launch_gram(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, d
   cpc = (cpc + 31) / 32 * 32;
   const int nblk = l / 32;
   prof::Scope ps(prof::GRAM, st, (double)l * m * 4.0 * batch);
-  hipLaunchKernelGGL(gram_partial_kernel, dim3(GRAM_CHUNKS, nblk * nblk, batch), dim3(256), 0, st, X, l, m, ldx,
+  hipLaunchKernelGGL(gram_partial_kernel, dim3(GRAM_CHUNKS, nblk * (nblk + 1) / 2, batch), dim3(256), 0, st, X, l, m, ldx,
                      strideX, cpc, part);
   LQ_HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(gram_reduce_kernel, dim3((l * l + 255) / 256, batch), dim3(256), 0, st, (const double*)part, G,
-                     l * l);
+                     l);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }
