@@ -45,6 +45,35 @@ def cpu_baseline(first_matrix: np.ndarray) -> dict:
                       "4^3 = 64 times as much."}
 
 
+TRAFFIC_TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "llama7b_layer_sweep_hbm_traffic.md")
+
+
+def measured_traffic(name: str):
+    """HBM-side bytes per launch of a kernel class (fetch + write) from the committed counter summary, averaged over
+    the class's template variants weighted by launches; None when the summary does not list the kernel."""
+    try:
+        lines = open(TRAFFIC_TABLE).read().splitlines()
+    except OSError:
+        return None
+    base = name.split("<")[0]
+    want = name.replace(" ", "")
+    tot = n = 0.0
+    for ln in lines:
+        cells = [c.strip() for c in ln.strip().strip("|").split("|")]
+        if len(cells) != 4 or not cells[0].startswith("`"):
+            continue
+        kern = cells[0].strip("`").replace(" ", "")
+        if name.startswith("wide_gemm_kernel"):
+            hit = kern.startswith(want[:-1] + ",")          # the table's names carry one more template argument
+        else:
+            hit = kern.split("<")[0] == base
+        if hit:
+            launches = float(cells[1])
+            tot += launches * (float(cells[2]) + float(cells[3])) * 1e6
+            n += launches
+    return tot / n if n else None
+
+
 def roofline_of(name: str, ms: float, launches: int, work: float) -> dict:
     """Roofline entry for one kernel class from its summed HIP-event time and algorithmic work."""
     sec = ms * 1e-3
@@ -184,6 +213,9 @@ def main() -> int:
     if prof:
         dname, (dms, dn, dwork) = max(prof.items(), key=lambda kv: kv[1][0])
         roof = roofline_of(dname, dms, dn, dwork)
+        # counter-measured traffic per launch; the summary was taken in the default launch configuration
+        if len(mats) == len(gen.LLAMA2_7B_LAYER) and not args.streams:
+            roof["traffic"] = measured_traffic(dname)
     line = {
         "metric": "matrix-configs decomposed/sec (LLaMA-2-7B layer sweep)", "value": value, "unit": "matrix-configs/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,

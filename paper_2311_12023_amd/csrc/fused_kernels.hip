@@ -178,8 +178,11 @@ __device__ __forceinline__ void phase1_dispatch_block(const PhaseArgs& a, int bl
 
 // SPLIT: L1 L2 from the packed bf16 hi/lo planes with three v_mfma_f32_32x32x16_bf16 per 16-deep group
 // (hi*hi + hi*lo + lo*hi, fp32 accumulation; products good to about 2^-16 relative) instead of fp32 MFMAs.
+// Launch: one-dimensional, batch * tiles8 workgroups (tiles8 = number of 64 x 128 tiles rounded up to a multiple
+// of 8).  Workgroups go to the 8 XCDs round-robin by index; the index is decoded as (tile mod 8, problem, tile div 8),
+// so the problems of a batch that share a tile of W run on one XCD and fetch it into that XCD's L2 once.
 template <bool WITH_ERR, bool SPLIT>
-__global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) {
+__global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a, int tiles, int tiles_n) {
   // The operand chunks and the product tile share one LDS buffer: the product is written after the last MFMA has
   // read its operands.  fp32: Y chunk KC x TM, B chunk KC x TN.  Split: four planes (Y hi, Y lo: TM rows; B hi, B lo:
   // TN rows) of KC2 reduction indices, pitch KP.
@@ -189,10 +192,13 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) 
   __shared__ LdsTables s_tab;
   float* pt = smem;
   static_assert(KC * TM + KC * TN <= TM * PP, "operand chunks must fit in the product tile");
-  // problem index fastest: the workgroups that share a tile of W run together and hit it in L2
-  const int z = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
+  const int slot8 = blockIdx.x >> 3;
+  const int z = slot8 % a.batch;
+  const int tile = (int)(blockIdx.x & 7) + 8 * (slot8 / a.batch);
+  if (tile >= tiles) return;                   // padding of the tile count to a multiple of 8
   const LoopProblem pr = a.prob[z];
-  const int64_t r0 = (int64_t)blockIdx.z * TM, c0 = (int64_t)blockIdx.y * TN;
+  const int64_t r0 = (int64_t)(tile / tiles_n) * TM, c0 = (int64_t)(tile % tiles_n) * TN;
   const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
   const int wr = wave >> 2, wc = wave & 3;      // 2 x 4 grid of 32x32 tiles
 
@@ -327,15 +333,18 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a) 
 }
 
 int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st) {
-  const dim3 grid((unsigned)a.batch, (unsigned)((a.k + TN - 1) / TN), (unsigned)((a.d + TM - 1) / TM));
+  const int tiles_n = (int)((a.k + TN - 1) / TN);
+  const int64_t tiles = (int64_t)tiles_n * ((a.d + TM - 1) / TM);
+  if ((tiles + 7) / 8 * 8 * a.batch >= (1ll << 31)) return LQ_ERR_SHAPE;
+  const dim3 grid((unsigned)((tiles + 7) / 8 * 8 * a.batch));
   prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st, (double)a.d * a.k * (2.0 * a.rank + 10.0) * a.batch);   // flops
   const bool split = a.packed != nullptr;
   if (split) {
-    if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, true>), grid, dim3(NTHR1), 0, st, a);
-    else hipLaunchKernelGGL((lowrank_blockquant_kernel<false, true>), grid, dim3(NTHR1), 0, st, a);
+    if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, true>), grid, dim3(NTHR1), 0, st, a, (int)tiles, tiles_n);
+    else hipLaunchKernelGGL((lowrank_blockquant_kernel<false, true>), grid, dim3(NTHR1), 0, st, a, (int)tiles, tiles_n);
   } else {
-    if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, false>), grid, dim3(NTHR1), 0, st, a);
-    else hipLaunchKernelGGL((lowrank_blockquant_kernel<false, false>), grid, dim3(NTHR1), 0, st, a);
+    if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, false>), grid, dim3(NTHR1), 0, st, a, (int)tiles, tiles_n);
+    else hipLaunchKernelGGL((lowrank_blockquant_kernel<false, false>), grid, dim3(NTHR1), 0, st, a, (int)tiles, tiles_n);
   }
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
