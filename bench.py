@@ -106,14 +106,16 @@ def main() -> int:
     ap.add_argument("--matrices", type=int, default=7, help="use only the first N matrices of the layer (debugging)")
     ap.add_argument("--no-isolated", action="store_true",
                     help="skip the extra non-overlapped profiled step that gives per-kernel rooflines without contention")
-    ap.add_argument("--overlap", type=int, default=3,
+    ap.add_argument("--overlap", type=int, default=7,
                     help="matrices decomposed concurrently (host threads, each with its own stream and workspace)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event timing")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain elementwise kernel that reads and writes exactly 1 GiB each, so that a "
                          "counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) of this command holds a dispatch of "
                          "known HBM traffic to scale the counters by")
-    ap.add_argument("--streams", type=int, default=0, help="lq_svd_params.streams (0 = library default)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="lq_svd_params.streams: interleaved sub-batches per matrix (0 = library default, 3, which is best "
+                         "for one matrix at a time; with every matrix of the layer in flight 2 is enough)")
     ap.add_argument("--gemm-mode", type=int, default=0, help="lq_svd_params.gemm_mode (0 = library default)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -214,7 +216,7 @@ def main() -> int:
         dname, (dms, dn, dwork) = max(prof.items(), key=lambda kv: kv[1][0])
         roof = roofline_of(dname, dms, dn, dwork)
         # counter-measured traffic per launch; the summary was taken in the default launch configuration
-        if len(mats) == len(gen.LLAMA2_7B_LAYER) and not args.streams:
+        if len(mats) == len(gen.LLAMA2_7B_LAYER) and args.streams == 2:
             roof["traffic"] = measured_traffic(dname)
     line = {
         "metric": "matrix-configs decomposed/sec (LLaMA-2-7B layer sweep)", "value": value, "unit": "matrix-configs/s",

@@ -121,6 +121,21 @@ def test_decompose_workload1(env, oracle, bits, b0, b1):
     assert np.max(np.abs(out["sigma"] - ref["sigma"]) / ref["sigma"]) < 2e-2
 
 
+@pytest.mark.parametrize("gemm_mode", [1, 2])
+def test_decompose_block128_both_precisions(env, oracle, gemm_mode):
+    """B0 = 128 (a block spans 32 lanes of the fused kernel's epilogue) in the all-fp32 mode and in the split-bf16
+    mode of the large products and of L1 L2."""
+    torch, lq = env
+    w = gen.weight_matrix(320, 640, 2024, 12, outlier_frac=0.004)
+    ocfg = oracle.config(4, 128, 16)
+    ref = oracle.lq(w, 8, ocfg, 4)
+    out = lq.decompose(torch.from_numpy(w).cuda(), 8, lq.config(4, 128, 16), 4, seed=9, want_dense=True,
+                       params=lq.SvdParams(gemm_mode=gemm_mode))
+    print("oracle trace", ref["trace"], "\ngpu trace   ", out["trace"])
+    assert np.max(np.abs(out["trace"] - ref["trace"]) / ref["trace"]) < ERR_TOL
+    check_decomposition_consistency(oracle, w, out, ocfg, 8)
+
+
 def test_decompose_weighted(env, oracle):
     torch, lq = env
     d, k, r = 256, 512, 8
