@@ -158,8 +158,12 @@ __device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const
     const int64_t quad = quad0 + (int64_t)u * quad_step;
     store_quad_codes<BITS>(codes, quad, c, live);
     if (live && (cq & (QPB - 1)) == 0) {
-      BlockRec rec; rec.s = amax; rec.e2 = e2; rec.eq = eq; rec.q2 = q2;
-      blk[quad / QPB] = rec;
+      if (WITH_ERR) {
+        BlockRec rec; rec.s = amax; rec.e2 = e2; rec.eq = eq; rec.q2 = q2;
+        blk[quad / QPB] = rec;
+      } else {
+        reinterpret_cast<float*>(blk)[quad / QPB] = amax;     // without error sums a record is the absmax alone
+      }
     }
   }
 }
@@ -352,6 +356,9 @@ int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st)
 
 // ------------------------------------------------------------------------------------------------
 // Phase 2: one lane per block.
+// WITH_ERR: phase 1 left full block records {s, e2, eq, q2}; otherwise only the block absmax values (4 B per block)
+// and the error output is zero.
+template <bool WITH_ERR>
 __global__ __launch_bounds__(256) void scalequant_error_kernel(PhaseArgs a) {
   __shared__ float s_wave[4];
   __shared__ double s_sum[4];
@@ -361,11 +368,14 @@ __global__ __launch_bounds__(256) void scalequant_error_kernel(PhaseArgs a) {
   const int64_t b = (int64_t)blockIdx.x * 256 + tid;
   double* part = a.err_part + (size_t)z * a.strideErrPart;
   if ((int64_t)blockIdx.x * 256 >= nb) {           // whole workgroup past this problem's blocks
-    if (tid == 0) part[blockIdx.x] = 0.0;
+    if (WITH_ERR && tid == 0) part[blockIdx.x] = 0.0;
     return;
   }
   BlockRec rec; rec.s = 0.f; rec.e2 = 0.f; rec.eq = 0.f; rec.q2 = 0.f;
-  if (b < nb) rec = a.blk[(size_t)z * a.strideBlk + b];
+  if (b < nb) {
+    if (WITH_ERR) rec = a.blk[(size_t)z * a.strideBlk + b];
+    else rec.s = reinterpret_cast<const float*>(a.blk + (size_t)z * a.strideBlk)[b];
+  }
   const float vmax = group_max(rec.s, pr.cfg.scale_block, s_wave);
   const float sigma = vmax / (float)pr.levels;
   const float vhat = cast_group_scale(vmax, pr.cfg.v_dtype);
@@ -374,15 +384,19 @@ __global__ __launch_bounds__(256) void scalequant_error_kernel(PhaseArgs a) {
     const uint32_t idx = scale_index(rec.s, sigma, pr.levels);
     a.sidx[(size_t)z * a.strideSidx + b] = (uint8_t)idx;
     if ((b & (pr.cfg.scale_block - 1)) == 0) a.v[(size_t)z * a.strideV + b / pr.cfg.scale_block] = vhat;
-    const float shat = block_scale(idx, vhat, pr.levels);
-    const double delta = (double)shat - (double)rec.s;
-    err = (double)rec.e2 - 2.0 * delta * (double)rec.eq + delta * delta * (double)rec.q2;
-    if (a.row_w) err *= (double)a.row_w[(b * pr.cfg.block) / a.k];
+    if constexpr (WITH_ERR) {
+      const float shat = block_scale(idx, vhat, pr.levels);
+      const double delta = (double)shat - (double)rec.s;
+      err = (double)rec.e2 - 2.0 * delta * (double)rec.eq + delta * delta * (double)rec.q2;
+      if (a.row_w) err *= (double)a.row_w[(b * pr.cfg.block) / a.k];
+    }
   }
-  for (int off = 1; off < 64; off <<= 1) err += __shfl_xor(err, off);
-  if ((tid & 63) == 0) s_sum[tid >> 6] = err;
-  __syncthreads();
-  if (tid == 0) part[blockIdx.x] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+  if constexpr (WITH_ERR) {
+    for (int off = 1; off < 64; off <<= 1) err += __shfl_xor(err, off);
+    if ((tid & 63) == 0) s_sum[tid >> 6] = err;
+    __syncthreads();
+    if (tid == 0) part[blockIdx.x] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+  }
 }
 
 // eps = sqrt(sum of the partials), one workgroup per problem, fixed summation order.
@@ -405,14 +419,17 @@ __global__ __launch_bounds__(256) void error_finalize_kernel(const double* __res
 
 int64_t err_partials_per_problem(int64_t n, int block) { return (n / block + 255) / 256; }
 
-int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st) {
+int launch_scalequant_error(const PhaseArgs& a, int min_block, bool with_err, hipStream_t st) {
   const int64_t nwg = err_partials_per_problem(a.d * a.k, min_block);
-  prof::Scope ps(prof::SCALEQUANT_ERROR, st, (double)(a.d * a.k / min_block) * 17.0 * a.batch);
-  hipLaunchKernelGGL(scalequant_error_kernel, dim3((unsigned)nwg, (unsigned)a.batch), dim3(256), 0, st, a);
+  prof::Scope ps(prof::SCALEQUANT_ERROR, st, (double)(a.d * a.k / min_block) * (with_err ? 17.0 : 5.0) * a.batch);
+  if (with_err) hipLaunchKernelGGL(scalequant_error_kernel<true>, dim3((unsigned)nwg, (unsigned)a.batch), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(scalequant_error_kernel<false>, dim3((unsigned)nwg, (unsigned)a.batch), dim3(256), 0, st, a);
   LQ_HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(error_finalize_kernel, dim3((unsigned)a.batch), dim3(256), 0, st, (const double*)a.err_part,
-                     a.strideErrPart, nwg, a.err_out, a.strideErrOut);
-  LQ_HIP_TRY(hipGetLastError());
+  if (with_err) {
+    hipLaunchKernelGGL(error_finalize_kernel, dim3((unsigned)a.batch), dim3(256), 0, st, (const double*)a.err_part,
+                       a.strideErrPart, nwg, a.err_out, a.strideErrOut);
+    LQ_HIP_TRY(hipGetLastError());
+  }
   return LQ_OK;
 }
 

@@ -121,9 +121,10 @@ int launch_pack_factors(const PhaseArgs& a, hipStream_t st);
 // Phase 1: T = W - L1 L2 tile by tile (MFMA), block absmax, codes and, with_err, the per-block error sums
 // (without them phase 2 still produces scale indices and v, but its error output is meaningless).
 int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st);
-// Phase 2: Quantize-INT of the block absmax values, cast of v, and eps of the iteration (err_out).
+// Phase 2: Quantize-INT of the block absmax values, cast of v, and eps of the iteration (err_out; needs with_err,
+// the same value phase 1 was launched with: it decides the layout of the block records).
 // min_block: smallest B0 in the batch (sizes the grid).
-int launch_scalequant_error(const PhaseArgs& a, int min_block, hipStream_t st);
+int launch_scalequant_error(const PhaseArgs& a, int min_block, bool with_err, hipStream_t st);
 // Phase 3: R = sqrt(rw_i) (W - Q) sqrt(cw_j) and / or dense Q.
 int launch_residual(const PhaseArgs& a, hipStream_t st);
 // Number of error partials phase 2 writes per problem for block size B0.

@@ -372,7 +372,7 @@ struct Loop {
       a.packed = nullptr; a.stridePacked = 0;
     }
     LQ_TRY(launch_lowrank_blockquant(a, with_err, c->st));
-    LQ_TRY(launch_scalequant_error(a, min_block, c->st));
+    LQ_TRY(launch_scalequant_error(a, min_block, with_err, c->st));
     done = t;
     bool last = t == iters;
     if (early_stop && batch == 1) {        // Algorithm 2's stopping rule needs eps_t on the host
