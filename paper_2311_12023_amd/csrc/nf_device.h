@@ -197,12 +197,24 @@ __device__ inline void load_quad_codes(const uint8_t* __restrict__ codes, int64_
 }
 
 // ---- second-level (integer) scale quantization -------------------------------------------------
+// Maximum over the `width` (power of two, <= 64, aligned) consecutive lanes of a wavefront: DPP moves up to 16 lanes
+// (quad permutes, then half-row and row mirrors, which act as xor 4 and xor 8 on quad-uniform values), the LDS
+// crossbar beyond.  `width` is uniform, so the branches are too.
+__device__ __forceinline__ float lanes_max(float x, int width) {
+  if (width > 1) x = fmaxf(x, dpp_move<DPP_QUAD_XOR1>(x));
+  if (width > 2) x = fmaxf(x, dpp_move<DPP_QUAD_XOR2>(x));
+  if (width > 4) x = fmaxf(x, dpp_move<DPP_ROW_HALF_MIRROR>(x));
+  if (width > 8) x = fmaxf(x, dpp_move<DPP_ROW_MIRROR>(x));
+  if (width > 16) x = fmaxf(x, __shfl_xor(x, 16));
+  if (width > 32) x = fmaxf(x, __shfl_xor(x, 32));
+  return x;
+}
+
 // Maximum over the `width` consecutive lanes (power of two, 16..256, aligned) that hold one scale
 // group; the workgroup has 256 threads.  s_wave: 4 floats of LDS.  Contains barriers when
 // width > 64, so every thread of the workgroup must call it.
 __device__ inline float group_max(float x, int width, float* s_wave) {
-  const int w = width < 64 ? width : 64;
-  for (int off = 1; off < w; off <<= 1) x = fmaxf(x, __shfl_xor(x, off));
+  x = lanes_max(x, width < 64 ? width : 64);
   if (width > 64) {
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) s_wave[wave] = x;

@@ -44,6 +44,7 @@ int ensure_device_tables() {
 // instruction of a wavefront covers one contiguous 4 KB stretch.  Block absmax: cross-lane maxima over
 // B0/16 lanes.  Group absmax: cross-lane / LDS maxima over B0*B1/16 runs.  Nothing but the inputs and
 // outputs touches memory.
+
 template <int BITS, int U>
 __global__ __launch_bounds__(256) void quantize_fused_kernel(const float* __restrict__ x, int64_t nruns,
                                                              int runs_per_block, int scale_block, int levels,
@@ -58,32 +59,40 @@ __global__ __launch_bounds__(256) void quantize_fused_kernel(const float* __rest
   const int runs_per_group = runs_per_block * scale_block;          // 16 .. 256*U
   const int slabs_per_group = runs_per_group > 256 ? runs_per_group / 256 : 1;
   const int lane_width = runs_per_group > 256 ? 256 : runs_per_group;
+  const int block_lanes = runs_per_block < 64 ? runs_per_block : 64;   // B0 <= 1024: a block never leaves a wavefront
   const int64_t chunk_runs = 256 * U;
   const int64_t nchunks = (nruns + chunk_runs - 1) / chunk_runs;
+
   for (int64_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
-    float t[U][16];
+    // Codes need the block absmax only, so each slab of 256 runs is searched and its codes stored as soon as it is
+    // loaded (the next slab's loads are already in flight); what waits for the whole chunk is the group absmax.
     float amax[U];
     int64_t run[U];
+    float4 nxt[4];
+    auto fetch = [&](int u) {
+      const int64_t r = chunk * chunk_runs + u * 256 + threadIdx.x;
+      const float4* p = reinterpret_cast<const float4*>(x + (r < nruns ? r : nruns - 1) * 16);   // clamped, masked below
+#pragma unroll
+      for (int q = 0; q < 4; ++q) nxt[q] = p[q];
+    };
+    fetch(0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       run[u] = chunk * chunk_runs + u * 256 + threadIdx.x;
-      if (run[u] < nruns) {
-        const float4* p = reinterpret_cast<const float4*>(x + run[u] * 16);
+      const bool live = run[u] < nruns;
+      float t[16];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float4 f = p[q];
-          t[u][4 * q] = f.x; t[u][4 * q + 1] = f.y; t[u][4 * q + 2] = f.z; t[u][4 * q + 3] = f.w;
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 16; ++j) t[u][j] = 0.0f;
+      for (int q = 0; q < 4; ++q) {
+        t[4 * q] = live ? nxt[q].x : 0.0f; t[4 * q + 1] = live ? nxt[q].y : 0.0f;
+        t[4 * q + 2] = live ? nxt[q].z : 0.0f; t[4 * q + 3] = live ? nxt[q].w : 0.0f;
       }
-    }
+      if (u + 1 < U) fetch(u + 1);
+      amax[u] = lanes_max(run_absmax(t), block_lanes);
+      const float rcp = safe_reciprocal(amax[u]);
+      uint32_t c[16];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float m = run_absmax(t[u]);
-      for (int off = 1; off < runs_per_block; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
-      amax[u] = m;
+      for (int j = 0; j < 16; ++j) c[j] = thr.nearest(t[j] * rcp);
+      if (live) store_codes<BITS>(codes, run[u], c);
     }
     // group maxima: first across the slabs that belong to one group, then across lanes
     float gmax[U];
@@ -98,15 +107,9 @@ __global__ __launch_bounds__(256) void quantize_fused_kernel(const float* __rest
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) gmax[u] = group_max(gmax[u], lane_width, s_wave);
-
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float rcp = safe_reciprocal(amax[u]);
-      uint32_t c[16];
-#pragma unroll
-      for (int j = 0; j < 16; ++j) c[j] = thr.nearest(t[u][j] * rcp);
       if (run[u] < nruns) {
-        store_codes<BITS>(codes, run[u], c);
         if ((run[u] & (runs_per_block - 1)) == 0) {
           const float sigma = gmax[u] / (float)levels;
           sidx[run[u] / runs_per_block] = (uint8_t)scale_index(amax[u], sigma, levels);
@@ -147,7 +150,7 @@ static void launch_quantize_bits(const float* x, int64_t nruns, const lq_config&
   const bool big = (int64_t)c.block * c.scale_block > 8192;
   const int64_t chunk_runs = big ? 1024 : 512;
   const int64_t nchunks = (nruns + chunk_runs - 1) / chunk_runs;
-  const int64_t cap = 256 * 8;
+  const int64_t cap = (int64_t)1 << 22;       // one chunk per workgroup: the loads of the many resident workgroups overlap
   const dim3 grid((unsigned)(nchunks < cap ? nchunks : cap)), block(256);
   if (big)
     hipLaunchKernelGGL((quantize_fused_kernel<BITS, 4>), grid, block, 0, st, x, nruns, rpb, c.scale_block, lv,
