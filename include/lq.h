@@ -32,7 +32,8 @@ extern "C" {
 typedef enum {
   LQ_OK = 0,
   LQ_ERR_NULL = -1,       /* a required pointer is NULL                                              */
-  LQ_ERR_SHAPE = -2,      /* d, k, n <= 0; n not a multiple of the block size; sizes beyond int32 rows */
+  LQ_ERR_SHAPE = -2,      /* d, k, n <= 0; n not a multiple of the block size; sizes beyond int32 rows; a matrix of
+                             2^30 weights or more in lq_factorize / lq_decompose / lq_error_table */
   LQ_ERR_CONFIG = -3,     /* bits / block sizes / scale bits / v dtype outside the supported set      */
   LQ_ERR_RANK = -4,       /* rank < 1, rank >= min(d,k) (Section 2.1 requires r < min(d,k)), rank > 128 */
   LQ_ERR_WEIGHT = -5,     /* exactly one of row_w / col_w is NULL                                     */

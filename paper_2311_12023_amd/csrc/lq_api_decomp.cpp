@@ -55,6 +55,7 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
 
 static int check_matrix_args(int64_t d, int64_t k, int rank) {
   if (d <= 0 || k <= 0 || d > (1 << 30) || k > (1 << 30)) return LQ_ERR_SHAPE;
+  if (d * k >= (1ll << 30)) return LQ_ERR_SHAPE;     // the large products address the matrix with 32-bit byte offsets
   if (k % 16 != 0) return LQ_ERR_SHAPE;       // rows are whole 16-weight runs (every block size divides k)
   if (rank < 1 || rank > MAX_RANK || rank >= std::min(d, k)) return LQ_ERR_RANK;
   return LQ_OK;

@@ -89,6 +89,7 @@ def test_argument_validation_without_gpu(L):
                               None, None, None, ws, wsb, None)
     assert dec(W=None) == -1
     assert dec(d=0) == -2 and dec(k=520) == -2
+    assert dec(d=1 << 15, k=1 << 15) == -2 and dec(d=1 << 14, k=1 << 15) != -2      # fewer than 2^30 weights
     assert dec(rank=0) == -4 and dec(rank=256) == -4 and dec(rank=129, d=1024, k=1024) == -4
     assert dec(cfg=Cfg(3, 64, 256, 8, 0), k=32 * 16, d=64) == 0 or True   # (shape valid: reaches the workspace check)
     assert dec(cfg=Cfg(6, 64, 256, 8, 0)) == -3
