@@ -483,7 +483,7 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
   }
   LQ_HIP_TRY(hipGetLastError());
   if (cut && g.per_wg % g.ns != 0) {
-    prof::Scope ps(prof::SPLITK_REDUCE, st, (double)tiles * batch * l * span * 4.0);
+    prof::Scope ps(prof::GEMM_FIXUP, st, (double)tiles * batch * l * span * 4.0);
     hipLaunchKernelGGL(gemm_fixup_kernel, dim3((unsigned)tiles, (unsigned)batch, (unsigned)(l / 8)), dim3(256), 0, st, g,
                        l, span);
     LQ_HIP_TRY(hipGetLastError());

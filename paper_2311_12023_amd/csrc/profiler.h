@@ -8,7 +8,7 @@ namespace prof {
 
 enum Cls {
   GEMM_BASE = 0,            // + mode * 8 + (l/32 - 1): 16 classes of wide_gemm_kernel
-  SPLITK_REDUCE = 16,
+  GEMM_FIXUP = 16,
   GRAM = 17,
   CHOLESKY = 18,
   TRSM = 19,
