@@ -109,6 +109,10 @@ def main() -> int:
     ap.add_argument("--overlap", type=int, default=7,
                     help="matrices decomposed concurrently (host threads, each with its own stream and workspace)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event timing")
+    ap.add_argument("--grid", choices=("sweep36", "paper243"), default="sweep36",
+                    help="configuration grid: the 36-cell sweep the headline metric is quoted on, or the paper's own "
+                         "243-cell search space (b0, b1 in {2,3,4}, b2 in {bf16,fp16,fp32}, B0 in {16,32,64}, "
+                         "B1 in {16,64,256})")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain elementwise kernel that reads and writes exactly 1 GiB each, so that a "
                          "counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) of this command holds a dispatch of "
@@ -128,7 +132,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
-    cfgs = [lq.config(*g) for g in gen.config_grid()]
+    cfgs = [lq.config(*g) for g in (gen.paper_config_grid() if args.grid == "paper243" else gen.config_grid())]
     params = lq.SvdParams(streams=args.streams, gemm_mode=args.gemm_mode)
     host = [gen.workload_matrix(3, i) for i in range(min(args.matrices, len(gen.LLAMA2_7B_LAYER)))]
     mats = [torch.from_numpy(w).to(dev) for w in host]
@@ -223,7 +227,9 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "LLaMA-2-7B-shaped layer (4x4096x4096, 2x4096x11008, 1x11008x4096), rank 64, "
-                               "36 configs (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256), 10 LQ iterations",
+                               + ("36 configs (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256)" if args.grid == "sweep36" else
+                                  "243 configs (b0, b1 in 2/3/4 x b2 in bf16/fp16/fp32 x B0 16/32/64 x B1 16/64/256)")
+                               + ", 10 LQ iterations",
                    "matrices": len(mats), "configs": len(cfgs), "iters": ITERS, "rank": RANK,
                    "concurrent_matrices": nthreads},
         "roofline": roof,

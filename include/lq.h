@@ -130,6 +130,13 @@ double lq_storage_bits(int64_t n, lq_config c);
 int lq_nf_quantize(const float* x, int64_t n, lq_config c, uint8_t* codes_packed, uint8_t* scale_idx,
                    float* v, void* stream);
 
+/* The scale indices of a quantized matrix as the b1-bit integers that Eq. 3 counts (Section 3.2: the absmax
+ * vector is quantized to b1 bits): `count` one-byte indices <-> a little-endian bit stream of scale_bits bits each,
+ * lq_codes_bytes(count, scale_bits) bytes, index j in bits [j*scale_bits, (j+1)*scale_bits).  scale_bits 2..8
+ * (LQ_ERR_CONFIG otherwise), count > 0 (LQ_ERR_SHAPE).  Both only enqueue work on `stream`. */
+int lq_pack_scale_indices(const uint8_t* scale_idx, int64_t count, int scale_bits, uint8_t* packed, void* stream);
+int lq_unpack_scale_indices(const uint8_t* packed, int64_t count, int scale_bits, uint8_t* scale_idx, void* stream);
+
 /* Dequantize (Section 3.2, the reverse of the above): out[j] = fl32(codebook[code_j] *
  * fl32(scale_idx[block] * fl32(v[group] / (2^(b1-1)-1)))).  out: n fp32 values. */
 int lq_nf_dequantize(const uint8_t* codes_packed, const uint8_t* scale_idx, const float* v, int64_t n,

@@ -66,4 +66,18 @@ int lq_nf_dequantize(const uint8_t* codes_packed, const uint8_t* scale_idx, cons
   return launch_dequant(codes_packed, scale_idx, v, n, c, out, (hipStream_t)stream);
 }
 
+int lq_pack_scale_indices(const uint8_t* scale_idx, int64_t count, int scale_bits, uint8_t* packed, void* stream) {
+  if (!scale_idx || !packed) return LQ_ERR_NULL;
+  if (count <= 0 || count >= ((int64_t)1 << 40)) return LQ_ERR_SHAPE;
+  if (scale_bits < 2 || scale_bits > 8) return LQ_ERR_CONFIG;
+  return launch_pack_bits(scale_idx, count, scale_bits, packed, false, (hipStream_t)stream);
+}
+
+int lq_unpack_scale_indices(const uint8_t* packed, int64_t count, int scale_bits, uint8_t* scale_idx, void* stream) {
+  if (!scale_idx || !packed) return LQ_ERR_NULL;
+  if (count <= 0 || count >= ((int64_t)1 << 40)) return LQ_ERR_SHAPE;
+  if (scale_bits < 2 || scale_bits > 8) return LQ_ERR_CONFIG;
+  return launch_pack_bits(packed, count, scale_bits, scale_idx, true, (hipStream_t)stream);
+}
+
 }  // extern "C"

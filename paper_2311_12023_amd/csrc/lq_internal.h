@@ -68,6 +68,8 @@ struct BlockRec {
 // Stand-alone Quantize(x, c) in one pass (requires B0*B1 <= 16384).
 int launch_quantize(const float* x, int64_t n, const lq_config& c, uint8_t* codes, uint8_t* sidx, float* v,
                     hipStream_t st);
+// idx -> packed (unpack = false) or packed (first argument) -> idx (last pointer argument), `bits` bits per index.
+int launch_pack_bits(const uint8_t* src, int64_t count, int bits, uint8_t* dst, bool unpack, hipStream_t st);
 int launch_dequant(const uint8_t* codes, const uint8_t* sidx, const float* v, int64_t n, const lq_config& c,
                    float* out, hipStream_t st);
 

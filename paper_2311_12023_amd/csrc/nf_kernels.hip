@@ -142,6 +142,48 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
+// Scale indices as a little-endian bit stream of `bits` bits each (the b1 bits per block that the storage formula
+// of Eq. 3 counts): one lane packs / unpacks 8 indices = `bits` bytes.
+__global__ __launch_bounds__(256) void pack_bits_kernel(const uint8_t* __restrict__ idx, int64_t count, int bits,
+                                                        uint8_t* __restrict__ packed) {
+  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;       // group of 8 indices
+  if (g * 8 >= count) return;
+  uint64_t w = 0;
+  for (int j = 0; j < 8; ++j) {
+    const int64_t i = g * 8 + j;
+    const uint64_t c = i < count ? (uint64_t)(idx[i] & ((1u << bits) - 1u)) : 0u;
+    w |= c << (j * bits);
+  }
+  const int64_t total = (count * bits + 7) / 8;
+  for (int b = 0; b < bits; ++b)
+    if (g * bits + b < total) packed[g * bits + b] = (uint8_t)(w >> (8 * b));
+}
+
+__global__ __launch_bounds__(256) void unpack_bits_kernel(const uint8_t* __restrict__ packed, int64_t count, int bits,
+                                                          uint8_t* __restrict__ idx) {
+  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (g * 8 >= count) return;
+  const int64_t total = (count * bits + 7) / 8;
+  uint64_t w = 0;
+  for (int b = 0; b < bits; ++b)
+    if (g * bits + b < total) w |= (uint64_t)packed[g * bits + b] << (8 * b);
+  for (int j = 0; j < 8; ++j) {
+    const int64_t i = g * 8 + j;
+    if (i < count) idx[i] = (uint8_t)((w >> (j * bits)) & ((1u << bits) - 1u));
+  }
+}
+
+int launch_pack_bits(const uint8_t* idx, int64_t count, int bits, uint8_t* packed, bool unpack, hipStream_t st) {
+  const int64_t groups = (count + 7) / 8;
+  const dim3 grid((unsigned)((groups + 255) / 256)), block(256);
+  prof::Scope ps(prof::MISC, st, (double)count * (1.0 + bits / 8.0));
+  if (unpack) hipLaunchKernelGGL(unpack_bits_kernel, grid, block, 0, st, idx, count, bits, packed);
+  else hipLaunchKernelGGL(pack_bits_kernel, grid, block, 0, st, idx, count, bits, packed);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 template <int BITS>
 static void launch_quantize_bits(const float* x, int64_t nruns, const lq_config& c, const DevTables* tab,
                                  uint8_t* codes, uint8_t* sidx, float* v, hipStream_t st) {

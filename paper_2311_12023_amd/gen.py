@@ -114,6 +114,13 @@ def positive_weights(n: int, seed: int, spread: float = 0.5) -> np.ndarray:
     return np.exp(spread * _rng(seed).standard_normal(n)).astype(np.float32)
 
 
+def paper_config_grid():
+    """The 243 configurations (b0, B0, B1, b1, b2) of the paper's search space (Section 3.2, Table 1):
+    b0, b1 in {2, 3, 4}, b2 in {bf16, fp16, fp32}, B0 in {16, 32, 64}, B1 in {16, 64, 256}."""
+    return [(b0, blk, sblk, b1, b2) for b0 in (2, 3, 4) for b1 in (2, 3, 4) for b2 in ("bf16", "fp16", "fp32")
+            for blk in (16, 32, 64) for sblk in (16, 64, 256)]
+
+
 def config_grid(bits=(2, 3, 4, 8), blocks=(16, 32, 64), scale_blocks=(16, 64, 256)):
     """(bits, B0, B1) triples in a fixed order; the default is the 36-config sweep."""
     return [(b, b0, b1) for b in bits for b0 in blocks for b1 in scale_blocks]

@@ -62,6 +62,8 @@ _lib.lq_storage_bits.restype = C.c_double
 _lib.lq_storage_bits.argtypes = [_i64, Config]
 _lib.lq_nf_quantize.argtypes = [_vp, _i64, Config, _vp, _vp, _vp, _vp]
 _lib.lq_nf_dequantize.argtypes = [_vp, _vp, _vp, _i64, Config, _vp, _vp]
+_lib.lq_pack_scale_indices.argtypes = [_vp, _i64, _int, _vp, _vp]
+_lib.lq_unpack_scale_indices.argtypes = [_vp, _i64, _int, _vp, _vp]
 _PP = C.POINTER(SvdParams)
 _lib.lq_factorize_workspace_bytes.restype = _sz
 _lib.lq_factorize_workspace_bytes.argtypes = [_i64, _i64, _int, _PP]
@@ -138,6 +140,21 @@ def nf_dequantize(codes: torch.Tensor, scale_idx: torch.Tensor, v: torch.Tensor,
     _check(_lib.lq_nf_dequantize(_dev(codes, torch.uint8, "codes"), _dev(scale_idx, torch.uint8, "scale_idx"),
                                  _dev(v, torch.float32, "v"), n, cfg, _dev(out, torch.float32, "out"), _stream()),
            "lq_nf_dequantize")
+    return out
+
+
+def pack_scale_indices(scale_idx: torch.Tensor, scale_bits: int) -> torch.Tensor:
+    """One-byte scale indices -> bit stream of scale_bits bits each."""
+    out = torch.empty(max(codes_bytes(scale_idx.numel(), scale_bits), 1), dtype=torch.uint8, device=scale_idx.device)
+    _check(_lib.lq_pack_scale_indices(_dev(scale_idx, torch.uint8, "scale_idx"), scale_idx.numel(), scale_bits,
+                                      out.data_ptr(), _stream()), "lq_pack_scale_indices")
+    return out
+
+
+def unpack_scale_indices(packed: torch.Tensor, count: int, scale_bits: int) -> torch.Tensor:
+    out = torch.empty(max(count, 1), dtype=torch.uint8, device=packed.device)
+    _check(_lib.lq_unpack_scale_indices(_dev(packed, torch.uint8, "packed"), count, scale_bits, out.data_ptr(),
+                                        _stream()), "lq_unpack_scale_indices")
     return out
 
 

@@ -197,3 +197,27 @@ def test_error_table_small(env, oracle):
     # and the whole call is deterministic
     e3, _ = lq.error_table(torch.from_numpy(w).cuda(), 4, [lq.config(*g) for g in grid], 4, seed=5)
     assert np.array_equal(e3, e)
+
+
+def test_error_table_paper_grid_sample(env, oracle):
+    """Cells of the paper's own 243-configuration search space (b1 in {2, 3, 4} scale bits, b2 in {bf16, fp16, fp32};
+    Section 3.2, Table 1): every 9th configuration of the grid on a small matrix against the oracle."""
+    torch, lq = env
+    grid = gen.paper_config_grid()
+    assert len(grid) == 243 and len(set(grid)) == 243
+    sample = grid[4::9]
+    w = gen.weight_matrix(192, 512, 4242, 8, outlier_frac=0.004)
+    e, s, tr = lq.error_table(torch.from_numpy(w).cuda(), 6, [lq.config(*g) for g in sample], 4, seed=3,
+                              want_trace=True)
+    oe, os_ = oracle.error_table(w, 6, [oracle.config(*g) for g in sample], 4)
+    assert np.array_equal(s, os_)
+    rel = np.abs(np.sqrt(e) - np.sqrt(oe)) / np.sqrt(oe)
+    print("max rel", rel.max())
+    # 2-bit codes: the oracle's own trajectory jumps by almost 1e-3 once its first low-rank part moves by 1e-4
+    # (tests/test_oracle_chaos.py), which is how well the last of six nearly equal singular directions is defined
+    two_bit = np.array([g[0] == 2 for g in sample])
+    assert np.max(rel[~two_bit]) < ERR_TOL
+    assert np.max(rel[two_bit]) < ERR_TOL_CHAOTIC
+    for i in (0, 13, 26):                       # first iteration of a few cells
+        first = oracle.lq(w, 6, oracle.config(*sample[i]), 1)["err"]
+        assert abs(tr[i, 0] - first) < ERR_TOL * first

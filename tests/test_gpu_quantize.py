@@ -103,3 +103,19 @@ def test_quantize_determinism_and_full_size_samples(lq, oracle):
             got = oracle.unpack(c1h[grp * g * b // 8:(grp + 1) * g * b // 8], g, b)
             assert np.array_equal(got, oc) and np.array_equal(s1h[grp * b1:(grp + 1) * b1], osi) and v1h[grp] == ov[0]
             assert np.array_equal(out[sl], oracle.dequantize(oc, osi, ov, oracle.config(*cfg_t)))
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 5, 8])
+@pytest.mark.parametrize("count", [1, 7, 8, 1000, 65537])
+def test_scale_index_bit_stream(lq, oracle, bits, count):
+    """Scale indices as b1-bit integers (the b1 / B0 term of Eq. 3): same little-endian stream as the oracle's."""
+    import torch
+    rng = np.random.default_rng(bits * 100003 + count)
+    idx = rng.integers(0, 1 << (bits - 1), size=count, dtype=np.uint8)     # indices are 0 .. 2^(b1-1) - 1
+    packed = lq.pack_scale_indices(torch.from_numpy(idx).cuda(), bits)
+    want = oracle.pack(idx, bits)
+    assert packed.numel() == want.size == (count * bits + 7) // 8
+    assert np.array_equal(packed.cpu().numpy(), want)
+    back = lq.unpack_scale_indices(packed, count, bits)
+    assert np.array_equal(back.cpu().numpy(), idx)
+    assert np.array_equal(oracle.unpack(want, count, bits), idx)

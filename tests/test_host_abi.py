@@ -77,6 +77,12 @@ def test_argument_validation_without_gpu(L):
                 Cfg(3, 64, 256, 8, 7), Cfg(3, 8, 16, 8, 0), Cfg(3, 128, 256, 8, 0)):
         assert L.lq_nf_quantize(fake, 1 << 20, bad, fake, fake, fake, None) == -3
     assert L.lq_nf_dequantize(fake, fake, None, 1024, ok, fake, None) == -1
+    L.lq_pack_scale_indices.argtypes = [vp, C.c_int64, C.c_int, vp, vp]
+    L.lq_unpack_scale_indices.argtypes = [vp, C.c_int64, C.c_int, vp, vp]
+    for f in (L.lq_pack_scale_indices, L.lq_unpack_scale_indices):
+        assert f(None, 8, 4, fake, None) == -1 and f(fake, 8, 4, None, None) == -1
+        assert f(fake, 0, 4, fake, None) == -2
+        assert f(fake, 8, 1, fake, None) == -3 and f(fake, 8, 9, fake, None) == -3
 
     i64, it = C.c_int64, C.c_int
     L.lq_decompose.argtypes = [vp, i64, i64, it, Cfg, it, it, vp, vp, C.c_uint64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
