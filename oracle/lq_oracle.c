@@ -193,6 +193,41 @@ int oq_dequantize(const uint8_t* codes, const uint8_t* scale_idx, const float* v
   return OQ_OK;
 }
 
+/* Forward product with a decomposed weight (Section 3.2 "Implementation", Appendix A): the plain definition
+ * Y = X (Q + L1 L2) in double, with Q = Dequantize of the stored codes (unpacked, one per byte).
+ * X: m x d, L1: d x r, L2: r x k (r may be 0), Y: m x k doubles.  absY, if not NULL, receives |X| (|Q| + |L1 L2|'s
+ * entrywise bound |L1| |L2|) -- the scale that floating-point error bounds of a product are stated against. */
+int oq_matmul(const float* X, int m, int d, int k, const uint8_t* codes, const uint8_t* scale_idx, const float* v,
+              oq_config c, const float* L1, const float* L2, int r, double* Y, double* absY) {
+  const int64_t n = (int64_t)d * k;
+  float* q = (float*)malloc((size_t)n * sizeof(float));
+  double* w = (double*)malloc((size_t)n * sizeof(double));
+  double* wa = (double*)malloc((size_t)n * sizeof(double));
+  if (!q || !w || !wa || oq_dequantize(codes, scale_idx, v, n, c, q) != OQ_OK) { free(q); free(w); free(wa); return OQ_ERR; }
+  for (int i = 0; i < d; ++i)
+    for (int j = 0; j < k; ++j) {
+      double low = 0.0, lowa = 0.0;
+      for (int t = 0; t < r; ++t) {
+        low += (double)L1[(int64_t)i * r + t] * (double)L2[(int64_t)t * k + j];
+        lowa += fabs((double)L1[(int64_t)i * r + t]) * fabs((double)L2[(int64_t)t * k + j]);
+      }
+      w[(int64_t)i * k + j] = (double)q[(int64_t)i * k + j] + low;
+      wa[(int64_t)i * k + j] = fabs((double)q[(int64_t)i * k + j]) + lowa;
+    }
+  for (int a = 0; a < m; ++a)
+    for (int j = 0; j < k; ++j) {
+      double y = 0.0, ya = 0.0;
+      for (int i = 0; i < d; ++i) {
+        y += (double)X[(int64_t)a * d + i] * w[(int64_t)i * k + j];
+        ya += fabs((double)X[(int64_t)a * d + i]) * wa[(int64_t)i * k + j];
+      }
+      Y[(int64_t)a * k + j] = y;
+      if (absY) absY[(int64_t)a * k + j] = ya;
+    }
+  free(q); free(w); free(wa);
+  return OQ_OK;
+}
+
 /* Packed code layout (the paper packs sub-8-bit codes into int8 containers, Appendix A, and gives
  * no layout).  reading: little-endian bit stream, code j occupies bits [j*b, (j+1)*b). */
 int64_t oq_packed_bytes(int64_t n, int bits) { return (n * bits + 7) / 8; }

@@ -108,6 +108,27 @@ def dequantize(codes, sidx, v, cfg: Config) -> np.ndarray:
     return out
 
 
+def matmul(x, codes, sidx, v, cfg: Config, k: int, l1=None, l2=None, want_abs: bool = False):
+    """Y = X (Q + L1 L2) in double; codes unpacked (one per byte).  want_abs: also |X| (|Q| + |L1||L2|)."""
+    x = np.ascontiguousarray(x, np.float32)
+    codes = np.ascontiguousarray(codes, np.uint8)
+    sidx = np.ascontiguousarray(sidx, np.uint8)
+    v = np.ascontiguousarray(v, np.float32)
+    m, d = x.shape
+    assert codes.size == d * k
+    r = 0 if l1 is None else l1.shape[1]
+    l1 = np.zeros((d, 1), np.float32) if l1 is None else np.ascontiguousarray(l1, np.float32)
+    l2 = np.zeros((1, k), np.float32) if l2 is None else np.ascontiguousarray(l2, np.float32)
+    y = np.zeros((m, k), np.float64)
+    ya = np.zeros((m, k), np.float64) if want_abs else None
+    rc = lib().oq_matmul(_p(x, C.c_float), C.c_int(m), C.c_int(d), C.c_int(k), _p(codes, C.c_uint8),
+                         _p(sidx, C.c_uint8), _p(v, C.c_float), cfg, _p(l1, C.c_float), _p(l2, C.c_float),
+                         C.c_int(r), _p(y, C.c_double), _p(ya, C.c_double) if want_abs else None)
+    if rc != 0:
+        raise ValueError("oq_matmul failed")
+    return (y, ya) if want_abs else y
+
+
 def pack(codes: np.ndarray, bits: int) -> np.ndarray:
     codes = np.ascontiguousarray(codes, np.uint8)
     out = np.zeros(lib().oq_packed_bytes(codes.size, bits), np.uint8)

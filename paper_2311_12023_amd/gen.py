@@ -114,6 +114,23 @@ def positive_weights(n: int, seed: int, spread: float = 0.5) -> np.ndarray:
     return np.exp(spread * _rng(seed).standard_normal(n)).astype(np.float32)
 
 
+def activations(m: int, d: int, seed: int) -> np.ndarray:
+    """Stand-in for a batch of layer inputs: unit normals with a few large feature columns, float32 (m, d)."""
+    rng = _rng(seed)
+    x = rng.standard_normal((m, d))
+    cols = rng.permutation(d)[:max(1, d // 256)]
+    x[:, cols] *= 8.0
+    return np.ascontiguousarray(x.astype(np.float32))
+
+
+def low_rank_factors(d: int, k: int, rank: int, seed: int, scale: float = 0.05):
+    """Seeded dense factors L1 (d, rank), L2 (rank, k), float32: stand-ins for the low-rank pair of a decomposition."""
+    rng = _rng(seed)
+    l1 = rng.standard_normal((d, rank)) * scale
+    l2 = rng.standard_normal((rank, k)) * scale
+    return np.ascontiguousarray(l1.astype(np.float32)), np.ascontiguousarray(l2.astype(np.float32))
+
+
 def paper_config_grid():
     """The 243 configurations (b0, B0, B1, b1, b2) of the paper's search space (Section 3.2, Table 1):
     b0, b1 in {2, 3, 4}, b2 in {bf16, fp16, fp32}, B0 in {16, 32, 64}, B1 in {16, 64, 256}."""
