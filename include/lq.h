@@ -15,7 +15,7 @@
  *    anything is launched, so a call that fails validation has no effect on any buffer.
  *    Device data is not inspected: non-finite weights, or non-positive Fisher weights, give
  *    unspecified numbers (never an out-of-bounds access).
- *  - lq_nf_quantize / lq_nf_dequantize only enqueue work on `stream`.  lq_factorize, lq_decompose
+ *  - lq_nf_quantize / lq_nf_dequantize / lq_matmul only enqueue work on `stream`.  lq_factorize, lq_decompose
  *    and lq_error_table write host outputs and therefore synchronize `stream` before returning.
  *  - Calls that share a workspace, or that overlap on outputs, must not run concurrently.
  */
@@ -191,6 +191,27 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
                    int iters, int early_stop, const float* row_w, const float* col_w, uint64_t seed,
                    const lq_svd_params* p, double* err_sq, double* storage_bits, double* err_trace,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Forward product with a decomposed weight (Section 3.2 "Implementation" and Appendix A: products between fp32
+ * inputs and quantized matrices with the matrix dequantized just in time):
+ *     Y = X (Q + L1 L2)  computed as  X Q + (X L1) L2,
+ * Q given in the quantized form that lq_decompose / lq_nf_quantize produce; its weights are decoded inside the
+ * GEMM's load stage and never written to memory.
+ *   X        m x d fp32, 16-byte aligned          Y        m x k fp32
+ *   codes_packed, scale_idx, v    Quantize(Q, c) of the d x k matrix Q (row-major flattening); k % B0 == 0
+ *   L1, L2   d x rank and rank x k fp32, or rank == 0 (then both may be NULL): Y = X Q
+ *   precision  0: every operand is split into bf16 hi + lo and each product takes three bf16 MFMAs with fp32
+ *                 accumulation (error of an output about 2^-16 of sum |x||w|);  1: bf16 operands, one MFMA
+ *                 (about 2^-8), for callers that train in bf16
+ *   workspace  lq_matmul_workspace_bytes(m, d, k, rank) bytes: X L1 and, for small m, partial sums
+ * d must be a multiple of 32 (LQ_ERR_SHAPE), rank <= 1024 (LQ_ERR_RANK).  Only enqueues work on `stream`; the
+ * result is deterministic (partial sums are added in a fixed order).
+ */
+size_t lq_matmul_workspace_bytes(int64_t m, int64_t d, int64_t k, int rank);
+int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* codes_packed, const uint8_t* scale_idx,
+              const float* v, lq_config c, const float* L1, const float* L2, int rank, int precision, float* Y,
+              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the library

@@ -34,6 +34,29 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
                      const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
                      float* part, size_t part_floats, hipStream_t st, int precision = 0, int workgroups = 0);
 
+// ---- forward product with a decomposed weight (matmul_kernels.hip) ------------------------------
+// Quantized part of a product: Xq (m x K, leading dimension ldx, a multiple of 4) times the K x N matrix stored as
+// NF codes (row-major flattening, N a multiple of `block`).  K is a multiple of 32; K == 0 leaves the part out.
+struct QmmPart {
+  const float* X; int64_t ldx; int64_t K;
+  const uint8_t* codes; const uint8_t* sidx; const float* v;
+  int bits, block, scale_block, levels;
+};
+// Dense part: Xd (m x K, leading dimension ldx, a multiple of 4, K a multiple of 32 with zero-filled padding) times
+// D (rows x cols fp32, leading dimension ldd); rows of D beyond `rows` and columns beyond `cols` count as zero.
+struct DensePart {
+  const float* X; int64_t ldx; int64_t K;
+  const float* D; int64_t ldd; int64_t rows, cols;
+};
+// Y[m x N] (leading dimension ldy) = quantized part + dense part.  precision 0: operands split into bf16 hi + lo,
+// three MFMAs per product (about 2^-16 relative per product); 1: bf16 operands, one MFMA.
+// `part`: qmatmul_part_floats(m, N, steps) floats of scratch, steps = (Kq + Kd) / 32 (0 when the tile grid fills
+// the machine without cutting the reduction).
+int qmatmul_splits(int64_t m, int64_t N, int nsteps);
+size_t qmatmul_part_floats(int64_t m, int64_t N, int nsteps);
+int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t N, float* Y, int64_t ldy, float* part,
+                   size_t part_floats, int precision, hipStream_t st);
+
 // ---- small dense kernels (small_kernels.hip) --------------------------------------------------
 constexpr int GRAM_CHUNKS = 16;
 // G[z] (l x l, fp64, row-major) = X[z] X[z]^T for wide X (l x m, fp32).  `part` holds

@@ -1,0 +1,65 @@
+// C ABI of the forward product with a decomposed weight (Section 3.2 "Implementation", Appendix A).
+#include "kernels.h"
+
+namespace lq {
+int check_quant_args(int64_t n, lq_config& c);
+
+static size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
+static int64_t up32(int64_t x) { return (x + 31) & ~(int64_t)31; }
+
+struct MatmulPlan {
+  int64_t r32;
+  size_t t_floats, part_floats;
+};
+static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
+  MatmulPlan p{};
+  p.r32 = up32(rank);
+  p.t_floats = rank > 0 ? (size_t)m * (size_t)p.r32 : 0;
+  const size_t p1 = rank > 0 ? qmatmul_part_floats(m, p.r32, (int)(d / 32)) : 0;
+  const size_t p2 = qmatmul_part_floats(m, k, (int)(d / 32 + p.r32 / 32));
+  p.part_floats = p1 > p2 ? p1 : p2;
+  return p;
+}
+}  // namespace lq
+
+using namespace lq;
+
+extern "C" {
+
+size_t lq_matmul_workspace_bytes(int64_t m, int64_t d, int64_t k, int rank) {
+  if (m <= 0 || d <= 0 || k <= 0 || rank < 0 || (d % 32) != 0) return 0;
+  const MatmulPlan p = plan_matmul(m, d, k, rank);
+  return up256(p.t_floats * sizeof(float)) + up256(p.part_floats * sizeof(float)) + 256;
+}
+
+int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* codes_packed, const uint8_t* scale_idx,
+              const float* v, lq_config c, const float* L1, const float* L2, int rank, int precision, float* Y,
+              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!X || !codes_packed || !scale_idx || !v || !Y) return LQ_ERR_NULL;
+  if (rank < 0 || rank > 1024) return LQ_ERR_RANK;
+  if (rank > 0 && (!L1 || !L2)) return LQ_ERR_NULL;
+  if (m <= 0 || d <= 0 || k <= 0 || m >= ((int64_t)1 << 31) || d >= ((int64_t)1 << 31) || k >= ((int64_t)1 << 31))
+    return LQ_ERR_SHAPE;
+  if ((d % 32) != 0) return LQ_ERR_SHAPE;
+  LQ_TRY(check_quant_args(d * k, c));
+  if ((k % c.block) != 0) return LQ_ERR_SHAPE;
+  if (precision != 0 && precision != 1) return LQ_ERR_ARG;
+  if (((uintptr_t)X & 15) != 0) return LQ_ERR_ARG;
+  const size_t need = lq_matmul_workspace_bytes(m, d, k, rank);
+  if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return LQ_ERR_WORKSPACE;
+  const MatmulPlan p = plan_matmul(m, d, k, rank);
+  float* T = reinterpret_cast<float*>(workspace);
+  float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + up256(p.t_floats * sizeof(float)));
+  hipStream_t st = (hipStream_t)stream;
+
+  QmmPart none{};
+  if (rank > 0) {   // T = X L1, m x r32 with zero columns beyond r
+    DensePart xl{X, d, d, L1, rank, d, rank};
+    LQ_TRY(launch_qmatmul(none, xl, m, p.r32, T, p.r32, part, p.part_floats, precision, st));
+  }
+  QmmPart q{X, d, d, codes_packed, scale_idx, v, c.bits, c.block, c.scale_block, scale_levels(c)};
+  DensePart tl{T, p.r32, rank > 0 ? p.r32 : 0, L2, k, rank, k};
+  return launch_qmatmul(q, tl, m, k, Y, k, part, p.part_floats, precision, st);
+}
+
+}  // extern "C"

@@ -20,7 +20,8 @@ enum Cls {
   DEQUANTIZE = 25,
   MISC = 26,
   GEMM_SPLIT_BASE = 27,     // + mode * 8 + (l/32 - 1): the bf16 hi/lo split variants of wide_gemm_kernel
-  NUM_CLASSES = 43
+  QMATMUL = 43,             // qmatmul_kernel (work = flops of the product)
+  NUM_CLASSES = 44
 };
 
 bool enabled();

@@ -76,7 +76,9 @@ _lib.lq_error_table_workspace_bytes.restype = _sz
 _lib.lq_error_table_workspace_bytes.argtypes = [_i64, _i64, _int, _int, _PP]
 _lib.lq_error_table.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _int, _int, _vp, _vp, C.c_uint64, _PP,
                                 _vp, _vp, _vp, _vp, _sz, _vp]
-
+_lib.lq_matmul_workspace_bytes.restype = _sz
+_lib.lq_matmul_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+_lib.lq_matmul.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, Config, _vp, _vp, _int, _int, _vp, _vp, _sz, _vp]
 
 _lib.lq_profile_enable.argtypes = [_int]
 _lib.lq_profile_class_name.restype = C.c_char_p
@@ -263,4 +265,25 @@ def profile_read() -> dict:
         _check(_lib.lq_profile_read(cls, C.addressof(ms), C.addressof(n), C.addressof(wk)), "lq_profile_read")
         if n.value:
             out[_lib.lq_profile_class_name(cls).decode()] = (ms.value, n.value, wk.value)
+    return out
+
+
+def matmul_workspace(m: int, d: int, k: int, rank: int, device="cuda") -> torch.Tensor:
+    return _workspace(_lib.lq_matmul_workspace_bytes(m, d, k, rank), device)
+
+
+def matmul(x: torch.Tensor, codes: torch.Tensor, scale_idx: torch.Tensor, v: torch.Tensor, cfg: Config, k: int,
+           l1: torch.Tensor | None = None, l2: torch.Tensor | None = None, precision: int = 0,
+           out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X (Q + L1 L2) with Q (d x k) in quantized form, dequantized inside the GEMM."""
+    m, d = x.shape
+    rank = 0 if l1 is None else l1.shape[1]
+    if out is None:
+        out = torch.empty((m, k), dtype=torch.float32, device=x.device)
+    ws = workspace if workspace is not None else matmul_workspace(m, d, k, rank, x.device)
+    _check(_lib.lq_matmul(_dev(x, torch.float32, "x"), m, d, k, _dev(codes, torch.uint8, "codes"),
+                          _dev(scale_idx, torch.uint8, "scale_idx"), _dev(v, torch.float32, "v"), cfg,
+                          _dev(l1, torch.float32, "l1"), _dev(l2, torch.float32, "l2"), rank, precision,
+                          _dev(out, torch.float32, "out"), _aligned_ptr(ws),
+                          ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()), "lq_matmul")
     return out

@@ -1,0 +1,114 @@
+"""GPU parity of the forward product Y = X (Q + L1 L2) with just-in-time dequantization (Section 3.2
+"Implementation", Appendix A) against the oracle's fp64 definition.
+
+Tolerance (derived from the arithmetic).  Precision 0 splits each operand into two bf16 halves: the split drops at
+most 2^-18 of an operand, the omitted lo*lo term is at most 2^-18 of a product, so a product is off by at most
+3 * 2^-18 = 1.1e-5 of |x||w|; fp32 accumulation over K terms adds about sqrt(K) * 2^-24 in practice.  The bound
+used is 4e-5 * S with S = |X| (|Q| + |L1||L2|) elementwise, which the oracle returns.  Precision 1 (bf16 operands)
+rounds each operand to 2^-9: 2^-8 per product, bound 1e-2 * S.  The quantized operand itself is exact: the kernel
+multiplies the same fl32(code * scale) values that Dequantize returns.
+"""
+import numpy as np
+import pytest
+
+from paper_2311_12023_amd import gen
+
+pytestmark = pytest.mark.gpu
+
+TOL_SPLIT = 4e-5
+TOL_BF16 = 1e-2
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2311_12023_amd import lq
+    return torch, lq
+
+
+def _case(oracle, d, k, cfg_tuple, rank, seed):
+    ocfg = oracle.config(*cfg_tuple)
+    w = gen.weight_matrix(d, k, seed, 4, outlier_frac=0.01)
+    codes, sidx, v, _ = oracle.quantize(w.ravel(), ocfg)
+    l1, l2 = gen.low_rank_factors(d, k, rank, seed + 1) if rank > 0 else (None, None)
+    return ocfg, codes, sidx, v, l1, l2
+
+
+def _gpu_product(env, oracle, x, codes, sidx, v, cfg_tuple, k, l1, l2, precision):
+    torch, lq = env
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    packed = oracle.pack(codes, cfg_tuple[0])
+    y = lq.matmul(t(x), t(packed), t(sidx), t(v), lq.config(*cfg_tuple), k, t(l1), t(l2), precision=precision)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("m,d,k,cfg,rank", [
+    (1, 32, 64, (4, 16, 16), 0),             # a single row, one reduction step, no low-rank part
+    (7, 96, 192, (3, 32, 16), 5),            # ragged against every tile size, rank below one step
+    (130, 256, 384, (4, 64, 256), 64),       # two row tiles (the second nearly empty), three column tiles
+    (257, 160, 144, (2, 16, 16), 8),         # three row tiles, column tile cut at 144
+    (64, 512, 128, (8, 64, 64), 40),         # 8-bit codes, rank that is not a multiple of 32
+    (300, 64, 2048, (4, 32, 64), 33),        # wide output
+])
+def test_matmul_matches_oracle(env, oracle, m, d, k, cfg, rank):
+    ocfg, codes, sidx, v, l1, l2 = _case(oracle, d, k, cfg, rank, 100 + m)
+    x = gen.activations(m, d, 200 + m)
+    ref, scale = oracle.matmul(x, codes, sidx, v, ocfg, k, l1, l2, want_abs=True)
+    for precision, tol in ((0, TOL_SPLIT), (1, TOL_BF16)):
+        y = _gpu_product(env, oracle, x, codes, sidx, v, cfg, k, l1, l2, precision)
+        assert y.shape == (m, k) and np.all(np.isfinite(y))
+        excess = np.abs(y - ref) - tol * scale
+        assert np.max(excess) <= 0, (precision, np.max(np.abs(y - ref) / scale))
+
+
+def test_matmul_identity_returns_dequantized_weights(env, oracle):
+    """X = I: every output is one stored weight; hi + lo of a weight carries 16 of its 24 bits."""
+    torch, lq = env
+    d, k, cfg = 128, 256, (4, 64, 256)
+    ocfg, codes, sidx, v, _, _ = _case(oracle, d, k, cfg, 0, 31)
+    q = oracle.dequantize(codes, sidx, v, ocfg).reshape(d, k).astype(np.float64)
+    y = _gpu_product(env, oracle, np.eye(d, dtype=np.float32), codes, sidx, v, cfg, k, None, None, 0)
+    assert np.max(np.abs(y - q) - 2.0 ** -16 * np.abs(q)) <= 0
+    dq = lq.nf_dequantize(torch.from_numpy(oracle.pack(codes, 4)).cuda(), torch.from_numpy(sidx).cuda(),
+                          torch.from_numpy(v).cuda(), d * k, lq.config(*cfg)).cpu().numpy()
+    assert np.array_equal(dq.reshape(d, k).astype(np.float64), q)
+
+
+def test_matmul_is_deterministic_and_ignores_workspace_contents(env, oracle):
+    torch, lq = env
+    m, d, k, cfg, rank = 48, 256, 256, (3, 64, 256), 16      # small grid: the reduction is cut, partial sums in scratch
+    ocfg, codes, sidx, v, l1, l2 = _case(oracle, d, k, cfg, rank, 41)
+    x = gen.activations(m, d, 42)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    args = (t(x), t(oracle.pack(codes, cfg[0])), t(sidx), t(v), lq.config(*cfg), k, t(l1), t(l2))
+    ws = lq.matmul_workspace(m, d, k, rank)
+    ws.fill_(0)
+    a = lq.matmul(*args, workspace=ws).clone()
+    ws.fill_(0xff)                                           # NaN patterns
+    b = lq.matmul(*args, workspace=ws)
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("shape", [(4096, 4096), (4096, 11008)])
+def test_matmul_full_size_sampled_rows(env, oracle, shape):
+    """The benchmark's shape (m = 4096 tokens, LLaMA-2-7B projections, NF4 with double quantization, rank 64):
+    the oracle computes sampled rows of X one by one; the GPU result for those rows must agree, and must not depend
+    on which other rows are in the batch."""
+    torch, lq = env
+    d, k = shape
+    cfg, rank, m = (4, 64, 256, 8, "bf16"), 64, 4096
+    ocfg = oracle.config(*cfg)
+    w = gen.workload_matrix(3, 0 if shape == (4096, 4096) else 4)
+    assert w.shape == shape
+    codes, sidx, v, _ = oracle.quantize(w.ravel(), ocfg)
+    l1, l2 = gen.low_rank_factors(d, k, rank, 77)
+    x = gen.activations(m, d, 78)
+    rows = [0, 127, 128, 2049, 4095]
+    ref, scale = oracle.matmul(x[rows], codes, sidx, v, ocfg, k, l1, l2, want_abs=True)
+    y = _gpu_product(env, oracle, x, codes, sidx, v, cfg, k, l1, l2, 0)
+    assert np.max(np.abs(y[rows] - ref) - TOL_SPLIT * scale) <= 0, np.max(np.abs(y[rows] - ref) / scale)
+    assert np.all(np.isfinite(y))
+    y_small = _gpu_product(env, oracle, x[rows], codes, sidx, v, cfg, k, l1, l2, 0)
+    assert np.max(np.abs(y_small - ref) - TOL_SPLIT * scale) <= 0
