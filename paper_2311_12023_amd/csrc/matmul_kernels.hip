@@ -30,7 +30,7 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int QM_BM = 128, QM_BN = 128, QM_BK = 32;
+constexpr int QM_BN = 128, QM_BK = 32;    // the tile has 64 * AT rows, AT = 2 or 4 (row tiles of 32 per wavefront)
 constexpr int QM_PITCH = 40;     // LDS row pitch in bf16 (80 B): 16-byte aligned rows, conflict-free b128 reads
 
 struct QmmArgs {
@@ -53,13 +53,21 @@ __device__ __forceinline__ void split4(const float (&x)[4], bf16x4& hi, bf16x4& 
   lo = __builtin_convertvector(f - __builtin_convertvector(hi, floatx4), bf16x4);
 }
 
-// Registers of one prefetched reduction step.
-struct QmmStep {
-  floatx4 x[4];         // X tile: 128 rows x 8 float4, four per thread
-  uint32_t cw[4];       // quantized step: code words of the thread's quad in 4 consecutive rows of Q ...
-  uint32_t si[4];       // ... the scale index of each row's block ...
-  float vv[4];          // ... and that block's group scale
-  floatx4 dn[4];        // dense step: the same 4 x 4 patch in fp32
+// Registers of one prefetched reduction step: the X tile (128 rows x 8 float4, four per thread) and the thread's
+// 4 x 4 patch of the weight tile, either as stored (code words of its quad in 4 consecutive rows of Q, the scale index
+// of each row's block and that block's group scale) or dense.
+template <int AT, bool QUANT>
+struct QmmStep;
+template <int AT>
+struct QmmStep<AT, true> {
+  floatx4 x[2 * AT];
+  uint32_t cw[4], si[4];
+  float vv[4];
+};
+template <int AT>
+struct QmmStep<AT, false> {
+  floatx4 x[2 * AT];
+  floatx4 dn[4];
 };
 
 template <int BITS>
@@ -73,26 +81,25 @@ __device__ __forceinline__ uint32_t quad_word(const uint8_t* __restrict__ codes,
   }
 }
 
-template <int BITS>
-__device__ __forceinline__ void qmm_fetch(const QmmArgs& a, int step, int64_t row0, int64_t col0, int tid, int kg,
-                                          int quad, QmmStep& r) {
-  const bool quantized = step < a.nq;
-  const float* X = quantized ? a.Xq : a.Xd;
-  const int64_t ldx = quantized ? a.ldxq : a.ldxd;
-  const int64_t k0 = (int64_t)(quantized ? step : step - a.nq) * QM_BK;
+// Per-thread addressing that does not change from step to step.
+template <int AT>
+struct QmmLane {
+  const float* xq[2 * AT];   // the thread's float4s of the X tile at reduction index 0 (quantized part's X)
+  const float* xd[2 * AT];   // same for the dense part's X
+  int64_t col;          // first column of the patch
+  int64_t colc;         // the same, clamped into the matrix (loaded, never stored)
+  int kg, quad;
+};
+
+template <int BITS, int AT, bool QUANT>
+__device__ __forceinline__ void qmm_fetch(const QmmArgs& a, const QmmLane<AT>& t, int step, QmmStep<AT, QUANT>& r) {
+  const int64_t k0 = (int64_t)step * QM_BK;          // within its own part
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int idx = tid + 256 * i;
-    int64_t row = row0 + (idx >> 3);
-    row = row < a.m ? row : a.m - 1;                 // clamped: loaded, never stored
-    r.x[i] = *reinterpret_cast<const floatx4*>(X + row * ldx + k0 + (idx & 7) * 4);
-  }
-  const int64_t col = col0 + 4 * quad;               // first column of the thread's patch
-  if (quantized) {
-    const int64_t colc = col < a.N ? col : a.N - 4;  // N is a multiple of the block size, hence of 4
+  for (int i = 0; i < 2 * AT; ++i) r.x[i] = *reinterpret_cast<const floatx4*>((QUANT ? t.xq[i] : t.xd[i]) + k0);
+  if constexpr (QUANT) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int64_t e = (k0 + 4 * kg + j) * a.N + colc;
+      const int64_t e = (k0 + 4 * t.kg + j) * a.N + t.colc;
       r.cw[j] = quad_word<BITS>(a.codes, e >> 2);
       const int64_t blk = e >> a.block_shift;
       r.si[j] = a.sidx[blk];
@@ -101,30 +108,30 @@ __device__ __forceinline__ void qmm_fetch(const QmmArgs& a, int step, int64_t ro
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int64_t p = k0 + 4 * kg + j;
-      float t[4];
+      const int64_t p = k0 + 4 * t.kg + j;
+      float w[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) t[c] = (p < a.drows && col + c < a.dcols) ? a.D[p * a.ldd + col + c] : 0.0f;
-      r.dn[j] = floatx4{t[0], t[1], t[2], t[3]};
+      for (int c = 0; c < 4; ++c) w[c] = (p < a.drows && t.col + c < a.dcols) ? a.D[p * a.ldd + t.col + c] : 0.0f;
+      r.dn[j] = floatx4{w[0], w[1], w[2], w[3]};
     }
   }
 }
 
-template <int BITS, bool SPLIT>
-__device__ __forceinline__ void qmm_stash(const QmmArgs& a, int step, int tid, int kg, int quad, const QmmStep& r,
+template <int BITS, int AT, bool SPLIT, bool QUANT>
+__device__ __forceinline__ void qmm_stash(const QmmArgs& a, const QmmLane<AT>& t, int tid, const QmmStep<AT, QUANT>& r,
                                           const float* s_code, __bf16* xh, __bf16* xl, __bf16* bh, __bf16* bl) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2 * AT; ++i) {
     const int idx = tid + 256 * i;
-    const float t[4] = {r.x[i].x, r.x[i].y, r.x[i].z, r.x[i].w};
+    const float f[4] = {r.x[i].x, r.x[i].y, r.x[i].z, r.x[i].w};
     bf16x4 hi, lo;
-    split4(t, hi, lo);
+    split4(f, hi, lo);
     const int at = (idx >> 3) * QM_PITCH + (idx & 7) * 4;
     *reinterpret_cast<bf16x4*>(xh + at) = hi;
     if constexpr (SPLIT) *reinterpret_cast<bf16x4*>(xl + at) = lo;
   }
   float w[4][4];                                     // [reduction index][column]
-  if (step < a.nq) {
+  if constexpr (QUANT) {
     constexpr uint32_t mask = (1u << BITS) - 1u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -138,18 +145,85 @@ __device__ __forceinline__ void qmm_stash(const QmmArgs& a, int step, int tid, i
   }
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
-    const float t[4] = {w[0][c], w[1][c], w[2][c], w[3][c]};
+    const float f[4] = {w[0][c], w[1][c], w[2][c], w[3][c]};
     bf16x4 hi, lo;
-    split4(t, hi, lo);
-    const int at = (4 * quad + c) * QM_PITCH + 4 * kg;
+    split4(f, hi, lo);
+    const int at = (4 * t.quad + c) * QM_PITCH + 4 * t.kg;
     *reinterpret_cast<bf16x4*>(bh + at) = hi;
     if constexpr (SPLIT) *reinterpret_cast<bf16x4*>(bl + at) = lo;
   }
 }
 
-template <int BITS, bool SPLIT>
+// One 32-deep step of the wavefront's (32 AT) x 64 quarter from the operand tiles in LDS.
+template <int AT, bool SPLIT>
+__device__ __forceinline__ void qmm_multiply(const __bf16* xh, const __bf16* xl, const __bf16* bhp, const __bf16* blp,
+                                             int arow, int brow, int lh, floatx16 (&acc)[AT][2]) {
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    bf16x8 ah[AT], al[AT], bh[2], bl[2];
+#pragma unroll
+    for (int i = 0; i < AT; ++i) {
+      const int at = (arow + 32 * i) * QM_PITCH + 16 * g + 8 * lh;
+      ah[i] = *reinterpret_cast<const bf16x8*>(xh + at);
+      if constexpr (SPLIT) al[i] = *reinterpret_cast<const bf16x8*>(xl + at);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int at = (brow + 32 * j) * QM_PITCH + 16 * g + 8 * lh;
+      bh[j] = *reinterpret_cast<const bf16x8*>(bhp + at);
+      if constexpr (SPLIT) bl[j] = *reinterpret_cast<const bf16x8*>(blp + at);
+    }
+#pragma unroll
+    for (int i = 0; i < AT; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if constexpr (SPLIT) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+        }
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+      }
+  }
+}
+
+// Steps [sa, sb) of one part (numbered within the part).  Operands are fetched DEPTH steps ahead into a ring of
+// register sets; the prefetch index is clamped instead of guarded (the last step is fetched again and dropped), so
+// the loop body is branch-free and the loads stay in flight across the barriers.
+template <int BITS, int AT, bool SPLIT, bool QUANT, int DEPTH>
+__device__ __forceinline__ void qmm_run(const QmmArgs& a, const QmmLane<AT>& t, int sa, int sb, int tid, int arow,
+                                        int brow, int lh, const float* s_code, __bf16 (*s_x)[64 * AT * QM_PITCH],
+                                        __bf16 (*s_b)[QM_BN * QM_PITCH], floatx16 (&acc)[AT][2]) {
+  if (sa >= sb) return;
+  const int last = sb - 1;
+  QmmStep<AT, QUANT> ring[DEPTH];
+  qmm_fetch<BITS, AT, QUANT>(a, t, sa, ring[0]);
+  if constexpr (DEPTH > 1) qmm_fetch<BITS, AT, QUANT>(a, t, sa + 1 < last ? sa + 1 : last, ring[1]);
+#define LQ_QMM_STEP(U, S)                                                                                  \
+  {                                                                                                        \
+    __syncthreads(); /* the previous step's operands have been read */                                     \
+    qmm_stash<BITS, AT, SPLIT, QUANT>(a, t, tid, ring[(U)], s_code, s_x[0], s_x[1], s_b[0], s_b[1]);       \
+    __syncthreads();                                                                                       \
+    qmm_fetch<BITS, AT, QUANT>(a, t, (S) + DEPTH < last ? (S) + DEPTH : last, ring[(U)]);                  \
+    qmm_multiply<AT, SPLIT>(s_x[0], s_x[1], s_b[0], s_b[1], arow, brow, lh, acc);                          \
+  }
+  int s = sa;
+  if constexpr (DEPTH > 1) {
+    for (; s + 2 <= sb; s += 2) {
+      LQ_QMM_STEP(0, s)
+      LQ_QMM_STEP(1, s + 1)
+    }
+    if (s < sb) LQ_QMM_STEP(0, s)
+  } else {
+    for (; s < sb; ++s) LQ_QMM_STEP(0, s)
+  }
+#undef LQ_QMM_STEP
+}
+
+template <int BITS, int AT, bool SPLIT>
 __global__ __launch_bounds__(256, 2) void qmatmul_kernel(QmmArgs a) {
-  __shared__ __attribute__((aligned(16))) __bf16 s_x[2][QM_BM * QM_PITCH];
+  constexpr int BM = 64 * AT;
+  constexpr int DEPTH = AT > 2 ? 1 : 2;
+  __shared__ __attribute__((aligned(16))) __bf16 s_x[2][BM * QM_PITCH];
   __shared__ __attribute__((aligned(16))) __bf16 s_b[2][QM_BN * QM_PITCH];
   __shared__ float s_code[1 << BITS];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
@@ -169,53 +243,37 @@ __global__ __launch_bounds__(256, 2) void qmatmul_kernel(QmmArgs a) {
     bm = blockIdx.x / a.tiles_n;
     bn = blockIdx.x % a.tiles_n;
   }
-  const int64_t row0 = (int64_t)bm * QM_BM, col0 = (int64_t)bn * QM_BN;
+  const int64_t row0 = (int64_t)bm * BM, col0 = (int64_t)bn * QM_BN;
   const int s0 = (int)((int64_t)a.nsteps * split / a.splits), s1 = (int)((int64_t)a.nsteps * (split + 1) / a.splits);
-  // the thread's 4 x 4 patch of the weight tile: reduction rows 4kg.., columns 4quad..
-  const int kg = lane & 7, quad = 8 * wave + (lane >> 3);
 
-  floatx16 acc[2][2];
+  QmmLane<AT> t;
+  t.kg = lane & 7;                     // the thread's 4 x 4 patch of the weight tile: reduction rows 4kg.., columns 4quad..
+  t.quad = 8 * wave + (lane >> 3);
+  t.col = col0 + 4 * t.quad;
+  t.colc = t.col < a.N ? t.col : a.N - 4;          // in the quantized part N is a multiple of the block size, hence of 4
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 2 * AT; ++i) {
+    const int idx = tid + 256 * i;
+    int64_t row = row0 + (idx >> 3);
+    row = row < a.m ? row : a.m - 1;               // clamped: loaded, never stored
+    t.xq[i] = a.Xq + row * a.ldxq + (idx & 7) * 4;
+    t.xd[i] = a.Xd + row * a.ldxd + (idx & 7) * 4;
+  }
+
+  floatx16 acc[AT][2];
+#pragma unroll
+  for (int i = 0; i < AT; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  QmmStep r;
-  if (s0 < s1) qmm_fetch<BITS>(a, s0, row0, col0, tid, kg, quad, r);
-  for (int s = s0; s < s1; ++s) {
-    __syncthreads();                   // the previous step's operands have been read (first pass: the code book is in LDS)
-    qmm_stash<BITS, SPLIT>(a, s, tid, kg, quad, r, s_code, s_x[0], s_x[1], s_b[0], s_b[1]);
-    __syncthreads();
-    if (s + 1 < s1) qmm_fetch<BITS>(a, s + 1, row0, col0, tid, kg, quad, r);
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-      bf16x8 ah[2], al[2], bh[2], bl[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int at = (64 * wm + 32 * i + ln) * QM_PITCH + 16 * g + 8 * lh;
-        ah[i] = *reinterpret_cast<const bf16x8*>(s_x[0] + at);
-        if constexpr (SPLIT) al[i] = *reinterpret_cast<const bf16x8*>(s_x[1] + at);
-      }
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int at = (64 * wn + 32 * j + ln) * QM_PITCH + 16 * g + 8 * lh;
-        bh[j] = *reinterpret_cast<const bf16x8*>(s_b[0] + at);
-        if constexpr (SPLIT) bl[j] = *reinterpret_cast<const bf16x8*>(s_b[1] + at);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          if constexpr (SPLIT) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
-          }
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
-        }
-    }
-  }
+  // quantized steps first, then the dense ones (the first barrier of either also covers the code book)
+  const int arow = 32 * AT * wm + ln, brow = 64 * wn + ln;
+  qmm_run<BITS, AT, SPLIT, true, DEPTH>(a, t, s0 < a.nq ? s0 : a.nq, s1 < a.nq ? s1 : a.nq, tid, arow, brow, lh, s_code,
+                                        s_x, s_b, acc);
+  qmm_run<BITS, AT, SPLIT, false, DEPTH>(a, t, (s0 > a.nq ? s0 : a.nq) - a.nq, (s1 > a.nq ? s1 : a.nq) - a.nq, tid, arow,
+                                         brow, lh, s_code, s_x, s_b, acc);
 
   // accumulator element e of a lane is row 8*(e/4) + 4*lh + e%4, column ln of its 32 x 32 tile
   float* __restrict__ Y = a.Y + (size_t)split * (size_t)a.m * a.ldy;
@@ -224,10 +282,10 @@ __global__ __launch_bounds__(256, 2) void qmatmul_kernel(QmmArgs a) {
     const int64_t col = col0 + 64 * wn + 32 * j + ln;
     if (col >= a.N) continue;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < AT; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int64_t row = row0 + 64 * wm + 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
+        const int64_t row = row0 + 32 * AT * wm + 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
         if (row < a.m) Y[row * a.ldy + col] = acc[i][j][e];
       }
   }
@@ -246,10 +304,16 @@ __global__ __launch_bounds__(256) void qmatmul_reduce_kernel(const float* __rest
   }
 }
 
+// Rows of an output tile: 256 when that still gives every compute unit a tile, else 128.
+int qmatmul_tile_rows(int64_t m, int64_t N) {
+  return ((m + 255) / 256) * ((N + QM_BN - 1) / QM_BN) >= 256 ? 256 : 128;
+}
+
 // Reduction ranges for an m x N product with `nsteps` 32-deep steps: enough workgroups to occupy every compute unit
 // twice over, at least four steps per range, at most 16 ranges.
 int qmatmul_splits(int64_t m, int64_t N, int nsteps) {
-  const int64_t tiles = ((m + QM_BM - 1) / QM_BM) * ((N + QM_BN - 1) / QM_BN);
+  const int bm = qmatmul_tile_rows(m, N);
+  const int64_t tiles = ((m + bm - 1) / bm) * ((N + QM_BN - 1) / QM_BN);
   if (tiles >= 256) return 1;
   const int64_t want = (512 + tiles - 1) / tiles;
   const int64_t cap = std::max<int64_t>(1, nsteps / 4);
@@ -262,9 +326,14 @@ size_t qmatmul_part_floats(int64_t m, int64_t N, int nsteps) {
 }
 
 template <int BITS>
-static void launch_bits(const QmmArgs& a, dim3 grid, bool split_precision, hipStream_t st) {
-  if (split_precision) hipLaunchKernelGGL((qmatmul_kernel<BITS, true>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((qmatmul_kernel<BITS, false>), grid, dim3(256), 0, st, a);
+static void launch_bits(const QmmArgs& a, dim3 grid, int tile_rows, bool split_precision, hipStream_t st) {
+  if (tile_rows == 256) {
+    if (split_precision) hipLaunchKernelGGL((qmatmul_kernel<BITS, 4, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((qmatmul_kernel<BITS, 4, false>), grid, dim3(256), 0, st, a);
+  } else {
+    if (split_precision) hipLaunchKernelGGL((qmatmul_kernel<BITS, 2, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((qmatmul_kernel<BITS, 2, false>), grid, dim3(256), 0, st, a);
+  }
 }
 
 int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t N, float* Y, int64_t ldy, float* part,
@@ -286,7 +355,8 @@ int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t N, 
   a.m = m; a.N = N;
   a.nq = (int)(q.K / QM_BK);
   a.nsteps = a.nq + (int)(dn.K / QM_BK);
-  a.tiles_m = (int)((m + QM_BM - 1) / QM_BM);
+  const int bm = qmatmul_tile_rows(m, N);
+  a.tiles_m = (int)((m + bm - 1) / bm);
   a.tiles_n = (int)((N + QM_BN - 1) / QM_BN);
   a.splits = qmatmul_splits(m, N, a.nsteps);
   if (a.splits > 1 && part_floats < (size_t)a.splits * (size_t)m * (size_t)N) return LQ_ERR_WORKSPACE;
@@ -302,10 +372,10 @@ int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t N, 
   {
     prof::Scope ps(prof::QMATMUL, st, 2.0 * (double)m * (double)N * (double)(q.K + dn.K));
     switch (bits) {
-      case 2: launch_bits<2>(a, grid, precision == 0, st); break;
-      case 3: launch_bits<3>(a, grid, precision == 0, st); break;
-      case 4: launch_bits<4>(a, grid, precision == 0, st); break;
-      case 8: launch_bits<8>(a, grid, precision == 0, st); break;
+      case 2: launch_bits<2>(a, grid, bm, precision == 0, st); break;
+      case 3: launch_bits<3>(a, grid, bm, precision == 0, st); break;
+      case 4: launch_bits<4>(a, grid, bm, precision == 0, st); break;
+      case 8: launch_bits<8>(a, grid, bm, precision == 0, st); break;
       default: return LQ_ERR_CONFIG;
     }
     LQ_HIP_TRY(hipGetLastError());
