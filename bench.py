@@ -97,6 +97,81 @@ def roofline_of(name: str, ms: float, launches: int, work: float) -> dict:
     return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
 
 
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+NF4_DOUBLE_QUANT = (4, 64, 256, 8, "bf16")
+
+
+def bench_matmul(args, torch, gen, lq, dev) -> int:
+    """Forward products Y = X (Q + L1 L2) of one LLaMA-2-7B-shaped layer; one step = all 7 matrices."""
+    shapes = gen.LLAMA2_7B_LAYER[:args.matrices]
+    cfg = lq.config(*NF4_DOUBLE_QUANT)
+    m = args.tokens
+    acts = {d: torch.from_numpy(gen.activations(m, d, gen.matrix_seed(3, 900 + i))).to(dev)
+            for i, d in enumerate(sorted({d for d, _ in shapes}))}
+    items = []
+    for i, (d, k) in enumerate(shapes):
+        w = torch.from_numpy(gen.workload_matrix(3, i)).to(dev)
+        codes, sidx, v = lq.nf_quantize(w.reshape(-1), cfg)
+        l1, l2 = (torch.from_numpy(a).to(dev) for a in gen.low_rank_factors(d, k, RANK, gen.matrix_seed(3, 800 + i)))
+        items.append(dict(d=d, k=k, codes=codes, sidx=sidx, v=v, l1=l1, l2=l2, x=acts[d],
+                          out=torch.empty((m, k), dtype=torch.float32, device=dev),
+                          ws=lq.matmul_workspace(m, d, k, RANK, dev)))
+        del w
+    flops = sum(2.0 * m * it["d"] * it["k"] + 2.0 * m * RANK * (it["d"] + it["k"]) for it in items)
+
+    def step():
+        for it in items:
+            lq.matmul(it["x"], it["codes"], it["sidx"], it["v"], cfg, it["k"], it["l1"], it["l2"],
+                      precision=args.precision, out=it["out"], workspace=it["ws"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lq.profile_enable(not args.no_profile)
+    lq.profile_reset()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    prof = lq.profile_read() if not args.no_profile else {}
+    lq.profile_enable(False)
+    ms = 1e3 * sec / args.steps
+    out = {"metric": "fp32-grade TFLOP/s of the forward product X (Q + L1 L2) with just-in-time dequantization",
+           "value": flops / (sec / args.steps) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16x3" if args.precision == 0 else "bf16", "data": "synthetic",
+           "config": {"workload": f"LLaMA-2-7B layer forward, {m} tokens, {len(items)} matrices, NF4 + double "
+                                  f"quantization, rank {RANK}"}}
+    if "qmatmul_kernel" in prof:
+        kms, launches, work = prof["qmatmul_kernel"]
+        mult = 3.0 if args.precision == 0 else 1.0          # bf16 MFMAs executed per product
+        ach = mult * work / (kms * 1e-3) / 1e12
+        out["roofline"] = {"kernel": "qmatmul_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS,
+                           "unit": "TFLOP/s", "frac": ach / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                           "launches": launches, "avg_us": 1e3 * kms / launches,
+                           "algorithmic_tflops": work / (kms * 1e-3) / 1e12}
+        out["roofline_note"] = ("achieved counts the bf16 MFMA flops the kernel executes (3 per product at precision 0) "
+                                "against the dense bf16 peak; algorithmic_tflops counts each product once.  The "
+                                "profiled run brackets every launch with events on the launch stream.")
+        out["kernels"] = {n: {"ms": v[0], "launches": v[1]} for n, v in prof.items()}
+    if not args.no_cpu_baseline:
+        from oracle import lq_oracle as O
+        it = items[0]
+        rows = 4
+        codes = O.unpack(it["codes"].cpu().numpy(), it["d"] * it["k"], 4)
+        t0 = time.perf_counter()
+        O.matmul(it["x"][:rows].cpu().numpy(), codes, it["sidx"].cpu().numpy(), it["v"].cpu().numpy(),
+                 O.config(*NF4_DOUBLE_QUANT), it["k"], it["l1"].cpu().numpy(), it["l2"].cpu().numpy())
+        cs = time.perf_counter() - t0
+        cfl = 2.0 * it["d"] * it["k"] * (rows + RANK)        # forming Q + L1 L2 and the product of `rows` rows
+        out["cpu_baseline"] = {"value": cfl / cs / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{rows} rows of X against the first {it['d']}x{it['k']} matrix "
+                                         f"(fp64 definition, Q + L1 L2 formed densely): {cs:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +196,12 @@ def main() -> int:
                     help="lq_svd_params.streams: interleaved sub-batches per matrix (0 = library default, 3, which is best "
                          "for one matrix at a time; with every matrix of the layer in flight 2 is enough)")
     ap.add_argument("--gemm-mode", type=int, default=0, help="lq_svd_params.gemm_mode (0 = library default)")
+    ap.add_argument("--workload", choices=("sweep", "matmul"), default="sweep",
+                    help="sweep: the error-table sweep (the headline metric).  matmul: the consumer of a decomposition, "
+                         "Y = X (Q + L1 L2) with just-in-time dequantization, for the 7 matrices of the layer at "
+                         "--tokens rows of X (NF4 with double quantization, rank 64); prints its own JSON line")
+    ap.add_argument("--tokens", type=int, default=4096, help="rows of X for --workload matmul")
+    ap.add_argument("--precision", type=int, default=0, help="lq_matmul precision for --workload matmul (0 split, 1 bf16)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sweep shards over GPUs by "
@@ -132,6 +213,8 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
+    if args.workload == "matmul":
+        return bench_matmul(args, torch, gen, lq, dev)
     cfgs = [lq.config(*g) for g in (gen.paper_config_grid() if args.grid == "paper243" else gen.config_grid())]
     params = lq.SvdParams(streams=args.streams, gemm_mode=args.gemm_mode)
     host = [gen.workload_matrix(3, i) for i in range(min(args.matrices, len(gen.LLAMA2_7B_LAYER)))]

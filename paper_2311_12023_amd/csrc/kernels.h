@@ -35,27 +35,31 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
                      float* part, size_t part_floats, hipStream_t st, int precision = 0, int workgroups = 0);
 
 // ---- forward product with a decomposed weight (matmul_kernels.hip) ------------------------------
-// Quantized part of a product: Xq (m x K, leading dimension ldx, a multiple of 4) times the K x N matrix stored as
-// NF codes (row-major flattening, N a multiple of `block`).  K is a multiple of 32; K == 0 leaves the part out.
+// X (rows x K fp32, leading dimension ldx, K and ldx multiples of 4) -> its bf16 halves: hi = bf16(x),
+// lo = bf16(x - hi), planes of rows_pad x K with zero rows beyond `rows`.
+int launch_split_planes(const float* X, int64_t rows, int64_t K, int64_t ldx, int64_t rows_pad, uint16_t* hi,
+                        uint16_t* lo, hipStream_t st);
+// Quantized part of a product: X (planes of rows_pad x K) times the K x N matrix stored as NF codes (row-major
+// flattening, N a multiple of `block`).  K is a multiple of 32; K == 0 leaves the part out.
 struct QmmPart {
-  const float* X; int64_t ldx; int64_t K;
+  const uint16_t* Xh; const uint16_t* Xl; int64_t K;
   const uint8_t* codes; const uint8_t* sidx; const float* v;
   int bits, block, scale_block, levels;
 };
-// Dense part: Xd (m x K, leading dimension ldx, a multiple of 4, K a multiple of 32 with zero-filled padding) times
-// D (rows x cols fp32, leading dimension ldd); rows of D beyond `rows` and columns beyond `cols` count as zero.
+// Dense part: X (planes of rows_pad x K, K a multiple of 32, zero-filled padding) times D (rows x cols fp32, leading
+// dimension ldd); rows of D beyond `rows` and columns beyond `cols` count as zero.
 struct DensePart {
-  const float* X; int64_t ldx; int64_t K;
+  const uint16_t* Xh; const uint16_t* Xl; int64_t K;
   const float* D; int64_t ldd; int64_t rows, cols;
 };
-// Y[m x N] (leading dimension ldy) = quantized part + dense part.  precision 0: operands split into bf16 hi + lo,
-// three MFMAs per product (about 2^-16 relative per product); 1: bf16 operands, one MFMA.
+// Y[m x N] (leading dimension ldy) = quantized part + dense part.  rows_pad: rows of the X planes, a multiple of 256.
+// precision 0: hi and lo halves, three MFMAs per product (about 2^-16 relative per product); 1: hi halves only.
 // `part`: qmatmul_part_floats(m, N, steps) floats of scratch, steps = (Kq + Kd) / 32 (0 when the tile grid fills
 // the machine without cutting the reduction).
 int qmatmul_splits(int64_t m, int64_t N, int nsteps);
 size_t qmatmul_part_floats(int64_t m, int64_t N, int nsteps);
-int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t N, float* Y, int64_t ldy, float* part,
-                   size_t part_floats, int precision, hipStream_t st);
+int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t rows_pad, int64_t N, float* Y, int64_t ldy,
+                   float* part, size_t part_floats, int precision, hipStream_t st);
 
 // ---- small dense kernels (small_kernels.hip) --------------------------------------------------
 constexpr int GRAM_CHUNKS = 16;

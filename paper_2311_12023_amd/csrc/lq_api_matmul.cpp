@@ -8,17 +8,23 @@ static size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
 static int64_t up32(int64_t x) { return (x + 31) & ~(int64_t)31; }
 
 struct MatmulPlan {
-  int64_t r32;
-  size_t t_floats, part_floats;
+  int64_t r32, rows_pad;
+  size_t x_plane, t_floats, t_plane, part_floats;   // elements
 };
 static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   MatmulPlan p{};
   p.r32 = up32(rank);
+  p.rows_pad = (m + 255) / 256 * 256;
+  p.x_plane = (size_t)p.rows_pad * (size_t)d;
   p.t_floats = rank > 0 ? (size_t)m * (size_t)p.r32 : 0;
+  p.t_plane = rank > 0 ? (size_t)p.rows_pad * (size_t)p.r32 : 0;
   const size_t p1 = rank > 0 ? qmatmul_part_floats(m, p.r32, (int)(d / 32)) : 0;
   const size_t p2 = qmatmul_part_floats(m, k, (int)(d / 32 + p.r32 / 32));
   p.part_floats = p1 > p2 ? p1 : p2;
   return p;
+}
+static size_t plan_bytes(const MatmulPlan& p) {
+  return 2 * up256(p.x_plane * 2) + up256(p.t_floats * 4) + 2 * up256(p.t_plane * 2) + up256(p.part_floats * 4);
 }
 }  // namespace lq
 
@@ -28,8 +34,7 @@ extern "C" {
 
 size_t lq_matmul_workspace_bytes(int64_t m, int64_t d, int64_t k, int rank) {
   if (m <= 0 || d <= 0 || k <= 0 || rank < 0 || (d % 32) != 0) return 0;
-  const MatmulPlan p = plan_matmul(m, d, k, rank);
-  return up256(p.t_floats * sizeof(float)) + up256(p.part_floats * sizeof(float)) + 256;
+  return plan_bytes(plan_matmul(m, d, k, rank)) + 256;
 }
 
 int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* codes_packed, const uint8_t* scale_idx,
@@ -45,21 +50,29 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   if ((k % c.block) != 0) return LQ_ERR_SHAPE;
   if (precision != 0 && precision != 1) return LQ_ERR_ARG;
   if (((uintptr_t)X & 15) != 0) return LQ_ERR_ARG;
-  const size_t need = lq_matmul_workspace_bytes(m, d, k, rank);
-  if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return LQ_ERR_WORKSPACE;
   const MatmulPlan p = plan_matmul(m, d, k, rank);
-  float* T = reinterpret_cast<float*>(workspace);
-  float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + up256(p.t_floats * sizeof(float)));
+  if (p.rows_pad * d >= ((int64_t)1 << 31)) return LQ_ERR_SHAPE;   // planes are addressed with 32-bit byte offsets
+  const size_t need = plan_bytes(p) + 256;
+  if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return LQ_ERR_WORKSPACE;
+  char* w = reinterpret_cast<char*>(workspace);
+  uint16_t* xh = reinterpret_cast<uint16_t*>(w); w += up256(p.x_plane * 2);
+  uint16_t* xl = reinterpret_cast<uint16_t*>(w); w += up256(p.x_plane * 2);
+  float* T = reinterpret_cast<float*>(w); w += up256(p.t_floats * 4);
+  uint16_t* th = reinterpret_cast<uint16_t*>(w); w += up256(p.t_plane * 2);
+  uint16_t* tl = reinterpret_cast<uint16_t*>(w); w += up256(p.t_plane * 2);
+  float* part = reinterpret_cast<float*>(w);
   hipStream_t st = (hipStream_t)stream;
 
+  LQ_TRY(launch_split_planes(X, m, d, d, p.rows_pad, xh, xl, st));
   QmmPart none{};
-  if (rank > 0) {   // T = X L1, m x r32 with zero columns beyond r
-    DensePart xl{X, d, d, L1, rank, d, rank};
-    LQ_TRY(launch_qmatmul(none, xl, m, p.r32, T, p.r32, part, p.part_floats, precision, st));
+  if (rank > 0) {   // T = X L1, m x r32 with zero columns beyond r, then its planes
+    DensePart xl1{xh, xl, d, L1, rank, d, rank};
+    LQ_TRY(launch_qmatmul(none, xl1, m, p.rows_pad, p.r32, T, p.r32, part, p.part_floats, precision, st));
+    LQ_TRY(launch_split_planes(T, m, p.r32, p.r32, p.rows_pad, th, tl, st));
   }
-  QmmPart q{X, d, d, codes_packed, scale_idx, v, c.bits, c.block, c.scale_block, scale_levels(c)};
-  DensePart tl{T, p.r32, rank > 0 ? p.r32 : 0, L2, k, rank, k};
-  return launch_qmatmul(q, tl, m, k, Y, k, part, p.part_floats, precision, st);
+  QmmPart q{xh, xl, d, codes_packed, scale_idx, v, c.bits, c.block, c.scale_block, scale_levels(c)};
+  DensePart tl2{th, tl, rank > 0 ? p.r32 : 0, L2, k, rank, k};
+  return launch_qmatmul(q, tl2, m, p.rows_pad, k, Y, k, part, p.part_floats, precision, st);
 }
 
 }  // extern "C"

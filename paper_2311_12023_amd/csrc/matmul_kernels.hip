@@ -5,15 +5,25 @@
 // may be empty.  The forward product is two launches of it:
 //   T = X L1          (dense part only, N = r rounded up to 32, the extra columns are zero)
 //   Y = X Q + T L2    (quantized part followed by r/32 dense steps)
+// with X and T split into bf16 planes beforehand.
 //
-// Mapping: a workgroup of 256 threads (2 x 2 wavefronts) owns a 128 x 128 output tile and walks the reduction in
-// 32-deep steps.  Per step the X tile (128 x 32 fp32) and the weight tile (32 x 128) are fetched into registers one
-// step ahead, then written to LDS as bf16 hi and lo halves in MFMA operand layout (rows = output rows or columns,
-// 32 reduction indices contiguous): the X tile is split, the weight tile is decoded from its packed codes, scaled
-// by the block's reconstructed scale (the same fl32(code * s^) that the stand-alone dequantizer produces) and split.
-// Each wavefront multiplies its 64 x 64 quarter with three v_mfma_f32_32x32x16_bf16 per tile pair (hi*hi + hi*lo +
-// lo*hi, fp32 accumulation; the bf16-only variant keeps the hi halves alone).  A thread decodes a 4 (reduction) x 4
-// (columns) patch: four code words from four consecutive rows of Q, so that its LDS writes are 8-byte runs.
+// Mapping: a workgroup of 512 threads (2 x 4 wavefronts, two per SIMD) owns a 256 x 256 output tile and walks the
+// reduction in 32-deep steps.  Both MFMA operands sit in LDS as bf16 hi and lo halves, rows = output rows (X) or
+// output columns (weights), the 32 reduction indices of a step contiguous, each double-buffered.
+//  - X is split into its two bf16 planes once per call by a small kernel (every column tile needs the same halves);
+//    the tiles then travel from global memory straight into LDS (global_load_lds_dwordx4: each lane moves 16 bytes,
+//    a wavefront fills 1 KB = 16 rows), one step ahead.  No register or vector-ALU instruction touches X.  Rows are
+//    64 bytes without padding; the four 16-byte units of a row are stored in the order unit ^ ((row / 2) % 4), which
+//    makes the 128-bit operand reads conflict-free.
+//  - The weight tile is decoded in registers: every thread fetches a 4 (reduction) x 4 (columns) patch a step or two
+//    ahead (four code words from four consecutive rows of Q, their blocks' scale indices and group scales),
+//    multiplies code-book value by reconstructed scale (the same fl32(code * s^) that the stand-alone dequantizer
+//    produces), splits it and writes 8-byte runs into the weight buffer of the next step.
+//  - Each wavefront multiplies its 128 x 64 part with three v_mfma_f32_32x32x16_bf16 per tile pair (hi*hi + hi*lo +
+//    lo*hi, fp32 accumulation; the bf16-only variant keeps the hi halves alone).
+// Within a step the decode of the next weight tile and the MFMAs of the current one are independent.  The two
+// wavefronts of a SIMD take them in opposite order, so that while one occupies the matrix pipe the other runs the
+// vector-ALU work and waits out its LDS and memory latencies.  One barrier per step.
 // When the tile grid is too small to fill the machine the reduction is cut into `splits` contiguous ranges whose
 // partial tiles go to scratch and are summed in a fixed order by a second kernel.
 #include <algorithm>
@@ -30,13 +40,14 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int QM_BN = 128, QM_BK = 32;    // the tile has 64 * AT rows, AT = 2 or 4 (row tiles of 32 per wavefront)
-constexpr int QM_PITCH = 40;     // LDS row pitch in bf16 (80 B): 16-byte aligned rows, conflict-free b128 reads
+constexpr int QM_BM = 256, QM_BN = 256, QM_BK = 32, QM_THREADS = 512;
+constexpr int QM_AT = 4;                  // 32-row tiles per wavefront (its part of the output is 128 x 64)
+constexpr int QM_PITCH = 40;              // LDS row pitch of the weight tile in bf16 (80 B): conflict-free b128 reads
 
 struct QmmArgs {
-  const float* Xq; int64_t ldxq;   // m x Kq
-  const float* Xd; int64_t ldxd;   // m x Kd
-  const float* D; int64_t ldd;     // Kd x dcols fp32; columns >= dcols count as zero
+  const uint16_t* Xqh; const uint16_t* Xql;   // bf16 planes of the quantized part's X: rows_pad x Kq
+  const uint16_t* Xdh; const uint16_t* Xdl;   // bf16 planes of the dense part's X: rows_pad x Kd
+  const float* D; int64_t ldd;     // drows x dcols fp32; rows and columns beyond count as zero
   const uint8_t* codes; const uint8_t* sidx; const float* v;   // Kq x N, row-major flattening
   float* Y; int64_t ldy;           // m x N (splits == 1), else partials: split s at Y + s * m * ldy
   int64_t m, N, Kq, Kd, drows, dcols;
@@ -53,20 +64,47 @@ __device__ __forceinline__ void split4(const float (&x)[4], bf16x4& hi, bf16x4& 
   lo = __builtin_convertvector(f - __builtin_convertvector(hi, floatx4), bf16x4);
 }
 
-// Registers of one prefetched reduction step: the X tile (128 rows x 8 float4, four per thread) and the thread's
-// 4 x 4 patch of the weight tile, either as stored (code words of its quad in 4 consecutive rows of Q, the scale index
-// of each row's block and that block's group scale) or dense.
-template <int AT, bool QUANT>
-struct QmmStep;
-template <int AT>
-struct QmmStep<AT, true> {
-  floatx4 x[2 * AT];
+// X (rows x K fp32, leading dimension ldx) -> bf16 planes hi, lo (rows_pad x K each); rows beyond `rows` are zero.
+__global__ __launch_bounds__(256) void split_planes_kernel(const float* __restrict__ X, int64_t rows, int64_t K,
+                                                           int64_t ldx, int64_t rows_pad, uint16_t* __restrict__ hi,
+                                                           uint16_t* __restrict__ lo) {
+  const int64_t kq = K >> 2, total = rows_pad * kq;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / kq, c4 = (i % kq) << 2;
+    float f[4] = {0.f, 0.f, 0.f, 0.f};
+    if (row < rows) {
+      const floatx4 x = *reinterpret_cast<const floatx4*>(X + row * ldx + c4);
+      f[0] = x.x; f[1] = x.y; f[2] = x.z; f[3] = x.w;
+    }
+    bf16x4 h, l;
+    split4(f, h, l);
+    *reinterpret_cast<bf16x4*>(hi + row * K + c4) = h;
+    *reinterpret_cast<bf16x4*>(lo + row * K + c4) = l;
+  }
+}
+
+int launch_split_planes(const float* X, int64_t rows, int64_t K, int64_t ldx, int64_t rows_pad, uint16_t* hi,
+                        uint16_t* lo, hipStream_t st) {
+  if (rows <= 0 || K <= 0 || (K & 3) != 0 || (ldx & 3) != 0 || rows_pad < rows) return LQ_ERR_SHAPE;
+  const int64_t total = rows_pad * (K >> 2);
+  const int64_t nwg = std::min<int64_t>((total + 255) / 256, 1 << 16);
+  prof::Scope ps(prof::MISC, st, 4.0 * (double)rows * (double)K + 4.0 * (double)rows_pad * (double)K);
+  hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)nwg), dim3(256), 0, st, X, rows, K, ldx, rows_pad, hi, lo);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
+// Registers of the thread's prefetched 4 x 4 patch of the weight tile, either as stored (code words of its quad in 4
+// consecutive rows of Q, the scale index of each row's block and that block's group scale) or dense.
+template <bool QUANT>
+struct QmmPatch;
+template <>
+struct QmmPatch<true> {
   uint32_t cw[4], si[4];
   float vv[4];
 };
-template <int AT>
-struct QmmStep<AT, false> {
-  floatx4 x[2 * AT];
+template <>
+struct QmmPatch<false> {
   floatx4 dn[4];
 };
 
@@ -82,20 +120,19 @@ __device__ __forceinline__ uint32_t quad_word(const uint8_t* __restrict__ codes,
 }
 
 // Per-thread addressing that does not change from step to step.
-template <int AT>
 struct QmmLane {
-  const float* xq[2 * AT];   // the thread's float4s of the X tile at reduction index 0 (quantized part's X)
-  const float* xd[2 * AT];   // same for the dense part's X
-  int64_t col;          // first column of the patch
+  int64_t col;          // first column of the weight patch
   int64_t colc;         // the same, clamped into the matrix (loaded, never stored)
-  int kg, quad;
+  int kg, quad;         // the patch: reduction rows 4kg.., columns 4quad.. of the tile
+  uint32_t xvoff;       // byte offset of the lane's 16 bytes inside an X plane for step 0, first row block of the wavefront
+  uint32_t xlds;        // LDS byte offset (inside a stage's plane) of the wavefront's first row block
+  uint32_t aoff[2];     // LDS byte offsets of the lane's A operand for the two 16-deep halves of a step (row tile 0)
+  uint32_t boff;        // LDS element offset of the lane's B operand (column tile 0, first half)
 };
 
-template <int BITS, int AT, bool QUANT>
-__device__ __forceinline__ void qmm_fetch(const QmmArgs& a, const QmmLane<AT>& t, int step, QmmStep<AT, QUANT>& r) {
+template <int BITS, bool QUANT>
+__device__ __forceinline__ void qmm_fetch(const QmmArgs& a, const QmmLane& t, int step, QmmPatch<QUANT>& r) {
   const int64_t k0 = (int64_t)step * QM_BK;          // within its own part
-#pragma unroll
-  for (int i = 0; i < 2 * AT; ++i) r.x[i] = *reinterpret_cast<const floatx4*>((QUANT ? t.xq[i] : t.xd[i]) + k0);
   if constexpr (QUANT) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -117,19 +154,9 @@ __device__ __forceinline__ void qmm_fetch(const QmmArgs& a, const QmmLane<AT>& t
   }
 }
 
-template <int BITS, int AT, bool SPLIT, bool QUANT>
-__device__ __forceinline__ void qmm_stash(const QmmArgs& a, const QmmLane<AT>& t, int tid, const QmmStep<AT, QUANT>& r,
-                                          const float* s_code, __bf16* xh, __bf16* xl, __bf16* bh, __bf16* bl) {
-#pragma unroll
-  for (int i = 0; i < 2 * AT; ++i) {
-    const int idx = tid + 256 * i;
-    const float f[4] = {r.x[i].x, r.x[i].y, r.x[i].z, r.x[i].w};
-    bf16x4 hi, lo;
-    split4(f, hi, lo);
-    const int at = (idx >> 3) * QM_PITCH + (idx & 7) * 4;
-    *reinterpret_cast<bf16x4*>(xh + at) = hi;
-    if constexpr (SPLIT) *reinterpret_cast<bf16x4*>(xl + at) = lo;
-  }
+template <int BITS, bool SPLIT, bool QUANT>
+__device__ __forceinline__ void qmm_stash(const QmmArgs& a, const QmmLane& t, const QmmPatch<QUANT>& r,
+                                          const float* s_code, __bf16* bh, __bf16* bl) {
   float w[4][4];                                     // [reduction index][column]
   if constexpr (QUANT) {
     constexpr uint32_t mask = (1u << BITS) - 1u;
@@ -154,27 +181,54 @@ __device__ __forceinline__ void qmm_stash(const QmmArgs& a, const QmmLane<AT>& t
   }
 }
 
-// One 32-deep step of the wavefront's (32 AT) x 64 quarter from the operand tiles in LDS.
-template <int AT, bool SPLIT>
-__device__ __forceinline__ void qmm_multiply(const __bf16* xh, const __bf16* xl, const __bf16* bhp, const __bf16* blp,
-                                             int arow, int brow, int lh, floatx16 (&acc)[AT][2]) {
+// LDS of one workgroup: two X stages (hi plane, lo plane; 256 rows of 64 bytes), two weight buffers (hi, lo; 256 rows
+// of QM_PITCH bf16) and the code book.
+struct QmmLds {
+  static constexpr uint32_t X_PLANE = QM_BM * 64, X_STAGE = 2 * X_PLANE;             // bytes
+  static constexpr uint32_t B_PLANE = QM_BN * QM_PITCH * 2, B_BUF = 2 * B_PLANE;     // bytes
+  static constexpr uint32_t B_BASE = 2 * X_STAGE, CODE_BASE = B_BASE + 2 * B_BUF;
+  static constexpr size_t BYTES = CODE_BASE + 256 * sizeof(float);
+};
+
+// One wavefront's share of the X tile of one step: 2 row blocks of 16 rows per plane, global memory -> LDS.
+// hi / lo: the planes; k_elems: the step's first reduction index; M0 carries the LDS address of each 1 KB block.
+template <bool SPLIT>
+__device__ __forceinline__ void qmm_dma(const uint16_t* hi, const uint16_t* lo, int64_t k_elems, int64_t row_elems,
+                                        uint32_t voff, uint32_t lds) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const uint16_t* ph = hi + k_elems + (int64_t)j * 128 * row_elems;    // wavefront-uniform
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds + (uint32_t)j * 8192u), "v"(voff), "s"(ph)
+                 : "memory", "m0");
+    if constexpr (SPLIT) {
+      const uint16_t* pl = lo + k_elems + (int64_t)j * 128 * row_elems;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds + QmmLds::X_PLANE + (uint32_t)j * 8192u),
+                   "v"(voff), "s"(pl)
+                   : "memory", "m0");
+    }
+  }
+}
+
+// One 32-deep step of the wavefront's 128 x 64 part from the operand tiles in LDS.
+template <bool SPLIT>
+__device__ __forceinline__ void qmm_multiply(const unsigned char* xstage, const __bf16* bhp, const __bf16* blp,
+                                             const QmmLane& t, floatx16 (&acc)[QM_AT][2]) {
 #pragma unroll
   for (int g = 0; g < 2; ++g) {
-    bf16x8 ah[AT], al[AT], bh[2], bl[2];
+    bf16x8 ah[QM_AT], al[QM_AT], bh[2], bl[2];
 #pragma unroll
-    for (int i = 0; i < AT; ++i) {
-      const int at = (arow + 32 * i) * QM_PITCH + 16 * g + 8 * lh;
-      ah[i] = *reinterpret_cast<const bf16x8*>(xh + at);
-      if constexpr (SPLIT) al[i] = *reinterpret_cast<const bf16x8*>(xl + at);
+    for (int i = 0; i < QM_AT; ++i) {
+      ah[i] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[g] + i * 2048);
+      if constexpr (SPLIT) al[i] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[g] + i * 2048);
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int at = (brow + 32 * j) * QM_PITCH + 16 * g + 8 * lh;
+      const int at = t.boff + 32 * j * QM_PITCH + 16 * g;
       bh[j] = *reinterpret_cast<const bf16x8*>(bhp + at);
       if constexpr (SPLIT) bl[j] = *reinterpret_cast<const bf16x8*>(blp + at);
     }
 #pragma unroll
-    for (int i = 0; i < AT; ++i)
+    for (int i = 0; i < QM_AT; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         if constexpr (SPLIT) {
@@ -186,49 +240,71 @@ __device__ __forceinline__ void qmm_multiply(const __bf16* xh, const __bf16* xl,
   }
 }
 
-// Steps [sa, sb) of one part (numbered within the part).  Operands are fetched DEPTH steps ahead into a ring of
-// register sets; the prefetch index is clamped instead of guarded (the last step is fetched again and dropped), so
-// the loop body is branch-free and the loads stay in flight across the barriers.
-template <int BITS, int AT, bool SPLIT, bool QUANT, int DEPTH>
-__device__ __forceinline__ void qmm_run(const QmmArgs& a, const QmmLane<AT>& t, int sa, int sb, int tid, int arow,
-                                        int brow, int lh, const float* s_code, __bf16 (*s_x)[64 * AT * QM_PITCH],
-                                        __bf16 (*s_b)[QM_BN * QM_PITCH], floatx16 (&acc)[AT][2]) {
+// Steps [sa, sb) of one part (numbered within the part).  At the top of step s (iteration `it` of this run) X stage
+// it % 2 and weight buffer it % 2 hold step s, and one patch register set holds step s + 1.  The step fetches the patch
+// of s + 2 and starts the X transfer of s + 1 into the other stage (free since the barrier that ended step s - 1), then
+// multiplies step s and decodes the patch of s + 1 into the other weight buffer -- in that order in the first four
+// wavefronts, in the opposite order in the last four -- waits for everything it has started and meets the barrier.
+// Prefetch indices are clamped, not guarded (the last step is fetched again and dropped): the body is branch-free
+// apart from the uniform choice of order.
+template <int BITS, bool SPLIT, bool QUANT, bool MULTIPLY_FIRST>
+__device__ __forceinline__ void qmm_run(const QmmArgs& a, const QmmLane& t, int sa, int sb, const float* s_code,
+                                        unsigned char* lds, uint32_t lds_addr, floatx16 (&acc)[QM_AT][2]) {
   if (sa >= sb) return;
+  typedef QmmLds L;
   const int last = sb - 1;
-  QmmStep<AT, QUANT> ring[DEPTH];
-  qmm_fetch<BITS, AT, QUANT>(a, t, sa, ring[0]);
-  if constexpr (DEPTH > 1) qmm_fetch<BITS, AT, QUANT>(a, t, sa + 1 < last ? sa + 1 : last, ring[1]);
-#define LQ_QMM_STEP(U, S)                                                                                  \
-  {                                                                                                        \
-    __syncthreads(); /* the previous step's operands have been read */                                     \
-    qmm_stash<BITS, AT, SPLIT, QUANT>(a, t, tid, ring[(U)], s_code, s_x[0], s_x[1], s_b[0], s_b[1]);       \
-    __syncthreads();                                                                                       \
-    qmm_fetch<BITS, AT, QUANT>(a, t, (S) + DEPTH < last ? (S) + DEPTH : last, ring[(U)]);                  \
-    qmm_multiply<AT, SPLIT>(s_x[0], s_x[1], s_b[0], s_b[1], arow, brow, lh, acc);                          \
+  const uint16_t* xh = QUANT ? a.Xqh : a.Xdh;
+  const uint16_t* xl = QUANT ? a.Xql : a.Xdl;
+  const int64_t row_elems = QUANT ? a.Kq : a.Kd;
+  QmmPatch<QUANT> ring[2];
+#define LQ_QMM_XSTAGE(U) (lds + (uint32_t)(U) * L::X_STAGE)
+#define LQ_QMM_BH(U) reinterpret_cast<__bf16*>(lds + L::B_BASE + (uint32_t)(U) * L::B_BUF)
+#define LQ_QMM_BL(U) reinterpret_cast<__bf16*>(lds + L::B_BASE + (uint32_t)(U) * L::B_BUF + L::B_PLANE)
+#define LQ_QMM_DMA(S, U)                                                                                     \
+  qmm_dma<SPLIT>(xh, xl, (int64_t)((S) < last ? (S) : last) * QM_BK, row_elems, t.xvoff,                    \
+                 lds_addr + (uint32_t)(U) * L::X_STAGE + t.xlds)
+  LQ_QMM_DMA(sa, 0);
+  qmm_fetch<BITS, QUANT>(a, t, sa, ring[0]);
+  qmm_fetch<BITS, QUANT>(a, t, sa + 1 < last ? sa + 1 : last, ring[1]);
+  qmm_stash<BITS, SPLIT, QUANT>(a, t, ring[0], s_code, LQ_QMM_BH(0), LQ_QMM_BL(0));
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  // U: parity of the step inside this run = its X stage, its weight buffer, and the patch registers that are free
+#define LQ_QMM_STEP(U, S)                                                                                    \
+  {                                                                                                          \
+    qmm_fetch<BITS, QUANT>(a, t, (S) + 2 < last ? (S) + 2 : last, ring[(U)]);                                \
+    LQ_QMM_DMA((S) + 1, 1 - (U));                                                                            \
+    if constexpr (MULTIPLY_FIRST) {                                                                          \
+      qmm_multiply<SPLIT>(LQ_QMM_XSTAGE(U), LQ_QMM_BH(U), LQ_QMM_BL(U), t, acc);                             \
+      qmm_stash<BITS, SPLIT, QUANT>(a, t, ring[1 - (U)], s_code, LQ_QMM_BH(1 - (U)), LQ_QMM_BL(1 - (U)));    \
+    } else {                                                                                                 \
+      qmm_stash<BITS, SPLIT, QUANT>(a, t, ring[1 - (U)], s_code, LQ_QMM_BH(1 - (U)), LQ_QMM_BL(1 - (U)));    \
+      qmm_multiply<SPLIT>(LQ_QMM_XSTAGE(U), LQ_QMM_BH(U), LQ_QMM_BL(U), t, acc);                             \
+    }                                                                                                        \
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* the X tile of S + 1 has landed */                    \
+    __syncthreads();                                                                                         \
   }
   int s = sa;
-  if constexpr (DEPTH > 1) {
-    for (; s + 2 <= sb; s += 2) {
-      LQ_QMM_STEP(0, s)
-      LQ_QMM_STEP(1, s + 1)
-    }
-    if (s < sb) LQ_QMM_STEP(0, s)
-  } else {
-    for (; s < sb; ++s) LQ_QMM_STEP(0, s)
+  for (; s + 2 <= sb; s += 2) {
+    LQ_QMM_STEP(0, s)
+    LQ_QMM_STEP(1, s + 1)
   }
+  if (s < sb) LQ_QMM_STEP(0, s)
 #undef LQ_QMM_STEP
+#undef LQ_QMM_DMA
+#undef LQ_QMM_BH
+#undef LQ_QMM_BL
+#undef LQ_QMM_XSTAGE
 }
 
-template <int BITS, int AT, bool SPLIT>
-__global__ __launch_bounds__(256, 2) void qmatmul_kernel(QmmArgs a) {
-  constexpr int BM = 64 * AT;
-  constexpr int DEPTH = AT > 2 ? 1 : 2;
-  __shared__ __attribute__((aligned(16))) __bf16 s_x[2][BM * QM_PITCH];
-  __shared__ __attribute__((aligned(16))) __bf16 s_b[2][QM_BN * QM_PITCH];
-  __shared__ float s_code[1 << BITS];
+template <int BITS, bool SPLIT>
+__global__ __launch_bounds__(QM_THREADS, 2) void qmatmul_kernel(QmmArgs a) {
+  typedef QmmLds L;
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
+  float* s_code = reinterpret_cast<float*>(s_raw + L::CODE_BASE);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
-  const int wm = wave >> 1, wn = wave & 1;
-  for (int i = tid; i < (1 << BITS); i += 256) s_code[i] = a.tables->code[Slot<BITS>::value][i];
+  const int wm = wave >> 2, wn = wave & 3;
+  for (int i = tid; i < (1 << BITS); i += QM_THREADS) s_code[i] = a.tables->code[Slot<BITS>::value][i];
 
   // Workgroups go to the 8 XCDs round-robin by linear index.  With at least 8 row tiles every XCD keeps to its own
   // row tiles (its X rows stay in its L2) and sweeps the column tiles; smaller grids are taken in plain order.
@@ -243,37 +319,53 @@ __global__ __launch_bounds__(256, 2) void qmatmul_kernel(QmmArgs a) {
     bm = blockIdx.x / a.tiles_n;
     bn = blockIdx.x % a.tiles_n;
   }
-  const int64_t row0 = (int64_t)bm * BM, col0 = (int64_t)bn * QM_BN;
+  const int64_t row0 = (int64_t)bm * QM_BM, col0 = (int64_t)bn * QM_BN;
   const int s0 = (int)((int64_t)a.nsteps * split / a.splits), s1 = (int)((int64_t)a.nsteps * (split + 1) / a.splits);
 
-  QmmLane<AT> t;
-  t.kg = lane & 7;                     // the thread's 4 x 4 patch of the weight tile: reduction rows 4kg.., columns 4quad..
+  QmmLane t;
+  t.kg = lane & 7;
   t.quad = 8 * wave + (lane >> 3);
   t.col = col0 + 4 * t.quad;
   t.colc = t.col < a.N ? t.col : a.N - 4;          // in the quantized part N is a multiple of the block size, hence of 4
-#pragma unroll
-  for (int i = 0; i < 2 * AT; ++i) {
-    const int idx = tid + 256 * i;
-    int64_t row = row0 + (idx >> 3);
-    row = row < a.m ? row : a.m - 1;               // clamped: loaded, never stored
-    t.xq[i] = a.Xq + row * a.ldxq + (idx & 7) * 4;
-    t.xd[i] = a.Xd + row * a.ldxd + (idx & 7) * 4;
-  }
+  // X transfer: the wavefront's row blocks are 16 * (8j + wave), j < 2; lane -> row lane / 4 of the block and the
+  // stored unit lane % 4, which holds the row's unit (lane % 4) ^ ((row / 2) % 4)
+  const int xr = lane >> 2, xu = (lane & 3) ^ ((xr >> 1) & 3);
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // wavefront-uniform, kept in a scalar register
+  t.xlds = (uint32_t)wave_s * 1024u;
+  // operands: row tile 0 of the wavefront's part, unit (2g + lh) ^ ((row / 2) % 4)
+  const int arow = 128 * wm + ln;
+  t.aoff[0] = (uint32_t)arow * 64u + (uint32_t)(((0 + lh) ^ ((arow >> 1) & 3)) << 4);
+  t.aoff[1] = (uint32_t)arow * 64u + (uint32_t)(((2 + lh) ^ ((arow >> 1) & 3)) << 4);
+  t.boff = (uint32_t)((64 * wn + ln) * QM_PITCH + 8 * lh);
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_raw;
+  const bool multiply_first = wave_s < 4;          // the two wavefronts of a SIMD (w and w + 4) take opposite orders
 
-  floatx16 acc[AT][2];
+  floatx16 acc[QM_AT][2];
 #pragma unroll
-  for (int i = 0; i < AT; ++i)
+  for (int i = 0; i < QM_AT; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  __syncthreads();                     // code book in LDS
 
-  // quantized steps first, then the dense ones (the first barrier of either also covers the code book)
-  const int arow = 32 * AT * wm + ln, brow = 64 * wn + ln;
-  qmm_run<BITS, AT, SPLIT, true, DEPTH>(a, t, s0 < a.nq ? s0 : a.nq, s1 < a.nq ? s1 : a.nq, tid, arow, brow, lh, s_code,
-                                        s_x, s_b, acc);
-  qmm_run<BITS, AT, SPLIT, false, DEPTH>(a, t, (s0 > a.nq ? s0 : a.nq) - a.nq, (s1 > a.nq ? s1 : a.nq) - a.nq, tid, arow,
-                                         brow, lh, s_code, s_x, s_b, acc);
+  // quantized steps first, then the dense ones; the byte offset of the lane's 16 bytes depends on the part's row length.
+  // The order of the two halves of a step is fixed per wavefront, so each order gets its own copy of the loops.
+  const int qa = s0 < a.nq ? s0 : a.nq, qb = s1 < a.nq ? s1 : a.nq;
+  const int da = (s0 > a.nq ? s0 : a.nq) - a.nq, db = (s1 > a.nq ? s1 : a.nq) - a.nq;
+  const uint32_t voff_q = (uint32_t)(((row0 + 16 * wave + xr) * a.Kq + 8 * xu) * 2);
+  const uint32_t voff_d = (uint32_t)(((row0 + 16 * wave + xr) * a.Kd + 8 * xu) * 2);
+  if (multiply_first) {
+    t.xvoff = voff_q;
+    qmm_run<BITS, SPLIT, true, true>(a, t, qa, qb, s_code, s_raw, lds_addr, acc);
+    t.xvoff = voff_d;
+    qmm_run<BITS, SPLIT, false, true>(a, t, da, db, s_code, s_raw, lds_addr, acc);
+  } else {
+    t.xvoff = voff_q;
+    qmm_run<BITS, SPLIT, true, false>(a, t, qa, qb, s_code, s_raw, lds_addr, acc);
+    t.xvoff = voff_d;
+    qmm_run<BITS, SPLIT, false, false>(a, t, da, db, s_code, s_raw, lds_addr, acc);
+  }
 
   // accumulator element e of a lane is row 8*(e/4) + 4*lh + e%4, column ln of its 32 x 32 tile
   float* __restrict__ Y = a.Y + (size_t)split * (size_t)a.m * a.ldy;
@@ -282,10 +374,10 @@ __global__ __launch_bounds__(256, 2) void qmatmul_kernel(QmmArgs a) {
     const int64_t col = col0 + 64 * wn + 32 * j + ln;
     if (col >= a.N) continue;
 #pragma unroll
-    for (int i = 0; i < AT; ++i)
+    for (int i = 0; i < QM_AT; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int64_t row = row0 + 32 * AT * wm + 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
+        const int64_t row = row0 + 128 * wm + 32 * i + 8 * (e >> 2) + 4 * lh + (e & 3);
         if (row < a.m) Y[row * a.ldy + col] = acc[i][j][e];
       }
   }
@@ -304,18 +396,12 @@ __global__ __launch_bounds__(256) void qmatmul_reduce_kernel(const float* __rest
   }
 }
 
-// Rows of an output tile: 256 when that still gives every compute unit a tile, else 128.
-int qmatmul_tile_rows(int64_t m, int64_t N) {
-  return ((m + 255) / 256) * ((N + QM_BN - 1) / QM_BN) >= 256 ? 256 : 128;
-}
-
-// Reduction ranges for an m x N product with `nsteps` 32-deep steps: enough workgroups to occupy every compute unit
-// twice over, at least four steps per range, at most 16 ranges.
+// Reduction ranges for an m x N product with `nsteps` 32-deep steps: enough workgroups to give every compute unit
+// one, at least four steps per range, at most 16 ranges.
 int qmatmul_splits(int64_t m, int64_t N, int nsteps) {
-  const int bm = qmatmul_tile_rows(m, N);
-  const int64_t tiles = ((m + bm - 1) / bm) * ((N + QM_BN - 1) / QM_BN);
-  if (tiles >= 256) return 1;
-  const int64_t want = (512 + tiles - 1) / tiles;
+  const int64_t tiles = ((m + QM_BM - 1) / QM_BM) * ((N + QM_BN - 1) / QM_BN);
+  if (tiles >= 128) return 1;
+  const int64_t want = (256 + tiles - 1) / tiles;
   const int64_t cap = std::max<int64_t>(1, nsteps / 4);
   return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(want, cap), 16));
 }
@@ -325,38 +411,48 @@ size_t qmatmul_part_floats(int64_t m, int64_t N, int nsteps) {
   return s > 1 ? (size_t)s * (size_t)m * (size_t)N : 0;
 }
 
-template <int BITS>
-static void launch_bits(const QmmArgs& a, dim3 grid, int tile_rows, bool split_precision, hipStream_t st) {
-  if (tile_rows == 256) {
-    if (split_precision) hipLaunchKernelGGL((qmatmul_kernel<BITS, 4, true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((qmatmul_kernel<BITS, 4, false>), grid, dim3(256), 0, st, a);
-  } else {
-    if (split_precision) hipLaunchKernelGGL((qmatmul_kernel<BITS, 2, true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((qmatmul_kernel<BITS, 2, false>), grid, dim3(256), 0, st, a);
+template <int BITS, bool SPLIT>
+static int launch_variant(const QmmArgs& a, dim3 grid, hipStream_t st) {
+  static bool raised[64] = {};          // per device: the kernel uses more than the default 64 KB of LDS
+  int dev = 0;
+  LQ_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return LQ_ERR_HIP;
+  if (!raised[dev]) {
+    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&qmatmul_kernel<BITS, SPLIT>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)QmmLds::BYTES));
+    raised[dev] = true;
   }
+  hipLaunchKernelGGL((qmatmul_kernel<BITS, SPLIT>), grid, dim3(QM_THREADS), QmmLds::BYTES, st, a);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
 }
 
-int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t N, float* Y, int64_t ldy, float* part,
-                   size_t part_floats, int precision, hipStream_t st) {
-  if (m <= 0 || N <= 0) return LQ_ERR_SHAPE;
+template <int BITS>
+static int launch_bits(const QmmArgs& a, dim3 grid, bool split_precision, hipStream_t st) {
+  return split_precision ? launch_variant<BITS, true>(a, grid, st) : launch_variant<BITS, false>(a, grid, st);
+}
+
+int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t rows_pad, int64_t N, float* Y, int64_t ldy,
+                   float* part, size_t part_floats, int precision, hipStream_t st) {
+  if (m <= 0 || N <= 0 || rows_pad < m || (rows_pad % 256) != 0) return LQ_ERR_SHAPE;
   if ((q.K % QM_BK) != 0 || (dn.K % QM_BK) != 0 || q.K + dn.K <= 0) return LQ_ERR_SHAPE;
   if (q.K > 0 && (q.block < 4 || (q.block & (q.block - 1)) != 0 || q.scale_block < 1 ||
                   (q.scale_block & (q.scale_block - 1)) != 0))
     return LQ_ERR_CONFIG;                                  // block sizes are powers of two
-  if (q.K > 0 && ((N % q.block) != 0 || (q.ldx & 3) != 0)) return LQ_ERR_SHAPE;
-  if (dn.K > 0 && (dn.ldx & 3) != 0) return LQ_ERR_SHAPE;
+  if (q.K > 0 && (N % q.block) != 0) return LQ_ERR_SHAPE;
+  // the X transfers address a plane with 32-bit byte offsets
+  if (rows_pad * std::max(q.K, dn.K) >= ((int64_t)1 << 31)) return LQ_ERR_SHAPE;
   QmmArgs a{};
-  a.Xq = q.X; a.ldxq = q.ldx; a.Kq = q.K;
+  a.Xqh = q.Xh; a.Xql = q.Xl; a.Kq = q.K;
   a.codes = q.codes; a.sidx = q.sidx; a.v = q.v;
   a.block_shift = q.K > 0 ? __builtin_ctz((unsigned)q.block) : 0;
   a.group_shift = q.K > 0 ? __builtin_ctz((unsigned)q.scale_block) : 0;
   a.levels = q.levels;
-  a.Xd = dn.X; a.ldxd = dn.ldx; a.Kd = dn.K; a.D = dn.D; a.ldd = dn.ldd; a.drows = dn.rows; a.dcols = dn.cols;
+  a.Xdh = dn.Xh; a.Xdl = dn.Xl; a.Kd = dn.K; a.D = dn.D; a.ldd = dn.ldd; a.drows = dn.rows; a.dcols = dn.cols;
   a.m = m; a.N = N;
   a.nq = (int)(q.K / QM_BK);
   a.nsteps = a.nq + (int)(dn.K / QM_BK);
-  const int bm = qmatmul_tile_rows(m, N);
-  a.tiles_m = (int)((m + bm - 1) / bm);
+  a.tiles_m = (int)((m + QM_BM - 1) / QM_BM);
   a.tiles_n = (int)((N + QM_BN - 1) / QM_BN);
   a.splits = qmatmul_splits(m, N, a.nsteps);
   if (a.splits > 1 && part_floats < (size_t)a.splits * (size_t)m * (size_t)N) return LQ_ERR_WORKSPACE;
@@ -372,13 +468,12 @@ int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t N, 
   {
     prof::Scope ps(prof::QMATMUL, st, 2.0 * (double)m * (double)N * (double)(q.K + dn.K));
     switch (bits) {
-      case 2: launch_bits<2>(a, grid, bm, precision == 0, st); break;
-      case 3: launch_bits<3>(a, grid, bm, precision == 0, st); break;
-      case 4: launch_bits<4>(a, grid, bm, precision == 0, st); break;
-      case 8: launch_bits<8>(a, grid, bm, precision == 0, st); break;
+      case 2: LQ_TRY(launch_bits<2>(a, grid, precision == 0, st)); break;
+      case 3: LQ_TRY(launch_bits<3>(a, grid, precision == 0, st)); break;
+      case 4: LQ_TRY(launch_bits<4>(a, grid, precision == 0, st)); break;
+      case 8: LQ_TRY(launch_bits<8>(a, grid, precision == 0, st)); break;
       default: return LQ_ERR_CONFIG;
     }
-    LQ_HIP_TRY(hipGetLastError());
   }
   if (a.splits > 1) {
     prof::Scope ps(prof::MISC, st, 4.0 * (double)m * (double)N * (a.splits + 1));
