@@ -204,8 +204,9 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
  *   precision  0: every operand is split into bf16 hi + lo and each product takes three bf16 MFMAs with fp32
  *                 accumulation (error of an output about 2^-16 of sum |x||w|);  1: bf16 operands, one MFMA
  *                 (about 2^-8), for callers that train in bf16
- *   workspace  lq_matmul_workspace_bytes(m, d, k, rank) bytes: X L1 and, for small m, partial sums
- * d must be a multiple of 32 (LQ_ERR_SHAPE), rank <= 1024 (LQ_ERR_RANK).  Only enqueues work on `stream`; the
+ *   workspace  lq_matmul_workspace_bytes(m, d, k, rank) bytes: the bf16 hi / lo planes of X (rows padded to a
+ *              multiple of 256), X L1 and its planes and, for small m, partial sums
+ * d must be a multiple of 32 and ceil(m / 256) * 256 * d below 2^31 (LQ_ERR_SHAPE), rank <= 1024 (LQ_ERR_RANK).  Only enqueues work on `stream`; the
  * result is deterministic (partial sums are added in a fixed order).
  */
 size_t lq_matmul_workspace_bytes(int64_t m, int64_t d, int64_t k, int rank);

@@ -118,6 +118,32 @@ def test_argument_validation_without_gpu(L):
             > 36 * 4096 * 4096 * 4)                                # every configuration of a batch has its own residual
 
 
+
+def test_matmul_validation_without_gpu(L):
+    vp, i64, it = C.c_void_p, C.c_int64, C.c_int
+    L.lq_matmul.argtypes = [vp, i64, i64, i64, vp, vp, vp, Cfg, vp, vp, it, it, vp, vp, C.c_size_t, vp]
+    L.lq_matmul_workspace_bytes.restype = C.c_size_t
+    L.lq_matmul_workspace_bytes.argtypes = [i64, i64, i64, it]
+    fake = vp(4096)          # never dereferenced: validation fails first
+    ok = Cfg(4, 64, 256, 8, 1)
+
+    def mm(X=fake, m=64, d=256, k=512, cfg=ok, l1=fake, l2=fake, rank=8, prec=0, Y=fake, ws=fake, wsb=1 << 40):
+        return L.lq_matmul(X, m, d, k, fake, fake, fake, cfg, l1, l2, rank, prec, Y, ws, wsb, None)
+    assert mm(X=None) == -1 and mm(Y=None) == -1 and mm(l1=None) == -1
+    assert mm(l1=None, l2=None, rank=0, ws=None) == -6              # rank 0 needs no factors; reaches the workspace check
+    assert mm(m=0) == -2 and mm(d=250) == -2 and mm(k=520) == -2     # d % 32, k % B0
+    assert mm(m=1 << 20, d=4096) == -2                                # planes beyond 32-bit byte offsets
+    assert mm(cfg=Cfg(5, 64, 256, 8, 0)) == -3
+    assert mm(rank=-1) == -4 and mm(rank=2000) == -4
+    assert mm(prec=2) == -8 and mm(X=vp(4096 + 4)) == -8
+    assert mm(ws=None) == -6 and mm(wsb=1024) == -6 and mm(ws=vp(4096 + 8)) == -6
+    need = L.lq_matmul_workspace_bytes(4096, 4096, 4096, 64)
+    assert need >= 4 * 4096 * 4096 + 4 * 4096 * 64                   # the two planes of X, X L1
+    assert L.lq_matmul_workspace_bytes(64, 250, 512, 8) == 0         # invalid shape
+    small = L.lq_matmul_workspace_bytes(16, 4096, 4096, 64)
+    assert small >= 16 * 16 * 4096 * 4                               # 16 reduction ranges of partial sums
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4, 8])
 def test_code_search_equals_brute_force(L, oracle, bits):
     """The search the kernels use (counting for 2/3 bits, bucket table + two comparisons for 4/8 bits),
