@@ -85,6 +85,9 @@ typedef struct {
  *   gemm_mode     arithmetic of the large products against the d x k matrix: 1 = fp32 MFMA; 2 = both operands
  *                 split on the fly into bf16 hi + lo and multiplied by three bf16 MFMAs with fp32 accumulation
  *                 (products good to about 2^-16 relative, several times faster).  Default 2.
+ *   init_quantized  lq_decompose only: 1 starts Algorithm 2 from Q(0) = Quantize(W) instead of Q(0) = 0 (the
+ *                 variant of the footnote in Section 3.1: the first Factorize then sees W - Quantize(W)).
+ *                 lq_error_table rejects it (LQ_ERR_ARG): its configurations share the first Factorize.
  */
 typedef struct {
   int32_t first_width;
@@ -97,6 +100,7 @@ typedef struct {
   int32_t max_batch;
   int32_t gemm_mode;
   int32_t streams;
+  int32_t init_quantized;
 } lq_svd_params;
 
 const char* lq_status_string(int status);

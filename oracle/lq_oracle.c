@@ -416,10 +416,10 @@ static double oq_lowrank_residual(const float* W, const float* L1, const float* 
  * Outputs (any may be NULL except L1, L2): codes[n] unpacked, scale_idx, v, Qd (dense Q, fp32),
  * err (eps of the last executed iteration), trace[iters], iters_done, sigma[r] of the last
  * Factorize. */
-int oq_lq(const float* W, int d, int k, int r, oq_config c, int iters, int early_stop,
+int oq_lq_init(const float* W, int d, int k, int r, oq_config c, int iters, int early_stop,
           const float* row_w, const float* col_w, float* L1, float* L2, uint8_t* codes,
           uint8_t* scale_idx, float* v, float* Qd, double* err, double* trace, int32_t* iters_done,
-          double* sigma) {
+          double* sigma, int init_quantized) {
   const int64_t n = (int64_t)d * k;
   if (!oq_config_ok(c) || n % c.block != 0 || iters < 1) return OQ_ERR;
   if ((row_w == NULL) != (col_w == NULL)) return OQ_ERR;
@@ -431,6 +431,10 @@ int oq_lq(const float* W, int d, int k, int r, oq_config c, int iters, int early
   uint8_t* si = (uint8_t*)malloc((size_t)nb);
   float* vv = (float*)malloc(sizeof(float) * (size_t)ng);
   if (!Q || !A || !T || !cd || !si || !vv) return OQ_ERR;
+  if (init_quantized) {   /* Section 3.1, footnote on the initialisation: Q(0) = Quantize(W) instead of 0 */
+    if (oq_quantize(W, n, c, cd, si, vv, NULL) != OQ_OK) return OQ_ERR;
+    oq_dequantize(cd, si, vv, n, c, Q);
+  }
   double prev = INFINITY, eps = INFINITY;
   int t = 0, rc = OQ_OK;
   for (t = 1; t <= iters; ++t) {
@@ -466,6 +470,14 @@ int oq_lq(const float* W, int d, int k, int r, oq_config c, int iters, int early
   if (Qd) memcpy(Qd, Q, sizeof(float) * (size_t)n);
   free(Q); free(A); free(T); free(cd); free(si); free(vv);
   return rc;
+}
+
+/* Algorithm 2 as printed: Q(0) = 0. */
+int oq_lq(const float* W, int d, int k, int r, oq_config c, int iters, int early_stop,
+          const float* row_w, const float* col_w, float* L1, float* L2, uint8_t* codes,
+          uint8_t* scale_idx, float* v, float* Qd, double* err, double* trace, int32_t* iters_done,
+          double* sigma) {
+  return oq_lq_init(W, d, k, r, c, iters, early_stop, row_w, col_w, L1, L2, codes, scale_idx, v, Qd, err, trace, iters_done, sigma, 0);
 }
 
 /* Inner loops of GetConfig (Algorithm 3): E[c] = eps^2, S[c] = storage(W, c) for every config. */

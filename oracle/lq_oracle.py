@@ -171,7 +171,8 @@ def factorize(a: np.ndarray, r: int, row_w=None, col_w=None):
     return l1, l2, sg
 
 
-def lq(w: np.ndarray, r: int, cfg: Config, iters: int, early_stop: bool = False, row_w=None, col_w=None):
+def lq(w: np.ndarray, r: int, cfg: Config, iters: int, early_stop: bool = False, row_w=None, col_w=None,
+       init_quantized: bool = False):
     """Algorithm 2.  -> dict(L1, L2, codes, scale_idx, v, Q, err, trace, iters_done, sigma)."""
     w = np.ascontiguousarray(w, np.float32)
     d, k = w.shape
@@ -184,11 +185,12 @@ def lq(w: np.ndarray, r: int, cfg: Config, iters: int, early_stop: bool = False,
                scale_idx=np.zeros(nb, np.uint8), v=np.zeros(ng, np.float32), Q=np.zeros((d, k), np.float32),
                trace=np.full(iters, np.nan), sigma=np.zeros(r))
     err = C.c_double(0.0); done = C.c_int32(0)
-    rc = lib().oq_lq(_p(w, C.c_float), C.c_int(d), C.c_int(k), C.c_int(r), cfg, C.c_int(iters),
+    rc = lib().oq_lq_init(_p(w, C.c_float), C.c_int(d), C.c_int(k), C.c_int(r), cfg, C.c_int(iters),
                      C.c_int(1 if early_stop else 0), _p(rw, C.c_float), _p(cw, C.c_float),
                      _p(out["L1"], C.c_float), _p(out["L2"], C.c_float), _p(out["codes"], C.c_uint8),
                      _p(out["scale_idx"], C.c_uint8), _p(out["v"], C.c_float), _p(out["Q"], C.c_float),
-                     C.byref(err), _p(out["trace"], C.c_double), C.byref(done), _p(out["sigma"], C.c_double))
+                     C.byref(err), _p(out["trace"], C.c_double), C.byref(done), _p(out["sigma"], C.c_double),
+                     C.c_int(1 if init_quantized else 0))
     if rc != 0:
         raise ValueError("oq_lq failed")
     out["err"] = err.value

@@ -27,7 +27,7 @@ static int64_t up32(int64_t x) { return (x + 31) / 32 * 32; }
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Params {
-  int l1, check, maxit, lw, qw, qw2, max_batch, prec, streams;
+  int l1, check, maxit, lw, qw, qw2, max_batch, prec, streams, init_quantized;
   double tol;
 };
 
@@ -47,6 +47,8 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   out.prec = z.gemm_mode == 1 ? 0 : 1;
   out.streams = z.streams ? z.streams : 3;
   if (out.streams < 1 || out.streams > 4) return LQ_ERR_ARG;
+  if (z.init_quantized != 0 && z.init_quantized != 1) return LQ_ERR_ARG;
+  out.init_quantized = z.init_quantized;
   if (out.l1 % 32 || out.l1 <= rank || out.l1 > 256) return LQ_ERR_ARG;
   if (out.lw % 32 || out.lw <= rank || out.lw > out.l1) return LQ_ERR_ARG;
   if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.max_batch < 1) return LQ_ERR_ARG;
@@ -353,8 +355,34 @@ struct Loop {
     a.err_part = c->at<double>(pl.epart); a.strideErrPart = pl.strideEpart;
     errs = c->at<double>(pl.errs);
     a.strideErrOut = MAX_ITERS;
+    set_first(Y1, B1);
+    return LQ_OK;
+  }
+
+  // The factors of the first Factorize (cold start): shared by every problem of the batch.
+  void set_first(const float* Yfirst, const float* Bfirst) {
+    Y1 = Yfirst; B1 = Bfirst;
     Ycur = Y1; Bcur = B1; sY = 0; sB = 0;
     lamcur = c->lam_cold;
+  }
+
+  // Q(0) = Quantize(W) (Section 3.1, footnote on the initialisation): quantizes W - 0 with the zeroed warm bases as
+  // factors and leaves the input of the first Factorize, W - Q(0) (scaled when weighted), in the residual buffer.
+  int init_quantized(const float** A0) {
+    const Plan& pl = c->pl;
+    a.Y = w.Yw; a.B = w.Bw; a.strideY = pl.strideYw; a.strideB = pl.strideBw;
+    a.R = nullptr; a.Qd = nullptr; a.err_out = errs;
+    if (pl.stridePacked) {
+      a.packed = c->at<uint16_t>(pl.packed); a.stridePacked = pl.stridePacked;
+      LQ_TRY(launch_pack_factors(a, c->st));
+    } else {
+      a.packed = nullptr; a.stridePacked = 0;
+    }
+    LQ_TRY(launch_lowrank_blockquant(a, false, c->st));
+    LQ_TRY(launch_scalequant_error(a, min_block, false, c->st));
+    a.R = c->at<float>(pl.R); a.strideR = pl.strideR;
+    LQ_TRY(launch_residual(a, c->st));
+    *A0 = a.R;
     return LQ_OK;
   }
 
@@ -515,15 +543,17 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   LQ_TRY(check_workspace(workspace, workspace_bytes, c.pl.total));
   LQ_TRY(setup_common(c, W, row_w, col_w, workspace, (hipStream_t)stream));
   const float* A0; const float* Y1; const float* B1;
-  LQ_TRY(first_input(c, &A0));
-  LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));
   LoopOut direct{q_codes, q_scale_idx, q_v, Q_dense};
   std::vector<double> trace(iters, NAN);
   int32_t done = 0;
   Loop lp;
   lp.c = &c; lp.cfgs = &cfg; lp.batch = 1; lp.iters = iters; lp.early_stop = early_stop;
-  lp.want_trace = err_trace != nullptr; lp.Y1 = Y1; lp.B1 = B1; lp.direct = &direct;
+  lp.want_trace = err_trace != nullptr; lp.direct = &direct;
   LQ_TRY(lp.begin());
+  if (prm.init_quantized) LQ_TRY(lp.init_quantized(&A0));
+  else LQ_TRY(first_input(c, &A0));
+  LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));
+  lp.set_first(Y1, B1);
   for (int t = 1; t <= iters; ++t) LQ_TRY(lp.step(t));
   LQ_TRY(lp.finish(trace.data(), &done));
   LQ_TRY(emit_factors(c, lp.Ycur, lp.Bcur, lp.lamcur, L1, L2, sigma));
@@ -550,6 +580,7 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
   if (!aligned16(W)) return LQ_ERR_ARG;
   Params prm;
   LQ_TRY(resolve_params(rank, p, prm));
+  if (prm.init_quantized) return LQ_ERR_ARG;   // the sweep shares the first Factorize between configurations
   // The configurations of a batch are split over `streams` sub-batches, each with its own stream and workspace
   // slice; the host enqueues their iterations alternately, so the latency-bound single-workgroup steps of one
   // sub-batch (Cholesky, Jacobi) overlap the bandwidth- and MFMA-bound kernels of the other.

@@ -136,6 +136,37 @@ def test_decompose_block128_both_precisions(env, oracle, gemm_mode):
     check_decomposition_consistency(oracle, w, out, ocfg, 8)
 
 
+@pytest.mark.parametrize("weighted", [False, True])
+def test_decompose_quantized_initialisation(env, oracle, weighted):
+    """Q(0) = Quantize(W) (Section 3.1, footnote) against the oracle's same variant."""
+    torch, lq = env
+    d, k, r = 192, 384, 8
+    w = gen.weight_matrix(d, k, 4242, 12, outlier_frac=0.004)
+    rw = cw = grw = gcw = None
+    if weighted:
+        rw, cw = gen.positive_weights(d, 5), gen.positive_weights(k, 6)
+        grw, gcw = torch.from_numpy(rw).cuda(), torch.from_numpy(cw).cuda()
+    ocfg = oracle.config(3, 32, 64)
+    ref = oracle.lq(w, r, ocfg, 4, row_w=rw, col_w=cw, init_quantized=True)
+    wt = torch.from_numpy(w).cuda()
+    out = lq.decompose(wt, r, lq.config(3, 32, 64), 4, row_w=grw, col_w=gcw, seed=3, want_dense=True,
+                       params=lq.SvdParams(init_quantized=1))
+    print("oracle trace", ref["trace"], "\ngpu trace   ", out["trace"])
+    assert np.max(np.abs(out["trace"] - ref["trace"]) / ref["trace"]) < ERR_TOL
+    check_decomposition_consistency(oracle, w, out, ocfg, r, rw, cw)
+    # first Factorize on an identical input, W - Quantize(W): singular values to 1e-4
+    one = lq.decompose(wt, r, lq.config(3, 32, 64), 1, row_w=grw, col_w=gcw, seed=3, params=lq.SvdParams(init_quantized=1))
+    c0, s0, v0, _ = oracle.quantize(w.ravel(), ocfg)
+    a0 = w - oracle.dequantize(c0, s0, v0, ocfg).reshape(w.shape)
+    _, _, osg = oracle.factorize(a0, r, rw, cw)
+    assert np.max(np.abs(one["sigma"] - osg) / osg) < SV_TOL
+    # the variant differs from the default start and the sweep refuses it
+    plain = lq.decompose(wt, r, lq.config(3, 32, 64), 1, row_w=grw, col_w=gcw, seed=3)
+    assert not np.allclose(plain["sigma"], one["sigma"], rtol=1e-3)
+    with pytest.raises(lq.LqError):
+        lq.error_table(wt, r, [lq.config(3, 32, 64)], 2, params=lq.SvdParams(init_quantized=1))
+
+
 def test_decompose_weighted(env, oracle):
     torch, lq = env
     d, k, r = 256, 512, 8

@@ -135,6 +135,31 @@ def test_lq_first_iteration_against_lapack(oracle):
     assert abs(np.linalg.norm(resid) - out["err"]) < 1e-9 * out["err"]
 
 
+def test_lq_quantized_initialisation(oracle):
+    """Q(0) = Quantize(W) (Section 3.1, footnote): the first Factorize sees W - Quantize(W); with one iteration this is
+    the "SVD of the quantization residual" correction, built here from LAPACK and the separately pinned quantizer."""
+    w = gen.weight_matrix(64, 128, 33, 8)
+    cfg = oracle.config(3, 16, 16)
+    r = 6
+    out = oracle.lq(w, r, cfg, 1, init_quantized=True)
+    c0, s0, v0, _ = oracle.quantize(w.ravel(), cfg)
+    q0 = oracle.dequantize(c0, s0, v0, cfg).reshape(w.shape)
+    u, sg, vt = np.linalg.svd((w - q0).astype(np.float64), full_matrices=False)
+    low = (u[:, :r] * sg[:r]) @ vt[:r]
+    assert np.allclose(out["sigma"], sg[:r], rtol=1e-9)
+    assert np.allclose(out["L1"].astype(np.float64) @ out["L2"].astype(np.float64), low, atol=1e-6)
+    c1, s1, v1, _ = oracle.quantize((w.astype(np.float64) - low).astype(np.float32).ravel(), cfg)
+    q1 = oracle.dequantize(c1, s1, v1, cfg).reshape(w.shape)
+    assert np.mean(out["Q"] != q1) < 1e-3
+    eps = np.linalg.norm(w.astype(np.float64) - low - q1)
+    assert abs(out["err"] - eps) < 1e-5 * eps
+    # it is a different starting point, not a relabelling of Algorithm 2: the spectra of W and W - Quantize(W) differ
+    plain = oracle.lq(w, r, cfg, 1)
+    assert not np.allclose(plain["sigma"], out["sigma"], rtol=1e-3)
+    # half-step optimality (Eckart-Young): the low-rank correction of the quantization residual cannot increase it
+    assert np.linalg.norm(w.astype(np.float64) - q0 - low) <= np.linalg.norm(w.astype(np.float64) - q0)
+
+
 def test_lq_weighted_first_iteration_and_error(oracle):
     w = gen.weight_matrix(48, 96, 32, 8)
     rw = gen.positive_weights(48, 1); cw = gen.positive_weights(96, 2)
