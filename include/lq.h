@@ -197,6 +197,17 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * RowAverage / ColAverage of Algorithm 4 (Section 3.3) from a full diagonal Fisher matrix F (d x k fp32, positive):
+ * with a_i, b_j the row and column means of sqrt(F), row_w[i] = a_i^2 and col_w[j] = (b_j / mean(sqrt F))^2, so that
+ * row_w[i] * col_w[j] reproduces F exactly when F has rank one.  Sums are taken in fp64 in a fixed order.  The two
+ * vectors are what lq_factorize / lq_decompose / lq_error_table take as row_w, col_w.  Only enqueues work.
+ *   row_w  d fp32    col_w  k fp32    workspace  lq_fisher_row_col_workspace_bytes(d, k) bytes
+ */
+size_t lq_fisher_row_col_workspace_bytes(int64_t d, int64_t k);
+int lq_fisher_row_col(const float* F, int64_t d, int64_t k, float* row_w, float* col_w, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/*
  * Forward product with a decomposed weight (Section 3.2 "Implementation" and Appendix A: products between fp32
  * inputs and quantized matrices with the matrix dequantized just in time):
  *     Y = X (Q + L1 L2)  computed as  X Q + (X L1) L2,

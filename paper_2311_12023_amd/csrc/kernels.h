@@ -34,6 +34,12 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
                      const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
                      float* part, size_t part_floats, hipStream_t st, int precision = 0, int workgroups = 0);
 
+// Row and column Fisher weights from a full Fisher matrix (Section 3.3): row_w = a^2, col_w = (b / mean(sqrt F))^2
+// with a, b the row / column means of sqrt(F), accumulated in fp64.  scratch: fisher_scratch_doubles(d, k) doubles.
+size_t fisher_scratch_doubles(int64_t d, int64_t k);
+int launch_fisher_row_col(const float* F, int64_t d, int64_t k, double* scratch, float* row_w, float* col_w,
+                          hipStream_t st);
+
 // ---- forward product with a decomposed weight (matmul_kernels.hip) ------------------------------
 // X (rows x K fp32, leading dimension ldx, K and ldx multiples of 4) -> its bf16 halves: hi = bf16(x),
 // lo = bf16(x - hi), planes of rows_pad x K with zero rows beyond `rows`.

@@ -563,6 +563,19 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   return LQ_OK;
 }
 
+size_t lq_fisher_row_col_workspace_bytes(int64_t d, int64_t k) {
+  if (d <= 0 || k <= 0 || d > (1 << 30) || k > (1 << 30)) return 0;
+  return fisher_scratch_doubles(d, k) * sizeof(double) + 256;
+}
+
+int lq_fisher_row_col(const float* F, int64_t d, int64_t k, float* row_w, float* col_w, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  if (!F || !row_w || !col_w) return LQ_ERR_NULL;
+  if (d <= 0 || k <= 0 || d > (1 << 30) || k > (1 << 30)) return LQ_ERR_SHAPE;
+  LQ_TRY(check_workspace(workspace, workspace_bytes, lq_fisher_row_col_workspace_bytes(d, k)));
+  return launch_fisher_row_col(F, d, k, reinterpret_cast<double*>(workspace), row_w, col_w, (hipStream_t)stream);
+}
+
 int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_config* cfgs, int n_cfgs, int iters,
                    int early_stop, const float* row_w, const float* col_w, uint64_t seed, const lq_svd_params* p,
                    double* err_sq, double* storage_bits, double* err_trace, void* workspace, size_t workspace_bytes,

@@ -706,4 +706,84 @@ int launch_assemble_factors(const float* Y, int64_t ldy, const float* B, int64_t
   return LQ_OK;
 }
 
+// ---- RowAverage / ColAverage of sqrt(F) (Section 3.3, Algorithm 4) ----------------------------------------------
+// Pass 1: a workgroup takes FISHER_ROWS rows; thread t walks the columns t, t + 256, ...: it adds sqrt(F) down its
+// column into one partial column sum per workgroup and across into FISHER_ROWS row sums, all in fp64.
+constexpr int FISHER_ROWS = 16;
+
+__global__ __launch_bounds__(256) void fisher_partial_kernel(const float* __restrict__ F, int64_t d, int64_t k,
+                                                             double* __restrict__ rowsum,
+                                                             double* __restrict__ colpart) {
+  __shared__ double s_red[4][FISHER_ROWS];
+  const int64_t row0 = (int64_t)blockIdx.x * FISHER_ROWS;
+  const int tid = threadIdx.x;
+  double racc[FISHER_ROWS];
+#pragma unroll
+  for (int r = 0; r < FISHER_ROWS; ++r) racc[r] = 0.0;
+  for (int64_t c = tid; c < k; c += 256) {
+    double cacc = 0.0;
+#pragma unroll
+    for (int r = 0; r < FISHER_ROWS; ++r) {
+      const double s = row0 + r < d ? sqrt((double)F[(row0 + r) * k + c]) : 0.0;
+      cacc += s;
+      racc[r] += s;
+    }
+    colpart[(size_t)blockIdx.x * k + c] = cacc;
+  }
+#pragma unroll
+  for (int r = 0; r < FISHER_ROWS; ++r) {
+    double x = racc[r];
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    if ((tid & 63) == 0) s_red[tid >> 6][r] = x;
+  }
+  __syncthreads();
+  if (tid < FISHER_ROWS && row0 + tid < d) rowsum[row0 + tid] = (s_red[0][tid] + s_red[1][tid]) + (s_red[2][tid] + s_red[3][tid]);
+}
+
+// Pass 2: every workgroup forms the grand total from the row sums in the same fixed order, then finishes its share
+// of the outputs: row_w = a^2, col_w = (b / mean)^2 with a, b the row and column means of sqrt(F).
+__global__ __launch_bounds__(256) void fisher_finalize_kernel(const double* __restrict__ rowsum,
+                                                              const double* __restrict__ colpart, int64_t d, int64_t k,
+                                                              int chunks, float* __restrict__ row_w,
+                                                              float* __restrict__ col_w) {
+  __shared__ double s_red[4];
+  const int tid = threadIdx.x;
+  double tot = 0.0;
+  for (int64_t i = tid; i < d; i += 256) tot += rowsum[i];
+  for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o);
+  if ((tid & 63) == 0) s_red[tid >> 6] = tot;
+  __syncthreads();
+  const double mean = ((s_red[0] + s_red[1]) + (s_red[2] + s_red[3])) / ((double)d * (double)k);
+  const int64_t gid = (int64_t)blockIdx.x * 256 + tid, stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = gid; i < d; i += stride) {
+    const double a = rowsum[i] / (double)k;
+    row_w[i] = (float)(a * a);
+  }
+  for (int64_t j = gid; j < k; j += stride) {
+    double b = 0.0;
+    for (int ch = 0; ch < chunks; ++ch) b += colpart[(size_t)ch * k + j];
+    b = b / (double)d / mean;
+    col_w[j] = (float)(b * b);
+  }
+}
+
+size_t fisher_scratch_doubles(int64_t d, int64_t k) {
+  return (size_t)d + (size_t)((d + FISHER_ROWS - 1) / FISHER_ROWS) * (size_t)k;
+}
+
+int launch_fisher_row_col(const float* F, int64_t d, int64_t k, double* scratch, float* row_w, float* col_w,
+                          hipStream_t st) {
+  const int64_t chunks = (d + FISHER_ROWS - 1) / FISHER_ROWS;
+  if (chunks >= (1ll << 31)) return LQ_ERR_SHAPE;
+  double* rowsum = scratch;
+  double* colpart = scratch + d;
+  hipLaunchKernelGGL(fisher_partial_kernel, dim3((unsigned)chunks), dim3(256), 0, st, F, d, k, rowsum, colpart);
+  LQ_HIP_TRY(hipGetLastError());
+  const int64_t want = (std::max(d, k) + 255) / 256;
+  hipLaunchKernelGGL(fisher_finalize_kernel, dim3((unsigned)std::min<int64_t>(want, 256)), dim3(256), 0, st, rowsum,
+                     colpart, d, k, (int)chunks, row_w, col_w);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
 }  // namespace lq

@@ -76,6 +76,9 @@ _lib.lq_error_table_workspace_bytes.restype = _sz
 _lib.lq_error_table_workspace_bytes.argtypes = [_i64, _i64, _int, _int, _PP]
 _lib.lq_error_table.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _int, _int, _vp, _vp, C.c_uint64, _PP,
                                 _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.lq_fisher_row_col_workspace_bytes.restype = _sz
+_lib.lq_fisher_row_col_workspace_bytes.argtypes = [_i64, _i64]
+_lib.lq_fisher_row_col.argtypes = [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
 _lib.lq_matmul_workspace_bytes.restype = _sz
 _lib.lq_matmul_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
 _lib.lq_matmul.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, Config, _vp, _vp, _int, _int, _vp, _vp, _sz, _vp]
@@ -240,13 +243,15 @@ def error_table(w: torch.Tensor, rank: int, cfgs, iters: int, early_stop: bool =
 
 
 def fisher_row_col(f: torch.Tensor):
-    """RowAverage / ColAverage of sqrt(F) (Algorithm 4) as Fisher-scale vectors for row_w / col_w:
-    row_w = a^2, col_w = (b / mean(sqrt F))^2 with a, b the row / column means of sqrt(F).
-    Set-up step, run once per matrix with plain tensor ops on the device holding F."""
-    sf = f.to(torch.float64).sqrt()
-    a = sf.mean(dim=1)
-    b = sf.mean(dim=0) / sf.mean()
-    return (a * a).to(torch.float32).contiguous(), (b * b).to(torch.float32).contiguous()
+    """RowAverage / ColAverage of sqrt(F) (Algorithm 4) as Fisher-scale vectors for row_w / col_w."""
+    d, k = f.shape
+    ws = _workspace(_lib.lq_fisher_row_col_workspace_bytes(d, k), f.device)
+    row_w = torch.empty(d, dtype=torch.float32, device=f.device)
+    col_w = torch.empty(k, dtype=torch.float32, device=f.device)
+    _check(_lib.lq_fisher_row_col(_dev(f, torch.float32, "f"), d, k, row_w.data_ptr(), col_w.data_ptr(),
+                                  _aligned_ptr(ws), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()),
+           "lq_fisher_row_col")
+    return row_w, col_w
 
 
 def profile_enable(on: bool) -> None:

@@ -171,8 +171,8 @@ def test_decompose_weighted(env, oracle):
     torch, lq = env
     d, k, r = 256, 512, 8
     w = gen.weight_matrix(d, k, 777, 16, outlier_frac=0.004)
-    f = gen.fisher_matrix(d, k, 778)
-    rw, cw = oracle.fisher_row_col(f)
+    f = gen.fisher_matrix(d, k, 778).astype(np.float32)       # the same fp32 values go to both sides
+    rw, cw = oracle.fisher_row_col(f.astype(np.float64))
     grw, gcw = lq.fisher_row_col(torch.from_numpy(f).cuda())
     assert np.allclose(grw.cpu().numpy(), rw, rtol=1e-6) and np.allclose(gcw.cpu().numpy(), cw, rtol=1e-6)
     ocfg = oracle.config(3, 32, 64)
@@ -182,6 +182,19 @@ def test_decompose_weighted(env, oracle):
     print("oracle trace", ref["trace"], "\ngpu trace   ", out["trace"])
     assert np.max(np.abs(out["trace"] - ref["trace"]) / ref["trace"]) < ERR_TOL
     check_decomposition_consistency(oracle, w, out, ocfg, r, rw, cw)
+
+
+@pytest.mark.parametrize("d,k", [(100, 300), (16, 256), (1, 16), (531, 4099)])
+def test_fisher_row_col_helper(env, oracle, d, k):
+    """RowAverage / ColAverage of Algorithm 4 on the device against the oracle (fp64 sums on both sides, fp32 results
+    equal up to one rounding), at sizes ragged against the kernel's 16-row and 256-column steps."""
+    torch, lq = env
+    f = gen.fisher_matrix(d, k, 900 + d).astype(np.float32)
+    rw, cw = oracle.fisher_row_col(f.astype(np.float64))
+    grw, gcw = lq.fisher_row_col(torch.from_numpy(f).cuda())
+    assert np.max(np.abs(grw.cpu().numpy() - rw) / rw) < 2.5e-7 and np.max(np.abs(gcw.cpu().numpy() - cw) / cw) < 2.5e-7
+    again = lq.fisher_row_col(torch.from_numpy(f).cuda())
+    assert torch.equal(again[0], grw) and torch.equal(again[1], gcw)
 
 
 def test_decompose_early_stop(env, oracle):

@@ -119,6 +119,20 @@ def test_argument_validation_without_gpu(L):
 
 
 
+def test_fisher_helper_validation_without_gpu(L):
+    vp, i64 = C.c_void_p, C.c_int64
+    L.lq_fisher_row_col.argtypes = [vp, i64, i64, vp, vp, vp, C.c_size_t, vp]
+    L.lq_fisher_row_col_workspace_bytes.restype = C.c_size_t
+    L.lq_fisher_row_col_workspace_bytes.argtypes = [i64, i64]
+    fake = vp(4096)
+    assert L.lq_fisher_row_col(None, 8, 8, fake, fake, fake, 1 << 30, None) == -1
+    assert L.lq_fisher_row_col(fake, 8, 8, None, fake, fake, 1 << 30, None) == -1
+    assert L.lq_fisher_row_col(fake, 0, 8, fake, fake, fake, 1 << 30, None) == -2
+    assert L.lq_fisher_row_col(fake, 8, 8, fake, fake, None, 1 << 30, None) == -6
+    assert L.lq_fisher_row_col(fake, 8, 8, fake, fake, fake, 8, None) == -6
+    assert L.lq_fisher_row_col_workspace_bytes(4096, 11008) >= 8 * (4096 + 256 * 11008)
+
+
 def test_matmul_validation_without_gpu(L):
     vp, i64, it = C.c_void_p, C.c_int64, C.c_int
     L.lq_matmul.argtypes = [vp, i64, i64, i64, vp, vp, vp, Cfg, vp, vp, it, it, vp, vp, C.c_size_t, vp]
