@@ -197,6 +197,24 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ILPSolve of Algorithm 3 (the integer program of Section 3.2, "Dynamic quantization configurations"): one
+ * configuration per matrix, minimising the summed error under a storage budget,
+ *     min sum_i err[i][c_i]   s.t.   sum_i storage[i][c_i] <= budget_bits.
+ * Host-only (all pointers are host pointers, no GPU is touched): the paper calls an external solver here.  The
+ * problem is a multiple-choice knapsack; it is solved by branch and bound on its linear relaxation.
+ *   err, storage   n_matrices x n_cfgs doubles, row per matrix (the err_sq / storage_bits rows of lq_error_table);
+ *                  finite and non-negative
+ *   node_limit     0 = search to proven optimality; otherwise stop after this many nodes with the best assignment found
+ *   choice         n_matrices configuration indices            total_err, total_storage   sums of the chosen cells
+ *   lower_bound    a proven lower bound on the optimum: equal to *total_err when the search completed
+ * Any of total_err, total_storage, lower_bound may be NULL.  LQ_ERR_ARG when even the cheapest configuration of
+ * every matrix exceeds the budget, or on non-finite / negative inputs.
+ */
+int lq_assign_configs(const double* err, const double* storage, int n_matrices, int n_cfgs, double budget_bits,
+                      int64_t node_limit, int32_t* choice, double* total_err, double* total_storage,
+                      double* lower_bound);
+
+/*
  * RowAverage / ColAverage of Algorithm 4 (Section 3.3) from a full diagonal Fisher matrix F (d x k fp32, positive):
  * with a_i, b_j the row and column means of sqrt(F), row_w[i] = a_i^2 and col_w[j] = (b_j / mean(sqrt F))^2, so that
  * row_w[i] * col_w[j] reproduces F exactly when F has rank one.  Sums are taken in fp64 in a fixed order.  The two

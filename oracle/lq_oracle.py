@@ -220,3 +220,22 @@ def fisher_row_col(f: np.ndarray):
     rw = np.zeros(d, np.float32); cw = np.zeros(k, np.float32)
     lib().oq_fisher_row_col(_p(f, C.c_double), C.c_int(d), C.c_int(k), _p(rw, C.c_float), _p(cw, C.c_float))
     return rw, cw
+
+
+def assign_bruteforce(err, storage, budget_bits):
+    """The integer program of Section 3.2 by definition: every assignment of one configuration per matrix is tried,
+    the feasible one with the smallest summed error wins (pure Python; tiny instances only).
+    -> (choice list, total error) or (None, inf) when nothing fits."""
+    import itertools
+    err = np.asarray(err, np.float64)
+    storage = np.asarray(storage, np.float64)
+    n, c = err.shape
+    best, best_err = None, float("inf")
+    for pick in itertools.product(range(c), repeat=n):
+        used = sum(storage[i, pick[i]] for i in range(n))
+        if used > budget_bits:
+            continue
+        total = sum(err[i, pick[i]] for i in range(n))
+        if total < best_err:
+            best, best_err = list(pick), total
+    return best, best_err

@@ -76,6 +76,7 @@ _lib.lq_error_table_workspace_bytes.restype = _sz
 _lib.lq_error_table_workspace_bytes.argtypes = [_i64, _i64, _int, _int, _PP]
 _lib.lq_error_table.argtypes = [_vp, _i64, _i64, _int, _vp, _int, _int, _int, _vp, _vp, C.c_uint64, _PP,
                                 _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.lq_assign_configs.argtypes = [_vp, _vp, _int, _int, C.c_double, _i64, _vp, _vp, _vp, _vp]
 _lib.lq_fisher_row_col_workspace_bytes.restype = _sz
 _lib.lq_fisher_row_col_workspace_bytes.argtypes = [_i64, _i64]
 _lib.lq_fisher_row_col.argtypes = [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
@@ -292,3 +293,38 @@ def matmul(x: torch.Tensor, codes: torch.Tensor, scale_idx: torch.Tensor, v: tor
                           _dev(out, torch.float32, "out"), _aligned_ptr(ws),
                           ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()), "lq_matmul")
     return out
+
+
+def assign_configs(err: np.ndarray, storage: np.ndarray, budget_bits: float, node_limit: int = 0):
+    """ILPSolve: -> (choice int32[n_matrices], total_err, total_storage, lower_bound).  Host only."""
+    err = np.ascontiguousarray(err, np.float64)
+    storage = np.ascontiguousarray(storage, np.float64)
+    n, c = err.shape
+    assert storage.shape == (n, c)
+    choice = np.zeros(n, np.int32)
+    te, ts, lb = C.c_double(0), C.c_double(0), C.c_double(0)
+    _check(_lib.lq_assign_configs(err.ctypes.data, storage.ctypes.data, n, c, float(budget_bits), node_limit,
+                                  choice.ctypes.data, C.addressof(te), C.addressof(ts), C.addressof(lb)),
+           "lq_assign_configs")
+    return choice, te.value, ts.value, lb.value
+
+
+def lq_lora_decompose(matrices, rank: int, cfgs, bits_per_weight: float, iters: int, fishers=None, seed: int = 0,
+                      params: SvdParams | None = None):
+    """Algorithm 1 without the finetuning: error tables of all matrices (GetConfig, Algorithm 3), the assignment under
+    the budget bits_per_weight * (total number of weights), then the decomposition of every matrix with its chosen
+    configuration.  matrices: list of fp32 GPU tensors; fishers: None or a list of (row_w, col_w) pairs.
+    -> (choice, list of lq.decompose results, err table, storage table)."""
+    n = len(matrices)
+    err = np.zeros((n, len(cfgs)))
+    sto = np.zeros((n, len(cfgs)))
+    for i, w in enumerate(matrices):
+        rw, cw = fishers[i] if fishers is not None else (None, None)
+        err[i], sto[i] = error_table(w, rank, cfgs, iters, row_w=rw, col_w=cw, seed=seed, params=params)
+    budget = bits_per_weight * sum(w.numel() for w in matrices)
+    choice, _, _, _ = assign_configs(err, sto, budget)
+    outs = []
+    for i, w in enumerate(matrices):
+        rw, cw = fishers[i] if fishers is not None else (None, None)
+        outs.append(decompose(w, rank, cfgs[choice[i]], iters, row_w=rw, col_w=cw, seed=seed, params=params))
+    return choice, outs, err, sto
