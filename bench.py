@@ -155,10 +155,20 @@ def bench_matmul(args, torch, gen, lq, dev) -> int:
                                 "against the dense bf16 peak; algorithmic_tflops counts each product once.  The "
                                 "profiled run brackets every launch with events on the launch stream.")
         out["kernels"] = {n: {"ms": v[0], "launches": v[1]} for n, v in prof.items()}
+    elif "qmatvec_kernel" in prof:                           # few tokens: bound by reading the weights once
+        kms, launches, work = prof["qmatvec_kernel"]
+        ach = work / (kms * 1e-3) / 1e9
+        out["dtype"] = "f32"
+        out["roofline"] = {"kernel": "qmatvec_kernel", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
+                           "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None, "launches": launches,
+                           "avg_us": 1e3 * kms / launches}
+        out["roofline_note"] = ("algorithmic bytes per launch: the packed codes and one scale index per block of the "
+                                "d x k matrix, the rank x k factor, X and Y")
+        out["kernels"] = {n: {"ms": v[0], "launches": v[1]} for n, v in prof.items()}
     if not args.no_cpu_baseline:
         from oracle import lq_oracle as O
         it = items[0]
-        rows = 4
+        rows = min(4, m)
         codes = O.unpack(it["codes"].cpu().numpy(), it["d"] * it["k"], 4)
         t0 = time.perf_counter()
         O.matmul(it["x"][:rows].cpu().numpy(), codes, it["sidx"].cpu().numpy(), it["v"].cpu().numpy(),

@@ -231,12 +231,14 @@ int lq_fisher_row_col(const float* F, int64_t d, int64_t k, float* row_w, float*
  *     Y = X (Q + L1 L2)  computed as  X Q + (X L1) L2,
  * Q given in the quantized form that lq_decompose / lq_nf_quantize produce; its weights are decoded inside the
  * GEMM's load stage and never written to memory.
- *   X        m x d fp32, 16-byte aligned          Y        m x k fp32
+ *   X        m x d fp32, 16-byte aligned          Y        m x k fp32, 16-byte aligned (so is L2)
  *   codes_packed, scale_idx, v    Quantize(Q, c) of the d x k matrix Q (row-major flattening); k % B0 == 0
  *   L1, L2   d x rank and rank x k fp32, or rank == 0 (then both may be NULL): Y = X Q
  *   precision  0: every operand is split into bf16 hi + lo and each product takes three bf16 MFMAs with fp32
  *                 accumulation (error of an output about 2^-16 of sum |x||w|);  1: bf16 operands, one MFMA
  *                 (about 2^-8), for callers that train in bf16
+ *              With m <= 8 and rank <= 512 the product is bound by reading the weights once; it then runs in plain
+ *              fp32 on the vector ALU (exact products, fp32 accumulation) and `precision` is ignored.
  *   workspace  lq_matmul_workspace_bytes(m, d, k, rank) bytes: the bf16 hi / lo planes of X (rows padded to a
  *              multiple of 256), X L1 and its planes and, for small m, partial sums
  * d must be a multiple of 32 and ceil(m / 256) * 256 * d below 2^31 (LQ_ERR_SHAPE), rank <= 1024 (LQ_ERR_RANK).  Only enqueues work on `stream`; the

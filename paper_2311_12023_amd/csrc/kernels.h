@@ -67,6 +67,29 @@ size_t qmatmul_part_floats(int64_t m, int64_t N, int nsteps);
 int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t rows_pad, int64_t N, float* Y, int64_t ldy,
                    float* part, size_t part_floats, int precision, hipStream_t st);
 
+// Y = sum of `splits` partial results (each m x N, contiguous, one after the other in `part`), in order.
+int launch_qmatmul_reduce(const float* part, int splits, int64_t m, int64_t N, float* Y, int64_t ldy, hipStream_t st);
+
+// ---- forward product for a few rows of X (matvec_kernels.hip) ------------------------------------
+constexpr int QMATVEC_MAX_ROWS = 8;
+// The K x N quantized right-hand side (row-major flattening, N a multiple of `block` and of 16).
+struct MvWeights {
+  const uint8_t* codes; const uint8_t* sidx; const float* v;
+  int bits, block, scale_block, levels;
+};
+// Y[m x N] = X[m x K] * dequant(q) + Xd[m x Kd] * D[Kd x N] (Kd may be 0), m <= QMATVEC_MAX_ROWS, in fp32 on the
+// vector ALU.  ldd and ldy are multiples of 4.  part: qmatvec_part_floats(m, K + Kd, N) floats of scratch.
+int qmatvec_splits(int m, int64_t ktot, int64_t N);
+size_t qmatvec_part_floats(int m, int64_t ktot, int64_t N);
+int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, const float* Xd, int64_t ldxd,
+                   const float* D, int64_t ldd, int64_t Kd, int m, int64_t N, float* Y, int64_t ldy, float* part,
+                   size_t part_floats, hipStream_t st);
+// T[m x N] = X[m x K] * D[K x N] for a narrow dense D (N at most a few hundred), m <= QMATVEC_MAX_ROWS.
+// part: xdense_part_floats(m, K, N) floats of scratch.
+size_t xdense_part_floats(int m, int64_t K, int64_t N);
+int launch_xdense_narrow(const float* X, int64_t ldx, const float* D, int64_t ldd, int64_t K, int N, int m, float* T,
+                         int64_t ldt, float* part, size_t part_floats, hipStream_t st);
+
 // ---- small dense kernels (small_kernels.hip) --------------------------------------------------
 constexpr int GRAM_CHUNKS = 16;
 // G[z] (l x l, fp64, row-major) = X[z] X[z]^T for wide X (l x m, fp32).  `part` holds

@@ -1,4 +1,6 @@
 // C ABI of the forward product with a decomposed weight (Section 3.2 "Implementation", Appendix A).
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace lq {
@@ -7,12 +9,27 @@ int check_quant_args(int64_t n, lq_config& c);
 static size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
 static int64_t up32(int64_t x) { return (x + 31) & ~(int64_t)31; }
 
+// Few rows of X: the product is bound by reading the weights and runs on the vector ALU (measured faster than the
+// MFMA path up to 8 rows).
+constexpr int64_t SMALL_M = QMATVEC_MAX_ROWS;
+constexpr int SMALL_RANK = 512;
+
 struct MatmulPlan {
+  bool small;
   int64_t r32, rows_pad;
   size_t x_plane, t_floats, t_plane, part_floats;   // elements
 };
 static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   MatmulPlan p{};
+  p.small = m <= SMALL_M && rank <= SMALL_RANK;
+  if (p.small) {
+    const int mc = (int)std::min<int64_t>(m, QMATVEC_MAX_ROWS);
+    p.t_floats = (size_t)m * (size_t)rank;
+    const size_t p1 = rank > 0 ? xdense_part_floats(mc, d, rank) : 0;
+    const size_t p2 = qmatvec_part_floats(mc, d + rank, k);
+    p.part_floats = p1 > p2 ? p1 : p2;
+    return p;
+  }
   p.r32 = up32(rank);
   p.rows_pad = (m + 255) / 256 * 256;
   p.x_plane = (size_t)p.rows_pad * (size_t)d;
@@ -49,19 +66,33 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   LQ_TRY(check_quant_args(d * k, c));
   if ((k % c.block) != 0) return LQ_ERR_SHAPE;
   if (precision != 0 && precision != 1) return LQ_ERR_ARG;
-  if (((uintptr_t)X & 15) != 0) return LQ_ERR_ARG;
+  if (((uintptr_t)X & 15) != 0 || ((uintptr_t)Y & 15) != 0 || (rank > 0 && ((uintptr_t)L2 & 15) != 0)) return LQ_ERR_ARG;
   const MatmulPlan p = plan_matmul(m, d, k, rank);
   if (p.rows_pad * d >= ((int64_t)1 << 31)) return LQ_ERR_SHAPE;   // planes are addressed with 32-bit byte offsets
   const size_t need = plan_bytes(p) + 256;
   if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return LQ_ERR_WORKSPACE;
   char* w = reinterpret_cast<char*>(workspace);
+  hipStream_t st = (hipStream_t)stream;
+  if (p.small) {
+    // plan_bytes lays the regions out in the same order with empty planes
+    float* T = reinterpret_cast<float*>(w); w += up256(p.t_floats * 4);
+    float* part = reinterpret_cast<float*>(w);
+    const MvWeights q{codes_packed, scale_idx, v, c.bits, c.block, c.scale_block, scale_levels(c)};
+    for (int64_t r0 = 0; r0 < m; r0 += QMATVEC_MAX_ROWS) {
+      const int mc = (int)std::min<int64_t>(QMATVEC_MAX_ROWS, m - r0);
+      const float* Xc = X + r0 * d;
+      float* Tc = T + r0 * rank;
+      if (rank > 0) LQ_TRY(launch_xdense_narrow(Xc, d, L1, rank, d, rank, mc, Tc, rank, part, p.part_floats, st));
+      LQ_TRY(launch_qmatvec(q, Xc, d, d, Tc, rank, L2, k, rank, mc, k, Y + r0 * k, k, part, p.part_floats, st));
+    }
+    return LQ_OK;
+  }
   uint16_t* xh = reinterpret_cast<uint16_t*>(w); w += up256(p.x_plane * 2);
   uint16_t* xl = reinterpret_cast<uint16_t*>(w); w += up256(p.x_plane * 2);
   float* T = reinterpret_cast<float*>(w); w += up256(p.t_floats * 4);
   uint16_t* th = reinterpret_cast<uint16_t*>(w); w += up256(p.t_plane * 2);
   uint16_t* tl = reinterpret_cast<uint16_t*>(w); w += up256(p.t_plane * 2);
   float* part = reinterpret_cast<float*>(w);
-  hipStream_t st = (hipStream_t)stream;
 
   LQ_TRY(launch_split_planes(X, m, d, d, p.rows_pad, xh, xl, st));
   QmmPart none{};

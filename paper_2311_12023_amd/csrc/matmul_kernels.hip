@@ -391,7 +391,8 @@ __global__ __launch_bounds__(256) void qmatmul_reduce_kernel(const float* __rest
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     const int64_t row = i / N, col = i % N;
     float s = 0.0f;
-    for (int z = 0; z < splits; ++z) s += part[((size_t)z * m + row) * ldp + col];
+#pragma unroll 8
+    for (int z = 0; z < splits; ++z) s += part[((size_t)z * m + row) * ldp + col];   // added in range order
     Y[row * ldy + col] = s;
   }
 }
@@ -475,12 +476,15 @@ int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t row
       default: return LQ_ERR_CONFIG;
     }
   }
-  if (a.splits > 1) {
-    prof::Scope ps(prof::MISC, st, 4.0 * (double)m * (double)N * (a.splits + 1));
-    const int64_t nwg = std::min<int64_t>((m * N + 255) / 256, 4096);
-    hipLaunchKernelGGL(qmatmul_reduce_kernel, dim3((unsigned)nwg), dim3(256), 0, st, part, a.splits, m, N, N, Y, ldy);
-    LQ_HIP_TRY(hipGetLastError());
-  }
+  if (a.splits > 1) LQ_TRY(launch_qmatmul_reduce(part, a.splits, m, N, Y, ldy, st));
+  return LQ_OK;
+}
+
+int launch_qmatmul_reduce(const float* part, int splits, int64_t m, int64_t N, float* Y, int64_t ldy, hipStream_t st) {
+  prof::Scope ps(prof::MISC, st, 4.0 * (double)m * (double)N * (splits + 1));
+  const int64_t nwg = std::min<int64_t>((m * N + 255) / 256, 4096);
+  hipLaunchKernelGGL(qmatmul_reduce_kernel, dim3((unsigned)nwg), dim3(256), 0, st, part, splits, m, N, N, Y, ldy);
+  LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }
 

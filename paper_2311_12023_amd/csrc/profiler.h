@@ -21,7 +21,8 @@ enum Cls {
   MISC = 26,
   GEMM_SPLIT_BASE = 27,     // + mode * 8 + (l/32 - 1): the bf16 hi/lo split variants of wide_gemm_kernel
   QMATMUL = 43,             // qmatmul_kernel (work = flops of the product)
-  NUM_CLASSES = 44
+  QMATVEC = 44,             // qmatvec_kernel (work = bytes)
+  NUM_CLASSES = 45
 };
 
 bool enabled();

@@ -6,7 +6,8 @@ most 2^-18 of an operand, the omitted lo*lo term is at most 2^-18 of a product, 
 3 * 2^-18 = 1.1e-5 of |x||w|; fp32 accumulation over K terms adds about sqrt(K) * 2^-24 in practice.  The bound
 used is 4e-5 * S with S = |X| (|Q| + |L1||L2|) elementwise, which the oracle returns.  Precision 1 (bf16 operands)
 rounds each operand to 2^-9: 2^-8 per product, bound 1e-2 * S.  The quantized operand itself is exact: the kernel
-multiplies the same fl32(code * scale) values that Dequantize returns.
+multiplies the same fl32(code * scale) values that Dequantize returns.  Up to 8 rows of X (and rank <= 512) the product
+runs in plain fp32 on the vector ALU whatever the precision argument says, and is held to the tighter bound as well.
 """
 import numpy as np
 import pytest
@@ -51,6 +52,13 @@ def _gpu_product(env, oracle, x, codes, sidx, v, cfg_tuple, k, l1, l2, precision
     (257, 160, 144, (2, 16, 16), 8),         # three row tiles, column tile cut at 144
     (64, 512, 128, (8, 64, 64), 40),         # 8-bit codes, rank that is not a multiple of 32
     (300, 64, 2048, (4, 32, 64), 33),        # wide output
+    (8, 256, 384, (4, 64, 256), 64),         # few rows: the vector-ALU path, one full chunk of 8 rows
+    (6, 160, 528, (3, 16, 16), 7),           # 3-bit runs, columns ragged against 128, rank not a multiple of anything
+    (4, 1056, 272, (8, 16, 64), 40),         # 8-bit runs, reduction ranges of unequal length
+    (2, 4192, 144, (2, 16, 16), 33),         # 2-bit runs, several ranges with the dense rows in the last one
+    (20, 160, 528, (3, 16, 16), 7),          # just above that path's limit
+    (3, 96, 64, (2, 32, 16), 1),             # rank 1
+    (5, 64, 128, (4, 64, 16), 600),          # a rank beyond that path's limit goes to the MFMA kernel
 ])
 def test_matmul_matches_oracle(env, oracle, m, d, k, cfg, rank):
     ocfg, codes, sidx, v, l1, l2 = _case(oracle, d, k, cfg, rank, 100 + m)

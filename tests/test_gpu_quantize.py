@@ -105,6 +105,18 @@ def test_quantize_determinism_and_full_size_samples(lq, oracle):
             assert np.array_equal(out[sl], oracle.dequantize(oc, osi, ov, oracle.config(*cfg_t)))
 
 
+def test_nf8_of_low_rank_factors(lq, oracle):
+    """The low-rank pair itself stored in NF-8 (Section 4, post-training quantization: NF-4's settings with 8-bit
+    first-level codes): the factors of a rank-64 decomposition of a 4096-wide matrix, bit for bit, and small error."""
+    l1, l2 = gen.low_rank_factors(4096, 11008, 64, 4321)
+    for x in (l1, l2):
+        run_pair(lq, oracle, x.ravel(), (8, 64, 256), 8, "bf16")
+        ocfg = oracle.config(8, 64, 256, 8, "bf16")
+        c, s, v, _ = oracle.quantize(x.ravel(), ocfg)
+        back = oracle.dequantize(c, s, v, ocfg)
+        assert np.linalg.norm(back - x.ravel()) < 1.5e-2 * np.linalg.norm(x)
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4, 5, 8])
 @pytest.mark.parametrize("count", [1, 7, 8, 1000, 65537])
 def test_scale_index_bit_stream(lq, oracle, bits, count):
