@@ -46,13 +46,14 @@ def cpu_baseline(first_matrix: np.ndarray) -> dict:
 
 
 TRAFFIC_TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "llama7b_layer_sweep_hbm_traffic.md")
+FORWARD_TRAFFIC_TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "llama7b_layer_forward_kernel_stats.md")
 
 
-def measured_traffic(name: str):
+def measured_traffic(name: str, table: str | None = None):
     """HBM-side bytes per launch of a kernel class (fetch + write) from the committed counter summary, averaged over
     the class's template variants weighted by launches; None when the summary does not list the kernel."""
     try:
-        lines = open(TRAFFIC_TABLE).read().splitlines()
+        lines = open(table or TRAFFIC_TABLE).read().splitlines()
     except OSError:
         return None
     base = name.split("<")[0]
@@ -147,8 +148,11 @@ def bench_matmul(args, torch, gen, lq, dev) -> int:
         kms, launches, work = prof["qmatmul_kernel"]
         mult = 3.0 if args.precision == 0 else 1.0          # bf16 MFMAs executed per product
         ach = mult * work / (kms * 1e-3) / 1e12
+        traffic = None
+        if m == 4096 and len(items) == 7 and args.precision == 0:      # the configuration the counter runs measured
+            traffic = measured_traffic("qmatmul_kernel", FORWARD_TRAFFIC_TABLE)
         out["roofline"] = {"kernel": "qmatmul_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS,
-                           "unit": "TFLOP/s", "frac": ach / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                           "unit": "TFLOP/s", "frac": ach / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic,
                            "launches": launches, "avg_us": 1e3 * kms / launches,
                            "algorithmic_tflops": work / (kms * 1e-3) / 1e12}
         out["roofline_note"] = ("achieved counts the bf16 MFMA flops the kernel executes (3 per product at precision 0) "
