@@ -164,15 +164,18 @@ int lq_factorize(const float* A, int64_t d, int64_t k, int rank, const float* ro
  * LQ(W, F, c, r) of Algorithm 2 (Eq. 2): Q <- 0; repeat `iters` times
  *   L1, L2 <- Factorize(W - Q, F, r);  Q <- Quantize(W - L1 L2, c);
  *   eps_t = || sqrt(F) .* (W - Q - L1 L2) ||_F  with F_ij = row_w[i]*col_w[j] (Eq. 4), or F = 1.
- * With early_stop != 0 the loop ends after the first iteration whose eps exceeds the previous one and
- * returns that iterate, as Algorithm 2 prints it (this mode synchronizes once per iteration).
+ * With early_stop == 1 the loop ends after the first iteration whose eps exceeds the previous one and
+ * returns that iterate, as Algorithm 2 prints it (this mode synchronizes once per iteration).  early_stop == 2 stops
+ * by the same rule but returns the iterate before it, the one with the smallest eps seen (a variant, not the
+ * paper's listing): L1, L2, the quantized component, sigma and err then belong to iteration iters_done - 1, or to
+ * iteration iters when the error never went up.  Other values: LQ_ERR_ARG.
  *   W            d x k
  *   L1, L2       d x rank, rank x k (balanced factors of the last Factorize)
  *   q_codes, q_scale_idx, q_v   the quantized component, laid out as for lq_nf_quantize (n = d*k)
  *   Q_dense      d x k dequantized Q, or NULL
- *   err          host, 1 double: eps of the last iteration run        (may be NULL)
+ *   err          host, 1 double: eps of the returned iterate          (may be NULL)
  *   err_trace    host, iters doubles: eps_1..; entries past iters_done are NaN   (may be NULL)
- *   iters_done   host, 1 int32                                         (may be NULL)
+ *   iters_done   host, 1 int32: iterations run                         (may be NULL)
  *   sigma        host, rank doubles: singular values of the last Factorize (may be NULL)
  */
 size_t lq_decompose_workspace_bytes(int64_t d, int64_t k, int rank, const lq_svd_params* p);
@@ -186,7 +189,8 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config c, in
  * Inner loops of GetConfig (Algorithm 3) for one matrix: for every configuration c of `cfgs`,
  * err_sq[c] = eps^2 of LQ(W, F, c, rank) and storage_bits[c] = storage(W, c) (Eq. 3).
  * The first Factorize (Q = 0) does not depend on c and is computed once; the configurations then
- * advance in lock step, `max_batch` at a time.
+ * advance in lock step, `max_batch` at a time.  early_stop as for lq_decompose: err_sq is that of the iterate
+ * lq_decompose would return (the rule is applied to the finished traces, every configuration runs `iters` iterations).
  *   cfgs          host, n_cfgs entries           err_sq, storage_bits   host, n_cfgs doubles each
  *   err_trace     host, n_cfgs * iters doubles (row per configuration), or NULL
  */

@@ -435,9 +435,26 @@ int oq_lq_init(const float* W, int d, int k, int r, oq_config c, int iters, int 
     if (oq_quantize(W, n, c, cd, si, vv, NULL) != OQ_OK) return OQ_ERR;
     oq_dequantize(cd, si, vv, n, c, Q);
   }
+  /* early_stop == 2 (a variant, not the listing): the iterate before the error went up is returned, so a copy of
+   * the previous iterate's pieces is kept */
+  const int keep = early_stop == 2;
+  float* pL1 = keep ? (float*)malloc(sizeof(float) * (size_t)d * r) : NULL;
+  float* pL2 = keep ? (float*)malloc(sizeof(float) * (size_t)r * k) : NULL;
+  float* pQ = keep ? (float*)malloc(sizeof(float) * (size_t)n) : NULL;
+  uint8_t* pcd = keep ? (uint8_t*)malloc((size_t)n) : NULL;
+  uint8_t* psi = keep ? (uint8_t*)malloc((size_t)nb) : NULL;
+  float* pvv = keep ? (float*)malloc(sizeof(float) * (size_t)ng) : NULL;
+  double* psg = keep ? (double*)malloc(sizeof(double) * (size_t)r) : NULL;
+  if (keep && (!pL1 || !pL2 || !pQ || !pcd || !psi || !pvv || !psg)) return OQ_ERR;
   double prev = INFINITY, eps = INFINITY;
   int t = 0, rc = OQ_OK;
   for (t = 1; t <= iters; ++t) {
+    if (keep && t > 1) {
+      memcpy(pL1, L1, sizeof(float) * (size_t)d * r); memcpy(pL2, L2, sizeof(float) * (size_t)r * k);
+      memcpy(pQ, Q, sizeof(float) * (size_t)n); memcpy(pcd, cd, (size_t)n); memcpy(psi, si, (size_t)nb);
+      memcpy(pvv, vv, sizeof(float) * (size_t)ng);
+      if (sigma) memcpy(psg, sigma, sizeof(double) * (size_t)r);
+    }
     for (int64_t e = 0; e < n; ++e) A[e] = W[e] - Q[e];
     rc = oq_factorize(A, d, k, row_w, col_w, r, L1, L2, sigma);
     if (rc != OQ_OK) break;
@@ -459,9 +476,20 @@ int oq_lq_init(const float* W, int d, int k, int r, oq_config c, int iters, int 
     }
     eps = sqrt(acc);
     if (trace) trace[t - 1] = eps;
-    if (early_stop && eps > prev) { ++t; break; }
+    if (early_stop && eps > prev) {
+      if (keep) {           /* hand back iterate t - 1 */
+        memcpy(L1, pL1, sizeof(float) * (size_t)d * r); memcpy(L2, pL2, sizeof(float) * (size_t)r * k);
+        memcpy(Q, pQ, sizeof(float) * (size_t)n); memcpy(cd, pcd, (size_t)n); memcpy(si, psi, (size_t)nb);
+        memcpy(vv, pvv, sizeof(float) * (size_t)ng);
+        if (sigma) memcpy(sigma, psg, sizeof(double) * (size_t)r);
+        eps = prev;
+      }
+      ++t;
+      break;
+    }
     prev = eps;
   }
+  free(pL1); free(pL2); free(pQ); free(pcd); free(psi); free(pvv); free(psg);
   if (iters_done) *iters_done = t - 1;
   if (err) *err = eps;
   if (codes) memcpy(codes, cd, (size_t)n);

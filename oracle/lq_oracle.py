@@ -186,7 +186,7 @@ def lq(w: np.ndarray, r: int, cfg: Config, iters: int, early_stop: bool = False,
                trace=np.full(iters, np.nan), sigma=np.zeros(r))
     err = C.c_double(0.0); done = C.c_int32(0)
     rc = lib().oq_lq_init(_p(w, C.c_float), C.c_int(d), C.c_int(k), C.c_int(r), cfg, C.c_int(iters),
-                     C.c_int(1 if early_stop else 0), _p(rw, C.c_float), _p(cw, C.c_float),
+                     C.c_int(int(early_stop)), _p(rw, C.c_float), _p(cw, C.c_float),
                      _p(out["L1"], C.c_float), _p(out["L2"], C.c_float), _p(out["codes"], C.c_uint8),
                      _p(out["scale_idx"], C.c_uint8), _p(out["v"], C.c_float), _p(out["Q"], C.c_float),
                      C.byref(err), _p(out["trace"], C.c_double), C.byref(done), _p(out["sigma"], C.c_double),

@@ -296,7 +296,11 @@ static int first_input(const Ctx& c, const float** A) {
 
 struct LoopOut {          // batch == 1 only: user buffers that receive the quantized component directly
   uint8_t* codes; uint8_t* sidx; float* v; float* Qd;
+  float* L1; float* L2; double* sigma;      // only used when the best iterate is kept (early_stop == 2)
 };
+
+static int emit_factors(const Ctx& c, const float* Y, const float* B, const double* lam, float* L1, float* L2,
+                        double* sigma_host);
 
 // Algorithm 2 for `batch` configurations in lock step from the shared first factorization (Y1, B1, lam_cold),
 // as a sequence of asynchronous steps on the context's stream so that several such loops (one per stream) can
@@ -320,6 +324,16 @@ struct Loop {
   double* errs = nullptr;
   double prev_eps = INFINITY;
   bool stopped = false;
+  // early_stop == 2 (batch == 1): the iterate before the error went up is the one returned.  Its quantized component is
+  // kept by writing the iterations alternately into the caller's buffers and into the workspace's, its factors by
+  // assembling L1, L2 after every iteration that did not make the error worse.
+  bool keep_best() const { return early_stop == 2 && direct != nullptr; }
+  int returned = 0;                         // iteration whose pieces the outputs hold
+  void point_codes(int t) {
+    const Plan& pl = c->pl;
+    if (!keep_best() || (t & 1)) { a.codes = direct->codes; a.sidx = direct->sidx; a.v = direct->v; }
+    else { a.codes = c->at<uint8_t>(pl.codes); a.sidx = c->at<uint8_t>(pl.sidx); a.v = c->at<float>(pl.v); }
+  }
 
   int begin() {
     const Plan& pl = c->pl;
@@ -392,6 +406,7 @@ struct Loop {
     const Plan& pl = c->pl;
     a.Y = Ycur; a.B = Bcur; a.strideY = sY; a.strideB = sB;
     a.R = nullptr; a.Qd = nullptr; a.err_out = errs + (t - 1);
+    if (direct) point_codes(t);
     // the error of an iteration costs extra arithmetic per weight: only computed when somebody looks at it
     const bool with_err = want_trace || early_stop || t == iters;
     if (pl.stridePacked) {
@@ -404,11 +419,17 @@ struct Loop {
     LQ_TRY(launch_scalequant_error(a, min_block, with_err, c->st));
     done = t;
     bool last = t == iters;
+    returned = t;
     if (early_stop && batch == 1) {        // Algorithm 2's stopping rule needs eps_t on the host
       double eps = 0.0;
       LQ_HIP_TRY(hipMemcpyAsync(&eps, errs + (t - 1), sizeof(double), hipMemcpyDeviceToHost, c->st));
       LQ_HIP_TRY(hipStreamSynchronize(c->st));
-      if (eps > prev_eps) last = true;
+      if (eps > prev_eps) {
+        last = true;
+        if (keep_best()) returned = t - 1;
+      } else if (keep_best()) {
+        LQ_TRY(emit_factors(*c, Ycur, Bcur, lamcur, direct->L1, direct->L2, direct->sigma));
+      }
       prev_eps = eps;
     }
     if (last) { stopped = true; return LQ_OK; }
@@ -422,7 +443,20 @@ struct Loop {
 
   // Dense Q if asked for, then the error trace comes to the host (synchronizes the stream).
   // Host outputs: trace[b * iters + t] (NaN where not computed), iters_done[b].
-  int finish(double* trace, int32_t* iters_done) {
+  int finish(double* trace, int32_t* iters_done, int32_t* best_iter = nullptr) {
+    if (keep_best() && returned > 0) {       // outputs = the pieces of iteration `returned`
+      const Plan& pl = c->pl;
+      point_codes(returned);
+      if (a.codes != direct->codes) {
+        const int64_t n = pl.d * pl.k;
+        const lq_config& cf = cfgs[0];
+        LQ_HIP_TRY(hipMemcpyAsync(direct->codes, a.codes, lq_codes_bytes(n, cf.bits), hipMemcpyDeviceToDevice, c->st));
+        LQ_HIP_TRY(hipMemcpyAsync(direct->sidx, a.sidx, (size_t)num_blocks(n, cf), hipMemcpyDeviceToDevice, c->st));
+        LQ_HIP_TRY(hipMemcpyAsync(direct->v, a.v, sizeof(float) * (size_t)num_groups(n, cf), hipMemcpyDeviceToDevice,
+                                  c->st));
+        point_codes(1);                      // the caller's buffers
+      }
+    }
     if (direct && direct->Qd) {
       a.R = nullptr; a.Qd = direct->Qd; a.strideQd = 0;
       LQ_TRY(launch_residual(a, c->st));
@@ -434,10 +468,18 @@ struct Loop {
     LQ_HIP_TRY(hipStreamSynchronize(c->st));
     for (int b = 0; b < batch; ++b) {
       int nd = done;
+      int best = done;
       if (early_stop && batch > 1) {         // lock-step batches apply the rule after the fact
         for (int t = 1; t < done; ++t)
-          if (host_err[(size_t)b * MAX_ITERS + t] > host_err[(size_t)b * MAX_ITERS + t - 1]) { nd = t + 1; break; }
+          if (host_err[(size_t)b * MAX_ITERS + t] > host_err[(size_t)b * MAX_ITERS + t - 1]) {
+            nd = t + 1;
+            best = early_stop == 2 ? t : t + 1;
+            break;
+          }
+      } else if (batch == 1) {
+        best = returned;
       }
+      if (best_iter) best_iter[b] = best;
       if (iters_done) iters_done[b] = nd;
       if (trace)
         for (int t = 0; t < iters; ++t)
@@ -533,7 +575,7 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   LQ_TRY(check_quant_args(d * k, cfg));
   if (cfg.block > 128 || k % cfg.block != 0) return cfg.block > 128 ? LQ_ERR_CONFIG : LQ_ERR_SHAPE;
   if ((row_w == nullptr) != (col_w == nullptr)) return LQ_ERR_WEIGHT;
-  if (iters < 1 || iters > MAX_ITERS) return LQ_ERR_ARG;
+  if (iters < 1 || iters > MAX_ITERS || early_stop < 0 || early_stop > 2) return LQ_ERR_ARG;
   if (!aligned16(W) || !aligned16(L1) || !aligned16(L2) || !aligned16(q_codes) || (Q_dense && !aligned16(Q_dense)))
     return LQ_ERR_ARG;
   Params prm;
@@ -543,7 +585,7 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   LQ_TRY(check_workspace(workspace, workspace_bytes, c.pl.total));
   LQ_TRY(setup_common(c, W, row_w, col_w, workspace, (hipStream_t)stream));
   const float* A0; const float* Y1; const float* B1;
-  LoopOut direct{q_codes, q_scale_idx, q_v, Q_dense};
+  LoopOut direct{q_codes, q_scale_idx, q_v, Q_dense, L1, L2, sigma};
   std::vector<double> trace(iters, NAN);
   int32_t done = 0;
   Loop lp;
@@ -555,9 +597,10 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));
   lp.set_first(Y1, B1);
   for (int t = 1; t <= iters; ++t) LQ_TRY(lp.step(t));
-  LQ_TRY(lp.finish(trace.data(), &done));
-  LQ_TRY(emit_factors(c, lp.Ycur, lp.Bcur, lp.lamcur, L1, L2, sigma));
-  if (err) *err = trace[done - 1];
+  int32_t best = 0;
+  LQ_TRY(lp.finish(trace.data(), &done, &best));
+  if (!lp.keep_best()) LQ_TRY(emit_factors(c, lp.Ycur, lp.Bcur, lp.lamcur, L1, L2, sigma));
+  if (err) *err = trace[best - 1];
   if (err_trace) std::memcpy(err_trace, trace.data(), sizeof(double) * iters);
   if (iters_done) *iters_done = done;
   return LQ_OK;
@@ -581,7 +624,7 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
                    double* err_sq, double* storage_bits, double* err_trace, void* workspace, size_t workspace_bytes,
                    void* stream) {
   if (!W || !cfgs || !err_sq || !storage_bits) return LQ_ERR_NULL;
-  if (n_cfgs < 1 || iters < 1 || iters > MAX_ITERS) return LQ_ERR_ARG;
+  if (n_cfgs < 1 || iters < 1 || iters > MAX_ITERS || early_stop < 0 || early_stop > 2) return LQ_ERR_ARG;
   LQ_TRY(check_matrix_args(d, k, rank));
   std::vector<lq_config> cf(cfgs, cfgs + n_cfgs);
   for (auto& cc : cf) {
@@ -622,7 +665,7 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
   }
   int rc = LQ_OK;
   std::vector<double> trace((size_t)per_sub * iters);
-  std::vector<int32_t> done(per_sub);
+  std::vector<int32_t> done(per_sub), best(per_sub);
   for (int c0 = 0; c0 < n_cfgs && rc == LQ_OK; c0 += batch_max) {
     const int nb = std::min(batch_max, n_cfgs - c0);
     std::vector<Loop> loops(nsub);
@@ -639,13 +682,13 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
     for (int t = 1; t <= iters && rc == LQ_OK; ++t)
       for (int s1 = 0; s1 < used && rc == LQ_OK; ++s1) rc = loops[s1].step(t);
     for (int s1 = 0; s1 < used; ++s1) {           // always drain every stream, even after an error
-      const int frc = loops[s1].finish(trace.data(), done.data());
+      const int frc = loops[s1].finish(trace.data(), done.data(), best.data());
       if (rc == LQ_OK) rc = frc;
       if (frc != LQ_OK) continue;
       const int b0 = s1 * per_sub;
       for (int b = 0; b < loops[s1].batch; ++b) {
         const int ci = c0 + b0 + b;
-        const double eps = trace[(size_t)b * iters + done[b] - 1];
+        const double eps = trace[(size_t)b * iters + best[b] - 1];   // the iterate that would be returned
         err_sq[ci] = eps * eps;
         storage_bits[ci] = lq_storage_bits(d * k, cf[ci]);
         if (err_trace) std::memcpy(err_trace + (size_t)ci * iters, trace.data() + (size_t)b * iters, sizeof(double) * iters);

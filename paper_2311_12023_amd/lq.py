@@ -210,7 +210,7 @@ def decompose(w: torch.Tensor, rank: int, cfg: Config, iters: int, early_stop: b
     done = C.c_int32(0)
     trace = np.full(max(iters, 1), np.nan)
     sigma = np.zeros(max(rank, 1))
-    _check(_lib.lq_decompose(_dev(w, torch.float32, "w"), d, k, rank, cfg, iters, 1 if early_stop else 0,
+    _check(_lib.lq_decompose(_dev(w, torch.float32, "w"), d, k, rank, cfg, iters, int(early_stop),
                              _dev(row_w, torch.float32, "row_w"), _dev(col_w, torch.float32, "col_w"), seed,
                              _pp(params), out["L1"].data_ptr(), out["L2"].data_ptr(), out["codes"].data_ptr(),
                              out["scale_idx"].data_ptr(), out["v"].data_ptr(),
@@ -236,7 +236,7 @@ def error_table(w: torch.Tensor, rank: int, cfgs, iters: int, early_stop: bool =
     s = np.zeros(max(len(cfgs), 1))
     tr = np.full((max(len(cfgs), 1), max(iters, 1)), np.nan) if want_trace else None
     _check(_lib.lq_error_table(_dev(w, torch.float32, "w"), d, k, rank, C.addressof(arr), len(cfgs), iters,
-                               1 if early_stop else 0, _dev(row_w, torch.float32, "row_w"),
+                               int(early_stop), _dev(row_w, torch.float32, "row_w"),
                                _dev(col_w, torch.float32, "col_w"), seed, _pp(params), e.ctypes.data, s.ctypes.data,
                                None if tr is None else tr.ctypes.data, _aligned_ptr(ws),
                                ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()), "lq_error_table")

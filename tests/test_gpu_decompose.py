@@ -184,6 +184,35 @@ def test_decompose_weighted(env, oracle):
     check_decomposition_consistency(oracle, w, out, ocfg, r, rw, cw)
 
 
+def test_decompose_keep_best_iterate(env, oracle):
+    """early_stop == 2: same stopping rule, the iterate before the increase comes back: identical to a run limited to
+    that many iterations (the library is deterministic), with the smallest error of the trace; the sweep reports that
+    error too."""
+    torch, lq = env
+    hit = 0
+    for seed in range(40, 52):
+        w = gen.weight_matrix(96, 128, seed, 2)
+        wt = torch.from_numpy(w).cuda()
+        cfg = lq.config(2, 16, 16)
+        stop = lq.decompose(wt, 2, cfg, 10, early_stop=True, seed=1, want_dense=True)
+        best = lq.decompose(wt, 2, cfg, 10, early_stop=2, seed=1, want_dense=True)
+        n = stop["iters_done"]
+        assert best["iters_done"] == n and np.array_equal(best["trace"], stop["trace"], equal_nan=True)
+        by_rule = n >= 2 and stop["trace"][n - 1] > stop["trace"][n - 2]
+        keep = n - 1 if by_rule else n
+        ref = lq.decompose(wt, 2, cfg, keep, seed=1, want_dense=True)
+        for key in ("L1", "L2", "codes", "scale_idx", "v", "Q"):
+            assert torch.equal(best[key], ref[key]), key
+        assert np.array_equal(best["sigma"], ref["sigma"])
+        assert best["err"] == ref["err"] == np.nanmin(best["trace"][:n])
+        check_decomposition_consistency(oracle, w, best, oracle.config(2, 16, 16), 2)
+        e2, _ = lq.error_table(wt, 2, [cfg, lq.config(3, 16, 16)], 10, early_stop=2, seed=1)
+        e1, _ = lq.error_table(wt, 2, [cfg, lq.config(3, 16, 16)], 10, early_stop=1, seed=1)
+        assert abs(np.sqrt(e2[0]) - best["err"]) < ERR_TOL_CHAOTIC * best["err"] and np.all(e2 <= e1)
+        hit += by_rule
+    assert hit > 0, "no seed exercised the stopping rule"
+
+
 @pytest.mark.parametrize("d,k", [(100, 300), (16, 256), (1, 16), (531, 4099)])
 def test_fisher_row_col_helper(env, oracle, d, k):
     """RowAverage / ColAverage of Algorithm 4 on the device against the oracle (fp64 sums on both sides, fp32 results

@@ -101,6 +101,7 @@ def test_argument_validation_without_gpu(L):
     assert dec(cfg=Cfg(6, 64, 256, 8, 0)) == -3
     assert dec(rw=fake) == -5 and dec(cw=fake) == -5
     assert dec(iters=0) == -8
+    L.lq_decompose.restype = C.c_int
     assert dec(ws=None) == -6 and dec(wsb=16) == -6 and dec(ws=vp(4096 + 8)) == -6
     need = L.lq_decompose_workspace_bytes(256, 512, 8, None)
     assert need > 256 * 512 * 4

@@ -225,6 +225,29 @@ def test_lq_early_stop_semantics(oracle):
     assert found, "no seed exercised the stopping rule"
 
 
+def test_lq_keep_best_iterate(oracle):
+    """early_stop == 2 (a variant of Algorithm 2's ending): same stopping rule, but the iterate before the increase is
+    returned.  Its pieces must be exactly those of a run limited to that many iterations, and its error the smallest
+    of the trace."""
+    found = False
+    for seed in range(40, 60):
+        w = gen.weight_matrix(32, 64, seed, 2)
+        cfg = oracle.config(2, 16, 16)
+        stop = oracle.lq(w, 2, cfg, 12, early_stop=True)
+        best = oracle.lq(w, 2, cfg, 12, early_stop=2)
+        assert best["iters_done"] == stop["iters_done"]
+        assert np.array_equal(best["trace"], stop["trace"], equal_nan=True)
+        n = stop["iters_done"]
+        stopped_by_rule = n >= 2 and stop["trace"][n - 1] > stop["trace"][n - 2]
+        keep = n - 1 if stopped_by_rule else n
+        ref = oracle.lq(w, 2, cfg, keep)
+        for key in ("L1", "L2", "codes", "scale_idx", "v", "Q", "sigma"):
+            assert np.array_equal(best[key], ref[key]), key
+        assert best["err"] == ref["err"] == np.nanmin(best["trace"][:n])
+        found |= stopped_by_rule
+    assert found, "no seed exercised the stopping rule"
+
+
 def test_error_table(oracle):
     w = gen.weight_matrix(48, 64, 35, 4)
     cfgs = [oracle.config(b, b0, 16) for b in (2, 4) for b0 in (16, 32)]
