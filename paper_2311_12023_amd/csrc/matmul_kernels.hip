@@ -227,16 +227,21 @@ __device__ __forceinline__ void qmm_multiply(const unsigned char* xstage, const 
       bh[j] = *reinterpret_cast<const bf16x8*>(bhp + at);
       if constexpr (SPLIT) bl[j] = *reinterpret_cast<const bf16x8*>(blp + at);
     }
+    // term by term over all eight accumulator tiles, so that consecutive MFMAs never wait for one another's result
+    if constexpr (SPLIT) {
+#pragma unroll
+      for (int i = 0; i < QM_AT; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < QM_AT; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+    }
 #pragma unroll
     for (int i = 0; i < QM_AT; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        if constexpr (SPLIT) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
-        }
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
-      }
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
   }
 }
 

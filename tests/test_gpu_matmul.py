@@ -99,7 +99,7 @@ def test_matmul_is_deterministic_and_ignores_workspace_contents(env, oracle):
     assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("shape", [(4096, 4096), (4096, 11008)])
+@pytest.mark.parametrize("shape", [(4096, 4096), (4096, 11008), (11008, 4096)])
 def test_matmul_full_size_sampled_rows(env, oracle, shape):
     """The benchmark's shape (m = 4096 tokens, LLaMA-2-7B projections, NF4 with double quantization, rank 64):
     the oracle computes sampled rows of X one by one; the GPU result for those rows must agree, and must not depend
@@ -108,7 +108,7 @@ def test_matmul_full_size_sampled_rows(env, oracle, shape):
     d, k = shape
     cfg, rank, m = (4, 64, 256, 8, "bf16"), 64, 4096
     ocfg = oracle.config(*cfg)
-    w = gen.workload_matrix(3, 0 if shape == (4096, 4096) else 4)
+    w = gen.workload_matrix(3, {(4096, 4096): 0, (4096, 11008): 4, (11008, 4096): 6}[shape])
     assert w.shape == shape
     codes, sidx, v, _ = oracle.quantize(w.ravel(), ocfg)
     l1, l2 = gen.low_rank_factors(d, k, rank, 77)
