@@ -120,3 +120,34 @@ def test_matmul_full_size_sampled_rows(env, oracle, shape):
     assert np.all(np.isfinite(y))
     y_small = _gpu_product(env, oracle, x[rows], codes, sidx, v, cfg, k, l1, l2, 0)
     assert np.max(np.abs(y_small - ref) - TOL_SPLIT * scale) <= 0
+
+
+@pytest.mark.parametrize("m", [4, 300])
+def test_matmul_in_a_hip_graph(env, oracle, m):
+    """lq_matmul only launches kernels, so it can be recorded into a graph (after one eager call, which uploads the
+    code-book tables and raises the kernel's LDS limit): every replay, with eager work on new inputs in between, must
+    reproduce the eager result bit for bit."""
+    torch, lq = env
+    d, k, cfg, rank = 256, 512, (4, 64, 256), 16
+    ocfg, codes, sidx, v, l1, l2 = _case(oracle, d, k, cfg, rank, 900 + m)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    packed, sidx_t, v_t, l1_t, l2_t = t(oracle.pack(codes, cfg[0])), t(sidx), t(v), t(l1), t(l2)
+    gcfg = lq.config(*cfg)
+    x = torch.empty((m, d), dtype=torch.float32, device="cuda")
+    y = torch.empty((m, k), dtype=torch.float32, device="cuda")
+    ws = lq.matmul_workspace(m, d, k, rank)
+    x.copy_(t(gen.activations(m, d, 1)))
+    lq.matmul(x, packed, sidx_t, v_t, gcfg, k, l1_t, l2_t, out=y, workspace=ws)          # eager warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lq.matmul(x, packed, sidx_t, v_t, gcfg, k, l1_t, l2_t, out=y, workspace=ws)
+    for rep in range(4):
+        xin = t(gen.activations(m, d, 10 + rep))
+        eager = lq.matmul(xin, packed, sidx_t, v_t, gcfg, k, l1_t, l2_t)                  # own output and workspace
+        torch.cuda.synchronize()
+        x.copy_(xin)
+        y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager), rep
