@@ -209,39 +209,41 @@ __device__ __forceinline__ void qmm_dma(const uint16_t* hi, const uint16_t* lo, 
   }
 }
 
-// One 32-deep step of the wavefront's 128 x 64 part from the operand tiles in LDS.
+// One 32-deep step of the wavefront's 128 x 64 part from the operand tiles in LDS.  The weight operands of both
+// 16-deep halves are read first (they are shared by the four row tiles); the X operands are read one row tile ahead of
+// the MFMAs that use them, so that the reads of the next tile travel while the matrix pipe works on the current one.
 template <bool SPLIT>
 __device__ __forceinline__ void qmm_multiply(const unsigned char* xstage, const __bf16* bhp, const __bf16* blp,
                                              const QmmLane& t, floatx16 (&acc)[QM_AT][2]) {
+  bf16x8 bh[2][2], bl[2][2];
 #pragma unroll
-  for (int g = 0; g < 2; ++g) {
-    bf16x8 ah[QM_AT], al[QM_AT], bh[2], bl[2];
-#pragma unroll
-    for (int i = 0; i < QM_AT; ++i) {
-      ah[i] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[g] + i * 2048);
-      if constexpr (SPLIT) al[i] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[g] + i * 2048);
-    }
+  for (int g = 0; g < 2; ++g)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int at = t.boff + 32 * j * QM_PITCH + 16 * g;
-      bh[j] = *reinterpret_cast<const bf16x8*>(bhp + at);
-      if constexpr (SPLIT) bl[j] = *reinterpret_cast<const bf16x8*>(blp + at);
+      bh[g][j] = *reinterpret_cast<const bf16x8*>(bhp + at);
+      if constexpr (SPLIT) bl[g][j] = *reinterpret_cast<const bf16x8*>(blp + at);
     }
-    // term by term over all eight accumulator tiles, so that consecutive MFMAs never wait for one another's result
+  bf16x8 ah[2], al[2];                   // current and next row tile
+  ah[0] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[0]);
+  if constexpr (SPLIT) al[0] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[0]);
+#pragma unroll
+  for (int idx = 0; idx < 2 * QM_AT; ++idx) {
+    const int g = idx / QM_AT, i = idx % QM_AT, cur = idx & 1, nxt = cur ^ 1;
+    if (idx + 1 < 2 * QM_AT) {
+      const int gn = (idx + 1) / QM_AT, in = (idx + 1) % QM_AT;
+      ah[nxt] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[gn] + in * 2048);
+      if constexpr (SPLIT) al[nxt] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[gn] + in * 2048);
+    }
+    // the two accumulators of the row tile alternate, three terms each
     if constexpr (SPLIT) {
 #pragma unroll
-      for (int i = 0; i < QM_AT; ++i)
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[cur], bh[g][j], acc[i][j], 0, 0, 0);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < QM_AT; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[cur], bl[g][j], acc[i][j], 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < QM_AT; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[cur], bh[g][j], acc[i][j], 0, 0, 0);
   }
 }
 
