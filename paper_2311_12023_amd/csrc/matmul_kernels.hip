@@ -209,12 +209,48 @@ __device__ __forceinline__ void qmm_dma(const uint16_t* hi, const uint16_t* lo, 
   }
 }
 
-// One 32-deep step of the wavefront's 128 x 64 part from the operand tiles in LDS.  The weight operands of both
-// 16-deep halves are read first (they are shared by the four row tiles); the X operands are read one row tile ahead of
-// the MFMAs that use them, so that the reads of the next tile travel while the matrix pipe works on the current one.
-template <bool SPLIT>
-__device__ __forceinline__ void qmm_multiply(const unsigned char* xstage, const __bf16* bhp, const __bf16* blp,
-                                             const QmmLane& t, floatx16 (&acc)[QM_AT][2]) {
+// Decode of the thread's 4 x 4 weight patch cut into QM_SLICES small pieces, so that one piece can follow every MFMA
+// of a step (see qmm_step): scales, code-book lookups, products, then the split into bf16 halves and the LDS writes,
+// one output column at a time.  `k` is a compile-time constant after unrolling; w and sh live in registers.
+constexpr int QM_SLICES = 44;
+template <int BITS, bool SPLIT, bool QUANT>
+__device__ __forceinline__ void qmm_stash_slice(int k, const QmmArgs& a, const QmmLane& t, const QmmPatch<QUANT>& r,
+                                                const float* s_code, float (&sh)[4], float (&w)[4][4], __bf16* bh,
+                                                __bf16* bl) {
+  if (k < 4) {                                     // the reconstructed scale of row k's block
+    if constexpr (QUANT) sh[k] = block_scale(r.si[k], r.vv[k], a.levels);
+  } else if (k < 20) {                             // code-book value of one weight
+    const int j = (k - 4) >> 2, c = (k - 4) & 3;
+    if constexpr (QUANT) w[j][c] = s_code[(r.cw[j] >> (c * BITS)) & ((1u << BITS) - 1u)];
+    else w[j][c] = c == 0 ? r.dn[j].x : c == 1 ? r.dn[j].y : c == 2 ? r.dn[j].z : r.dn[j].w;
+  } else if (k < 36) {                             // times the scale: the same fl32(code * s^) that Dequantize returns
+    const int j = (k - 20) >> 2, c = (k - 20) & 3;
+    if constexpr (QUANT) w[j][c] = w[j][c] * sh[j];
+  } else {                                         // one column: its four reduction indices as bf16 hi (even k) or lo (odd)
+    const int c = (k - 36) >> 1;
+    const floatx4 f = {w[0][c], w[1][c], w[2][c], w[3][c]};
+    const bf16x4 hi = __builtin_convertvector(f, bf16x4);
+    const int at = (4 * t.quad + c) * QM_PITCH + 4 * t.kg;
+    if (((k - 36) & 1) == 0) {
+      *reinterpret_cast<bf16x4*>(bh + at) = hi;
+    } else if constexpr (SPLIT) {
+      *reinterpret_cast<bf16x4*>(bl + at) = __builtin_convertvector(f - __builtin_convertvector(hi, floatx4), bf16x4);
+    }
+  }
+}
+
+// One 32-deep step of the wavefront's 128 x 64 part from the operand tiles in LDS, with the decode of the next step's
+// weight patch (registers r -> LDS buffer nbh / nbl) woven in: every MFMA is followed by a few pieces of the decode
+// and a scheduling fence, so that the vector ALU works in the shadow of the matrix pipe of the same wavefront (a
+// wavefront that has an MFMA waiting for the pipe holds the SIMD's vector issue slot, so the two cannot be overlapped
+// across wavefronts).  The weight operands of both 16-deep halves are read first (they are shared by the four row
+// tiles); the X operands are read one row tile ahead of the MFMAs that use them.
+template <int BITS, bool SPLIT, bool QUANT>
+__device__ __forceinline__ void qmm_step(const QmmArgs& a, const QmmLane& t, const unsigned char* xstage,
+                                         const __bf16* bhp, const __bf16* blp, const QmmPatch<QUANT>& r,
+                                         const float* s_code, __bf16* nbh, __bf16* nbl, floatx16 (&acc)[QM_AT][2]) {
+  constexpr int MFMAS = 2 * QM_AT * 2 * (SPLIT ? 3 : 1);
+  float sh[4], w[4][4];
   bf16x8 bh[2][2], bl[2][2];
 #pragma unroll
   for (int g = 0; g < 2; ++g)
@@ -227,6 +263,15 @@ __device__ __forceinline__ void qmm_multiply(const unsigned char* xstage, const 
   bf16x8 ah[2], al[2];                   // current and next row tile
   ah[0] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[0]);
   if constexpr (SPLIT) al[0] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[0]);
+  int m = 0;                             // MFMAs issued so far: slices [m * QM_SLICES / MFMAS, (m + 1) * QM_SLICES / MFMAS) follow
+#define LQ_QMM_MFMA(A, B, I, J)                                                                            \
+  {                                                                                                        \
+    acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc[I][J], 0, 0, 0);                         \
+    for (int k = m * QM_SLICES / MFMAS; k < (m + 1) * QM_SLICES / MFMAS; ++k)                              \
+      qmm_stash_slice<BITS, SPLIT, QUANT>(k, a, t, r, s_code, sh, w, nbh, nbl);                            \
+    ++m;                                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                                     \
+  }
 #pragma unroll
   for (int idx = 0; idx < 2 * QM_AT; ++idx) {
     const int g = idx / QM_AT, i = idx % QM_AT, cur = idx & 1, nxt = cur ^ 1;
@@ -237,24 +282,24 @@ __device__ __forceinline__ void qmm_multiply(const unsigned char* xstage, const 
     }
     // the two accumulators of the row tile alternate, three terms each
     if constexpr (SPLIT) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[cur], bh[g][j], acc[i][j], 0, 0, 0);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[cur], bl[g][j], acc[i][j], 0, 0, 0);
+      LQ_QMM_MFMA(al[cur], bh[g][0], i, 0)
+      LQ_QMM_MFMA(al[cur], bh[g][1], i, 1)
+      LQ_QMM_MFMA(ah[cur], bl[g][0], i, 0)
+      LQ_QMM_MFMA(ah[cur], bl[g][1], i, 1)
     }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[cur], bh[g][j], acc[i][j], 0, 0, 0);
+    LQ_QMM_MFMA(ah[cur], bh[g][0], i, 0)
+    LQ_QMM_MFMA(ah[cur], bh[g][1], i, 1)
   }
+#undef LQ_QMM_MFMA
 }
 
 // Steps [sa, sb) of one part (numbered within the part).  At the top of step s (iteration `it` of this run) X stage
 // it % 2 and weight buffer it % 2 hold step s, and one patch register set holds step s + 1.  The step fetches the patch
 // of s + 2 and starts the X transfer of s + 1 into the other stage (free since the barrier that ended step s - 1), then
-// multiplies step s and decodes the patch of s + 1 into the other weight buffer -- in that order in the first four
-// wavefronts, in the opposite order in the last four -- waits for everything it has started and meets the barrier.
-// Prefetch indices are clamped, not guarded (the last step is fetched again and dropped): the body is branch-free
-// apart from the uniform choice of order.
-template <int BITS, bool SPLIT, bool QUANT, bool MULTIPLY_FIRST>
+// multiplies step s while decoding the patch of s + 1 into the other weight buffer, waits for everything it has
+// started and meets the barrier.  Prefetch indices are clamped, not guarded (the last step is fetched again and
+// dropped): the body is branch-free.
+template <int BITS, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void qmm_run(const QmmArgs& a, const QmmLane& t, int sa, int sb, const float* s_code,
                                         unsigned char* lds, uint32_t lds_addr, floatx16 (&acc)[QM_AT][2]) {
   if (sa >= sb) return;
@@ -281,13 +326,8 @@ __device__ __forceinline__ void qmm_run(const QmmArgs& a, const QmmLane& t, int 
   {                                                                                                          \
     qmm_fetch<BITS, QUANT>(a, t, (S) + 2 < last ? (S) + 2 : last, ring[(U)]);                                \
     LQ_QMM_DMA((S) + 1, 1 - (U));                                                                            \
-    if constexpr (MULTIPLY_FIRST) {                                                                          \
-      qmm_multiply<SPLIT>(LQ_QMM_XSTAGE(U), LQ_QMM_BH(U), LQ_QMM_BL(U), t, acc);                             \
-      qmm_stash<BITS, SPLIT, QUANT>(a, t, ring[1 - (U)], s_code, LQ_QMM_BH(1 - (U)), LQ_QMM_BL(1 - (U)));    \
-    } else {                                                                                                 \
-      qmm_stash<BITS, SPLIT, QUANT>(a, t, ring[1 - (U)], s_code, LQ_QMM_BH(1 - (U)), LQ_QMM_BL(1 - (U)));    \
-      qmm_multiply<SPLIT>(LQ_QMM_XSTAGE(U), LQ_QMM_BH(U), LQ_QMM_BL(U), t, acc);                             \
-    }                                                                                                        \
+    qmm_step<BITS, SPLIT, QUANT>(a, t, LQ_QMM_XSTAGE(U), LQ_QMM_BH(U), LQ_QMM_BL(U), ring[1 - (U)], s_code,  \
+                                 LQ_QMM_BH(1 - (U)), LQ_QMM_BL(1 - (U)), acc);                               \
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* the X tile of S + 1 has landed */                    \
     __syncthreads();                                                                                         \
   }
@@ -345,7 +385,6 @@ __global__ __launch_bounds__(QM_THREADS, 2) void qmatmul_kernel(QmmArgs a) {
   t.aoff[1] = (uint32_t)arow * 64u + (uint32_t)(((2 + lh) ^ ((arow >> 1) & 3)) << 4);
   t.boff = (uint32_t)((64 * wn + ln) * QM_PITCH + 8 * lh);
   const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_raw;
-  const bool multiply_first = wave_s < 4;          // the two wavefronts of a SIMD (w and w + 4) take opposite orders
 
   floatx16 acc[QM_AT][2];
 #pragma unroll
@@ -356,23 +395,13 @@ __global__ __launch_bounds__(QM_THREADS, 2) void qmatmul_kernel(QmmArgs a) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
   __syncthreads();                     // code book in LDS
 
-  // quantized steps first, then the dense ones; the byte offset of the lane's 16 bytes depends on the part's row length.
-  // The order of the two halves of a step is fixed per wavefront, so each order gets its own copy of the loops.
+  // quantized steps first, then the dense ones; the byte offset of the lane's 16 bytes depends on the part's row length
   const int qa = s0 < a.nq ? s0 : a.nq, qb = s1 < a.nq ? s1 : a.nq;
   const int da = (s0 > a.nq ? s0 : a.nq) - a.nq, db = (s1 > a.nq ? s1 : a.nq) - a.nq;
-  const uint32_t voff_q = (uint32_t)(((row0 + 16 * wave + xr) * a.Kq + 8 * xu) * 2);
-  const uint32_t voff_d = (uint32_t)(((row0 + 16 * wave + xr) * a.Kd + 8 * xu) * 2);
-  if (multiply_first) {
-    t.xvoff = voff_q;
-    qmm_run<BITS, SPLIT, true, true>(a, t, qa, qb, s_code, s_raw, lds_addr, acc);
-    t.xvoff = voff_d;
-    qmm_run<BITS, SPLIT, false, true>(a, t, da, db, s_code, s_raw, lds_addr, acc);
-  } else {
-    t.xvoff = voff_q;
-    qmm_run<BITS, SPLIT, true, false>(a, t, qa, qb, s_code, s_raw, lds_addr, acc);
-    t.xvoff = voff_d;
-    qmm_run<BITS, SPLIT, false, false>(a, t, da, db, s_code, s_raw, lds_addr, acc);
-  }
+  t.xvoff = (uint32_t)(((row0 + 16 * wave + xr) * a.Kq + 8 * xu) * 2);
+  qmm_run<BITS, SPLIT, true>(a, t, qa, qb, s_code, s_raw, lds_addr, acc);
+  t.xvoff = (uint32_t)(((row0 + 16 * wave + xr) * a.Kd + 8 * xu) * 2);
+  qmm_run<BITS, SPLIT, false>(a, t, da, db, s_code, s_raw, lds_addr, acc);
 
   // accumulator element e of a lane is row 8*(e/4) + 4*lh + e%4, column ln of its 32 x 32 tile
   float* __restrict__ Y = a.Y + (size_t)split * (size_t)a.m * a.ldy;
