@@ -46,12 +46,16 @@ int launch_fisher_row_col(const float* F, int64_t d, int64_t k, double* scratch,
 int launch_split_planes(const float* X, int64_t rows, int64_t K, int64_t ldx, int64_t rows_pad, uint16_t* hi,
                         uint16_t* lo, hipStream_t st);
 // Quantized part of a product: X (planes of rows_pad x K) times the K x N matrix stored as NF codes (row-major
-// flattening, N a multiple of `block`).  K is a multiple of 32; K == 0 leaves the part out.
+// flattening, N a multiple of `block`, K * N below 2^31).  K is a multiple of 32; K == 0 leaves the part out.
 struct QmmPart {
   const uint16_t* Xh; const uint16_t* Xl; int64_t K;
-  const uint8_t* codes; const uint8_t* sidx; const float* v;
-  int bits, block, scale_block, levels;
+  const uint8_t* codes;
+  const float* bscale;      // reconstructed scale of every block (launch_block_scales)
+  int bits, block;
 };
+// out[b] = s^ of block b = fl32(scale_idx[b] * fl32(v[b / scale_block] / levels)), nblocks floats.
+int launch_block_scales(const uint8_t* sidx, const float* v, int64_t nblocks, int scale_block, int levels, float* out,
+                        hipStream_t st);
 // Dense part: X (planes of rows_pad x K, K a multiple of 32, zero-filled padding) times D (rows x cols fp32, leading
 // dimension ldd); rows of D beyond `rows` and columns beyond `cols` count as zero.
 struct DensePart {

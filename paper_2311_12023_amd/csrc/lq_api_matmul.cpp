@@ -17,7 +17,7 @@ constexpr int SMALL_RANK = 512;
 struct MatmulPlan {
   bool small;
   int64_t r32, rows_pad;
-  size_t x_plane, t_floats, t_plane, part_floats;   // elements
+  size_t x_plane, t_floats, t_plane, part_floats, scale_floats;   // elements
 };
 static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   MatmulPlan p{};
@@ -38,10 +38,12 @@ static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   const size_t p1 = rank > 0 ? qmatmul_part_floats(m, p.r32, (int)(d / 32)) : 0;
   const size_t p2 = qmatmul_part_floats(m, k, (int)(d / 32 + p.r32 / 32));
   p.part_floats = p1 > p2 ? p1 : p2;
+  p.scale_floats = (size_t)(d * k / 16);            // one scale per block, block size at least 16
   return p;
 }
 static size_t plan_bytes(const MatmulPlan& p) {
-  return 2 * up256(p.x_plane * 2) + up256(p.t_floats * 4) + 2 * up256(p.t_plane * 2) + up256(p.part_floats * 4);
+  return 2 * up256(p.x_plane * 2) + up256(p.t_floats * 4) + 2 * up256(p.t_plane * 2) + up256(p.part_floats * 4) +
+         up256(p.scale_floats * 4);
 }
 }  // namespace lq
 
@@ -69,6 +71,7 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   if (((uintptr_t)X & 15) != 0 || ((uintptr_t)Y & 15) != 0 || (rank > 0 && ((uintptr_t)L2 & 15) != 0)) return LQ_ERR_ARG;
   const MatmulPlan p = plan_matmul(m, d, k, rank);
   if (p.rows_pad * d >= ((int64_t)1 << 31)) return LQ_ERR_SHAPE;   // planes are addressed with 32-bit byte offsets
+  if (!p.small && d * k >= ((int64_t)1 << 31)) return LQ_ERR_SHAPE;   // and so are the codes
   const size_t need = plan_bytes(p) + 256;
   if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return LQ_ERR_WORKSPACE;
   char* w = reinterpret_cast<char*>(workspace);
@@ -92,16 +95,18 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   float* T = reinterpret_cast<float*>(w); w += up256(p.t_floats * 4);
   uint16_t* th = reinterpret_cast<uint16_t*>(w); w += up256(p.t_plane * 2);
   uint16_t* tl = reinterpret_cast<uint16_t*>(w); w += up256(p.t_plane * 2);
-  float* part = reinterpret_cast<float*>(w);
+  float* part = reinterpret_cast<float*>(w); w += up256(p.part_floats * 4);
+  float* bscale = reinterpret_cast<float*>(w);
 
   LQ_TRY(launch_split_planes(X, m, d, d, p.rows_pad, xh, xl, st));
+  LQ_TRY(launch_block_scales(scale_idx, v, d * k / c.block, c.scale_block, scale_levels(c), bscale, st));
   QmmPart none{};
   if (rank > 0) {   // T = X L1, m x r32 with zero columns beyond r, then its planes
     DensePart xl1{xh, xl, d, L1, rank, d, rank};
     LQ_TRY(launch_qmatmul(none, xl1, m, p.rows_pad, p.r32, T, p.r32, part, p.part_floats, precision, st));
     LQ_TRY(launch_split_planes(T, m, p.r32, p.r32, p.rows_pad, th, tl, st));
   }
-  QmmPart q{xh, xl, d, codes_packed, scale_idx, v, c.bits, c.block, c.scale_block, scale_levels(c)};
+  QmmPart q{xh, xl, d, codes_packed, bscale, c.bits, c.block};
   DensePart tl2{th, tl, rank > 0 ? p.r32 : 0, L2, k, rank, k};
   return launch_qmatmul(q, tl2, m, p.rows_pad, k, Y, k, part, p.part_floats, precision, st);
 }

@@ -48,10 +48,12 @@ struct QmmArgs {
   const uint16_t* Xqh; const uint16_t* Xql;   // bf16 planes of the quantized part's X: rows_pad x Kq
   const uint16_t* Xdh; const uint16_t* Xdl;   // bf16 planes of the dense part's X: rows_pad x Kd
   const float* D; int64_t ldd;     // drows x dcols fp32; rows and columns beyond count as zero
-  const uint8_t* codes; const uint8_t* sidx; const float* v;   // Kq x N, row-major flattening
+  const uint8_t* codes;            // Kq x N, row-major flattening
+  const float* bscale;             // reconstructed scale of every block of Q (Kq * N / B0 floats)
+  uint32_t cw_step, blk_step;      // code bytes and blocks per 32 rows of Q
   float* Y; int64_t ldy;           // m x N (splits == 1), else partials: split s at Y + s * m * ldy
   int64_t m, N, Kq, Kd, drows, dcols;
-  int block_shift, group_shift, levels;   // log2 of the block size B0 and of the scale group size B1
+  int block_shift;                 // log2 of the block size B0
   int nq, nsteps, splits;          // quantized steps, all steps, reduction ranges
   int tiles_m, tiles_n;
   const DevTables* tables;
@@ -95,29 +97,18 @@ int launch_split_planes(const float* X, int64_t rows, int64_t K, int64_t ldx, in
 }
 
 // Registers of the thread's prefetched 4 x 4 patch of the weight tile, either as stored (code words of its quad in 4
-// consecutive rows of Q, the scale index of each row's block and that block's group scale) or dense.
+// consecutive rows of Q and the reconstructed scale of each row's block) or dense.
 template <bool QUANT>
 struct QmmPatch;
 template <>
 struct QmmPatch<true> {
-  uint32_t cw[4], si[4];
-  float vv[4];
+  uint32_t cw[4];
+  float sc[4];
 };
 template <>
 struct QmmPatch<false> {
   floatx4 dn[4];
 };
-
-template <int BITS>
-__device__ __forceinline__ uint32_t quad_word(const uint8_t* __restrict__ codes, int64_t quad) {
-  if constexpr (BITS == 8) return *reinterpret_cast<const uint32_t*>(codes + quad * 4);
-  else if constexpr (BITS == 4) return *reinterpret_cast<const uint16_t*>(codes + quad * 2);
-  else if constexpr (BITS == 2) return codes[quad];
-  else {   // 3 bits: 12 bits starting at bit 12*quad
-    const int64_t byte = (quad * 3) >> 1;
-    return ((uint32_t)codes[byte] | ((uint32_t)codes[byte + 1] << 8)) >> ((quad & 1) * 4);
-  }
-}
 
 // Per-thread addressing that does not change from step to step.
 struct QmmLane {
@@ -128,21 +119,29 @@ struct QmmLane {
   uint32_t xlds;        // LDS byte offset (inside a stage's plane) of the wavefront's first row block
   uint32_t aoff[2];     // LDS byte offsets of the lane's A operand for the two 16-deep halves of a step (row tile 0)
   uint32_t boff;        // LDS element offset of the lane's B operand (column tile 0, first half)
+  uint32_t cwoff[4];    // byte offset of the patch's code word in rows 4kg .. 4kg + 3 of the first step
+  uint32_t blk0[4];     // index of those rows' blocks
+  uint32_t cwshift;     // 3-bit codes: 4 when the quad starts in the upper half of its first byte
 };
 
+// The code words and block scales of a step sit at a wavefront-uniform distance (step * cw_step bytes, step * blk_step
+// blocks) from those of the first step, so a fetch is a scalar base plus the lane's fixed 32-bit offsets.
 template <int BITS, bool QUANT>
 __device__ __forceinline__ void qmm_fetch(const QmmArgs& a, const QmmLane& t, int step, QmmPatch<QUANT>& r) {
-  const int64_t k0 = (int64_t)step * QM_BK;          // within its own part
   if constexpr (QUANT) {
+    const uint8_t* cb = a.codes + (size_t)step * a.cw_step;
+    const float* sb = a.bscale + (size_t)step * a.blk_step;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int64_t e = (k0 + 4 * t.kg + j) * a.N + t.colc;
-      r.cw[j] = quad_word<BITS>(a.codes, e >> 2);
-      const int64_t blk = e >> a.block_shift;
-      r.si[j] = a.sidx[blk];
-      r.vv[j] = a.v[blk >> a.group_shift];
+      const uint8_t* p = cb + t.cwoff[j];
+      if constexpr (BITS == 8) r.cw[j] = *reinterpret_cast<const uint32_t*>(p);
+      else if constexpr (BITS == 4) r.cw[j] = *reinterpret_cast<const uint16_t*>(p);
+      else if constexpr (BITS == 2) r.cw[j] = *p;
+      else r.cw[j] = ((uint32_t)p[0] | ((uint32_t)p[1] << 8)) >> t.cwshift;   // 12 bits starting at bit 12 * quad
+      r.sc[j] = sb[t.blk0[j]];
     }
   } else {
+    const int64_t k0 = (int64_t)step * QM_BK;        // within its own part
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int64_t p = k0 + 4 * t.kg + j;
@@ -162,7 +161,7 @@ __device__ __forceinline__ void qmm_stash(const QmmArgs& a, const QmmLane& t, co
     constexpr uint32_t mask = (1u << BITS) - 1u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const float sh = block_scale(r.si[j], r.vv[j], a.levels);
+      const float sh = r.sc[j];
 #pragma unroll
       for (int c = 0; c < 4; ++c) w[j][c] = s_code[(r.cw[j] >> (c * BITS)) & mask] * sh;
     }
@@ -218,7 +217,7 @@ __device__ __forceinline__ void qmm_stash_slice(int k, const QmmArgs& a, const Q
                                                 const float* s_code, float (&sh)[4], float (&w)[4][4], __bf16* bh,
                                                 __bf16* bl) {
   if (k < 4) {                                     // the reconstructed scale of row k's block
-    if constexpr (QUANT) sh[k] = block_scale(r.si[k], r.vv[k], a.levels);
+    if constexpr (QUANT) sh[k] = r.sc[k];
   } else if (k < 20) {                             // code-book value of one weight
     const int j = (k - 4) >> 2, c = (k - 4) & 3;
     if constexpr (QUANT) w[j][c] = s_code[(r.cw[j] >> (c * BITS)) & ((1u << BITS) - 1u)];
@@ -385,6 +384,15 @@ __global__ __launch_bounds__(QM_THREADS, 2) void qmatmul_kernel(QmmArgs a) {
   t.aoff[1] = (uint32_t)arow * 64u + (uint32_t)(((2 + lh) ^ ((arow >> 1) & 3)) << 4);
   t.boff = (uint32_t)((64 * wn + ln) * QM_PITCH + 8 * lh);
   const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_raw;
+  t.cwshift = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {                    // the host has checked that Kq * N fits in 31 bits
+    const uint32_t e = (uint32_t)(4 * t.kg + j) * (uint32_t)a.N + (uint32_t)t.colc;
+    const uint32_t q = e >> 2;
+    t.cwoff[j] = BITS == 8 ? 4 * q : BITS == 4 ? 2 * q : BITS == 2 ? q : (3 * q) >> 1;
+    t.blk0[j] = e >> a.block_shift;
+    if (BITS == 3) t.cwshift = (q & 1) * 4;        // N is a multiple of 16: the parity of q is the same in every row and step
+  }
 
   floatx16 acc[QM_AT][2];
 #pragma unroll
@@ -417,6 +425,25 @@ __global__ __launch_bounds__(QM_THREADS, 2) void qmatmul_kernel(QmmArgs a) {
         if (row < a.m) Y[row * a.ldy + col] = acc[i][j][e];
       }
   }
+}
+
+// s^ of every block: fl32(index * fl32(v / levels)), as in Dequantize (Section 3.2).
+__global__ __launch_bounds__(256) void block_scales_kernel(const uint8_t* __restrict__ sidx, const float* __restrict__ v,
+                                                           int64_t nblocks, int group_shift, int levels,
+                                                           float* __restrict__ out) {
+  for (int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x; b < nblocks; b += (int64_t)gridDim.x * 256)
+    out[b] = block_scale(sidx[b], v[b >> group_shift], levels);
+}
+
+int launch_block_scales(const uint8_t* sidx, const float* v, int64_t nblocks, int scale_block, int levels, float* out,
+                        hipStream_t st) {
+  if (nblocks <= 0 || scale_block < 1 || (scale_block & (scale_block - 1)) != 0) return LQ_ERR_SHAPE;
+  prof::Scope ps(prof::MISC, st, 5.0 * (double)nblocks);
+  const int64_t nwg = std::min<int64_t>((nblocks + 255) / 256, 4096);
+  hipLaunchKernelGGL(block_scales_kernel, dim3((unsigned)nwg), dim3(256), 0, st, sidx, v, nblocks,
+                     __builtin_ctz((unsigned)scale_block), levels, out);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
 }
 
 // Y = sum over the reduction ranges of their partial results, in range order.
@@ -473,18 +500,16 @@ int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t row
                    float* part, size_t part_floats, int precision, hipStream_t st) {
   if (m <= 0 || N <= 0 || rows_pad < m || (rows_pad % 256) != 0) return LQ_ERR_SHAPE;
   if ((q.K % QM_BK) != 0 || (dn.K % QM_BK) != 0 || q.K + dn.K <= 0) return LQ_ERR_SHAPE;
-  if (q.K > 0 && (q.block < 4 || (q.block & (q.block - 1)) != 0 || q.scale_block < 1 ||
-                  (q.scale_block & (q.scale_block - 1)) != 0))
-    return LQ_ERR_CONFIG;                                  // block sizes are powers of two
-  if (q.K > 0 && (N % q.block) != 0) return LQ_ERR_SHAPE;
+  if (q.K > 0 && (q.block < 16 || (q.block & (q.block - 1)) != 0)) return LQ_ERR_CONFIG;   // a power of two
+  if (q.K > 0 && ((N % q.block) != 0 || q.K * N >= ((int64_t)1 << 31))) return LQ_ERR_SHAPE;  // 32-bit code offsets
   // the X transfers address a plane with 32-bit byte offsets
   if (rows_pad * std::max(q.K, dn.K) >= ((int64_t)1 << 31)) return LQ_ERR_SHAPE;
   QmmArgs a{};
   a.Xqh = q.Xh; a.Xql = q.Xl; a.Kq = q.K;
-  a.codes = q.codes; a.sidx = q.sidx; a.v = q.v;
+  a.codes = q.codes; a.bscale = q.bscale;
   a.block_shift = q.K > 0 ? __builtin_ctz((unsigned)q.block) : 0;
-  a.group_shift = q.K > 0 ? __builtin_ctz((unsigned)q.scale_block) : 0;
-  a.levels = q.levels;
+  a.cw_step = q.K > 0 ? (uint32_t)(QM_BK * N * q.bits / 8) : 0;
+  a.blk_step = q.K > 0 ? (uint32_t)(QM_BK * N / q.block) : 0;
   a.Xdh = dn.Xh; a.Xdl = dn.Xl; a.Kd = dn.K; a.D = dn.D; a.ldd = dn.ldd; a.drows = dn.rows; a.dcols = dn.cols;
   a.m = m; a.N = N;
   a.nq = (int)(q.K / QM_BK);
