@@ -16,14 +16,13 @@
 //    64 bytes without padding; the four 16-byte units of a row are stored in the order unit ^ ((row / 2) % 4), which
 //    makes the 128-bit operand reads conflict-free.
 //  - The weight tile is decoded in registers: every thread fetches a 4 (reduction) x 4 (columns) patch a step or two
-//    ahead (four code words from four consecutive rows of Q, their blocks' scale indices and group scales),
-//    multiplies code-book value by reconstructed scale (the same fl32(code * s^) that the stand-alone dequantizer
-//    produces), splits it and writes 8-byte runs into the weight buffer of the next step.
+//    ahead (four code words from four consecutive rows of Q and the reconstructed scales of their blocks, which a
+//    small kernel computes once per call), multiplies code-book value by scale (the same fl32(code * s^) that the
+//    stand-alone dequantizer produces), splits it and writes 8-byte runs into the weight buffer of the next step.
 //  - Each wavefront multiplies its 128 x 64 part with three v_mfma_f32_32x32x16_bf16 per tile pair (hi*hi + hi*lo +
 //    lo*hi, fp32 accumulation; the bf16-only variant keeps the hi halves alone).
-// Within a step the decode of the next weight tile and the MFMAs of the current one are independent.  The two
-// wavefronts of a SIMD take them in opposite order, so that while one occupies the matrix pipe the other runs the
-// vector-ALU work and waits out its LDS and memory latencies.  One barrier per step.
+// Within a step the decode of the next weight tile and the MFMAs of the current one are independent; the decode is cut
+// into small pieces that follow the individual MFMAs of the same wavefront (qmm_step).  One barrier per step.
 // When the tile grid is too small to fill the machine the reduction is cut into `splits` contiguous ranges whose
 // partial tiles go to scratch and are summed in a fixed order by a second kernel.
 #include <algorithm>
