@@ -22,7 +22,8 @@
 //  - Each wavefront multiplies its 128 x 64 part with three v_mfma_f32_32x32x16_bf16 per tile pair (hi*hi + hi*lo +
 //    lo*hi, fp32 accumulation; the bf16-only variant keeps the hi halves alone).
 // Within a step the decode of the next weight tile and the MFMAs of the current one are independent; the decode is cut
-// into small pieces that follow the individual MFMAs of the same wavefront (qmm_step).  One barrier per step.
+// into small operations that are dealt out, by instruction count, over the individual MFMAs of the same wavefront
+// (QM_OPS, qmm_step).  One barrier per step.
 // When the tile grid is too small to fill the machine the reduction is cut into `splits` contiguous ranges whose
 // partial tiles go to scratch and are summed in a fixed order by a second kernel.
 #include <algorithm>
@@ -38,6 +39,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int QM_BM = 256, QM_BN = 256, QM_BK = 32, QM_THREADS = 512;
 constexpr int QM_AT = 4;                  // 32-row tiles per wavefront (its part of the output is 128 x 64)
@@ -126,30 +128,27 @@ struct QmmLane {
 // The code words and block scales of a step sit at a wavefront-uniform distance (step * cw_step bytes, step * blk_step
 // blocks) from those of the first step, so a fetch is a scalar base plus the lane's fixed 32-bit offsets.
 template <int BITS, bool QUANT>
-__device__ __forceinline__ void qmm_fetch(const QmmArgs& a, const QmmLane& t, int step, QmmPatch<QUANT>& r) {
+__device__ __forceinline__ void qmm_fetch_row(const QmmArgs& a, const QmmLane& t, int step, int j, QmmPatch<QUANT>& r) {
   if constexpr (QUANT) {
-    const uint8_t* cb = a.codes + (size_t)step * a.cw_step;
-    const float* sb = a.bscale + (size_t)step * a.blk_step;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint8_t* p = cb + t.cwoff[j];
-      if constexpr (BITS == 8) r.cw[j] = *reinterpret_cast<const uint32_t*>(p);
-      else if constexpr (BITS == 4) r.cw[j] = *reinterpret_cast<const uint16_t*>(p);
-      else if constexpr (BITS == 2) r.cw[j] = *p;
-      else r.cw[j] = ((uint32_t)p[0] | ((uint32_t)p[1] << 8)) >> t.cwshift;   // 12 bits starting at bit 12 * quad
-      r.sc[j] = sb[t.blk0[j]];
-    }
+    const uint8_t* p = a.codes + (size_t)step * a.cw_step + t.cwoff[j];
+    if constexpr (BITS == 8) r.cw[j] = *reinterpret_cast<const uint32_t*>(p);
+    else if constexpr (BITS == 4) r.cw[j] = *reinterpret_cast<const uint16_t*>(p);
+    else if constexpr (BITS == 2) r.cw[j] = *p;
+    else r.cw[j] = ((uint32_t)p[0] | ((uint32_t)p[1] << 8)) >> t.cwshift;   // 12 bits starting at bit 12 * quad
+    r.sc[j] = (a.bscale + (size_t)step * a.blk_step)[t.blk0[j]];
   } else {
-    const int64_t k0 = (int64_t)step * QM_BK;        // within its own part
+    const int64_t p = (int64_t)step * QM_BK + 4 * t.kg + j;                  // within its own part
+    float w[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int64_t p = k0 + 4 * t.kg + j;
-      float w[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) w[c] = (p < a.drows && t.col + c < a.dcols) ? a.D[p * a.ldd + t.col + c] : 0.0f;
-      r.dn[j] = floatx4{w[0], w[1], w[2], w[3]};
-    }
+    for (int c = 0; c < 4; ++c) w[c] = (p < a.drows && t.col + c < a.dcols) ? a.D[p * a.ldd + t.col + c] : 0.0f;
+    r.dn[j] = floatx4{w[0], w[1], w[2], w[3]};
   }
+}
+
+template <int BITS, bool QUANT>
+__device__ __forceinline__ void qmm_fetch(const QmmArgs& a, const QmmLane& t, int step, QmmPatch<QUANT>& r) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) qmm_fetch_row<BITS, QUANT>(a, t, step, j, r);
 }
 
 template <int BITS, bool SPLIT, bool QUANT>
@@ -207,48 +206,103 @@ __device__ __forceinline__ void qmm_dma(const uint16_t* hi, const uint16_t* lo, 
   }
 }
 
-// Decode of the thread's 4 x 4 weight patch cut into QM_SLICES small pieces, so that one piece can follow every MFMA
-// of a step (see qmm_step): scales, code-book lookups, products, then the split into bf16 halves and the LDS writes,
-// one output column at a time.  `k` is a compile-time constant after unrolling; w and sh live in registers.
-constexpr int QM_SLICES = 44;
-template <int BITS, bool SPLIT, bool QUANT>
-__device__ __forceinline__ void qmm_stash_slice(int k, const QmmArgs& a, const QmmLane& t, const QmmPatch<QUANT>& r,
-                                                const float* s_code, float (&sh)[4], float (&w)[4][4], __bf16* bh,
-                                                __bf16* bl) {
-  if (k < 4) {                                     // the reconstructed scale of row k's block
-    if constexpr (QUANT) sh[k] = r.sc[k];
-  } else if (k < 20) {                             // code-book value of one weight
-    const int j = (k - 4) >> 2, c = (k - 4) & 3;
+// The patch fetch that a step weaves into its MFMAs: the registers it fills and the step they belong to.
+template <bool QUANT>
+struct QmmAhead {
+  QmmPatch<QUANT>& patch;
+  int fetch_step;
+};
+
+// Decode of the thread's 4 x 4 weight patch cut into small operations, so that a few can follow every MFMA of a step
+// (see qmm_step).  Per output column: four code-book lookups, four products with the block scales, the bf16 hi halves
+// of the column's four reduction indices and their LDS write, the remainders (two operations of two values), the lo
+// halves and their write.  The operations of the columns are staggered so that a lookup's LDS latency is covered by
+// another column's arithmetic, and each carries a rough instruction count by which they are dealt out evenly.
+enum QmmOpKind { QM_FETCH, QM_LOOKUP, QM_SCALE, QM_HI, QM_BACK, QM_REST, QM_LO };
+struct QmmOp { int kind, c, j, cost; };
+#define LQ_QMM_LOOKUPS(C) {QM_LOOKUP, C, 0, 2}, {QM_LOOKUP, C, 1, 2}, {QM_LOOKUP, C, 2, 2}, {QM_LOOKUP, C, 3, 2}
+#define LQ_QMM_SCALES(C) {QM_SCALE, C, 0, 1}, {QM_SCALE, C, 1, 1}, {QM_SCALE, C, 2, 1}, {QM_SCALE, C, 3, 1}
+#define LQ_QMM_LOWS(C) {QM_BACK, C, 0, 3}, {QM_REST, C, 0, 2}, {QM_BACK, C, 2, 3}, {QM_REST, C, 2, 2}, {QM_LO, C, 0, 3}
+constexpr QmmOp QM_OPS[] = {
+    {QM_FETCH, 0, 0, 2}, {QM_FETCH, 0, 1, 2}, {QM_FETCH, 0, 2, 2}, {QM_FETCH, 0, 3, 2},
+    LQ_QMM_LOOKUPS(0), LQ_QMM_LOOKUPS(1), LQ_QMM_LOOKUPS(2), LQ_QMM_LOOKUPS(3), LQ_QMM_SCALES(0), {QM_HI, 0, 0, 3},
+    LQ_QMM_SCALES(1), LQ_QMM_LOWS(0), {QM_HI, 1, 0, 3}, LQ_QMM_SCALES(2), LQ_QMM_LOWS(1), {QM_HI, 2, 0, 3},
+    LQ_QMM_SCALES(3), LQ_QMM_LOWS(2), {QM_HI, 3, 0, 3}, LQ_QMM_LOWS(3)};
+#undef LQ_QMM_LOOKUPS
+#undef LQ_QMM_SCALES
+#undef LQ_QMM_LOWS
+constexpr int QM_NOPS = sizeof(QM_OPS) / sizeof(QM_OPS[0]);
+
+// 3-bit code words are assembled from two loads, which would stall a woven fetch: that variant fetches up front.
+constexpr bool qmm_woven_fetch(int bits, bool quant, bool split) { return split && (!quant || bits != 3); }
+constexpr bool qmm_op_used(int k, bool split, bool woven_fetch) {
+  return (split || QM_OPS[k].kind < QM_BACK) && (woven_fetch || QM_OPS[k].kind != QM_FETCH);
+}
+// The MFMA (0 .. mfmas - 1) of the step that operation k follows: operations are spread by cumulative cost.
+constexpr int qmm_op_slot(int k, int mfmas, bool split, bool woven_fetch) {
+  int total = 0, before = 0;
+  for (int i = 0; i < QM_NOPS; ++i) {
+    if (!qmm_op_used(i, split, woven_fetch)) continue;
+    if (i < k) before += QM_OPS[i].cost;
+    total += QM_OPS[i].cost;
+  }
+  return before * mfmas / total;
+}
+
+template <int BITS, bool SPLIT, bool QUANT, int K>
+__device__ __forceinline__ void qmm_stash_op(const QmmArgs& a, const QmmLane& t, const QmmAhead<QUANT>& ahead,
+                                             const QmmPatch<QUANT>& r, const float* s_code, float (&w)[4][4],
+                                             floatx2& back, __bf16* bh, __bf16* bl) {
+  constexpr QmmOp op = QM_OPS[K];
+  constexpr int c = op.c, j = op.j;
+  if constexpr (op.kind == QM_FETCH) {
+    qmm_fetch_row<BITS, QUANT>(a, t, ahead.fetch_step, j, ahead.patch);
+  } else if constexpr (op.kind == QM_LOOKUP) {
     if constexpr (QUANT) w[j][c] = s_code[(r.cw[j] >> (c * BITS)) & ((1u << BITS) - 1u)];
     else w[j][c] = c == 0 ? r.dn[j].x : c == 1 ? r.dn[j].y : c == 2 ? r.dn[j].z : r.dn[j].w;
-  } else if (k < 36) {                             // times the scale: the same fl32(code * s^) that Dequantize returns
-    const int j = (k - 20) >> 2, c = (k - 20) & 3;
-    if constexpr (QUANT) w[j][c] = w[j][c] * sh[j];
-  } else {                                         // one column: its four reduction indices as bf16 hi (even k) or lo (odd)
-    const int c = (k - 36) >> 1;
+  } else if constexpr (op.kind == QM_SCALE) {      // the same fl32(code * s^) that Dequantize returns
+    if constexpr (QUANT) w[j][c] = w[j][c] * r.sc[j];
+  } else if constexpr (op.kind == QM_HI) {
     const floatx4 f = {w[0][c], w[1][c], w[2][c], w[3][c]};
-    const bf16x4 hi = __builtin_convertvector(f, bf16x4);
-    const int at = (4 * t.quad + c) * QM_PITCH + 4 * t.kg;
-    if (((k - 36) & 1) == 0) {
-      *reinterpret_cast<bf16x4*>(bh + at) = hi;
-    } else if constexpr (SPLIT) {
-      *reinterpret_cast<bf16x4*>(bl + at) = __builtin_convertvector(f - __builtin_convertvector(hi, floatx4), bf16x4);
-    }
+    *reinterpret_cast<bf16x4*>(bh + (4 * t.quad + c) * QM_PITCH + 4 * t.kg) = __builtin_convertvector(f, bf16x4);
+  } else if constexpr (op.kind == QM_BACK) {       // what the hi halves of values j, j + 1 of the column hold
+    const floatx2 f = {w[j][c], w[j + 1][c]};
+    back = __builtin_convertvector(__builtin_convertvector(f, bf16x2), floatx2);
+  } else if constexpr (op.kind == QM_REST) {       // values j, j + 1 of the column give way to what their hi halves miss
+    w[j][c] -= back.x; w[j + 1][c] -= back.y;
+  } else {
+    const floatx4 f = {w[0][c], w[1][c], w[2][c], w[3][c]};
+    *reinterpret_cast<bf16x4*>(bl + (4 * t.quad + c) * QM_PITCH + 4 * t.kg) = __builtin_convertvector(f, bf16x4);
+  }
+}
+
+// The operations that follow MFMA number M of a step with MFMAS of them.
+template <int BITS, bool SPLIT, bool QUANT, int MFMAS, int M, int K = 0>
+__device__ __forceinline__ void qmm_stash_after(const QmmArgs& a, const QmmLane& t, const QmmAhead<QUANT>& ahead,
+                                                const QmmPatch<QUANT>& r, const float* s_code, float (&w)[4][4],
+                                                floatx2& back, __bf16* bh, __bf16* bl) {
+  if constexpr (K < QM_NOPS) {
+    constexpr bool WF = qmm_woven_fetch(BITS, QUANT, SPLIT);
+    if constexpr (qmm_op_used(K, SPLIT, WF) && qmm_op_slot(K, MFMAS, SPLIT, WF) == M)
+      qmm_stash_op<BITS, SPLIT, QUANT, K>(a, t, ahead, r, s_code, w, back, bh, bl);
+    qmm_stash_after<BITS, SPLIT, QUANT, MFMAS, M, K + 1>(a, t, ahead, r, s_code, w, back, bh, bl);
   }
 }
 
 // One 32-deep step of the wavefront's 128 x 64 part from the operand tiles in LDS, with the decode of the next step's
-// weight patch (registers r -> LDS buffer nbh / nbl) woven in: every MFMA is followed by a few pieces of the decode
-// and a scheduling fence, so that the vector ALU works in the shadow of the matrix pipe of the same wavefront (a
+// weight patch (registers r -> LDS buffer nbh / nbl) and, in the three-term variant, the fetch of the patch after
+// that (`ahead`) woven in: every MFMA is followed by the operations dealt to it and a scheduling fence, so that the vector ALU works in the shadow of the matrix pipe of the same wavefront (a
 // wavefront that has an MFMA waiting for the pipe holds the SIMD's vector issue slot, so the two cannot be overlapped
 // across wavefronts).  The weight operands of both 16-deep halves are read first (they are shared by the four row
 // tiles); the X operands are read one row tile ahead of the MFMAs that use them.
 template <int BITS, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void qmm_step(const QmmArgs& a, const QmmLane& t, const unsigned char* xstage,
                                          const __bf16* bhp, const __bf16* blp, const QmmPatch<QUANT>& r,
-                                         const float* s_code, __bf16* nbh, __bf16* nbl, floatx16 (&acc)[QM_AT][2]) {
-  constexpr int MFMAS = 2 * QM_AT * 2 * (SPLIT ? 3 : 1);
-  float sh[4], w[4][4];
+                                         const QmmAhead<QUANT>& ahead, const float* s_code, __bf16* nbh, __bf16* nbl,
+                                         floatx16 (&acc)[QM_AT][2]) {
+  constexpr int MFMAS = 2 * QM_AT * 2 * (SPLIT ? 3 : 1), PER = SPLIT ? 6 : 2, LAST = PER - 2;   // MFMAs per row tile
+  float w[4][4];
+  floatx2 back;
   bf16x8 bh[2][2], bl[2][2];
 #pragma unroll
   for (int g = 0; g < 2; ++g)
@@ -261,41 +315,44 @@ __device__ __forceinline__ void qmm_step(const QmmArgs& a, const QmmLane& t, con
   bf16x8 ah[2], al[2];                   // current and next row tile
   ah[0] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[0]);
   if constexpr (SPLIT) al[0] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[0]);
-  int m = 0;                             // MFMAs issued so far: slices [m * QM_SLICES / MFMAS, (m + 1) * QM_SLICES / MFMAS) follow
-#define LQ_QMM_MFMA(A, B, I, J)                                                                            \
+#define LQ_QMM_MFMA(A, B, I, J, M)                                                                         \
   {                                                                                                        \
     acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc[I][J], 0, 0, 0);                         \
-    for (int k = m * QM_SLICES / MFMAS; k < (m + 1) * QM_SLICES / MFMAS; ++k)                              \
-      qmm_stash_slice<BITS, SPLIT, QUANT>(k, a, t, r, s_code, sh, w, nbh, nbl);                            \
-    ++m;                                                                                                   \
+    qmm_stash_after<BITS, SPLIT, QUANT, MFMAS, M>(a, t, ahead, r, s_code, w, back, nbh, nbl);                             \
     __builtin_amdgcn_sched_barrier(0);                                                                     \
   }
-#pragma unroll
-  for (int idx = 0; idx < 2 * QM_AT; ++idx) {
-    const int g = idx / QM_AT, i = idx % QM_AT, cur = idx & 1, nxt = cur ^ 1;
-    if (idx + 1 < 2 * QM_AT) {
-      const int gn = (idx + 1) / QM_AT, in = (idx + 1) % QM_AT;
-      ah[nxt] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[gn] + in * 2048);
-      if constexpr (SPLIT) al[nxt] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[gn] + in * 2048);
-    }
-    // the two accumulators of the row tile alternate, three terms each
-    if constexpr (SPLIT) {
-      LQ_QMM_MFMA(al[cur], bh[g][0], i, 0)
-      LQ_QMM_MFMA(al[cur], bh[g][1], i, 1)
-      LQ_QMM_MFMA(ah[cur], bl[g][0], i, 0)
-      LQ_QMM_MFMA(ah[cur], bl[g][1], i, 1)
-    }
-    LQ_QMM_MFMA(ah[cur], bh[g][0], i, 0)
-    LQ_QMM_MFMA(ah[cur], bh[g][1], i, 1)
+  // one row tile (IDX = 0 .. 2 * QM_AT - 1: 16-deep half IDX / QM_AT, row tile IDX % QM_AT): the two accumulators of
+  // the row tile alternate, three terms each
+#define LQ_QMM_TILE(IDX)                                                                                   \
+  {                                                                                                        \
+    constexpr int g = (IDX) / QM_AT, i = (IDX) % QM_AT, cur = (IDX) & 1, nxt = cur ^ 1, m0 = (IDX) * PER;   \
+    if constexpr ((IDX) + 1 < 2 * QM_AT) {                                                                 \
+      constexpr int gn = ((IDX) + 1) / QM_AT, in = ((IDX) + 1) % QM_AT;                                    \
+      ah[nxt] = *reinterpret_cast<const bf16x8*>(xstage + t.aoff[gn] + in * 2048);                         \
+      if constexpr (SPLIT)                                                                                 \
+        al[nxt] = *reinterpret_cast<const bf16x8*>(xstage + QmmLds::X_PLANE + t.aoff[gn] + in * 2048);     \
+    }                                                                                                      \
+    if constexpr (SPLIT) {                                                                                 \
+      LQ_QMM_MFMA(al[cur], bh[g][0], i, 0, m0)                                                             \
+      LQ_QMM_MFMA(al[cur], bh[g][1], i, 1, m0 + 1)                                                         \
+      LQ_QMM_MFMA(ah[cur], bl[g][0], i, 0, m0 + 2)                                                         \
+      LQ_QMM_MFMA(ah[cur], bl[g][1], i, 1, m0 + 3)                                                         \
+    }                                                                                                      \
+    LQ_QMM_MFMA(ah[cur], bh[g][0], i, 0, m0 + LAST)                                                         \
+    LQ_QMM_MFMA(ah[cur], bh[g][1], i, 1, m0 + LAST + 1)                                                    \
   }
+  static_assert(QM_AT == 4, "eight row-tile steps are written out");
+  LQ_QMM_TILE(0) LQ_QMM_TILE(1) LQ_QMM_TILE(2) LQ_QMM_TILE(3)
+  LQ_QMM_TILE(4) LQ_QMM_TILE(5) LQ_QMM_TILE(6) LQ_QMM_TILE(7)
+#undef LQ_QMM_TILE
 #undef LQ_QMM_MFMA
 }
 
 // Steps [sa, sb) of one part (numbered within the part).  At the top of step s (iteration `it` of this run) X stage
-// it % 2 and weight buffer it % 2 hold step s, and one patch register set holds step s + 1.  The step fetches the patch
-// of s + 2 and starts the X transfer of s + 1 into the other stage (free since the barrier that ended step s - 1), then
-// multiplies step s while decoding the patch of s + 1 into the other weight buffer, waits for everything it has
-// started and meets the barrier.  Prefetch indices are clamped, not guarded (the last step is fetched again and
+// it % 2 and weight buffer it % 2 hold step s, and one patch register set holds step s + 1.  The step starts the X
+// transfer of s + 1 into the other stage (free since the barrier that ended step s - 1), then multiplies step s while
+// fetching the patch of s + 2 and decoding the patch of s + 1 into the other weight buffer, waits for everything it
+// has started and meets the barrier.  Prefetch indices are clamped, not guarded (the last step is fetched again and
 // dropped): the body is branch-free.
 template <int BITS, bool SPLIT, bool QUANT>
 __device__ __forceinline__ void qmm_run(const QmmArgs& a, const QmmLane& t, int sa, int sb, const float* s_code,
@@ -322,10 +379,11 @@ __device__ __forceinline__ void qmm_run(const QmmArgs& a, const QmmLane& t, int 
   // U: parity of the step inside this run = its X stage, its weight buffer, and the patch registers that are free
 #define LQ_QMM_STEP(U, S)                                                                                    \
   {                                                                                                          \
-    qmm_fetch<BITS, QUANT>(a, t, (S) + 2 < last ? (S) + 2 : last, ring[(U)]);                                \
+    const QmmAhead<QUANT> ahead = {ring[(U)], (S) + 2 < last ? (S) + 2 : last};                              \
+    if constexpr (!qmm_woven_fetch(BITS, QUANT, SPLIT)) qmm_fetch<BITS, QUANT>(a, t, ahead.fetch_step, ring[(U)]); \
     LQ_QMM_DMA((S) + 1, 1 - (U));                                                                            \
-    qmm_step<BITS, SPLIT, QUANT>(a, t, LQ_QMM_XSTAGE(U), LQ_QMM_BH(U), LQ_QMM_BL(U), ring[1 - (U)], s_code,  \
-                                 LQ_QMM_BH(1 - (U)), LQ_QMM_BL(1 - (U)), acc);                               \
+    qmm_step<BITS, SPLIT, QUANT>(a, t, LQ_QMM_XSTAGE(U), LQ_QMM_BH(U), LQ_QMM_BL(U), ring[1 - (U)], ahead,   \
+                                 s_code, LQ_QMM_BH(1 - (U)), LQ_QMM_BL(1 - (U)), acc);                       \
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* the X tile of S + 1 has landed */                    \
     __syncthreads();                                                                                         \
   }
