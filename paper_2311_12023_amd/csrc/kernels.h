@@ -45,6 +45,20 @@ int launch_fisher_row_col(const float* F, int64_t d, int64_t k, double* scratch,
 // lo = bf16(x - hi), planes of rows_pad x K with zero rows beyond `rows`.
 int launch_split_planes(const float* X, int64_t rows, int64_t K, int64_t ldx, int64_t rows_pad, uint16_t* hi,
                         uint16_t* lo, hipStream_t st);
+// The same planes of X and, from the same pass over X, T = X L1 (L1: K x rank fp32, contiguous, rank at most
+// SPLIT_PROJECT_MAX_RANK) as bf16 planes th / tl of rows_pad x Kd (Kd = 32 or 64, at least rank; columns beyond rank
+// and rows beyond `rows` are zero).  rows_pad is a multiple of 64.  precision 1 computes T from the hi halves alone
+// and leaves the lo plane of X unwritten.  `part`: split_project_part_floats(rows_pad, K) floats of scratch.
+// `bs`: block scales to reconstruct in the same launch (see launch_block_scales; nblocks == 0: none).
+constexpr int SPLIT_PROJECT_MAX_RANK = 64;
+struct BlockScales {
+  const uint8_t* sidx; const float* v; int64_t nblocks; int scale_block, levels;
+  float* out;
+};
+size_t split_project_part_floats(int64_t rows_pad, int64_t K);
+int launch_split_project(const float* X, int64_t rows, int64_t K, int64_t ldx, int64_t rows_pad, const float* L1,
+                         int rank, int precision, uint16_t* xh, uint16_t* xl, float* part, size_t part_floats,
+                         uint16_t* th, uint16_t* tl, int Kd, const BlockScales& bs, hipStream_t st);
 // Quantized part of a product: X (planes of rows_pad x K) times the K x N matrix stored as NF codes (row-major
 // flattening, N a multiple of `block`, K * N below 2^31).  K is a multiple of 32; K == 0 leaves the part out.
 struct QmmPart {

@@ -16,6 +16,7 @@ constexpr int SMALL_RANK = 512;
 
 struct MatmulPlan {
   bool small;
+  bool fused;      // T = X L1 comes out of the pass that splits X (rank up to SPLIT_PROJECT_MAX_RANK)
   int64_t r32, rows_pad;
   size_t x_plane, t_floats, t_plane, part_floats, scale_floats;   // elements
 };
@@ -33,9 +34,11 @@ static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   p.r32 = up32(rank);
   p.rows_pad = (m + 255) / 256 * 256;
   p.x_plane = (size_t)p.rows_pad * (size_t)d;
-  p.t_floats = rank > 0 ? (size_t)m * (size_t)p.r32 : 0;
+  p.fused = rank > 0 && rank <= SPLIT_PROJECT_MAX_RANK;
+  p.t_floats = rank > 0 && !p.fused ? (size_t)m * (size_t)p.r32 : 0;
   p.t_plane = rank > 0 ? (size_t)p.rows_pad * (size_t)p.r32 : 0;
-  const size_t p1 = rank > 0 ? qmatmul_part_floats(m, p.r32, (int)(d / 32)) : 0;
+  const size_t p1 = p.fused ? split_project_part_floats(p.rows_pad, d)
+                            : rank > 0 ? qmatmul_part_floats(m, p.r32, (int)(d / 32)) : 0;
   const size_t p2 = qmatmul_part_floats(m, k, (int)(d / 32 + p.r32 / 32));
   p.part_floats = p1 > p2 ? p1 : p2;
   p.scale_floats = (size_t)(d * k / 16);            // one scale per block, block size at least 16
@@ -98,10 +101,16 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   float* part = reinterpret_cast<float*>(w); w += up256(p.part_floats * 4);
   float* bscale = reinterpret_cast<float*>(w);
 
-  LQ_TRY(launch_split_planes(X, m, d, d, p.rows_pad, xh, xl, st));
-  LQ_TRY(launch_block_scales(scale_idx, v, d * k / c.block, c.scale_block, scale_levels(c), bscale, st));
   QmmPart none{};
-  if (rank > 0) {   // T = X L1, m x r32 with zero columns beyond r, then its planes
+  if (p.fused) {    // planes of X and of T = X L1 from one pass over X, the block scales of Q in the same launch
+    const BlockScales bs{scale_idx, v, d * k / c.block, c.scale_block, scale_levels(c), bscale};
+    LQ_TRY(launch_split_project(X, m, d, d, p.rows_pad, L1, rank, precision, xh, xl, part, p.part_floats, th, tl,
+                                (int)p.r32, bs, st));
+  } else {
+    LQ_TRY(launch_block_scales(scale_idx, v, d * k / c.block, c.scale_block, scale_levels(c), bscale, st));
+    LQ_TRY(launch_split_planes(X, m, d, d, p.rows_pad, xh, xl, st));
+  }
+  if (rank > 0 && !p.fused) {   // T = X L1, m x r32 with zero columns beyond r, then its planes
     DensePart xl1{xh, xl, d, L1, rank, d, rank};
     LQ_TRY(launch_qmatmul(none, xl1, m, p.rows_pad, p.r32, T, p.r32, part, p.part_floats, precision, st));
     LQ_TRY(launch_split_planes(T, m, p.r32, p.r32, p.rows_pad, th, tl, st));

@@ -51,7 +51,7 @@ static const char* const kNames[NUM_CLASSES] = {
     "wide_gemm_kernel<5,0,1,1>", "wide_gemm_kernel<6,0,1,1>", "wide_gemm_kernel<7,0,1,1>", "wide_gemm_kernel<8,0,1,1>",
     "wide_gemm_kernel<1,1,2,1>", "wide_gemm_kernel<2,1,2,1>", "wide_gemm_kernel<3,1,2,1>", "wide_gemm_kernel<4,1,2,1>",
     "wide_gemm_kernel<5,1,1,1>", "wide_gemm_kernel<6,1,1,1>", "wide_gemm_kernel<7,1,1,1>", "wide_gemm_kernel<8,1,1,1>",
-    "qmatmul_kernel", "qmatvec_kernel"};
+    "qmatmul_kernel", "qmatvec_kernel", "split_project_kernel"};
 
 }  // namespace prof
 }  // namespace lq

@@ -22,7 +22,8 @@ enum Cls {
   GEMM_SPLIT_BASE = 27,     // + mode * 8 + (l/32 - 1): the bf16 hi/lo split variants of wide_gemm_kernel
   QMATMUL = 43,             // qmatmul_kernel (work = flops of the product)
   QMATVEC = 44,             // qmatvec_kernel (work = bytes)
-  NUM_CLASSES = 45
+  SPLIT_PROJECT = 45,       // split_project_kernel (work = bytes)
+  NUM_CLASSES = 46
 };
 
 bool enabled();
