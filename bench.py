@@ -59,9 +59,14 @@ def measured_traffic(name: str, table: str | None = None):
     base = name.split("<")[0]
     want = name.replace(" ", "")
     tot = n = 0.0
+    # a summary that also holds other tables marks the counter table with a heading that names the traffic
+    headed = any(ln.startswith("#") and "traffic" in ln.lower() for ln in lines[1:])
+    inside = not headed
     for ln in lines:
+        if headed and ln.startswith("#"):
+            inside = "traffic" in ln.lower()
         cells = [c.strip() for c in ln.strip().strip("|").split("|")]
-        if len(cells) != 4 or not cells[0].startswith("`"):
+        if not inside or len(cells) != 4 or not cells[0].startswith("`"):
             continue
         kern = cells[0].strip("`").replace(" ", "")
         if name.startswith("wide_gemm_kernel"):
@@ -199,8 +204,8 @@ def bench_matmul(args, torch, gen, lq, dev) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 2 for the sweep, 100 forward steps)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default: 1 / 20)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--matrices", type=int, default=7, help="use only the first N matrices of the layer (debugging)")
     ap.add_argument("--no-isolated", action="store_true",
@@ -231,6 +236,10 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sweep shards over GPUs by "
               "matrix without any collective, see DESIGN.md).", file=sys.stderr)
         return 2
+    if args.steps is None:          # a forward step is a few milliseconds, a sweep step more than half a second
+        args.steps = 100 if args.workload == "matmul" else 2
+    if args.warmup is None:
+        args.warmup = 20 if args.workload == "matmul" else 1
 
     import torch
     from paper_2311_12023_amd import gen, lq

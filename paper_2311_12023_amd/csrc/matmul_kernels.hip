@@ -2,22 +2,23 @@
 // (Section 3.2 "Implementation" and Appendix A: matrix products between fp32 inputs and quantized matrices).
 //
 // One kernel computes  Y[m x N] = Xq[m x Kq] * dequant(codes)[Kq x N]  +  Xd[m x Kd] * D[Kd x N]  where either part
-// may be empty.  The forward product is two launches of it:
-//   T = X L1          (dense part only, N = r rounded up to 32, the extra columns are zero)
+// may be empty.  The forward product is the launch
 //   Y = X Q + T L2    (quantized part followed by r/32 dense steps)
-// with X and T split into bf16 planes beforehand.
+// with X and T = X L1 as bf16 planes, which a first stage produces in one pass over X (project_kernels.hip) for ranks
+// up to 64.  Higher ranks split X with the small kernel below and form T with a launch of this kernel,
+//   T = X L1          (dense part only, N = r rounded up to 32, the extra columns are zero).
 //
 // Mapping: a workgroup of 512 threads (2 x 4 wavefronts, two per SIMD) owns a 256 x 256 output tile and walks the
 // reduction in 32-deep steps.  Both MFMA operands sit in LDS as bf16 hi and lo halves, rows = output rows (X) or
 // output columns (weights), the 32 reduction indices of a step contiguous, each double-buffered.
-//  - X is split into its two bf16 planes once per call by a small kernel (every column tile needs the same halves);
-//    the tiles then travel from global memory straight into LDS (global_load_lds_dwordx4: each lane moves 16 bytes,
-//    a wavefront fills 1 KB = 16 rows), one step ahead.  No register or vector-ALU instruction touches X.  Rows are
+//  - X is split into its two bf16 planes once per call (every column tile needs the same halves); the tiles then
+//    travel from global memory straight into LDS (global_load_lds_dwordx4: each lane moves 16 bytes, a wavefront
+//    fills 1 KB = 16 rows), one step ahead.  No register or vector-ALU instruction touches X.  Rows are
 //    64 bytes without padding; the four 16-byte units of a row are stored in the order unit ^ ((row / 2) % 4), which
 //    makes the 128-bit operand reads conflict-free.
 //  - The weight tile is decoded in registers: every thread fetches a 4 (reduction) x 4 (columns) patch a step or two
-//    ahead (four code words from four consecutive rows of Q and the reconstructed scales of their blocks, which a
-//    small kernel computes once per call), multiplies code-book value by scale (the same fl32(code * s^) that the
+//    ahead (four code words from four consecutive rows of Q and the reconstructed scales of their blocks, which are
+//    computed once per call), multiplies code-book value by scale (the same fl32(code * s^) that the
 //    stand-alone dequantizer produces), splits it and writes 8-byte runs into the weight buffer of the next step.
 //  - Each wavefront multiplies its 128 x 64 part with three v_mfma_f32_32x32x16_bf16 per tile pair (hi*hi + hi*lo +
 //    lo*hi, fp32 accumulation; the bf16-only variant keeps the hi halves alone).

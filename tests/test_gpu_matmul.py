@@ -59,6 +59,10 @@ def _gpu_product(env, oracle, x, codes, sidx, v, cfg_tuple, k, l1, l2, precision
     (20, 160, 528, (3, 16, 16), 7),          # just above that path's limit
     (3, 96, 64, (2, 32, 16), 1),             # rank 1
     (5, 64, 128, (4, 64, 16), 600),          # a rank beyond that path's limit goes to the MFMA kernel
+    (520, 1120, 256, (4, 64, 256), 64),      # nine 64-row strips of X, 17.5 steps of 64 cut into reduction ranges
+    (70, 224, 192, (3, 32, 32), 32),         # rank 32: T keeps one 32-deep step
+    (40, 96, 128, (4, 32, 16), 0),           # MFMA path without a low-rank part
+    (33, 128, 256, (4, 64, 64), 65),         # the smallest rank that takes the separate X L1 product
 ])
 def test_matmul_matches_oracle(env, oracle, m, d, k, cfg, rank):
     ocfg, codes, sidx, v, l1, l2 = _case(oracle, d, k, cfg, rank, 100 + m)
