@@ -75,6 +75,28 @@ def test_matmul_matches_oracle(env, oracle, m, d, k, cfg, rank):
         assert np.max(excess) <= 0, (precision, np.max(np.abs(y - ref) / scale))
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_matmul_random_shapes(env, oracle, seed):
+    """Seeded random shapes around the tile and strip sizes of all three paths (rows against 8, 64 and 256; the
+    reduction against 32 and 64; columns against 256; ranks against 4, 32 and 64)."""
+    rng = np.random.default_rng(5000 + seed)
+    bits = int(rng.choice([2, 3, 4, 8]))
+    block = int(rng.choice([16, 32, 64]))
+    scale_block = int(rng.choice([16, 64, 256]))
+    m = int(rng.choice([rng.integers(1, 9), rng.integers(9, 70), rng.integers(70, 600)]))
+    d = 32 * int(rng.integers(1, 20))
+    k = block * int(rng.integers(1, 1 + 640 // block))
+    rank = int(rng.choice([0, rng.integers(1, 33), rng.integers(33, 65), rng.integers(65, 90)]))
+    cfg = (bits, block, scale_block)
+    ocfg, codes, sidx, v, l1, l2 = _case(oracle, d, k, cfg, rank, 6000 + seed)
+    x = gen.activations(m, d, 7000 + seed)
+    ref, scale = oracle.matmul(x, codes, sidx, v, ocfg, k, l1, l2, want_abs=True)
+    for precision, tol in ((0, TOL_SPLIT), (1, TOL_BF16)):
+        y = _gpu_product(env, oracle, x, codes, sidx, v, cfg, k, l1, l2, precision)
+        assert y.shape == (m, k) and np.all(np.isfinite(y))
+        assert np.max(np.abs(y - ref) - tol * scale) <= 0, (m, d, k, cfg, rank, precision, np.max(np.abs(y - ref) / scale))
+
+
 def test_matmul_identity_returns_dequantized_weights(env, oracle):
     """X = I: every output is one stored weight; hi + lo of a weight carries 16 of its 24 bits."""
     torch, lq = env
