@@ -25,10 +25,8 @@ static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   p.small = m <= SMALL_M && rank <= SMALL_RANK;
   if (p.small) {
     const int mc = (int)std::min<int64_t>(m, QMATVEC_MAX_ROWS);
-    p.t_floats = (size_t)m * (size_t)rank;
-    const size_t p1 = rank > 0 ? xdense_part_floats(mc, d, rank) : 0;
-    const size_t p2 = qmatvec_part_floats(mc, d + rank, k);
-    p.part_floats = p1 > p2 ? p1 : p2;
+    p.t_floats = rank > 0 ? xdense_part_floats(mc, d, rank) : 0;      // T = X L1 as partial sums of its ranges
+    p.part_floats = qmatvec_part_floats(mc, d + rank, k);
     return p;
   }
   p.r32 = up32(rank);
@@ -87,9 +85,10 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
     for (int64_t r0 = 0; r0 < m; r0 += QMATVEC_MAX_ROWS) {
       const int mc = (int)std::min<int64_t>(QMATVEC_MAX_ROWS, m - r0);
       const float* Xc = X + r0 * d;
-      float* Tc = T + r0 * rank;
-      if (rank > 0) LQ_TRY(launch_xdense_narrow(Xc, d, L1, rank, d, rank, mc, Tc, rank, part, p.part_floats, st));
-      LQ_TRY(launch_qmatvec(q, Xc, d, d, Tc, rank, L2, k, rank, mc, k, Y + r0 * k, k, part, p.part_floats, st));
+      // the product kernel adds the ranges of T while it loads them: no launch in between
+      if (rank > 0) LQ_TRY(launch_xdense_narrow(Xc, d, L1, rank, d, rank, mc, T, p.t_floats, st));
+      LQ_TRY(launch_qmatvec(q, Xc, d, d, T, rank, rank > 0 ? xdense_splits(d) : 1, (int64_t)mc * rank, L2, k, rank, mc, k,
+                            Y + r0 * k, k, part, p.part_floats, st));
     }
     return LQ_OK;
   }

@@ -28,7 +28,8 @@ constexpr int MV_DEPTH = MV_ROWS_MAX / MV_GROUPS;   // rows per thread at most
 
 struct MvArgs {
   const float* X; int64_t ldx;      // m x K
-  const float* Xd; int64_t ldxd;    // m x Kd
+  const float* Xd; int64_t ldxd;    // m x Kd, given as xd_splits partial sums xd_stride floats apart (added in order)
+  int xd_splits; int64_t xd_stride;
   const uint8_t* codes; const uint8_t* sidx; const float* v;   // K x N, row-major flattening
   const float* D; int64_t ldd;      // Kd x N dense
   float* Y; int64_t ldy;            // splits == 1: m x N; else partial sums, range s at Y + s * m * ldy
@@ -58,7 +59,13 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
       float x = 0.0f;
       if (i < a.m) {
         const int64_t g = ra + r;
-        x = g < a.K ? a.X[(int64_t)i * a.ldx + g] : a.Xd[(int64_t)i * a.ldxd + (g - a.K)];
+        if (g < a.K) {
+          x = a.X[(int64_t)i * a.ldx + g];
+        } else {
+          const float* p = a.Xd + (int64_t)i * a.ldxd + (g - a.K);
+#pragma unroll 8
+          for (int z = 0; z < a.xd_splits; ++z) x += p[(int64_t)z * a.xd_stride];
+        }
       }
       s_x[i][r] = x;
     }
@@ -182,7 +189,8 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
 
 // T[m x N] = X[m x K] * D[K x N] for a narrow dense D (the d x rank factor): thread (p, g) of a workgroup takes column
 // p and every (256 / N')-th row of the workgroup's range (N' = N rounded up to a power of two, at most 256); the row
-// groups are added in a fixed order through LDS, the ranges by the reduce kernel.
+// groups are added in a fixed order through LDS; the ranges' partial sums (range s at Y + s * m * ldy) are left to the
+// consumer, which adds them in range order.
 constexpr int XDENSE_ROWS = 128;    // reduction rows per workgroup
 template <int M>
 __global__ __launch_bounds__(256) void xdense_narrow_kernel(const float* __restrict__ X, int64_t ldx,
@@ -244,10 +252,8 @@ size_t qmatvec_part_floats(int m, int64_t ktot, int64_t N) {
 }
 
 // Ranges of XDENSE_ROWS rows each.
-size_t xdense_part_floats(int m, int64_t K, int64_t N) {
-  const int64_t splits = (K + XDENSE_ROWS - 1) / XDENSE_ROWS;
-  return splits > 1 ? (size_t)splits * (size_t)m * (size_t)N : 0;
-}
+int xdense_splits(int64_t K) { return (int)((K + XDENSE_ROWS - 1) / XDENSE_ROWS); }
+size_t xdense_part_floats(int m, int64_t K, int64_t N) { return (size_t)xdense_splits(K) * (size_t)m * (size_t)N; }
 
 template <int BITS>
 static void launch_m(const MvArgs& a, dim3 grid, hipStream_t st) {
@@ -258,14 +264,15 @@ static void launch_m(const MvArgs& a, dim3 grid, hipStream_t st) {
 }
 
 int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, const float* Xd, int64_t ldxd,
-                   const float* D, int64_t ldd, int64_t Kd, int m, int64_t N, float* Y, int64_t ldy, float* part,
-                   size_t part_floats, hipStream_t st) {
+                   int xd_splits, int64_t xd_stride, const float* D, int64_t ldd, int64_t Kd, int m, int64_t N, float* Y,
+                   int64_t ldy, float* part, size_t part_floats, hipStream_t st) {
   if (m < 1 || m > QMATVEC_MAX_ROWS || K <= 0 || Kd < 0 || N <= 0 || (N % 16) != 0) return LQ_ERR_SHAPE;
+  if (Kd > 0 && xd_splits < 1) return LQ_ERR_ARG;
   if (q.block < 16 || (q.block & (q.block - 1)) != 0 || q.scale_block < 1 || (q.scale_block & (q.scale_block - 1)) != 0)
     return LQ_ERR_CONFIG;
   if ((N % q.block) != 0 || (ldy & 3) != 0 || (Kd > 0 && (ldd & 3) != 0)) return LQ_ERR_SHAPE;
   MvArgs a{};
-  a.X = X; a.ldx = ldx; a.K = K; a.Xd = Xd; a.ldxd = ldxd; a.D = D; a.ldd = ldd; a.Kd = Kd; a.N = N; a.m = m;
+  a.X = X; a.ldx = ldx; a.K = K; a.Xd = Xd; a.ldxd = ldxd; a.xd_splits = xd_splits; a.xd_stride = xd_stride; a.D = D; a.ldd = ldd; a.Kd = Kd; a.N = N; a.m = m;
   a.codes = q.codes; a.sidx = q.sidx; a.v = q.v;
   a.block_shift = __builtin_ctz((unsigned)q.block);
   a.group_shift = __builtin_ctz((unsigned)q.scale_block);
@@ -303,28 +310,22 @@ int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, c
   return LQ_OK;
 }
 
-int launch_xdense_narrow(const float* X, int64_t ldx, const float* D, int64_t ldd, int64_t K, int N, int m, float* T,
-                         int64_t ldt, float* part, size_t part_floats, hipStream_t st) {
+int launch_xdense_narrow(const float* X, int64_t ldx, const float* D, int64_t ldd, int64_t K, int N, int m, float* part,
+                         size_t part_floats, hipStream_t st) {
   if (m < 1 || m > QMATVEC_MAX_ROWS || K <= 0 || N <= 0) return LQ_ERR_SHAPE;
   int npow = 1;
   while (npow < N && npow < 256) npow <<= 1;
   const int rows = XDENSE_ROWS;
-  const int64_t splits64 = (K + rows - 1) / rows;
-  if (splits64 >= (1 << 16)) return LQ_ERR_SHAPE;
-  const int splits = (int)splits64;
-  if (splits > 1 && part_floats < (size_t)splits * (size_t)m * (size_t)N) return LQ_ERR_WORKSPACE;
-  float* out = splits > 1 ? part : T;
-  const int64_t ldo = splits > 1 ? N : ldt;
-  {
-    prof::Scope ps(prof::MISC, st, 4.0 * (double)K * N);
-    const dim3 grid((unsigned)splits), block(256);
-    if (m <= 1) hipLaunchKernelGGL((xdense_narrow_kernel<1>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, out, ldo);
-    else if (m <= 2) hipLaunchKernelGGL((xdense_narrow_kernel<2>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, out, ldo);
-    else if (m <= 4) hipLaunchKernelGGL((xdense_narrow_kernel<4>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, out, ldo);
-    else hipLaunchKernelGGL((xdense_narrow_kernel<8>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, out, ldo);
-    LQ_HIP_TRY(hipGetLastError());
-  }
-  if (splits > 1) LQ_TRY(launch_qmatmul_reduce(part, splits, m, N, T, ldt, st));
+  if ((K + rows - 1) / rows >= (1 << 16)) return LQ_ERR_SHAPE;
+  const int splits = xdense_splits(K);
+  if (part_floats < (size_t)splits * (size_t)m * (size_t)N) return LQ_ERR_WORKSPACE;
+  prof::Scope ps(prof::MISC, st, 4.0 * (double)K * N);
+  const dim3 grid((unsigned)splits), block(256);
+  if (m <= 1) hipLaunchKernelGGL((xdense_narrow_kernel<1>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
+  else if (m <= 2) hipLaunchKernelGGL((xdense_narrow_kernel<2>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
+  else if (m <= 4) hipLaunchKernelGGL((xdense_narrow_kernel<4>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
+  else hipLaunchKernelGGL((xdense_narrow_kernel<8>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
+  LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }
 
