@@ -95,20 +95,14 @@ struct MvWeights {
   const uint8_t* codes; const uint8_t* sidx; const float* v;
   int bits, block, scale_block, levels;
 };
-// Y[m x N] = X[m x K] * dequant(q) + Xd[m x Kd] * D[Kd x N] (Kd may be 0), m <= QMATVEC_MAX_ROWS, in fp32 on the
-// vector ALU.  ldd and ldy are multiples of 4.  part: qmatvec_part_floats(m, K + Kd, N) floats of scratch.
-int qmatvec_splits(int m, int64_t ktot, int64_t N);
-size_t qmatvec_part_floats(int m, int64_t ktot, int64_t N);
-// Xd is given as xd_splits partial sums, xd_stride floats apart, which the kernel adds in order (1 and 0: Xd itself).
-int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, const float* Xd, int64_t ldxd,
-                   int xd_splits, int64_t xd_stride, const float* D, int64_t ldd, int64_t Kd, int m, int64_t N, float* Y,
-                   int64_t ldy, float* part, size_t part_floats, hipStream_t st);
-// T[m x N] = X[m x K] * D[K x N] for a narrow dense D (N at most a few hundred), m <= QMATVEC_MAX_ROWS, left as
-// xdense_splits(K) partial sums of m x N each (contiguous, one after the other in `part`): T is their sum in order.
-int xdense_splits(int64_t K);
-size_t xdense_part_floats(int m, int64_t K, int64_t N);
-int launch_xdense_narrow(const float* X, int64_t ldx, const float* D, int64_t ldd, int64_t K, int N, int m, float* part,
-                         size_t part_floats, hipStream_t st);
+// Y[m x N] = X[m x K] * dequant(q) + (X L1) L2 with L1 (K x rank, contiguous) and L2 (rank x N, leading dimension
+// ldl2), rank at most 512 (0: no low-rank part), m <= QMATVEC_MAX_ROWS, in fp32 on the vector ALU.  ldy is a multiple
+// of 4.  part: qmatvec_part_floats(m, K, N, rank) floats of scratch.
+int qmatvec_splits(int m, int64_t K, int64_t N, int rank);
+size_t qmatvec_part_floats(int m, int64_t K, int64_t N, int rank);
+int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, const float* L1, const float* L2,
+                   int64_t ldl2, int rank, int m, int64_t N, float* Y, int64_t ldy, float* part, size_t part_floats,
+                   hipStream_t st);
 
 // ---- small dense kernels (small_kernels.hip) --------------------------------------------------
 constexpr int GRAM_CHUNKS = 16;

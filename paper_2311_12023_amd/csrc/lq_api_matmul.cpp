@@ -25,8 +25,7 @@ static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   p.small = m <= SMALL_M && rank <= SMALL_RANK;
   if (p.small) {
     const int mc = (int)std::min<int64_t>(m, QMATVEC_MAX_ROWS);
-    p.t_floats = rank > 0 ? xdense_part_floats(mc, d, rank) : 0;      // T = X L1 as partial sums of its ranges
-    p.part_floats = qmatvec_part_floats(mc, d + rank, k);
+    p.part_floats = qmatvec_part_floats(mc, d, k, rank);
     return p;
   }
   p.r32 = up32(rank);
@@ -79,16 +78,11 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   hipStream_t st = (hipStream_t)stream;
   if (p.small) {
     // plan_bytes lays the regions out in the same order with empty planes
-    float* T = reinterpret_cast<float*>(w); w += up256(p.t_floats * 4);
-    float* part = reinterpret_cast<float*>(w);
+    float* part = reinterpret_cast<float*>(w);           // the only region of the plan that is not empty
     const MvWeights q{codes_packed, scale_idx, v, c.bits, c.block, c.scale_block, scale_levels(c)};
     for (int64_t r0 = 0; r0 < m; r0 += QMATVEC_MAX_ROWS) {
       const int mc = (int)std::min<int64_t>(QMATVEC_MAX_ROWS, m - r0);
-      const float* Xc = X + r0 * d;
-      // the product kernel adds the ranges of T while it loads them: no launch in between
-      if (rank > 0) LQ_TRY(launch_xdense_narrow(Xc, d, L1, rank, d, rank, mc, T, p.t_floats, st));
-      LQ_TRY(launch_qmatvec(q, Xc, d, d, T, rank, rank > 0 ? xdense_splits(d) : 1, (int64_t)mc * rank, L2, k, rank, mc, k,
-                            Y + r0 * k, k, part, p.part_floats, st));
+      LQ_TRY(launch_qmatvec(q, X + r0 * d, d, d, L1, L2, k, rank, mc, k, Y + r0 * k, k, part, p.part_floats, st));
     }
     return LQ_OK;
   }

@@ -1,17 +1,18 @@
 // Forward product with a decomposed weight for a handful of input rows (single tokens, small decode batches):
-//     Y[m x N] = X[m x K] * dequant(codes)[K x N] + T[m x Kd] * D[Kd x N],      m <= 8,
+//     Y[m x N] = X[m x K] * dequant(codes)[K x N] + (X * L1)[m x r] * L2[r x N],      m <= 8,
 // (Section 3.2 "Implementation", Appendix A: the matrix-vector case of the run-time comparison).  With so few rows the
 // product is bound by reading the weights once from HBM (b0/8 bytes each), not by arithmetic, so the weights are decoded
 // and multiplied on the vector ALU in fp32: exact products of the same fl32(code * s^) values that Dequantize returns,
-// fp32 accumulation.  The forward product is T = X L1 (a narrow dense product), then Y = X Q + T L2.
+// fp32 accumulation.  Two launches: the first multiplies X with [Q | L1] (the columns of L1 are extra column tiles of
+// the same grid), the second adds the reduction ranges of both results and the small product (X L1) L2.
 //
-// Mapping: a thread owns one 16-weight run (one block scale per run, codes fetched as one 2..16-byte word) in every
-// 32nd row of its workgroup's range of reduction rows; a workgroup is 8 runs (128 columns) x 32 row groups, so that
-// 256 workgroups of up to 512 rows cover a 4096 x 4096 matrix with every load of a thread issued before the first is
-// used (the whole matrix is in flight at once, which is what an HBM-bound kernel needs).  The X values of the range sit in
-// LDS.  Row groups are summed by a fixed butterfly inside each wavefront and in wavefront order through LDS; the ranges
-// (`splits` of them: enough to fill the machine while the partial sums stay small next to the weights) are added in a
-// fixed order by a second kernel, so results are deterministic.
+// Mapping of the first kernel: a thread owns one 16-weight run (one block scale per run, codes fetched as one
+// 2..16-byte word) in every 32nd row of its workgroup's range of reduction rows; a workgroup is 8 runs (128 columns) x
+// 32 row groups, so that 256 workgroups of up to 512 rows cover a 4096 x 4096 matrix with every load of a thread issued
+// before the first is used (the whole matrix is in flight at once, which is what an HBM-bound kernel needs).  The X
+// values of the range sit in LDS.  Row groups are summed by a fixed butterfly inside each wavefront and in wavefront
+// order through LDS; the ranges (`splits` of them: enough to fill the machine while the partial sums stay small next to
+// the weights) are added in a fixed order by the second kernel, so results are deterministic.
 #include <algorithm>
 
 #include "kernels.h"
@@ -28,13 +29,13 @@ constexpr int MV_DEPTH = MV_ROWS_MAX / MV_GROUPS;   // rows per thread at most
 
 struct MvArgs {
   const float* X; int64_t ldx;      // m x K
-  const float* Xd; int64_t ldxd;    // m x Kd, given as xd_splits partial sums xd_stride floats apart (added in order)
-  int xd_splits; int64_t xd_stride;
   const uint8_t* codes; const uint8_t* sidx; const float* v;   // K x N, row-major flattening
-  const float* D; int64_t ldd;      // Kd x N dense
-  float* Y; int64_t ldy;            // splits == 1: m x N; else partial sums, range s at Y + s * m * ldy
-  int64_t K, Kd, N;
-  int m, splits, rows_per_split;
+  const float* D; int64_t ldd;      // K x Nd dense (the factor L1), columns tiles_q * 128 onward of the grid
+  int d_vec;                        // Nd % 4 == 0 and D 16-byte aligned: float4 loads
+  float* Y; int64_t ldy;            // partial sums of X Q: range s at Y + s * m * ldy (splits == 1 and Nd == 0: Y itself)
+  float* Yd;                        // partial sums of X D: range s at Yd + s * m * Nd
+  int64_t K, N, Nd;
+  int m, splits, rows_per_split, tiles_q;
   int block_shift, group_shift, levels;
   const DevTables* tables;
 };
@@ -45,30 +46,15 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
   __shared__ float s_code[1 << BITS];
   __shared__ __attribute__((aligned(16))) float s_sum[3][M][MV_COLS];
   const int tid = threadIdx.x, wave = tid >> 6, run = tid & (MV_RUNS - 1), grp = tid >> 3;
-  const int64_t col = (int64_t)blockIdx.x * MV_COLS + 16 * run;         // first column of the thread's run
+  const bool dense = (int)blockIdx.x >= a.tiles_q;                      // a column tile of D instead of the quantized matrix
+  const int64_t col = (int64_t)(dense ? blockIdx.x - a.tiles_q : blockIdx.x) * MV_COLS + 16 * run;   // first column of the run
   const int split = blockIdx.y;
-  const int64_t ktot = a.K + a.Kd;
   const int64_t ra = (int64_t)split * a.rows_per_split;
-  const int64_t rb = ra + a.rows_per_split < ktot ? ra + a.rows_per_split : ktot;
+  const int64_t rb = ra + a.rows_per_split < a.K ? ra + a.rows_per_split : a.K;
   const int nrows = (int)(rb - ra);
-  const int64_t qend = a.K < rb ? a.K : rb;
-  const int nq = qend > ra ? (int)(qend - ra) : 0;                      // quantized rows of the range (they come first)
   for (int i = tid; i < (1 << BITS); i += 256) s_code[i] = a.tables->code[Slot<BITS>::value][i];
   for (int i = 0; i < M; ++i)
-    for (int r = tid; r < nrows; r += 256) {
-      float x = 0.0f;
-      if (i < a.m) {
-        const int64_t g = ra + r;
-        if (g < a.K) {
-          x = a.X[(int64_t)i * a.ldx + g];
-        } else {
-          const float* p = a.Xd + (int64_t)i * a.ldxd + (g - a.K);
-#pragma unroll 8
-          for (int z = 0; z < a.xd_splits; ++z) x += p[(int64_t)z * a.xd_stride];
-        }
-      }
-      s_x[i][r] = x;
-    }
+    for (int r = tid; r < nrows; r += 256) s_x[i][r] = i < a.m ? a.X[(int64_t)i * a.ldx + ra + r] : 0.0f;
   __syncthreads();
 
   float acc[M][16];
@@ -76,12 +62,12 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
   for (int i = 0; i < M; ++i)
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[i][j] = 0.0f;
-  const bool live = col < a.N;                    // N is a multiple of 16
+  const bool live = col < (dense ? a.Nd : a.N);   // N is a multiple of 16
   const int64_t colc = live ? col : 0;
 
-  // quantized rows of the thread: local rows grp, grp + 32, ... below nq; every load is issued before the first use
-  // (a row past the end is loaded clamped and skipped)
-  if (nq > 0) {
+  if (!dense) {
+    // rows of the thread: local rows grp, grp + 32, ...; every load is issued before the first use (a row past the
+    // end is loaded clamped and skipped)
     uint2 cw[MV_DEPTH];                           // at most 64 bits of codes per run for b0 <= 4; 8-bit codes take two passes
     uint32_t si[MV_DEPTH];
     float vv[MV_DEPTH];
@@ -91,7 +77,7 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
 #pragma unroll
       for (int j = 0; j < MV_DEPTH; ++j) {
         int r = grp + MV_GROUPS * j;
-        r = r < nq ? r : nq - 1;
+        r = r < nrows ? r : nrows - 1;
         const int64_t e = (ra + r) * a.N + colc;
         const uint8_t* p = a.codes + (e >> 4) * (2 * BITS) + 8 * pass;
         if constexpr (BITS == 2) cw[j] = make_uint2(*reinterpret_cast<const uint32_t*>(p), 0u);
@@ -110,7 +96,7 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
 #pragma unroll
       for (int j = 0; j < MV_DEPTH; ++j) {
         const int r = grp + MV_GROUPS * j;
-        if (r < nq) {
+        if (r < nrows) {
           const float sh = block_scale(si[j], vv[j], a.levels);
           const uint64_t word = (uint64_t)cw[j].x | ((uint64_t)cw[j].y << 32);
           float xr[M];
@@ -125,22 +111,40 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
         }
       }
     }
-  }
-  // dense rows of the thread: local rows >= nq
-  for (int r = grp; r < nrows; r += MV_GROUPS) {
-    if (r < nq) continue;
-    const float* drow = a.D + (ra + r - a.K) * a.ldd + colc;
-    float w[16];
+  } else if (live) {
+    // 16 columns of D in the thread's rows, four rows' loads issued together; columns past Nd count as zero
+    constexpr int DCH = 4;
+    for (int r0 = grp; r0 < nrows; r0 += DCH * MV_GROUPS) {
+      float w[DCH][16];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 f = *reinterpret_cast<const float4*>(drow + 4 * q);
-      w[4 * q] = f.x; w[4 * q + 1] = f.y; w[4 * q + 2] = f.z; w[4 * q + 3] = f.w;
-    }
+      for (int u = 0; u < DCH; ++u) {
+        int r = r0 + u * MV_GROUPS;
+        r = r < nrows ? r : nrows - 1;            // loaded clamped, skipped below
+        const float* drow = a.D + (ra + r) * a.ldd + col;
+        if (a.d_vec) {
 #pragma unroll
-    for (int i = 0; i < M; ++i) {
-      const float x = s_x[i][r];
+          for (int q = 0; q < 4; ++q) {
+            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col + 4 * q < a.Nd) f = *reinterpret_cast<const float4*>(drow + 4 * q);
+            w[u][4 * q] = f.x; w[u][4 * q + 1] = f.y; w[u][4 * q + 2] = f.z; w[u][4 * q + 3] = f.w;
+          }
+        } else {
 #pragma unroll
-      for (int j = 0; j < 16; ++j) acc[i][j] = fmaf(x, w[j], acc[i][j]);
+          for (int j = 0; j < 16; ++j) w[u][j] = col + j < a.Nd ? drow[j] : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < DCH; ++u) {
+        const int r = r0 + u * MV_GROUPS;
+        if (r < nrows) {
+#pragma unroll
+          for (int i = 0; i < M; ++i) {
+            const float x = s_x[i][r];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[i][j] = fmaf(x, w[u][j], acc[i][j]);
+          }
+        }
+      }
     }
   }
 
@@ -166,7 +170,8 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
   }
   __syncthreads();
   if (wave == 0 && lane < MV_RUNS && live) {
-    float* __restrict__ Y = a.Y + (size_t)split * (size_t)a.m * a.ldy;
+    float* __restrict__ Yq = a.Y + (size_t)split * (size_t)a.m * a.ldy;
+    float* __restrict__ Yd = a.Yd + (size_t)split * (size_t)a.m * a.Nd;
 #pragma unroll
     for (int i = 0; i < M; ++i) {
       if (i >= a.m) break;
@@ -181,79 +186,101 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
           s += s_sum[2][i][16 * run + 4 * q + e];
           o[e] = s;
         }
-        *reinterpret_cast<float4*>(Y + (int64_t)i * a.ldy + col + 4 * q) = make_float4(o[0], o[1], o[2], o[3]);
+        if (!dense) {
+          *reinterpret_cast<float4*>(Yq + (int64_t)i * a.ldy + col + 4 * q) = make_float4(o[0], o[1], o[2], o[3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (col + 4 * q + e < a.Nd) Yd[(int64_t)i * a.Nd + col + 4 * q + e] = o[e];
+        }
       }
     }
   }
 }
 
-// T[m x N] = X[m x K] * D[K x N] for a narrow dense D (the d x rank factor): thread (p, g) of a workgroup takes column
-// p and every (256 / N')-th row of the workgroup's range (N' = N rounded up to a power of two, at most 256); the row
-// groups are added in a fixed order through LDS; the ranges' partial sums (range s at Y + s * m * ldy) are left to the
-// consumer, which adds them in range order.
-constexpr int XDENSE_ROWS = 128;    // reduction rows per workgroup
+// Second kernel: Y = sum of the ranges of X Q (in range order) + T L2 with T = sum of the ranges of X L1.  A workgroup
+// owns 64 columns; thread (column, slot) takes rows slot, slot + 4 of the result (SLOTS = min(M, 4) slots, one
+// wavefront each).  The workgroup first sums the rank values of T per row into LDS; the loads of a column of L2 are
+// issued 32 at a time.
+constexpr int MVF_COLS = 64;
+constexpr int MVF_RANK_MAX = 512;
+// p[0] + p[stride] + ... (n terms, in this order), the loads issued eight at a time.
+__device__ __forceinline__ float mvf_range_sum(const float* __restrict__ p, size_t stride, int n) {
+  float s = 0.0f;
+  for (int z0 = 0; z0 < n; z0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = z0 + u < n ? p[(size_t)(z0 + u) * stride] : 0.0f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  return s;
+}
 template <int M>
-__global__ __launch_bounds__(256) void xdense_narrow_kernel(const float* __restrict__ X, int64_t ldx,
-                                                            const float* __restrict__ D, int64_t ldd, int64_t K, int N,
-                                                            int npow, int m, int rows_per_split, float* __restrict__ Y,
-                                                            int64_t ldy) {
-  __shared__ float s_x[M][XDENSE_ROWS];
-  __shared__ float s_red[M][256];
-  const int tid = threadIdx.x;
-  const int p0 = tid & (npow - 1), g = tid / npow, groups = 256 / npow;
-  const int64_t ra = (int64_t)blockIdx.x * rows_per_split;
-  const int64_t rb = ra + rows_per_split < K ? ra + rows_per_split : K;
-  const int nrows = (int)(rb - ra);
-  for (int i = 0; i < M; ++i)
-    for (int r = tid; r < nrows; r += 256) s_x[i][r] = i < m ? X[(int64_t)i * ldx + ra + r] : 0.0f;
-  float* __restrict__ out = Y + (size_t)blockIdx.x * (size_t)m * ldy;
-  for (int pc = 0; pc < N; pc += npow) {             // column chunks (one, unless N > 256)
-    const int p = pc + p0;
-    float acc[M];
+__global__ __launch_bounds__(MVF_COLS * (M < 4 ? M : 4)) void qmatvec_finish_kernel(
+    const float* __restrict__ part, const float* __restrict__ tpart, int splits, int m, int64_t N, int rank,
+    const float* __restrict__ L2, int64_t ldl2, float* __restrict__ Y, int64_t ldy) {
+  constexpr int SLOTS = M < 4 ? M : 4, THREADS = MVF_COLS * SLOTS, RT = (M + SLOTS - 1) / SLOTS;
+  __shared__ float s_t[M][MVF_RANK_MAX];
+  const int tid = threadIdx.x, slot = tid / MVF_COLS;
+  const int64_t col = (int64_t)blockIdx.x * MVF_COLS + (tid % MVF_COLS);
+  const bool live = col < N;
+  const int64_t colc = live ? col : 0;
+  // the thread's rows of X Q
+  float acc[RT];
 #pragma unroll
-    for (int i = 0; i < M; ++i) acc[i] = 0.0f;
-    __syncthreads();                                 // X slice ready; s_red free again
-    if (p < N)
-      for (int r = g; r < nrows; r += groups) {
-        const float w = D[(ra + r) * ldd + p];
+  for (int j = 0; j < RT; ++j) {
+    const int i = slot + SLOTS * j;
+    float s = 0.0f;
+    if (i < m) s = mvf_range_sum(part + (size_t)i * N + colc, (size_t)m * N, splits);
+    acc[j] = s;
+  }
+  // T, with the tail up to a multiple of 32 zero
+  const int rank32 = (rank + 31) & ~31;
+  for (int idx = tid; idx < m * rank32; idx += THREADS) {
+    const int i = idx / rank32, p = idx % rank32;
+    float t = 0.0f;
+    if (p < rank) t = mvf_range_sum(tpart + (size_t)i * rank + p, (size_t)m * rank, splits);
+    s_t[i][p] = t;
+  }
+  __syncthreads();
+  for (int p0 = 0; p0 < rank; p0 += 32) {
+    float w[32];
 #pragma unroll
-        for (int i = 0; i < M; ++i) acc[i] = fmaf(s_x[i][r], w, acc[i]);
-      }
+    for (int u = 0; u < 32; ++u) w[u] = p0 + u < rank ? L2[(int64_t)(p0 + u) * ldl2 + colc] : 0.0f;
 #pragma unroll
-    for (int i = 0; i < M; ++i) s_red[i][tid] = acc[i];
-    __syncthreads();
-    if (g == 0 && p < N) {
+    for (int j = 0; j < RT; ++j) {
+      const int i = slot + SLOTS * j;
+      if (i < M) {
 #pragma unroll
-      for (int i = 0; i < M; ++i) {
-        if (i >= m) break;
-        float s = 0.0f;
-        for (int gg = 0; gg < groups; ++gg) s += s_red[i][gg * npow + p0];
-        out[(int64_t)i * ldy + p] = s;
+        for (int u = 0; u < 32; ++u) acc[j] = fmaf(s_t[i][p0 + u], w[u], acc[j]);
       }
     }
   }
+#pragma unroll
+  for (int j = 0; j < RT; ++j) {
+    const int i = slot + SLOTS * j;
+    if (live && i < m) Y[(int64_t)i * ldy + col] = acc[j];
+  }
 }
 
-// Reduction ranges for m rows against (K + Kd) x N weights: about 512 workgroups, at most 512 rows each (a multiple
-// of 32), and partial sums (splits * m * N floats) that stay below about a quarter of a 4-bit matrix's bytes.
-int qmatvec_splits(int m, int64_t ktot, int64_t N) {
-  const int64_t tiles = (N + MV_COLS - 1) / MV_COLS;
-  int64_t s = (512 + tiles - 1) / tiles;
-  s = std::min<int64_t>(s, std::max<int64_t>(1, ktot / (32 * (int64_t)std::max(m, 1))));
-  s = std::max<int64_t>(s, (ktot + MV_ROWS_MAX - 1) / MV_ROWS_MAX);     // the X slice must fit in LDS
-  int64_t rows = (ktot + s - 1) / s;
+// Reduction ranges for m rows against K x (N + rank) weights: at most 512 workgroups (with 8 rows two fit a CU, and a
+// few more than the machine holds would cost a second round), at most 512 rows each (a multiple of 32), and partial
+// sums (splits * m * (N + rank) floats) that stay below about a quarter of a 4-bit matrix's bytes.
+int qmatvec_splits(int m, int64_t K, int64_t N, int rank) {
+  const int64_t tiles = (N + MV_COLS - 1) / MV_COLS + (rank + MV_COLS - 1) / MV_COLS;
+  int64_t s = std::max<int64_t>(1, 512 / tiles);
+  s = std::min<int64_t>(s, std::max<int64_t>(1, K / (32 * (int64_t)std::max(m, 1))));
+  s = std::max<int64_t>(s, (K + MV_ROWS_MAX - 1) / MV_ROWS_MAX);        // the X slice must fit in LDS
+  int64_t rows = (K + s - 1) / s;
   rows = (rows + 31) / 32 * 32;
-  return (int)std::max<int64_t>(1, (ktot + rows - 1) / rows);
+  return (int)std::max<int64_t>(1, (K + rows - 1) / rows);
 }
 
-size_t qmatvec_part_floats(int m, int64_t ktot, int64_t N) {
-  const int s = qmatvec_splits(m, ktot, N);
-  return s > 1 ? (size_t)s * (size_t)m * (size_t)N : 0;
+size_t qmatvec_part_floats(int m, int64_t K, int64_t N, int rank) {
+  const int s = qmatvec_splits(m, K, N, rank);
+  return (s > 1 || rank > 0) ? (size_t)s * (size_t)m * (size_t)(N + rank) : 0;
 }
-
-// Ranges of XDENSE_ROWS rows each.
-int xdense_splits(int64_t K) { return (int)((K + XDENSE_ROWS - 1) / XDENSE_ROWS); }
-size_t xdense_part_floats(int m, int64_t K, int64_t N) { return (size_t)xdense_splits(K) * (size_t)m * (size_t)N; }
 
 template <int BITS>
 static void launch_m(const MvArgs& a, dim3 grid, hipStream_t st) {
@@ -263,40 +290,44 @@ static void launch_m(const MvArgs& a, dim3 grid, hipStream_t st) {
   else hipLaunchKernelGGL((qmatvec_kernel<BITS, 8>), grid, dim3(256), 0, st, a);
 }
 
-int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, const float* Xd, int64_t ldxd,
-                   int xd_splits, int64_t xd_stride, const float* D, int64_t ldd, int64_t Kd, int m, int64_t N, float* Y,
-                   int64_t ldy, float* part, size_t part_floats, hipStream_t st) {
-  if (m < 1 || m > QMATVEC_MAX_ROWS || K <= 0 || Kd < 0 || N <= 0 || (N % 16) != 0) return LQ_ERR_SHAPE;
-  if (Kd > 0 && xd_splits < 1) return LQ_ERR_ARG;
+int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, const float* L1, const float* L2,
+                   int64_t ldl2, int rank, int m, int64_t N, float* Y, int64_t ldy, float* part, size_t part_floats,
+                   hipStream_t st) {
+  if (m < 1 || m > QMATVEC_MAX_ROWS || K <= 0 || N <= 0 || (N % 16) != 0) return LQ_ERR_SHAPE;
+  if (rank < 0 || rank > MVF_RANK_MAX) return LQ_ERR_RANK;
   if (q.block < 16 || (q.block & (q.block - 1)) != 0 || q.scale_block < 1 || (q.scale_block & (q.scale_block - 1)) != 0)
     return LQ_ERR_CONFIG;
-  if ((N % q.block) != 0 || (ldy & 3) != 0 || (Kd > 0 && (ldd & 3) != 0)) return LQ_ERR_SHAPE;
+  if ((N % q.block) != 0 || (ldy & 3) != 0) return LQ_ERR_SHAPE;
   MvArgs a{};
-  a.X = X; a.ldx = ldx; a.K = K; a.Xd = Xd; a.ldxd = ldxd; a.xd_splits = xd_splits; a.xd_stride = xd_stride; a.D = D; a.ldd = ldd; a.Kd = Kd; a.N = N; a.m = m;
+  a.X = X; a.ldx = ldx; a.K = K; a.N = N; a.m = m;
+  a.D = L1; a.ldd = rank; a.Nd = rank;
+  a.d_vec = (rank > 0 && (rank & 3) == 0 && ((uintptr_t)L1 & 15) == 0) ? 1 : 0;
   a.codes = q.codes; a.sidx = q.sidx; a.v = q.v;
   a.block_shift = __builtin_ctz((unsigned)q.block);
   a.group_shift = __builtin_ctz((unsigned)q.scale_block);
   a.levels = q.levels;
-  const int64_t ktot = K + Kd;
-  a.splits = qmatvec_splits(m, ktot, N);
-  int64_t rows = (ktot + a.splits - 1) / a.splits;
+  a.splits = qmatvec_splits(m, K, N, rank);
+  int64_t rows = (K + a.splits - 1) / a.splits;
   rows = (rows + 31) / 32 * 32;
   if (rows > MV_ROWS_MAX) return LQ_ERR_SHAPE;
   a.rows_per_split = (int)rows;
-  a.splits = (int)((ktot + rows - 1) / rows);                           // no empty range
-  if (a.splits > 1 && part_floats < (size_t)a.splits * (size_t)m * (size_t)N) return LQ_ERR_WORKSPACE;
-  a.Y = a.splits > 1 ? part : Y;
-  a.ldy = a.splits > 1 ? N : ldy;
+  a.splits = (int)((K + rows - 1) / rows);                              // no empty range
+  const bool direct = a.splits == 1 && rank == 0;                       // nothing to add afterwards
+  if (!direct && part_floats < (size_t)a.splits * (size_t)m * (size_t)(N + rank)) return LQ_ERR_WORKSPACE;
+  a.Y = direct ? Y : part;
+  a.ldy = direct ? ldy : N;
+  a.Yd = direct ? nullptr : part + (size_t)a.splits * (size_t)m * (size_t)N;   // after the partial sums of X Q
   const DevTables* tab = nullptr;
   LQ_TRY(device_tables(&tab));
   a.tables = tab;
-  const int64_t tiles = (N + MV_COLS - 1) / MV_COLS;
-  if (tiles >= (1ll << 31)) return LQ_ERR_SHAPE;
-  const dim3 grid((unsigned)tiles, (unsigned)a.splits);
+  const int64_t tiles_q = (N + MV_COLS - 1) / MV_COLS, tiles_d = (rank + MV_COLS - 1) / MV_COLS;
+  if (tiles_q + tiles_d >= (1ll << 31)) return LQ_ERR_SHAPE;
+  a.tiles_q = (int)tiles_q;
+  const dim3 grid((unsigned)(tiles_q + tiles_d), (unsigned)a.splits);
   {
-    // algorithmic bytes: the weights once (codes, one scale index per block, the dense rows), X, Y
-    const double wbytes = (double)K * (double)N * (q.bits / 8.0 + 1.0 / q.block) + 4.0 * (double)Kd * (double)N;
-    prof::Scope ps(prof::QMATVEC, st, wbytes + 4.0 * m * (double)(ktot + N));
+    // algorithmic bytes: the weights once (codes, one scale index per block, both factors), X, Y
+    const double wbytes = (double)K * (double)N * (q.bits / 8.0 + 1.0 / q.block) + 4.0 * (double)rank * (double)(K + N);
+    prof::Scope ps(prof::QMATVEC, st, wbytes + 4.0 * m * (double)(K + N));
     switch (q.bits) {
       case 2: launch_m<2>(a, grid, st); break;
       case 3: launch_m<3>(a, grid, st); break;
@@ -306,25 +337,14 @@ int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, c
     }
     LQ_HIP_TRY(hipGetLastError());
   }
-  if (a.splits > 1) LQ_TRY(launch_qmatmul_reduce(part, a.splits, m, N, Y, ldy, st));
-  return LQ_OK;
-}
-
-int launch_xdense_narrow(const float* X, int64_t ldx, const float* D, int64_t ldd, int64_t K, int N, int m, float* part,
-                         size_t part_floats, hipStream_t st) {
-  if (m < 1 || m > QMATVEC_MAX_ROWS || K <= 0 || N <= 0) return LQ_ERR_SHAPE;
-  int npow = 1;
-  while (npow < N && npow < 256) npow <<= 1;
-  const int rows = XDENSE_ROWS;
-  if ((K + rows - 1) / rows >= (1 << 16)) return LQ_ERR_SHAPE;
-  const int splits = xdense_splits(K);
-  if (part_floats < (size_t)splits * (size_t)m * (size_t)N) return LQ_ERR_WORKSPACE;
-  prof::Scope ps(prof::MISC, st, 4.0 * (double)K * N);
-  const dim3 grid((unsigned)splits), block(256);
-  if (m <= 1) hipLaunchKernelGGL((xdense_narrow_kernel<1>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
-  else if (m <= 2) hipLaunchKernelGGL((xdense_narrow_kernel<2>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
-  else if (m <= 4) hipLaunchKernelGGL((xdense_narrow_kernel<4>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
-  else hipLaunchKernelGGL((xdense_narrow_kernel<8>), grid, block, 0, st, X, ldx, D, ldd, K, N, npow, m, rows, part, (int64_t)N);
+  if (direct) return LQ_OK;
+  prof::Scope ps(prof::MISC, st, 4.0 * ((double)a.splits * m * (double)(N + rank) + (double)rank * (double)N + m * (double)N));
+  const dim3 fgrid((unsigned)((N + MVF_COLS - 1) / MVF_COLS));
+  const float* tpart = a.Yd;
+  if (m <= 1) hipLaunchKernelGGL((qmatvec_finish_kernel<1>), fgrid, dim3(MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
+  else if (m <= 2) hipLaunchKernelGGL((qmatvec_finish_kernel<2>), fgrid, dim3(2 * MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
+  else if (m <= 4) hipLaunchKernelGGL((qmatvec_finish_kernel<4>), fgrid, dim3(4 * MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
+  else hipLaunchKernelGGL((qmatvec_finish_kernel<8>), fgrid, dim3(4 * MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }

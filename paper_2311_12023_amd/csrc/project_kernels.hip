@@ -155,8 +155,15 @@ __global__ __launch_bounds__(256) void project_finish_kernel(const float* __rest
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     const int64_t row = i / q, c4 = (i % q) << 2;
     const float* p = part + row * XP_COLS + c4;
-    floatx4 sum = *reinterpret_cast<const floatx4*>(p);
-    for (int s = 1; s < splits; ++s) sum += *reinterpret_cast<const floatx4*>(p + (int64_t)s * stride);
+    floatx4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < splits; s0 += 8) {       // the loads issued eight at a time
+      floatx4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        v[u] = s0 + u < splits ? *reinterpret_cast<const floatx4*>(p + (int64_t)(s0 + u) * stride) : floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += v[u];
+    }
     bf16x4 hi, lo;
     xp_split(sum, hi, lo);
     *reinterpret_cast<bf16x4*>(th + row * Kd + c4) = hi;
