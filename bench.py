@@ -180,7 +180,7 @@ def bench_matmul(args, torch, gen, lq, dev) -> int:
                            "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None, "launches": launches,
                            "avg_us": 1e3 * kms / launches}
         out["roofline_note"] = ("algorithmic bytes per launch: the packed codes and one scale index per block of the "
-                                "d x k matrix, the rank x k factor, X and Y.  Kernel durations come from a second pass "
+                                "d x k matrix, both low-rank factors, X and Y.  Kernel durations come from a second pass "
                                 "over the same steps with every launch bracketed by events (an upper bound for kernels "
                                 "this short); value and ms_per_step from the pass without brackets.")
         out["kernels"] = {n: {"ms": v[0], "launches": v[1]} for n, v in prof.items()}
