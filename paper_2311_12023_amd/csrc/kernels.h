@@ -49,12 +49,15 @@ int launch_split_planes(const float* X, int64_t rows, int64_t K, int64_t ldx, in
 // SPLIT_PROJECT_MAX_RANK) as bf16 planes th / tl of rows_pad x Kd (Kd = 32 or 64, at least rank; columns beyond rank
 // and rows beyond `rows` are zero).  rows_pad is a multiple of 64.  precision 1 computes T from the hi halves alone
 // and leaves the lo plane of X unwritten.  `part`: split_project_part_floats(rows_pad, K) floats of scratch.
+// th == NULL: the planes of T are not formed; T stays as split_project_splits(rows_pad, K) partial results in `part`
+// (range z, row i at part + (z * rows_pad + i) * 64).
 // `bs`: block scales to reconstruct in the same launch (see launch_block_scales; nblocks == 0: none).
 constexpr int SPLIT_PROJECT_MAX_RANK = 64;
 struct BlockScales {
   const uint8_t* sidx; const float* v; int64_t nblocks; int scale_block, levels;
   float* out;
 };
+int split_project_splits(int64_t rows_pad, int64_t K);
 size_t split_project_part_floats(int64_t rows_pad, int64_t K);
 int launch_split_project(const float* X, int64_t rows, int64_t K, int64_t ldx, int64_t rows_pad, const float* L1,
                          int rank, int precision, uint16_t* xh, uint16_t* xl, float* part, size_t part_floats,
@@ -82,8 +85,10 @@ struct DensePart {
 // the machine without cutting the reduction).
 int qmatmul_splits(int64_t m, int64_t N, int nsteps);
 size_t qmatmul_part_floats(int64_t m, int64_t N, int nsteps);
+// splits_out: when given and the reduction was cut, the partial results stay in `part` (range z at part + z * m * N,
+// nothing is written to Y) and *splits_out is their number; otherwise *splits_out = 1 and Y holds the result.
 int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t rows_pad, int64_t N, float* Y, int64_t ldy,
-                   float* part, size_t part_floats, int precision, hipStream_t st);
+                   float* part, size_t part_floats, int precision, hipStream_t st, int* splits_out = nullptr);
 
 // Y = sum of `splits` partial results (each m x N, contiguous, one after the other in `part`), in order.
 int launch_qmatmul_reduce(const float* part, int splits, int64_t m, int64_t N, float* Y, int64_t ldy, hipStream_t st);
@@ -103,6 +108,11 @@ size_t qmatvec_part_floats(int m, int64_t K, int64_t N, int rank);
 int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, const float* L1, const float* L2,
                    int64_t ldl2, int rank, int m, int64_t N, float* Y, int64_t ldy, float* part, size_t part_floats,
                    hipStream_t st);
+// Y[m x N] = sum of `splits` partial results (range z, row i at part + z * pstride + i * N, added in order) + T L2,
+// T[m x rank] = sum of `tsplits` partial results (range z, row i at tpart + z * tstride + i * tld); rank at most 512.
+int launch_range_sum_lowrank(const float* part, size_t pstride, int splits, const float* tpart, size_t tstride,
+                             int64_t tld, int tsplits, int64_t m, int64_t N, int rank, const float* L2, int64_t ldl2,
+                             float* Y, int64_t ldy, hipStream_t st);
 
 // ---- small dense kernels (small_kernels.hip) --------------------------------------------------
 constexpr int GRAM_CHUNKS = 16;

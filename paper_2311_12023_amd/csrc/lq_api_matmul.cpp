@@ -13,10 +13,14 @@ static int64_t up32(int64_t x) { return (x + 31) & ~(int64_t)31; }
 // MFMA path up to 8 rows).
 constexpr int64_t SMALL_M = QMATVEC_MAX_ROWS;
 constexpr int SMALL_RANK = 512;
+// Up to this many rows (and when the main kernel's reduction is cut into ranges anyway) the kernel that adds the
+// ranges also adds the ranges of T = X L1 and the product T L2: one launch and the main kernel's dense steps less.
+constexpr int64_t LEAN_M = 128;
 
 struct MatmulPlan {
   bool small;
   bool fused;      // T = X L1 comes out of the pass that splits X (rank up to SPLIT_PROJECT_MAX_RANK)
+  bool lean;       // fused, and T L2 is added by the kernel that adds the main kernel's reduction ranges
   int64_t r32, rows_pad;
   size_t x_plane, t_floats, t_plane, part_floats, scale_floats;   // elements
 };
@@ -32,6 +36,13 @@ static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
   p.rows_pad = (m + 255) / 256 * 256;
   p.x_plane = (size_t)p.rows_pad * (size_t)d;
   p.fused = rank > 0 && rank <= SPLIT_PROJECT_MAX_RANK;
+  p.lean = p.fused && m <= LEAN_M && qmatmul_splits(m, k, (int)(d / 32)) > 1;
+  if (p.lean) {    // the ranges of T stay alive until the last kernel: a region of their own
+    p.t_floats = split_project_part_floats(p.rows_pad, d);
+    p.part_floats = qmatmul_part_floats(m, k, (int)(d / 32));
+    p.scale_floats = (size_t)(d * k / 16);
+    return p;
+  }
   p.t_floats = rank > 0 && !p.fused ? (size_t)m * (size_t)p.r32 : 0;
   p.t_plane = rank > 0 ? (size_t)p.rows_pad * (size_t)p.r32 : 0;
   const size_t p1 = p.fused ? split_project_part_floats(p.rows_pad, d)
@@ -95,6 +106,19 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   float* bscale = reinterpret_cast<float*>(w);
 
   QmmPart none{};
+  if (p.lean) {
+    const BlockScales bs{scale_idx, v, d * k / c.block, c.scale_block, scale_levels(c), bscale};
+    LQ_TRY(launch_split_project(X, m, d, d, p.rows_pad, L1, rank, precision, xh, xl, T, p.t_floats, nullptr, nullptr,
+                                (int)p.r32, bs, st));
+    const QmmPart q{xh, xl, d, codes_packed, bscale, c.bits, c.block};
+    const DensePart nodense{};
+    int splits = 1;
+    LQ_TRY(launch_qmatmul(q, nodense, m, p.rows_pad, k, Y, k, part, p.part_floats, precision, st, &splits));
+    // without ranges the main kernel has written X Q into Y: each thread then reads and rewrites its own outputs
+    return launch_range_sum_lowrank(splits > 1 ? part : Y, (size_t)m * (size_t)k, splits, T,
+                                    (size_t)p.rows_pad * SPLIT_PROJECT_MAX_RANK, SPLIT_PROJECT_MAX_RANK,
+                                    split_project_splits(p.rows_pad, d), m, k, rank, L2, k, Y, k, st);
+  }
   if (p.fused) {    // planes of X and of T = X L1 from one pass over X, the block scales of Q in the same launch
     const BlockScales bs{scale_idx, v, d * k / c.block, c.scale_block, scale_levels(c), bscale};
     LQ_TRY(launch_split_project(X, m, d, d, p.rows_pad, L1, rank, precision, xh, xl, part, p.part_floats, th, tl,

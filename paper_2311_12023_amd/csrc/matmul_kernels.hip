@@ -561,7 +561,7 @@ static int launch_bits(const QmmArgs& a, dim3 grid, bool split_precision, hipStr
 }
 
 int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t rows_pad, int64_t N, float* Y, int64_t ldy,
-                   float* part, size_t part_floats, int precision, hipStream_t st) {
+                   float* part, size_t part_floats, int precision, hipStream_t st, int* splits_out) {
   if (m <= 0 || N <= 0 || rows_pad < m || (rows_pad % 256) != 0) return LQ_ERR_SHAPE;
   if ((q.K % QM_BK) != 0 || (dn.K % QM_BK) != 0 || q.K + dn.K <= 0) return LQ_ERR_SHAPE;
   if (q.K > 0 && (q.block < 16 || (q.block & (q.block - 1)) != 0)) return LQ_ERR_CONFIG;   // a power of two
@@ -601,7 +601,8 @@ int launch_qmatmul(const QmmPart& q, const DensePart& dn, int64_t m, int64_t row
       default: return LQ_ERR_CONFIG;
     }
   }
-  if (a.splits > 1) LQ_TRY(launch_qmatmul_reduce(part, a.splits, m, N, Y, ldy, st));
+  if (splits_out) *splits_out = a.splits;
+  else if (a.splits > 1) LQ_TRY(launch_qmatmul_reduce(part, a.splits, m, N, Y, ldy, st));
   return LQ_OK;
 }
 

@@ -199,9 +199,10 @@ __global__ __launch_bounds__(256) void qmatvec_kernel(MvArgs a) {
 }
 
 // Second kernel: Y = sum of the ranges of X Q (in range order) + T L2 with T = sum of the ranges of X L1.  A workgroup
-// owns 64 columns; thread (column, slot) takes rows slot, slot + 4 of the result (SLOTS = min(M, 4) slots, one
-// wavefront each).  The workgroup first sums the rank values of T per row into LDS; the loads of a column of L2 are
-// issued 32 at a time.
+// owns 64 columns and M rows (blockIdx.y picks the rows); thread (column, slot) takes rows slot, slot + 4 of them
+// (SLOTS = min(M, 4) slots, one wavefront each).  The workgroup first sums the rank values of T per row into LDS; the
+// loads of a column of L2 are issued 32 at a time.  Both sets of partial sums are described by the distance between
+// ranges and (for T) the row pitch, so the kernel also finishes the MFMA path's products of a few dozen rows.
 constexpr int MVF_COLS = 64;
 constexpr int MVF_RANK_MAX = 512;
 // p[0] + p[stride] + ... (n terms, in this order), the loads issued eight at a time.
@@ -216,15 +217,22 @@ __device__ __forceinline__ float mvf_range_sum(const float* __restrict__ p, size
   }
   return s;
 }
+struct MvfArgs {
+  const float* part; size_t pstride; int splits;               // ranges of X Q: range z, row i at part + z * pstride + i * N
+  const float* tpart; size_t tstride; int64_t tld; int tsplits;  // ranges of T: row i at tpart + z * tstride + i * tld
+  int m; int64_t N; int rank;
+  const float* L2; int64_t ldl2;
+  float* Y; int64_t ldy;
+};
 template <int M>
-__global__ __launch_bounds__(MVF_COLS * (M < 4 ? M : 4)) void qmatvec_finish_kernel(
-    const float* __restrict__ part, const float* __restrict__ tpart, int splits, int m, int64_t N, int rank,
-    const float* __restrict__ L2, int64_t ldl2, float* __restrict__ Y, int64_t ldy) {
+__global__ __launch_bounds__(MVF_COLS * (M < 4 ? M : 4)) void qmatvec_finish_kernel(MvfArgs a) {
   constexpr int SLOTS = M < 4 ? M : 4, THREADS = MVF_COLS * SLOTS, RT = (M + SLOTS - 1) / SLOTS;
   __shared__ float s_t[M][MVF_RANK_MAX];
   const int tid = threadIdx.x, slot = tid / MVF_COLS;
   const int64_t col = (int64_t)blockIdx.x * MVF_COLS + (tid % MVF_COLS);
-  const bool live = col < N;
+  const int row0 = (int)blockIdx.y * M;
+  const int m = a.m - row0 < M ? a.m - row0 : M;     // rows of this workgroup
+  const bool live = col < a.N;
   const int64_t colc = live ? col : 0;
   // the thread's rows of X Q
   float acc[RT];
@@ -232,22 +240,22 @@ __global__ __launch_bounds__(MVF_COLS * (M < 4 ? M : 4)) void qmatvec_finish_ker
   for (int j = 0; j < RT; ++j) {
     const int i = slot + SLOTS * j;
     float s = 0.0f;
-    if (i < m) s = mvf_range_sum(part + (size_t)i * N + colc, (size_t)m * N, splits);
+    if (i < m) s = mvf_range_sum(a.part + (size_t)(row0 + i) * a.N + colc, a.pstride, a.splits);
     acc[j] = s;
   }
   // T, with the tail up to a multiple of 32 zero
-  const int rank32 = (rank + 31) & ~31;
+  const int rank32 = (a.rank + 31) & ~31;
   for (int idx = tid; idx < m * rank32; idx += THREADS) {
     const int i = idx / rank32, p = idx % rank32;
     float t = 0.0f;
-    if (p < rank) t = mvf_range_sum(tpart + (size_t)i * rank + p, (size_t)m * rank, splits);
+    if (p < a.rank) t = mvf_range_sum(a.tpart + (size_t)(row0 + i) * a.tld + p, a.tstride, a.tsplits);
     s_t[i][p] = t;
   }
   __syncthreads();
-  for (int p0 = 0; p0 < rank; p0 += 32) {
+  for (int p0 = 0; p0 < a.rank; p0 += 32) {
     float w[32];
 #pragma unroll
-    for (int u = 0; u < 32; ++u) w[u] = p0 + u < rank ? L2[(int64_t)(p0 + u) * ldl2 + colc] : 0.0f;
+    for (int u = 0; u < 32; ++u) w[u] = p0 + u < a.rank ? a.L2[(int64_t)(p0 + u) * a.ldl2 + colc] : 0.0f;
 #pragma unroll
     for (int j = 0; j < RT; ++j) {
       const int i = slot + SLOTS * j;
@@ -260,8 +268,23 @@ __global__ __launch_bounds__(MVF_COLS * (M < 4 ? M : 4)) void qmatvec_finish_ker
 #pragma unroll
   for (int j = 0; j < RT; ++j) {
     const int i = slot + SLOTS * j;
-    if (live && i < m) Y[(int64_t)i * ldy + col] = acc[j];
+    if (live && i < m) a.Y[(int64_t)(row0 + i) * a.ldy + col] = acc[j];
   }
+}
+
+int launch_range_sum_lowrank(const float* part, size_t pstride, int splits, const float* tpart, size_t tstride,
+                             int64_t tld, int tsplits, int64_t m, int64_t N, int rank, const float* L2, int64_t ldl2,
+                             float* Y, int64_t ldy, hipStream_t st) {
+  if (m < 1 || N < 1 || splits < 1 || rank < 0 || rank > MVF_RANK_MAX || (rank > 0 && tsplits < 1)) return LQ_ERR_SHAPE;
+  const MvfArgs a{part, pstride, splits, tpart, tstride, tld, tsplits, (int)m, N, rank, L2, ldl2, Y, ldy};
+  prof::Scope ps(prof::MISC, st, 4.0 * ((double)splits * m * (double)N + (double)tsplits * m * rank + (double)rank * (double)N + m * (double)N));
+  const unsigned gx = (unsigned)((N + MVF_COLS - 1) / MVF_COLS);
+  if (m <= 1) hipLaunchKernelGGL((qmatvec_finish_kernel<1>), dim3(gx), dim3(MVF_COLS), 0, st, a);
+  else if (m <= 2) hipLaunchKernelGGL((qmatvec_finish_kernel<2>), dim3(gx), dim3(2 * MVF_COLS), 0, st, a);
+  else if (m <= 4) hipLaunchKernelGGL((qmatvec_finish_kernel<4>), dim3(gx), dim3(4 * MVF_COLS), 0, st, a);
+  else hipLaunchKernelGGL((qmatvec_finish_kernel<8>), dim3(gx, (unsigned)((m + 7) / 8)), dim3(4 * MVF_COLS), 0, st, a);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
 }
 
 // Reduction ranges for m rows against K x (N + rank) weights: at most 512 workgroups (with 8 rows two fit a CU, and a
@@ -338,15 +361,8 @@ int launch_qmatvec(const MvWeights& q, const float* X, int64_t ldx, int64_t K, c
     LQ_HIP_TRY(hipGetLastError());
   }
   if (direct) return LQ_OK;
-  prof::Scope ps(prof::MISC, st, 4.0 * ((double)a.splits * m * (double)(N + rank) + (double)rank * (double)N + m * (double)N));
-  const dim3 fgrid((unsigned)((N + MVF_COLS - 1) / MVF_COLS));
-  const float* tpart = a.Yd;
-  if (m <= 1) hipLaunchKernelGGL((qmatvec_finish_kernel<1>), fgrid, dim3(MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
-  else if (m <= 2) hipLaunchKernelGGL((qmatvec_finish_kernel<2>), fgrid, dim3(2 * MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
-  else if (m <= 4) hipLaunchKernelGGL((qmatvec_finish_kernel<4>), fgrid, dim3(4 * MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
-  else hipLaunchKernelGGL((qmatvec_finish_kernel<8>), fgrid, dim3(4 * MVF_COLS), 0, st, part, tpart, a.splits, m, N, rank, L2, ldl2, Y, ldy);
-  LQ_HIP_TRY(hipGetLastError());
-  return LQ_OK;
+  return launch_range_sum_lowrank(part, (size_t)m * N, a.splits, a.Yd, (size_t)m * rank, rank, a.splits, m, N, rank, L2,
+                                  ldl2, Y, ldy, st);
 }
 
 }  // namespace lq

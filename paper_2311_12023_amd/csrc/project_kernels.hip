@@ -212,6 +212,7 @@ int launch_split_project(const float* X, int64_t m, int64_t K, int64_t ldx, int6
     else hipLaunchKernelGGL(split_project_kernel<false>, grid, dim3(XP_THREADS), 0, st, a);
     LQ_HIP_TRY(hipGetLastError());
   }
+  if (!th) return LQ_OK;                     // the caller adds the ranges of T itself
   prof::Scope ps(prof::MISC, st, (double)(a.splits + 1) * (double)rows_pad * XP_COLS * 4.0);
   const int64_t total = rows_pad * (Kd >> 2);
   hipLaunchKernelGGL(project_finish_kernel, dim3((unsigned)std::min<int64_t>((total + 255) / 256, 4096)), dim3(256), 0, st,

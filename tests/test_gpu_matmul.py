@@ -63,6 +63,9 @@ def _gpu_product(env, oracle, x, codes, sidx, v, cfg_tuple, k, l1, l2, precision
     (70, 224, 192, (3, 32, 32), 32),         # rank 32: T keeps one 32-deep step
     (40, 96, 128, (4, 32, 16), 0),           # MFMA path without a low-rank part
     (33, 128, 256, (4, 64, 64), 65),         # the smallest rank that takes the separate X L1 product
+    (48, 1024, 512, (4, 64, 256), 64),       # a few dozen rows, reduction cut into ranges: T L2 joins the range sum
+    (100, 2048, 320, (3, 32, 64), 17),       # the same with a ragged rank and column tile
+    (9, 4096, 256, (2, 16, 16), 33),         # just above the vector path, one column tile, 16 ranges
 ])
 def test_matmul_matches_oracle(env, oracle, m, d, k, cfg, rank):
     ocfg, codes, sidx, v, l1, l2 = _case(oracle, d, k, cfg, rank, 100 + m)
