@@ -151,7 +151,7 @@ def test_matmul_full_size_sampled_rows(env, oracle, shape):
     assert np.max(np.abs(y_small - ref) - TOL_SPLIT * scale) <= 0
 
 
-@pytest.mark.parametrize("m", [4, 300])
+@pytest.mark.parametrize("m", [4, 40, 300])
 def test_matmul_in_a_hip_graph(env, oracle, m):
     """lq_matmul only launches kernels, so it can be recorded into a graph (after one eager call, which uploads the
     code-book tables and raises the kernel's LDS limit): every replay, with eager work on new inputs in between, must
