@@ -151,6 +151,24 @@ def test_matmul_full_size_sampled_rows(env, oracle, shape):
     assert np.max(np.abs(y_small - ref) - TOL_SPLIT * scale) <= 0
 
 
+def test_matmul_full_size_few_dozen_rows(env, oracle):
+    """96 rows against the 4096 x 4096 benchmark matrix: the path that adds T L2 together with the reduction ranges, at
+    its real shape (16 column tiles x 16 ranges), checked on sampled rows."""
+    d = k = 4096
+    cfg, rank, m = (4, 64, 256, 8, "bf16"), 64, 96
+    ocfg = oracle.config(*cfg)
+    w = gen.workload_matrix(3, 1)
+    codes, sidx, v, _ = oracle.quantize(w.ravel(), ocfg)
+    l1, l2 = gen.low_rank_factors(d, k, rank, 79)
+    x = gen.activations(m, d, 80)
+    rows = [0, 31, 32, 95]
+    ref, scale = oracle.matmul(x[rows], codes, sidx, v, ocfg, k, l1, l2, want_abs=True)
+    for precision, tol in ((0, TOL_SPLIT), (1, TOL_BF16)):
+        y = _gpu_product(env, oracle, x, codes, sidx, v, cfg, k, l1, l2, precision)
+        assert np.all(np.isfinite(y))
+        assert np.max(np.abs(y[rows] - ref) - tol * scale) <= 0, (precision, np.max(np.abs(y[rows] - ref) / scale))
+
+
 @pytest.mark.parametrize("m", [4, 40, 300])
 def test_matmul_in_a_hip_graph(env, oracle, m):
     """lq_matmul only launches kernels, so it can be recorded into a graph (after one eager call, which uploads the
