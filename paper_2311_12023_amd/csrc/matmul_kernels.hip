@@ -524,12 +524,11 @@ __global__ __launch_bounds__(256) void qmatmul_reduce_kernel(const float* __rest
   }
 }
 
-// Reduction ranges for an m x N product with `nsteps` 32-deep steps: enough workgroups to give every compute unit
-// one, at least four steps per range, at most 16 ranges.
+// Reduction ranges for an m x N product with `nsteps` 32-deep steps: as many as keep the grid within one workgroup per
+// compute unit (a second round would cost more than it saves), at least four steps per range, at most 16 ranges.
 int qmatmul_splits(int64_t m, int64_t N, int nsteps) {
   const int64_t tiles = ((m + QM_BM - 1) / QM_BM) * ((N + QM_BN - 1) / QM_BN);
-  if (tiles >= 128) return 1;
-  const int64_t want = (256 + tiles - 1) / tiles;
+  const int64_t want = std::max<int64_t>(1, 256 / tiles);
   const int64_t cap = std::max<int64_t>(1, nsteps / 4);
   return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(want, cap), 16));
 }
