@@ -10,7 +10,10 @@
  *    row-major, contiguous, fp32.  `stream` is a hipStream_t passed as void* (NULL = default stream).
  *  - The caller owns every buffer.  The library allocates no device memory: scratch space comes in
  *    through `workspace` (device, 256-byte aligned), sized by the matching *_workspace_bytes call.
- *    The library keeps no state except immutable code-book tables built on first use per device.
+ *    State the library keeps, per process: the immutable code-book tables (uploaded once per device on first
+ *    use); a pool of idle HIP streams that lq_error_table leases for its interleaved sub-batches (created on demand, at
+ *    most concurrent calls x (streams - 1) of them, returned to the pool when the call ends; lq_release_streams
+ *    destroys the idle ones); and, while lq_profile_enable is on, the per-launch event records.
  *  - Return value: LQ_OK (0) or a negative lq_status.  Arguments are validated on the host before
  *    anything is launched, so a call that fails validation has no effect on any buffer.
  *    Device data is not inspected: non-finite weights, or non-positive Fisher weights, give
@@ -106,6 +109,10 @@ typedef struct {
 const char* lq_status_string(int status);
 /* hipError_t of the most recent failing HIP call on this thread (0 if none). */
 int lq_last_hip_error(void);
+/* Destroys the idle streams of the pool that lq_error_table leases its extra streams from (all devices).  Streams that a
+ * running call holds are not touched; later calls create what they need again.  LQ_ERR_HIP if a stream could not be
+ * destroyed. */
+int lq_release_streams(void);
 
 /* NF-`bits` code book (Section 2.2): host_out[i] = value of code i, 2^bits ascending fp32 values
  * in [-1, 1] with host_out[2^(bits-1) - 1] == 0.  host pointer.  LQ_ERR_CONFIG for bits not in 2..8. */

@@ -1,7 +1,9 @@
 /*
- * lq_testing.h  --  entry points that expose single kernels of the randomized SVD to the test-suite.
- * They are part of the shared library so that each building block can be checked against a plain
- * reference on the GPU machine; applications use lq.h only.  All pointers are device pointers, matrices
+ * lq_testing.h  --  entry points that expose single kernels of the randomized SVD, and one iterate of the sweep, to
+ * the test-suite, so that each building block can be checked against a plain reference on the GPU machine.  They exist
+ * only in the testing build of the library (liblq_hip_testing.so: the same sources compiled with
+ * -DLQ_TESTING_HOOKS plus csrc/lq_testing_hooks.cpp, which also exports everything lq.h declares); the product
+ * library liblq_hip.so exports none of them and applications use lq.h only.  All pointers are device pointers, matrices
  * row-major.  "Wide" matrices have l rows (multiple of 32, at most 256) and a leading dimension that
  * is a multiple of 32 with zero padding.  Each call enqueues on `stream` and returns an lq_status.
  */
@@ -43,6 +45,12 @@ int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void
 int lq_test_bucket_code(int bits, float x);
 /* Largest LDS allocation per workgroup the device reports, in bytes. */
 size_t lq_test_lds_limit(void);
+/* Arms a capture for the next lq_error_table call of this host thread (of the testing library): after iteration `iter`
+ * of configuration cfg_index (index into that call's cfgs) the dequantized component Q of that iterate is written to
+ * Q_dense (device, d x k fp32), and, if iter < iters and sigma_next != NULL, the singular values that the Factorize of
+ * iteration iter + 1 finds for W - Q are written to sigma_next (host, rank doubles).  A test can then redo exactly that
+ * step of Algorithm 2 on the CPU from the same Q.  The request serves one call; cfg_index < 0 disarms it. */
+int lq_test_capture_iterate(int cfg_index, int iter, float* Q_dense, double* sigma_next);
 
 #ifdef __cplusplus
 }

@@ -407,6 +407,67 @@ static double oq_lowrank_residual(const float* W, const float* L1, const float* 
   return (double)W[(size_t)i * k + j] - acc;
 }
 
+/* One pass through the loop body of Algorithm 2 from a given Q(t-1):
+ *   L1, L2 <- Factorize(W - Q(t-1), F, r);  Q(t) <- Quantize(W - L1 L2, c);  eps_t (Eq. 4 when weighted).
+ * Q holds Q(t-1) on entry and Q(t) on return; A and T are n-element work arrays; cd, si, vv receive the codes, scale
+ * indices and group scales of Q(t). */
+static int oq_lq_iteration(const float* W, int d, int k, int r, oq_config c, const float* row_w, const float* col_w,
+                           float* Q, float* A, float* T, float* L1, float* L2, uint8_t* cd, uint8_t* si, float* vv,
+                           double* sigma, double* eps_out) {
+  const int64_t n = (int64_t)d * k;
+  int rc;
+  for (int64_t e = 0; e < n; ++e) A[e] = W[e] - Q[e];
+  rc = oq_factorize(A, d, k, row_w, col_w, r, L1, L2, sigma);
+  if (rc != OQ_OK) return rc;
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < d; ++i)
+    for (int j = 0; j < k; ++j) T[(size_t)i * k + j] = (float)oq_lowrank_residual(W, L1, L2, k, r, i, j);
+  rc = oq_quantize(T, n, c, cd, si, vv, NULL);
+  if (rc != OQ_OK) return rc;
+  oq_dequantize(cd, si, vv, n, c, Q);
+  double acc = 0.0;
+  for (int i = 0; i < d; ++i) {
+    double rowacc = 0.0;
+    for (int j = 0; j < k; ++j) {
+      double diff = oq_lowrank_residual(W, L1, L2, k, r, i, j) - (double)Q[(size_t)i * k + j];
+      double w = row_w ? (double)row_w[i] * (double)col_w[j] : 1.0;
+      rowacc += w * diff * diff;
+    }
+    acc += rowacc;
+  }
+  *eps_out = sqrt(acc);
+  return OQ_OK;
+}
+
+/* The same single iteration for callers: Algorithm 2's loop body applied once to a given Q(t-1) (Qprev, d x k fp32,
+ * any matrix; all zeros gives the first iteration).  Outputs as for oq_lq_init; any of codes, scale_idx, v, Qd,
+ * sigma may be NULL. */
+int oq_lq_step(const float* W, int d, int k, int r, oq_config c, const float* row_w, const float* col_w,
+               const float* Qprev, float* L1, float* L2, uint8_t* codes, uint8_t* scale_idx, float* v, float* Qd,
+               double* err, double* sigma) {
+  const int64_t n = (int64_t)d * k;
+  if (!oq_config_ok(c) || n % c.block != 0) return OQ_ERR;
+  if ((row_w == NULL) != (col_w == NULL)) return OQ_ERR;
+  const int64_t nb = n / c.block, ng = (nb + c.scale_block - 1) / c.scale_block;
+  float* Q = (float*)malloc(sizeof(float) * (size_t)n);
+  float* A = (float*)malloc(sizeof(float) * (size_t)n);
+  float* T = (float*)malloc(sizeof(float) * (size_t)n);
+  uint8_t* cd = (uint8_t*)malloc((size_t)n);
+  uint8_t* si = (uint8_t*)malloc((size_t)nb);
+  float* vv = (float*)malloc(sizeof(float) * (size_t)ng);
+  if (!Q || !A || !T || !cd || !si || !vv) return OQ_ERR;
+  memcpy(Q, Qprev, sizeof(float) * (size_t)n);
+  double eps = INFINITY;
+  int rc = oq_lq_iteration(W, d, k, r, c, row_w, col_w, Q, A, T, L1, L2, cd, si, vv, sigma, &eps);
+  if (err) *err = eps;
+  if (codes) memcpy(codes, cd, (size_t)n);
+  if (scale_idx) memcpy(scale_idx, si, (size_t)nb);
+  if (v) memcpy(v, vv, sizeof(float) * (size_t)ng);
+  if (Qd) memcpy(Qd, Q, sizeof(float) * (size_t)n);
+  free(Q); free(A); free(T); free(cd); free(si); free(vv);
+  return rc;
+}
+
 /* LQ(W, F, c, r)  (Algorithm 2; Eq. 2; stopping rule of Section 3.1).
  * Q <- 0, eps_0 <- inf; for t = 1..iters: L1,L2 <- Factorize(W - Q); Q <- Quantize(W - L1 L2, c);
  * eps_t = || sqrt(w) .* (W - Q - L1 L2) ||_F with w = 1 or row_w[i]*col_w[j]  (Eq. 4);
@@ -455,26 +516,8 @@ int oq_lq_init(const float* W, int d, int k, int r, oq_config c, int iters, int 
       memcpy(pvv, vv, sizeof(float) * (size_t)ng);
       if (sigma) memcpy(psg, sigma, sizeof(double) * (size_t)r);
     }
-    for (int64_t e = 0; e < n; ++e) A[e] = W[e] - Q[e];
-    rc = oq_factorize(A, d, k, row_w, col_w, r, L1, L2, sigma);
+    rc = oq_lq_iteration(W, d, k, r, c, row_w, col_w, Q, A, T, L1, L2, cd, si, vv, sigma, &eps);
     if (rc != OQ_OK) break;
-#pragma omp parallel for schedule(static)
-    for (int i = 0; i < d; ++i)
-      for (int j = 0; j < k; ++j) T[(size_t)i * k + j] = (float)oq_lowrank_residual(W, L1, L2, k, r, i, j);
-    rc = oq_quantize(T, n, c, cd, si, vv, NULL);
-    if (rc != OQ_OK) break;
-    oq_dequantize(cd, si, vv, n, c, Q);
-    double acc = 0.0;
-    for (int i = 0; i < d; ++i) {
-      double rowacc = 0.0;
-      for (int j = 0; j < k; ++j) {
-        double diff = oq_lowrank_residual(W, L1, L2, k, r, i, j) - (double)Q[(size_t)i * k + j];
-        double w = row_w ? (double)row_w[i] * (double)col_w[j] : 1.0;
-        rowacc += w * diff * diff;
-      }
-      acc += rowacc;
-    }
-    eps = sqrt(acc);
     if (trace) trace[t - 1] = eps;
     if (early_stop && eps > prev) {
       if (keep) {           /* hand back iterate t - 1 */

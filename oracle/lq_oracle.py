@@ -198,6 +198,32 @@ def lq(w: np.ndarray, r: int, cfg: Config, iters: int, early_stop: bool = False,
     return out
 
 
+def lq_step(w: np.ndarray, q_prev: np.ndarray, r: int, cfg: Config, row_w=None, col_w=None):
+    """One pass through Algorithm 2's loop body from a given Q(t-1).
+    -> dict(L1, L2, codes, scale_idx, v, Q, err, sigma)."""
+    w = np.ascontiguousarray(w, np.float32)
+    q_prev = np.ascontiguousarray(q_prev, np.float32)
+    d, k = w.shape
+    assert q_prev.shape == (d, k)
+    n = d * k
+    nb = n // cfg.block
+    ng = (nb + cfg.scale_block - 1) // cfg.scale_block
+    rw = None if row_w is None else np.ascontiguousarray(row_w, np.float32)
+    cw = None if col_w is None else np.ascontiguousarray(col_w, np.float32)
+    out = dict(L1=np.zeros((d, r), np.float32), L2=np.zeros((r, k), np.float32), codes=np.zeros(n, np.uint8),
+               scale_idx=np.zeros(nb, np.uint8), v=np.zeros(ng, np.float32), Q=np.zeros((d, k), np.float32),
+               sigma=np.zeros(r))
+    err = C.c_double(0.0)
+    rc = lib().oq_lq_step(_p(w, C.c_float), C.c_int(d), C.c_int(k), C.c_int(r), cfg, _p(rw, C.c_float),
+                          _p(cw, C.c_float), _p(q_prev, C.c_float), _p(out["L1"], C.c_float), _p(out["L2"], C.c_float),
+                          _p(out["codes"], C.c_uint8), _p(out["scale_idx"], C.c_uint8), _p(out["v"], C.c_float),
+                          _p(out["Q"], C.c_float), C.byref(err), _p(out["sigma"], C.c_double))
+    if rc != 0:
+        raise ValueError("oq_lq_step failed")
+    out["err"] = err.value
+    return out
+
+
 def error_table(w: np.ndarray, r: int, cfgs, iters: int, early_stop: bool = False, row_w=None, col_w=None):
     """Algorithm 3 inner loops.  -> err_sq (n_cfgs), storage_bits (n_cfgs)."""
     w = np.ascontiguousarray(w, np.float32)

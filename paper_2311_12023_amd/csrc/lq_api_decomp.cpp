@@ -9,19 +9,22 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
-#include "../../include/lq_testing.h"
 #include "kernels.h"
 #include "nf_device.h"
+#ifdef LQ_TESTING_HOOKS
+#include "testing_capture.h"
+#endif
 
 namespace lq {
 
 int check_quant_args(int64_t n, lq_config& c);
-size_t lds_limit_for_tests();
 
 constexpr int MAX_ITERS = 1024;
 constexpr int MAX_RANK = 128;
+constexpr int MAX_DEVICES = 64;
 
 static int64_t up32(int64_t x) { return (x + 31) / 32 * 32; }
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
@@ -312,6 +315,7 @@ struct Loop {
   bool want_trace = false;
   const float* Y1 = nullptr; const float* B1 = nullptr;
   const LoopOut* direct = nullptr;
+  int cfg_base = 0;                         // index of cfgs[0] in the caller's configuration list
   // state
   std::vector<LoopProblem> probs;
   std::vector<double> host_err;
@@ -417,6 +421,9 @@ struct Loop {
     }
     LQ_TRY(launch_lowrank_blockquant(a, with_err, c->st));
     LQ_TRY(launch_scalequant_error(a, min_block, with_err, c->st));
+#ifdef LQ_TESTING_HOOKS
+    LQ_TRY(capture_iterate(t));
+#endif
     done = t;
     bool last = t == iters;
     returned = t;
@@ -426,7 +433,7 @@ struct Loop {
       LQ_HIP_TRY(hipStreamSynchronize(c->st));
       if (eps > prev_eps) {
         last = true;
-        if (keep_best()) returned = t - 1;
+        if (early_stop == 2) returned = t - 1;     // also without output buffers: the sweep reports that iterate's error
       } else if (keep_best()) {
         LQ_TRY(emit_factors(*c, Ycur, Bcur, lamcur, direct->L1, direct->L2, direct->sigma));
       }
@@ -438,8 +445,44 @@ struct Loop {
     LQ_TRY(warm_factorize(*c, w, Bcur, sB, t == 1 ? pl.prm.qw2 : pl.prm.qw, batch));
     Ycur = w.Yw; Bcur = w.Bw; sY = pl.strideYw; sB = pl.strideBw;
     lamcur = c->at<double>(pl.lam);
+#ifdef LQ_TESTING_HOOKS
+    LQ_TRY(capture_sigma(t));
+#endif
     return LQ_OK;
   }
+
+#ifdef LQ_TESTING_HOOKS
+  // Testing build: the sweep copies out one configuration's quantized component after a chosen iteration (dense) and
+  // the singular values the next Factorize finds for W - Q of that iterate, so that a test can redo that single step
+  // from the very same Q on the CPU.
+  int capture_slot(int t) const {
+    const testing::Capture& cap = testing::capture();
+    if (!cap.armed || direct || t != cap.iter || cap.cfg < cfg_base || cap.cfg >= cfg_base + batch) return -1;
+    return cap.cfg - cfg_base;
+  }
+  int capture_iterate(int t) {
+    const int b = capture_slot(t);
+    if (b < 0) return LQ_OK;
+    PhaseArgs one = a;
+    one.batch = 1; one.prob = a.prob + b;
+    one.codes = a.codes + (size_t)b * a.strideCodes; one.sidx = a.sidx + (size_t)b * a.strideSidx;
+    one.v = a.v + (size_t)b * a.strideV;
+    one.R = nullptr; one.Qd = testing::capture().Q; one.strideQd = 0;
+    return launch_residual(one, c->st);
+  }
+  int capture_sigma(int t) {
+    const int b = capture_slot(t);
+    const testing::Capture& cap = testing::capture();
+    if (b < 0 || !cap.sigma) return LQ_OK;
+    const Plan& pl = c->pl;
+    std::vector<double> lamh(pl.rank);
+    LQ_HIP_TRY(hipMemcpyAsync(lamh.data(), c->at<double>(pl.lam) + (size_t)b * pl.prm.lw, sizeof(double) * pl.rank,
+                              hipMemcpyDeviceToHost, c->st));
+    LQ_HIP_TRY(hipStreamSynchronize(c->st));
+    for (int j = 0; j < pl.rank; ++j) cap.sigma[j] = std::sqrt(lamh[j]);
+    return LQ_OK;
+  }
+#endif
 
   // Dense Q if asked for, then the error trace comes to the host (synchronizes the stream).
   // Host outputs: trace[b * iters + t] (NaN where not computed), iters_done[b].
@@ -490,14 +533,44 @@ struct Loop {
   }
 };
 
-// Extra streams for lq_error_table's interleaved sub-batches: created once per host thread, default priority.
-static int extra_stream(int i, hipStream_t* out) {
-  static thread_local hipStream_t pool[4] = {nullptr, nullptr, nullptr, nullptr};   // per host thread: concurrent calls do not share them
-  if (i < 0 || i >= 4) return LQ_ERR_ARG;
-  if (!pool[i]) LQ_HIP_TRY(hipStreamCreateWithFlags(&pool[i], hipStreamNonBlocking));
-  *out = pool[i];
-  return LQ_OK;
-}
+// Extra streams for lq_error_table's interleaved sub-batches (default priority).  One process-wide pool per device:
+// a call leases what it needs and hands it back on every exit path, so the number of streams the library ever creates
+// is the largest number in use at one time (concurrent calls x (streams - 1)), whatever the number of host threads
+// that come and go.  lq_release_streams destroys the idle ones.
+struct StreamPool {
+  std::mutex mu;
+  std::vector<hipStream_t> idle[MAX_DEVICES];
+};
+static StreamPool& stream_pool() { static StreamPool p; return p; }
+
+struct StreamLease {            // also owns the event the sub-batches wait for
+  int dev = -1;
+  std::vector<hipStream_t> held;
+  hipEvent_t ready = nullptr;
+  int take(hipStream_t* out) {
+    if (dev < 0) {
+      LQ_HIP_TRY(hipGetDevice(&dev));
+      if (dev < 0 || dev >= MAX_DEVICES) { dev = -1; return LQ_ERR_HIP; }
+    }
+    StreamPool& p = stream_pool();
+    hipStream_t s = nullptr;
+    {
+      std::lock_guard<std::mutex> lock(p.mu);
+      if (!p.idle[dev].empty()) { s = p.idle[dev].back(); p.idle[dev].pop_back(); }
+    }
+    if (!s) LQ_HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+    held.push_back(s);
+    *out = s;
+    return LQ_OK;
+  }
+  ~StreamLease() {
+    if (ready) (void)hipEventDestroy(ready);
+    if (held.empty()) return;
+    StreamPool& p = stream_pool();
+    std::lock_guard<std::mutex> lock(p.mu);
+    for (hipStream_t s : held) p.idle[dev].push_back(s);
+  }
+};
 
 static int emit_factors(const Ctx& c, const float* Y, const float* B, const double* lam, float* L1, float* L2,
                         double* sigma_host) {
@@ -652,18 +725,21 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
   const float* A0; const float* Y1; const float* B1;
   LQ_TRY(first_input(c, &A0));
   LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));
-  hipEvent_t ready = nullptr;
+  StreamLease lease;             // streams go back to the pool and the event is destroyed on every return below
   if (nsub > 1) {
-    LQ_HIP_TRY(hipEventCreateWithFlags(&ready, hipEventDisableTiming));
-    LQ_HIP_TRY(hipEventRecord(ready, c.st));
+    LQ_HIP_TRY(hipEventCreateWithFlags(&lease.ready, hipEventDisableTiming));
+    LQ_HIP_TRY(hipEventRecord(lease.ready, c.st));
   }
   for (int s1 = 1; s1 < nsub; ++s1) {
     cs[s1] = c;
     cs[s1].ws = (char*)workspace + slice * s1;
-    LQ_TRY(extra_stream(s1 - 1, &cs[s1].st));
-    LQ_HIP_TRY(hipStreamWaitEvent(cs[s1].st, ready, 0));
+    LQ_TRY(lease.take(&cs[s1].st));
+    LQ_HIP_TRY(hipStreamWaitEvent(cs[s1].st, lease.ready, 0));
   }
   int rc = LQ_OK;
+#ifdef LQ_TESTING_HOOKS
+  struct Disarm { ~Disarm() { testing::capture().armed = false; } } disarm;     // a capture request serves one call
+#endif
   std::vector<double> trace((size_t)per_sub * iters);
   std::vector<int32_t> done(per_sub), best(per_sub);
   for (int c0 = 0; c0 < n_cfgs && rc == LQ_OK; c0 += batch_max) {
@@ -675,7 +751,7 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
       if (b0 >= b1) break;
       Loop& lp = loops[s1];
       lp.c = &cs[s1]; lp.cfgs = cf.data() + c0 + b0; lp.batch = b1 - b0; lp.iters = iters; lp.early_stop = early_stop;
-      lp.want_trace = err_trace != nullptr; lp.Y1 = Y1; lp.B1 = B1; lp.direct = nullptr;
+      lp.want_trace = err_trace != nullptr; lp.Y1 = Y1; lp.B1 = B1; lp.direct = nullptr; lp.cfg_base = c0 + b0;
       if ((rc = lp.begin()) != LQ_OK) break;
       ++used;
     }
@@ -695,72 +771,19 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
       }
     }
   }
-  if (ready) (void)hipEventDestroy(ready);
   return rc;
 }
 
-// ---- test hooks (include/lq_testing.h) ----------------------------------------------------------------
-int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
-                      int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
-                      int precision, void* stream) {
-  if (!X || !A || !C) return LQ_ERR_NULL;
-  if ((precision != 0 && precision != 1) || workgroups < -32768 || workgroups > 32768 || batch < 1) return LQ_ERR_ARG;
-  const size_t sA = (size_t)(mode == MODE_NT ? big : K) * lda;
-  return launch_wide_gemm(mode, l, big, K, X, ldx, (size_t)l * ldx, A, lda, sA, C, ldc, (size_t)l * ldc, batch, part,
-                          part_floats, (hipStream_t)stream, precision, workgroups);
-}
-
-size_t lq_test_wide_gemm_part_floats(int l, int workgroups) {
-  if (l % 32 != 0 || l < 32 || l > 256) return 0;
-  return gemm_part_floats(l, workgroups);
-}
-
-int lq_test_orthonormalize(float* X, int l, int64_t m, int64_t ldx, double* scratch, float* alt, void* stream) {
-  if (!X || !scratch) return LQ_ERR_NULL;
-  if (l % 32 || l < 32 || l > 256) return LQ_ERR_ARG;
-  double* G = scratch;
-  double* part = scratch + (size_t)l * l;
-  LQ_TRY(launch_gram(X, l, m, ldx, 0, part, G, 1, (hipStream_t)stream));
-  if (cholinv_supported(l) && alt) {
-    float* Cinv = reinterpret_cast<float*>(part);       // the Gram partials are dead by now
-    LQ_TRY(launch_cholinv(G, l, Cinv, 1, (hipStream_t)stream));
-    LQ_TRY(launch_wide_gemm(MODE_NN, l, ldx, l, Cinv, l, 0, X, ldx, 0, alt, ldx, 0, 1, nullptr, 0, (hipStream_t)stream));
-    LQ_HIP_TRY(hipMemcpyAsync(X, alt, (size_t)l * ldx * sizeof(float), hipMemcpyDeviceToDevice, (hipStream_t)stream));
-    return LQ_OK;
+int lq_release_streams(void) {
+  StreamPool& p = stream_pool();
+  std::lock_guard<std::mutex> lock(p.mu);
+  int rc = LQ_OK;
+  for (int dev = 0; dev < MAX_DEVICES; ++dev) {
+    for (hipStream_t st : p.idle[dev])
+      if (hipStreamDestroy(st) != hipSuccess) rc = LQ_ERR_HIP;
+    p.idle[dev].clear();
   }
-  LQ_TRY(launch_cholesky(G, l, 1, (hipStream_t)stream));
-  return launch_trsm(G, l, X, m, ldx, 0, 1, (hipStream_t)stream);
+  return rc;
 }
-
-int lq_test_sym_eig(double* G, int l, float* Ut, double* lambda, double* scratch, void* stream) {
-  if (!G || !Ut || !lambda || !scratch) return LQ_ERR_NULL;
-  if (l % 2 || l < 2 || l > 256) return LQ_ERR_ARG;
-  return launch_jacobi_eig(G, l, scratch, Ut, lambda, 1, (hipStream_t)stream);
-}
-
-int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void* stream) {
-  if (!G || !Ut || !lambda) return LQ_ERR_NULL;
-  if (!jacobi_fast_supported(l)) return LQ_ERR_ARG;
-  return launch_jacobi_fast(G, l, Ut, lambda, 1, (hipStream_t)stream);
-}
-
-int lq_test_bucket_code(int bits, float x) {
-  const int slot = bits_slot(bits);
-  if (slot < 0) return -1;
-  const HostTables& t = host_tables();
-  if (bits <= 3) {
-    int c = 0;
-    for (int i = 0; i < (1 << bits) - 1; ++i) c += x >= t.thr[slot][i];
-    return c;
-  }
-  int j = (int)std::fmaf(x, 256.0f, 256.0f);
-  if (!(std::fmaf(x, 256.0f, 256.0f) >= 0.0f)) j = 0;   // NaN and negatives as the device's conversion treats them
-  j = j < 0 ? 0 : (j > 511 ? 511 : j);
-  const int c0 = t.lut[slot][j];
-  if (bits == 4) return c0 + (x >= t.thr[slot][c0]);          // one threshold per bucket at most
-  return c0 + (x >= t.thr[slot][c0]) + (x >= t.thr[slot][c0 + 1]);
-}
-
-size_t lq_test_lds_limit(void) { return lds_limit_for_tests(); }
 
 }  // extern "C"

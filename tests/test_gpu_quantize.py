@@ -131,3 +131,20 @@ def test_scale_index_bit_stream(lq, oracle, bits, count):
     back = lq.unpack_scale_indices(packed, count, bits)
     assert np.array_equal(back.cpu().numpy(), idx)
     assert np.array_equal(oracle.unpack(want, count, bits), idx)
+
+
+@pytest.mark.parametrize("scale_bits", [2, 3, 4, 8])
+def test_scale_index_exact_halves(lq, oracle, scale_bits):
+    """Block absmax values exactly half way between two scale levels (built as in the oracle's own pin): the kernels
+    round them to the even level like the oracle, in the stand-alone quantizer and for every first-level bit width."""
+    from test_oracle_quantizer import half_way_scale_group
+    levels = (1 << (scale_bits - 1)) - 1
+    x, absmax, _ = half_way_scale_group(levels)
+    sb = 16
+    while sb < len(absmax):
+        sb *= 2
+    pad = np.zeros(sb * 16 - x.size, np.float32)             # fill the scale group with zero blocks
+    for scale in (1.0, 2.0 ** -9):
+        xx = np.concatenate([x, pad]) * np.float32(scale)
+        for bits in (2, 3, 4, 8):
+            run_pair(lq, oracle, xx, (bits, 16, sb), scale_bits, "fp32")

@@ -12,15 +12,8 @@ def env():
     import torch
     assert torch.cuda.is_available()
     from paper_2311_12023_amd import lq
-    L = lq._lib
-    vp, i64, it = C.c_void_p, C.c_int64, C.c_int
-    L.lq_test_wide_gemm.argtypes = [it, it, i64, i64, vp, i64, vp, i64, vp, i64, it, it, vp, C.c_size_t, it, vp]
-    L.lq_test_wide_gemm_part_floats.restype = C.c_size_t
-    L.lq_test_wide_gemm_part_floats.argtypes = [it, it]
-    L.lq_test_orthonormalize.argtypes = [vp, it, i64, i64, vp, vp, vp]
-    L.lq_test_sym_eig.argtypes = [vp, it, vp, vp, vp, vp]
-    L.lq_test_sym_eig_fast.argtypes = [vp, it, vp, vp, vp]
-    L.lq_test_lds_limit.restype = C.c_size_t
+    import testing_lib
+    L = testing_lib.load()
     return torch, lq, L
 
 

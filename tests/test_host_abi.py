@@ -9,6 +9,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2311_12023_amd", "liblq_hip.so")
+TEST_LIB = os.path.join(ROOT, "paper_2311_12023_amd", "liblq_hip_testing.so")
 
 
 @pytest.fixture(scope="module")
@@ -24,20 +25,26 @@ class Cfg(C.Structure):
                 ("v_dtype", C.c_int32)]
 
 
-def declared_symbols():
-    names = set()
-    for header in ("lq.h", "lq_testing.h"):
-        text = open(os.path.join(ROOT, "include", header)).read()
-        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(lq_[a-z0-9_]+)\s*\(", text))
-    return sorted(names)
+def declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lq_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(L):
-    names = declared_symbols()
+    names = declared_symbols("lq.h")
     assert len(names) >= 20
     for n in names:
-        assert hasattr(L, n), f"{n} is declared in include/ but not exported"
+        assert hasattr(L, n), f"{n} is declared in include/lq.h but not exported"
+    # the test hooks live in the testing build only, which also exports the whole product interface
+    T = C.CDLL(TEST_LIB)
+    hooks = declared_symbols("lq_testing.h")
+    assert len(hooks) >= 8
+    for n in hooks:
+        assert hasattr(T, n), f"{n} is declared in include/lq_testing.h but not exported by the testing build"
+        assert not hasattr(L, n), f"test hook {n} leaked into the product library"
+    for n in names:
+        assert hasattr(T, n)
 
 
 def test_status_strings_and_codebook(L, oracle):
@@ -164,6 +171,7 @@ def test_code_search_equals_brute_force(L, oracle, bits):
     """The search the kernels use (counting for 2/3 bits, bucket table + two comparisons for 4/8 bits),
     evaluated on the host, against the oracle's brute force: a dense sweep of [-1.001, 1.001], every float
     within 3 ulp of each threshold and of each bucket edge, and the special values."""
+    L = C.CDLL(TEST_LIB)          # the host evaluation of the code search is a hook of the testing build
     L.lq_test_bucket_code.argtypes = [C.c_int, C.c_float]
     q = oracle.codebook(bits)
     pts = [np.linspace(-1.001, 1.001, 40001, dtype=np.float32)]

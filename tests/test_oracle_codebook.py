@@ -47,11 +47,19 @@ def test_quantile_function_closed_forms(oracle):
     assert abs(oracle.norm_ppf(1 - 0.5 * (1 / 30 + 1 / 32)) - 1.8481314) < 1e-6
 
 
-def test_nf4_published_table(oracle):
-    vals = [float(l) for l in open(os.path.join(GOLD, "nf4_published_table.txt")) if l.strip() and l[0] != "#"]
-    q = oracle.codebook(4).astype(np.float64)
-    assert len(vals) == 16
-    assert np.max(np.abs(q - np.array(vals))) < 1e-6
+def test_storage_values_printed_in_the_paper(oracle):
+    """tests/golden/storage_bits_per_parameter.txt: the bits per parameter the paper prints (three decimals)."""
+    rows = [l.split("#")[0].split() for l in open(os.path.join(GOLD, "storage_bits_per_parameter.txt"))]
+    rows = [r for r in rows if r]
+    seen = 0
+    for r in rows:
+        if r[0] == "search_space":
+            assert int(r[1]) == 3 ** 5
+            continue
+        b0, b1, b2, blk, sblk, printed = int(r[0]), int(r[1]), r[2], int(r[3]), int(r[4]), r[5]
+        assert f"{oracle.storage_bits(1, oracle.config(b0, blk, sblk, b1, b2)):.3f}" == printed
+        seen += 1
+    assert seen == 2
 
 
 def test_storage_formula(oracle):

@@ -170,3 +170,40 @@ def test_eight_bit_error_is_tiny_next_to_two_bit(oracle):
         errs[bits] = np.linalg.norm(w.astype(np.float64) - oracle.dequantize(c, si, v, cfg))
     assert errs[2] > errs[3] > errs[4] > errs[8]
     assert errs[8] < 0.05 * errs[2]
+
+
+def half_way_scale_group(levels, block=16):
+    """One scale group whose block absmax values sit exactly half way between two scale levels: the group's largest
+    absmax is `levels` (so sigma = fl32(levels / levels) = 1 exactly) and the other blocks have absmax n + 1/2, all
+    exactly representable, which makes s / sigma = n + 1/2 with no rounding anywhere before the integer rounding."""
+    halves = [n + 0.5 for n in range(0, levels)]
+    absmax = [float(levels)] + halves
+    x = np.zeros((len(absmax), block), np.float32)
+    for b, s in enumerate(absmax):
+        x[b, 3] = -s if b % 2 else s          # the sign must not matter
+        x[b, 5] = 0.25 * s
+    return x.ravel(), absmax, halves
+
+
+@pytest.mark.parametrize("scale_bits", [2, 3, 4, 8])
+def test_scale_index_rounds_exact_halves_to_even(oracle, scale_bits):
+    """Integer quantization of the absmax vector (Section 2.2: round to nearest; reading: IEEE round-half-to-even):
+    n + 1/2 goes to the even neighbour, never always up and never always down."""
+    levels = (1 << (scale_bits - 1)) - 1
+    x, absmax, halves = half_way_scale_group(levels)
+    nblocks = len(absmax)
+    sb = 16
+    while sb < nblocks:
+        sb *= 2
+    codes, sidx, v, s = oracle.quantize(x, oracle.config(4, 16, sb, scale_bits, "fp32"))
+    assert v.tolist() == [float(levels)] and s.tolist() == absmax
+    want = [levels] + [int(h + 0.5) if int(h + 0.5) % 2 == 0 else int(h - 0.5) for h in halves]
+    assert want[1:4] == [0, 2, 2][:len(want) - 1]                      # 0.5 -> 0, 1.5 -> 2, 2.5 -> 2, by hand
+    assert sidx.tolist() == want
+    # the three wrong rounding rules each fail on this input
+    up = [levels] + [int(h + 0.5) for h in halves]
+    down = [levels] + [int(h - 0.5) for h in halves]
+    assert sidx.tolist() != up and (levels < 3 or sidx.tolist() != down)      # with one level only 1/2 -> 0 exists
+    # scaling the whole group by a power of two keeps every ratio an exact half
+    _, sidx2, v2, _ = oracle.quantize(x * np.float32(2.0 ** -9), oracle.config(4, 16, sb, scale_bits, "fp32"))
+    assert sidx2.tolist() == want and v2.tolist() == [levels * 2.0 ** -9]
