@@ -1,17 +1,27 @@
 #!/usr/bin/env python3
-"""Benchmark: LQ error-table sweep of one LLaMA-2-7B-shaped layer on one MI355X.
+"""Benchmarks of the LQ decomposition path on one MI355X.  Every mode prints one JSON line.
 
-One step = the whole hot path over the workload: for each of the 7 weight matrices of the layer
-(4x 4096x4096, 2x 4096x11008, 1x 11008x4096; synthetic, see paper_2311_12023_amd/gen.py) one
-lq_error_table call over the 36 configurations bits {2,3,4,8} x B0 {16,32,64} x B1 {16,64,256}, rank 64,
-10 LQ iterations each.  Inputs are resident in HBM before the timed region.  Prints one JSON line.
+--workload sweep (default): one step = the whole hot path over one of the five benchmark workloads (--config):
+  1  one 768 x 768 matrix, rank 8, NF3 B0 = 64 B1 = 256, 5 LQ iterations (one lq_decompose call)
+  2  RoBERTa-Large-shaped stack, 24 blocks x (4x 1024x1024, 1024x4096, 4096x1024), rank 8, 9 configurations
+     (bits 2/3/4 x B0 16/32/64, B1 = 256), 10 iterations: one lq_error_table call per matrix
+  3  (default, the headline metric) one LLaMA-2-7B-shaped block (4x 4096x4096, 2x 4096x11008, 11008x4096), rank 64,
+     36 configurations (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256), 10 iterations
+  4  one Fisher-weighted 4096 x 11008 matrix, rank 64, NF3 64/256, 10 iterations (one weighted lq_decompose call)
+  5  one LLaMA-2-70B-shaped block (2x 8192x8192, 2x 8192x1024, 2x 8192x28672, 28672x8192), rank 64, 36 configurations
+--workload quant: the other half of the metric, lq_nf_quantize / lq_nf_dequantize in algorithmic GB/s over the
+  matrix shapes of workloads 3 and 5, buffers rotated so that nothing stays in the 256 MB Infinity Cache.
+--workload matmul: the consumer of a decomposition, Y = X (Q + L1 L2) with just-in-time dequantization.
+Inputs are synthetic (paper_2311_12023_amd/gen.py) and resident in HBM before the timed region.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import queue
 import sys
+import threading
 import time
 
 import numpy as np
@@ -19,38 +29,28 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-RANK = 64
-ITERS = 10
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
+ROBERTA_GRID = [(b, b0, 256) for b in (2, 3, 4) for b0 in (16, 32, 64)]
+NF3_DEFAULT = (3, 64, 256)
 
-def cpu_baseline(first_matrix: np.ndarray) -> dict:
-    """The oracle, as it stands, timed on a bounded sample of the workload on the host cores."""
-    from oracle import lq_oracle as O
-    O.build()
-    sample = np.ascontiguousarray(first_matrix[:1024, :1024])
-    cfg = O.config(3, 64, 256)
-    t0 = time.perf_counter()
-    O.lq(sample, RANK, cfg, ITERS)
-    dt = time.perf_counter() - t0
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "llama7b_layer_sweep_hbm_traffic.md")
+FORWARD_TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "llama7b_layer_forward_kernel_stats.md")
+QUANT_TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "nf_quantize_dequantize_kernel_stats.md")
+
+
+def host_cores() -> int:
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
         cores = os.cpu_count() or 1
-    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
-    return {"value": 1.0 / dt, "unit": "matrix-configs/s on the sample", "cores": cores, "kind": "oracle",
-            "sample": "one 1024x1024 corner of matrix 0, rank 64, NF3 B0=64 B1=256, 10 iterations "
-                      f"(exact Jacobi SVD each iteration); {dt:.1f} s. A full 4096x4096 cell costs about "
-                      "4^3 = 64 times as much."}
-
-
-TRAFFIC_TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "llama7b_layer_sweep_hbm_traffic.md")
-FORWARD_TRAFFIC_TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "llama7b_layer_forward_kernel_stats.md")
+    return min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
 
 
 def measured_traffic(name: str, table: str | None = None):
-    """HBM-side bytes per launch of a kernel class (fetch + write) from the committed counter summary, averaged over
+    """HBM-side bytes per launch of a kernel class (fetch + write) from a committed counter summary, averaged over
     the class's template variants weighted by launches; None when the summary does not list the kernel."""
     try:
         lines = open(table or TRAFFIC_TABLE).read().splitlines()
@@ -80,8 +80,17 @@ def measured_traffic(name: str, table: str | None = None):
     return tot / n if n else None
 
 
-def roofline_of(name: str, ms: float, launches: int, work: float) -> dict:
-    """Roofline entry for one kernel class from its summed HIP-event time and algorithmic work."""
+# Kernel classes with a roofline of their own.  Everything else the library launches (Gram matrices, Cholesky, Jacobi,
+# fix-ups, packing) is a short or single-workgroup kernel bound by latency; those are listed with their time only.
+STREAMING = ("lowrank_blockquant_kernel", "residual_kernel", "scalequant_error_kernel", "quantize_fused_kernel",
+             "dequant_kernel")
+
+
+def roofline_of(name: str, ms: float, launches: int, work: float) -> dict | None:
+    """Roofline entry of one kernel class from its summed HIP-event time and algorithmic work (what the operation
+    has to move or multiply, not what the kernel happened to move)."""
+    if ms <= 0 or launches <= 0:
+        return None
     sec = ms * 1e-3
     common = {"kernel": name, "traffic": None, "launches": launches, "avg_us": 1e3 * ms / launches}
     if name.startswith("wide_gemm_kernel"):
@@ -90,25 +99,180 @@ def roofline_of(name: str, ms: float, launches: int, work: float) -> dict:
             ach = work / sec / 1e12
             return {**common, "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / PEAK_FP32_MFMA_TFLOPS}
-        # split-bf16 mode: three bf16 MFMAs per product leave the kernel bound by streaming A (4 B per element,
-        # 2*l flop per element)
+        # split mode: every product is three bf16 MFMAs; the operand A (4 B per element, 2 l flop per element) is
+        # streamed once, which is what bounds the kernel
         ach = work / (2.0 * 32 * lt) * 4.0 / sec / 1e9
         return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                "algorithmic_tflops": work / sec / 1e12}
-    if name.startswith("lowrank_blockquant"):   # (2r + 10) flop per weight, ALU + MFMA; W is read from HBM once per batch
-        ach = work / sec / 1e12
-        return {**common, "bound": "alu", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_FP32_MFMA_TFLOPS}
-    ach = work / sec / 1e9
-    return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+                "algorithmic_tflops": work / sec / 1e12,
+                "executed_bf16_mfma_frac": 3.0 * work / sec / 1e12 / PEAK_BF16_MFMA_TFLOPS}
+    if name.split("+")[0] in STREAMING:
+        ach = work / sec / 1e9
+        return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS}
+    return None
 
 
-PEAK_BF16_MFMA_TFLOPS = 2500.0
+def dominant_roofline(prof: dict):
+    """-> (roofline of the class with the largest summed time among those that have one, share of the summed kernel
+    time spent in latency-bound classes)."""
+    total = sum(v[0] for v in prof.values())
+    best = None
+    lat = 0.0
+    for name, (ms, n, work) in prof.items():
+        r = roofline_of(name, ms, n, work)
+        if r is None:
+            lat += ms
+        elif best is None or ms > best[0]:
+            best = (ms, r)
+    return (best[1] if best else None), (lat / total if total > 0 else 0.0)
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# CPU baselines: the oracle as it stands on a bounded sample
+def cpu_baseline_lq(sample: np.ndarray, rank: int, cfg_tuple, iters: int, what: str, row_w=None, col_w=None) -> dict:
+    from oracle import lq_oracle as O
+    O.build()
+    t0 = time.perf_counter()
+    O.lq(sample, rank, O.config(*cfg_tuple), iters, row_w=row_w, col_w=col_w)
+    dt = time.perf_counter() - t0
+    return {"value": 1.0 / dt, "unit": "matrix-configs/s on the sample", "cores": host_cores(), "kind": "oracle",
+            "sample": f"{what}: {dt:.1f} s"}
+
+
+def cpu_baseline_quant(sample: np.ndarray, cfg_tuple) -> dict:
+    from oracle import lq_oracle as O
+    O.build()
+    cfg = O.config(*cfg_tuple)
+    flat = np.ascontiguousarray(sample.ravel())
+    t0 = time.perf_counter()
+    codes, sidx, v, _ = O.quantize(flat, cfg)
+    t1 = time.perf_counter()
+    O.dequantize(codes, sidx, v, cfg)
+    t2 = time.perf_counter()
+    b = quant_bytes(flat.size, cfg_tuple)
+    return {"value": 2.0 * b / (t2 - t0) / 1e9, "unit": "GB/s", "cores": host_cores(), "kind": "oracle",
+            "sample": f"quantize + dequantize of one {sample.shape[0]}x{sample.shape[1]} matrix, NF{cfg_tuple[0]} "
+                      f"B0={cfg_tuple[1]} B1={cfg_tuple[2]} (brute-force nearest code): {t1 - t0:.2f} s + {t2 - t1:.2f} s"}
+
+
+def quant_bytes(n: int, cfg_tuple) -> float:
+    """Algorithmic bytes of one Quantize (or Dequantize) of n weights: fp32 on one side, codes, one byte per block scale
+    and one fp32 per scale group on the other."""
+    b0, blk, sblk = cfg_tuple[:3]
+    return n * (4.0 + b0 / 8.0 + 1.0 / blk + 4.0 / (blk * sblk))
+
+
+# ------------------------------------------------------------------------------------------------------------------
+def bench_quant(args, torch, gen, lq, dev) -> int:
+    """lq_nf_quantize and lq_nf_dequantize over the distinct matrix shapes of workloads 3 and 5 for the corners of the
+    configuration grid.  One step = every (shape, configuration) cell quantized and dequantized once."""
+    shapes = [(3, 0, "4096x4096"), (3, 4, "4096x11008"), (5, 0, "8192x8192"), (5, 4, "8192x28672")]
+    if args.matrices < len(shapes):
+        shapes = shapes[:args.matrices]
+    grid = [(2, 16, 16), (2, 64, 256), NF3_DEFAULT, (4, 64, 256), (8, 16, 16), (8, 64, 256)]
+    rotate_bytes = 1.5e9            # every buffer class cycles through at least this much memory
+    cells = []
+    host0 = None
+    for wl, idx, label in shapes:
+        w = gen.workload_matrix(wl, idx)
+        if host0 is None:
+            host0 = w
+        n = w.size
+        copies = max(2, int(np.ceil(rotate_bytes / (4.0 * n))))
+        xs = [torch.from_numpy(w).to(dev).reshape(-1)]
+        for _ in range(copies - 1):
+            xs.append(xs[0].clone())
+        outs = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(copies)]
+        for g in grid:
+            cfg = lq.config(*g)
+            packs = [lq.nf_quantize(xs[0], cfg) for _ in range(copies)]
+            cells.append(dict(label=label, n=n, g=g, cfg=cfg, xs=xs, outs=outs, packs=packs, copies=copies))
+        del w
+    torch.cuda.synchronize()
+    counter = [0]
+
+    def step():
+        counter[0] += 1
+        for c in cells:
+            i = counter[0] % c["copies"]
+            lq.nf_quantize(c["xs"][i], c["cfg"], out=c["packs"][i])
+        for c in cells:
+            i = counter[0] % c["copies"]
+            lq.nf_dequantize(*c["packs"][i], c["n"], c["cfg"], out=c["outs"][i])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    total_bytes = 2.0 * sum(quant_bytes(c["n"], c["g"]) for c in cells)
+    # per-cell and per-kernel durations: each call bracketed by events on its stream, in passes of their own
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    per_cell = []
+    for c in cells:
+        tq = td = 0.0
+        for _ in range(args.steps):
+            counter[0] += 1
+            i = counter[0] % c["copies"]
+            a, b, e = ev(), ev(), ev()
+            a.record()
+            lq.nf_quantize(c["xs"][i], c["cfg"], out=c["packs"][i])
+            b.record()
+            lq.nf_dequantize(*c["packs"][i], c["n"], c["cfg"], out=c["outs"][i])
+            e.record()
+            torch.cuda.synchronize()
+            tq += a.elapsed_time(b)
+            td += b.elapsed_time(e)
+        by = quant_bytes(c["n"], c["g"])
+        per_cell.append({"shape": c["label"], "config": list(c["g"]), "bytes": by,
+                         "quantize_us": 1e3 * tq / args.steps, "dequantize_us": 1e3 * td / args.steps,
+                         "quantize_GBs": by / (tq / args.steps * 1e-3) / 1e9,
+                         "dequantize_GBs": by / (td / args.steps * 1e-3) / 1e9})
+    lq.profile_enable(True)
+    lq.profile_reset()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = lq.profile_read()
+    lq.profile_enable(False)
+    roofs = {n: roofline_of(n, *v) for n, v in prof.items()}
+    roofs = {n: r for n, r in roofs.items() if r}
+    dom = max(roofs.values(), key=lambda r: r["avg_us"] * r["launches"]) if roofs else None
+    if dom is not None and len(shapes) == 4:
+        dom["traffic"] = measured_traffic(dom["kernel"], QUANT_TRAFFIC_TABLE)
+    big = [p for p in per_cell if p["shape"] != "4096x4096"]
+    out = {"metric": "NF quant HBM GB/s (lq_nf_quantize + lq_nf_dequantize, algorithmic bytes)",
+           "value": total_bytes * args.steps / sec / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": 1e3 * sec / args.steps, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "Quantize and Dequantize (Section 3.2) of " + ", ".join(s[2] for s in shapes)
+                                  + " matrices (workload 3 and 5 shapes) for " + ", ".join(f"NF{g[0]} {g[1]}/{g[2]}" for g in grid),
+                      "cells": len(cells), "rotation": "each buffer class cycles through >= 1.5 GB"},
+           "roofline": dom,
+           "roofline_note": "algorithmic bytes per call = n (4 + b0/8 + 1/B0 + 4/(B0 B1)); roofline = the kernel class "
+                            "with the larger summed time, durations from a pass of the same steps with every launch "
+                            "bracketed by events on its stream; value from the pass without brackets",
+           "roofline_kernels": roofs,
+           "quantize_frac_of_hbm_min_max": [min(p["quantize_GBs"] for p in big) / PEAK_HBM_GBS,
+                                            max(p["quantize_GBs"] for p in big) / PEAK_HBM_GBS] if big else None,
+           "dequantize_frac_of_hbm_min_max": [min(p["dequantize_GBs"] for p in big) / PEAK_HBM_GBS,
+                                              max(p["dequantize_GBs"] for p in big) / PEAK_HBM_GBS] if big else None,
+           "cells": per_cell}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_quant(host0, NF3_DEFAULT)
+    print(json.dumps(out))
+    return 0
+
+
+# ------------------------------------------------------------------------------------------------------------------
 NF4_DOUBLE_QUANT = (4, 64, 256, 8, "bf16")
 
 
 def bench_matmul(args, torch, gen, lq, dev) -> int:
     """Forward products Y = X (Q + L1 L2) of one LLaMA-2-7B-shaped layer; one step = all 7 matrices."""
+    RANK = 64
     shapes = gen.LLAMA2_7B_LAYER[:args.matrices]
     cfg = lq.config(*NF4_DOUBLE_QUANT)
     m = args.tokens
@@ -201,20 +365,222 @@ def bench_matmul(args, torch, gen, lq, dev) -> int:
     return 0
 
 
+# ------------------------------------------------------------------------------------------------------------------
+class Workers:
+    """Host threads that live for the whole benchmark, each with its own stream and workspace; run(jobs) hands the
+    jobs out largest first and returns when all are done."""
+
+    def __init__(self, torch, dev, workspaces):
+        self.torch = torch
+        self.n = len(workspaces)
+        self.workspaces = workspaces
+        self.streams = [torch.cuda.Stream(device=dev) for _ in workspaces]
+        self.todo: queue.Queue = queue.Queue()
+        self.done: queue.Queue = queue.Queue()
+        self.threads = [threading.Thread(target=self._loop, args=(t,), daemon=True) for t in range(self.n)]
+        for th in self.threads:
+            th.start()
+
+    def _loop(self, tid):
+        with self.torch.cuda.stream(self.streams[tid]):
+            while True:
+                job = self.todo.get()
+                if job is None:
+                    return
+                key, fn, limit = job
+                if tid >= limit:                 # this pass runs on fewer threads: leave the job to them
+                    self.todo.put(job)
+                    time.sleep(0.001)
+                    continue
+                try:
+                    self.done.put((key, fn(self.workspaces[tid]), None))
+                except Exception as exc:     # surfaced by run()
+                    self.done.put((key, None, exc))
+
+    def run(self, jobs, threads=None):
+        limit = self.n if threads is None else max(1, min(threads, self.n))
+        for key, fn in jobs:
+            self.todo.put((key, fn, limit))
+        out = {}
+        for _ in jobs:
+            key, res, exc = self.done.get()
+            if exc is not None:
+                raise exc
+            out[key] = res
+        return out
+
+    def close(self):
+        for _ in self.threads:
+            self.todo.put(None)
+        for th in self.threads:
+            th.join()
+
+
+def bench_sweep(args, torch, gen, lq, dev) -> int:
+    wl = args.config
+    serial_params = lq.SvdParams(streams=1, gemm_mode=args.gemm_mode)
+    params = lq.SvdParams(streams=args.streams, gemm_mode=args.gemm_mode)
+    if wl in (1, 4):
+        # one matrix, one configuration: a single lq_decompose call per step
+        rank, iters = (8, 5) if wl == 1 else (64, 10)
+        host = gen.workload_matrix(wl, 0)
+        w = torch.from_numpy(host).to(dev)
+        rw = cw = None
+        if wl == 4:
+            f = torch.from_numpy(gen.fisher_matrix(*host.shape, gen.matrix_seed(4, 1)).astype(np.float32)).to(dev)
+            rw, cw = lq.fisher_row_col(f)       # set-up, not timed (Section 3.3: F comes from calibration gradients)
+            del f
+        cfg = lq.config(*NF3_DEFAULT)
+        ws = torch.empty(lq._lib.lq_decompose_workspace_bytes(host.shape[0], host.shape[1], rank, None) + 256,
+                         dtype=torch.uint8, device=dev)
+        res = [None]
+
+        def step(profiled_serial=False):
+            res[0] = lq.decompose(w, rank, cfg, iters, row_w=rw, col_w=cw, seed=1, workspace=ws,
+                                  params=serial_params if profiled_serial else None)
+        cells, n_mats, n_cfgs, nthreads = 1, 1, 1, 1
+        label = ("one 768x768 matrix, rank 8, NF3 B0=64 B1=256, 5 LQ iterations" if wl == 1 else
+                 "one Fisher-weighted 4096x11008 matrix, rank 64, NF3 B0=64 B1=256, 10 LQ iterations (weighted error)")
+        checksum = lambda: float(res[0]["err"])
+        workers = None
+    else:
+        rank, iters = (8, 10) if wl == 2 else (64, 10)
+        if wl == 2:
+            count, grid = 24 * len(gen.ROBERTA_LARGE_LAYER), ROBERTA_GRID
+        elif wl == 3:
+            count, grid = len(gen.LLAMA2_7B_LAYER), (gen.paper_config_grid() if args.grid == "paper243" else gen.config_grid())
+        else:
+            count, grid = len(gen.LLAMA2_70B_LAYER), gen.config_grid()
+        count = min(count, args.matrices)
+        cfgs = [lq.config(*g) for g in grid]
+        host0 = gen.workload_matrix(wl, 0)
+        mats = [torch.from_numpy(host0 if i == 0 else gen.workload_matrix(wl, i)).to(dev) for i in range(count)]
+        host = host0
+        shapes = {tuple(m.shape) for m in mats}
+        default_overlap = {2: 7, 3: 7, 5: 2}[wl]
+        nthreads = max(1, min(args.overlap or default_overlap, len(mats)))
+        # one workspace per concurrent matrix, each large enough for every shape of the workload
+        need = max(lq._lib.lq_error_table_workspace_bytes(d, k, rank, len(cfgs), lq._pp(params)) for d, k in shapes)
+        workers = Workers(torch, dev, [torch.empty(need + 256, dtype=torch.uint8, device=dev) for _ in range(nthreads)])
+        order = sorted(range(len(mats)), key=lambda i: -mats[i].numel())      # largest first
+        res = [None]
+
+        def step(profiled_serial=False):
+            p = serial_params if profiled_serial else params
+            jobs = [(i, (lambda ws, i=i: lq.error_table(mats[i], rank, cfgs, iters, seed=1, params=p, workspace=ws)))
+                    for i in order]
+            res[0] = workers.run(jobs, threads=1 if profiled_serial else None)
+        n_mats, n_cfgs = len(mats), len(cfgs)
+        cells = n_mats * n_cfgs
+        shape_text = {2: "RoBERTa-Large-shaped stack (24 blocks x (4x1024x1024, 1024x4096, 4096x1024)), rank 8, 9 configs "
+                         "(bits 2/3/4 x B0 16/32/64, B1 256)",
+                      3: "LLaMA-2-7B-shaped layer (4x4096x4096, 2x4096x11008, 1x11008x4096), rank 64, "
+                         + ("36 configs (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256)" if args.grid == "sweep36" else
+                            "243 configs (b0, b1 in 2/3/4 x b2 in bf16/fp16/fp32 x B0 16/32/64 x B1 16/64/256)"),
+                      5: "LLaMA-2-70B-shaped layer (2x8192x8192, 2x8192x1024, 2x8192x28672, 1x28672x8192), rank 64, "
+                         "36 configs (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256)"}[wl]
+        label = shape_text + ", 10 LQ iterations"
+        checksum = lambda: float(sum(np.sqrt(res[0][i][0]).sum() for i in range(len(mats))))
+
+    torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 2.0, out=dst)          # one elementwise kernel: 1 GiB in, 1 GiB out
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    check = checksum()
+    # Kernel durations come from one more step with every launch bracketed by events on its stream, run one matrix at a
+    # time on one stream so that every kernel has the GPU to itself (in the timed region up to four kernels of different
+    # matrices share the compute units, and a bracket there measures the sharing, not the kernel).
+    prof = {}
+    if not args.no_profile:
+        lq.profile_enable(True)
+        lq.profile_reset()
+        t1 = time.perf_counter()
+        step(profiled_serial=True)
+        torch.cuda.synchronize()
+        serial_ms = 1e3 * (time.perf_counter() - t1)
+        prof = lq.profile_read()
+        lq.profile_enable(False)
+    if workers is not None:
+        workers.close()
+    lq.release_streams()
+
+    roof, latency_share = dominant_roofline(prof) if prof else (None, None)
+    if roof is not None and wl == 3 and n_mats == 7 and args.grid == "sweep36":
+        roof["traffic"] = measured_traffic(roof["kernel"])
+    split = args.gemm_mode != 1
+    line = {
+        "metric": "matrix-configs decomposed/sec" + (" (LLaMA-2-7B layer sweep)" if wl == 3 else f" (workload {wl})"),
+        "value": cells * args.steps / dt, "unit": "matrix-configs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (large products as three bf16 MFMAs on hi/lo splits, fp32 accumulation)" if split else "f32",
+        "data": "synthetic",
+        "config": {"workload": label, "baseline_config": wl, "matrices": n_mats, "configs": n_cfgs, "iters": iters,
+                   "rank": rank, "concurrent_matrices": nthreads},
+        "roofline": roof,
+        "roofline_note": "the kernel class with the largest summed duration among the machine-filling classes (large "
+                         "GEMMs against HBM for the operand they stream, with the executed bf16 MFMA work beside it; the "
+                         "quantize / residual classes against HBM with their algorithmic bytes).  Durations are from "
+                         "one extra step run one matrix at a time on one stream with every launch bracketed by events "
+                         "(the kernel has the GPU to itself, as in the committed rocprofv3 table of that mode); value "
+                         "and ms_per_step are from the steps without brackets.",
+        "error_checksum": check,
+    }
+    if prof:
+        line["serial_profiled_step_ms"] = serial_ms
+        line["latency_bound_kernel_share"] = latency_share
+        line["roofline_kernels"] = {n: r for n, r in ((n, roofline_of(n, *v)) for n, v in prof.items()) if r and v[0] > 0.5}
+        line["kernels"] = {n: {"ms": round(v[0], 3), "launches": v[1]} for n, v in prof.items()}
+    if not args.no_cpu_baseline:
+        if wl == 1:
+            line["cpu_baseline"] = cpu_baseline_lq(host, 8, NF3_DEFAULT, 5, "the whole workload (768x768, rank 8, NF3 64/256, "
+                                                   "5 iterations, exact Jacobi SVD each)")
+        elif wl == 2:
+            line["cpu_baseline"] = cpu_baseline_lq(host, 8, NF3_DEFAULT, 10, "one cell of the table: matrix 0 (1024x1024), rank 8, "
+                                                   "NF3 B0=64 B1=256, 10 iterations (exact Jacobi SVD each); the workload has 1296 "
+                                                   "cells, a third of them on four times larger matrices")
+        elif wl == 4:
+            s = np.ascontiguousarray(host[:768, :1024])
+            line["cpu_baseline"] = cpu_baseline_lq(s, 64, NF3_DEFAULT, 10, "the 768x1024 corner of the matrix, rank 64, NF3 64/256, "
+                                                   "10 weighted iterations (exact Jacobi SVD each); the full matrix is 57 times "
+                                                   "larger and its SVD cost grows with the 1.5th power of that",
+                                                   row_w=rw.cpu().numpy()[:768], col_w=cw.cpu().numpy()[:1024])
+        else:
+            s = np.ascontiguousarray(host[:1024, :1024])
+            line["cpu_baseline"] = cpu_baseline_lq(s, 64, NF3_DEFAULT, 10, "one 1024x1024 corner of matrix 0, rank 64, NF3 B0=64 "
+                                                   "B1=256, 10 iterations (exact Jacobi SVD each); a full 4096x4096 cell costs "
+                                                   "about 4^3 = 64 times as much")
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 2 for the sweep, 100 forward steps)")
-    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default: 1 / 20)")
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default depends on the workload)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--matrices", type=int, default=7, help="use only the first N matrices of the layer (debugging)")
-    ap.add_argument("--no-isolated", action="store_true",
-                    help="skip the extra non-overlapped profiled step that gives per-kernel rooflines without contention")
-    ap.add_argument("--overlap", type=int, default=7,
-                    help="matrices decomposed concurrently (host threads, each with its own stream and workspace)")
-    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event timing")
+    ap.add_argument("--config", type=int, choices=(1, 2, 3, 4, 5), default=3,
+                    help="benchmark workload of --workload sweep (3 = the headline LLaMA-2-7B layer sweep)")
+    ap.add_argument("--matrices", type=int, default=1 << 20, help="use only the first N matrices of the workload (debugging)")
+    ap.add_argument("--overlap", type=int, default=0,
+                    help="matrices decomposed concurrently (host threads, each with its own stream and workspace); "
+                         "0 = 7 for workloads 2 and 3, 2 for workload 5 (52 GB of workspace per 8192x28672 matrix)")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event pass")
     ap.add_argument("--grid", choices=("sweep36", "paper243"), default="sweep36",
-                    help="configuration grid: the 36-cell sweep the headline metric is quoted on, or the paper's own "
+                    help="workload 3 only: the 36-cell sweep the headline metric is quoted on, or the paper's own "
                          "243-cell search space (b0, b1 in {2,3,4}, b2 in {bf16,fp16,fp32}, B0 in {16,32,64}, "
                          "B1 in {16,64,256})")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -225,10 +591,7 @@ def main() -> int:
                     help="lq_svd_params.streams: interleaved sub-batches per matrix (0 = library default, 3, which is best "
                          "for one matrix at a time; with every matrix of the layer in flight 2 is enough)")
     ap.add_argument("--gemm-mode", type=int, default=0, help="lq_svd_params.gemm_mode (0 = library default)")
-    ap.add_argument("--workload", choices=("sweep", "matmul"), default="sweep",
-                    help="sweep: the error-table sweep (the headline metric).  matmul: the consumer of a decomposition, "
-                         "Y = X (Q + L1 L2) with just-in-time dequantization, for the 7 matrices of the layer at "
-                         "--tokens rows of X (NF4 with double quantization, rank 64); prints its own JSON line")
+    ap.add_argument("--workload", choices=("sweep", "quant", "matmul"), default="sweep")
     ap.add_argument("--tokens", type=int, default=4096, help="rows of X for --workload matmul")
     ap.add_argument("--precision", type=int, default=0, help="lq_matmul precision for --workload matmul (0 split, 1 bf16)")
     args = ap.parse_args()
@@ -236,10 +599,10 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sweep shards over GPUs by "
               "matrix without any collective, see DESIGN.md).", file=sys.stderr)
         return 2
-    if args.steps is None:          # a forward step is a few milliseconds, a sweep step more than half a second
-        args.steps = 100 if args.workload == "matmul" else 2
+    if args.steps is None:
+        args.steps = {"matmul": 100, "quant": 10}.get(args.workload) or {1: 50, 2: 2, 3: 2, 4: 5, 5: 1}[args.config]
     if args.warmup is None:
-        args.warmup = 20 if args.workload == "matmul" else 1
+        args.warmup = {"matmul": 20, "quant": 2}.get(args.workload) or {1: 5, 2: 1, 3: 1, 4: 1, 5: 1}[args.config]
 
     import torch
     from paper_2311_12023_amd import gen, lq
@@ -247,119 +610,12 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
     if args.workload == "matmul":
+        if args.matrices > 7:
+            args.matrices = 7
         return bench_matmul(args, torch, gen, lq, dev)
-    cfgs = [lq.config(*g) for g in (gen.paper_config_grid() if args.grid == "paper243" else gen.config_grid())]
-    params = lq.SvdParams(streams=args.streams, gemm_mode=args.gemm_mode)
-    host = [gen.workload_matrix(3, i) for i in range(min(args.matrices, len(gen.LLAMA2_7B_LAYER)))]
-    mats = [torch.from_numpy(w).to(dev) for w in host]
-    # one workspace per concurrent matrix, each large enough for every shape of the layer
-    shapes = {tuple(m.shape) for m in mats}
-    nthreads = max(1, min(args.overlap, len(mats)))
-    workspaces = [max((lq.error_table_workspace(d, k, RANK, len(cfgs), params, device=dev) for d, k in shapes),
-                      key=lambda t: t.numel()) for _ in range(nthreads)]
-    streams = [torch.cuda.Stream(device=dev) for _ in range(nthreads)]
-    order = sorted(range(len(mats)), key=lambda i: -mats[i].numel())      # largest first
-    torch.cuda.synchronize()
-    if args.calibration_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        torch.mul(src, 2.0, out=dst)          # one elementwise kernel: 1 GiB in, 1 GiB out
-        torch.cuda.synchronize()
-        del src, dst
-
-    import queue
-    import threading
-
-    def step(nthreads=nthreads, params=params):
-        """One pass of the whole hot path over the layer: every matrix, every configuration."""
-        out = [None] * len(mats)
-        todo = queue.SimpleQueue()
-        for i in order:
-            todo.put(i)
-        errors = []
-
-        def worker(tid):
-            try:
-                with torch.cuda.stream(streams[tid]):
-                    while True:
-                        try:
-                            i = todo.get_nowait()
-                        except queue.Empty:
-                            return
-                        out[i] = lq.error_table(mats[i], RANK, cfgs, ITERS, seed=1, params=params,
-                                                workspace=workspaces[tid])
-            except Exception as exc:      # surfaced after the join
-                errors.append(exc)
-
-        threads = [threading.Thread(target=worker, args=(t,)) for t in range(nthreads)]
-        for th in threads:
-            th.start()
-        for th in threads:
-            th.join()
-        if errors:
-            raise errors[0]
-        return out
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if not args.no_profile:
-        lq.profile_enable(True)
-        lq.profile_reset()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        res = step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = lq.profile_read() if not args.no_profile else {}
-    lq.profile_enable(False)
-    # Per-kernel durations in the timed region include contention between concurrent matrices and streams.  One more
-    # pass, one matrix at a time on one stream, gives each kernel's duration with the GPU to itself.
-    prof_iso = {}
-    if not (args.no_isolated or args.no_profile):
-        lq.profile_enable(True)
-        lq.profile_reset()
-        step(nthreads=1, params=lq.SvdParams(streams=1, gemm_mode=args.gemm_mode))
-        torch.cuda.synchronize()
-        prof_iso = lq.profile_read()
-        lq.profile_enable(False)
-
-    cells = len(mats) * len(cfgs)
-    value = cells * args.steps / dt
-    # dominant kernel = largest summed event time
-    kernels = {}
-    for name, (ms, n, work) in prof.items():
-        kernels[name] = {"ms_total": round(ms, 3), "launches": n, "avg_us": round(1e3 * ms / n, 2),
-                         "work_per_s": work / (ms * 1e-3) if ms > 0 else 0.0}
-    roof = None
-    if prof:
-        dname, (dms, dn, dwork) = max(prof.items(), key=lambda kv: kv[1][0])
-        roof = roofline_of(dname, dms, dn, dwork)
-        # counter-measured traffic per launch; the summary was taken in the default launch configuration
-        if len(mats) == len(gen.LLAMA2_7B_LAYER) and args.streams == 2:
-            roof["traffic"] = measured_traffic(dname)
-    line = {
-        "metric": "matrix-configs decomposed/sec (LLaMA-2-7B layer sweep)", "value": value, "unit": "matrix-configs/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "LLaMA-2-7B-shaped layer (4x4096x4096, 2x4096x11008, 1x11008x4096), rank 64, "
-                               + ("36 configs (bits 2/3/4/8 x B0 16/32/64 x B1 16/64/256)" if args.grid == "sweep36" else
-                                  "243 configs (b0, b1 in 2/3/4 x b2 in bf16/fp16/fp32 x B0 16/32/64 x B1 16/64/256)")
-                               + ", 10 LQ iterations",
-                   "matrices": len(mats), "configs": len(cfgs), "iters": ITERS, "rank": RANK,
-                   "concurrent_matrices": nthreads},
-        "roofline": roof,
-        "roofline_note": "dominant kernel (largest summed HIP-event time) of the timed region; its launches overlap "
-                         "with other streams there, see roofline_isolated for the same kernels run alone",
-        "roofline_isolated": {n: roofline_of(n, ms, cnt, wk) for n, (ms, cnt, wk) in prof_iso.items()
-                              if n.startswith(("wide_gemm", "lowrank", "residual")) and ms > 1.0},
-        "kernels": kernels,
-        "error_table_checksum": float(sum(np.sqrt(e).sum() for e, _ in res)),
-    }
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(host[0])
-    print(json.dumps(line))
-    return 0
+    if args.workload == "quant":
+        return bench_quant(args, torch, gen, lq, dev)
+    return bench_sweep(args, torch, gen, lq, dev)
 
 
 if __name__ == "__main__":

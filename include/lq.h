@@ -80,6 +80,10 @@ typedef struct {
  *   warm_power    subspace iterations per later LQ iteration.  Default 2.
  *   warm_power_2  subspace iterations of the second LQ iteration (the one whose input differs most
  *                 from its warm start).  Default 3.
+ *   warm_power_coarse  subspace iterations per later LQ iteration (the second included) for configurations whose scale
+ *                 quantizer has a single level (b1 = 2: every block scale is 0 or v), whose residual W - Q changes far more
+ *                 from one iteration to the next; used when larger than warm_power / warm_power_2.  lq_error_table
+ *                 processes such configurations first, in batches of their own.  Default 4.
  *   max_batch     lq_error_table advances up to this many configurations in lock step (more
  *                 workspace, better GPU occupancy).  Default 36.
  *   streams       lq_error_table splits a batch over this many HIP streams (1..4, all default priority, the
@@ -104,6 +108,7 @@ typedef struct {
   int32_t gemm_mode;
   int32_t streams;
   int32_t init_quantized;
+  int32_t warm_power_coarse;
 } lq_svd_params;
 
 const char* lq_status_string(int status);
@@ -264,7 +269,7 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
  * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the library
  * is bracketed by two HIP events on the launch stream; lq_profile_read synchronizes the device and returns,
  * for one kernel class, the summed event time, the number of launches and the summed algorithmic work
- * (flops for the GEMM classes and for lowrank_blockquant_kernel, bytes otherwise) since the last lq_profile_reset.  Class names are the
+ * (flops for the GEMM classes, bytes otherwise: what the operation has to move, not what the kernel moved) since the last lq_profile_reset.  Class names are the
  * kernels' names.  Not thread-safe against concurrent library calls.
  */
 int lq_profile_enable(int on);

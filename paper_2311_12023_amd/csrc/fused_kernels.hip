@@ -341,7 +341,10 @@ int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st)
   const int64_t tiles = (int64_t)tiles_n * ((a.d + TM - 1) / TM);
   if ((tiles + 7) / 8 * 8 * a.batch >= (1ll << 31)) return LQ_ERR_SHAPE;
   const dim3 grid((unsigned)((tiles + 7) / 8 * 8 * a.batch));
-  prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st, (double)a.d * a.k * (2.0 * a.rank + 10.0) * a.batch);   // flops
+  // algorithmic bytes: W and the factors in, the quantized form out, per configuration (the scale part of the latter is
+  // finished by the scale kernel that follows)
+  prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st,
+                 (double)a.d * a.k * (4.0 * a.batch + a.quant_bytes_per_weight) + 4.0 * a.rank * (double)(a.d + a.k) * a.batch);
   const bool split = a.packed != nullptr;
   if (split) {
     if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, true>), grid, dim3(NTHR1), 0, st, a, (int)tiles, tiles_n);
@@ -546,7 +549,8 @@ int launch_residual(const PhaseArgs& a, hipStream_t st) {
   const int groups = (a.batch + RES_G - 1) / RES_G;
   const int64_t nwg = (nquads + 256 * RES_U - 1) / (256 * RES_U) * groups;
   if (nwg >= (1ll << 31)) return LQ_ERR_SHAPE;
-  prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * 4.0 * (a.batch + 1));   // R out per problem, W in once
+  // R (or dense Q) out per problem, the quantized form in per problem, W in once
+  prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * (4.0 * (a.batch + 1) + a.quant_bytes_per_weight));
   hipLaunchKernelGGL(residual_kernel, dim3((unsigned)nwg), dim3(256), 0, st, a, groups);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;

@@ -30,7 +30,7 @@ static int64_t up32(int64_t x) { return (x + 31) / 32 * 32; }
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Params {
-  int l1, check, maxit, lw, qw, qw2, max_batch, prec, streams, init_quantized;
+  int l1, check, maxit, lw, qw, qw2, qw_coarse, max_batch, prec, streams, init_quantized;
   double tol;
 };
 
@@ -45,6 +45,7 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   out.lw = z.warm_width ? z.warm_width : (int)std::min<int64_t>(out.l1, up32(rank + std::max(rank / 2, 24)));
   out.qw = z.warm_power ? z.warm_power : 2;
   out.qw2 = z.warm_power_2 ? z.warm_power_2 : 3;
+  out.qw_coarse = z.warm_power_coarse ? z.warm_power_coarse : 4;
   out.max_batch = z.max_batch ? z.max_batch : 36;
   if (z.gemm_mode < 0 || z.gemm_mode > 2) return LQ_ERR_ARG;
   out.prec = z.gemm_mode == 1 ? 0 : 1;
@@ -54,7 +55,7 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   out.init_quantized = z.init_quantized;
   if (out.l1 % 32 || out.l1 <= rank || out.l1 > 256) return LQ_ERR_ARG;
   if (out.lw % 32 || out.lw <= rank || out.lw > out.l1) return LQ_ERR_ARG;
-  if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.max_batch < 1) return LQ_ERR_ARG;
+  if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.qw_coarse < 1 || out.max_batch < 1) return LQ_ERR_ARG;
   return LQ_OK;
 }
 
@@ -297,6 +298,8 @@ static int first_input(const Ctx& c, const float** A) {
   return LQ_OK;
 }
 
+static bool is_coarse(const lq_config& c) { return c.scale_bits != 0 && c.scale_bits <= 2; }
+
 struct LoopOut {          // batch == 1 only: user buffers that receive the quantized component directly
   uint8_t* codes; uint8_t* sidx; float* v; float* Qd;
   float* L1; float* L2; double* sigma;      // only used when the best iterate is kept (early_stop == 2)
@@ -315,7 +318,8 @@ struct Loop {
   bool want_trace = false;
   const float* Y1 = nullptr; const float* B1 = nullptr;
   const LoopOut* direct = nullptr;
-  int cfg_base = 0;                         // index of cfgs[0] in the caller's configuration list
+  const int* cfg_ids = nullptr;             // position of each configuration in the caller's list (NULL: 0, 1, ..)
+  int qw = 0, qw2 = 0;                      // subspace iterations per Factorize (second pass: qw2), set by begin()
   // state
   std::vector<LoopProblem> probs;
   std::vector<double> host_err;
@@ -348,6 +352,12 @@ struct Loop {
       probs[b].levels = scale_levels(cfgs[b]);
       min_block = std::min(min_block, (int)cfgs[b].block);
     }
+    // A scale quantizer with a single level (b1 = 2: every block scale is 0 or v) leaves a residual W - Q that moves a lot
+    // from pass to pass, and the warm-started subspace needs more iterations to follow it.
+    bool coarse = false;
+    for (int b = 0; b < batch; ++b) coarse = coarse || is_coarse(cfgs[b]);
+    qw = coarse ? std::max(pl.prm.qw, pl.prm.qw_coarse) : pl.prm.qw;
+    qw2 = coarse ? std::max(pl.prm.qw2, pl.prm.qw_coarse) : pl.prm.qw2;
     LoopProblem* dprob = c->at<LoopProblem>(pl.prob);
     LQ_HIP_TRY(hipMemcpyAsync(dprob, probs.data(), sizeof(LoopProblem) * batch, hipMemcpyHostToDevice, c->st));
     w = WideSet{c->at<float>(pl.Yw), c->at<float>(pl.Yw2), c->at<float>(pl.Bw), c->at<float>(pl.Bw2)};
@@ -362,6 +372,9 @@ struct Loop {
       a.row_w = c->row_w; a.col_w = c->col_w;
     }
     a.prob = dprob; a.tables = c->tables; a.batch = batch;
+    for (int b = 0; b < batch; ++b)
+      a.quant_bytes_per_weight += cfgs[b].bits / 8.0 + 1.0 / cfgs[b].block +
+                                  (v_bits(cfgs[b]) / 8.0) / ((double)cfgs[b].block * cfgs[b].scale_block);
     if (direct) {
       a.codes = direct->codes; a.sidx = direct->sidx; a.v = direct->v;
     } else {
@@ -442,7 +455,7 @@ struct Loop {
     if (last) { stopped = true; return LQ_OK; }
     a.R = c->at<float>(pl.R); a.strideR = pl.strideR;
     LQ_TRY(launch_residual(a, c->st));
-    LQ_TRY(warm_factorize(*c, w, Bcur, sB, t == 1 ? pl.prm.qw2 : pl.prm.qw, batch));
+    LQ_TRY(warm_factorize(*c, w, Bcur, sB, t == 1 ? qw2 : qw, batch));
     Ycur = w.Yw; Bcur = w.Bw; sY = pl.strideYw; sB = pl.strideBw;
     lamcur = c->at<double>(pl.lam);
 #ifdef LQ_TESTING_HOOKS
@@ -457,14 +470,16 @@ struct Loop {
   // from the very same Q on the CPU.
   int capture_slot(int t) const {
     const testing::Capture& cap = testing::capture();
-    if (!cap.armed || direct || t != cap.iter || cap.cfg < cfg_base || cap.cfg >= cfg_base + batch) return -1;
-    return cap.cfg - cfg_base;
+    if (!cap.armed || direct || t != cap.iter) return -1;
+    for (int b = 0; b < batch; ++b)
+      if ((cfg_ids ? cfg_ids[b] : b) == cap.cfg) return b;
+    return -1;
   }
   int capture_iterate(int t) {
     const int b = capture_slot(t);
     if (b < 0) return LQ_OK;
     PhaseArgs one = a;
-    one.batch = 1; one.prob = a.prob + b;
+    one.batch = 1; one.prob = a.prob + b; one.quant_bytes_per_weight = a.quant_bytes_per_weight / batch;
     one.codes = a.codes + (size_t)b * a.strideCodes; one.sidx = a.sidx + (size_t)b * a.strideSidx;
     one.v = a.v + (size_t)b * a.strideV;
     one.R = nullptr; one.Qd = testing::capture().Q; one.strideQd = 0;
@@ -705,6 +720,17 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
     if (cc.block > 128) return LQ_ERR_CONFIG;
     if (k % cc.block != 0) return LQ_ERR_SHAPE;
   }
+  // Configurations with a single-level scale quantizer get more subspace iterations per pass (see Loop::begin); they
+  // are moved to the front, keeping the caller's order otherwise, so that they share lock-step batches.  order[i] is
+  // the caller's index of the i-th configuration processed.
+  std::vector<int> order(n_cfgs);
+  for (int i = 0; i < n_cfgs; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return is_coarse(cf[a]) > is_coarse(cf[b]); });
+  {
+    std::vector<lq_config> sorted(n_cfgs);
+    for (int i = 0; i < n_cfgs; ++i) sorted[i] = cf[order[i]];
+    cf.swap(sorted);
+  }
   if ((row_w == nullptr) != (col_w == nullptr)) return LQ_ERR_WEIGHT;
   if (!aligned16(W)) return LQ_ERR_ARG;
   Params prm;
@@ -751,7 +777,7 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
       if (b0 >= b1) break;
       Loop& lp = loops[s1];
       lp.c = &cs[s1]; lp.cfgs = cf.data() + c0 + b0; lp.batch = b1 - b0; lp.iters = iters; lp.early_stop = early_stop;
-      lp.want_trace = err_trace != nullptr; lp.Y1 = Y1; lp.B1 = B1; lp.direct = nullptr; lp.cfg_base = c0 + b0;
+      lp.want_trace = err_trace != nullptr; lp.Y1 = Y1; lp.B1 = B1; lp.direct = nullptr; lp.cfg_ids = order.data() + c0 + b0;
       if ((rc = lp.begin()) != LQ_OK) break;
       ++used;
     }
@@ -763,10 +789,10 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
       if (frc != LQ_OK) continue;
       const int b0 = s1 * per_sub;
       for (int b = 0; b < loops[s1].batch; ++b) {
-        const int ci = c0 + b0 + b;
+        const int ci = order[c0 + b0 + b];                            // the caller's index of this configuration
         const double eps = trace[(size_t)b * iters + best[b] - 1];   // the iterate that would be returned
         err_sq[ci] = eps * eps;
-        storage_bits[ci] = lq_storage_bits(d * k, cf[ci]);
+        storage_bits[ci] = lq_storage_bits(d * k, cf[c0 + b0 + b]);
         if (err_trace) std::memcpy(err_trace + (size_t)ci * iters, trace.data() + (size_t)b * iters, sizeof(double) * iters);
       }
     }

@@ -44,7 +44,7 @@ class SvdParams(C.Structure):
     _fields_ = [("first_width", C.c_int32), ("first_tol", C.c_float), ("first_check", C.c_int32),
                 ("first_max", C.c_int32), ("warm_width", C.c_int32), ("warm_power", C.c_int32),
                 ("warm_power_2", C.c_int32), ("max_batch", C.c_int32), ("gemm_mode", C.c_int32),
-                ("streams", C.c_int32), ("init_quantized", C.c_int32)]
+                ("streams", C.c_int32), ("init_quantized", C.c_int32), ("warm_power_coarse", C.c_int32)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -125,15 +125,21 @@ def storage_bits(n: int, cfg: Config) -> float:
     return _lib.lq_storage_bits(n, cfg)
 
 
-def nf_quantize(x: torch.Tensor, cfg: Config):
-    """Quantize(x, c): -> (codes_packed uint8, scale_idx uint8, v fp32), all on x's device."""
+def nf_quantize(x: torch.Tensor, cfg: Config, out=None):
+    """Quantize(x, c): -> (codes_packed uint8, scale_idx uint8, v fp32), all on x's device; `out`: such a triple of the
+    right sizes to write into instead of new tensors."""
     n = x.numel()
-    sb = cfg.scale_bits or 8
     nb = n // max(cfg.block, 1)
     ng = (nb + max(cfg.scale_block, 1) - 1) // max(cfg.scale_block, 1)
-    codes = torch.empty(max(codes_bytes(n, cfg.bits), 1), dtype=torch.uint8, device=x.device)
-    sidx = torch.empty(max(nb, 1), dtype=torch.uint8, device=x.device)
-    v = torch.empty(max(ng, 1), dtype=torch.float32, device=x.device)
+    if out is not None:
+        codes, sidx, v = out
+        if codes.numel() < codes_bytes(n, cfg.bits) or sidx.numel() < nb or v.numel() < ng:
+            raise ValueError("nf_quantize: output buffers too small")
+        _dev(codes, torch.uint8, "codes"), _dev(sidx, torch.uint8, "scale_idx"), _dev(v, torch.float32, "v")
+    else:
+        codes = torch.empty(max(codes_bytes(n, cfg.bits), 1), dtype=torch.uint8, device=x.device)
+        sidx = torch.empty(max(nb, 1), dtype=torch.uint8, device=x.device)
+        v = torch.empty(max(ng, 1), dtype=torch.float32, device=x.device)
     _check(_lib.lq_nf_quantize(_dev(x, torch.float32, "x"), n, cfg, codes.data_ptr(), sidx.data_ptr(), v.data_ptr(),
                                _stream()), "lq_nf_quantize")
     return codes, sidx, v
@@ -253,6 +259,11 @@ def fisher_row_col(f: torch.Tensor):
                                   _aligned_ptr(ws), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()),
            "lq_fisher_row_col")
     return row_w, col_w
+
+
+def release_streams() -> None:
+    """Destroys the idle HIP streams the library keeps for lq_error_table's interleaved sub-batches."""
+    _check(_lib.lq_release_streams(), "lq_release_streams")
 
 
 def profile_enable(on: bool) -> None:

@@ -81,13 +81,22 @@ def test_decompose_largest_shape(env, oracle):
     check_decomposition_consistency(oracle, w, out, oracle.config(3, 32, 64), RANK)
 
 
-def test_error_table_full_size(env, oracle, square):
+@pytest.fixture(scope="module")
+def table(env, square):
+    """The 36-configuration error table of the first 4096 x 4096 matrix, 10 iterations, with its trace."""
     torch, lq = env
-    w, u, s, vt = square
+    w = square[0]
     grid = gen.config_grid()
     assert len(grid) == 36
     wt = torch.from_numpy(w).cuda()
     e, st, tr = lq.error_table(wt, RANK, [lq.config(*g) for g in grid], 10, seed=1, want_trace=True)
+    return grid, wt, e, st, tr
+
+
+def test_error_table_full_size_properties(env, oracle, square, table):
+    torch, lq = env
+    w = square[0]
+    grid, wt, e, st, tr = table
     assert np.all(np.isfinite(e)) and np.all(np.isfinite(tr))
     assert np.array_equal(tr[:, -1] ** 2, e)
     for i, g in enumerate(grid):
@@ -99,7 +108,15 @@ def test_error_table_full_size(env, oracle, square):
             assert cell[(2, b0, b1)] > cell[(3, b0, b1)] > cell[(4, b0, b1)] > cell[(8, b0, b1)]
     # the iteration helps: the final error is below the first iterate's for every cell
     assert np.all(tr[:, -1] < tr[:, 0])
-    # sampled cells, first iteration: exact rank-r SVD of W, oracle quantizer on the fp32 residual
+    # deterministic
+    e2, _ = lq.error_table(wt, RANK, [lq.config(*g) for g in grid], 10, seed=1)
+    assert np.array_equal(e2, e)
+
+
+def test_error_table_full_size_first_pass(oracle, square, table):
+    """Sampled cells, first iteration: exact rank-r SVD of W, oracle quantizer on the fp32 residual."""
+    w, u, s, vt = square
+    grid, _, _, _, tr = table
     low = (u[:, :RANK] * s[:RANK]) @ vt[:RANK]
     t = (w.astype(np.float64) - low).astype(np.float32)
     for i in (1, 14, 22, 35):
@@ -108,18 +125,27 @@ def test_error_table_full_size(env, oracle, square):
         q = oracle.dequantize(codes, sidx, v, ocfg).reshape(w.shape)
         first = np.sqrt(np.sum((w.astype(np.float64) - low - q) ** 2))
         assert abs(tr[i, 0] - first) < ERR_TOL * first, (grid[i], tr[i, 0], first)
-    # sampled cells (2, 3, 4 and 8 bits), last pass anchored: the sweep's own Q(9) -> pass 10 on the CPU
-    for i in (1, 14, 22, 35):
-        e_c, _, tr_c, q9, sg = capture_cell(lq, wt, RANK, grid, 10, i, seed=1)
-        assert np.array_equal(tr_c, tr)
-        anchor.check_anchored_cell(oracle, w, RANK, grid[i], q9, tr[i, 9], sg, label="full-size table cell")
-    # stand-alone decompositions of sampled configurations: consistent pieces, last pass anchored; against the sweep's
-    # cell only as a diagnostic (the two differ in the summation order of a split reduction from pass 2 on)
-    for i in (1, 22, 35):
-        one = anchor.check_anchored_decompose(oracle, lq, torch, w, RANK, grid[i], 10, seed=1, which=[10],
-                                              label="full-size stand-alone")
-        check_decomposition_consistency(oracle, w, one, oracle.config(*grid[i]), RANK)
-        print("stand-alone vs sweep cell (diagnostic):", grid[i], abs(one["err"] - np.sqrt(e[i])) / one["err"])
-    # deterministic
-    e2, _ = lq.error_table(wt, RANK, [lq.config(*g) for g in grid], 10, seed=1)
-    assert np.array_equal(e2, e)
+
+
+@pytest.mark.parametrize("i", [1, 14, 22, 35])
+def test_error_table_full_size_last_pass_anchored(env, oracle, square, table, i):
+    """Sampled cells (2, 3, 4 and 8 bits), last pass anchored: the sweep's own Q(9) -> pass 10 on the CPU."""
+    torch, lq = env
+    w = square[0]
+    grid, wt, _, _, tr = table
+    _, _, tr_c, q9, sg = capture_cell(lq, wt, RANK, grid, 10, i, seed=1)
+    assert np.array_equal(tr_c, tr)
+    anchor.check_anchored_cell(oracle, w, RANK, grid[i], q9, tr[i, 9], sg, label="full-size table cell")
+
+
+@pytest.mark.parametrize("i", [1, 22, 35])
+def test_decompose_full_size_last_pass_anchored(env, oracle, square, table, i):
+    """Stand-alone decompositions of sampled configurations: consistent pieces, last pass anchored; against the sweep's
+    cell only as a diagnostic (the two differ in the summation order of a split reduction from pass 2 on)."""
+    torch, lq = env
+    w = square[0]
+    grid, _, e, _, _ = table
+    one = anchor.check_anchored_decompose(oracle, lq, torch, w, RANK, grid[i], 10, seed=1, which=[10],
+                                          label="full-size stand-alone")
+    check_decomposition_consistency(oracle, w, one, oracle.config(*grid[i]), RANK)
+    print("stand-alone vs sweep cell (diagnostic):", grid[i], abs(one["err"] - np.sqrt(e[i])) / one["err"])
