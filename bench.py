@@ -541,7 +541,7 @@ def bench_sweep(args, torch, gen, lq, dev) -> int:
     if prof:
         line["serial_profiled_step_ms"] = serial_ms
         line["latency_bound_kernel_share"] = latency_share
-        line["roofline_kernels"] = {n: r for n, r in ((n, roofline_of(n, *v)) for n, v in prof.items()) if r and v[0] > 0.5}
+        line["roofline_kernels"] = {n: r for n, r in ((n, roofline_of(n, *v)) for n, v in prof.items() if v[0] > 0.5) if r}
         line["kernels"] = {n: {"ms": round(v[0], 3), "launches": v[1]} for n, v in prof.items()}
     if not args.no_cpu_baseline:
         if wl == 1:

@@ -27,6 +27,13 @@ extern "C" {
 int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const float* A,
                       int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
                       int precision, void* stream);
+/* The same products with A stored in fp16 (l <= 96, ldx a multiple of 64): C = out_scale * X * op(A), X multiplied by
+ * x_scale before it is split into fp16 halves, or, with lam0 (device, one double per problem: the largest squared row
+ * norm of that X), by a power of two derived from it that is divided out again.  A_lo: NULL, or a second fp16 matrix of
+ * the same layout; the product is then taken with A + A_lo. */
+int lq_test_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const uint16_t* A,
+                          const uint16_t* A_lo, int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
+                          float x_scale, const double* lam0, float out_scale, void* stream);
 size_t lq_test_wide_gemm_part_floats(int l, int workgroups);
 /* Rows of X (l x m) are orthonormalised in place by Cholesky-QR (Gram in fp64).
  * scratch: at least 17 * l * l doubles.  alt: l * ldx floats of scratch, or NULL to force the

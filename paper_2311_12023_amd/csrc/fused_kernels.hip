@@ -29,6 +29,7 @@ constexpr int KP = KC2 + 8;// LDS row pitch of its operand planes in bf16 elemen
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------------------
 // Split-precision operands of L1 L2 = Y_r^T B_r: every factor entry x is stored as bf16 hi + bf16 lo
@@ -523,6 +524,8 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) 
     const float* code = s_code[bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3];
     const uint32_t mask = (1u << bits) - 1u;
     float* R = a.R ? a.R + (size_t)z * a.strideR : nullptr;
+    _Float16* R16 = a.R16 ? reinterpret_cast<_Float16*>(a.R16) + (size_t)z * a.strideR : nullptr;
+    _Float16* R16lo = a.R16lo ? reinterpret_cast<_Float16*>(a.R16lo) + (size_t)z * a.strideR : nullptr;
     float* Qd = a.Qd ? a.Qd + (size_t)z * a.strideQd : nullptr;
 #pragma unroll
     for (int u = 0; u < RES_U; ++u) {
@@ -539,6 +542,19 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) 
         rv.z = srow[u] * rv.z * cs[u].z; rv.w = srow[u] * rv.w * cs[u].w;
       }
       if (R) *reinterpret_cast<float4*>(R + (quad << 2)) = rv;
+      if (R16) {
+        const float lim = 65504.0f;        // largest fp16: out-of-range entries saturate instead of becoming infinite
+        const float sv[4] = {__builtin_amdgcn_fmed3f(rv.x * a.r_scale, -lim, lim), __builtin_amdgcn_fmed3f(rv.y * a.r_scale, -lim, lim),
+                             __builtin_amdgcn_fmed3f(rv.z * a.r_scale, -lim, lim), __builtin_amdgcn_fmed3f(rv.w * a.r_scale, -lim, lim)};
+        halfx4 h, l;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          h[e] = (_Float16)sv[e];
+          l[e] = (_Float16)(sv[e] - (float)h[e]);
+        }
+        *reinterpret_cast<halfx4*>(R16 + (quad << 2)) = h;
+        if (R16lo) *reinterpret_cast<halfx4*>(R16lo + (quad << 2)) = l;
+      }
       if (Qd) *reinterpret_cast<float4*>(Qd + (quad << 2)) = qv;
     }
   }
@@ -550,7 +566,8 @@ int launch_residual(const PhaseArgs& a, hipStream_t st) {
   const int64_t nwg = (nquads + 256 * RES_U - 1) / (256 * RES_U) * groups;
   if (nwg >= (1ll << 31)) return LQ_ERR_SHAPE;
   // R (or dense Q) out per problem, the quantized form in per problem, W in once
-  prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * (4.0 * (a.batch + 1) + a.quant_bytes_per_weight));
+  const double out_bytes = (a.R ? 4.0 : 0.0) + (a.R16 ? 2.0 : 0.0) + (a.R16 && a.R16lo ? 2.0 : 0.0) + (a.Qd ? 4.0 : 0.0);
+  prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * (out_bytes * a.batch + 4.0 + a.quant_bytes_per_weight));
   hipLaunchKernelGGL(residual_kernel, dim3((unsigned)nwg), dim3(256), 0, st, a, groups);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;

@@ -375,6 +375,249 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g, int l, int 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Products whose large operand is stored in fp16 (the residual W - Q of the warm LQ iterations, scaled by a power of
+// two so that it sits in the middle of the fp16 range): half the bytes of the fp32 form stream from HBM, which is
+// what bounds these products.  X is split on the fly into fp16 hi + lo (after scaling by a power of two xs that puts
+// its entries where both halves are normal numbers) and every product is two v_mfma_f32_32x32x16_f16
+// (hi * a + lo * a, fp32 accumulation).  PLANES == 2: A comes as two fp16 planes, a = hi + lo (22 significant bits),
+// and a product is three MFMAs (xl * ah + xh * al + xh * ah); used where the rounding of A to fp16 would show in the
+// result to first order.  The result is multiplied by out_scale (a power of two) when stored.
+// Same work decomposition, tile shapes and fix-up as wide_gemm_kernel; the reduction is cut into steps of 64 (one
+// plane) or 32 (two planes), and both operands keep the natural order of the reduction index.
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int HP16 = 64 + 8;     // LDS row pitch of the X halves in fp16 elements (144 B: conflict-free b128 reads)
+
+// X tile: L x (16 G) floats, LT * G / 2 float4 per thread.  The leading dimension of X is a multiple of 64.
+template <int LT, int G>
+__device__ __forceinline__ void fetch_x16(const float* __restrict__ X, int64_t ldx, int64_t k0, int tid,
+                                          floatx4 (&xreg)[LT * G / 2]) {
+#pragma unroll
+  for (int i = 0; i < LT * G / 2; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx / (4 * G), c4 = idx % (4 * G);
+    xreg[i] = *reinterpret_cast<const floatx4*>(X + (size_t)row * ldx + k0 + c4 * 4);
+  }
+}
+
+template <int LT, int G>
+__device__ __forceinline__ void stash_x16(_Float16* xh, _Float16* xl, int tid, float xs,
+                                          const floatx4 (&xreg)[LT * G / 2]) {
+#pragma unroll
+  for (int i = 0; i < LT * G / 2; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx / (4 * G), c4 = idx % (4 * G);
+    const floatx4 v = xreg[i] * xs;
+    const halfx4 h = __builtin_convertvector(v, halfx4);
+    const halfx4 l = __builtin_convertvector(v - __builtin_convertvector(h, floatx4), halfx4);
+    *reinterpret_cast<halfx4*>(xh + row * HP16 + 4 * c4) = h;
+    *reinterpret_cast<halfx4*>(xl + row * HP16 + 4 * c4) = l;
+  }
+}
+
+template <int MODE>
+__device__ __forceinline__ void lane_offsets16(int64_t lda, int64_t big, int64_t big0, int ln, int lh,
+                                               uint32_t (&off)[2]) {
+  if constexpr (MODE == MODE_NT) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int64_t row = big0 + 32 * j + ln;
+      if (row >= big) row = big - 1;            // clamped rows are computed and never stored
+      off[j] = (uint32_t)((row * lda + 8 * lh) * 2);
+    }
+  } else {
+    int64_t col = big0 + (int64_t)ln * 2;
+    if (col + 2 > big) col = big - 2;           // big is even; clamped columns never stored
+    off[0] = (uint32_t)((8 * lh * lda + col) * 2);
+    off[1] = 0;
+  }
+}
+
+// One plane of the A operand of a step as it comes from memory.  NT mode: ring[g][j] = the 8 halves
+// k0 + 16 g + 8 h + (0..7) of row j's lane row.  NN mode: ring[g][e / 4][e % 4] = the word holding columns col, col + 1
+// of reduction row k0 + 16 g + 8 h + e.
+template <int MODE, int G, bool GUARD>
+__device__ __forceinline__ void fetch_a16(const _Float16* __restrict__ A, int64_t lda, const uint32_t (&off)[2], int lh,
+                                          int64_t k0, int64_t kend, uintx4 (&ring)[G][2]) {
+  const uintx4 zero = {0u, 0u, 0u, 0u};
+  if constexpr (MODE == MODE_NT) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const char* base = reinterpret_cast<const char*>(A + k0 + 16 * g);
+        uintx4 f = zero;
+        if (!GUARD || k0 + 16 * g + 8 * lh < kend)                      // K and kend are multiples of 8
+          f = *reinterpret_cast<const uintx4*>(base + off[j]);
+        ring[g][j] = f;
+      }
+  } else {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const char* base = reinterpret_cast<const char*>(A + (size_t)(k0 + 16 * g + e) * lda);
+        uint32_t f = 0u;
+        if (!GUARD || k0 + 16 * g + 8 * lh + e < kend) f = *reinterpret_cast<const uint32_t*>(base + off[0]);
+        ring[g][e >> 2][e & 3] = f;
+      }
+  }
+}
+
+// The two MFMA operands (columns j = 0, 1 of the lane's pair) of 16-group g from a fetched plane.
+template <int MODE, int G>
+__device__ __forceinline__ void operands16(const uintx4 (&cur)[G][2], int g, halfx8 (&av)[2]) {
+  if constexpr (MODE == MODE_NT) {
+    av[0] = __builtin_bit_cast(halfx8, cur[g][0]);
+    av[1] = __builtin_bit_cast(halfx8, cur[g][1]);
+  } else {
+    // words (col, col + 1) of 8 reduction rows -> the 8 halves of column col and of column col + 1
+    uintx4 c0, c1;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const uint32_t w0 = cur[g][m >> 1][2 * (m & 1)], w1 = cur[g][m >> 1][2 * (m & 1) + 1];
+      c0[m] = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
+      c1[m] = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
+    }
+    av[0] = __builtin_bit_cast(halfx8, c0);
+    av[1] = __builtin_bit_cast(halfx8, c1);
+  }
+}
+
+template <int LT, int MODE, int PLANES, int G>
+__device__ __forceinline__ void multiply_chunk16(const _Float16* xh, const _Float16* xl, int ln, int lh,
+                                                 const uintx4 (&cur)[PLANES][G][2], floatx16 (&acc)[LT][2]) {
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    halfx8 ah[2], al[2];
+    operands16<MODE, G>(cur[0], g, ah);
+    if constexpr (PLANES == 2) operands16<MODE, G>(cur[1], g, al);
+#pragma unroll
+    for (int i = 0; i < LT; ++i) {
+      const halfx8 xhv = *reinterpret_cast<const halfx8*>(xh + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
+      const halfx8 xlv = *reinterpret_cast<const halfx8*>(xl + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xlv, ah[j], acc[i][j], 0, 0, 0);
+        if constexpr (PLANES == 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, al[j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, ah[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+}
+
+// Power of two xs with |x| xs <= 2^13 for the rows of a wide matrix whose largest squared row norm is lam0.
+__device__ __forceinline__ float x_scale_from(double lam0) {
+  const float s = (float)lam0;
+  if (!(s > 0.0f) || !(s < 3.0e38f)) return 1.0f;
+  return exp2f(13.0f - ceilf(0.5f * log2f(s)));
+}
+
+template <int LT, int MODE, int PLANES>
+__global__ __launch_bounds__(256, 2) void wide_gemm_f16_kernel(GemmArgs g) {
+  constexpr int NT = 2;
+  constexpr int SPAN = 128 * NT;
+  constexpr int G = PLANES == 1 ? 4 : 2;       // 16-groups per step
+  constexpr int BKH = 16 * G;
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // hi then lo halves of X, [32*LT][HP16] fp16 each
+  _Float16* xh = reinterpret_cast<_Float16*>(xs);
+  _Float16* xl = xh + 32 * LT * HP16;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int ln = lane & 31, lh = lane >> 5;
+
+  const int tile = (blockIdx.x >> 3) % g.tiles;
+  const int share = (int)(blockIdx.x & 7) + 8 * (int)((blockIdx.x >> 3) / g.tiles);
+  const int share0 = share * g.per_wg;
+  if (share0 >= g.total) return;                 // padding of the share count to a multiple of 8
+  const int share1 = share0 + g.per_wg < g.total ? share0 + g.per_wg : g.total;
+
+  const int64_t big0 = (int64_t)tile * SPAN + wave * (32 * NT);
+  uint32_t off[2];
+  lane_offsets16<MODE>(g.lda, g.big, big0, ln, lh, off);
+
+  for (int gs = share0; gs < share1;) {
+    const int z = gs / g.ns;
+    const int s0 = gs - z * g.ns;
+    const int s1 = g.ns - s0 < share1 - gs ? g.ns : s0 + (share1 - gs);
+    const float* __restrict__ X = g.X + (size_t)z * g.strideX;
+    const _Float16* __restrict__ A = reinterpret_cast<const _Float16*>(g.A) + (size_t)z * g.strideA;
+    const _Float16* __restrict__ A2 = reinterpret_cast<const _Float16*>(g.A2) + (size_t)z * g.strideA;
+    const float xscale = g.lam0 ? x_scale_from(g.lam0[(size_t)z * g.strideLam]) : g.x_scale;
+    const int64_t kbeg = (int64_t)s0 * BKH;
+    const int64_t kend = (int64_t)s1 * BKH < g.K ? (int64_t)s1 * BKH : g.K;
+    const int nsteps = s1 - s0;
+
+    floatx16 acc[LT][NT];
+#pragma unroll
+    for (int i = 0; i < LT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // as in wide_gemm_kernel: the pipelined loop has no guarded load; a partial last step is handled after it
+    const bool tail = s1 == g.ns && (g.K & (BKH - 1)) != 0;
+    const int nfull = tail ? nsteps - 1 : nsteps;
+    const int64_t klast = kbeg + (int64_t)(nfull > 0 ? nfull - 1 : 0) * BKH;
+    const int64_t kxlast = kbeg + (int64_t)(nsteps - 1) * BKH;
+
+    floatx4 xreg[LT * G / 2];
+    uintx4 ring[2][PLANES][G][2];
+    fetch_x16<LT, G>(X, g.ldx, kbeg, tid, xreg);
+    if (nfull > 0) {
+      fetch_a16<MODE, G, false>(A, g.lda, off, lh, kbeg, kend, ring[0][0]);
+      if constexpr (PLANES == 2) fetch_a16<MODE, G, false>(A2, g.lda, off, lh, kbeg, kend, ring[0][1]);
+    }
+
+#define LQ_GEMM16_STEP(U, STEP, PREFETCH)                                                                         \
+  {                                                                                                               \
+    __syncthreads(); /* everyone is done reading the previous X tile */                                           \
+    stash_x16<LT, G>(xh, xl, tid, xscale, xreg);                                                                  \
+    __syncthreads();                                                                                              \
+    {                                                                                                             \
+      const int64_t kx = kbeg + (int64_t)((STEP) + 1) * BKH;                                                      \
+      fetch_x16<LT, G>(X, g.ldx, kx < kxlast ? kx : kxlast, tid, xreg);                                           \
+    }                                                                                                             \
+    if constexpr (PREFETCH) {                                                                                     \
+      const int64_t k1 = kbeg + (int64_t)((STEP) + 1) * BKH;                                                      \
+      const int64_t k1c = k1 < klast ? k1 : klast;                                                                \
+      fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[((U) + 1) & 1][0]);                            \
+      if constexpr (PLANES == 2) fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[((U) + 1) & 1][1]); \
+    }                                                                                                             \
+    multiply_chunk16<LT, MODE, PLANES, G>(xh, xl, ln, lh, ring[(U)], acc);                                        \
+  }
+    int step0 = 0;
+    for (; step0 + 2 <= nfull; step0 += 2) {
+      LQ_GEMM16_STEP(0, step0, true)
+      LQ_GEMM16_STEP(1, step0 + 1, true)
+    }
+    if (step0 < nfull) LQ_GEMM16_STEP(0, step0, false)
+    if (tail) {
+      const int64_t kt = kbeg + (int64_t)nfull * BKH;
+      fetch_a16<MODE, G, true>(A, g.lda, off, lh, kt, kend, ring[0][0]);
+      if constexpr (PLANES == 2) fetch_a16<MODE, G, true>(A2, g.lda, off, lh, kt, kend, ring[0][1]);
+      LQ_GEMM16_STEP(0, nfull, false)
+    }
+#undef LQ_GEMM16_STEP
+
+    const float os = g.out_scale / (g.lam0 ? xscale : 1.0f);
+#pragma unroll
+    for (int i = 0; i < LT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] *= os;
+    const bool whole = s0 == 0 && s1 == g.ns;
+    const size_t slot = ((size_t)share * g.tiles + tile) * 2 + (gs == share0 ? 0 : 1);
+    float* dst = whole ? g.C + (size_t)z * g.strideC : g.part + slot * (size_t)(32 * LT * SPAN);
+    store_acc<LT, MODE, NT>(dst, whole ? g.ldc : SPAN, whole ? big0 : wave * (32 * NT), whole ? g.big : SPAN, ln, lh,
+                            acc);
+    gs += nsteps;
+  }
+}
+
 template <int LT, int MODE, int NT, int PREC>
 static void launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
   const size_t lds = PREC == PREC_FP32 ? (size_t)32 * LT * XPITCH * sizeof(float)
@@ -479,6 +722,77 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
     else
       rc = (mode == MODE_NT) ? launch_mode<MODE_NT, PREC_FP32>(g, lt, grid, st)
                              : launch_mode<MODE_NN, PREC_FP32>(g, lt, grid, st);
+    if (rc != LQ_OK) return rc;
+  }
+  LQ_HIP_TRY(hipGetLastError());
+  if (cut && g.per_wg % g.ns != 0) {
+    prof::Scope ps(prof::GEMM_FIXUP, st, (double)tiles * batch * l * span * 4.0);
+    hipLaunchKernelGGL(gemm_fixup_kernel, dim3((unsigned)tiles, (unsigned)batch, (unsigned)(l / 8)), dim3(256), 0, st, g,
+                       l, span);
+    LQ_HIP_TRY(hipGetLastError());
+  }
+  return LQ_OK;
+}
+
+template <int MODE, int PLANES>
+static int launch_f16_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
+  const size_t lds = (size_t)2 * 32 * lt * HP16 * sizeof(_Float16);
+  switch (lt) {
+    case 1: hipLaunchKernelGGL((wide_gemm_f16_kernel<1, MODE, PLANES>), grid, dim3(256), lds, st, g); break;
+    case 2: hipLaunchKernelGGL((wide_gemm_f16_kernel<2, MODE, PLANES>), grid, dim3(256), lds, st, g); break;
+    case 3: hipLaunchKernelGGL((wide_gemm_f16_kernel<3, MODE, PLANES>), grid, dim3(256), lds, st, g); break;
+    default: return LQ_ERR_ARG;
+  }
+  return LQ_OK;
+}
+
+bool wide_gemm_f16_supported(int l) { return l % 32 == 0 && l >= 32 && l <= 96; }   // four row tiles spill registers
+
+// C = out_scale * X * op(A) for `batch` problems with A stored in fp16 (strideA, lda in fp16 elements), as one plane
+// (A_lo == NULL) or as hi + lo planes of the same layout.  X is scaled by x_scale before it is split into fp16 halves,
+// or, when lam0 is given, by a power of two derived from lam0[z * strideLam], the largest squared row norm of X[z]
+// (that scale is divided out again).  ldx must be a multiple of 64; NT mode needs K and lda to be multiples of 8,
+// NN mode an even lda.
+int launch_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
+                         const uint16_t* A, const uint16_t* A_lo, int64_t lda, size_t strideA, float* C, int64_t ldc,
+                         size_t strideC, int batch, float* part, size_t part_floats, float x_scale, const double* lam0,
+                         size_t strideLam, float out_scale, hipStream_t st, int workgroups) {
+  if (!wide_gemm_f16_supported(l) || big < 1 || K < 1 || batch < 1 || ldx % 64 != 0) return LQ_ERR_ARG;
+  if (mode == MODE_NN && ((big % 2) != 0 || (lda % 2) != 0)) return LQ_ERR_ARG;
+  if (mode == MODE_NT && ((K % 8) != 0 || (lda % 8) != 0)) return LQ_ERR_ARG;
+  // lane offsets into A are 32-bit byte offsets
+  if ((mode == MODE_NT ? (uint64_t)big * (uint64_t)lda : (uint64_t)16 * lda + (uint64_t)big) * 2 >= (1ull << 32))
+    return LQ_ERR_SHAPE;
+  const int lt = l / 32;
+  const int span = 256;
+  const int bk = A_lo ? 32 : 64;
+  GemmArgs g;
+  g.X = X; g.A = reinterpret_cast<const float*>(A); g.A2 = reinterpret_cast<const float*>(A_lo ? A_lo : A);
+  g.C = C; g.part = part; g.ldx = ldx; g.lda = lda; g.ldc = ldc;
+  g.strideX = strideX; g.strideA = strideA; g.strideC = strideC;
+  g.big = big; g.K = K;
+  g.x_scale = x_scale; g.out_scale = out_scale; g.lam0 = lam0; g.strideLam = strideLam;
+  const int64_t tiles = (big + span - 1) / span;
+  const int64_t ns = (K + bk - 1) / bk;
+  if (tiles > (1 << 20) || ns * batch >= (1ll << 31)) return LQ_ERR_SHAPE;
+  g.ns = (int)ns;
+  g.tiles = (int)tiles;
+  g.total = (int)(ns * batch);
+  const int64_t forced = workgroups < 0 ? -(int64_t)workgroups : 0;
+  if (workgroups <= 0) workgroups = resident_workgroups();
+  int64_t groups = forced ? std::min<int64_t>(forced, g.total) : choose_groups(tiles, g.total, batch, workgroups);
+  int64_t per = (g.total + groups - 1) / groups;
+  if (per < 4 && !forced) per = std::min<int64_t>(4, g.total);
+  const size_t need = (size_t)2 * tiles * ((g.total + per - 1) / per) * l * span;
+  const bool cut = part != nullptr && part_floats >= need && groups > 1 && batch < (1 << 16);
+  g.per_wg = cut ? (int)per : (int)ns;
+  const int64_t ngroups = (g.total + g.per_wg - 1) / g.per_wg;
+  const dim3 grid((unsigned)(tiles * ((ngroups + 7) / 8 * 8)));
+  {
+    prof::Scope ps(prof::GEMM_F16_BASE + (A_lo ? 8 : 0) + mode * 4 + (lt - 1), st, 2.0 * l * (double)big * (double)K * batch);
+    int rc;
+    if (A_lo) rc = mode == MODE_NT ? launch_f16_mode<MODE_NT, 2>(g, lt, grid, st) : launch_f16_mode<MODE_NN, 2>(g, lt, grid, st);
+    else rc = mode == MODE_NT ? launch_f16_mode<MODE_NT, 1>(g, lt, grid, st) : launch_f16_mode<MODE_NN, 1>(g, lt, grid, st);
     if (rc != LQ_OK) return rc;
   }
   LQ_HIP_TRY(hipGetLastError());

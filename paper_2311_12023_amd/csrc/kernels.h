@@ -23,6 +23,11 @@ struct GemmArgs {
   int64_t K;                          // reduction length
   int tiles, ns;                      // tile positions along the large dimension, 32-deep reduction steps per problem
   int total, per_wg;                  // steps of the whole batch, steps per workgroup (share)
+  // fp16-operand products only (launch_wide_gemm_f16)
+  const float* A2;                    // second (lo) fp16 plane of A, same layout
+  float x_scale, out_scale;
+  const double* lam0;                 // per problem: largest squared row norm of X, or NULL (x_scale applies)
+  size_t strideLam;
 };
 
 int gemm_tile_span(int lt);
@@ -33,6 +38,13 @@ size_t gemm_part_floats(int l, int workgroups);
 int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
                      const float* A, int64_t lda, size_t strideA, float* C, int64_t ldc, size_t strideC, int batch,
                      float* part, size_t part_floats, hipStream_t st, int precision = 0, int workgroups = 0);
+
+// The same products with A stored in fp16 (see gemm_kernels.hip); l <= 96.
+bool wide_gemm_f16_supported(int l);
+int launch_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
+                         const uint16_t* A, const uint16_t* A_lo, int64_t lda, size_t strideA, float* C, int64_t ldc,
+                         size_t strideC, int batch, float* part, size_t part_floats, float x_scale, const double* lam0,
+                         size_t strideLam, float out_scale, hipStream_t st, int workgroups = 0);
 
 // Row and column Fisher weights from a full Fisher matrix (Section 3.3): row_w = a^2, col_w = (b / mean(sqrt F))^2
 // with a, b the row / column means of sqrt(F), accumulated in fp64.  scratch: fisher_scratch_doubles(d, k) doubles.
@@ -143,6 +155,8 @@ int launch_jacobi_fast(const double* G, int l, float* Ut, double* lambda, int ba
 // lam[z][i] = squared norm of row i of the wide matrix X[z] (l x m), fp64.
 int launch_row_sumsq(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, double* lam, int batch,
                      hipStream_t st);
+// out[1024] = max |x[i]| over n floats (out[0..1023]: per-workgroup maxima); non-finite values are skipped.
+int launch_absmax(const float* x, int64_t n, float* out, hipStream_t st);
 // X <- X - alpha * Y, both `count` floats (multiple of 4).
 int launch_axpy_sub(float* X, const float* Y, float alpha, int64_t count, hipStream_t st);
 // Fills a wide matrix (l x m, padded ld) with N(0,1) draws from a counter-based generator; pads are zeroed.
@@ -188,6 +202,9 @@ struct PhaseArgs {
   uint8_t* sidx;    size_t strideSidx;
   float* v;         size_t strideV;
   float* R;         size_t strideR;         // scaled residual sqrt(rw_i) (W - Q) sqrt(cw_j), or NULL
+  uint16_t* R16;    float r_scale;          // the same residual times r_scale (a power of two) as fp16, clamped to the
+                                            // fp16 range (stride strideR, in fp16 elements), or NULL
+  uint16_t* R16lo;                          // with R16: fp16 of what the rounding of R16 dropped, same layout
   float* Qd;        size_t strideQd;        // dense Q or NULL
   double* err_part; size_t strideErrPart;   // per-workgroup partial sums of the squared error
   double* err_out;  size_t strideErrOut;    // eps (norm) of this iteration, one double per problem
@@ -207,7 +224,7 @@ int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st)
 // the same value phase 1 was launched with: it decides the layout of the block records).
 // min_block: smallest B0 in the batch (sizes the grid).
 int launch_scalequant_error(const PhaseArgs& a, int min_block, bool with_err, hipStream_t st);
-// Phase 3: R = sqrt(rw_i) (W - Q) sqrt(cw_j) and / or dense Q.
+// Phase 3: R = sqrt(rw_i) (W - Q) sqrt(cw_j) (fp32, or scaled fp16: R16) and / or dense Q.
 int launch_residual(const PhaseArgs& a, hipStream_t st);
 // Number of error partials phase 2 writes per problem for block size B0.
 int64_t err_partials_per_problem(int64_t n, int block);

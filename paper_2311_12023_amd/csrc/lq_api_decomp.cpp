@@ -27,6 +27,7 @@ constexpr int MAX_RANK = 128;
 constexpr int MAX_DEVICES = 64;
 
 static int64_t up32(int64_t x) { return (x + 31) / 32 * 32; }
+static int64_t up64(int64_t x) { return (x + 63) / 64 * 64; }
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Params {
@@ -47,14 +48,17 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   out.qw2 = z.warm_power_2 ? z.warm_power_2 : 3;
   out.qw_coarse = z.warm_power_coarse ? z.warm_power_coarse : 4;
   out.max_batch = z.max_batch ? z.max_batch : 36;
-  if (z.gemm_mode < 0 || z.gemm_mode > 2) return LQ_ERR_ARG;
-  out.prec = z.gemm_mode == 1 ? 0 : 1;
+  if (z.gemm_mode < 0 || z.gemm_mode > 3) return LQ_ERR_ARG;
+  // 0: fp32 MFMA everywhere; 1: large products on bf16 hi/lo splits; 2: as 1, and the residual W - Q of the warm
+  // iterations is kept in fp16 (products against it: fp16 hi/lo split of the skinny operand)
+  out.prec = z.gemm_mode == 1 ? 0 : (z.gemm_mode == 2 ? 1 : 2);
   out.streams = z.streams ? z.streams : 3;
   if (out.streams < 1 || out.streams > 4) return LQ_ERR_ARG;
   if (z.init_quantized != 0 && z.init_quantized != 1) return LQ_ERR_ARG;
   out.init_quantized = z.init_quantized;
   if (out.l1 % 32 || out.l1 <= rank || out.l1 > 256) return LQ_ERR_ARG;
   if (out.lw % 32 || out.lw <= rank || out.lw > out.l1) return LQ_ERR_ARG;
+  if (out.prec == 2 && !wide_gemm_f16_supported(out.lw)) out.prec = 1;
   if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.qw_coarse < 1 || out.max_batch < 1) return LQ_ERR_ARG;
   return LQ_OK;
 }
@@ -87,7 +91,7 @@ struct Plan {
 };
 
 static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int batch, Plan& pl) {
-  pl.d = d; pl.k = k; pl.ldd = up32(d); pl.ldk = up32(k); pl.n = d * k;
+  pl.d = d; pl.k = k; pl.ldd = up64(d); pl.ldk = up64(k); pl.n = d * k;
   pl.rank = rank; pl.batch = batch; pl.prm = prm; pl.lmax = prm.l1;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
@@ -107,7 +111,11 @@ static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int bat
   pl.prob = take((size_t)batch * sizeof(LoopProblem));
   pl.errs = take((size_t)batch * MAX_ITERS * 8);
   const size_t n = (size_t)pl.n;
-  pl.strideR = up256(n * 4) / 4;            pl.R = take(pl.strideR * 4 * batch);
+  if (prm.prec == 2) {      // fp16 residuals; the area also has to hold one fp32 matrix (input of the first Factorize)
+    pl.strideR = up256(n * 2) / 2;          pl.R = take(std::max(pl.strideR * 4 * batch, up256(n * 4)));   // hi planes, lo planes
+  } else {
+    pl.strideR = up256(n * 4) / 4;          pl.R = take(pl.strideR * 4 * batch);
+  }
   pl.strideYw = (size_t)lw * pl.ldd;        pl.Yw = take(pl.strideYw * 4 * batch); pl.Yw2 = take(pl.strideYw * 4 * batch);
   pl.strideBw = (size_t)lw * pl.ldk;        pl.Bw = take(pl.strideBw * 4 * batch); pl.Bw2 = take(pl.strideBw * 4 * batch);
   pl.strideCodes = up256(n);                pl.codes = take(pl.strideCodes * batch);
@@ -133,6 +141,7 @@ struct Ctx {
   // set once per call and shared by the per-stream contexts of a sweep
   const float* sr; const float* sc; const float* rsr; const float* rsc;   // sqrt / 1/sqrt of the Fisher weights
   const double* lam_cold;                                                   // Ritz values of the cold start
+  float a_scale;            // power of two the fp16 residual is multiplied by (residual_scale)
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
 
@@ -158,7 +167,7 @@ static int orthonormalize(const Ctx& c, float*& X, float*& Xalt, int l, int64_t 
 static int gemm(const Ctx& c, int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t sX,
                 const float* A, int64_t lda, size_t sA, float* C, int64_t ldc, size_t sC, int batch) {
   return launch_wide_gemm(mode, l, big, K, X, ldx, sX, A, lda, sA, C, ldc, sC, batch, c.at<float>(c.pl.gpart),
-                          c.pl.gpart_floats, c.st, c.pl.prm.prec);
+                          c.pl.gpart_floats, c.st, c.pl.prm.prec ? 1 : 0);
 }
 
 // Rayleigh-Ritz on the subspace spanned by the rows of Y (orthonormal) with B = Y A:
@@ -256,16 +265,39 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
 // starting from the rows of Bsrc, then Rayleigh-Ritz.  Results land in Yw / Bw (swapped with Yw2 / Bw2).
 struct WideSet { float* Yw; float* Yw2; float* Bw; float* Bw2; };
 
-static int warm_factorize(const Ctx& c, WideSet& w, const float* Bsrc, size_t sBsrc, int power, int batch) {
+static int batch_planes(const Ctx& c) { return c.pl.batch; }      // problems per plane set of the fp16 residual area
+
+static int warm_factorize(const Ctx& c, WideSet& w, const float* Bsrc, size_t sBsrc, const double* lamsrc, size_t sLam,
+                          int power, int batch) {
   const Plan& pl = c.pl;
   const int l = pl.prm.lw;
   const float* R = c.at<float>(pl.R);
+  const uint16_t* R16 = c.at<uint16_t>(pl.R);
+  const uint16_t* R16lo = R16 + pl.strideR * (size_t)batch_planes(c);
   const float* X = Bsrc; size_t sX = sBsrc;
+  const bool half = pl.prm.prec == 2;
+  float* part = c.at<float>(pl.gpart);
+  // fp16 residual: the rows of X = B (norms at most sigma_1, taken from the Ritz values the rows of Bsrc came with;
+  // the products Y A of the later iterations have rows no longer than sigma_1 of the new residual, which the headroom
+  // of the scale covers) are scaled per problem; an orthonormal X by 2^13.  Both products come back in true scale.
+  const float ys = 8192.0f;
   for (int it = 0; it < power; ++it) {
-    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, X, pl.ldk, sX, R, pl.k, pl.strideR, w.Yw, pl.ldd, pl.strideYw, batch));
+    if (half)
+      LQ_TRY(launch_wide_gemm_f16(MODE_NT, l, pl.d, pl.k, X, pl.ldk, sX, R16, nullptr, pl.k, pl.strideR, w.Yw, pl.ldd,
+                                  pl.strideYw, batch, part, pl.gpart_floats, 1.0f, lamsrc, sLam, 1.0f / c.a_scale, c.st));
+    else
+      LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, X, pl.ldk, sX, R, pl.k, pl.strideR, w.Yw, pl.ldd, pl.strideYw, batch));
     LQ_TRY(orthonormalize(c, w.Yw, w.Yw2, l, pl.d, pl.ldd, pl.strideYw, batch));
-    LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R, pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw,
-                batch));
+    if (half)
+      // the last product is the projection B = Y A that the Ritz values and the factors are read from: it takes both
+      // planes of the residual (a rounding of A to fp16 would show in sigma to first order wherever a few entries carry a
+      // singular vector); the products before it only steer the subspace and take the hi plane
+      LQ_TRY(launch_wide_gemm_f16(MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R16, it + 1 == power ? R16lo : nullptr,
+                                  pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw, batch, part, pl.gpart_floats, ys, nullptr, 0,
+                                  1.0f / (ys * c.a_scale), c.st));
+    else
+      LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R, pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw,
+                  batch));
     X = w.Bw; sX = pl.strideBw;
   }
   LQ_TRY(ritz_rotate(c, l, w.Yw, w.Yw2, pl.strideYw, w.Bw, w.Bw2, pl.strideBw, c.at<double>(pl.lam), batch));
@@ -279,12 +311,39 @@ static int setup_common(Ctx& c, const float* W, const float* row_w, const float*
   LQ_TRY(device_tables(&c.tables));
   const Plan& pl = c.pl;
   c.sr = c.sc = c.rsr = c.rsc = nullptr;
+  c.a_scale = 1.0f;
   c.lam_cold = c.at<double>(pl.lam_cold);
   if (c.weighted) {
     c.sr = c.at<float>(pl.sr); c.sc = c.at<float>(pl.sc); c.rsr = c.at<float>(pl.rsr); c.rsc = c.at<float>(pl.rsc);
     LQ_TRY(launch_sqrt_vecs(row_w, pl.d, c.at<float>(pl.sr), c.at<float>(pl.rsr), st));
     LQ_TRY(launch_sqrt_vecs(col_w, pl.k, c.at<float>(pl.sc), c.at<float>(pl.rsc), st));
   }
+  return LQ_OK;
+}
+
+// Power of two that puts the entries of D_row (W - Q) D_col in the middle of the fp16 range: the largest |w| times the
+// largest square roots of the weights lands in [2^9, 2^10), which leaves a factor of 64 for |W - Q| to exceed |W| by
+// (beyond that the residual kernel saturates) and keeps everything above 2^-24 of the largest entry a normal number.
+// Synchronizes the stream.
+static int residual_scale(Ctx& c) {
+  const Plan& pl = c.pl;
+  if (pl.prm.prec != 2) return LQ_OK;
+  float* scratch = c.at<float>(pl.gram_part);
+  LQ_TRY(launch_absmax(c.W, pl.n, scratch, c.st));
+  if (c.weighted) {
+    LQ_TRY(launch_absmax(c.sr, pl.d, scratch + 1056, c.st));
+    LQ_TRY(launch_absmax(c.sc, pl.k, scratch + 2112, c.st));
+  }
+  float m[3] = {0.f, 1.f, 1.f};
+  LQ_HIP_TRY(hipMemcpyAsync(&m[0], scratch + 1024, sizeof(float), hipMemcpyDeviceToHost, c.st));
+  if (c.weighted) {
+    LQ_HIP_TRY(hipMemcpyAsync(&m[1], scratch + 1056 + 1024, sizeof(float), hipMemcpyDeviceToHost, c.st));
+    LQ_HIP_TRY(hipMemcpyAsync(&m[2], scratch + 2112 + 1024, sizeof(float), hipMemcpyDeviceToHost, c.st));
+  }
+  LQ_HIP_TRY(hipStreamSynchronize(c.st));
+  const double top = (double)m[0] * m[1] * m[2];
+  c.a_scale = (top > 0.0 && std::isfinite(top)) ? (float)std::ldexp(1.0, 9 - std::ilogb(top)) : 1.0f;
+  if (!(c.a_scale > 0.0f) || !std::isfinite(c.a_scale)) c.a_scale = 1.0f;
   return LQ_OK;
 }
 
@@ -328,7 +387,7 @@ struct Loop {
   WideSet w;
   const float* Ycur = nullptr; const float* Bcur = nullptr;
   size_t sY = 0, sB = 0;
-  const double* lamcur = nullptr;
+  const double* lamcur = nullptr; size_t sLam = 0;   // Ritz values the rows of Bcur came with (stride per problem)
   double* errs = nullptr;
   double prev_eps = INFINITY;
   bool stopped = false;
@@ -394,7 +453,7 @@ struct Loop {
   void set_first(const float* Yfirst, const float* Bfirst) {
     Y1 = Yfirst; B1 = Bfirst;
     Ycur = Y1; Bcur = B1; sY = 0; sB = 0;
-    lamcur = c->lam_cold;
+    lamcur = c->lam_cold; sLam = 0;
   }
 
   // Q(0) = Quantize(W) (Section 3.1, footnote on the initialisation): quantizes W - 0 with the zeroed warm bases as
@@ -453,11 +512,16 @@ struct Loop {
       prev_eps = eps;
     }
     if (last) { stopped = true; return LQ_OK; }
-    a.R = c->at<float>(pl.R); a.strideR = pl.strideR;
+    a.strideR = pl.strideR;
+    if (pl.prm.prec == 2) {
+      a.R16 = c->at<uint16_t>(pl.R); a.R16lo = a.R16 + pl.strideR * (size_t)pl.batch; a.r_scale = c->a_scale;
+    }
+    else a.R = c->at<float>(pl.R);
     LQ_TRY(launch_residual(a, c->st));
-    LQ_TRY(warm_factorize(*c, w, Bcur, sB, t == 1 ? qw2 : qw, batch));
+    a.R16 = nullptr; a.R16lo = nullptr;
+    LQ_TRY(warm_factorize(*c, w, Bcur, sB, lamcur, sLam, t == 1 ? qw2 : qw, batch));
     Ycur = w.Yw; Bcur = w.Bw; sY = pl.strideYw; sB = pl.strideBw;
-    lamcur = c->at<double>(pl.lam);
+    lamcur = c->at<double>(pl.lam); sLam = pl.prm.lw;
 #ifdef LQ_TESTING_HOOKS
     LQ_TRY(capture_sigma(t));
 #endif
@@ -672,6 +736,7 @@ int lq_decompose(const float* W, int64_t d, int64_t k, int rank, lq_config cfg, 
   make_plan(d, k, rank, prm, 1, c.pl);
   LQ_TRY(check_workspace(workspace, workspace_bytes, c.pl.total));
   LQ_TRY(setup_common(c, W, row_w, col_w, workspace, (hipStream_t)stream));
+  LQ_TRY(residual_scale(c));
   const float* A0; const float* Y1; const float* B1;
   LoopOut direct{q_codes, q_scale_idx, q_v, Q_dense, L1, L2, sigma};
   std::vector<double> trace(iters, NAN);
@@ -748,6 +813,7 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
   LQ_TRY(check_workspace(workspace, workspace_bytes, slice * nsub));
   Ctx& c = cs[0];
   LQ_TRY(setup_common(c, W, row_w, col_w, workspace, (hipStream_t)stream));
+  LQ_TRY(residual_scale(c));
   const float* A0; const float* Y1; const float* B1;
   LQ_TRY(first_input(c, &A0));
   LQ_TRY(cold_factorize(c, A0, seed, &Y1, &B1));

@@ -41,6 +41,16 @@ int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, i
                           part_floats, (hipStream_t)stream, precision, workgroups);
 }
 
+int lq_test_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const uint16_t* A,
+                          const uint16_t* A_lo, int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
+                          float x_scale, const double* lam0, float out_scale, void* stream) {
+  if (!X || !A || !C) return LQ_ERR_NULL;
+  if (workgroups < -32768 || workgroups > 32768 || batch < 1) return LQ_ERR_ARG;
+  const size_t sA = (size_t)(mode == MODE_NT ? big : K) * lda;
+  return launch_wide_gemm_f16(mode, l, big, K, X, ldx, (size_t)l * ldx, A, A_lo, lda, sA, C, ldc, (size_t)l * ldc, batch, part,
+                              part_floats, x_scale, lam0, 1, out_scale, (hipStream_t)stream, workgroups);
+}
+
 size_t lq_test_wide_gemm_part_floats(int l, int workgroups) {
   if (l % 32 != 0 || l < 32 || l > 256) return 0;
   return gemm_part_floats(l, workgroups);

@@ -51,7 +51,12 @@ static const char* const kNames[NUM_CLASSES] = {
     "wide_gemm_kernel<5,0,1,1>", "wide_gemm_kernel<6,0,1,1>", "wide_gemm_kernel<7,0,1,1>", "wide_gemm_kernel<8,0,1,1>",
     "wide_gemm_kernel<1,1,2,1>", "wide_gemm_kernel<2,1,2,1>", "wide_gemm_kernel<3,1,2,1>", "wide_gemm_kernel<4,1,2,1>",
     "wide_gemm_kernel<5,1,1,1>", "wide_gemm_kernel<6,1,1,1>", "wide_gemm_kernel<7,1,1,1>", "wide_gemm_kernel<8,1,1,1>",
-    "qmatmul_kernel", "qmatvec_kernel", "split_project_kernel"};
+    "qmatmul_kernel", "qmatvec_kernel", "split_project_kernel",
+    "wide_gemm_f16_kernel<1,0,1>", "wide_gemm_f16_kernel<2,0,1>", "wide_gemm_f16_kernel<3,0,1>", "wide_gemm_f16_kernel<4,0,1>",
+    "wide_gemm_f16_kernel<1,1,1>", "wide_gemm_f16_kernel<2,1,1>", "wide_gemm_f16_kernel<3,1,1>", "wide_gemm_f16_kernel<4,1,1>",
+    "wide_gemm_f16_kernel<1,0,2>", "wide_gemm_f16_kernel<2,0,2>", "wide_gemm_f16_kernel<3,0,2>", "wide_gemm_f16_kernel<4,0,2>",
+    "wide_gemm_f16_kernel<1,1,2>", "wide_gemm_f16_kernel<2,1,2>", "wide_gemm_f16_kernel<3,1,2>", "wide_gemm_f16_kernel<4,1,2>",
+    "absmax_kernel"};
 
 }  // namespace prof
 }  // namespace lq

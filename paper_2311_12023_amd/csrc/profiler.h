@@ -23,7 +23,9 @@ enum Cls {
   QMATMUL = 43,             // qmatmul_kernel (work = flops of the product)
   QMATVEC = 44,             // qmatvec_kernel (work = bytes)
   SPLIT_PROJECT = 45,       // split_project_kernel (work = bytes)
-  NUM_CLASSES = 46
+  GEMM_F16_BASE = 46,       // + planes * 8 + mode * 4 + (l/32 - 1): wide_gemm_f16_kernel (work = flops of the product)
+  ABSMAX = 62,
+  NUM_CLASSES = 63
 };
 
 bool enabled();

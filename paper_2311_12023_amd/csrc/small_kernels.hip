@@ -604,6 +604,39 @@ __global__ __launch_bounds__(256) void gaussian_fill_kernel(float* __restrict__ 
   }
 }
 
+// Largest finite |x[i]|: 1024 workgroups leave their maxima in out[0..1023], then one workgroup reduces them into
+// out[1024] (two launches; a maximum does not depend on the order it is taken in).
+__global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x, int64_t n, float* __restrict__ out,
+                                                     int stage) {
+  __shared__ float s_max[256];
+  const int tid = threadIdx.x;
+  float m = 0.0f;
+  if (stage == 0) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + tid; i < n; i += (int64_t)gridDim.x * 256) {
+      const float a = fabsf(x[i]);
+      if (a < __builtin_inff()) m = fmaxf(m, a);     // false for NaN as well
+    }
+  } else {
+    for (int i = tid; i < 1024; i += 256) m = fmaxf(m, out[i]);
+  }
+  s_max[tid] = m;
+  __syncthreads();
+  for (int w = 128; w >= 1; w >>= 1) {
+    if (tid < w) s_max[tid] = fmaxf(s_max[tid], s_max[tid + w]);
+    __syncthreads();
+  }
+  if (tid == 0) out[stage == 0 ? blockIdx.x : 1024] = s_max[0];
+}
+
+int launch_absmax(const float* x, int64_t n, float* out, hipStream_t st) {
+  prof::Scope ps(prof::ABSMAX, st, (double)n * 4.0);
+  hipLaunchKernelGGL(absmax_kernel, dim3(1024), dim3(256), 0, st, x, n, out, 0);
+  LQ_HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(absmax_kernel, dim3(1), dim3(256), 0, st, x, n, out, 1);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
 // X <- X - alpha * Y over `count` floats (count a multiple of 4).
 __global__ __launch_bounds__(256) void axpy_sub_kernel(float* __restrict__ X, const float* __restrict__ Y, float alpha,
                                                        int64_t count4) {

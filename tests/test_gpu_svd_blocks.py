@@ -64,6 +64,59 @@ def test_wide_gemm(env, mode, l, big, K, batch, wgs, precision):
     assert rc == 0 and torch.equal(ct, ct2)
 
 
+def up64(x):
+    return (x + 63) // 64 * 64
+
+
+# The products against an fp16 operand (the warm iterations' residual): ragged against the 256-column tiles and the
+# 64-deep steps, cut and uncut reductions, fixed and data-derived scaling of X.  The reference multiplies the very same
+# fp16 values in fp64, so what is left is the fp16 hi/lo split of X (about 2^-21 relative) and fp32 accumulation.
+@pytest.mark.parametrize("mode,l,big,K,batch,wgs", [
+    (0, 32, 200, 160, 1, None), (0, 64, 768, 768, 1, 5), (0, 96, 130, 1040, 3, 7), (0, 96, 1000, 4096, 1, 0),
+    (0, 96, 1500, 704, 5, 20), (0, 96, 1500, 704, 1, 1), (0, 96, 520, 4096, 1, 64), (0, 96, 300, 1000, 7, 6),
+    (1, 32, 208, 150, 1, None), (1, 64, 768, 768, 1, 5), (1, 96, 1040, 131, 3, 7), (1, 96, 4096, 1000, 1, 0),
+    (1, 96, 1500, 700, 5, 20), (1, 96, 520, 4096, 1, 64), (1, 96, 300, 1000, 7, 6), (1, 64, 96, 33, 1, None)])
+@pytest.mark.parametrize("scaling,planes", [("fixed", 1), ("lam", 1), ("fixed", 2)])
+def test_wide_gemm_f16(env, mode, l, big, K, batch, wgs, scaling, planes):
+    torch, lq, L = env
+    rng = np.random.default_rng(l * 11 + big + mode)
+    ldx = up64(K)
+    x = np.zeros((batch, l, ldx), np.float32)
+    x[:, :, :K] = rng.standard_normal((batch, l, K)) * (37.0 if scaling == "lam" else 0.02)
+    a32 = (rng.standard_normal((batch, big, K) if mode == 0 else (batch, K, big)) * 3.0).astype(np.float32)
+    a = a32.astype(np.float16)
+    alo = (a32 - a.astype(np.float32)).astype(np.float16)       # planes == 2: the product is taken with a + alo
+    ldc = up32(big)
+    xt, at, alt = torch.from_numpy(x).cuda(), torch.from_numpy(a).cuda(), torch.from_numpy(alo).cuda()
+    ct = torch.full((batch, l, ldc), 7.0, dtype=torch.float32, device="cuda")
+    nfl = 0 if wgs is None else L.lq_test_wide_gemm_part_floats(l, wgs)
+    part = torch.full((max(nfl, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    lam = torch.from_numpy(np.max(np.sum(x.astype(np.float64) ** 2, axis=2), axis=1)).cuda()     # per problem
+    out_scale = 0.25
+
+    def run(dst):
+        rc = L.lq_test_wide_gemm_f16(mode, l, big, K, xt.data_ptr(), ldx, at.data_ptr(),
+                                     alt.data_ptr() if planes == 2 else None, a.shape[2], dst.data_ptr(), ldc,
+                                     batch, wgs or 0, part.data_ptr() if nfl else None, nfl, 64.0,
+                                     lam.data_ptr() if scaling == "lam" else None, out_scale, None)
+        assert rc == 0
+        torch.cuda.synchronize()
+
+    run(ct)
+    got = ct.cpu().numpy()
+    a64 = a.astype(np.float64) + (alo.astype(np.float64) if planes == 2 else 0.0)
+    ref = np.matmul(x[:, :, :K].astype(np.float64), a64.transpose(0, 2, 1) if mode == 0 else a64) * out_scale
+    if scaling == "fixed":
+        ref *= 64.0
+    err = np.abs(got[:, :, :big] - ref)
+    assert err.max() < 2e-5 * np.abs(ref).max(), (err.max(), np.abs(ref).max())
+    assert np.sqrt(np.mean(err ** 2)) < 2e-6 * np.sqrt(np.mean(ref ** 2))
+    assert np.all(got[:, :, big:] == 7.0)           # columns past the matrix are never written
+    ct2 = torch.full((batch, l, ldc), 7.0, dtype=torch.float32, device="cuda")
+    run(ct2)
+    assert torch.equal(ct, ct2)
+
+
 @pytest.mark.parametrize("use_alt", [True, False])
 @pytest.mark.parametrize("l,m", [(32, 100), (64, 768), (96, 4096), (128, 1000), (256, 2048)])
 def test_orthonormalize(env, l, m, use_alt):

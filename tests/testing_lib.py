@@ -19,6 +19,8 @@ def load():
         L = C.CDLL(TEST_LIB)
         vp, i64, it = C.c_void_p, C.c_int64, C.c_int
         L.lq_test_wide_gemm.argtypes = [it, it, i64, i64, vp, i64, vp, i64, vp, i64, it, it, vp, C.c_size_t, it, vp]
+        L.lq_test_wide_gemm_f16.argtypes = [it, it, i64, i64, vp, i64, vp, vp, i64, vp, i64, it, it, vp, C.c_size_t,
+                                            C.c_float, vp, C.c_float, vp]
         L.lq_test_wide_gemm_part_floats.restype = C.c_size_t
         L.lq_test_wide_gemm_part_floats.argtypes = [it, it]
         L.lq_test_orthonormalize.argtypes = [vp, it, i64, i64, vp, vp, vp]
