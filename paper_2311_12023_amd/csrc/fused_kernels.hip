@@ -76,19 +76,20 @@ int launch_pack_factors(const PhaseArgs& a, hipStream_t st) {
   return LQ_OK;
 }
 
-// Stores the 4 codes of one quad.  2, 4, 8 bits: 1, 2, 4 bytes per lane, contiguous across lanes.  3 bits: the
-// four lanes of a 16-weight run gather their 12-bit pieces into the run's 48-bit word and three of them store
-// 16 bits each.  All 64 lanes must call (cross-lane exchange inside).
+// Stores the 4 codes of one quad.  `base`: address of the codes of a quad whose index is a multiple of 4 (uniform across
+// the wavefront in phase 1), `lq`: this lane's quad index relative to it.  2, 4, 8 bits: 1, 2, 4 bytes per lane,
+// contiguous across lanes.  3 bits: the four lanes of a 16-weight run gather their 12-bit pieces into the run's 48-bit
+// word and three of them store 16 bits each.  All 64 lanes must call (cross-lane exchange inside).
 template <int BITS>
-__device__ __forceinline__ void store_quad_codes(uint8_t* __restrict__ codes, int64_t quad, const uint32_t (&c)[4],
+__device__ __forceinline__ void store_quad_codes(uint8_t* __restrict__ base, uint32_t lq, const uint32_t (&c)[4],
                                                  bool live) {
   const uint32_t w = c[0] | (c[1] << BITS) | (c[2] << (2 * BITS)) | (c[3] << (3 * BITS));
   if constexpr (BITS == 8) {
-    if (live) *reinterpret_cast<uint32_t*>(codes + quad * 4) = w;
+    if (live) *reinterpret_cast<uint32_t*>(base + lq * 4u) = w;
   } else if constexpr (BITS == 4) {
-    if (live) *reinterpret_cast<uint16_t*>(codes + quad * 2) = (uint16_t)w;
+    if (live) *reinterpret_cast<uint16_t*>(base + lq * 2u) = (uint16_t)w;
   } else if constexpr (BITS == 2) {
-    if (live) codes[quad] = (uint8_t)w;
+    if (live) base[lq] = (uint8_t)w;
   } else {
     const int sub = threadIdx.x & 3;
     uint32_t lo = sub < 2 ? (w << (12 * sub)) : (sub == 2 ? (w << 24) : 0u);        // bits 0..31 of the run word
@@ -97,73 +98,142 @@ __device__ __forceinline__ void store_quad_codes(uint8_t* __restrict__ codes, in
     lo |= dpp_move_u32<DPP_QUAD_XOR2>(lo); hi |= dpp_move_u32<DPP_QUAD_XOR2>(hi);
     if (live && sub < 3) {
       const uint16_t piece = sub == 0 ? (uint16_t)lo : (sub == 1 ? (uint16_t)(lo >> 16) : (uint16_t)hi);
-      *reinterpret_cast<uint16_t*>(codes + (quad >> 2) * 6 + 2 * sub) = piece;
+      *reinterpret_cast<uint16_t*>(base + (lq >> 2) * 6u + 2u * sub) = piece;
     }
   }
 }
 
+// Code search of phase 1.  One 16-byte LDS entry per bucket j = floor((x + 1) * 256), j = 0..513 (x lies in
+// [-1, 1] up to rounding; the index is clamped all the same): {thr[c0], c0, thr[c0 + 1]} with c0 = the number of
+// thresholds safely below the bucket.  The code of x is c0 + (x >= thr[c0]) (+ (x >= thr[c0 + 1]) for 8 bits, where two
+// thresholds can fall into one bucket): one LDS read and one or two comparisons per weight for every bit width.
+struct SearchEntry { float ta; uint32_t c0; float tb; uint32_t pad; };
+constexpr int SEARCH_ENTRIES = 514;
+
+__device__ __forceinline__ void build_search_nosync(const DevTables* __restrict__ tab, int slot, SearchEntry* s_search) {
+  for (int j = threadIdx.x; j < SEARCH_ENTRIES; j += blockDim.x) {
+    const uint32_t c0 = tab->lut[slot][j < 511 ? j : 511];
+    SearchEntry e;
+    e.ta = tab->thr[slot][c0]; e.c0 = c0; e.tb = tab->thr[slot][c0 + 1]; e.pad = 0;
+    s_search[j] = e;
+  }
+}
+
+template <int BITS>
+__device__ __forceinline__ uint32_t search_code(const SearchEntry* s_search, float x) {
+  int j = (int)fmaf(x, 256.0f, 256.0f);                         // NaN -> 0
+  j = j < 0 ? 0 : (j > SEARCH_ENTRIES - 1 ? SEARCH_ENTRIES - 1 : j);
+  if constexpr (BITS == 8) {
+    const float4 e = *reinterpret_cast<const float4*>(s_search + j);
+    return __float_as_uint(e.y) + ((x >= e.x) ? 1u : 0u) + ((x >= e.z) ? 1u : 0u);
+  } else {
+    const float2 e = *reinterpret_cast<const float2*>(s_search + j);
+    return __float_as_uint(e.y) + ((x >= e.x) ? 1u : 0u);
+  }
+}
+
+// max |t| of a quad, as the bit pattern of a non-negative float (unsigned order = numeric order).
+__device__ __forceinline__ uint32_t quad_absmax_bits(const float (&t)[4]) {
+  float m;
+  asm("v_max3_f32 %0, |%1|, |%2|, |%3|\n\tv_max_f32 %0, |%4|, %0" : "=&v"(m) : "v"(t[0]), "v"(t[1]), "v"(t[2]), "v"(t[3]));
+  return __float_as_uint(m);
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t umax_dpp(uint32_t x) {
+  const uint32_t y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, 0xf, 0xf, false);
+  return x > y ? x : y;
+}
+// Maximum over the QPB consecutive lanes that hold one block (see group_max_lanes), on bit patterns.
+template <int QPB>
+__device__ __forceinline__ uint32_t block_umax(uint32_t x) {
+  x = umax_dpp<DPP_QUAD_XOR1>(x);
+  x = umax_dpp<DPP_QUAD_XOR2>(x);
+  if constexpr (QPB >= 8) x = umax_dpp<DPP_ROW_HALF_MIRROR>(x);
+  if constexpr (QPB >= 16) x = umax_dpp<DPP_ROW_MIRROR>(x);
+  if constexpr (QPB >= 32) { const uint32_t y = (uint32_t)__shfl_xor((int)x, 16); x = x > y ? x : y; }
+  return x;
+}
+
 // Epilogue of phase 1 in quad layout: lane `tid` handles quads tid, tid+512, ... of the 64 x 128 tile (32 quads
 // per row), so W loads, LDS reads of the product and code stores are all contiguous across lanes.  QPB = B0/4
-// lanes hold one block.
+// lanes hold one block.  The four quads of a lane lie in four different blocks; their block maxima are found first,
+// then one division serves all four (lane i of every hardware quad divides for quad i, the quotients go back by quad
+// broadcasts: the four lanes of a hardware quad always share their blocks), then the codes.
 template <int BITS, int QPB, bool WITH_ERR>
-__device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const float* pt, const LdsTables& s_tab,
-                                                int64_t r0, int64_t c0, const float4 (&wreg)[4]) {
-  Thresholds<BITS> thr(s_tab);
-  const float* s_code = s_tab.code;
+__device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const float* pt, const SearchEntry* s_search,
+                                                const float* s_code, int64_t r0, int64_t c0, const float4 (&wreg)[4]) {
   const int tid = threadIdx.x;
   uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
   BlockRec* blk = a.blk + (size_t)z * a.strideBlk;
-  // quad index of this lane's first quad; the next ones are NTHR1 / 32 rows further down
-  const int64_t quad0 = ((r0 + (tid >> 5)) * a.k + c0 + 4 * (tid & 31)) >> 2, quad_step = (NTHR1 / 32) * (a.k >> 2);
+  // quad indices: a uniform part per quad u (first quad of the tile, NTHR1 / 32 rows further down for each u) plus a
+  // 32-bit lane part; both are multiples of QPB where a block starts, so block indices split the same way
+  const int cq = tid & 31;
+  const int64_t col = c0 + 4 * cq;
+  const int64_t tq0 = (r0 * a.k + c0) >> 2, quad_step = (NTHR1 / 32) * (a.k >> 2);
+  const uint32_t lq = (uint32_t)((tid >> 5) * (a.k >> 2) + cq);
+  constexpr int CODE_BYTES_X2 = BITS;            // bytes per quad = BITS / 2
+  const bool col_live = col < a.k;
+  float4 rc = make_float4(1.f, 1.f, 1.f, 1.f), cw = make_float4(1.f, 1.f, 1.f, 1.f);
+  if (a.rsc && col_live) {
+    rc = *reinterpret_cast<const float4*>(a.rsc + col);
+    if (WITH_ERR) cw = *reinterpret_cast<const float4*>(a.col_w + col);
+  }
+  float t[4][4];
+  uint32_t mbits[4];
+  bool live[4];
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
-    const int qid = tid + NTHR1 * u;
-    const int lr = qid >> 5, cq = qid & 31;
-    const int64_t row = r0 + lr, col = c0 + 4 * cq;
-    const bool live = row < a.d && col < a.k;
+    const int lr = (tid >> 5) + (NTHR1 / 32) * u;
+    const int64_t row = r0 + lr;
+    live[u] = row < a.d && col_live;
     const float4 p = *reinterpret_cast<const float4*>(pt + lr * PP + 4 * cq);
-    float t[4] = {0.f, 0.f, 0.f, 0.f}, w[4] = {0.f, 0.f, 0.f, 0.f};
-    if (live) {
-      float pv[4] = {p.x, p.y, p.z, p.w};
-      const float fv[4] = {wreg[u].x, wreg[u].y, wreg[u].z, wreg[u].w};
-      if (a.rsc) {
-        const float rs = a.rsr[row];
-        const float4 rc = *reinterpret_cast<const float4*>(a.rsc + col);
-        pv[0] *= rs * rc.x; pv[1] *= rs * rc.y; pv[2] *= rs * rc.z; pv[3] *= rs * rc.w;
-        if (WITH_ERR) {
-          const float4 cw = *reinterpret_cast<const float4*>(a.col_w + col);
-          w[0] = cw.x; w[1] = cw.y; w[2] = cw.z; w[3] = cw.w;
-        }
-      } else {
-        w[0] = w[1] = w[2] = w[3] = 1.0f;
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) t[e] = fv[e] - pv[e];
+    float pv[4] = {p.x, p.y, p.z, p.w};
+    const float fv[4] = {wreg[u].x, wreg[u].y, wreg[u].z, wreg[u].w};
+    if (a.rsc) {
+      const float rs = live[u] ? a.rsr[row] : 0.0f;
+      pv[0] *= rs * rc.x; pv[1] *= rs * rc.y; pv[2] *= rs * rc.z; pv[3] *= rs * rc.w;
     }
-    const float amax = group_max_lanes<QPB>(fmaxf(fmaxf(fabsf(t[0]), fabsf(t[1])), fmaxf(fabsf(t[2]), fabsf(t[3]))));
-    const float rcp = safe_reciprocal(amax);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t[u][e] = live[u] ? fv[e] - pv[e] : 0.0f;
+    mbits[u] = block_umax<QPB>(quad_absmax_bits(t[u]));
+  }
+  // lane i of each hardware quad divides for quad i
+  const int sub = tid & 3;
+  const uint32_t mine = sub == 0 ? mbits[0] : sub == 1 ? mbits[1] : sub == 2 ? mbits[2] : mbits[3];
+  const int rmine = (int)__float_as_uint(safe_reciprocal(__uint_as_float(mine)));
+  const float rcp[4] = {__int_as_float(__builtin_amdgcn_mov_dpp(rmine, 0x00, 0xf, 0xf, true)),
+                        __int_as_float(__builtin_amdgcn_mov_dpp(rmine, 0x55, 0xf, 0xf, true)),
+                        __int_as_float(__builtin_amdgcn_mov_dpp(rmine, 0xAA, 0xf, 0xf, true)),
+                        __int_as_float(__builtin_amdgcn_mov_dpp(rmine, 0xFF, 0xf, 0xf, true))};
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const float amax = __uint_as_float(mbits[u]);
     uint32_t c[4];
     float e2 = 0.f, eq = 0.f, q2 = 0.f;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      c[e] = thr.nearest(t[e] * rcp);
+      c[e] = search_code<BITS>(s_search, t[u][e] * rcp[u]);
       if (WITH_ERR) {
+        const float w = a.rsc ? (e == 0 ? cw.x : e == 1 ? cw.y : e == 2 ? cw.z : cw.w) : 1.0f;
         const float q = s_code[c[e]];
-        const float err = t[e] - q * amax;
-        e2 = fmaf(w[e] * err, err, e2);
-        eq = fmaf(w[e] * err, q, eq);
-        q2 = fmaf(w[e] * q, q, q2);
+        const float err = t[u][e] - q * amax;
+        e2 = fmaf(w * err, err, e2);
+        eq = fmaf(w * err, q, eq);
+        q2 = fmaf(w * q, q, q2);
       }
     }
-    if (WITH_ERR) { e2 = group_sum_lanes<QPB>(e2); eq = group_sum_lanes<QPB>(eq); q2 = group_sum_lanes<QPB>(q2); }
-    const int64_t quad = quad0 + (int64_t)u * quad_step;
-    store_quad_codes<BITS>(codes, quad, c, live);
-    if (live && (cq & (QPB - 1)) == 0) {
+    if (WITH_ERR) {
+      if (!live[u]) { e2 = 0.f; eq = 0.f; q2 = 0.f; }
+      e2 = group_sum_lanes<QPB>(e2); eq = group_sum_lanes<QPB>(eq); q2 = group_sum_lanes<QPB>(q2);
+    }
+    const int64_t quad_u = tq0 + (int64_t)u * quad_step;                   // uniform
+    store_quad_codes<BITS>(codes + ((quad_u * CODE_BYTES_X2) >> 1), lq, c, live[u]);
+    if (live[u] && (cq & (QPB - 1)) == 0) {
       if (WITH_ERR) {
         BlockRec rec; rec.s = amax; rec.e2 = e2; rec.eq = eq; rec.q2 = q2;
-        blk[quad / QPB] = rec;
+        (blk + quad_u / QPB)[lq / QPB] = rec;
       } else {
-        reinterpret_cast<float*>(blk)[quad / QPB] = amax;     // without error sums a record is the absmax alone
+        (reinterpret_cast<float*>(blk) + quad_u / QPB)[lq / QPB] = amax;   // without error sums a record is the absmax alone
       }
     }
   }
@@ -171,13 +241,13 @@ __device__ __forceinline__ void phase1_epilogue(const PhaseArgs& a, int z, const
 
 template <int BITS, bool WITH_ERR>
 __device__ __forceinline__ void phase1_dispatch_block(const PhaseArgs& a, int block, int z, const float* pt,
-                                                      const LdsTables& s_tab, int64_t r0, int64_t c0,
-                                                      const float4 (&wreg)[4]) {
+                                                      const SearchEntry* s_search, const float* s_code, int64_t r0,
+                                                      int64_t c0, const float4 (&wreg)[4]) {
   switch (block) {
-    case 16: phase1_epilogue<BITS, 4, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
-    case 32: phase1_epilogue<BITS, 8, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
-    case 64: phase1_epilogue<BITS, 16, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
-    default: phase1_epilogue<BITS, 32, WITH_ERR>(a, z, pt, s_tab, r0, c0, wreg); break;
+    case 16: phase1_epilogue<BITS, 4, WITH_ERR>(a, z, pt, s_search, s_code, r0, c0, wreg); break;
+    case 32: phase1_epilogue<BITS, 8, WITH_ERR>(a, z, pt, s_search, s_code, r0, c0, wreg); break;
+    case 64: phase1_epilogue<BITS, 16, WITH_ERR>(a, z, pt, s_search, s_code, r0, c0, wreg); break;
+    default: phase1_epilogue<BITS, 32, WITH_ERR>(a, z, pt, s_search, s_code, r0, c0, wreg); break;
   }
 }
 
@@ -194,7 +264,8 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a, 
   constexpr int SMEM_FLOATS = SPLIT ? ((2 * (TM + TN) * KP * 2 + 3) / 4 > TM * PP ? (2 * (TM + TN) * KP * 2 + 3) / 4 : TM * PP)
                                     : TM * PP;
   __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
-  __shared__ LdsTables s_tab;
+  __shared__ __attribute__((aligned(16))) SearchEntry s_search[SEARCH_ENTRIES];
+  __shared__ float s_code[WITH_ERR ? 256 : 1];
   float* pt = smem;
   static_assert(KC * TM + KC * TN <= TM * PP, "operand chunks must fit in the product tile");
   const int tid = threadIdx.x;
@@ -207,16 +278,23 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a, 
   const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
   const int wr = wave >> 2, wc = wave & 3;      // 2 x 4 grid of 32x32 tiles
 
-  // code-book tables of this problem's bit width (visible after the barriers of the product stage)
-  load_tables_slot_nosync(a.tables, pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3, s_tab);
-  // this lane's 4 quads of W, fetched now so that the loads overlap the MFMA stage
+  // search table (and, for the error sums, the code book) of this problem's bit width, visible after the barriers of
+  // the product stage
+  const int slot = pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3;
+  build_search_nosync(a.tables, slot, s_search);
+  if constexpr (WITH_ERR)
+    for (int i = tid; i < 256; i += NTHR1) s_code[i] = a.tables->code[slot][i];
+  // this lane's 4 quads of W, fetched now so that the loads overlap the MFMA stage.  Addresses are a uniform base per
+  // quad plus one 32-bit lane offset (rows of a tile are at most 63 apart).
   float4 wreg[4];
+  const uint32_t w_lane = (uint32_t)(((tid >> 5) * a.k + 4 * (tid & 31)) * 4);
+  const bool w_col_live = c0 + 4 * (tid & 31) < a.k;
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
-    const int qid = tid + NTHR1 * u;
-    const int64_t row = r0 + (qid >> 5), col = c0 + 4 * (qid & 31);
-    wreg[u] = (row < a.d && col < a.k) ? *reinterpret_cast<const float4*>(a.W + (size_t)row * a.k + col)
-                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+    const int64_t row_u = r0 + (NTHR1 / 32) * u;                       // uniform
+    const char* base = reinterpret_cast<const char*>(a.W + (size_t)row_u * a.k + c0);
+    wreg[u] = (row_u + (tid >> 5) < a.d && w_col_live) ? *reinterpret_cast<const float4*>(base + w_lane)
+                                                         : make_float4(0.f, 0.f, 0.f, 0.f);
   }
 
   floatx16 acc;
@@ -229,22 +307,26 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a, 
     const int64_t dpad = (a.d + TM - 1) / TM * TM, kpad = (a.k + TN - 1) / TN * TN;
     const __bf16* gy = reinterpret_cast<const __bf16*>(a.packed) + (size_t)z * a.stridePacked;
     const __bf16* gb = gy + (size_t)2 * dpad * rk;
-    // piece idx = tid + 512 i, i < 6: 16 bytes (8 reduction indices) of one row of one plane
+    // piece idx = tid + 512 i, i < 6: 16 bytes (8 reduction indices) of one row of one plane.  Rows tid / 8 + 64 i of the
+    // stacked planes [Yh | Yl | Bh | Bl]: piece i always falls into the same plane, at row (tid / 8) (+ 64 for the second
+    // half of a B plane), so its address is a uniform base plus the lane offset all pieces share.
     constexpr int PIECES = 2 * (TM + TN) * (KC2 / 8) / NTHR1;
+    static_assert(PIECES == 6 && TM == 64 && TN == 128 && NTHR1 == 512, "piece-to-plane map below");
     floatx4 st[PIECES];
     const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t p_lane = (uint32_t)(((tid >> 3) * rk + 8 * (tid & 7)) * 2);
+    const char* pbase[PIECES] = {
+        reinterpret_cast<const char*>(gy + (size_t)r0 * rk),                   // Y hi
+        reinterpret_cast<const char*>(gy + (size_t)(dpad + r0) * rk),          // Y lo
+        reinterpret_cast<const char*>(gb + (size_t)c0 * rk),                   // B hi, rows 0..63
+        reinterpret_cast<const char*>(gb + (size_t)(c0 + 64) * rk),            // B hi, rows 64..127
+        reinterpret_cast<const char*>(gb + (size_t)(kpad + c0) * rk),          // B lo, rows 0..63
+        reinterpret_cast<const char*>(gb + (size_t)(kpad + c0 + 64) * rk)};    // B lo, rows 64..127
     auto fetch_planes = [&](int k0) {
+      const bool ok = k0 + 8 * (tid & 7) < rk;
 #pragma unroll
-      for (int i = 0; i < PIECES; ++i) {
-        const int idx = tid + NTHR1 * i;
-        const int q = idx & 7, rowall = idx >> 3;            // rowall: 0..TM-1 Yh, TM..2TM-1 Yl, then TN Bh, TN Bl
-        const bool isy = rowall < 2 * TM;
-        const int rr = isy ? rowall : rowall - 2 * TM;
-        const int rows = isy ? TM : TN;
-        const int plane = rr >= rows ? 1 : 0, row = rr - plane * rows;
-        const __bf16* g = isy ? gy + ((size_t)plane * dpad + r0 + row) * rk : gb + ((size_t)plane * kpad + c0 + row) * rk;
-        st[i] = (k0 + 8 * q < rk) ? *reinterpret_cast<const floatx4*>(g + k0 + 8 * q) : zero4;
-      }
+      for (int i = 0; i < PIECES; ++i)
+        st[i] = ok ? *reinterpret_cast<const floatx4*>(pbase[i] + p_lane + 2 * k0) : zero4;
     };
     fetch_planes(0);
     for (int k0 = 0; k0 < rk; k0 += KC2) {
@@ -330,23 +412,160 @@ __global__ __launch_bounds__(NTHR1) void lowrank_blockquant_kernel(PhaseArgs a, 
   }
   __syncthreads();
   switch (pr.cfg.bits) {
-    case 2: phase1_dispatch_block<2, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
-    case 3: phase1_dispatch_block<3, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
-    case 4: phase1_dispatch_block<4, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
-    default: phase1_dispatch_block<8, WITH_ERR>(a, pr.cfg.block, z, pt, s_tab, r0, c0, wreg); break;
+    case 2: phase1_dispatch_block<2, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wreg); break;
+    case 3: phase1_dispatch_block<3, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wreg); break;
+    case 4: phase1_dispatch_block<4, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wreg); break;
+    default: phase1_dispatch_block<8, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wreg); break;
+  }
+}
+
+// The split-precision variant used by default: a workgroup keeps the planes of one 128-column stretch of B in LDS and
+// walks `nb` consecutive 64-row bands of W with them, so the B planes (half of what a tile needs from memory) are
+// fetched once per `nb` tiles, and the W quads and Y planes of band i + 1 are fetched while band i is being quantized.
+// Launch: one-dimensional, batch * units8 workgroups, units = column stretches x groups of bands, rounded up to a
+// multiple of 8; index decoded as (unit mod 8, problem, unit div 8) so that the problems of a batch that share a
+// stretch of W run on one XCD at the same time.
+template <bool WITH_ERR>
+__global__ __launch_bounds__(NTHR1) void lowrank_blockquant_bands_kernel(PhaseArgs a, int units, int tiles_n, int nb) {
+  constexpr int BPLANE = 2 * TN * KP;                     // bf16 elements: B hi, B lo
+  constexpr int YPLANE = 2 * TM * KP;                     // Y hi, Y lo; shares its space with the product tile
+  constexpr int PT_BYTES = TM * PP * 4 > YPLANE * 2 ? TM * PP * 4 : YPLANE * 2;
+  __shared__ __attribute__((aligned(16))) __bf16 s_b[BPLANE];
+  __shared__ __attribute__((aligned(16))) char s_yp[PT_BYTES];
+  __shared__ __attribute__((aligned(16))) SearchEntry s_search[SEARCH_ENTRIES];
+  __shared__ float s_code[WITH_ERR ? 256 : 1];
+  __bf16* s_y = reinterpret_cast<__bf16*>(s_yp);
+  float* pt = reinterpret_cast<float*>(s_yp);
+  const int tid = threadIdx.x;
+  const int slot8 = blockIdx.x >> 3;
+  const int z = slot8 % a.batch;
+  const int unit = (int)(blockIdx.x & 7) + 8 * (slot8 / a.batch);
+  if (unit >= units) return;                   // padding of the unit count to a multiple of 8
+  const LoopProblem pr = a.prob[z];
+  const int nbands = (int)((a.d + TM - 1) / TM);
+  const int band0 = (unit / tiles_n) * nb;
+  const int band1 = band0 + nb < nbands ? band0 + nb : nbands;
+  const int64_t c0 = (int64_t)(unit % tiles_n) * TN;
+  const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
+  const int wr = wave >> 2, wc = wave & 3;      // 2 x 4 grid of 32x32 tiles
+
+  const int slot = pr.cfg.bits == 2 ? 0 : pr.cfg.bits == 3 ? 1 : pr.cfg.bits == 4 ? 2 : 3;
+  build_search_nosync(a.tables, slot, s_search);
+  if constexpr (WITH_ERR)
+    for (int i = tid; i < 256; i += NTHR1) s_code[i] = a.tables->code[slot][i];
+
+  const int rk = (a.rank + 15) / 16 * 16;
+  const int64_t dpad = (a.d + TM - 1) / TM * TM, kpad = (a.k + TN - 1) / TN * TN;
+  const __bf16* gy = reinterpret_cast<const __bf16*>(a.packed) + (size_t)z * a.stridePacked;
+  const __bf16* gb = gy + (size_t)2 * dpad * rk;
+  const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  // lane parts of the addresses: 16-byte piece (tid & 7) of row tid / 8 of a plane; quad tid & 31 of row tid / 32 of W
+  const uint32_t p_lane = (uint32_t)(((tid >> 3) * rk + 8 * (tid & 7)) * 2);
+  const bool p_ok = 8 * (tid & 7) < rk;         // the rank fits one 64-deep chunk (checked by the launcher)
+  const uint32_t w_lane = (uint32_t)(((tid >> 5) * a.k + 4 * (tid & 31)) * 4);
+  const bool w_col_live = c0 + 4 * (tid & 31) < a.k;
+
+  // B planes of this column stretch: rows 0..63 and 64..127 of hi and of lo, one piece each per thread
+  {
+    const char* bbase[4] = {reinterpret_cast<const char*>(gb + (size_t)c0 * rk),
+                            reinterpret_cast<const char*>(gb + (size_t)(c0 + 64) * rk),
+                            reinterpret_cast<const char*>(gb + (size_t)(kpad + c0) * rk),
+                            reinterpret_cast<const char*>(gb + (size_t)(kpad + c0 + 64) * rk)};
+    floatx4 bp[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bp[i] = p_ok ? *reinterpret_cast<const floatx4*>(bbase[i] + p_lane) : zero4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<floatx4*>(s_b + (size_t)((tid >> 3) + 64 * i) * KP + 8 * (tid & 7)) = bp[i];
+  }
+
+  float4 wnext[4];
+  floatx4 ynext[2];
+  auto prefetch = [&](int band) {
+    const int64_t r0 = (int64_t)band * TM;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t row_u = r0 + (NTHR1 / 32) * u;                       // uniform
+      const char* base = reinterpret_cast<const char*>(a.W + (size_t)row_u * a.k + c0);
+      wnext[u] = (row_u + (tid >> 5) < a.d && w_col_live) ? *reinterpret_cast<const float4*>(base + w_lane)
+                                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    const char* ybase[2] = {reinterpret_cast<const char*>(gy + (size_t)r0 * rk),
+                            reinterpret_cast<const char*>(gy + (size_t)(dpad + r0) * rk)};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) ynext[i] = p_ok ? *reinterpret_cast<const floatx4*>(ybase[i] + p_lane) : zero4;
+  };
+  prefetch(band0);
+
+  for (int band = band0; band < band1; ++band) {
+    const int64_t r0 = (int64_t)band * TM;
+    __syncthreads();          // the previous band's epilogue is done with the product tile (first band: nothing)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      *reinterpret_cast<floatx4*>(s_y + (size_t)((tid >> 3) + 64 * i) * KP + 8 * (tid & 7)) = ynext[i];
+    float4 wcur[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) wcur[u] = wnext[u];
+    __syncthreads();          // Y planes (and, first band, B planes and tables) visible
+    if (band + 1 < band1) prefetch(band + 1);
+
+    floatx16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+    const __bf16* yh = s_y + (size_t)(32 * wr + ln) * KP + 8 * lh;
+    const __bf16* yl = yh + (size_t)TM * KP;
+    const __bf16* bh = s_b + (size_t)(32 * wc + ln) * KP + 8 * lh;
+    const __bf16* bl = bh + (size_t)TN * KP;
+#pragma unroll
+    for (int kg = 0; kg < KC2 / 16; ++kg) {
+      if (16 * kg < rk) {
+        const bf16x8 ah = *reinterpret_cast<const bf16x8*>(yh + 16 * kg), al = *reinterpret_cast<const bf16x8*>(yl + 16 * kg);
+        const bf16x8 vh = *reinterpret_cast<const bf16x8*>(bh + 16 * kg), vl = *reinterpret_cast<const bf16x8*>(bl + 16 * kg);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh, acc, 0, 0, 0);
+      }
+    }
+    __syncthreads();          // all reads of the Y planes done before the product overwrites them
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int row = 32 * wr + 8 * (e >> 2) + 4 * lh + (e & 3);
+      pt[row * PP + 32 * wc + ln] = acc[e];
+    }
+    __syncthreads();
+    switch (pr.cfg.bits) {
+      case 2: phase1_dispatch_block<2, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wcur); break;
+      case 3: phase1_dispatch_block<3, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wcur); break;
+      case 4: phase1_dispatch_block<4, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wcur); break;
+      default: phase1_dispatch_block<8, WITH_ERR>(a, pr.cfg.block, z, pt, s_search, s_code, r0, c0, wcur); break;
+    }
   }
 }
 
 int launch_lowrank_blockquant(const PhaseArgs& a, bool with_err, hipStream_t st) {
   const int tiles_n = (int)((a.k + TN - 1) / TN);
-  const int64_t tiles = (int64_t)tiles_n * ((a.d + TM - 1) / TM);
+  const int64_t nbands = (a.d + TM - 1) / TM;
+  const int64_t tiles = (int64_t)tiles_n * nbands;
   if ((tiles + 7) / 8 * 8 * a.batch >= (1ll << 31)) return LQ_ERR_SHAPE;
-  const dim3 grid((unsigned)((tiles + 7) / 8 * 8 * a.batch));
+  if (a.k > (1ll << 25)) return LQ_ERR_SHAPE;      // lane offsets within a tile (up to 63 rows apart) are 32-bit byte offsets
   // algorithmic bytes: W and the factors in, the quantized form out, per configuration (the scale part of the latter is
   // finished by the scale kernel that follows)
   prof::Scope ps(prof::LOWRANK_BLOCKQUANT, st,
                  (double)a.d * a.k * (4.0 * a.batch + a.quant_bytes_per_weight) + 4.0 * a.rank * (double)(a.d + a.k) * a.batch);
   const bool split = a.packed != nullptr;
+  if (split && a.rank <= KC2) {
+    // bands per workgroup: as many as leave a few thousand workgroups, at most 8
+    int64_t nb = tiles * a.batch / 4096;
+    nb = nb < 1 ? 1 : (nb > 8 ? 8 : nb);
+    if (nb > nbands) nb = nbands;
+    const int64_t units = (int64_t)tiles_n * ((nbands + nb - 1) / nb);
+    const dim3 grid((unsigned)((units + 7) / 8 * 8 * a.batch));
+    if (with_err) hipLaunchKernelGGL(lowrank_blockquant_bands_kernel<true>, grid, dim3(NTHR1), 0, st, a, (int)units, tiles_n, (int)nb);
+    else hipLaunchKernelGGL(lowrank_blockquant_bands_kernel<false>, grid, dim3(NTHR1), 0, st, a, (int)units, tiles_n, (int)nb);
+    LQ_HIP_TRY(hipGetLastError());
+    return LQ_OK;
+  }
+  const dim3 grid((unsigned)((tiles + 7) / 8 * 8 * a.batch));
   if (split) {
     if (with_err) hipLaunchKernelGGL((lowrank_blockquant_kernel<true, true>), grid, dim3(NTHR1), 0, st, a, (int)tiles, tiles_n);
     else hipLaunchKernelGGL((lowrank_blockquant_kernel<false, true>), grid, dim3(NTHR1), 0, st, a, (int)tiles, tiles_n);

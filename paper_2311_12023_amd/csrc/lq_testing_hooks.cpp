@@ -89,16 +89,13 @@ int lq_test_bucket_code(int bits, float x) {
   const int slot = bits_slot(bits);
   if (slot < 0) return -1;
   const HostTables& t = host_tables();
-  if (bits <= 3) {
-    int c = 0;
-    for (int i = 0; i < (1 << bits) - 1; ++i) c += x >= t.thr[slot][i];
-    return c;
-  }
+  // the search of the decomposition's quantize pass (search_code in fused_kernels.hip): bucket table, then one
+  // comparison (two for 8 bits); the stand-alone quantizer counts thresholds for 2 and 3 bits, which is the definition
   int j = (int)std::fmaf(x, 256.0f, 256.0f);
   if (!(std::fmaf(x, 256.0f, 256.0f) >= 0.0f)) j = 0;   // NaN and negatives as the device's conversion treats them
-  j = j < 0 ? 0 : (j > 511 ? 511 : j);
-  const int c0 = t.lut[slot][j];
-  if (bits == 4) return c0 + (x >= t.thr[slot][c0]);          // one threshold per bucket at most
+  j = j < 0 ? 0 : (j > 513 ? 513 : j);
+  const int c0 = t.lut[slot][j < 511 ? j : 511];
+  if (bits <= 4) return c0 + (x >= t.thr[slot][c0]);          // one threshold per bucket at most
   return c0 + (x >= t.thr[slot][c0]) + (x >= t.thr[slot][c0 + 1]);
 }
 
