@@ -266,6 +266,23 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The few-row forward product for callers that cannot allocate or size a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): Y = X (Q + L1 L2) as lq_matmul computes it for m <= 8 rows and
+ * rank <= 512 (plain fp32 on the vector ALU, deterministic), with the partial sums in a fixed array of
+ * lq_matmul_few_rows_static_scratch_bytes() = 4 MiB of device memory that the library owns (one copy per GPU, held until
+ * the process ends) instead of a caller's workspace.  The call allocates nothing and only enqueues kernels on `stream`.
+ * Arguments as for lq_matmul.  A shape whose partial sums do not fit (the LLaMA-2-7B shapes fit at 8 rows, 8192 x 8192
+ * at 4, 8192 x 28672 at 2) is refused with LQ_ERR_WORKSPACE before anything is launched; m > 8: LQ_ERR_SHAPE; rank > 512:
+ * LQ_ERR_RANK.  Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different streams or
+ * threads) race and must be serialized by the caller.  The array keeps the previous call's contents; the kernels write
+ * every partial sum they later read, so nothing needs clearing.
+ */
+size_t lq_matmul_few_rows_static_scratch_bytes(void);
+int lq_matmul_few_rows_static(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* codes_packed,
+                              const uint8_t* scale_idx, const float* v, lq_config c, const float* L1, const float* L2,
+                              int rank, float* Y, void* stream);
+
+/*
  * Per-kernel timing for benchmarks (off by default).  While enabled, every kernel launch of the library
  * is bracketed by two HIP events on the launch stream; lq_profile_read synchronizes the device and returns,
  * for one kernel class, the summed event time, the number of launches and the summed algorithmic work

@@ -1,5 +1,6 @@
 // C ABI of the forward product with a decomposed weight (Section 3.2 "Implementation", Appendix A).
 #include <algorithm>
+#include <mutex>
 
 #include "kernels.h"
 
@@ -55,6 +56,29 @@ static MatmulPlan plan_matmul(int64_t m, int64_t d, int64_t k, int rank) {
 static size_t plan_bytes(const MatmulPlan& p) {
   return 2 * up256(p.x_plane * 2) + up256(p.t_floats * 4) + 2 * up256(p.t_plane * 2) + up256(p.part_floats * 4) +
          up256(p.scale_floats * 4);
+}
+
+// Scratch of lq_matmul_few_rows_static: a fixed array in device memory (every GPU the library runs on holds its own copy
+// until the process ends).  Host code never uses the array's name as an address: the device address is looked up once per
+// device and kept.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64] = {nullptr};
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  LQ_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return LQ_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    LQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return LQ_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LQ_OK;
 }
 }  // namespace lq
 
@@ -135,6 +159,29 @@ int lq_matmul(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* co
   QmmPart q{xh, xl, d, codes_packed, bscale, c.bits, c.block};
   DensePart tl2{th, tl, rank > 0 ? p.r32 : 0, L2, k, rank, k};
   return launch_qmatmul(q, tl2, m, p.rows_pad, k, Y, k, part, p.part_floats, precision, st);
+}
+
+size_t lq_matmul_few_rows_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int lq_matmul_few_rows_static(const float* X, int64_t m, int64_t d, int64_t k, const uint8_t* codes_packed,
+                              const uint8_t* scale_idx, const float* v, lq_config c, const float* L1, const float* L2,
+                              int rank, float* Y, void* stream) {
+  if (!X || !codes_packed || !scale_idx || !v || !Y) return LQ_ERR_NULL;
+  if (rank < 0 || rank > SMALL_RANK) return LQ_ERR_RANK;
+  if (rank > 0 && (!L1 || !L2)) return LQ_ERR_NULL;
+  if (m <= 0 || m > SMALL_M || d <= 0 || k <= 0 || d >= ((int64_t)1 << 31) || k >= ((int64_t)1 << 31)) return LQ_ERR_SHAPE;
+  if ((d % 32) != 0) return LQ_ERR_SHAPE;
+  LQ_TRY(check_quant_args(d * k, c));
+  if ((k % c.block) != 0) return LQ_ERR_SHAPE;
+  if (((uintptr_t)X & 15) != 0 || ((uintptr_t)Y & 15) != 0 || (rank > 0 && ((uintptr_t)L2 & 15) != 0)) return LQ_ERR_ARG;
+  const size_t part_floats = qmatvec_part_floats((int)m, d, k, rank);
+  if (part_floats * sizeof(float) > STATIC_SCRATCH_BYTES) return LQ_ERR_WORKSPACE;   // beyond the fixed scratch: use lq_matmul
+  void* sp = nullptr;
+  LQ_TRY(static_scratch(&sp));
+  const MvWeights q{codes_packed, scale_idx, v, c.bits, c.block, c.scale_block, scale_levels(c)};
+  // every partial sum the second kernel reads is written by the first in the same call: nothing has to start at zero
+  return launch_qmatvec(q, X, d, d, L1, L2, k, rank, (int)m, k, Y, k, reinterpret_cast<float*>(sp),
+                        STATIC_SCRATCH_BYTES / sizeof(float), (hipStream_t)stream);
 }
 
 }  // extern "C"

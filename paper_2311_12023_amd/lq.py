@@ -83,6 +83,8 @@ _lib.lq_fisher_row_col.argtypes = [_vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
 _lib.lq_matmul_workspace_bytes.restype = _sz
 _lib.lq_matmul_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
 _lib.lq_matmul.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, Config, _vp, _vp, _int, _int, _vp, _vp, _sz, _vp]
+_lib.lq_matmul_few_rows_static_scratch_bytes.restype = _sz
+_lib.lq_matmul_few_rows_static.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, Config, _vp, _vp, _int, _vp, _vp]
 
 _lib.lq_profile_enable.argtypes = [_int]
 _lib.lq_profile_class_name.restype = C.c_char_p
@@ -303,6 +305,22 @@ def matmul(x: torch.Tensor, codes: torch.Tensor, scale_idx: torch.Tensor, v: tor
                           _dev(l1, torch.float32, "l1"), _dev(l2, torch.float32, "l2"), rank, precision,
                           _dev(out, torch.float32, "out"), _aligned_ptr(ws),
                           ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream()), "lq_matmul")
+    return out
+
+
+def matmul_few_rows_static(x: torch.Tensor, codes: torch.Tensor, scale_idx: torch.Tensor, v: torch.Tensor, cfg: Config,
+                           k: int, l1: torch.Tensor | None = None, l2: torch.Tensor | None = None,
+                           out: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X (Q + L1 L2) for at most 8 rows of X through the entry point that allocates nothing: its partial sums live
+    in the library's fixed device array (lq_matmul_few_rows_static).  `out`: m x k fp32 tensor to write into."""
+    m, d = x.shape
+    rank = 0 if l1 is None else l1.shape[1]
+    if out is None:
+        out = torch.empty((m, k), dtype=torch.float32, device=x.device)
+    _check(_lib.lq_matmul_few_rows_static(_dev(x, torch.float32, "x"), m, d, k, _dev(codes, torch.uint8, "codes"),
+                                          _dev(scale_idx, torch.uint8, "scale_idx"), _dev(v, torch.float32, "v"), cfg,
+                                          _dev(l1, torch.float32, "l1"), _dev(l2, torch.float32, "l2"), rank,
+                                          _dev(out, torch.float32, "out"), _stream()), "lq_matmul_few_rows_static")
     return out
 
 
