@@ -93,6 +93,14 @@ def roofline_of(name: str, ms: float, launches: int, work: float) -> dict | None
         return None
     sec = ms * 1e-3
     common = {"kernel": name, "traffic": None, "launches": launches, "avg_us": 1e3 * ms / launches}
+    if name.startswith("wide_gemm_f16_kernel"):
+        # A as one or two fp16 planes (2 or 4 B per element, 2 l flop per element), X split into fp16 hi + lo: two
+        # (one plane) or three (two planes) fp16 MFMAs per product; bound by streaming A
+        lt, _, planes = (int(t) for t in name[name.index("<") + 1:name.index(">")].split(","))
+        ach = work / (2.0 * 32 * lt) * 2.0 * planes / sec / 1e9
+        return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                "algorithmic_tflops": work / sec / 1e12,
+                "executed_f16_mfma_frac": (planes + 1.0) * work / sec / 1e12 / PEAK_BF16_MFMA_TFLOPS}
     if name.startswith("wide_gemm_kernel"):
         lt, _, _, prec = (int(t) for t in name[name.index("<") + 1:name.index(">")].split(","))
         if prec == 0:      # fp32 MFMA: work is flops
@@ -208,28 +216,32 @@ def bench_quant(args, torch, gen, lq, dev) -> int:
     torch.cuda.synchronize()
     sec = time.perf_counter() - t0
     total_bytes = 2.0 * sum(quant_bytes(c["n"], c["g"]) for c in cells)
-    # per-cell and per-kernel durations: each call bracketed by events on its stream, in passes of their own
+    # per-cell durations: for each cell a run of back-to-back calls over the rotated buffers between two events (a single
+    # call of 15 - 250 us bracketed on an otherwise idle GPU would mostly measure launch latency and the clock ramp)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     per_cell = []
     for c in cells:
-        tq = td = 0.0
-        for _ in range(args.steps):
-            counter[0] += 1
-            i = counter[0] % c["copies"]
-            a, b, e = ev(), ev(), ev()
-            a.record()
-            lq.nf_quantize(c["xs"][i], c["cfg"], out=c["packs"][i])
-            b.record()
-            lq.nf_dequantize(*c["packs"][i], c["n"], c["cfg"], out=c["outs"][i])
-            e.record()
-            torch.cuda.synchronize()
-            tq += a.elapsed_time(b)
-            td += b.elapsed_time(e)
+        reps = max(4, 2 * c["copies"])
+        times = []
+        for which in (0, 1):
+            for timed in (False, True):
+                a, b = ev(), ev()
+                a.record()
+                for r in range(reps):
+                    i = r % c["copies"]
+                    if which == 0:
+                        lq.nf_quantize(c["xs"][i], c["cfg"], out=c["packs"][i])
+                    else:
+                        lq.nf_dequantize(*c["packs"][i], c["n"], c["cfg"], out=c["outs"][i])
+                b.record()
+                torch.cuda.synchronize()
+                if timed:
+                    times.append(a.elapsed_time(b) / reps)
+        tq, td = times
         by = quant_bytes(c["n"], c["g"])
         per_cell.append({"shape": c["label"], "config": list(c["g"]), "bytes": by,
-                         "quantize_us": 1e3 * tq / args.steps, "dequantize_us": 1e3 * td / args.steps,
-                         "quantize_GBs": by / (tq / args.steps * 1e-3) / 1e9,
-                         "dequantize_GBs": by / (td / args.steps * 1e-3) / 1e9})
+                         "quantize_us": 1e3 * tq, "dequantize_us": 1e3 * td,
+                         "quantize_GBs": by / (tq * 1e-3) / 1e9, "dequantize_GBs": by / (td * 1e-3) / 1e9})
     lq.profile_enable(True)
     lq.profile_reset()
     for _ in range(args.steps):
@@ -525,13 +537,14 @@ def bench_sweep(args, torch, gen, lq, dev) -> int:
         "value": cells * args.steps / dt, "unit": "matrix-configs/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 (large products as three bf16 MFMAs on hi/lo splits, fp32 accumulation)" if split else "f32",
+        "dtype": ("f32 (large products on hi/lo splits: three bf16 MFMAs against fp32 operands, two or three fp16 MFMAs "
+                  "against the residual kept as fp16 hi + lo planes; fp32 accumulation)") if split else "f32",
         "data": "synthetic",
         "config": {"workload": label, "baseline_config": wl, "matrices": n_mats, "configs": n_cfgs, "iters": iters,
                    "rank": rank, "concurrent_matrices": nthreads},
         "roofline": roof,
         "roofline_note": "the kernel class with the largest summed duration among the machine-filling classes (large "
-                         "GEMMs against HBM for the operand they stream, with the executed bf16 MFMA work beside it; the "
+                         "GEMMs against HBM for the operand they stream, with the executed 16-bit MFMA work beside it; the "
                          "quantize / residual classes against HBM with their algorithmic bytes).  Durations are from "
                          "one extra step run one matrix at a time on one stream with every launch bracketed by events "
                          "(the kernel has the GPU to itself, as in the committed rocprofv3 table of that mode); value "

@@ -760,7 +760,7 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) 
         rv.x = srow[u] * rv.x * cs[u].x; rv.y = srow[u] * rv.y * cs[u].y;
         rv.z = srow[u] * rv.z * cs[u].z; rv.w = srow[u] * rv.w * cs[u].w;
       }
-      if (R) *reinterpret_cast<float4*>(R + (quad << 2)) = rv;
+      if (R) __builtin_nontemporal_store(floatx4{rv.x, rv.y, rv.z, rv.w}, reinterpret_cast<floatx4*>(R + (quad << 2)));
       if (R16) {
         const float lim = 65504.0f;        // largest fp16: out-of-range entries saturate instead of becoming infinite
         const float sv[4] = {__builtin_amdgcn_fmed3f(rv.x * a.r_scale, -lim, lim), __builtin_amdgcn_fmed3f(rv.y * a.r_scale, -lim, lim),
@@ -771,12 +771,139 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) 
           h[e] = (_Float16)sv[e];
           l[e] = (_Float16)(sv[e] - (float)h[e]);
         }
-        *reinterpret_cast<halfx4*>(R16 + (quad << 2)) = h;
-        if (R16lo) *reinterpret_cast<halfx4*>(R16lo + (quad << 2)) = l;
+        // streamed out: nothing reads these lines before they have left the caches anyway
+        __builtin_nontemporal_store(h, reinterpret_cast<halfx4*>(R16 + (quad << 2)));
+        if (R16lo) __builtin_nontemporal_store(l, reinterpret_cast<halfx4*>(R16lo + (quad << 2)));
       }
-      if (Qd) *reinterpret_cast<float4*>(Qd + (quad << 2)) = qv;
+      if (Qd) __builtin_nontemporal_store(floatx4{qv.x, qv.y, qv.z, qv.w}, reinterpret_cast<floatx4*>(Qd + (quad << 2)));
     }
   }
+}
+
+// The form of phase 3 that the warm iterations use: only the scaled fp16 planes of the residual are written.  A
+// workgroup owns one stretch of W (RP_U runs of 8 consecutive weights per lane, kept in registers) and walks through the
+// problems of the batch with it, so W is read once per batch; the codes and scales of problem z + 1 are fetched before
+// problem z is computed and stored, so no load ever waits behind a store; every store of a plane is 16 bytes per lane,
+// 1 KB contiguous per wavefront, and is streamed past the caches (measured: the kernel is bound by the bytes it moves;
+// per-problem workgroups that re-read W, in either launch order, took 1.29 - 1.36 ms per 36 problems where this takes
+// less).
+constexpr int RP_U = 2;
+typedef _Float16 halfx8r __attribute__((ext_vector_type(8)));
+
+struct PlaneFetch { uint32_t cw[RP_U][2]; uint32_t si[RP_U]; float vv[RP_U]; };
+
+template <int BITS>
+__device__ __forceinline__ void residual_planes_fetch(const PhaseArgs& a, int blk_shift, int sb_shift, int z,
+                                                      const int64_t (&oct)[RP_U], PlaneFetch& f) {
+  const uint8_t* codes = a.codes + (size_t)z * a.strideCodes;
+  const uint8_t* sidx = a.sidx + (size_t)z * a.strideSidx;
+  const float* v = a.v + (size_t)z * a.strideV;
+#pragma unroll
+  for (int u = 0; u < RP_U; ++u) {
+    const int64_t o = oct[u];
+    f.cw[u][1] = 0;
+    if constexpr (BITS == 8) {
+      const uint2 c2 = *reinterpret_cast<const uint2*>(codes + o * 8);
+      f.cw[u][0] = c2.x; f.cw[u][1] = c2.y;
+    } else if constexpr (BITS == 4) {
+      f.cw[u][0] = *reinterpret_cast<const uint32_t*>(codes + o * 4);
+    } else if constexpr (BITS == 2) {
+      f.cw[u][0] = *reinterpret_cast<const uint16_t*>(codes + o * 2);
+    } else {       // 24 bits at byte 3 * oct: a 16-bit and an 8-bit piece, the 16-bit one at the even address
+      const int64_t b = o * 3;
+      const uint32_t h = *reinterpret_cast<const uint16_t*>(codes + b + (o & 1));
+      const uint32_t q = codes[b + ((o & 1) ? 0 : 2)];
+      f.cw[u][0] = (o & 1) ? (q | (h << 8)) : (h | (q << 16));
+    }
+    const int64_t blk = o >> blk_shift;
+    f.si[u] = sidx[blk];
+    f.vv[u] = v[blk >> sb_shift];
+  }
+}
+
+// zmask: the problems of the batch (bit z) this launch serves; all of them have BITS code bits.
+// The loop over them is unrolled twice over two fetch buffers and has no conditional load or store inside (past the
+// last problem it fetches the last one again; lanes past the end of the matrix work on the last run of 8 weights again
+// and store the same values as its owner), so the compiler's wait for the loads of problem i + 1 never includes the
+// stores of problem i that were issued after them.
+template <int BITS, bool WEIGHTED>
+__global__ __launch_bounds__(256) void residual_planes_kernel(PhaseArgs a, uint64_t zmask) {
+  __shared__ float s_code[1 << BITS];
+  __shared__ int s_list[64];
+  __shared__ int s_par[64][4];         // per problem: log2(B0 / 8), log2(B1), levels
+  const int tid = threadIdx.x;
+  for (int i = tid; i < (1 << BITS); i += 256) s_code[i] = a.tables->code[Slot<BITS>::value][i];
+  if (tid < 64 && ((zmask >> tid) & 1)) {
+    const LoopProblem p = a.prob[tid];
+    s_list[__builtin_popcountll(zmask & ((1ull << tid) - 1ull))] = tid;
+    s_par[tid][0] = __builtin_ctz(p.cfg.block / 8); s_par[tid][1] = __builtin_ctz(p.cfg.scale_block); s_par[tid][2] = p.levels;
+  }
+  const int count = __builtin_popcountll(zmask);
+  const int64_t nocts = (a.d * a.k) >> 3;
+  const int64_t oct0 = (int64_t)blockIdx.x * (256 * RP_U) + tid;
+  int64_t oct[RP_U];
+  float wv[RP_U][8], cv[RP_U][8], srow[RP_U];
+#pragma unroll
+  for (int u = 0; u < RP_U; ++u) {
+    oct[u] = oct0 + 256 * u < nocts ? oct0 + 256 * u : nocts - 1;
+    const float4 w0 = *reinterpret_cast<const float4*>(a.W + (oct[u] << 3));
+    const float4 w1 = *reinterpret_cast<const float4*>(a.W + (oct[u] << 3) + 4);
+    wv[u][0] = w0.x; wv[u][1] = w0.y; wv[u][2] = w0.z; wv[u][3] = w0.w;
+    wv[u][4] = w1.x; wv[u][5] = w1.y; wv[u][6] = w1.z; wv[u][7] = w1.w;
+    if constexpr (WEIGHTED) {
+      const int64_t e0 = oct[u] << 3;
+      srow[u] = a.sr[e0 / a.k];
+      const float4 c0 = *reinterpret_cast<const float4*>(a.sc + e0 % a.k);
+      const float4 c1 = *reinterpret_cast<const float4*>(a.sc + e0 % a.k + 4);
+      cv[u][0] = c0.x; cv[u][1] = c0.y; cv[u][2] = c0.z; cv[u][3] = c0.w;
+      cv[u][4] = c1.x; cv[u][5] = c1.y; cv[u][6] = c1.z; cv[u][7] = c1.w;
+    }
+  }
+  __syncthreads();                     // code book, problem list and parameters in LDS
+  const float lim = 65504.0f;          // largest fp16: out-of-range entries saturate instead of becoming infinite
+  constexpr uint32_t mask = (1u << BITS) - 1u;
+  auto fetch = [&](int i, PlaneFetch& f) {
+    const int z = s_list[i < count ? i : count - 1];
+    residual_planes_fetch<BITS>(a, s_par[z][0], s_par[z][1], z, oct, f);
+  };
+  auto emit = [&](int i, const PlaneFetch& f) {
+    const int z = s_list[i];
+    const int levels = s_par[z][2];
+    _Float16* hi = reinterpret_cast<_Float16*>(a.R16) + (size_t)z * a.strideR;
+    _Float16* lo = reinterpret_cast<_Float16*>(a.R16lo) + (size_t)z * a.strideR;
+#pragma unroll
+    for (int u = 0; u < RP_U; ++u) {
+      const float sh = block_scale(f.si[u], f.vv[u], levels);
+      halfx8r h, l;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t c = BITS == 8 ? (f.cw[u][e >> 2] >> (8 * (e & 3))) & mask : (f.cw[u][0] >> (BITS * e)) & mask;
+        float r = wv[u][e] - s_code[c] * sh;
+        if constexpr (WEIGHTED) r = srow[u] * r * cv[u][e];
+        const float sv = __builtin_amdgcn_fmed3f(r * a.r_scale, -lim, lim);
+        h[e] = (_Float16)sv;
+        l[e] = (_Float16)(sv - (float)h[e]);
+      }
+      __builtin_nontemporal_store(h, reinterpret_cast<halfx8r*>(hi + (oct[u] << 3)));
+      __builtin_nontemporal_store(l, reinterpret_cast<halfx8r*>(lo + (oct[u] << 3)));
+    }
+  };
+  PlaneFetch fa, fb;
+  fetch(0, fa);
+  for (int i = 0;;) {
+    fetch(i + 1, fb);
+    emit(i, fa);
+    if (++i >= count) break;
+    fetch(i + 1, fa);
+    emit(i, fb);
+    if (++i >= count) break;
+  }
+}
+
+template <int BITS>
+static void launch_residual_planes(const PhaseArgs& a, uint64_t zmask, dim3 grid, hipStream_t st) {
+  if (a.sr) hipLaunchKernelGGL((residual_planes_kernel<BITS, true>), grid, dim3(256), 0, st, a, zmask);
+  else hipLaunchKernelGGL((residual_planes_kernel<BITS, false>), grid, dim3(256), 0, st, a, zmask);
 }
 
 int launch_residual(const PhaseArgs& a, hipStream_t st) {
@@ -787,6 +914,23 @@ int launch_residual(const PhaseArgs& a, hipStream_t st) {
   // R (or dense Q) out per problem, the quantized form in per problem, W in once
   const double out_bytes = (a.R ? 4.0 : 0.0) + (a.R16 ? 2.0 : 0.0) + (a.R16 && a.R16lo ? 2.0 : 0.0) + (a.Qd ? 4.0 : 0.0);
   prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * (out_bytes * a.batch + 4.0 + a.quant_bytes_per_weight));
+  if (a.R16 && a.R16lo && !a.R && !a.Qd && ((a.d * a.k) & 7) == 0 && a.batch <= 64 && a.bits_host) {
+    const int64_t nwg2 = (((a.d * a.k) >> 3) + 256 * RP_U - 1) / (256 * RP_U);
+    if (nwg2 >= (1ll << 31)) return LQ_ERR_SHAPE;
+    const dim3 grid((unsigned)nwg2);
+    // one launch per code width present in the batch (the kernel's loads depend on it)
+    uint64_t m[4] = {0, 0, 0, 0};
+    for (int z = 0; z < a.batch; ++z) {
+      const int b = a.bits_host[z];
+      m[b == 2 ? 0 : b == 3 ? 1 : b == 4 ? 2 : 3] |= 1ull << z;
+    }
+    if (m[0]) launch_residual_planes<2>(a, m[0], grid, st);
+    if (m[1]) launch_residual_planes<3>(a, m[1], grid, st);
+    if (m[2]) launch_residual_planes<4>(a, m[2], grid, st);
+    if (m[3]) launch_residual_planes<8>(a, m[3], grid, st);
+    LQ_HIP_TRY(hipGetLastError());
+    return LQ_OK;
+  }
   hipLaunchKernelGGL(residual_kernel, dim3((unsigned)nwg), dim3(256), 0, st, a, groups);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;

@@ -209,6 +209,7 @@ struct PhaseArgs {
   double* err_part; size_t strideErrPart;   // per-workgroup partial sums of the squared error
   double* err_out;  size_t strideErrOut;    // eps (norm) of this iteration, one double per problem
   int batch;
+  const uint8_t* bits_host;                 // host copy of the problems' code widths (batch entries), or NULL
   double quant_bytes_per_weight;            // host bookkeeping for the profiler: sum over the batch of the bytes one
                                             // weight occupies in quantized form, b0/8 + 1/B0 + bytes(b2)/(B0 B1)
 };

@@ -382,6 +382,7 @@ struct Loop {
   // state
   std::vector<LoopProblem> probs;
   std::vector<double> host_err;
+  std::vector<uint8_t> bits_host;
   int min_block = 1 << 30, done = 0;
   PhaseArgs a;
   WideSet w;
@@ -431,6 +432,9 @@ struct Loop {
       a.row_w = c->row_w; a.col_w = c->col_w;
     }
     a.prob = dprob; a.tables = c->tables; a.batch = batch;
+    bits_host.resize(batch);
+    for (int b = 0; b < batch; ++b) bits_host[b] = (uint8_t)cfgs[b].bits;
+    a.bits_host = bits_host.data();
     for (int b = 0; b < batch; ++b)
       a.quant_bytes_per_weight += cfgs[b].bits / 8.0 + 1.0 / cfgs[b].block +
                                   (v_bits(cfgs[b]) / 8.0) / ((double)cfgs[b].block * cfgs[b].scale_block);
@@ -543,7 +547,7 @@ struct Loop {
     const int b = capture_slot(t);
     if (b < 0) return LQ_OK;
     PhaseArgs one = a;
-    one.batch = 1; one.prob = a.prob + b; one.quant_bytes_per_weight = a.quant_bytes_per_weight / batch;
+    one.batch = 1; one.prob = a.prob + b; one.bits_host = a.bits_host + b; one.quant_bytes_per_weight = a.quant_bytes_per_weight / batch;
     one.codes = a.codes + (size_t)b * a.strideCodes; one.sidx = a.sidx + (size_t)b * a.strideSidx;
     one.v = a.v + (size_t)b * a.strideV;
     one.R = nullptr; one.Qd = testing::capture().Q; one.strideQd = 0;

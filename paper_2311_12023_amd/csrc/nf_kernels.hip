@@ -121,23 +121,48 @@ __global__ __launch_bounds__(256) void quantize_fused_kernel(const float* __rest
 }
 
 // ---------------------------------------------------------------------------------------------
-// Dequantize: one quad (4 consecutive weights) per lane and step; every wavefront store is 1 KB contiguous.
+// Dequantize: one quad (4 consecutive weights) per lane and step, DQ_U steps per lane, so every wavefront store is
+// 1 KB contiguous.  A workgroup owns one stretch of 256 * DQ_U quads: every load is issued first, then everything is
+// computed and stored, and the wavefront ends without waiting for a store (loads and stores retire through one in-order
+// counter, so a loop that alternates them runs at the pace of the store latency).
+constexpr int DQ_U = 4;
+typedef float floatx4n __attribute__((ext_vector_type(4)));
+
 template <int BITS>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ codes,
                                                       const uint8_t* __restrict__ sidx, const float* __restrict__ v,
                                                       int64_t nquads, int qpb_shift, int sb_shift, int levels,
                                                       const DevTables* __restrict__ tab, float* __restrict__ out) {
-  __shared__ LdsTables s_tab;
-  load_tables<BITS>(tab, s_tab);
-  const float* s_code = s_tab.code;
-  for (int64_t quad = (int64_t)blockIdx.x * 256 + threadIdx.x; quad < nquads; quad += (int64_t)gridDim.x * 256) {
+  __shared__ float s_code[1 << BITS];
+  for (int i = threadIdx.x; i < (1 << BITS); i += 256) s_code[i] = tab->code[Slot<BITS>::value][i];
+  const int64_t q0 = (int64_t)blockIdx.x * (256 * DQ_U) + threadIdx.x;
+  uint32_t cw[DQ_U], si[DQ_U];
+  float vv[DQ_U];
+#pragma unroll
+  for (int u = 0; u < DQ_U; ++u) {
+    const int64_t quad = q0 + 256 * u < nquads ? q0 + 256 * u : nquads - 1;      // clamped: loaded, never stored
     const int64_t blk = quad >> qpb_shift;
-    const float sh = block_scale(sidx[blk], v[blk >> sb_shift], levels);
-    uint32_t c[4];
-    load_quad_codes<BITS>(codes, quad, c);
-    float4 f;
-    f.x = s_code[c[0]] * sh; f.y = s_code[c[1]] * sh; f.z = s_code[c[2]] * sh; f.w = s_code[c[3]] * sh;
-    *reinterpret_cast<float4*>(out + (quad << 2)) = f;
+    if constexpr (BITS == 8) cw[u] = *reinterpret_cast<const uint32_t*>(codes + quad * 4);
+    else if constexpr (BITS == 4) cw[u] = *reinterpret_cast<const uint16_t*>(codes + quad * 2);
+    else if constexpr (BITS == 2) cw[u] = codes[quad];
+    else {   // 3 bits: 12 bits starting at bit 12*quad = byte floor(1.5*quad), nibble-aligned
+      const int64_t byte = (quad * 3) >> 1;
+      cw[u] = (((uint32_t)codes[byte] | ((uint32_t)codes[byte + 1] << 8)) >> ((quad & 1) * 4)) & 0xfffu;
+    }
+    si[u] = sidx[blk];
+    vv[u] = v[blk >> sb_shift];
+  }
+  __syncthreads();                     // code book in LDS
+  constexpr uint32_t mask = (1u << BITS) - 1u;
+#pragma unroll
+  for (int u = 0; u < DQ_U; ++u) {
+    const int64_t quad = q0 + 256 * u;
+    if (quad >= nquads) break;
+    const float sh = block_scale(si[u], vv[u], levels);
+    floatx4n f;
+    f[0] = s_code[cw[u] & mask] * sh; f[1] = s_code[(cw[u] >> BITS) & mask] * sh;
+    f[2] = s_code[(cw[u] >> (2 * BITS)) & mask] * sh; f[3] = s_code[(cw[u] >> (3 * BITS)) & mask] * sh;
+    __builtin_nontemporal_store(f, reinterpret_cast<floatx4n*>(out + (quad << 2)));
   }
 }
 
@@ -226,8 +251,9 @@ int launch_dequant(const uint8_t* codes, const uint8_t* sidx, const float* v, in
   LQ_TRY(device_tables(&tab));
   const int64_t nruns = n / 4;            // quads
   const int rpb = __builtin_ctz(c.block / 4);            // log2(quads per block)
-  const int64_t want = (nruns + 255) / 256;
-  const dim3 grid((unsigned)(want < 16384 ? want : 16384)), block(256);
+  const int64_t want = (nruns + 256 * DQ_U - 1) / (256 * DQ_U);
+  if (want >= (1ll << 31)) return LQ_ERR_SHAPE;
+  const dim3 grid((unsigned)want), block(256);
   const int lv = scale_levels(c);
   prof::Scope ps(prof::DEQUANTIZE, st,
                  (double)n * (4.0 + c.bits / 8.0 + 1.0 / c.block + 4.0 / ((double)c.block * c.scale_block)));
