@@ -15,6 +15,7 @@
 // 128-bit loads; any permutation is valid as long as A and X agree on it.
 // The launch is one-dimensional: see the work decomposition at wide_gemm_kernel.
 #include <algorithm>
+#include <cstdlib>
 
 #include "kernels.h"
 #include "profiler.h"
@@ -436,7 +437,9 @@ __device__ __forceinline__ void lane_offsets16(int64_t lda, int64_t big, int64_t
   }
 }
 
-// One plane of the A operand of a step as it comes from memory.  NT mode: ring[g][j] = the 8 halves
+// One plane of the A operand of a step as it comes from memory (plain loads: in NT mode a 128-byte line of a row is
+// consumed by four loads of the same wavefront, which rely on the caches; streaming loads made that mode 40 % slower).
+// NT mode: ring[g][j] = the 8 halves
 // k0 + 16 g + 8 h + (0..7) of row j's lane row.  NN mode: ring[g][e / 4][e % 4] = the word holding columns col, col + 1
 // of reduction row k0 + 16 g + 8 h + e.
 template <int MODE, int G, bool GUARD>
@@ -516,8 +519,8 @@ __device__ __forceinline__ float x_scale_from(double lam0) {
   return exp2f(13.0f - ceilf(0.5f * log2f(s)));
 }
 
-template <int LT, int MODE, int PLANES>
-__global__ __launch_bounds__(256, 2) void wide_gemm_f16_kernel(GemmArgs g) {
+template <int LT, int MODE, int PLANES, int STAGES>
+__global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(GemmArgs g) {
   constexpr int NT = 2;
   constexpr int SPAN = 128 * NT;
   constexpr int G = PLANES == 1 ? 4 : 2;       // 16-groups per step
@@ -566,13 +569,19 @@ __global__ __launch_bounds__(256, 2) void wide_gemm_f16_kernel(GemmArgs g) {
     const int64_t kxlast = kbeg + (int64_t)(nsteps - 1) * BKH;
 
     floatx4 xreg[LT * G / 2];
-    uintx4 ring[2][PLANES][G][2];
+    uintx4 ring[STAGES][PLANES][G][2];
     fetch_x16<LT, G>(X, g.ldx, kbeg, tid, xreg);
     if (nfull > 0) {
-      fetch_a16<MODE, G, false>(A, g.lda, off, lh, kbeg, kend, ring[0][0]);
-      if constexpr (PLANES == 2) fetch_a16<MODE, G, false>(A2, g.lda, off, lh, kbeg, kend, ring[0][1]);
+#pragma unroll
+      for (int u = 0; u < STAGES - 1; ++u) {
+        const int64_t k1 = kbeg + (int64_t)u * BKH;
+        const int64_t k1c = k1 < klast ? k1 : klast;
+        fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[u][0]);
+        if constexpr (PLANES == 2) fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[u][1]);
+      }
     }
 
+    // one step of the ring, U = position of the consumed chunk (compile-time so that the ring stays in registers)
 #define LQ_GEMM16_STEP(U, STEP, PREFETCH)                                                                         \
   {                                                                                                               \
     __syncthreads(); /* everyone is done reading the previous X tile */                                           \
@@ -583,19 +592,23 @@ __global__ __launch_bounds__(256, 2) void wide_gemm_f16_kernel(GemmArgs g) {
       fetch_x16<LT, G>(X, g.ldx, kx < kxlast ? kx : kxlast, tid, xreg);                                           \
     }                                                                                                             \
     if constexpr (PREFETCH) {                                                                                     \
-      const int64_t k1 = kbeg + (int64_t)((STEP) + 1) * BKH;                                                      \
+      const int64_t k1 = kbeg + (int64_t)((STEP) + STAGES - 1) * BKH;                                             \
       const int64_t k1c = k1 < klast ? k1 : klast;                                                                \
-      fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[((U) + 1) & 1][0]);                            \
-      if constexpr (PLANES == 2) fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[((U) + 1) & 1][1]); \
+      fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][0]);              \
+      if constexpr (PLANES == 2)                                                                                  \
+        fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][1]);           \
     }                                                                                                             \
     multiply_chunk16<LT, MODE, PLANES, G>(xh, xl, ln, lh, ring[(U)], acc);                                        \
   }
     int step0 = 0;
-    for (; step0 + 2 <= nfull; step0 += 2) {
-      LQ_GEMM16_STEP(0, step0, true)
-      LQ_GEMM16_STEP(1, step0 + 1, true)
+    for (; step0 + STAGES <= nfull; step0 += STAGES) {
+#pragma unroll
+      for (int u = 0; u < STAGES; ++u) LQ_GEMM16_STEP(u, step0 + u, true)
     }
-    if (step0 < nfull) LQ_GEMM16_STEP(0, step0, false)
+    // the remaining full chunks are already in the ring
+#pragma unroll
+    for (int u = 0; u < STAGES - 1; ++u)
+      if (step0 + u < nfull) LQ_GEMM16_STEP(u, step0 + u, false)
     if (tail) {
       const int64_t kt = kbeg + (int64_t)nfull * BKH;
       fetch_a16<MODE, G, true>(A, g.lda, off, lh, kt, kend, ring[0][0]);
@@ -734,16 +747,23 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
   return LQ_OK;
 }
 
-template <int MODE, int PLANES>
-static int launch_f16_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
+template <int MODE, int PLANES, int STAGES>
+static int launch_f16_stages(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
   const size_t lds = (size_t)2 * 32 * lt * HP16 * sizeof(_Float16);
   switch (lt) {
-    case 1: hipLaunchKernelGGL((wide_gemm_f16_kernel<1, MODE, PLANES>), grid, dim3(256), lds, st, g); break;
-    case 2: hipLaunchKernelGGL((wide_gemm_f16_kernel<2, MODE, PLANES>), grid, dim3(256), lds, st, g); break;
-    case 3: hipLaunchKernelGGL((wide_gemm_f16_kernel<3, MODE, PLANES>), grid, dim3(256), lds, st, g); break;
+    case 1: hipLaunchKernelGGL((wide_gemm_f16_kernel<1, MODE, PLANES, STAGES>), grid, dim3(256), lds, st, g); break;
+    case 2: hipLaunchKernelGGL((wide_gemm_f16_kernel<2, MODE, PLANES, STAGES>), grid, dim3(256), lds, st, g); break;
+    case 3: hipLaunchKernelGGL((wide_gemm_f16_kernel<3, MODE, PLANES, STAGES>), grid, dim3(256), lds, st, g); break;
     default: return LQ_ERR_ARG;
   }
   return LQ_OK;
+}
+
+template <int MODE, int PLANES>
+static int launch_f16_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
+  // two-deep ring, two workgroups per compute unit: rings of 4 and 6 chunks with one workgroup per compute unit (the
+  // registers of a whole SIMD per wavefront) were 8 % slower
+  return launch_f16_stages<MODE, PLANES, 2>(g, lt, grid, st);
 }
 
 bool wide_gemm_f16_supported(int l) { return l % 32 == 0 && l >= 32 && l <= 96; }   // four row tiles spill registers
