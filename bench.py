@@ -59,6 +59,7 @@ def measured_traffic(name: str, table: str | None = None):
     base = name.split("<")[0]
     want = name.replace(" ", "")
     tot = n = 0.0
+    parts = 0.0          # residual_kernel: one launch of the class is one launch per code width; their traffic adds up
     # a summary that also holds other tables marks the counter table with a heading that names the traffic
     headed = any(ln.startswith("#") and "traffic" in ln.lower() for ln in lines[1:])
     inside = not headed
@@ -69,14 +70,23 @@ def measured_traffic(name: str, table: str | None = None):
         if not inside or len(cells) != 4 or not cells[0].startswith("`"):
             continue
         kern = cells[0].strip("`").replace(" ", "")
-        if name.startswith("wide_gemm_kernel"):
+        per_launch = (float(cells[2]) + float(cells[3])) * 1e6
+        if name.startswith("wide_gemm"):
             hit = kern.startswith(want[:-1] + ",")          # the table's names carry one more template argument
+        elif base == "lowrank_blockquant_kernel":
+            hit = kern.startswith("lowrank_blockquant")
+        elif base == "residual_kernel":
+            if kern.startswith("residual_planes_kernel"):
+                parts += per_launch
+            hit = kern.split("<")[0] == base
         else:
             hit = kern.split("<")[0] == base
         if hit:
             launches = float(cells[1])
-            tot += launches * (float(cells[2]) + float(cells[3])) * 1e6
+            tot += launches * per_launch
             n += launches
+    if parts:
+        return parts
     return tot / n if n else None
 
 
@@ -196,6 +206,12 @@ def bench_quant(args, torch, gen, lq, dev) -> int:
             cells.append(dict(label=label, n=n, g=g, cfg=cfg, xs=xs, outs=outs, packs=packs, copies=copies))
         del w
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 2.0, out=dst)          # one elementwise kernel: 1 GiB in, 1 GiB out
+        torch.cuda.synchronize()
+        del src, dst
     counter = [0]
 
     def step():
@@ -530,7 +546,12 @@ def bench_sweep(args, torch, gen, lq, dev) -> int:
 
     roof, latency_share = dominant_roofline(prof) if prof else (None, None)
     if roof is not None and wl == 3 and n_mats == 7 and args.grid == "sweep36":
-        roof["traffic"] = measured_traffic(roof["kernel"])
+        # the counter runs were taken in the default launch configuration (18 configurations per launch); the launches
+        # timed here serve 36, and every byte of these kernels scales with the configurations served
+        tr = measured_traffic(roof["kernel"])
+        roof["traffic"] = None if tr is None else 2.0 * tr
+        roof["traffic_note"] = ("FETCH_SIZE + WRITE_SIZE per launch of 18 configurations from "
+                                "profiles/llama7b_layer_sweep_hbm_traffic.md, times two for the 36 served per launch here")
     split = args.gemm_mode != 1
     line = {
         "metric": "matrix-configs decomposed/sec" + (" (LLaMA-2-7B layer sweep)" if wl == 3 else f" (workload {wl})"),
