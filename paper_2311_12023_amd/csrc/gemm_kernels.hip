@@ -490,6 +490,59 @@ __device__ __forceinline__ void operands16(const uintx4 (&cur)[G][2], int g, hal
   }
 }
 
+// NT mode with one plane, staged through LDS.  Loading a row's 8 halves per lane and MFMA (above) touches every 128-byte
+// line of a row with four load instructions of 32 bytes each.  Here a wavefront loads its 64 rows of a 64-deep step with
+// full lines (instruction i: lane l takes the 16-byte piece l % 8 of row 8 i + l / 8), writes them to its own LDS
+// stage (row pitch 144 bytes) and reads them back in operand layout; only the wavefront itself touches the stage, so no
+// barrier is involved (LDS operations of a wavefront complete in order).
+constexpr int STAGE_PITCH = 72;                  // fp16 elements per staged row: 64 + 8 (conflict-free 128-bit reads)
+constexpr int STAGE_HALVES = 64 * STAGE_PITCH;   // per wavefront
+
+__device__ __forceinline__ void lane_offsets_staged(int64_t lda, int64_t big, int64_t big0, int lane, uint32_t (&off)[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    int64_t row = big0 + 8 * i + (lane >> 3);
+    if (row >= big) row = big - 1;              // clamped rows are computed and never stored
+    off[i] = (uint32_t)((row * lda + 8 * (lane & 7)) * 2);
+  }
+}
+
+template <bool GUARD>
+__device__ __forceinline__ void fetch_a_staged(const _Float16* __restrict__ A, const uint32_t (&off)[8], int lane,
+                                               int64_t k0, int64_t kend, uintx4 (&ring)[4][2]) {
+  const uintx4 zero = {0u, 0u, 0u, 0u};
+  const char* base = reinterpret_cast<const char*>(A + k0);
+  const bool ok = !GUARD || k0 + 8 * (lane & 7) < kend;             // K and kend are multiples of 8
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ring[i >> 1][i & 1] = ok ? *reinterpret_cast<const uintx4*>(base + off[i]) : zero;
+}
+
+template <int LT>
+__device__ __forceinline__ void multiply_chunk_staged(const _Float16* xh, const _Float16* xl, _Float16* stage, int lane,
+                                                      const uintx4 (&cur)[1][4][2], floatx16 (&acc)[LT][2]) {
+  const int ln = lane & 31, lh = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    *reinterpret_cast<uintx4*>(stage + (8 * i + (lane >> 3)) * STAGE_PITCH + 8 * (lane & 7)) = cur[0][i >> 1][i & 1];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    halfx8 av[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      av[j] = *reinterpret_cast<const halfx8*>(stage + (32 * j + ln) * STAGE_PITCH + 16 * g + 8 * lh);
+#pragma unroll
+    for (int i = 0; i < LT; ++i) {
+      const halfx8 xhv = *reinterpret_cast<const halfx8*>(xh + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
+      const halfx8 xlv = *reinterpret_cast<const halfx8*>(xl + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xlv, av[j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, av[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+}
+
 template <int LT, int MODE, int PLANES, int G>
 __device__ __forceinline__ void multiply_chunk16(const _Float16* xh, const _Float16* xl, int ln, int lh,
                                                  const uintx4 (&cur)[PLANES][G][2], floatx16 (&acc)[LT][2]) {
@@ -526,11 +579,13 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
   constexpr int G = PLANES == 1 ? 4 : 2;       // 16-groups per step
   constexpr int BKH = 16 * G;
   extern __shared__ __attribute__((aligned(16))) float xs[];   // hi then lo halves of X, [32*LT][HP16] fp16 each
+  constexpr bool STAGED = MODE == MODE_NT && PLANES == 1;
   _Float16* xh = reinterpret_cast<_Float16*>(xs);
   _Float16* xl = xh + 32 * LT * HP16;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int ln = lane & 31, lh = lane >> 5;
+  _Float16* stage = xl + 32 * LT * HP16 + wave * STAGE_HALVES;        // STAGED only
 
   const int tile = (blockIdx.x >> 3) % g.tiles;
   const int share = (int)(blockIdx.x & 7) + 8 * (int)((blockIdx.x >> 3) / g.tiles);
@@ -540,7 +595,9 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
 
   const int64_t big0 = (int64_t)tile * SPAN + wave * (32 * NT);
   uint32_t off[2];
+  uint32_t off8[STAGED ? 8 : 1];
   lane_offsets16<MODE>(g.lda, g.big, big0, ln, lh, off);
+  if constexpr (STAGED) lane_offsets_staged(g.lda, g.big, big0, lane, off8);
 
   for (int gs = share0; gs < share1;) {
     const int z = gs / g.ns;
@@ -576,7 +633,8 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
       for (int u = 0; u < STAGES - 1; ++u) {
         const int64_t k1 = kbeg + (int64_t)u * BKH;
         const int64_t k1c = k1 < klast ? k1 : klast;
-        fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[u][0]);
+        if constexpr (STAGED) fetch_a_staged<false>(A, off8, lane, k1c, kend, ring[u][0]);
+        else fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[u][0]);
         if constexpr (PLANES == 2) fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[u][1]);
       }
     }
@@ -594,11 +652,13 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
     if constexpr (PREFETCH) {                                                                                     \
       const int64_t k1 = kbeg + (int64_t)((STEP) + STAGES - 1) * BKH;                                             \
       const int64_t k1c = k1 < klast ? k1 : klast;                                                                \
-      fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][0]);              \
+      if constexpr (STAGED) fetch_a_staged<false>(A, off8, lane, k1c, kend, ring[((U) + STAGES - 1) % STAGES][0]); \
+      else fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][0]);         \
       if constexpr (PLANES == 2)                                                                                  \
         fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][1]);           \
     }                                                                                                             \
-    multiply_chunk16<LT, MODE, PLANES, G>(xh, xl, ln, lh, ring[(U)], acc);                                        \
+    if constexpr (STAGED) multiply_chunk_staged<LT>(xh, xl, stage, lane, ring[(U)], acc);                         \
+    else multiply_chunk16<LT, MODE, PLANES, G>(xh, xl, ln, lh, ring[(U)], acc);                                   \
   }
     int step0 = 0;
     for (; step0 + STAGES <= nfull; step0 += STAGES) {
@@ -611,7 +671,8 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
       if (step0 + u < nfull) LQ_GEMM16_STEP(u, step0 + u, false)
     if (tail) {
       const int64_t kt = kbeg + (int64_t)nfull * BKH;
-      fetch_a16<MODE, G, true>(A, g.lda, off, lh, kt, kend, ring[0][0]);
+      if constexpr (STAGED) fetch_a_staged<true>(A, off8, lane, kt, kend, ring[0][0]);
+      else fetch_a16<MODE, G, true>(A, g.lda, off, lh, kt, kend, ring[0][0]);
       if constexpr (PLANES == 2) fetch_a16<MODE, G, true>(A2, g.lda, off, lh, kt, kend, ring[0][1]);
       LQ_GEMM16_STEP(0, nfull, false)
     }
@@ -749,7 +810,8 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
 
 template <int MODE, int PLANES, int STAGES>
 static int launch_f16_stages(const GemmArgs& g, int lt, dim3 grid, hipStream_t st) {
-  const size_t lds = (size_t)2 * 32 * lt * HP16 * sizeof(_Float16);
+  const size_t lds = (size_t)2 * 32 * lt * HP16 * sizeof(_Float16) +
+                     (MODE == MODE_NT && PLANES == 1 ? (size_t)4 * STAGE_HALVES * sizeof(_Float16) : 0);
   switch (lt) {
     case 1: hipLaunchKernelGGL((wide_gemm_f16_kernel<1, MODE, PLANES, STAGES>), grid, dim3(256), lds, st, g); break;
     case 2: hipLaunchKernelGGL((wide_gemm_f16_kernel<2, MODE, PLANES, STAGES>), grid, dim3(256), lds, st, g); break;
