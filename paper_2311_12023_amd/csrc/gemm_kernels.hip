@@ -379,11 +379,11 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g, int l, int 
 // ------------------------------------------------------------------------------------------------
 // Products whose large operand is stored in fp16 (the residual W - Q of the warm LQ iterations, scaled by a power of
 // two so that it sits in the middle of the fp16 range): half the bytes of the fp32 form stream from HBM, which is
-// what bounds these products.  X is split on the fly into fp16 hi + lo (after scaling by a power of two xs that puts
-// its entries where both halves are normal numbers) and every product is two v_mfma_f32_32x32x16_f16
-// (hi * a + lo * a, fp32 accumulation).  PLANES == 2: A comes as two fp16 planes, a = hi + lo (22 significant bits),
-// and a product is three MFMAs (xl * ah + xh * al + xh * ah); used where the rounding of A to fp16 would show in the
-// result to first order.  The result is multiplied by out_scale (a power of two) when stored.
+// what bounds these products.  PLANES == 1: A is one fp16 plane and X is rounded to fp16 as well (after scaling by a
+// power of two xs that keeps its entries normal numbers): one v_mfma_f32_32x32x16_f16 per product, about 2^-12 relative
+// per operand; for the products that only steer a subspace.  PLANES == 2: A comes as two fp16 planes, a = hi + lo
+// (22 significant bits), X is split into fp16 hi + lo, and a product is three MFMAs (xl * ah + xh * al + xh * ah); used
+// where the rounding of an operand to fp16 would show in the result to first order.  The result is multiplied by out_scale (a power of two) when stored.
 // Same work decomposition, tile shapes and fix-up as wide_gemm_kernel; the reduction is cut into steps of 64 (one
 // plane) or 32 (two planes), and both operands keep the natural order of the reduction index.
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
@@ -404,7 +404,7 @@ __device__ __forceinline__ void fetch_x16(const float* __restrict__ X, int64_t l
   }
 }
 
-template <int LT, int G>
+template <int LT, int G, bool LO>
 __device__ __forceinline__ void stash_x16(_Float16* xh, _Float16* xl, int tid, float xs,
                                           const floatx4 (&xreg)[LT * G / 2]) {
 #pragma unroll
@@ -413,9 +413,11 @@ __device__ __forceinline__ void stash_x16(_Float16* xh, _Float16* xl, int tid, f
     const int row = idx / (4 * G), c4 = idx % (4 * G);
     const floatx4 v = xreg[i] * xs;
     const halfx4 h = __builtin_convertvector(v, halfx4);
-    const halfx4 l = __builtin_convertvector(v - __builtin_convertvector(h, floatx4), halfx4);
     *reinterpret_cast<halfx4*>(xh + row * HP16 + 4 * c4) = h;
-    *reinterpret_cast<halfx4*>(xl + row * HP16 + 4 * c4) = l;
+    if constexpr (LO) {
+      const halfx4 l = __builtin_convertvector(v - __builtin_convertvector(h, floatx4), halfx4);
+      *reinterpret_cast<halfx4*>(xl + row * HP16 + 4 * c4) = l;
+    }
   }
 }
 
@@ -533,12 +535,8 @@ __device__ __forceinline__ void multiply_chunk_staged(const _Float16* xh, const 
 #pragma unroll
     for (int i = 0; i < LT; ++i) {
       const halfx8 xhv = *reinterpret_cast<const halfx8*>(xh + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
-      const halfx8 xlv = *reinterpret_cast<const halfx8*>(xl + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xlv, av[j], acc[i][j], 0, 0, 0);
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, av[j], acc[i][j], 0, 0, 0);
-      }
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, av[j], acc[i][j], 0, 0, 0);
     }
   }
 }
@@ -554,11 +552,13 @@ __device__ __forceinline__ void multiply_chunk16(const _Float16* xh, const _Floa
 #pragma unroll
     for (int i = 0; i < LT; ++i) {
       const halfx8 xhv = *reinterpret_cast<const halfx8*>(xh + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
-      const halfx8 xlv = *reinterpret_cast<const halfx8*>(xl + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xlv, ah[j], acc[i][j], 0, 0, 0);
-        if constexpr (PLANES == 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, al[j], acc[i][j], 0, 0, 0);
+        if constexpr (PLANES == 2) {
+          const halfx8 xlv = *reinterpret_cast<const halfx8*>(xl + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xlv, ah[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, al[j], acc[i][j], 0, 0, 0);
+        }
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, ah[j], acc[i][j], 0, 0, 0);
       }
     }
@@ -643,7 +643,7 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
 #define LQ_GEMM16_STEP(U, STEP, PREFETCH)                                                                         \
   {                                                                                                               \
     __syncthreads(); /* everyone is done reading the previous X tile */                                           \
-    stash_x16<LT, G>(xh, xl, tid, xscale, xreg);                                                                  \
+    stash_x16<LT, G, PLANES == 2>(xh, xl, tid, xscale, xreg);                                                                  \
     __syncthreads();                                                                                              \
     {                                                                                                             \
       const int64_t kx = kbeg + (int64_t)((STEP) + 1) * BKH;                                                      \

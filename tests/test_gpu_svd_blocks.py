@@ -70,7 +70,8 @@ def up64(x):
 
 # The products against an fp16 operand (the warm iterations' residual): ragged against the 256-column tiles and the
 # 64-deep steps, cut and uncut reductions, fixed and data-derived scaling of X.  The reference multiplies the very same
-# fp16 values in fp64, so what is left is the fp16 hi/lo split of X (about 2^-21 relative) and fp32 accumulation.
+# fp16 values in fp64, so what is left is the rounding (one plane) or the fp16 hi/lo split (two planes) of X and fp32
+# accumulation.
 @pytest.mark.parametrize("mode,l,big,K,batch,wgs", [
     (0, 32, 200, 160, 1, None), (0, 64, 768, 768, 1, 5), (0, 96, 130, 1040, 3, 7), (0, 96, 1000, 4096, 1, 0),
     (0, 96, 1500, 704, 5, 20), (0, 96, 1500, 704, 1, 1), (0, 96, 520, 4096, 1, 64), (0, 96, 300, 1000, 7, 6),
@@ -109,8 +110,10 @@ def test_wide_gemm_f16(env, mode, l, big, K, batch, wgs, scaling, planes):
     if scaling == "fixed":
         ref *= 64.0
     err = np.abs(got[:, :, :big] - ref)
-    assert err.max() < 2e-5 * np.abs(ref).max(), (err.max(), np.abs(ref).max())
-    assert np.sqrt(np.mean(err ** 2)) < 2e-6 * np.sqrt(np.mean(ref ** 2))
+    # two planes: X is split into fp16 hi + lo (2^-21); one plane: X is rounded to fp16 (2^-12 per entry, random sign)
+    tol_max, tol_rms = (2e-5, 2e-6) if planes == 2 else (2e-3, 3e-4)
+    assert err.max() < tol_max * np.abs(ref).max(), (err.max(), np.abs(ref).max())
+    assert np.sqrt(np.mean(err ** 2)) < tol_rms * np.sqrt(np.mean(ref ** 2))
     assert np.all(got[:, :, big:] == 7.0)           # columns past the matrix are never written
     ct2 = torch.full((batch, l, ldc), 7.0, dtype=torch.float32, device="cuda")
     run(ct2)
