@@ -621,9 +621,10 @@ def main() -> int:
                     help="also launch one plain elementwise kernel that reads and writes exactly 1 GiB each, so that a "
                          "counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) of this command holds a dispatch of "
                          "known HBM traffic to scale the counters by")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=None,
                     help="lq_svd_params.streams: interleaved sub-batches per matrix (0 = library default, 3, which is best "
-                         "for one matrix at a time; with every matrix of the layer in flight 2 is enough)")
+                         "for one matrix at a time; default here: 2 with every matrix of a LLaMA-shaped layer in flight, "
+                         "1 for workload 2, whose batches of 9 configurations are too small to split)")
     ap.add_argument("--gemm-mode", type=int, default=0, help="lq_svd_params.gemm_mode (0 = library default)")
     ap.add_argument("--workload", choices=("sweep", "quant", "matmul"), default="sweep")
     ap.add_argument("--tokens", type=int, default=4096, help="rows of X for --workload matmul")
@@ -637,6 +638,9 @@ def main() -> int:
         args.steps = {"matmul": 100, "quant": 10}.get(args.workload) or {1: 50, 2: 2, 3: 2, 4: 5, 5: 1}[args.config]
     if args.warmup is None:
         args.warmup = {"matmul": 20, "quant": 2}.get(args.workload) or {1: 5, 2: 1, 3: 1, 4: 1, 5: 1}[args.config]
+
+    if args.streams is None:
+        args.streams = 1 if (args.workload == "sweep" and args.config == 2) else 2
 
     import torch
     from paper_2311_12023_amd import gen, lq
