@@ -162,12 +162,17 @@ int launch_cholesky(double* G, int l, int batch, hipStream_t st) {
 // (double-buffered, one barrier per step) and every thread updates its own elements:
 //   a(i,k) -= c_ij c_kj,   T(i,k) -= c_ij T(j,k)   (Gauss-Jordan on [C | I]).
 // A non-positive pivot (dependent direction) zeroes that row of C^-1, which removes the direction.
+// 1 / sqrt(x) for positive finite x: fp32 seed on the mantissa (so that the seed exists whatever the magnitude of x),
+// three Newton steps in fp64, exponent put back.
 __device__ inline double fast_rsqrt(double x) {
-  double r = (double)rsqrtf((float)x);
-  r = r * (1.5 - 0.5 * x * r * r);
-  r = r * (1.5 - 0.5 * x * r * r);
-  r = r * (1.5 - 0.5 * x * r * r);
-  return r;
+  int e;
+  double m = frexp(x, &e);                    // x = m 2^e, m in [0.5, 1)
+  if (e & 1) { m *= 2.0; e -= 1; }            // even exponent, m in [0.5, 2)
+  double r = (double)rsqrtf((float)m);
+  r = r * (1.5 - 0.5 * m * r * r);
+  r = r * (1.5 - 0.5 * m * r * r);
+  r = r * (1.5 - 0.5 * m * r * r);
+  return ldexp(r, -(e / 2));
 }
 
 template <int NB>
@@ -422,9 +427,19 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
   float* V = fl + l * P;
   const int z = blockIdx.x, tid = threadIdx.x, nthr = 8 * l;
   const double* G = Gall + (size_t)z * l * l;
+  // M is brought to unit scale by a power of two first: the rotations work with products of four of its entries, which
+  // leave the fp32 range for matrices whose singular values are below 1e-5 or above 1e4 otherwise
+  __shared__ double s_scale;
+  if (tid == 0) {
+    double mx = 0.0;
+    for (int i = 0; i < l; ++i) mx = fmax(mx, fabs(G[(size_t)i * l + i]));
+    s_scale = (mx > 0.0 && mx < 1.0e300) ? ldexp(1.0, -ilogb(mx)) : 1.0;
+  }
+  __syncthreads();
+  const double mscale = s_scale;
   for (int idx = tid; idx < l * l; idx += nthr) {
     const int c = idx / l, i = idx % l;
-    X[c * P + i] = (float)G[idx];             // symmetric: row c of M is column c
+    X[c * P + i] = (float)(G[idx] * mscale);  // symmetric: row c of M is column c
     V[c * P + i] = (c == i) ? 1.0f : 0.0f;
   }
   const int g = tid >> 4, sub = tid & 15;
@@ -496,7 +511,7 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
     int r = 0;
     for (int j = 0; j < l; ++j) r += (s_norm[j] > li || (s_norm[j] == li && j < tid)) ? 1 : 0;
     s_rank[tid] = r;
-    lamall[(size_t)z * l + r] = (double)li;
+    lamall[(size_t)z * l + r] = (double)li / mscale;
   }
   __syncthreads();
   float* Ut = Utall + (size_t)z * l * l;

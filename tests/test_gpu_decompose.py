@@ -117,6 +117,33 @@ def test_decompose_block128_both_precisions(env, oracle, gemm_mode):
     check_decomposition_consistency(oracle, w, out, oracle.config(4, 128, 16), 8)
 
 
+@pytest.mark.parametrize("shift", [-24, 20])
+def test_decompose_power_of_two_scaling(env, shift):
+    """W scaled by a power of two: every operation of the path scales exactly (the fp16 residual planes take their
+    power-of-two scale from max |W|), so the error trace scales by the same factor bit for bit and the codes are the same."""
+    torch, lq = env
+    w = gen.weight_matrix(256, 512, 31, 8, outlier_frac=0.004)
+    cfg = lq.config(3, 32, 64)
+    base = lq.decompose(torch.from_numpy(w).cuda(), 8, cfg, 4, seed=5)
+    scaled = lq.decompose(torch.from_numpy(np.ldexp(w, shift)).cuda(), 8, cfg, 4, seed=5)
+    assert np.array_equal(np.ldexp(base["trace"], shift), scaled["trace"])
+    assert torch.equal(base["codes"], scaled["codes"]) and torch.equal(base["scale_idx"], scaled["scale_idx"])
+    assert np.array_equal(np.ldexp(base["sigma"], shift), scaled["sigma"])
+
+
+def test_decompose_dominant_entries(env, oracle):
+    """A few entries a hundred times the rest carry the leading singular vectors almost alone: the case in which a
+    rounding of the residual to fp16 in the projection would show in sigma to first order (2^-12 of a dominant entry).
+    The projection multiplies against both fp16 planes, so every pass still holds 1e-4."""
+    torch, lq = env
+    w = gen.weight_matrix(256, 512, 47, 0)
+    rng = np.random.default_rng(47)
+    for _ in range(5):
+        w[rng.integers(256), rng.integers(512)] = np.float32(rng.choice([-1.0, 1.0]) * rng.uniform(2.0, 4.0))
+    out = anchor.check_anchored_decompose(oracle, lq, torch, w, 8, (4, 64, 256), 4, seed=3, label="dominant entries")
+    check_decomposition_consistency(oracle, w, out, oracle.config(4, 64, 256), 8)
+
+
 @pytest.mark.parametrize("weighted", [False, True])
 def test_decompose_quantized_initialisation(env, oracle, weighted):
     """Q(0) = Quantize(W) (Section 3.1, footnote): every pass anchored, the first one on W - Dequantize(Quantize(W))
