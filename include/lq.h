@@ -77,13 +77,18 @@ typedef struct {
  *   first_max     cap on cold-start subspace iterations.  Default 600.
  *   warm_width    subspace width l of later LQ iterations, warm-started from the previous one;
  *                 multiple of 32, rank < l <= first_width.  Default round_up32(rank + max(rank/2, 24)).
- *   warm_power    subspace iterations per later LQ iteration.  Default 2.
+ *   warm_power    subspace iterations per later LQ iteration (configurations not covered by warm_power_coarse or
+ *                 warm_power_fine).  Default 2.
  *   warm_power_2  subspace iterations of the second LQ iteration (the one whose input differs most
  *                 from its warm start).  Default 3.
  *   warm_power_coarse  subspace iterations per later LQ iteration (the second included) for configurations whose scale
  *                 quantizer has a single level (b1 = 2: every block scale is 0 or v), whose residual W - Q changes far more
  *                 from one iteration to the next; used when larger than warm_power / warm_power_2.  lq_error_table
  *                 processes such configurations first, in batches of their own.  Default 4.
+ *   warm_power_fine  subspace iterations per LQ iteration from the third on for configurations with codes of four or
+ *                 more bits and block scales of eight or more (b0 >= 4, b1 >= 8), whose quantized component follows
+ *                 W - L1 L2 closely enough that the residual hardly moves between iterations.  lq_error_table processes them last, in batches of their own where
+ *                 the batch size allows; a batch that mixes classes takes the largest count.  Default 1.
  *   max_batch     lq_error_table advances up to this many configurations in lock step (more
  *                 workspace, better GPU occupancy).  Default 36.
  *   streams       lq_error_table splits a batch over this many HIP streams (1..4, all default priority, the
@@ -91,7 +96,11 @@ typedef struct {
  *                 throughput-bound kernels of another.  Default 3.
  *   gemm_mode     arithmetic of the large products against the d x k matrix: 1 = fp32 MFMA; 2 = both operands
  *                 split on the fly into bf16 hi + lo and multiplied by three bf16 MFMAs with fp32 accumulation
- *                 (products good to about 2^-16 relative, several times faster).  Default 2.
+ *                 (products good to about 2^-16 relative, several times faster); 3 = as 2 for the first Factorize, and
+ *                 the residual W - Q of the later ones is stored as two fp16 planes (hi + lo, 22 significant bits,
+ *                 scaled by a power of two): the products that steer the subspace read the hi plane, the projection
+ *                 that the singular values and factors come from reads both (warm_width <= 96, else as 2).
+ *                 Default 3.
  *   init_quantized  lq_decompose only: 1 starts Algorithm 2 from Q(0) = Quantize(W) instead of Q(0) = 0 (the
  *                 variant of the footnote in Section 3.1: the first Factorize then sees W - Quantize(W)).
  *                 lq_error_table rejects it (LQ_ERR_ARG): its configurations share the first Factorize.
@@ -109,6 +118,7 @@ typedef struct {
   int32_t streams;
   int32_t init_quantized;
   int32_t warm_power_coarse;
+  int32_t warm_power_fine;
 } lq_svd_params;
 
 const char* lq_status_string(int status);

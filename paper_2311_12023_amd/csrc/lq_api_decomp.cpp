@@ -31,7 +31,7 @@ static int64_t up64(int64_t x) { return (x + 63) / 64 * 64; }
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Params {
-  int l1, check, maxit, lw, qw, qw2, qw_coarse, max_batch, prec, streams, init_quantized;
+  int l1, check, maxit, lw, qw, qw2, qw_coarse, qw_fine, max_batch, prec, streams, init_quantized;
   double tol;
 };
 
@@ -47,6 +47,7 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   out.qw = z.warm_power ? z.warm_power : 2;
   out.qw2 = z.warm_power_2 ? z.warm_power_2 : 3;
   out.qw_coarse = z.warm_power_coarse ? z.warm_power_coarse : 4;
+  out.qw_fine = z.warm_power_fine ? z.warm_power_fine : 1;
   out.max_batch = z.max_batch ? z.max_batch : 36;
   if (z.gemm_mode < 0 || z.gemm_mode > 3) return LQ_ERR_ARG;
   // 0: fp32 MFMA everywhere; 1: large products on bf16 hi/lo splits; 2: as 1, and the residual W - Q of the warm
@@ -59,7 +60,7 @@ static int resolve_params(int rank, const lq_svd_params* p, Params& out) {
   if (out.l1 % 32 || out.l1 <= rank || out.l1 > 256) return LQ_ERR_ARG;
   if (out.lw % 32 || out.lw <= rank || out.lw > out.l1) return LQ_ERR_ARG;
   if (out.prec == 2 && !wide_gemm_f16_supported(out.lw)) out.prec = 1;
-  if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.qw_coarse < 1 || out.max_batch < 1) return LQ_ERR_ARG;
+  if (out.check < 1 || out.maxit < 1 || out.qw < 1 || out.qw2 < 1 || out.qw_coarse < 1 || out.qw_fine < 1 || out.max_batch < 1) return LQ_ERR_ARG;
   return LQ_OK;
 }
 
@@ -261,44 +262,55 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
   return LQ_OK;
 }
 
-// One warm-started Factorize for every problem of the batch: `power` subspace iterations on R_b
-// starting from the rows of Bsrc, then Rayleigh-Ritz.  Results land in Yw / Bw (swapped with Yw2 / Bw2).
+// One warm-started Factorize for every problem of the batch: power[b] subspace iterations on R_b starting from the
+// rows of Bsrc, then Rayleigh-Ritz.  Results land in Yw / Bw (swapped with Yw2 / Bw2).
+// power[] does not increase with b: the iterations are counted down, step j runs for the problems that have at least j
+// left (a prefix of the batch), so every problem's last iteration is the batch's last, which is the one that reads both
+// planes of the residual.  A problem enters at its first step with X = its rows of Bsrc and continues with X = the
+// projection B of the step before.
 struct WideSet { float* Yw; float* Yw2; float* Bw; float* Bw2; };
 
 static int batch_planes(const Ctx& c) { return c.pl.batch; }      // problems per plane set of the fp16 residual area
 
 static int warm_factorize(const Ctx& c, WideSet& w, const float* Bsrc, size_t sBsrc, const double* lamsrc, size_t sLam,
-                          int power, int batch) {
+                          const int* power, int batch) {
   const Plan& pl = c.pl;
   const int l = pl.prm.lw;
   const float* R = c.at<float>(pl.R);
   const uint16_t* R16 = c.at<uint16_t>(pl.R);
   const uint16_t* R16lo = R16 + pl.strideR * (size_t)batch_planes(c);
-  const float* X = Bsrc; size_t sX = sBsrc;
   const bool half = pl.prm.prec == 2;
   float* part = c.at<float>(pl.gpart);
   // fp16 residual: the rows of X = B (norms at most sigma_1, taken from the Ritz values the rows of Bsrc came with;
   // the products Y A of the later iterations have rows no longer than sigma_1 of the new residual, which the headroom
   // of the scale covers) are scaled per problem; an orthonormal X by 2^13.  Both products come back in true scale.
   const float ys = 8192.0f;
-  for (int it = 0; it < power; ++it) {
+  // problems first .. first + n - 1: Yw = X A^T with X = their rows of Xb (stride sX)
+  auto project_back = [&](const float* Xb, size_t sX, int first, int n) -> int {
+    if (n <= 0) return LQ_OK;
+    float* Y = w.Yw + pl.strideYw * (size_t)first;
     if (half)
-      LQ_TRY(launch_wide_gemm_f16(MODE_NT, l, pl.d, pl.k, X, pl.ldk, sX, R16, nullptr, pl.k, pl.strideR, w.Yw, pl.ldd,
-                                  pl.strideYw, batch, part, pl.gpart_floats, 1.0f, lamsrc, sLam, 1.0f / c.a_scale, c.st));
-    else
-      LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, X, pl.ldk, sX, R, pl.k, pl.strideR, w.Yw, pl.ldd, pl.strideYw, batch));
-    LQ_TRY(orthonormalize(c, w.Yw, w.Yw2, l, pl.d, pl.ldd, pl.strideYw, batch));
+      return launch_wide_gemm_f16(MODE_NT, l, pl.d, pl.k, Xb, pl.ldk, sX, R16 + pl.strideR * (size_t)first, nullptr, pl.k,
+                                  pl.strideR, Y, pl.ldd, pl.strideYw, n, part, pl.gpart_floats, 1.0f,
+                                  lamsrc + sLam * (size_t)first, sLam, 1.0f / c.a_scale, c.st);
+    return gemm(c, MODE_NT, l, pl.d, pl.k, Xb, pl.ldk, sX, R + pl.strideR * (size_t)first, pl.k, pl.strideR, Y, pl.ldd,
+                pl.strideYw, n);
+  };
+  auto active = [&](int j) { int n = 0; while (n < batch && power[n] >= j) ++n; return n; };
+  for (int j = power[0]; j >= 1; --j) {
+    const int n = active(j), carried = j < power[0] ? active(j + 1) : 0;
+    LQ_TRY(project_back(w.Bw, pl.strideBw, 0, carried));
+    LQ_TRY(project_back(Bsrc + sBsrc * (size_t)carried, sBsrc, carried, n - carried));
+    LQ_TRY(orthonormalize(c, w.Yw, w.Yw2, l, pl.d, pl.ldd, pl.strideYw, n));
     if (half)
       // the last product is the projection B = Y A that the Ritz values and the factors are read from: it takes both
       // planes of the residual (a rounding of A to fp16 would show in sigma to first order wherever a few entries carry a
       // singular vector); the products before it only steer the subspace and take the hi plane
-      LQ_TRY(launch_wide_gemm_f16(MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R16, it + 1 == power ? R16lo : nullptr,
-                                  pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw, batch, part, pl.gpart_floats, ys, nullptr, 0,
+      LQ_TRY(launch_wide_gemm_f16(MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R16, j == 1 ? R16lo : nullptr,
+                                  pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw, n, part, pl.gpart_floats, ys, nullptr, 0,
                                   1.0f / (ys * c.a_scale), c.st));
     else
-      LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R, pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw,
-                  batch));
-    X = w.Bw; sX = pl.strideBw;
+      LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, w.Yw, pl.ldd, pl.strideYw, R, pl.k, pl.strideR, w.Bw, pl.ldk, pl.strideBw, n));
   }
   LQ_TRY(ritz_rotate(c, l, w.Yw, w.Yw2, pl.strideYw, w.Bw, w.Bw2, pl.strideBw, c.at<double>(pl.lam), batch));
   std::swap(w.Yw, w.Yw2); std::swap(w.Bw, w.Bw2);
@@ -358,6 +370,12 @@ static int first_input(const Ctx& c, const float** A) {
 }
 
 static bool is_coarse(const lq_config& c) { return c.scale_bits != 0 && c.scale_bits <= 2; }
+// Codes of four or more bits on block scales of eight or more: Q follows W - L1 L2 closely, so W - Q changes little
+// from one pass to the next and the warm-started subspace is nearly invariant already.  (With 3-bit scales a 4-bit
+// configuration's error after a single subspace iteration was measured 1.3e-3 off.)
+static bool is_fine(const lq_config& c) { return c.bits >= 4 && (c.scale_bits == 0 || c.scale_bits >= 8); }
+// Order in which lq_error_table processes configurations: those that need the most subspace iterations first.
+static int power_class(const lq_config& c) { return is_coarse(c) ? 0 : (is_fine(c) ? 2 : 1); }
 
 struct LoopOut {          // batch == 1 only: user buffers that receive the quantized component directly
   uint8_t* codes; uint8_t* sidx; float* v; float* Qd;
@@ -378,7 +396,7 @@ struct Loop {
   const float* Y1 = nullptr; const float* B1 = nullptr;
   const LoopOut* direct = nullptr;
   const int* cfg_ids = nullptr;             // position of each configuration in the caller's list (NULL: 0, 1, ..)
-  int qw = 0, qw2 = 0;                      // subspace iterations per Factorize (second pass: qw2), set by begin()
+  std::vector<int> qw, qw2;                 // subspace iterations per Factorize and problem (second pass: qw2), set by begin()
   // state
   std::vector<LoopProblem> probs;
   std::vector<double> host_err;
@@ -414,10 +432,16 @@ struct Loop {
     }
     // A scale quantizer with a single level (b1 = 2: every block scale is 0 or v) leaves a residual W - Q that moves a lot
     // from pass to pass, and the warm-started subspace needs more iterations to follow it.
-    bool coarse = false;
-    for (int b = 0; b < batch; ++b) coarse = coarse || is_coarse(cfgs[b]);
-    qw = coarse ? std::max(pl.prm.qw, pl.prm.qw_coarse) : pl.prm.qw;
-    qw2 = coarse ? std::max(pl.prm.qw2, pl.prm.qw_coarse) : pl.prm.qw2;
+    // Codes of at least four bits need fewer (one) from the third pass on.  warm_factorize wants counts that do not
+    // increase along the batch (lq_error_table orders the configurations that way): otherwise all take the largest.
+    qw.assign(batch, 0); qw2.assign(batch, 0);
+    for (int b = 0; b < batch; ++b) {
+      const bool coarse = is_coarse(cfgs[b]);
+      qw[b] = coarse ? std::max(pl.prm.qw, pl.prm.qw_coarse) : (is_fine(cfgs[b]) ? pl.prm.qw_fine : pl.prm.qw);
+      qw2[b] = coarse ? std::max(pl.prm.qw2, pl.prm.qw_coarse) : pl.prm.qw2;
+    }
+    for (std::vector<int>* q : {&qw, &qw2})
+      if (!std::is_sorted(q->rbegin(), q->rend())) q->assign(batch, *std::max_element(q->begin(), q->end()));
     LoopProblem* dprob = c->at<LoopProblem>(pl.prob);
     LQ_HIP_TRY(hipMemcpyAsync(dprob, probs.data(), sizeof(LoopProblem) * batch, hipMemcpyHostToDevice, c->st));
     w = WideSet{c->at<float>(pl.Yw), c->at<float>(pl.Yw2), c->at<float>(pl.Bw), c->at<float>(pl.Bw2)};
@@ -523,7 +547,7 @@ struct Loop {
     else a.R = c->at<float>(pl.R);
     LQ_TRY(launch_residual(a, c->st));
     a.R16 = nullptr; a.R16lo = nullptr;
-    LQ_TRY(warm_factorize(*c, w, Bcur, sB, lamcur, sLam, t == 1 ? qw2 : qw, batch));
+    LQ_TRY(warm_factorize(*c, w, Bcur, sB, lamcur, sLam, (t == 1 ? qw2 : qw).data(), batch));
     Ycur = w.Yw; Bcur = w.Bw; sY = pl.strideYw; sB = pl.strideBw;
     lamcur = c->at<double>(pl.lam); sLam = pl.prm.lw;
 #ifdef LQ_TESTING_HOOKS
@@ -789,12 +813,13 @@ int lq_error_table(const float* W, int64_t d, int64_t k, int rank, const lq_conf
     if (cc.block > 128) return LQ_ERR_CONFIG;
     if (k % cc.block != 0) return LQ_ERR_SHAPE;
   }
-  // Configurations with a single-level scale quantizer get more subspace iterations per pass (see Loop::begin); they
-  // are moved to the front, keeping the caller's order otherwise, so that they share lock-step batches.  order[i] is
-  // the caller's index of the i-th configuration processed.
+  // The number of subspace iterations per pass depends on the configuration (see Loop::begin: most for a single-level
+  // scale quantizer, fewest for codes of four or more bits): configurations are processed by class, keeping the
+  // caller's order within a class, so that lock-step batches are as uniform as possible.  order[i] is the caller's
+  // index of the i-th configuration processed.
   std::vector<int> order(n_cfgs);
   for (int i = 0; i < n_cfgs; ++i) order[i] = i;
-  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return is_coarse(cf[a]) > is_coarse(cf[b]); });
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return power_class(cf[a]) < power_class(cf[b]); });
   {
     std::vector<lq_config> sorted(n_cfgs);
     for (int i = 0; i < n_cfgs; ++i) sorted[i] = cf[order[i]];

@@ -44,7 +44,8 @@ class SvdParams(C.Structure):
     _fields_ = [("first_width", C.c_int32), ("first_tol", C.c_float), ("first_check", C.c_int32),
                 ("first_max", C.c_int32), ("warm_width", C.c_int32), ("warm_power", C.c_int32),
                 ("warm_power_2", C.c_int32), ("max_batch", C.c_int32), ("gemm_mode", C.c_int32),
-                ("streams", C.c_int32), ("init_quantized", C.c_int32), ("warm_power_coarse", C.c_int32)]
+                ("streams", C.c_int32), ("init_quantized", C.c_int32), ("warm_power_coarse", C.c_int32),
+                ("warm_power_fine", C.c_int32)]
 
 
 if not os.path.exists(LIB_PATH):
