@@ -158,7 +158,7 @@ int launch_row_sumsq(const float* X, int l, int64_t m, int64_t ldx, size_t strid
 // out[1024] = max |x[i]| over n floats (out[0..1023]: per-workgroup maxima); non-finite values are skipped.
 int launch_absmax(const float* x, int64_t n, float* out, hipStream_t st);
 // X <- X - alpha * Y, both `count` floats (multiple of 4).
-int launch_axpy_sub(float* X, const float* Y, float alpha, int64_t count, hipStream_t st);
+int launch_lincomb3(float* X, float a, const float* Y, float b, const float* Z, float c, int64_t count, hipStream_t st);
 // Fills a wide matrix (l x m, padded ld) with N(0,1) draws from a counter-based generator; pads are zeroed.
 int launch_gaussian_fill(float* X, int l, int64_t m, int64_t ldx, uint64_t seed, hipStream_t st);
 // out[i][j] = sr[i] * A[i][j] * sc[j]  (sr = sqrt(row_w), sc = sqrt(col_w): D_row A D_col of Eq. 5).

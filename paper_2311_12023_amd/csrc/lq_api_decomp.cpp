@@ -79,7 +79,7 @@ struct Plan {
   Params prm;
   // shared
   size_t sr, sc, rsr, rsc;              // floats: d, k, d, k
-  size_t Ya, Yb, Ba, Bb;                // cold-start wide bases (l1 rows)
+  size_t Ya, Yb, Yc, Yd, Ba, Bb;        // cold-start wide bases (l1 rows)
   size_t gpart, gram_part, G, Vt, Ut, lam, lam_cold, prob, errs;
   // per problem (offset of problem 0, stride)
   size_t R, strideR;
@@ -99,6 +99,7 @@ static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int bat
   const int l1 = prm.l1, lw = prm.lw;
   pl.sr = take(d * 4); pl.sc = take(k * 4); pl.rsr = take(d * 4); pl.rsc = take(k * 4);
   pl.Ya = take((size_t)l1 * pl.ldd * 4); pl.Yb = take((size_t)l1 * pl.ldd * 4);
+  pl.Yc = take((size_t)l1 * pl.ldd * 4); pl.Yd = take((size_t)l1 * pl.ldd * 4);
   pl.Ba = take((size_t)l1 * pl.ldk * 4); pl.Bb = take((size_t)l1 * pl.ldk * 4);
   pl.gpart_floats = std::max(gemm_part_floats(l1, 0), gemm_part_floats(lw, 0));
   pl.gpart = take(pl.gpart_floats * 4);
@@ -193,35 +194,49 @@ static int ritz_rotate(const Ctx& c, int l, const float* Y, float* Y2, size_t sY
 
 // Cold-start randomized SVD of A (d x k): on return *Yout / *Bout (l1 rows, Ritz order) and lam_cold.
 //
-// Subspace iteration on the shifted operator A A^T - alpha I, alpha = half the smallest Ritz value of the block:
-// same invariant subspaces, but the contraction factor per iteration improves from (s_{l+1}/s_r)^2 to
-// (s_{l+1}^2 - alpha)/(s_r^2 - alpha), about twice as fast on the flat spectra of weight matrices.  Convergence is
-// judged on the top-`rank` Ritz values; the Rayleigh-Ritz steps are scheduled from the observed rate instead
-// of at a fixed period, since each one costs an l x l eigen-solve.
+// Chebyshev-filtered subspace iteration on M = A A^T.  With theta_1 >= .. >= theta_l the Ritz values of the block, the
+// part of the spectrum below b = theta_l is what the block must lose; T_m mapped to [0, b] stays within +-1 there and
+// grows like cosh(m acosh(2 lambda / b - 1)) above, so on the flat spectra of weight matrices m filter steps separate
+// the wanted directions like ~m^2 / 2 power iterations would.  Any cut-off is stable (the interval starts at 0, below
+// the whole spectrum); a poor b only costs speed.  A cycle is m steps of the three-term recurrence
+//   Y_1 = (2/b) Y_0 M - Y_0,   Y_{j+1} = (4/b) Y_j M - 2 Y_j - Y_{j-1}
+// from an orthonormal Y_0, then one Cholesky-QR.  The rows are independent under the recurrence, and after a
+// Rayleigh-Ritz the rows that matter for convergence (around theta_rank) are orthogonal to the dominant directions up
+// to rounding, ~1e-6; the recurrence amplifies that leak by T_m(2 theta_1 / b - 1) / T_m(2 theta_rank / b - 1), and m is
+// limited so that this stays below `growth` = 1e5 (the leak stays a small part of the row).  For a spectrum with a
+// strongly dominant part that gives m = 1, which is subspace iteration on M - (b/2) I.  Before the first Rayleigh-Ritz
+// there is no b: plain power steps.
+// Convergence is judged on the top-`rank` Ritz values; the Rayleigh-Ritz steps are scheduled from the observed rate
+// instead of at a fixed period, since each one costs an l x l eigen-solve.
 static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const float** Yout, const float** Bout) {
   const Plan& pl = c.pl;
   const int l = pl.prm.l1, r = pl.rank;
-  float* Ya = c.at<float>(pl.Ya); float* Yb = c.at<float>(pl.Yb);
+  float* Y0 = c.at<float>(pl.Ya);                                         // orthonormal rows: start of the cycle
+  float* P[3] = {c.at<float>(pl.Yb), c.at<float>(pl.Yc), c.at<float>(pl.Yd)};   // the other three of four row blocks
   float* Ba = c.at<float>(pl.Ba); float* Bb = c.at<float>(pl.Bb);
   double* lam = c.at<double>(pl.lam_cold);
-  LQ_HIP_TRY(hipMemsetAsync(Ya, 0, (size_t)l * pl.ldd * 4, c.st));
-  LQ_HIP_TRY(hipMemsetAsync(Yb, 0, (size_t)l * pl.ldd * 4, c.st));
+  const int64_t ycount = (int64_t)l * pl.ldd;
+  LQ_HIP_TRY(hipMemsetAsync(Y0, 0, ycount * 4, c.st));
+  for (float* p : P) LQ_HIP_TRY(hipMemsetAsync(p, 0, ycount * 4, c.st));
   LQ_HIP_TRY(hipMemsetAsync(Bb, 0, (size_t)l * pl.ldk * 4, c.st));
   LQ_TRY(launch_gaussian_fill(Ba, l, pl.k, pl.ldk, seed, c.st));
-  LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Ya, pl.ldd, 0, 1));
-  LQ_TRY(orthonormalize(c, Ya, Yb, l, pl.d, pl.ldd, 0, 1));
+  LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Y0, pl.ldd, 0, 1));
+  LQ_TRY(orthonormalize(c, Y0, P[0], l, pl.d, pl.ldd, 0, 1));
   std::vector<double> prev(r, 0.0), cur(l, 0.0);
   bool have_prev = false;
-  double alpha = 0.0;
+  double bcut = 0.0, top = 0.0, wanted = 0.0;   // filter cut-off theta_l, theta_1 and theta_rank of the last Rayleigh-Ritz (0: none yet)
   double last_delta = -1.0;   // change of the Ritz values over the previous gap (valid when rate_ok)
-  double kappa = 0.0;         // observed decay rate of the error per iteration (natural log), 0 = unknown
-  int next_check = pl.prm.check, last_check = 0, last_gap = 0;
-  bool rate_ok = false;       // last_delta was measured with the current shift
-  for (int it = 1; it <= pl.prm.maxit; ++it) {
-    LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, Ya, pl.ldd, 0, A, pl.k, 0, Ba, pl.ldk, 0, 1));
-    if (it >= next_check || it == pl.prm.maxit) {
-      LQ_TRY(ritz_rotate(c, l, Ya, Yb, 0, Ba, Bb, 0, lam, 1));
-      std::swap(Ya, Yb); std::swap(Ba, Bb);
+  double kappa = 0.0;         // observed decay rate of the error per application of M (natural log), 0 = unknown
+  const int first_gap = std::min(2, pl.prm.check);
+  int next_check = first_gap, last_check = 0, last_gap = 0, m_prev = 1;
+  bool rate_ok = false;       // last_delta was measured with the current cut-off
+  const double growth = 1.0e5;
+  const int m_max = 8;
+  for (int it = 0;;) {        // it: applications of M so far
+    LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, Y0, pl.ldd, 0, A, pl.k, 0, Ba, pl.ldk, 0, 1));
+    if (it >= next_check || it >= pl.prm.maxit) {
+      LQ_TRY(ritz_rotate(c, l, Y0, P[0], 0, Ba, Bb, 0, lam, 1));
+      std::swap(Y0, P[0]); std::swap(Ba, Bb);
       LQ_HIP_TRY(hipMemcpyAsync(cur.data(), lam, sizeof(double) * l, hipMemcpyDeviceToHost, c.st));
       LQ_HIP_TRY(hipStreamSynchronize(c.st));
       double delta = 0.0;
@@ -232,13 +247,13 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
       }
       const int gap = it - last_check;
       // The error decays geometrically, err(it) ~ exp(-kappa it), so the change over a gap is
-      // err(it) (exp(kappa gap) - 1).  kappa comes from two successive equal-shift gaps, derated by 0.7.
+      // err(it) (exp(kappa gap) - 1).  kappa comes from two successive equal-filter gaps, derated by 0.7.
       if (have_prev && rate_ok && last_delta > 0 && delta > 0 && delta < last_delta && gap == last_gap)
         kappa = 0.7 * std::log(last_delta / delta) / gap;
       double err_est = delta;
       if (kappa > 0) err_est = std::min(delta, delta / std::expm1(kappa * gap));
       const bool done = have_prev && err_est <= pl.prm.tol;
-      if (done || it == pl.prm.maxit) break;
+      if (done || it >= pl.prm.maxit) break;
       // next Rayleigh-Ritz where the error is predicted to reach the tolerance
       int next_gap = pl.prm.check;
       if (kappa > 0 && have_prev) {
@@ -249,16 +264,36 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
       last_delta = delta; last_gap = gap; last_check = it; next_check = it + next_gap;
       for (int j = 0; j < r; ++j) prev[j] = cur[j];
       have_prev = true;
-      const double new_alpha = 0.5 * cur[l - 1];
-      if (new_alpha > 1.25 * alpha) { alpha = new_alpha; rate_ok = false; kappa = 0.0; next_check = it + pl.prm.check; }
+      // the cut-off follows theta_l upwards; a change of the filter invalidates the measured rate
+      const bool usable = cur[0] > 0 && cur[l - 1] > 1e-12 * cur[0] && std::isfinite(cur[0]);
+      if (usable && cur[l - 1] > 1.1 * bcut) { bcut = cur[l - 1]; rate_ok = false; kappa = 0.0; next_check = it + pl.prm.check; }
+      if (usable) { top = cur[0]; wanted = cur[r - 1]; }
     }
-    // Y <- orth((A A^T - alpha I) Y)
-    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Yb, pl.ldd, 0, 1));
-    if (alpha > 0.0) LQ_TRY(launch_axpy_sub(Yb, Ya, (float)alpha, (int64_t)l * pl.ldd, c.st));
-    LQ_TRY(orthonormalize(c, Yb, Ya, l, pl.d, pl.ldd, 0, 1));
-    std::swap(Ya, Yb);
+    // one cycle: m filter steps from Y0, then Cholesky-QR
+    int m = 1;
+    if (bcut > 0.0) {
+      const double x1 = std::max(2.0 * top / bcut - 1.0, 1.0 + 1e-9);
+      const double xr = std::max(2.0 * wanted / bcut - 1.0, 1.0);
+      auto cheb = [](int deg, double x) { return std::cosh(deg * std::acosh(x)); };
+      while (m < std::min(m_max, 2 * m_prev) && cheb(m + 1, x1) <= growth * cheb(m + 1, xr)) ++m;
+    }
+    m = std::max(1, std::min(m, std::min(next_check, pl.prm.maxit) - it));
+    m_prev = m;
+    // step 1 (Ba = Y0 A is at hand)
+    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, P[0], pl.ldd, 0, 1));
+    if (bcut > 0.0) LQ_TRY(launch_lincomb3(P[0], (float)(2.0 / bcut), Y0, -1.0f, nullptr, 0.0f, ycount, c.st));
+    float* Yj = P[0]; float* Yjm1 = Y0; float* Ynew = P[1]; float* spare = P[2];
+    for (int j = 1; j < m; ++j) {
+      LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, Yj, pl.ldd, 0, A, pl.k, 0, Bb, pl.ldk, 0, 1));
+      LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Bb, pl.ldk, 0, A, pl.k, 0, Ynew, pl.ldd, 0, 1));
+      LQ_TRY(launch_lincomb3(Ynew, (float)(4.0 / bcut), Yj, -2.0f, Yjm1, -1.0f, ycount, c.st));
+      float* freed = Yjm1; Yjm1 = Yj; Yj = Ynew; Ynew = freed;
+    }
+    LQ_TRY(orthonormalize(c, Yj, spare, l, pl.d, pl.ldd, 0, 1));    // Yj now names the orthonormal block, spare the old one
+    Y0 = Yj; P[0] = Yjm1; P[1] = Ynew; P[2] = spare;
+    it += m;
   }
-  *Yout = Ya; *Bout = Ba;
+  *Yout = Y0; *Bout = Ba;
   return LQ_OK;
 }
 

@@ -652,22 +652,26 @@ int launch_absmax(const float* x, int64_t n, float* out, hipStream_t st) {
   return LQ_OK;
 }
 
-// X <- X - alpha * Y over `count` floats (count a multiple of 4).
-__global__ __launch_bounds__(256) void axpy_sub_kernel(float* __restrict__ X, const float* __restrict__ Y, float alpha,
-                                                       int64_t count4) {
+// X <- a X + b Y + c Z over `count` floats (count a multiple of 4; Z may be NULL: no third term).
+__global__ __launch_bounds__(256) void lincomb3_kernel(float* __restrict__ X, float a, const float* __restrict__ Y, float b,
+                                                       const float* __restrict__ Z, float c, int64_t count4) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += (int64_t)gridDim.x * 256) {
     float4 x = reinterpret_cast<float4*>(X)[i];
     const float4 y = reinterpret_cast<const float4*>(Y)[i];
-    x.x = fmaf(-alpha, y.x, x.x); x.y = fmaf(-alpha, y.y, x.y); x.z = fmaf(-alpha, y.z, x.z); x.w = fmaf(-alpha, y.w, x.w);
+    x.x = fmaf(a, x.x, b * y.x); x.y = fmaf(a, x.y, b * y.y); x.z = fmaf(a, x.z, b * y.z); x.w = fmaf(a, x.w, b * y.w);
+    if (Z != nullptr) {
+      const float4 z = reinterpret_cast<const float4*>(Z)[i];
+      x.x = fmaf(c, z.x, x.x); x.y = fmaf(c, z.y, x.y); x.z = fmaf(c, z.z, x.z); x.w = fmaf(c, z.w, x.w);
+    }
     reinterpret_cast<float4*>(X)[i] = x;
   }
 }
 
-int launch_axpy_sub(float* X, const float* Y, float alpha, int64_t count, hipStream_t st) {
+int launch_lincomb3(float* X, float a, const float* Y, float b, const float* Z, float c, int64_t count, hipStream_t st) {
   const int64_t count4 = count / 4;
   const int64_t want = (count4 + 255) / 256;
-  prof::Scope ps(prof::MISC, st, (double)count * 12.0);
-  hipLaunchKernelGGL(axpy_sub_kernel, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, st, X, Y, alpha, count4);
+  prof::Scope ps(prof::MISC, st, (double)count * (Z ? 16.0 : 12.0));
+  hipLaunchKernelGGL(lincomb3_kernel, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, st, X, a, Y, b, Z, c, count4);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }
