@@ -562,7 +562,8 @@ def bench_sweep(args, torch, gen, lq, dev) -> int:
                   "against the residual kept as fp16 hi + lo planes; fp32 accumulation)") if split else "f32",
         "data": "synthetic",
         "config": {"workload": label, "baseline_config": wl, "matrices": n_mats, "configs": n_cfgs, "iters": iters,
-                   "rank": rank, "concurrent_matrices": nthreads},
+                   "rank": rank, "concurrent_matrices": nthreads,
+                   "hip_hardware_queues": args.hw_queues},
         "roofline": roof,
         "roofline_note": "the kernel class with the largest summed duration among the machine-filling classes (large "
                          "GEMMs against HBM for the operand they stream, with the executed 16-bit MFMA work beside it; the "
@@ -629,7 +630,19 @@ def main() -> int:
     ap.add_argument("--workload", choices=("sweep", "quant", "matmul"), default="sweep")
     ap.add_argument("--tokens", type=int, default=4096, help="rows of X for --workload matmul")
     ap.add_argument("--precision", type=int, default=0, help="lq_matmul precision for --workload matmul (0 split, 1 bf16)")
+    ap.add_argument("--hw-queues", type=int, default=None,
+                    help="HIP hardware queues of this process (GPU_MAX_HW_QUEUES, 1..32).  Default 8 for the sweeps of "
+                         "workloads 3 and 5, the runtime's own 4 otherwise.  Workload 3 keeps up to 14 streams busy (7 "
+                         "matrices x 2 sub-batches); with 4 queues the streams share queues and a latency-bound "
+                         "single-workgroup kernel (Cholesky, Jacobi) of one stream holds back the machine-filling kernels "
+                         "of another in the same queue: 8 measured 4 %% faster, 14 no better.  Workload 2 (small "
+                         "matrices, every kernel latency-bound) measured 16 %% slower with 8 than with 4")
     args = ap.parse_args()
+    if args.hw_queues is None:
+        args.hw_queues = 8 if (args.workload == "sweep" and args.config in (3, 5)) else 4
+    if not 1 <= args.hw_queues <= 32:
+        ap.error("--hw-queues must be within 1..32")
+    os.environ["GPU_MAX_HW_QUEUES"] = str(args.hw_queues)       # read by the HIP runtime when it starts: before torch
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sweep shards over GPUs by "
               "matrix without any collective, see DESIGN.md).", file=sys.stderr)

@@ -53,6 +53,43 @@ def test_factorize_matches_exact_svd(env, oracle, shape, rank, planted, outl):
     assert np.allclose(l1h.T.astype(np.float64) @ l1h, np.diag(osg), atol=2e-4 * osg[0])
 
 
+def spectrum_case(kind):
+    """Matrices whose spectra drive the cold start's filter to its different regimes."""
+    rng = np.random.default_rng(20231112)
+    if kind == "flat":                  # pure noise: no dominant part, the longest filter cycles
+        return gen.weight_matrix(512, 768, 99, 0), 16
+    if kind == "dominant":              # one direction 100 times above a flat bulk: filter degree held down by the leak rule
+        w = rng.standard_normal((384, 640)) * 0.02
+        w += 100.0 * 0.02 * np.sqrt(640) * np.outer(rng.standard_normal(384) / np.sqrt(384), rng.standard_normal(640) / np.sqrt(640))
+        return w.astype(np.float32), 12
+    if kind == "geometric":             # sigma_i = 0.8^i over a noise floor 1e-4 of sigma_1
+        u, _ = np.linalg.qr(rng.standard_normal((320, 64)))
+        v, _ = np.linalg.qr(rng.standard_normal((576, 64)))
+        w = (u * 0.8 ** np.arange(64)) @ v.T + 1e-4 / np.sqrt(576) * rng.standard_normal((320, 576))
+        return w.astype(np.float32), 12
+    if kind == "low_rank":              # rank 6 plus noise at 1e-5: the block's smallest Ritz values are noise
+        w = rng.standard_normal((256, 6)) @ rng.standard_normal((6, 512)) / 16 + 1e-5 * rng.standard_normal((256, 512))
+        return w.astype(np.float32), 4
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind", ["flat", "dominant", "geometric", "low_rank"])
+def test_factorize_spectra(env, kind):
+    """Factorize (Algorithm 4 with the randomized SVD of Section 3.1, footnote 1) on spectra other than the benchmark's:
+    singular values and the Eckart-Young optimum against LAPACK."""
+    torch, lq = env
+    w, rank = spectrum_case(kind)
+    l1, l2, sg = lq.factorize(torch.from_numpy(w).cuda(), rank, seed=11)
+    ref = np.linalg.svd(w.astype(np.float64), compute_uv=False)
+    rel = np.max(np.abs(sg - ref[:rank]) / ref[:rank])
+    print(f"{kind}: sigma rel {rel:.2e}")
+    assert rel < SV_TOL
+    l1h, l2h = l1.cpu().numpy().astype(np.float64), l2.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(sv_of_factors(l1h, l2h) - ref[:rank]) / ref[:rank]) < SV_TOL
+    tail = np.sum(ref[rank:] ** 2)
+    assert abs(np.sum((w.astype(np.float64) - l1h @ l2h) ** 2) - tail) < 1e-4 * tail + 1e-10 * np.sum(ref ** 2)
+
+
 def test_factorize_weighted(env, oracle):
     torch, lq = env
     d, k, r = 320, 512, 8
