@@ -127,6 +127,31 @@ def test_argument_validation_without_gpu(L):
 
 
 
+def header_struct(name):
+    """[(field, C type)] of `typedef struct { ... } name;` in include/lq.h."""
+    text = open(os.path.join(ROOT, "include", "lq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    body = re.search(r"typedef\s+struct\s*\{([^}]*)\}\s*" + name + r"\s*;", text).group(1)
+    return [(m.group(2), m.group(1)) for m in re.finditer(r"(\w+)\s+(\w+)\s*;", body)]
+
+
+def test_binding_structs_mirror_the_header(L):
+    """The ctypes structures of the binding have the header's fields, in order and with the same types: a field added on
+    one side only would shift every later one."""
+    from paper_2311_12023_amd import lq
+    ctype = {"int32_t": C.c_int32, "float": C.c_float, "int64_t": C.c_int64, "double": C.c_double}
+    for cname, pytype in (("lq_svd_params", lq.SvdParams), ("lq_config", lq.Config)):
+        fields = header_struct(cname)
+        assert len(fields) >= 5
+        assert [(n, ctype[t]) for n, t in fields] == list(pytype._fields_), cname
+    # a bad value in the last field is seen by the library (so the whole structure arrives): workspace query -> 0
+    L.lq_error_table_workspace_bytes.restype = C.c_size_t
+    L.lq_error_table_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p]
+    good, bad = lq.SvdParams(warm_power_fine=2), lq.SvdParams(warm_power_fine=-1)
+    assert L.lq_error_table_workspace_bytes(256, 512, 8, 4, C.byref(good)) > 0
+    assert L.lq_error_table_workspace_bytes(256, 512, 8, 4, C.byref(bad)) == 0
+
+
 def test_fisher_helper_validation_without_gpu(L):
     vp, i64 = C.c_void_p, C.c_int64
     L.lq_fisher_row_col.argtypes = [vp, i64, i64, vp, vp, vp, C.c_size_t, vp]
