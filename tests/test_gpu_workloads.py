@@ -80,6 +80,21 @@ def test_workload4_fisher_weighted(env, oracle):
     assert out["err"] < weighted_err_of_plain
 
 
+def test_weighted_four_bit_configuration_large(env, oracle):
+    """A configuration that takes a single subspace iteration per pass (4-bit codes on 8-bit scales) on the 11008 x 4096
+    shape with Fisher weights: the first such pass (3) and a later one (6) anchored, pieces consistent."""
+    torch, lq = env
+    w = gen.workload_matrix(3, 6)
+    assert w.shape == (11008, 4096)
+    f = gen.fisher_matrix(11008, 4096, gen.matrix_seed(4, 2)).astype(np.float64)
+    rw, cw = (x.astype(np.float32) for x in oracle.fisher_row_col(f))
+    del f
+    out = anchor.check_anchored_decompose(oracle, lq, torch, w, 64, (4, 32, 64), 6, seed=8, row_w=rw, col_w=cw,
+                                          which=[3, 6], label="weighted NF4")
+    assert out["iters_done"] == 6 and out["trace"][-1] < out["trace"][0]
+    check_decomposition_consistency(oracle, w, out, oracle.config(4, 32, 64), 64, rw, cw)
+
+
 @pytest.mark.parametrize("index", [4, 6])
 def test_workload5_largest_shapes(env, oracle, index):
     """8192 x 28672 and 28672 x 8192 (235 M weights, the largest matrices of a LLaMA-2-70B block): two iterations, returned
