@@ -408,20 +408,34 @@ __global__ __launch_bounds__(JT) void jacobi_eig_kernel(double* __restrict__ Gal
   }
 }
 
+// Sum over the 16 lanes of a DPP row (quad swaps, then the two mirrors), every lane gets the total; no LDS traffic.
+__device__ __forceinline__ float row16_sum(float x) {
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, false));   // row_half_mirror
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, false));   // row_mirror
+  return x;
+}
+
 // One-sided (Hestenes) Jacobi in fp32, everything in LDS (l = 16*NE <= 128).  Works on X = M itself:
 // rotating the columns of X = M J until they are mutually orthogonal makes J^T M^2 J diagonal, so J holds
 // the eigenvectors of the symmetric M and the column norms are the eigenvalues.  fp32 rotations give
 // eigenvectors good to about 1e-6; the Ritz values are not taken from here but recomputed in fp64 from
 // the rotated basis (row_sumsq_kernel), which is second-order accurate in the eigenvector error.
-// 16 lanes per column pair; a round handles l/2 disjoint pairs, one barrier per round.
+// 16 lanes per column pair, each lane owning NE consecutive entries of both columns (64-bit LDS accesses); a round
+// handles l/2 disjoint pairs, one barrier per round.  The squared column norms are kept in LDS and updated with the
+// rotation (|x_p|^2 -= t g, |x_q|^2 += t g), so a round computes one inner product instead of three; they are
+// recomputed from the columns at the start of every sweep, and they only enter the angle and the skip test (the inner
+// product that a rotation annihilates is always computed from the columns themselves).
 template <int NE>
 __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __restrict__ Gall, float* __restrict__ Utall,
                                                               double* __restrict__ lamall) {
-  constexpr int l = 16 * NE, P = l + 1;
-  extern __shared__ float fl[];             // X[l][P] then V[l][P], column c at row c
+  constexpr int l = 16 * NE, P = l + 2;     // even pitch: every lane's chunk starts on an 8-byte boundary
+  extern __shared__ __attribute__((aligned(16))) float fl[];   // X[l][P] then V[l][P], column c at row c
   __shared__ int s_rot;
   __shared__ float s_big;
   __shared__ float s_norm[128];
+  __shared__ float s_n2[128];
   __shared__ int s_rank[128];
   float* X = fl;
   float* V = fl + l * P;
@@ -443,9 +457,23 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
     V[c * P + i] = (c == i) ? 1.0f : 0.0f;
   }
   const int g = tid >> 4, sub = tid & 15;
+  const int eo = NE * sub;                    // this lane's entries of a column: eo .. eo + NE - 1
   __syncthreads();
   for (int sweep = 0; sweep < 30; ++sweep) {
     if (tid == 0) { s_rot = 0; s_big = 0.0f; }
+    // squared norms of the columns, fresh from the columns: group g takes columns g and g + l/2
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c = g + h * (l / 2);
+      float n2 = 0.f;
+#pragma unroll
+      for (int e = 0; e < NE; e += 2) {
+        const float2 x = *reinterpret_cast<const float2*>(X + c * P + eo + e);
+        n2 = fmaf(x.x, x.x, n2); n2 = fmaf(x.y, x.y, n2);
+      }
+      n2 = row16_sum(n2);
+      if (sub == 0) s_n2[c] = n2;
+    }
     __syncthreads();
     float worst = 0.0f;
     bool rotated = false;
@@ -453,17 +481,24 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
       int p, q;
       rr_pair(g, round, l, p, q);
       float xp[NE], xq[NE];
-      float al = 0.f, be = 0.f, ga = 0.f;
+      float ga = 0.f;
 #pragma unroll
-      for (int e = 0; e < NE; ++e) {
-        xp[e] = X[p * P + sub + 16 * e];
-        xq[e] = X[q * P + sub + 16 * e];
-        al = fmaf(xp[e], xp[e], al); be = fmaf(xq[e], xq[e], be); ga = fmaf(xp[e], xq[e], ga);
+      for (int e = 0; e < NE; e += 2) {
+        const float2 a = *reinterpret_cast<const float2*>(X + p * P + eo + e);
+        const float2 b = *reinterpret_cast<const float2*>(X + q * P + eo + e);
+        xp[e] = a.x; xp[e + 1] = a.y; xq[e] = b.x; xq[e + 1] = b.y;
+        ga = fmaf(a.x, b.x, ga); ga = fmaf(a.y, b.y, ga);
       }
+      const float al = s_n2[p], be = s_n2[q];
+      // the eigenvector entries are fetched now, whether or not the pair rotates: their latency passes behind the
+      // reduction and the angle
+      float2 vp[NE / 2], vq[NE / 2];
 #pragma unroll
-      for (int off = 1; off < 16; off <<= 1) {
-        al += __shfl_xor(al, off); be += __shfl_xor(be, off); ga += __shfl_xor(ga, off);
+      for (int e = 0; e < NE; e += 2) {
+        vp[e / 2] = *reinterpret_cast<const float2*>(V + p * P + eo + e);
+        vq[e / 2] = *reinterpret_cast<const float2*>(V + q * P + eo + e);
       }
+      ga = row16_sum(ga);
       // hardware reciprocal / square-root approximations (1 ulp) are enough here: a rotation that is orthogonal
       // to 1e-7 and an angle that misses the exact one by 1e-7 change nothing in the convergence, and the
       // eigenvector rows are renormalised at the end
@@ -475,12 +510,20 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
         const float tt = copysignf(__builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.0f + zeta * zeta)), zeta);
         const float cs = __builtin_amdgcn_rsqf(1.0f + tt * tt), sn = cs * tt;
 #pragma unroll
-        for (int e = 0; e < NE; ++e) {
-          X[p * P + sub + 16 * e] = cs * xp[e] - sn * xq[e];
-          X[q * P + sub + 16 * e] = sn * xp[e] + cs * xq[e];
-          const float vp = V[p * P + sub + 16 * e], vq = V[q * P + sub + 16 * e];
-          V[p * P + sub + 16 * e] = cs * vp - sn * vq;
-          V[q * P + sub + 16 * e] = sn * vp + cs * vq;
+        for (int e = 0; e < NE; e += 2) {
+          float2 a, b;
+          a.x = cs * xp[e] - sn * xq[e];         a.y = cs * xp[e + 1] - sn * xq[e + 1];
+          b.x = sn * xp[e] + cs * xq[e];         b.y = sn * xp[e + 1] + cs * xq[e + 1];
+          *reinterpret_cast<float2*>(X + p * P + eo + e) = a;
+          *reinterpret_cast<float2*>(X + q * P + eo + e) = b;
+          a.x = cs * vp[e / 2].x - sn * vq[e / 2].x;   a.y = cs * vp[e / 2].y - sn * vq[e / 2].y;
+          b.x = sn * vp[e / 2].x + cs * vq[e / 2].x;   b.y = sn * vp[e / 2].y + cs * vq[e / 2].y;
+          *reinterpret_cast<float2*>(V + p * P + eo + e) = a;
+          *reinterpret_cast<float2*>(V + q * P + eo + e) = b;
+        }
+        if (sub == 0) {                          // the pairs of a round are disjoint: nobody else touches these two
+          s_n2[p] = fmaxf(al - tt * ga, 0.0f);
+          s_n2[q] = be + tt * ga;
         }
       }
       __syncthreads();
@@ -524,7 +567,7 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
 template <int NE>
 static int launch_onesided(const double* G, float* Ut, double* lambda, int batch, hipStream_t st) {
   constexpr int l = 16 * NE;
-  const size_t need = (size_t)2 * l * (l + 1) * sizeof(float);
+  const size_t need = (size_t)2 * l * (l + 2) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
     LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_onesided_kernel<NE>),
