@@ -408,13 +408,44 @@ __global__ __launch_bounds__(JT) void jacobi_eig_kernel(double* __restrict__ Gal
   }
 }
 
-// Sum over the 16 lanes of a DPP row (quad swaps, then the two mirrors), every lane gets the total; no LDS traffic.
-__device__ __forceinline__ float row16_sum(float x) {
+// Sum over the LP = 16 lanes of a DPP row, or over its 8-lane halves (quad swaps, then the mirrors); every lane gets the
+// total, bit-identical in all of them (each step adds the same two numbers in both lanes); no LDS traffic.
+template <int LP>
+__device__ __forceinline__ float lanes_sum(float x) {
   x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
   x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
   x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, false));   // row_half_mirror
-  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, false));   // row_mirror
+  if constexpr (LP == 16)
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, false)); // row_mirror
   return x;
+}
+
+// CE consecutive floats between LDS and registers with the widest accesses the chunk allows (16-byte aligned).
+template <int CE>
+__device__ __forceinline__ void chunk_load(const float* src, float (&v)[CE]) {
+  if constexpr (CE % 4 == 0) {
+#pragma unroll
+    for (int e = 0; e < CE; e += 4) {
+      const float4 t = *reinterpret_cast<const float4*>(src + e);
+      v[e] = t.x; v[e + 1] = t.y; v[e + 2] = t.z; v[e + 3] = t.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < CE; e += 2) {
+      const float2 t = *reinterpret_cast<const float2*>(src + e);
+      v[e] = t.x; v[e + 1] = t.y;
+    }
+  }
+}
+template <int CE>
+__device__ __forceinline__ void chunk_store(float* dst, const float (&v)[CE]) {
+  if constexpr (CE % 4 == 0) {
+#pragma unroll
+    for (int e = 0; e < CE; e += 4) *reinterpret_cast<float4*>(dst + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < CE; e += 2) *reinterpret_cast<float2*>(dst + e) = make_float2(v[e], v[e + 1]);
+  }
 }
 
 // One-sided (Hestenes) Jacobi in fp32, everything in LDS (l = 16*NE <= 128).  Works on X = M itself:
@@ -422,15 +453,19 @@ __device__ __forceinline__ float row16_sum(float x) {
 // the eigenvectors of the symmetric M and the column norms are the eigenvalues.  fp32 rotations give
 // eigenvectors good to about 1e-6; the Ritz values are not taken from here but recomputed in fp64 from
 // the rotated basis (row_sumsq_kernel), which is second-order accurate in the eigenvector error.
-// 16 lanes per column pair, each lane owning NE consecutive entries of both columns (64-bit LDS accesses); a round
+// LP lanes per column pair, each lane owning l / LP consecutive entries of both columns (128-bit LDS accesses); a round
 // handles l/2 disjoint pairs, one barrier per round.  The squared column norms are kept in LDS and updated with the
 // rotation (|x_p|^2 -= t g, |x_q|^2 += t g), so a round computes one inner product instead of three; they are
 // recomputed from the columns at the start of every sweep, and they only enter the angle and the skip test (the inner
 // product that a rotation annihilates is always computed from the columns themselves).
-template <int NE>
-__global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __restrict__ Gall, float* __restrict__ Utall,
-                                                              double* __restrict__ lamall) {
-  constexpr int l = 16 * NE, P = l + 2;     // even pitch: every lane's chunk starts on an 8-byte boundary
+template <int NE, int LP>
+__global__ __launch_bounds__(LP * 8 * NE) void jacobi_onesided_kernel(const double* __restrict__ Gall,
+                                                                    float* __restrict__ Utall,
+                                                                    double* __restrict__ lamall) {
+  constexpr int l = 16 * NE, P = l + 4;     // pitch a multiple of 4: every lane's chunk starts on a 16-byte boundary
+  constexpr int CE = l / LP;                // entries of a column per lane
+  static_assert(LP == 8 || LP == 16, "a pair's lanes are a DPP row or half of one");
+  static_assert(CE % 2 == 0, "chunks move as 64- or 128-bit accesses");
   extern __shared__ __attribute__((aligned(16))) float fl[];   // X[l][P] then V[l][P], column c at row c
   __shared__ int s_rot;
   __shared__ float s_big;
@@ -439,7 +474,7 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
   __shared__ int s_rank[128];
   float* X = fl;
   float* V = fl + l * P;
-  const int z = blockIdx.x, tid = threadIdx.x, nthr = 8 * l;
+  const int z = blockIdx.x, tid = threadIdx.x, nthr = LP * l / 2;
   const double* G = Gall + (size_t)z * l * l;
   // M is brought to unit scale by a power of two first: the rotations work with products of four of its entries, which
   // leave the fp32 range for matrices whose singular values are below 1e-5 or above 1e4 otherwise
@@ -456,8 +491,8 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
     X[c * P + i] = (float)(G[idx] * mscale);  // symmetric: row c of M is column c
     V[c * P + i] = (c == i) ? 1.0f : 0.0f;
   }
-  const int g = tid >> 4, sub = tid & 15;
-  const int eo = NE * sub;                    // this lane's entries of a column: eo .. eo + NE - 1
+  const int g = tid / LP, sub = tid % LP;
+  const int eo = CE * sub;                    // this lane's entries of a column: eo .. eo + CE - 1
   __syncthreads();
   for (int sweep = 0; sweep < 30; ++sweep) {
     if (tid == 0) { s_rot = 0; s_big = 0.0f; }
@@ -465,13 +500,12 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int c = g + h * (l / 2);
+      float x[CE];
+      chunk_load<CE>(X + c * P + eo, x);
       float n2 = 0.f;
 #pragma unroll
-      for (int e = 0; e < NE; e += 2) {
-        const float2 x = *reinterpret_cast<const float2*>(X + c * P + eo + e);
-        n2 = fmaf(x.x, x.x, n2); n2 = fmaf(x.y, x.y, n2);
-      }
-      n2 = row16_sum(n2);
+      for (int e = 0; e < CE; ++e) n2 = fmaf(x[e], x[e], n2);
+      n2 = lanes_sum<LP>(n2);
       if (sub == 0) s_n2[c] = n2;
     }
     __syncthreads();
@@ -480,25 +514,18 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
     for (int round = 0; round < l - 1; ++round) {
       int p, q;
       rr_pair(g, round, l, p, q);
-      float xp[NE], xq[NE];
-      float ga = 0.f;
-#pragma unroll
-      for (int e = 0; e < NE; e += 2) {
-        const float2 a = *reinterpret_cast<const float2*>(X + p * P + eo + e);
-        const float2 b = *reinterpret_cast<const float2*>(X + q * P + eo + e);
-        xp[e] = a.x; xp[e + 1] = a.y; xq[e] = b.x; xq[e + 1] = b.y;
-        ga = fmaf(a.x, b.x, ga); ga = fmaf(a.y, b.y, ga);
-      }
+      float xp[CE], xq[CE], vp[CE], vq[CE];
+      chunk_load<CE>(X + p * P + eo, xp);
+      chunk_load<CE>(X + q * P + eo, xq);
       const float al = s_n2[p], be = s_n2[q];
       // the eigenvector entries are fetched now, whether or not the pair rotates: their latency passes behind the
       // reduction and the angle
-      float2 vp[NE / 2], vq[NE / 2];
+      chunk_load<CE>(V + p * P + eo, vp);
+      chunk_load<CE>(V + q * P + eo, vq);
+      float ga = 0.f;
 #pragma unroll
-      for (int e = 0; e < NE; e += 2) {
-        vp[e / 2] = *reinterpret_cast<const float2*>(V + p * P + eo + e);
-        vq[e / 2] = *reinterpret_cast<const float2*>(V + q * P + eo + e);
-      }
-      ga = row16_sum(ga);
+      for (int e = 0; e < CE; ++e) ga = fmaf(xp[e], xq[e], ga);
+      ga = lanes_sum<LP>(ga);
       // hardware reciprocal / square-root approximations (1 ulp) are enough here: a rotation that is orthogonal
       // to 1e-7 and an angle that misses the exact one by 1e-7 change nothing in the convergence, and the
       // eigenvector rows are renormalised at the end
@@ -509,18 +536,15 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
         const float zeta = (be - al) * 0.5f * __builtin_amdgcn_rcpf(ga);
         const float tt = copysignf(__builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.0f + zeta * zeta)), zeta);
         const float cs = __builtin_amdgcn_rsqf(1.0f + tt * tt), sn = cs * tt;
+        float np[CE], nq[CE];
 #pragma unroll
-        for (int e = 0; e < NE; e += 2) {
-          float2 a, b;
-          a.x = cs * xp[e] - sn * xq[e];         a.y = cs * xp[e + 1] - sn * xq[e + 1];
-          b.x = sn * xp[e] + cs * xq[e];         b.y = sn * xp[e + 1] + cs * xq[e + 1];
-          *reinterpret_cast<float2*>(X + p * P + eo + e) = a;
-          *reinterpret_cast<float2*>(X + q * P + eo + e) = b;
-          a.x = cs * vp[e / 2].x - sn * vq[e / 2].x;   a.y = cs * vp[e / 2].y - sn * vq[e / 2].y;
-          b.x = sn * vp[e / 2].x + cs * vq[e / 2].x;   b.y = sn * vp[e / 2].y + cs * vq[e / 2].y;
-          *reinterpret_cast<float2*>(V + p * P + eo + e) = a;
-          *reinterpret_cast<float2*>(V + q * P + eo + e) = b;
-        }
+        for (int e = 0; e < CE; ++e) { np[e] = cs * xp[e] - sn * xq[e]; nq[e] = sn * xp[e] + cs * xq[e]; }
+        chunk_store<CE>(X + p * P + eo, np);
+        chunk_store<CE>(X + q * P + eo, nq);
+#pragma unroll
+        for (int e = 0; e < CE; ++e) { np[e] = cs * vp[e] - sn * vq[e]; nq[e] = sn * vp[e] + cs * vq[e]; }
+        chunk_store<CE>(V + p * P + eo, np);
+        chunk_store<CE>(V + q * P + eo, nq);
         if (sub == 0) {                          // the pairs of a round are disjoint: nobody else touches these two
           s_n2[p] = fmaxf(al - tt * ga, 0.0f);
           s_n2[q] = be + tt * ga;
@@ -537,23 +561,23 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
   }
   // eigenvalue estimates = column norms; rank them (descending) and emit eigenvectors as rows
   __shared__ float s_vscale[128];
-  if (tid < l) {
+  for (int c = tid; c < l; c += nthr) {
     float n2 = 0.f;
     double v2 = 0.0;
     for (int i = 0; i < l; ++i) {
-      n2 = fmaf(X[tid * P + i], X[tid * P + i], n2);
-      const double vv = V[tid * P + i];
+      n2 = fmaf(X[c * P + i], X[c * P + i], n2);
+      const double vv = V[c * P + i];
       v2 = fma(vv, vv, v2);
     }
-    s_norm[tid] = sqrtf(n2);
-    s_vscale[tid] = (float)(1.0 / sqrt(v2));    // accumulated rotations drift from unit norm by ~1e-6
+    s_norm[c] = sqrtf(n2);
+    s_vscale[c] = (float)(1.0 / sqrt(v2));    // accumulated rotations drift from unit norm by ~1e-6
   }
   __syncthreads();
-  if (tid < l) {
-    const float li = s_norm[tid];
+  for (int c = tid; c < l; c += nthr) {
+    const float li = s_norm[c];
     int r = 0;
-    for (int j = 0; j < l; ++j) r += (s_norm[j] > li || (s_norm[j] == li && j < tid)) ? 1 : 0;
-    s_rank[tid] = r;
+    for (int j = 0; j < l; ++j) r += (s_norm[j] > li || (s_norm[j] == li && j < c)) ? 1 : 0;
+    s_rank[c] = r;
     lamall[(size_t)z * l + r] = (double)li / mscale;
   }
   __syncthreads();
@@ -564,17 +588,17 @@ __global__ __launch_bounds__(1024) void jacobi_onesided_kernel(const double* __r
   }
 }
 
-template <int NE>
+template <int NE, int LP>
 static int launch_onesided(const double* G, float* Ut, double* lambda, int batch, hipStream_t st) {
   constexpr int l = 16 * NE;
-  const size_t need = (size_t)2 * l * (l + 2) * sizeof(float);
+  const size_t need = (size_t)2 * l * (l + 4) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_onesided_kernel<NE>),
+    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_onesided_kernel<NE, LP>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)need));
     attr_set = true;
   }
-  hipLaunchKernelGGL(jacobi_onesided_kernel<NE>, dim3(batch), dim3(8 * l), need, st, G, Ut, lambda);
+  hipLaunchKernelGGL((jacobi_onesided_kernel<NE, LP>), dim3(batch), dim3(LP * l / 2), need, st, G, Ut, lambda);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }
@@ -604,11 +628,12 @@ int launch_row_sumsq(const float* X, int l, int64_t m, int64_t ldx, size_t strid
 
 int launch_jacobi_fast(const double* G, int l, float* Ut, double* lambda, int batch, hipStream_t st) {
   prof::Scope ps(prof::JACOBI, st, (double)l * l * 8.0 * batch);
+  // 16 lanes per column pair: 8 lanes with twice the entries each measured 30 % slower
   switch (l / 16) {
-    case 2: return launch_onesided<2>(G, Ut, lambda, batch, st);
-    case 4: return launch_onesided<4>(G, Ut, lambda, batch, st);
-    case 6: return launch_onesided<6>(G, Ut, lambda, batch, st);
-    case 8: return launch_onesided<8>(G, Ut, lambda, batch, st);
+    case 2: return launch_onesided<2, 16>(G, Ut, lambda, batch, st);
+    case 4: return launch_onesided<4, 16>(G, Ut, lambda, batch, st);
+    case 6: return launch_onesided<6, 16>(G, Ut, lambda, batch, st);
+    case 8: return launch_onesided<8, 16>(G, Ut, lambda, batch, st);
     default: return LQ_ERR_ARG;
   }
 }
