@@ -153,11 +153,15 @@ int launch_jacobi_eig(double* G, int l, double* vt, float* Ut, double* lambda, i
 bool jacobi_fast_supported(int l);
 int launch_jacobi_fast(const double* G, int l, float* Ut, double* lambda, int batch, hipStream_t st);
 // lam[z][i] = squared norm of row i of the wide matrix X[z] (l x m), fp64.
+int launch_ritz_residual(const float* G, const float* Y, const double* lam, int rows, int64_t m, int64_t ldx, double* res,
+                         hipStream_t st);
 int launch_row_sumsq(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, double* lam, int batch,
                      hipStream_t st);
 // out[1024] = max |x[i]| over n floats (out[0..1023]: per-workgroup maxima); non-finite values are skipped.
 int launch_absmax(const float* x, int64_t n, float* out, hipStream_t st);
 // X <- X - alpha * Y, both `count` floats (multiple of 4).
+constexpr int DEFLATE_ROWS_MAX = 16;
+int launch_deflate_rows(float* X, const float* L, int l, int locked, int64_t m, int64_t ldx, hipStream_t st);
 int launch_lincomb3(float* X, float a, const float* Y, float b, const float* Z, float c, int64_t count, hipStream_t st);
 // Fills a wide matrix (l x m, padded ld) with N(0,1) draws from a counter-based generator; pads are zeroed.
 int launch_gaussian_fill(float* X, int l, int64_t m, int64_t ldx, uint64_t seed, hipStream_t st);

@@ -203,41 +203,84 @@ static int ritz_rotate(const Ctx& c, int l, const float* Y, float* Y2, size_t sY
 // from an orthonormal Y_0, then one Cholesky-QR.  The rows are independent under the recurrence, and after a
 // Rayleigh-Ritz the rows that matter for convergence (around theta_rank) are orthogonal to the dominant directions up
 // to rounding, ~1e-6; the recurrence amplifies that leak by T_m(2 theta_1 / b - 1) / T_m(2 theta_rank / b - 1), and m is
-// limited so that this stays below `growth` = 1e5 (the leak stays a small part of the row).  For a spectrum with a
-// strongly dominant part that gives m = 1, which is subspace iteration on M - (b/2) I.  Before the first Rayleigh-Ritz
-// there is no b: plain power steps.
-// Convergence is judged on the top-`rank` Ritz values; the Rayleigh-Ritz steps are scheduled from the observed rate
-// instead of at a fixed period, since each one costs an l x l eigen-solve.
+// limited so that this stays below `growth` = 1e5 (the leak stays a small part of the row).
+// Dominant directions that would hold the degree down are locked once converged (a direction theta_i has converged to
+// (b / theta_i)^it after `it` applications of M; 1e-5 is asked for): their rows stay as the last Rayleigh-Ritz left them
+// and every filter step ends by removing their components from the other rows (deflate_rows_kernel), so the recurrence
+// runs on the deflated operator and theta_1 above is the largest unlocked Ritz value.  Spectra with a dominant part
+// that is neither locked yet nor small get m = 1, which is subspace iteration on M - (b/2) I.  Before the first
+// Rayleigh-Ritz there is no b: plain power steps.
+// Convergence is judged on the top-`rank` Ritz values.  Each Rayleigh-Ritz costs an l x l eigen-solve, so they are
+// scheduled: after 2 applications (to get b), when lock candidates will have converged, and then where the error is
+// predicted to reach the tolerance, by the decay rate measured over two equal gaps if there is one, else by the
+// filter's own rate for theta_rank (derated by 0.7).  The iteration only stops on measured quantities: the change over
+// the last gap, divided by the measured decay over that gap where available.
 static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const float** Yout, const float** Bout) {
   const Plan& pl = c.pl;
   const int l = pl.prm.l1, r = pl.rank;
-  float* Y0 = c.at<float>(pl.Ya);                                         // orthonormal rows: start of the cycle
-  float* P[3] = {c.at<float>(pl.Yb), c.at<float>(pl.Yc), c.at<float>(pl.Yd)};   // the other three of four row blocks
+  float* const all[4] = {c.at<float>(pl.Ya), c.at<float>(pl.Yb), c.at<float>(pl.Yc), c.at<float>(pl.Yd)};
+  float* Y0 = all[0];                                         // orthonormal rows: start of the cycle
+  float* P[3] = {all[1], all[2], all[3]};                     // the other three of the four row blocks
   float* Ba = c.at<float>(pl.Ba); float* Bb = c.at<float>(pl.Bb);
   double* lam = c.at<double>(pl.lam_cold);
   const int64_t ycount = (int64_t)l * pl.ldd;
-  LQ_HIP_TRY(hipMemsetAsync(Y0, 0, ycount * 4, c.st));
-  for (float* p : P) LQ_HIP_TRY(hipMemsetAsync(p, 0, ycount * 4, c.st));
+  for (float* p : all) LQ_HIP_TRY(hipMemsetAsync(p, 0, ycount * 4, c.st));
   LQ_HIP_TRY(hipMemsetAsync(Bb, 0, (size_t)l * pl.ldk * 4, c.st));
   LQ_TRY(launch_gaussian_fill(Ba, l, pl.k, pl.ldk, seed, c.st));
   LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, Y0, pl.ldd, 0, 1));
   LQ_TRY(orthonormalize(c, Y0, P[0], l, pl.d, pl.ldd, 0, 1));
   std::vector<double> prev(r, 0.0), cur(l, 0.0);
   bool have_prev = false;
-  double bcut = 0.0, top = 0.0, wanted = 0.0;   // filter cut-off theta_l, theta_1 and theta_rank of the last Rayleigh-Ritz (0: none yet)
-  double last_delta = -1.0;   // change of the Ritz values over the previous gap (valid when rate_ok)
-  double kappa = 0.0;         // observed decay rate of the error per application of M (natural log), 0 = unknown
+  double bcut = 0.0;          // filter cut-off: theta_l of a Rayleigh-Ritz (0: none yet)
+  double free_top = 0.0;      // largest unlocked Ritz value
+  double wanted = 0.0;        // theta_rank
+  int locked = 0;             // leading rows of Y0 that the filter leaves alone
+  double kappa = 0.0;         // measured decay rate of the error per application of M (natural log), 0 = unknown
   const int first_gap = std::min(2, pl.prm.check);
-  int next_check = first_gap, last_check = 0, last_gap = 0, m_prev = 1;
-  bool rate_ok = false;       // last_delta was measured with the current cut-off
-  const double growth = 1.0e5;
+  int next_check = first_gap, last_check = 0, m_prev = 1;
+  bool rate_ok = false;       // last_est was measured with the current filter
+  const double rounding = 1.0e-6, crowding = 10.0, lock_accuracy = 1.0e-5;
   const int m_max = 8;
+  auto cheb = [](int deg, double x) { return std::cosh(deg * std::acosh(std::max(x, 1.0))); };
+  // Degree of the next cycle by the leak rule (before the caps that depend on the schedule).  A direction theta_i above
+  // theta_rank is present in the other rows at a level of about (b / theta_i)^it (its convergence so far), at least
+  // 1e-6 (rounding); a cycle multiplies that by T_m(x_i) / T_m(x_rank), and the product, the factor by which such a
+  // direction can come to outweigh a row's own content, has to stay below `crowding`: the Cholesky-QR that follows and
+  // the fp32 rows themselves lose that many digits of the rest.
+  auto filter_degree = [&](int it_now) {
+    if (!(bcut > 0.0)) return 1;
+    const double xr = 2.0 * wanted / bcut - 1.0;
+    int m = 1;
+    while (m < m_max) {
+      // the largest unlocked direction grows by T_m(x) in a cycle: the rows of a block stay within 1e8 of each other
+      bool ok = cheb(m + 1, 2.0 * cur[locked] / bcut - 1.0) <= 1.0e8;
+      for (int i = locked; i < r - 1 && ok; ++i) {
+        const double ratio = cur[i] / bcut;
+        if (!(ratio > 1.0)) break;
+        const double leak = std::max(rounding, std::exp(-it_now * std::log(ratio)));
+        ok = leak * cheb(m + 1, 2.0 * ratio - 1.0) <= crowding * cheb(m + 1, xr);
+      }
+      if (!ok) break;
+      ++m;
+    }
+    return m;
+  };
+  double* res_dev = c.at<double>(pl.lam);     // squared residual norms of the top-r Ritz pairs (free until the warm passes)
+  std::vector<double> res(r, 0.0);
+  double last_est = 0.0;      // residual-based error estimate of the previous Rayleigh-Ritz (valid when rate_ok)
   for (int it = 0;;) {        // it: applications of M so far
     LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, Y0, pl.ldd, 0, A, pl.k, 0, Ba, pl.ldk, 0, 1));
+    bool have_g = false;      // P[0] = Ba A^T = Y0 M already computed (by the residual check)
     if (it >= next_check || it >= pl.prm.maxit) {
       LQ_TRY(ritz_rotate(c, l, Y0, P[0], 0, Ba, Bb, 0, lam, 1));
       std::swap(Y0, P[0]); std::swap(Ba, Bb);
+      // residuals of the top-r Ritz pairs, |y_j M - theta_j y_j|: y_j M = (y_j A) A^T is the first product of the next
+      // cycle anyway
+      LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, P[0], pl.ldd, 0, 1));
+      LQ_TRY(launch_ritz_residual(P[0], Y0, lam, r, pl.d, pl.ldd, res_dev, c.st));
+      have_g = true;
       LQ_HIP_TRY(hipMemcpyAsync(cur.data(), lam, sizeof(double) * l, hipMemcpyDeviceToHost, c.st));
+      LQ_HIP_TRY(hipMemcpyAsync(res.data(), res_dev, sizeof(double) * r, hipMemcpyDeviceToHost, c.st));
       LQ_HIP_TRY(hipStreamSynchronize(c.st));
       double delta = 0.0;
       for (int j = 0; j < r; ++j) {
@@ -246,51 +289,94 @@ static int cold_factorize(const Ctx& c, const float* A, uint64_t seed, const flo
         if (!(rel <= delta)) delta = rel;      // NaN-safe maximum
       }
       const int gap = it - last_check;
-      // The error decays geometrically, err(it) ~ exp(-kappa it), so the change over a gap is
-      // err(it) (exp(kappa gap) - 1).  kappa comes from two successive equal-filter gaps, derated by 0.7.
-      if (have_prev && rate_ok && last_delta > 0 && delta > 0 && delta < last_delta && gap == last_gap)
-        kappa = 0.7 * std::log(last_delta / delta) / gap;
-      double err_est = delta;
-      if (kappa > 0) err_est = std::min(delta, delta / std::expm1(kappa * gap));
-      const bool done = have_prev && err_est <= pl.prm.tol;
-      if (done || it >= pl.prm.maxit) break;
-      // next Rayleigh-Ritz where the error is predicted to reach the tolerance
-      int next_gap = pl.prm.check;
-      if (kappa > 0 && have_prev) {
-        const double need = std::log(err_est / pl.prm.tol) / kappa;
-        next_gap = (int)std::min<double>(std::max<double>(std::ceil(need), pl.prm.check), 8.0 * pl.prm.check);
+      const bool usable = cur[0] > 0 && cur[l - 1] > 1e-12 * cur[0] && std::isfinite(cur[0]);
+      // Error of sigma_j = sqrt(theta_j) from the residual rho_j of its Ritz pair: theta_j misses the eigenvalue by at
+      // most rho_j^2 / gap_j, gap_j = distance from theta_j to the spectrum outside the block.  That spectrum ends near
+      // theta_l; half of theta_j - theta_l is used for the gap (theta_l is itself an underestimate), so
+      // d sigma / sigma = d theta / (2 theta) <= rho_j^2 / (theta_j (theta_j - theta_l)).
+      double est = INFINITY;
+      if (usable) {
+        est = 0.0;
+        for (int j = 0; j < r; ++j) {
+          const double gapj = cur[j] - cur[l - 1];
+          const double e = gapj > 1e-9 * cur[j] ? res[j] / (cur[j] * gapj) : INFINITY;
+          if (!(e <= est)) est = e;
+        }
       }
-      rate_ok = have_prev;
-      last_delta = delta; last_gap = gap; last_check = it; next_check = it + next_gap;
+      // measured decay rate per application of M between two Rayleigh-Ritz steps under the same filter, derated by 0.7
+      if (rate_ok && last_est > 0 && est > 0 && est < last_est && std::isfinite(last_est) && gap > 0)
+        kappa = 0.7 * std::log(last_est / est) / gap;
+      // the change over the last gap, as a second witness: err(it) ~ exp(-kappa it), so the change is err(it) (exp(kappa gap) - 1)
+      double change_est = delta;
+      if (kappa > 0) change_est = std::min(delta, delta / std::expm1(kappa * gap));
+      const bool done = est <= pl.prm.tol || (have_prev && change_est <= pl.prm.tol);
+      if (done || it >= pl.prm.maxit) break;
+      rate_ok = usable;
+      // the cut-off follows theta_l upwards; a noticeable change of the filter invalidates the measured rate
+      if (usable && cur[l - 1] > bcut) {
+        if (cur[l - 1] > 1.03 * bcut) { rate_ok = false; kappa = 0.0; }
+        bcut = cur[l - 1];
+      }
+      int lock_at = 0;        // application count at which the next lock candidate will have converged (0: none waiting)
+      if (usable) {
+        wanted = cur[r - 1];
+        const double xr = 2.0 * wanted / bcut - 1.0;
+        int n = 0;
+        while (n < std::min(DEFLATE_ROWS_MAX, l - 1)) {
+          const double th = cur[n];
+          if (!(rounding * cheb(m_max, 2.0 * th / bcut - 1.0) > crowding * cheb(m_max, xr))) break;   // would not hold the degree down
+          const double per_step = std::log(th / bcut);
+          if (it * per_step < std::log(1.0 / lock_accuracy)) {
+            lock_at = (int)std::ceil(std::log(1.0 / lock_accuracy) / per_step);
+            break;
+          }
+          ++n;
+        }
+        if (n != locked) { rate_ok = false; kappa = 0.0; }
+        locked = n;
+        free_top = cur[locked];
+      }
+      // next Rayleigh-Ritz where the error is predicted to reach the tolerance: by the measured rate, else by the
+      // filter's own rate for theta_rank, derated by 0.5 (theta_l below the true edge of the unwanted spectrum and the
+      // shorter first cycles both make the real decay slower)
+      double rate = kappa;
+      if (!(rate > 0) && bcut > 0.0 && lock_at == 0) {
+        const int m = filter_degree(it);
+        rate = 0.5 * 2.0 * std::log(cheb(m, 2.0 * wanted / bcut - 1.0)) / m;   // values converge like squared angles
+      }
+      int next_gap = pl.prm.check;
+      if (rate > 0 && std::isfinite(est) && est > 0) {
+        const double need = std::log(est / pl.prm.tol) / rate;
+        next_gap = (int)std::min<double>(std::max<double>(std::ceil(need), (pl.prm.check + 1) / 2), 8.0 * pl.prm.check);
+      }
+      last_est = est; last_check = it; next_check = it + next_gap;
+      if (lock_at > it) next_check = std::min(next_check, lock_at);
       for (int j = 0; j < r; ++j) prev[j] = cur[j];
       have_prev = true;
-      // the cut-off follows theta_l upwards; a change of the filter invalidates the measured rate
-      const bool usable = cur[0] > 0 && cur[l - 1] > 1e-12 * cur[0] && std::isfinite(cur[0]);
-      if (usable && cur[l - 1] > 1.1 * bcut) { bcut = cur[l - 1]; rate_ok = false; kappa = 0.0; next_check = it + pl.prm.check; }
-      if (usable) { top = cur[0]; wanted = cur[r - 1]; }
     }
     // one cycle: m filter steps from Y0, then Cholesky-QR
-    int m = 1;
-    if (bcut > 0.0) {
-      const double x1 = std::max(2.0 * top / bcut - 1.0, 1.0 + 1e-9);
-      const double xr = std::max(2.0 * wanted / bcut - 1.0, 1.0);
-      auto cheb = [](int deg, double x) { return std::cosh(deg * std::acosh(x)); };
-      while (m < std::min(m_max, 2 * m_prev) && cheb(m + 1, x1) <= growth * cheb(m + 1, xr)) ++m;
-    }
+    int m = std::min(filter_degree(it), 4 * m_prev);
     m = std::max(1, std::min(m, std::min(next_check, pl.prm.maxit) - it));
     m_prev = m;
     // step 1 (Ba = Y0 A is at hand)
-    LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, P[0], pl.ldd, 0, 1));
+    if (!have_g) LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Ba, pl.ldk, 0, A, pl.k, 0, P[0], pl.ldd, 0, 1));
     if (bcut > 0.0) LQ_TRY(launch_lincomb3(P[0], (float)(2.0 / bcut), Y0, -1.0f, nullptr, 0.0f, ycount, c.st));
-    float* Yj = P[0]; float* Yjm1 = Y0; float* Ynew = P[1]; float* spare = P[2];
+    LQ_TRY(launch_deflate_rows(P[0], Y0, l, locked, pl.d, pl.ldd, c.st));
+    // Y0 keeps the locked rows for the whole cycle: the recurrence rotates through the other three blocks
+    float* Yj = P[0]; float* Yjm1 = Y0; float* Ynew = P[1]; float* third = P[2];
     for (int j = 1; j < m; ++j) {
       LQ_TRY(gemm(c, MODE_NN, l, pl.k, pl.d, Yj, pl.ldd, 0, A, pl.k, 0, Bb, pl.ldk, 0, 1));
       LQ_TRY(gemm(c, MODE_NT, l, pl.d, pl.k, Bb, pl.ldk, 0, A, pl.k, 0, Ynew, pl.ldd, 0, 1));
       LQ_TRY(launch_lincomb3(Ynew, (float)(4.0 / bcut), Yj, -2.0f, Yjm1, -1.0f, ycount, c.st));
-      float* freed = Yjm1; Yjm1 = Yj; Yj = Ynew; Ynew = freed;
+      LQ_TRY(launch_deflate_rows(Ynew, Y0, l, locked, pl.d, pl.ldd, c.st));
+      float* freed = Yjm1 == Y0 ? third : Yjm1;
+      Yjm1 = Yj; Yj = Ynew; Ynew = freed;
     }
-    LQ_TRY(orthonormalize(c, Yj, spare, l, pl.d, pl.ldd, 0, 1));    // Yj now names the orthonormal block, spare the old one
-    Y0 = Yj; P[0] = Yjm1; P[1] = Ynew; P[2] = spare;
+    float* alt = Y0;                                                 // its locked rows are in Yj by now
+    LQ_TRY(orthonormalize(c, Yj, alt, l, pl.d, pl.ldd, 0, 1));       // Yj now names the orthonormal block
+    Y0 = Yj;
+    for (int q = 0, n = 0; q < 4; ++q)
+      if (all[q] != Y0) P[n++] = all[q];
     it += m;
   }
   *Yout = Y0; *Bout = Ba;

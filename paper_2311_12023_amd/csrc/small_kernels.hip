@@ -88,7 +88,6 @@ template <bool PACKED>
 __global__ __launch_bounds__(256) void cholesky_kernel(double* __restrict__ Gall, int l) {
   extern __shared__ double lds[];
   __shared__ double s_inv;
-  __shared__ double s_tol;
   double* G = Gall + (size_t)blockIdx.x * l * l;
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
   double* Lw = PACKED ? lds : G;
@@ -99,15 +98,15 @@ __global__ __launch_bounds__(256) void cholesky_kernel(double* __restrict__ Gall
       if (j <= i) at(i, j) = G[idx];
     }
   }
-  if (tid == 0) {
-    double mx = 0;
-    for (int i = 0; i < l; ++i) mx = fmax(mx, G[(size_t)i * l + i]);
-    s_tol = 1e-12 * mx;
-  }
+  // A pivot is compared with the row's own squared norm (what is left of row j after the rows before it have been
+  // taken out is negligible below 1e-6 of its length), not with the largest one: the rows of a block may differ in
+  // length by many orders of magnitude (filtered rows beside rows kept at unit length).
+  __shared__ double s_diag[256];
+  for (int i = tid; i < l; i += 256) s_diag[i] = G[(size_t)i * l + i];
   for (int j = 0; j < l; ++j) {
     __syncthreads();
     const double piv = at(j, j);
-    const bool ok = piv > s_tol;
+    const bool ok = piv > 1e-12 * s_diag[j];
     const double cjj = ok ? sqrt(piv) : 0.0;
     const double inv = ok ? 1.0 / cjj : 0.0;
     for (int i = j + 1 + tid; i < l; i += 256) at(i, j) *= inv;
@@ -180,7 +179,6 @@ __global__ __launch_bounds__(1024) void cholinv_kernel(const double* __restrict_
   constexpr int l = 32 * NB;
   __shared__ double colbuf[2][l];
   __shared__ double rowbuf[2][l];
-  __shared__ double s_red[32];
   const int tid = threadIdx.x, ty = tid >> 5, tx = tid & 31;
   const double* G = Gall + (size_t)blockIdx.x * l * l;
   double a[NB][NB], t[NB][NB];
@@ -192,18 +190,13 @@ __global__ __launch_bounds__(1024) void cholinv_kernel(const double* __restrict_
       a[ei][ek] = G[(size_t)i * l + k];
       t[ei][ek] = (i == k) ? 1.0 : 0.0;
     }
-  // tolerance from the largest diagonal entry
-  double mx = 0.0;
+  // A pivot is compared with the row's own squared norm, not with the largest one (see cholesky_kernel).
+  __shared__ double s_diag[l];
   if (ty == tx) {
 #pragma unroll
-    for (int e = 0; e < NB; ++e) mx = fmax(mx, a[e][e]);
+    for (int e = 0; e < NB; ++e) s_diag[ty + 32 * e] = a[e][e];
   }
-  for (int off = 1; off < 64; off <<= 1) mx = fmax(mx, __shfl_xor(mx, off));
-  if ((tid & 63) == 0) s_red[tid >> 6] = mx;
   __syncthreads();
-  mx = 0.0;
-  for (int w = 0; w < 16; ++w) mx = fmax(mx, s_red[w]);
-  const double tol = 1e-12 * mx;
 
 #pragma unroll
   for (int jb = 0; jb < NB; ++jb) {
@@ -219,7 +212,7 @@ __global__ __launch_bounds__(1024) void cholinv_kernel(const double* __restrict_
       }
       __syncthreads();
       const double piv = colbuf[buf][j];
-      const bool ok = piv > tol;
+      const bool ok = piv > 1e-12 * s_diag[j];
       const double inv = ok ? fast_rsqrt(piv) : 0.0;
       double ci[NB], ck[NB], tr[NB];
 #pragma unroll
@@ -618,6 +611,32 @@ __global__ __launch_bounds__(256) void row_sumsq_kernel(const float* __restrict_
   if (tid == 0) lam[(size_t)z * l + row] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
 }
 
+// res[i] = |G_i - lam[i] Y_i|^2 for the first `rows` rows: squared residual norms of the Ritz pairs (lam_i, Y_i) of the
+// operator that G = Y M was formed with.
+__global__ __launch_bounds__(256) void ritz_residual_kernel(const float* __restrict__ G, const float* __restrict__ Y,
+                                                            const double* __restrict__ lam, int64_t m, int64_t ldx,
+                                                            double* __restrict__ res) {
+  __shared__ double s_sum[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const float* g = G + (size_t)row * ldx;
+  const float* y = Y + (size_t)row * ldx;
+  const double th = lam[row];
+  double s = 0.0;
+  for (int64_t j = tid; j < m; j += 256) { const double v = (double)g[j] - th * (double)y[j]; s = fma(v, v, s); }
+  for (int off = 1; off < 64; off <<= 1) s += __shfl_xor(s, off);
+  if ((tid & 63) == 0) s_sum[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) res[row] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+}
+
+int launch_ritz_residual(const float* G, const float* Y, const double* lam, int rows, int64_t m, int64_t ldx, double* res,
+                         hipStream_t st) {
+  prof::Scope ps(prof::MISC, st, (double)rows * m * 8.0);
+  hipLaunchKernelGGL(ritz_residual_kernel, dim3(rows), dim3(256), 0, st, G, Y, lam, m, ldx, res);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
 int launch_row_sumsq(const float* X, int l, int64_t m, int64_t ldx, size_t strideX, double* lam, int batch,
                      hipStream_t st) {
   prof::Scope ps(prof::MISC, st, (double)l * m * 4.0 * batch);
@@ -740,6 +759,65 @@ int launch_lincomb3(float* X, float a, const float* Y, float b, const float* Z, 
   const int64_t want = (count4 + 255) / 256;
   prof::Scope ps(prof::MISC, st, (double)count * (Z ? 16.0 : 12.0));
   hipLaunchKernelGGL(lincomb3_kernel, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, st, X, a, Y, b, Z, c, count4);
+  LQ_HIP_TRY(hipGetLastError());
+  return LQ_OK;
+}
+
+// Rows of X against the first `locked` rows of L (orthonormal): rows i >= locked lose their components along them,
+// x_i <- x_i - sum_o (x_i . l_o) l_o; rows i < locked become copies of l_i.  One workgroup per row; inner products in
+// fp32 with a fixed summation order.  locked <= DEFLATE_MAX.
+constexpr int DEFLATE_MAX = 16;
+
+__global__ __launch_bounds__(256) void deflate_rows_kernel(float* __restrict__ X, const float* __restrict__ L, int locked,
+                                                           int64_t m4, int64_t ldx) {
+  __shared__ float s_part[4][DEFLATE_MAX];
+  __shared__ float s_dot[DEFLATE_MAX];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  float4* x = reinterpret_cast<float4*>(X + (size_t)row * ldx);
+  if (row < locked) {
+    const float4* src = reinterpret_cast<const float4*>(L + (size_t)row * ldx);
+    for (int64_t j = tid; j < m4; j += 256) x[j] = src[j];
+    return;
+  }
+  float dot[DEFLATE_MAX];
+#pragma unroll
+  for (int o = 0; o < DEFLATE_MAX; ++o) dot[o] = 0.f;
+  for (int64_t j = tid; j < m4; j += 256) {
+    const float4 v = x[j];
+#pragma unroll
+    for (int o = 0; o < DEFLATE_MAX; ++o)
+      if (o < locked) {
+        const float4 u = reinterpret_cast<const float4*>(L + (size_t)o * ldx)[j];
+        dot[o] = fmaf(v.x, u.x, fmaf(v.y, u.y, fmaf(v.z, u.z, fmaf(v.w, u.w, dot[o]))));
+      }
+  }
+#pragma unroll
+  for (int o = 0; o < DEFLATE_MAX; ++o) {
+    float t = dot[o];
+    for (int off = 1; off < 64; off <<= 1) t += __shfl_xor(t, off);
+    if ((tid & 63) == 0) s_part[tid >> 6][o] = t;
+  }
+  __syncthreads();
+  if (tid < DEFLATE_MAX) s_dot[tid] = (s_part[0][tid] + s_part[1][tid]) + (s_part[2][tid] + s_part[3][tid]);
+  __syncthreads();
+  for (int64_t j = tid; j < m4; j += 256) {
+    float4 v = x[j];
+#pragma unroll
+    for (int o = 0; o < DEFLATE_MAX; ++o)
+      if (o < locked) {
+        const float4 u = reinterpret_cast<const float4*>(L + (size_t)o * ldx)[j];
+        const float c = s_dot[o];
+        v.x = fmaf(-c, u.x, v.x); v.y = fmaf(-c, u.y, v.y); v.z = fmaf(-c, u.z, v.z); v.w = fmaf(-c, u.w, v.w);
+      }
+    x[j] = v;
+  }
+}
+
+int launch_deflate_rows(float* X, const float* L, int l, int locked, int64_t m, int64_t ldx, hipStream_t st) {
+  if (locked < 0 || locked > DEFLATE_MAX || ldx % 4 != 0) return LQ_ERR_ARG;
+  if (locked == 0) return LQ_OK;
+  prof::Scope ps(prof::MISC, st, (double)l * m * 4.0 * 2.0 * (1 + locked));
+  hipLaunchKernelGGL(deflate_rows_kernel, dim3(l), dim3(256), 0, st, X, L, locked, (m + 3) / 4, ldx);
   LQ_HIP_TRY(hipGetLastError());
   return LQ_OK;
 }
