@@ -47,6 +47,16 @@ int lq_test_sym_eig(double* G, int l, float* Ut, double* lambda, double* scratch
  * approximate eigenvectors of the symmetric fp64 G (left untouched), ordered by descending eigenvalue
  * estimate lambda (fp32 accuracy). */
 int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void* stream);
+/* The small kernels of the cold-start filter, one launch each on device arrays of l rows with leading dimension ldx
+ * (a multiple of 4, m <= ldx):
+ *   lincomb3:       X <- a X + b Y + c Z over all l * ldx entries (Z may be NULL: no third term).
+ *   deflate_rows:   rows i >= locked of X lose their components along the first `locked` (<= 16) rows of L, which are
+ *                   orthonormal; rows i < locked of X become copies of those rows of L.
+ *   ritz_residual:  res[i] = |G_i - lam[i] Y_i|^2 for the first `rows` rows (lam, res: device doubles). */
+int lq_test_lincomb3(float* X, float a, const float* Y, float b, const float* Z, float c, int l, int64_t ldx, void* stream);
+int lq_test_deflate_rows(float* X, const float* L, int l, int locked, int64_t m, int64_t ldx, void* stream);
+int lq_test_ritz_residual(const float* G, const float* Y, const double* lam, int rows, int64_t m, int64_t ldx, double* res,
+                          void* stream);
 /* Host-side evaluation of the code search the kernels use (threshold count for 2 and 3 bits, bucket table
  * plus two comparisons for 4 and 8 bits) on one normalised weight x; -1 for an unsupported bit width.
  * Needs no GPU. */

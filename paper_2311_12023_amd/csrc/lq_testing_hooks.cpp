@@ -85,6 +85,25 @@ int lq_test_sym_eig_fast(const double* G, int l, float* Ut, double* lambda, void
   return launch_jacobi_fast(G, l, Ut, lambda, 1, (hipStream_t)stream);
 }
 
+int lq_test_lincomb3(float* X, float a, const float* Y, float b, const float* Z, float c, int l, int64_t ldx, void* stream) {
+  if (!X || !Y) return LQ_ERR_NULL;
+  if (l < 1 || ldx < 4 || ldx % 4) return LQ_ERR_ARG;
+  return launch_lincomb3(X, a, Y, b, Z, c, (int64_t)l * ldx, (hipStream_t)stream);
+}
+
+int lq_test_deflate_rows(float* X, const float* L, int l, int locked, int64_t m, int64_t ldx, void* stream) {
+  if (!X || !L) return LQ_ERR_NULL;
+  if (l < 1 || m < 1 || m > ldx || locked > l) return LQ_ERR_ARG;
+  return launch_deflate_rows(X, L, l, locked, m, ldx, (hipStream_t)stream);
+}
+
+int lq_test_ritz_residual(const float* G, const float* Y, const double* lam, int rows, int64_t m, int64_t ldx, double* res,
+                          void* stream) {
+  if (!G || !Y || !lam || !res) return LQ_ERR_NULL;
+  if (rows < 1 || m < 1 || m > ldx) return LQ_ERR_ARG;
+  return launch_ritz_residual(G, Y, lam, rows, m, ldx, res, (hipStream_t)stream);
+}
+
 int lq_test_bucket_code(int bits, float x) {
   const int slot = bits_slot(bits);
   if (slot < 0) return -1;

@@ -146,6 +146,81 @@ def test_orthonormalize(env, l, m, use_alt):
     assert np.all(q[:, m:] == 0)
 
 
+@pytest.mark.parametrize("l", [96, 256])
+def test_orthonormalize_rows_of_very_different_length(env, l):
+    """Rows kept at unit length beside rows that a filter has amplified by many orders of magnitude (the cold start's
+    locked and filtered rows): every row still gets its direction, none is taken for linearly dependent."""
+    torch, lq, L = env
+    rng = np.random.default_rng(7 * l)
+    m = 1500
+    ld = up32(m)
+    q0, _ = np.linalg.qr(rng.standard_normal((m, l)))
+    scale = np.ones(l)
+    scale[4:] = 10.0 ** rng.uniform(5, 9, l - 4)          # rows 0..3 at unit length, the rest 1e5 .. 1e9 times longer
+    mix = np.eye(l) + 1e-3 * np.tril(rng.standard_normal((l, l)), -1)      # and not quite orthogonal
+    x = np.zeros((l, ld), np.float32)
+    x[:, :m] = (scale[:, None] * (mix @ q0.T)).astype(np.float32)
+    xt = torch.from_numpy(x).cuda()
+    scratch = torch.empty(17 * l * l, dtype=torch.float64, device="cuda")
+    alt = torch.zeros((l, ld), dtype=torch.float32, device="cuda")
+    assert L.lq_test_orthonormalize(xt.data_ptr(), l, m, ld, scratch.data_ptr(), alt.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    q = xt.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(q @ q.T - np.eye(l))) < 5e-5
+    assert np.max(np.abs(np.abs(np.sum(q[:, :m] * q0.T, axis=1)) - 1.0)) < 1e-4      # row i is +-(row i of q0^T), to the mixing
+
+
+def test_filter_small_kernels(env):
+    """lincomb3, deflate_rows and ritz_residual against numpy."""
+    torch, lq, L = env
+    rng = np.random.default_rng(99)
+    l, m = 64, 1003
+    ld = up32(m)
+    def rows():
+        a = np.zeros((l, ld), np.float32)
+        a[:, :m] = rng.standard_normal((l, m))
+        return a
+    x, y, z = rows(), rows(), rows()
+    for third in (True, False):
+        xt = torch.from_numpy(x.copy()).cuda()
+        yt, zt = torch.from_numpy(y).cuda(), torch.from_numpy(z).cuda()
+        assert L.lq_test_lincomb3(xt.data_ptr(), C.c_float(0.75), yt.data_ptr(), C.c_float(-2.0),
+                                  zt.data_ptr() if third else None, C.c_float(-1.0), l, ld, None) == 0
+        torch.cuda.synchronize()
+        ref = 0.75 * x.astype(np.float64) - 2.0 * y + (-1.0 * z if third else 0.0)
+        assert np.max(np.abs(xt.cpu().numpy() - ref)) < 1e-5
+    # deflation against 0, 5 and 16 orthonormal rows
+    lock_rows = np.zeros((l, ld), np.float32)
+    qq, _ = np.linalg.qr(rng.standard_normal((m, l)))
+    lock_rows[:, :m] = qq.T
+    lt = torch.from_numpy(lock_rows).cuda()
+    for locked in (0, 5, 16):
+        big = (x * np.float32(1e6)).astype(np.float32)
+        xt = torch.from_numpy(big.copy()).cuda()
+        assert L.lq_test_deflate_rows(xt.data_ptr(), lt.data_ptr(), l, locked, m, ld, None) == 0
+        torch.cuda.synchronize()
+        got = xt.cpu().numpy().astype(np.float64)
+        u = lock_rows[:locked].astype(np.float64)
+        ref = big.astype(np.float64) - (big.astype(np.float64) @ u.T) @ u
+        ref[:locked] = u
+        assert np.max(np.abs(got - ref)) < 2e-6 * np.max(np.abs(big))
+        if locked:
+            assert np.max(np.abs(got[locked:] @ u.T)) < 2e-6 * np.max(np.abs(big)) * np.sqrt(m)
+            assert np.array_equal(got[:locked], u)
+    assert L.lq_test_deflate_rows(xt.data_ptr(), lt.data_ptr(), l, 17, m, ld, None) != 0      # more than the kernel holds
+    # residuals of Ritz pairs
+    lam = rng.uniform(0.5, 2.0, l)
+    g = (lam[:, None] * y.astype(np.float64) + 1e-3 * z).astype(np.float32)
+    gt, yt = torch.from_numpy(g).cuda(), torch.from_numpy(y).cuda()
+    lamt = torch.from_numpy(lam).cuda()
+    res = torch.zeros(l, dtype=torch.float64, device="cuda")
+    assert L.lq_test_ritz_residual(gt.data_ptr(), yt.data_ptr(), lamt.data_ptr(), 40, m, ld, res.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    ref = np.sum((g.astype(np.float64) - lam[:, None] * y.astype(np.float64))[:, :m] ** 2, axis=1)
+    got = res.cpu().numpy()
+    assert np.max(np.abs(got[:40] - ref[:40]) / ref[:40]) < 1e-10 and np.all(got[40:] == 0)
+
+
 @pytest.mark.parametrize("l", [32, 64, 96, 128, 256])
 def test_sym_eig(env, l):
     torch, lq, L = env

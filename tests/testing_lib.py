@@ -26,6 +26,9 @@ def load():
         L.lq_test_orthonormalize.argtypes = [vp, it, i64, i64, vp, vp, vp]
         L.lq_test_sym_eig.argtypes = [vp, it, vp, vp, vp, vp]
         L.lq_test_sym_eig_fast.argtypes = [vp, it, vp, vp, vp]
+        L.lq_test_lincomb3.argtypes = [vp, C.c_float, vp, C.c_float, vp, C.c_float, it, i64, vp]
+        L.lq_test_deflate_rows.argtypes = [vp, vp, it, it, i64, i64, vp]
+        L.lq_test_ritz_residual.argtypes = [vp, vp, vp, it, i64, i64, vp, vp]
         L.lq_test_lds_limit.restype = C.c_size_t
         L.lq_test_bucket_code.argtypes = [C.c_int, C.c_float]
         L.lq_test_capture_iterate.argtypes = [it, it, vp, vp]
