@@ -67,13 +67,19 @@ def spectrum_case(kind):
         v, _ = np.linalg.qr(rng.standard_normal((576, 64)))
         w = (u * 0.8 ** np.arange(64)) @ v.T + 1e-4 / np.sqrt(576) * rng.standard_normal((320, 576))
         return w.astype(np.float32), 12
+    if kind == "power_law":             # sigma_i = i^-0.6, no gap anywhere (the shape trained weights tend to have)
+        n = 768
+        u, _ = np.linalg.qr(rng.standard_normal((n, n)))
+        v, _ = np.linalg.qr(rng.standard_normal((1280, n)))
+        w = (u * np.arange(1, n + 1) ** -0.6) @ v.T
+        return w.astype(np.float32), 32
     if kind == "low_rank":              # rank 6 plus noise at 1e-5: the block's smallest Ritz values are noise
         w = rng.standard_normal((256, 6)) @ rng.standard_normal((6, 512)) / 16 + 1e-5 * rng.standard_normal((256, 512))
         return w.astype(np.float32), 4
     raise ValueError(kind)
 
 
-@pytest.mark.parametrize("kind", ["flat", "dominant", "geometric", "low_rank"])
+@pytest.mark.parametrize("kind", ["flat", "dominant", "geometric", "power_law", "low_rank"])
 def test_factorize_spectra(env, kind):
     """Factorize (Algorithm 4 with the randomized SVD of Section 3.1, footnote 1) on spectra other than the benchmark's:
     singular values and the Eckart-Young optimum against LAPACK."""
