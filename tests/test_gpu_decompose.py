@@ -96,6 +96,33 @@ def test_factorize_spectra(env, kind):
     assert abs(np.sum((w.astype(np.float64) - l1h @ l2h) ** 2) - tail) < 1e-4 * tail + 1e-10 * np.sum(ref ** 2)
 
 
+def test_factorize_many_shapes_and_seeds(env):
+    """Factorize over a spread of shapes, ranks, sketch seeds and spectra (noise with 0 to 12 planted directions of random
+    strength, some columns scaled up): singular values against LAPACK every time."""
+    torch, lq = env
+    rng = np.random.default_rng(424242)
+    worst = 0.0
+    for case in range(14):
+        d = int(rng.choice([160, 256, 384, 512, 768, 1024]))
+        k = int(rng.choice([256, 512, 768, 1024, 1536]))
+        rank = int(rng.choice([2, 4, 8, 16, 32]))
+        rank = min(rank, min(d, k) // 4)
+        w = rng.standard_normal((d, k)) * 0.02
+        for _ in range(int(rng.integers(0, 13))):
+            strength = 0.02 * np.sqrt(max(d, k)) * 10.0 ** rng.uniform(-0.5, 2.0)
+            w += strength * np.outer(rng.standard_normal(d) / np.sqrt(d), rng.standard_normal(k) / np.sqrt(k))
+        if case % 3 == 0:
+            w[:, rng.permutation(k)[:3]] *= 20.0
+        w = np.ascontiguousarray(w.astype(np.float32))
+        _, _, sg = lq.factorize(torch.from_numpy(w).cuda(), rank, seed=1000 + case)
+        ref = np.linalg.svd(w.astype(np.float64), compute_uv=False)[:rank]
+        rel = np.max(np.abs(sg - ref) / ref)
+        print(f"case {case}: {d}x{k} rank {rank}: sigma rel {rel:.2e}", flush=True)
+        worst = max(worst, rel)
+        assert rel < SV_TOL, (case, d, k, rank, rel)
+    print("worst", worst)
+
+
 def test_factorize_weighted(env, oracle):
     torch, lq = env
     d, k, r = 320, 512, 8
