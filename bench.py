@@ -645,8 +645,8 @@ def main() -> int:
         ap.error("--hw-queues must be within 1..32")
     os.environ["GPU_MAX_HW_QUEUES"] = str(args.hw_queues)       # read by the HIP runtime when it starts: before torch
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sweep shards over GPUs by "
-              "matrix without any collective, see DESIGN.md).", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (several GPUs would share the sweep by matrix, "
+              "without any collective; that path is not built).", file=sys.stderr)
         return 2
     if args.steps is None:
         args.steps = {"matmul": 100, "quant": 10}.get(args.workload) or {1: 50, 2: 2, 3: 2, 4: 5, 5: 1}[args.config]
