@@ -446,8 +446,8 @@ class Workers:
 
 def bench_sweep(args, torch, gen, lq, dev) -> int:
     wl = args.config
-    serial_params = lq.SvdParams(streams=1, gemm_mode=args.gemm_mode)
-    params = lq.SvdParams(streams=args.streams, gemm_mode=args.gemm_mode)
+    serial_params = lq.SvdParams(streams=1, gemm_mode=args.gemm_mode, first_width=args.first_width)
+    params = lq.SvdParams(streams=args.streams, gemm_mode=args.gemm_mode, first_width=args.first_width)
     if wl in (1, 4):
         # one matrix, one configuration: a single lq_decompose call per step
         rank, iters = (8, 5) if wl == 1 else (64, 10)
@@ -628,6 +628,7 @@ def main() -> int:
                          "for one matrix at a time; default here: 2 with every matrix of a LLaMA-shaped layer in flight, "
                          "1 for workload 2, whose batches of 9 configurations are too small to split)")
     ap.add_argument("--gemm-mode", type=int, default=0, help="lq_svd_params.gemm_mode (0 = library default)")
+    ap.add_argument("--first-width", type=int, default=0, help="lq_svd_params.first_width (0 = library default)")
     ap.add_argument("--workload", choices=("sweep", "quant", "matmul"), default="sweep")
     ap.add_argument("--tokens", type=int, default=4096, help="rows of X for --workload matmul")
     ap.add_argument("--precision", type=int, default=0, help="lq_matmul precision for --workload matmul (0 split, 1 bf16)")
