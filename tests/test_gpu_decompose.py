@@ -383,6 +383,36 @@ def test_error_table_small(env, oracle):
     assert np.array_equal(e3, e)
 
 
+def test_error_table_random_mixed_batches(env, oracle):
+    """Tables over random lists of configurations that mix the classes with different numbers of subspace iterations per
+    pass (single-level scales, few-bit codes, >= 4-bit codes on 8-bit scales), in random order and with batch sizes that
+    cut the ordered list at arbitrary places: sampled cells' last pass anchored, storage column, determinism."""
+    torch, lq = env
+    rng = np.random.default_rng(77001)
+    pool = [(b, b0, b1, s1) for b in (2, 3, 4, 8) for b0 in (16, 32, 64) for b1 in (16, 64, 256) for s1 in (2, 3, 8)]
+    for case in range(4):
+        d, k = [(256, 384), (192, 512), (320, 256), (128, 768)][case]
+        rank = [4, 6, 3, 8][case]
+        w = gen.weight_matrix(d, k, 9000 + case, 8, outlier_frac=0.004 if case % 2 else 0.0)
+        wt = torch.from_numpy(w).cuda()
+        picks = [pool[i] for i in rng.permutation(len(pool))[:int(rng.integers(5, 12))]]
+        grid = [(b, b0, b1, s1, "fp32") for b, b0, b1, s1 in picks]
+        params = lq.SvdParams(max_batch=int(rng.integers(2, 8)), streams=int(rng.integers(1, 4)))
+        iters = 4
+        cfgs = [lq.config(*g) for g in grid]
+        e, st, tr = lq.error_table(wt, rank, cfgs, iters, seed=5 + case, params=params, want_trace=True)
+        assert np.all(np.isfinite(tr)) and np.array_equal(tr[:, -1] ** 2, e)
+        for i, g in enumerate(grid):
+            assert st[i] == oracle.storage_bits(w.size, oracle.config(*g))
+        e2, _ = lq.error_table(wt, rank, cfgs, iters, seed=5 + case, params=params)
+        assert np.array_equal(e2, e)
+        for i in rng.permutation(len(grid))[:3]:
+            _, _, tr_c, q_prev, sg = capture_cell(lq, wt, rank, grid, iters, int(i), seed=5 + case, params=params)
+            assert np.array_equal(tr_c, tr)
+            anchor.check_anchored_cell(oracle, w, rank, grid[i], q_prev, tr[i, iters - 1], sg,
+                                       label=f"mixed batch case {case} (max_batch {params.max_batch}, streams {params.streams})")
+
+
 def test_error_table_paper_grid_sample(env, oracle):
     """Cells of the paper's own 243-configuration search space (b1 in {2, 3, 4} scale bits, b2 in {bf16, fp16, fp32};
     Section 3.2, Table 1): every 9th configuration of the grid on a small matrix, each cell's last pass anchored."""
