@@ -88,7 +88,8 @@ typedef struct {
  *   warm_power_fine  subspace iterations per LQ iteration from the third on for configurations with codes of four or
  *                 more bits and block scales of eight or more (b0 >= 4, b1 >= 8), whose quantized component follows
  *                 W - L1 L2 closely enough that the residual hardly moves between iterations.  lq_error_table processes them last, in batches of their own where
- *                 the batch size allows; a batch that mixes classes takes the largest count.  Default 1.
+ *                 the batch size allows; in a batch that mixes classes each configuration still does its own count.
+ *                 Their second LQ iteration takes one more (at most warm_power_2).  Default 1.
  *   max_batch     lq_error_table advances up to this many configurations in lock step (more
  *                 workspace, better GPU occupancy).  Default 36.
  *   streams       lq_error_table splits a batch over this many HIP streams (1..4, all default priority, the

@@ -559,7 +559,7 @@ struct Loop {
     for (int b = 0; b < batch; ++b) {
       const bool coarse = is_coarse(cfgs[b]);
       qw[b] = coarse ? std::max(pl.prm.qw, pl.prm.qw_coarse) : (is_fine(cfgs[b]) ? pl.prm.qw_fine : pl.prm.qw);
-      qw2[b] = coarse ? std::max(pl.prm.qw2, pl.prm.qw_coarse) : pl.prm.qw2;
+      qw2[b] = coarse ? std::max(pl.prm.qw2, pl.prm.qw_coarse) : (is_fine(cfgs[b]) ? std::min(pl.prm.qw2, pl.prm.qw_fine + 1) : pl.prm.qw2);
     }
     for (std::vector<int>* q : {&qw, &qw2})
       if (!std::is_sorted(q->rbegin(), q->rend())) q->assign(batch, *std::max_element(q->begin(), q->end()));
