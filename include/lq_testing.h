@@ -29,11 +29,11 @@ int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, i
                       int precision, void* stream);
 /* The same products with A stored in fp16 (l <= 96, ldx a multiple of 64): C = out_scale * X * op(A), X multiplied by
  * x_scale before it is split into fp16 halves, or, with lam0 (device, one double per problem: the largest squared row
- * norm of that X), by a power of two derived from it that is divided out again.  A_lo: NULL, or a second fp16 matrix of
- * the same layout; the product is then taken with A + A_lo and X split into fp16 hi + lo
- * (about 2^-21 per operand); with one plane X is rounded to fp16 (2^-12). */
+ * norm of that X), by a power of two derived from it that is divided out again.  A_lo: NULL, or (NN mode only) a byte
+ * matrix of the same layout, each byte the upper byte of an fp16 number v; the product is then taken with
+ * A + v / 2048 and X split into fp16 hi + lo (about 2^-21); with one plane X is rounded to fp16 (2^-12). */
 int lq_test_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const uint16_t* A,
-                          const uint16_t* A_lo, int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
+                          const uint8_t* A_lo, int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
                           float x_scale, const double* lam0, float out_scale, void* stream);
 size_t lq_test_wide_gemm_part_floats(int l, int workgroups);
 /* Rows of X (l x m) are orthonormalised in place by Cholesky-QR (Gram in fp64).

@@ -699,6 +699,15 @@ __device__ __forceinline__ void residual_fetch(const PhaseArgs& a, const LoopPro
 // alternates loads and stores runs at the pace of the store latency.)  Measured on 36 x 4096 x 11008: 3.7 TB/s
 // written; a kernel that only stores reaches 5.7 - 6.9 TB/s, one that loads 2 B per quad before storing 3.8 TB/s.  The problem group is the fastest launch
 // index, so the groups of a batch that read the same stretch of W run together and share it in L2.
+// The lo plane of the fp16 residual: what the rounding of sv to hi dropped, times 2^11, rounded to the upper byte of
+// its fp16 form (sign, five exponent bits, two fraction bits; round to nearest even on the bit pattern, which carries
+// into the exponent where it has to).  |sv - hi| <= 16 for |sv| <= 65504, so the scaled value stays below 2^15 + 1.
+__device__ __forceinline__ uint32_t lo_plane_byte(float sv, _Float16 hi) {
+  const _Float16 l = (_Float16)((sv - (float)hi) * 2048.0f);
+  const uint32_t b = (uint32_t)__builtin_bit_cast(uint16_t, l);
+  return (b + 0x7Fu + ((b >> 8) & 1u)) >> 8;
+}
+
 constexpr int RES_G = 6;
 
 __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) {
@@ -744,7 +753,7 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) 
     const uint32_t mask = (1u << bits) - 1u;
     float* R = a.R ? a.R + (size_t)z * a.strideR : nullptr;
     _Float16* R16 = a.R16 ? reinterpret_cast<_Float16*>(a.R16) + (size_t)z * a.strideR : nullptr;
-    _Float16* R16lo = a.R16lo ? reinterpret_cast<_Float16*>(a.R16lo) + (size_t)z * a.strideR : nullptr;
+    uint8_t* R16lo = a.R16lo ? a.R16lo + (size_t)z * a.strideR : nullptr;
     float* Qd = a.Qd ? a.Qd + (size_t)z * a.strideQd : nullptr;
 #pragma unroll
     for (int u = 0; u < RES_U; ++u) {
@@ -765,15 +774,16 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) 
         const float lim = 65504.0f;        // largest fp16: out-of-range entries saturate instead of becoming infinite
         const float sv[4] = {__builtin_amdgcn_fmed3f(rv.x * a.r_scale, -lim, lim), __builtin_amdgcn_fmed3f(rv.y * a.r_scale, -lim, lim),
                              __builtin_amdgcn_fmed3f(rv.z * a.r_scale, -lim, lim), __builtin_amdgcn_fmed3f(rv.w * a.r_scale, -lim, lim)};
-        halfx4 h, l;
+        halfx4 h;
+        uint32_t l = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           h[e] = (_Float16)sv[e];
-          l[e] = (_Float16)(sv[e] - (float)h[e]);
+          l |= lo_plane_byte(sv[e], h[e]) << (8 * e);
         }
         // streamed out: nothing reads these lines before they have left the caches anyway
         __builtin_nontemporal_store(h, reinterpret_cast<halfx4*>(R16 + (quad << 2)));
-        if (R16lo) __builtin_nontemporal_store(l, reinterpret_cast<halfx4*>(R16lo + (quad << 2)));
+        if (R16lo) __builtin_nontemporal_store(l, reinterpret_cast<uint32_t*>(R16lo + (quad << 2)));
       }
       if (Qd) __builtin_nontemporal_store(floatx4{qv.x, qv.y, qv.z, qv.w}, reinterpret_cast<floatx4*>(Qd + (quad << 2)));
     }
@@ -789,6 +799,7 @@ __global__ __launch_bounds__(256) void residual_kernel(PhaseArgs a, int groups) 
 // less).
 constexpr int RP_U = 2;
 typedef _Float16 halfx8r __attribute__((ext_vector_type(8)));
+typedef uint32_t uintx2r __attribute__((ext_vector_type(2)));
 
 struct PlaneFetch { uint32_t cw[RP_U][2]; uint32_t si[RP_U]; float vv[RP_U]; };
 
@@ -870,11 +881,12 @@ __global__ __launch_bounds__(256) void residual_planes_kernel(PhaseArgs a, uint6
     const int z = s_list[i];
     const int levels = s_par[z][2];
     _Float16* hi = reinterpret_cast<_Float16*>(a.R16) + (size_t)z * a.strideR;
-    _Float16* lo = reinterpret_cast<_Float16*>(a.R16lo) + (size_t)z * a.strideR;
+    uint8_t* lo = a.R16lo + (size_t)z * a.strideR;
 #pragma unroll
     for (int u = 0; u < RP_U; ++u) {
       const float sh = block_scale(f.si[u], f.vv[u], levels);
-      halfx8r h, l;
+      halfx8r h;
+      uint32_t l[2] = {0u, 0u};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const uint32_t c = BITS == 8 ? (f.cw[u][e >> 2] >> (8 * (e & 3))) & mask : (f.cw[u][0] >> (BITS * e)) & mask;
@@ -882,10 +894,10 @@ __global__ __launch_bounds__(256) void residual_planes_kernel(PhaseArgs a, uint6
         if constexpr (WEIGHTED) r = srow[u] * r * cv[u][e];
         const float sv = __builtin_amdgcn_fmed3f(r * a.r_scale, -lim, lim);
         h[e] = (_Float16)sv;
-        l[e] = (_Float16)(sv - (float)h[e]);
+        l[e >> 2] |= lo_plane_byte(sv, h[e]) << (8 * (e & 3));
       }
       __builtin_nontemporal_store(h, reinterpret_cast<halfx8r*>(hi + (oct[u] << 3)));
-      __builtin_nontemporal_store(l, reinterpret_cast<halfx8r*>(lo + (oct[u] << 3)));
+      __builtin_nontemporal_store(uintx2r{l[0], l[1]}, reinterpret_cast<uintx2r*>(lo + (oct[u] << 3)));
     }
   };
   PlaneFetch fa, fb;
@@ -912,7 +924,7 @@ int launch_residual(const PhaseArgs& a, hipStream_t st) {
   const int64_t nwg = (nquads + 256 * RES_U - 1) / (256 * RES_U) * groups;
   if (nwg >= (1ll << 31)) return LQ_ERR_SHAPE;
   // R (or dense Q) out per problem, the quantized form in per problem, W in once
-  const double out_bytes = (a.R ? 4.0 : 0.0) + (a.R16 ? 2.0 : 0.0) + (a.R16 && a.R16lo ? 2.0 : 0.0) + (a.Qd ? 4.0 : 0.0);
+  const double out_bytes = (a.R ? 4.0 : 0.0) + (a.R16 ? 2.0 : 0.0) + (a.R16 && a.R16lo ? 1.0 : 0.0) + (a.Qd ? 4.0 : 0.0);
   prof::Scope ps(prof::RESIDUAL, st, (double)a.d * a.k * (out_bytes * a.batch + 4.0 + a.quant_bytes_per_weight));
   if (a.R16 && a.R16lo && !a.R && !a.Qd && ((a.d * a.k) & 7) == 0 && a.batch <= 64 && a.bits_host) {
     const int64_t nwg2 = (((a.d * a.k) >> 3) + 256 * RP_U - 1) / (256 * RP_U);

@@ -492,6 +492,39 @@ __device__ __forceinline__ void operands16(const uintx4 (&cur)[G][2], int g, hal
   }
 }
 
+// The lo plane of the residual: one byte per element, the upper byte of the fp16 number 2^11 (a - hi) (sign, five exponent
+// bits, two fraction bits).  NN mode only: ring[g][e / 4][e % 4] = the 16 bits holding columns col, col + 1 of reduction
+// row k0 + 16 g + 8 h + e; off is the lane's byte offset in the fp16 plane, i.e. twice the one here.
+constexpr float LO8_SCALE = 2048.0f;
+
+template <int G, bool GUARD>
+__device__ __forceinline__ void fetch_a8(const uint8_t* __restrict__ A, int64_t lda, uint32_t off, int lh, int64_t k0,
+                                         int64_t kend, uintx4 (&ring)[G][2]) {
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint8_t* base = A + (size_t)(k0 + 16 * g + e) * lda;
+      uint32_t f = 0u;
+      if (!GUARD || k0 + 16 * g + 8 * lh + e < kend) f = *reinterpret_cast<const uint16_t*>(base + (off >> 1));
+      ring[g][e >> 2][e & 3] = f;
+    }
+}
+
+// bytes (col, col + 1) of 8 reduction rows -> the 8 halves (byte << 8) of column col and of column col + 1
+template <int G>
+__device__ __forceinline__ void operands8(const uintx4 (&cur)[G][2], int g, halfx8 (&av)[2]) {
+  uintx4 c0, c1;
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const uint32_t w0 = cur[g][m >> 1][2 * (m & 1)], w1 = cur[g][m >> 1][2 * (m & 1) + 1];
+    c0[m] = __builtin_amdgcn_perm(w1, w0, 0x040c000cu);
+    c1[m] = __builtin_amdgcn_perm(w1, w0, 0x050c010cu);
+  }
+  av[0] = __builtin_bit_cast(halfx8, c0);
+  av[1] = __builtin_bit_cast(halfx8, c1);
+}
+
 // NT mode with one plane, staged through LDS.  Loading a row's 8 halves per lane and MFMA (above) touches every 128-byte
 // line of a row with four load instructions of 32 bytes each.  Here a wavefront loads its 64 rows of a 64-deep step with
 // full lines (instruction i: lane l takes the 16-byte piece l % 8 of row 8 i + l / 8), writes them to its own LDS
@@ -548,7 +581,7 @@ __device__ __forceinline__ void multiply_chunk16(const _Float16* xh, const _Floa
   for (int g = 0; g < G; ++g) {
     halfx8 ah[2], al[2];
     operands16<MODE, G>(cur[0], g, ah);
-    if constexpr (PLANES == 2) operands16<MODE, G>(cur[1], g, al);
+    if constexpr (PLANES == 2) operands8<G>(cur[1], g, al);
 #pragma unroll
     for (int i = 0; i < LT; ++i) {
       const halfx8 xhv = *reinterpret_cast<const halfx8*>(xh + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
@@ -557,7 +590,7 @@ __device__ __forceinline__ void multiply_chunk16(const _Float16* xh, const _Floa
         if constexpr (PLANES == 2) {
           const halfx8 xlv = *reinterpret_cast<const halfx8*>(xl + (32 * i + ln) * HP16 + 16 * g + 8 * lh);
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xlv, ah[j], acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, al[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv * (_Float16)(1.0f / LO8_SCALE), al[j], acc[i][j], 0, 0, 0);
         }
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xhv, ah[j], acc[i][j], 0, 0, 0);
       }
@@ -605,7 +638,7 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
     const int s1 = g.ns - s0 < share1 - gs ? g.ns : s0 + (share1 - gs);
     const float* __restrict__ X = g.X + (size_t)z * g.strideX;
     const _Float16* __restrict__ A = reinterpret_cast<const _Float16*>(g.A) + (size_t)z * g.strideA;
-    const _Float16* __restrict__ A2 = reinterpret_cast<const _Float16*>(g.A2) + (size_t)z * g.strideA;
+    const uint8_t* __restrict__ A2 = reinterpret_cast<const uint8_t*>(g.A2) + (size_t)z * g.strideA;   // PLANES == 2: NN mode only
     const float xscale = g.lam0 ? x_scale_from(g.lam0[(size_t)z * g.strideLam]) : g.x_scale;
     const int64_t kbeg = (int64_t)s0 * BKH;
     const int64_t kend = (int64_t)s1 * BKH < g.K ? (int64_t)s1 * BKH : g.K;
@@ -635,7 +668,7 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
         const int64_t k1c = k1 < klast ? k1 : klast;
         if constexpr (STAGED) fetch_a_staged<false>(A, off8, lane, k1c, kend, ring[u][0]);
         else fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[u][0]);
-        if constexpr (PLANES == 2) fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[u][1]);
+        if constexpr (PLANES == 2) fetch_a8<G, false>(A2, g.lda, off[0], lh, k1c, kend, ring[u][1]);
       }
     }
 
@@ -655,7 +688,7 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
       if constexpr (STAGED) fetch_a_staged<false>(A, off8, lane, k1c, kend, ring[((U) + STAGES - 1) % STAGES][0]); \
       else fetch_a16<MODE, G, false>(A, g.lda, off, lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][0]);         \
       if constexpr (PLANES == 2)                                                                                  \
-        fetch_a16<MODE, G, false>(A2, g.lda, off, lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][1]);           \
+        fetch_a8<G, false>(A2, g.lda, off[0], lh, k1c, kend, ring[((U) + STAGES - 1) % STAGES][1]);              \
     }                                                                                                             \
     if constexpr (STAGED) multiply_chunk_staged<LT>(xh, xl, stage, lane, ring[(U)], acc);                         \
     else multiply_chunk16<LT, MODE, PLANES, G>(xh, xl, ln, lh, ring[(U)], acc);                                   \
@@ -673,7 +706,7 @@ __global__ __launch_bounds__(256, STAGES > 2 ? 1 : 2) void wide_gemm_f16_kernel(
       const int64_t kt = kbeg + (int64_t)nfull * BKH;
       if constexpr (STAGED) fetch_a_staged<true>(A, off8, lane, kt, kend, ring[0][0]);
       else fetch_a16<MODE, G, true>(A, g.lda, off, lh, kt, kend, ring[0][0]);
-      if constexpr (PLANES == 2) fetch_a16<MODE, G, true>(A2, g.lda, off, lh, kt, kend, ring[0][1]);
+      if constexpr (PLANES == 2) fetch_a8<G, true>(A2, g.lda, off[0], lh, kt, kend, ring[0][1]);
       LQ_GEMM16_STEP(0, nfull, false)
     }
 #undef LQ_GEMM16_STEP
@@ -830,15 +863,17 @@ static int launch_f16_mode(const GemmArgs& g, int lt, dim3 grid, hipStream_t st)
 
 bool wide_gemm_f16_supported(int l) { return l % 32 == 0 && l >= 32 && l <= 96; }   // four row tiles spill registers
 
-// C = out_scale * X * op(A) for `batch` problems with A stored in fp16 (strideA, lda in fp16 elements), as one plane
-// (A_lo == NULL) or as hi + lo planes of the same layout.  X is scaled by x_scale before it is split into fp16 halves,
+// C = out_scale * X * op(A) for `batch` problems with A stored in fp16 (strideA, lda in elements), as one plane
+// (A_lo == NULL) or, NN mode only, as a hi plane plus a lo plane of one byte per element in the same layout: the upper
+// byte of the fp16 number 2^11 (a - hi), which brings A to 14 significant bits.  X is scaled by x_scale before it is split into fp16 halves,
 // or, when lam0 is given, by a power of two derived from lam0[z * strideLam], the largest squared row norm of X[z]
 // (that scale is divided out again).  ldx must be a multiple of 64; NT mode needs K and lda to be multiples of 8,
 // NN mode an even lda.
 int launch_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
-                         const uint16_t* A, const uint16_t* A_lo, int64_t lda, size_t strideA, float* C, int64_t ldc,
+                         const uint16_t* A, const uint8_t* A_lo, int64_t lda, size_t strideA, float* C, int64_t ldc,
                          size_t strideC, int batch, float* part, size_t part_floats, float x_scale, const double* lam0,
                          size_t strideLam, float out_scale, hipStream_t st, int workgroups) {
+  if (A_lo && mode != MODE_NN) return LQ_ERR_ARG;      // the byte plane is read in NN layout only
   if (!wide_gemm_f16_supported(l) || big < 1 || K < 1 || batch < 1 || ldx % 64 != 0) return LQ_ERR_ARG;
   if (mode == MODE_NN && ((big % 2) != 0 || (lda % 2) != 0)) return LQ_ERR_ARG;
   if (mode == MODE_NT && ((K % 8) != 0 || (lda % 8) != 0)) return LQ_ERR_ARG;
@@ -849,7 +884,7 @@ int launch_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X
   const int span = 256;
   const int bk = A_lo ? 32 : 64;
   GemmArgs g;
-  g.X = X; g.A = reinterpret_cast<const float*>(A); g.A2 = reinterpret_cast<const float*>(A_lo ? A_lo : A);
+  g.X = X; g.A = reinterpret_cast<const float*>(A); g.A2 = A_lo ? reinterpret_cast<const float*>(A_lo) : reinterpret_cast<const float*>(A);
   g.C = C; g.part = part; g.ldx = ldx; g.lda = lda; g.ldc = ldc;
   g.strideX = strideX; g.strideA = strideA; g.strideC = strideC;
   g.big = big; g.K = K;
@@ -873,7 +908,7 @@ int launch_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X
   {
     prof::Scope ps(prof::GEMM_F16_BASE + (A_lo ? 8 : 0) + mode * 4 + (lt - 1), st, 2.0 * l * (double)big * (double)K * batch);
     int rc;
-    if (A_lo) rc = mode == MODE_NT ? launch_f16_mode<MODE_NT, 2>(g, lt, grid, st) : launch_f16_mode<MODE_NN, 2>(g, lt, grid, st);
+    if (A_lo) rc = launch_f16_mode<MODE_NN, 2>(g, lt, grid, st);
     else rc = mode == MODE_NT ? launch_f16_mode<MODE_NT, 1>(g, lt, grid, st) : launch_f16_mode<MODE_NN, 1>(g, lt, grid, st);
     if (rc != LQ_OK) return rc;
   }

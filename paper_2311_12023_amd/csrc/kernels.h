@@ -24,7 +24,7 @@ struct GemmArgs {
   int tiles, ns;                      // tile positions along the large dimension, 32-deep reduction steps per problem
   int total, per_wg;                  // steps of the whole batch, steps per workgroup (share)
   // fp16-operand products only (launch_wide_gemm_f16)
-  const float* A2;                    // second (lo) fp16 plane of A, same layout
+  const float* A2;                    // lo plane of A: one byte per element, same layout (NN mode)
   float x_scale, out_scale;
   const double* lam0;                 // per problem: largest squared row norm of X, or NULL (x_scale applies)
   size_t strideLam;
@@ -42,7 +42,7 @@ int launch_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, in
 // The same products with A stored in fp16 (see gemm_kernels.hip); l <= 96.
 bool wide_gemm_f16_supported(int l);
 int launch_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, size_t strideX,
-                         const uint16_t* A, const uint16_t* A_lo, int64_t lda, size_t strideA, float* C, int64_t ldc,
+                         const uint16_t* A, const uint8_t* A_lo, int64_t lda, size_t strideA, float* C, int64_t ldc,
                          size_t strideC, int batch, float* part, size_t part_floats, float x_scale, const double* lam0,
                          size_t strideLam, float out_scale, hipStream_t st, int workgroups = 0);
 
@@ -208,7 +208,8 @@ struct PhaseArgs {
   float* R;         size_t strideR;         // scaled residual sqrt(rw_i) (W - Q) sqrt(cw_j), or NULL
   uint16_t* R16;    float r_scale;          // the same residual times r_scale (a power of two) as fp16, clamped to the
                                             // fp16 range (stride strideR, in fp16 elements), or NULL
-  uint16_t* R16lo;                          // with R16: fp16 of what the rounding of R16 dropped, same layout
+  uint8_t* R16lo;                           // with R16: what the rounding of R16 dropped, one byte per element (upper byte
+                                            // of the fp16 number 2^11 (a - hi)), same layout
   float* Qd;        size_t strideQd;        // dense Q or NULL
   double* err_part; size_t strideErrPart;   // per-workgroup partial sums of the squared error
   double* err_out;  size_t strideErrOut;    // eps (norm) of this iteration, one double per problem

@@ -399,7 +399,7 @@ static int warm_factorize(const Ctx& c, WideSet& w, const float* Bsrc, size_t sB
   const int l = pl.prm.lw;
   const float* R = c.at<float>(pl.R);
   const uint16_t* R16 = c.at<uint16_t>(pl.R);
-  const uint16_t* R16lo = R16 + pl.strideR * (size_t)batch_planes(c);
+  const uint8_t* R16lo = reinterpret_cast<const uint8_t*>(R16 + pl.strideR * (size_t)batch_planes(c));   // one byte per element
   const bool half = pl.prm.prec == 2;
   float* part = c.at<float>(pl.gpart);
   // fp16 residual: the rows of X = B (norms at most sigma_1, taken from the Ritz values the rows of Bsrc came with;
@@ -663,7 +663,7 @@ struct Loop {
     if (last) { stopped = true; return LQ_OK; }
     a.strideR = pl.strideR;
     if (pl.prm.prec == 2) {
-      a.R16 = c->at<uint16_t>(pl.R); a.R16lo = a.R16 + pl.strideR * (size_t)pl.batch; a.r_scale = c->a_scale;
+      a.R16 = c->at<uint16_t>(pl.R); a.R16lo = reinterpret_cast<uint8_t*>(a.R16 + pl.strideR * (size_t)pl.batch); a.r_scale = c->a_scale;
     }
     else a.R = c->at<float>(pl.R);
     LQ_TRY(launch_residual(a, c->st));

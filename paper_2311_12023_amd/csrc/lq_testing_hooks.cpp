@@ -42,7 +42,7 @@ int lq_test_wide_gemm(int mode, int l, int64_t big, int64_t K, const float* X, i
 }
 
 int lq_test_wide_gemm_f16(int mode, int l, int64_t big, int64_t K, const float* X, int64_t ldx, const uint16_t* A,
-                          const uint16_t* A_lo, int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
+                          const uint8_t* A_lo, int64_t lda, float* C, int64_t ldc, int batch, int workgroups, float* part, size_t part_floats,
                           float x_scale, const double* lam0, float out_scale, void* stream) {
   if (!X || !A || !C) return LQ_ERR_NULL;
   if (workgroups < -32768 || workgroups > 32768 || batch < 1) return LQ_ERR_ARG;
