@@ -104,10 +104,11 @@ def roofline_of(name: str, ms: float, launches: int, work: float) -> dict | None
     sec = ms * 1e-3
     common = {"kernel": name, "traffic": None, "launches": launches, "avg_us": 1e3 * ms / launches}
     if name.startswith("wide_gemm_f16_kernel"):
-        # A as one or two fp16 planes (2 or 4 B per element, 2 l flop per element); one plane: X rounded to fp16, one
-        # MFMA per product; two planes: X split into fp16 hi + lo, three MFMAs per product; bound by streaming A
+        # A as an fp16 plane (2 B per element) or as that plane plus a byte plane (3 B), 2 l flop per element; one plane: X
+        # rounded to fp16, one MFMA per product; two planes: X split into fp16 hi + lo, three MFMAs per product; bound by
+        # streaming A
         lt, _, planes = (int(t) for t in name[name.index("<") + 1:name.index(">")].split(","))
-        ach = work / (2.0 * 32 * lt) * 2.0 * planes / sec / 1e9
+        ach = work / (2.0 * 32 * lt) * (2.0 if planes == 1 else 3.0) / sec / 1e9
         return {**common, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
                 "algorithmic_tflops": work / sec / 1e12,
                 "executed_f16_mfma_frac": (1.0 if planes == 1 else 3.0) * work / sec / 1e12 / PEAK_BF16_MFMA_TFLOPS}
@@ -559,8 +560,9 @@ def bench_sweep(args, torch, gen, lq, dev) -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("f32 (large products: three bf16 MFMAs on hi/lo splits against fp32 operands; against the residual kept "
-                  "as fp16 hi + lo planes, one fp16 MFMA on the hi plane where the product only steers the subspace, three "
-                  "on both planes for the projection the results are read from; fp32 accumulation)") if split else "f32",
+                  "as an fp16 plane plus a byte plane of what its rounding dropped, one fp16 MFMA on the fp16 plane where the "
+                  "product only steers the subspace, three on both planes for the projection the results are read from; fp32 "
+                  "accumulation)") if split else "f32",
         "data": "synthetic",
         "config": {"workload": label, "baseline_config": wl, "matrices": n_mats, "configs": n_cfgs, "iters": iters,
                    "rank": rank, "concurrent_matrices": nthreads,
