@@ -98,9 +98,10 @@ typedef struct {
  *   gemm_mode     arithmetic of the large products against the d x k matrix: 1 = fp32 MFMA; 2 = both operands
  *                 split on the fly into bf16 hi + lo and multiplied by three bf16 MFMAs with fp32 accumulation
  *                 (products good to about 2^-16 relative, several times faster); 3 = as 2 for the first Factorize, and
- *                 the residual W - Q of the later ones is stored as two fp16 planes (hi + lo, 22 significant bits,
- *                 scaled by a power of two): the products that steer the subspace read the hi plane, the projection
- *                 that the singular values and factors come from reads both (warm_width <= 96, else as 2).
+ *                 the residual W - Q of the later ones is stored, scaled by a power of two, as an fp16 plane plus a
+ *                 byte plane of what that rounding dropped (14 significant bits together): the products that steer the
+ *                 subspace read the fp16 plane, the projection that the singular values and factors come from reads
+ *                 both (warm_width <= 96, else as 2).
  *                 Default 3.
  *   init_quantized  lq_decompose only: 1 starts Algorithm 2 from Q(0) = Quantize(W) instead of Q(0) = 0 (the
  *                 variant of the footnote in Section 3.1: the first Factorize then sees W - Quantize(W)).

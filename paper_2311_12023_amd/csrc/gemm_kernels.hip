@@ -381,9 +381,10 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g, int l, int 
 // two so that it sits in the middle of the fp16 range): half the bytes of the fp32 form stream from HBM, which is
 // what bounds these products.  PLANES == 1: A is one fp16 plane and X is rounded to fp16 as well (after scaling by a
 // power of two xs that keeps its entries normal numbers): one v_mfma_f32_32x32x16_f16 per product, about 2^-12 relative
-// per operand; for the products that only steer a subspace.  PLANES == 2: A comes as two fp16 planes, a = hi + lo
-// (22 significant bits), X is split into fp16 hi + lo, and a product is three MFMAs (xl * ah + xh * al + xh * ah); used
-// where the rounding of an operand to fp16 would show in the result to first order.  The result is multiplied by out_scale (a power of two) when stored.
+// per operand; for the products that only steer a subspace.  PLANES == 2 (NN mode): A comes as the fp16 plane hi plus a byte
+// plane, each byte the upper byte of the fp16 number 2^11 (a - hi) (14 significant bits together), X is split into fp16
+// hi + lo, and a product is three MFMAs (xl * ah + (2^-11 xh) * al + xh * ah); used where the rounding of an operand to
+// fp16 would show in the result to first order.  The result is multiplied by out_scale (a power of two) when stored.
 // Same work decomposition, tile shapes and fix-up as wide_gemm_kernel; the reduction is cut into steps of 64 (one
 // plane) or 32 (two planes), and both operands keep the natural order of the reduction index.
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));

@@ -114,7 +114,7 @@ static void make_plan(int64_t d, int64_t k, int rank, const Params& prm, int bat
   pl.errs = take((size_t)batch * MAX_ITERS * 8);
   const size_t n = (size_t)pl.n;
   if (prm.prec == 2) {      // fp16 residuals; the area also has to hold one fp32 matrix (input of the first Factorize)
-    pl.strideR = up256(n * 2) / 2;          pl.R = take(std::max(pl.strideR * 4 * batch, up256(n * 4)));   // hi planes, lo planes
+    pl.strideR = up256(n * 2) / 2;          pl.R = take(std::max(pl.strideR * 3 * batch, up256(n * 4)));   // fp16 planes, then byte planes
   } else {
     pl.strideR = up256(n * 4) / 4;          pl.R = take(pl.strideR * 4 * batch);
   }
