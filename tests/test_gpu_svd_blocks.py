@@ -129,6 +129,19 @@ def test_wide_gemm_f16(env, mode, l, big, K, batch, wgs, scaling, planes):
     assert torch.equal(ct, ct2)
 
 
+def test_wide_gemm_f16_rejects_byte_plane_in_nt_mode(env):
+    torch, lq, L = env
+    x = torch.zeros((32, 64), dtype=torch.float32, device="cuda")
+    a = torch.zeros((64, 64), dtype=torch.float16, device="cuda")
+    lo = torch.zeros((64, 64), dtype=torch.uint8, device="cuda")
+    c = torch.zeros((32, 64), dtype=torch.float32, device="cuda")
+    args = (32, 64, 64, x.data_ptr(), 64, a.data_ptr(), lo.data_ptr(), 64, c.data_ptr(), 64, 1, 0, None, 0, 1.0, None, 1.0, None)
+    assert L.lq_test_wide_gemm_f16(0, *args) != 0
+    assert L.lq_test_wide_gemm_f16(1, *args) == 0
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(c) == 0
+
+
 @pytest.mark.parametrize("use_alt", [True, False])
 @pytest.mark.parametrize("l,m", [(32, 100), (64, 768), (96, 4096), (128, 1000), (256, 2048)])
 def test_orthonormalize(env, l, m, use_alt):
