@@ -96,6 +96,24 @@ def test_factorize_spectra(env, kind):
     assert abs(np.sum((w.astype(np.float64) - l1h @ l2h) ** 2) - tail) < 1e-4 * tail + 1e-10 * np.sum(ref ** 2)
 
 
+@pytest.mark.parametrize("kw,accurate", [(dict(first_max=1), False), (dict(first_max=5, first_check=1), False),
+                                         (dict(first_check=1), True), (dict(first_check=40), True),
+                                         (dict(first_tol=1e-1), False), (dict(first_tol=1e-9, first_max=60), True)])
+def test_factorize_schedule_parameters(env, kw, accurate):
+    """The cold start ends whatever its schedule parameters are (cap on the applications of A A^T, spacing of the
+    Rayleigh-Ritz checks, tolerance), with finite results; where the parameters leave it room, with accurate ones."""
+    torch, lq = env
+    w = gen.weight_matrix(384, 640, 777, 12, outlier_frac=0.005)
+    l1, l2, sg = lq.factorize(torch.from_numpy(w).cuda(), 8, seed=2, params=lq.SvdParams(**kw))
+    assert np.all(np.isfinite(sg)) and torch.isfinite(l1).all() and torch.isfinite(l2).all()
+    ref = np.linalg.svd(w.astype(np.float64), compute_uv=False)[:8]
+    rel = np.max(np.abs(sg - ref) / ref)
+    print(kw, "sigma rel", rel)
+    assert np.all(sg <= ref * (1 + 1e-5))            # Ritz values never exceed the singular values they approximate
+    if accurate:
+        assert rel < SV_TOL
+
+
 def test_factorize_many_shapes_and_seeds(env):
     """Factorize over a spread of shapes, ranks, sketch seeds and spectra (noise with 0 to 12 planted directions of random
     strength, some columns scaled up): singular values against LAPACK every time."""
